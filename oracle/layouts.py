@@ -1,0 +1,79 @@
+"""TEST INFRASTRUCTURE ONLY: the layout rewrites and the GEMM unit, by definition.
+
+Each function is the index map of the corresponding rewrite written out with
+numpy slicing; no blocking or fusion beyond what the map itself states.
+
+  pack_layout   Table 2 rows Pad, Split, Reorder applied to the input (the
+                reference mapping of Sec. 5.1: the channel dimension is padded to
+                a multiple of the block, split, and the block moved innermost);
+                the spatial zero border of the convolution is materialised too.
+  pack_weights  the same rewrites on the weights, then Fuse (Table 2 row 5) of the
+                reduction dimensions into one GEMM depth, zero-padded to `kalign`.
+  im2col        Stencil Unroll + Fuse (Table 2 rows 1 and 5; "im2col" in Sec. 6.2).
+  gemm_nt       the matrix unit of Sec. 5.1: C[x][y] += sum_z A[x][z] * B[y][z].
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def ceil_to(x: int, m: int) -> int:
+    return (x + m - 1) // m * m
+
+
+def pack_layout(x: np.ndarray, cb: int, pad: int) -> np.ndarray:
+    """[N,C,H,W] -> [N, ceil(C/cb), H+2pad, W+2pad, cb]; zeros for c >= C and the border."""
+    N, C, H, W = x.shape
+    Cb = (C + cb - 1) // cb
+    y = np.zeros((N, Cb, H + 2 * pad, W + 2 * pad, cb), dtype=x.dtype)
+    for c in range(C):
+        y[:, c // cb, pad:pad + H, pad:pad + W, c % cb] = x[:, c]
+    return y
+
+
+def packed_depth(C: int, R: int, S: int, cb: int, kalign: int = 64) -> int:
+    return ceil_to(((C + cb - 1) // cb) * R * S * cb, kalign)
+
+
+def pack_weights_blocked(w: np.ndarray, cb: int, kalign: int = 64) -> np.ndarray:
+    """[K,C,R,S] -> [K, depth]; depth index j = ((c//cb * R + r) * S + s) * cb + c%cb."""
+    K, C, R, S = w.shape
+    y = np.zeros((K, packed_depth(C, R, S, cb, kalign)), dtype=w.dtype)
+    for c in range(C):
+        for r in range(R):
+            for s in range(S):
+                j = ((c // cb * R + r) * S + s) * cb + c % cb
+                y[:, j] = w[:, c, r, s]
+    return y
+
+
+def pack_weights_im2col(w: np.ndarray, kalign: int = 64) -> np.ndarray:
+    """[K,C,R,S] -> [K, depth]; depth index j = (c*R + r)*S + s, zero-padded."""
+    K, C, R, S = w.shape
+    y = np.zeros((K, ceil_to(C * R * S, kalign)), dtype=w.dtype)
+    y[:, :C * R * S] = w.reshape(K, C * R * S)
+    return y
+
+
+def im2col(x: np.ndarray, R: int, S: int, stride: int, pad: int,
+           kalign: int = 64) -> np.ndarray:
+    """[N,C,H,W] -> [N*P*Q, depth]; A[(n,p,q)][(c,r,s)] = x0[n][c][p*st+r-pad][q*st+s-pad]."""
+    N, C, H, W = x.shape
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    x0 = np.zeros((N, C, H + 2 * pad, W + 2 * pad), dtype=x.dtype)
+    x0[:, :, pad:pad + H, pad:pad + W] = x
+    A = np.zeros((N, P, Q, ceil_to(C * R * S, kalign)), dtype=x.dtype)
+    for c in range(C):
+        for r in range(R):
+            for s in range(S):
+                A[:, :, :, (c * R + r) * S + s] = \
+                    x0[:, c, r:r + stride * (P - 1) + 1:stride, s:s + stride * (Q - 1) + 1:stride]
+    return A.reshape(N * P * Q, -1)
+
+
+def gemm_nt(A: np.ndarray, B: np.ndarray) -> np.ndarray:
+    """C[x][y] = sum_z A[x][z] * B[y][z], int8 operands, exact, returned as int32."""
+    C = A.astype(np.int64) @ B.astype(np.int64).T
+    assert np.all(np.abs(C) < 2 ** 31)
+    return C.astype(np.int32)

@@ -1,0 +1,67 @@
+"""TEST INFRASTRUCTURE ONLY: candidate-selection overheads of Sec. 4.4, by definition.
+
+    O_MAC  = MAC_total  - MAC_min
+    O_Data = move_total - move_min          (counted in tensor elements, as the paper does)
+    score  = w_mac * O_MAC + w_data * O_Data,   minimised over the candidates
+
+Reading of the terms (the paper gives only their names):
+  MAC_min    = M*K*C*R*S, the MACs of the definition (M = N*P*Q output pixels).
+  MAC_total  = MACs the matrix unit issues once every mapped dimension is padded to
+               the unit's extent (Sec. 4.2.4 rule b): ceil(M,x) * ceil(K,y) * depth,
+               depth = fused reduction length of the candidate, padded to z.
+  move_min   = |in| + |wt| + |out|.
+  move_total = every element a layout rewrite reads or writes plus every element the
+               GEMM stage reads or writes:
+               (|in| + |X'|) + (|wt| + |W'|) + (|X'| + |W'| + |out|)
+               with X' the rewritten input and W' the rewritten weights.
+Candidates: channel blocks cb in {16,32,64} (pad + split + reorder), a single padded
+block cb = ceil(C,16) (pad only), and stencil unroll (im2col).
+"""
+from __future__ import annotations
+
+PACKED, IM2COL, PAD_ONLY = 1, 2, 3
+UNIT_X, UNIT_Y, UNIT_Z = 32, 32, 64  # pixels, output channels, depth
+
+
+def _ceil(x, m):
+    return -(-x // m) * m
+
+
+def candidates(C):
+    out = [(PACKED, cb) for cb in (64, 32, 16)]
+    out.append((IM2COL, 0))
+    out.append((PAD_ONLY, _ceil(C, 16)))
+    return out
+
+
+def overheads(N, C, H, W, K, R, S, stride, pad, layout, cb):
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    M = N * P * Q
+    mac_min = M * K * C * R * S
+    if layout == IM2COL:
+        depth = _ceil(C * R * S, UNIT_Z)
+        x_elems = M * depth
+    else:
+        cpad = _ceil(C, cb)
+        depth = _ceil(cpad * R * S, UNIT_Z)
+        x_elems = N * cpad * (H + 2 * pad) * (W + 2 * pad)
+    w_elems = K * depth
+    mac_total = _ceil(M, UNIT_X) * _ceil(K, UNIT_Y) * depth
+    o_mac = mac_total - mac_min
+    o_data = 2 * x_elems + 2 * w_elems
+    return o_mac, o_data, x_elems + w_elems
+
+
+def select(N, C, H, W, K, R, S, stride, pad, w_mac, w_data):
+    """Return (layout, cb, score) of the cheapest candidate.
+
+    Ties: fewer rewritten elements, then lower layout code, then larger block."""
+    best = None
+    for layout, cb in candidates(C):
+        o_mac, o_data, ws = overheads(N, C, H, W, K, R, S, stride, pad, layout, cb)
+        score = w_mac * o_mac + w_data * o_data
+        key = (score, ws, layout, -cb)
+        if best is None or key < best[0]:
+            best = (key, layout, cb, score)
+    return best[1], best[2], best[3]

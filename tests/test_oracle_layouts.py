@@ -1,0 +1,98 @@
+"""Pins for the layout-rewrite and GEMM-unit definitions (CPU only).
+
+The rewrites are pinned against the independently written direct convolution:
+a rewritten operand pair, pushed through the matrix unit's definition, must give the
+convolution itself.  Element-wise brute force, round trips and zero counts pin the rest.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import direct, layouts
+from paper_2104_04731_amd.inputs import uniform_int8, CONFIGS
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_gemm_unit_hand_example():
+    want = np.loadtxt(os.path.join(GOLD, "gemm_unit_1x16x16.txt"), dtype=np.int64).reshape(1, 16)
+    A = np.arange(1, 17, dtype=np.int8).reshape(1, 16)
+    B = np.array([[y - z for z in range(16)] for y in range(16)], dtype=np.int8)
+    np.testing.assert_array_equal(layouts.gemm_nt(A, B), want)
+    np.testing.assert_array_equal(want[0], 136 * np.arange(16) - 1360)
+
+
+def test_gemm_unit_is_b_transposed_and_signed():
+    A = np.array([[-128, 127, 3]], np.int8); B = np.array([[-128, -128, 0], [1, 2, 3]], np.int8)
+    np.testing.assert_array_equal(layouts.gemm_nt(A, B), [[16384 - 16256, -128 + 254 + 9]])
+
+
+@pytest.mark.parametrize("cb,pad", [(4, 0), (16, 1), (16, 3), (32, 2), (64, 1)])
+def test_pack_layout_elementwise(cb, pad):
+    N, C, H, W = 2, 37, 5, 6
+    x = uniform_int8(61, (N, C, H, W))
+    y = layouts.pack_layout(x, cb, pad)
+    Cb = -(-C // cb)
+    assert y.shape == (N, Cb, H + 2 * pad, W + 2 * pad, cb)
+    yl, xl = y.tolist(), x.tolist()
+    for n, b, hp, wp, i in itertools.product(range(N), range(Cb), range(H + 2 * pad), range(W + 2 * pad), range(cb)):
+        c, h, w = b * cb + i, hp - pad, wp - pad
+        want = xl[n][c][h][w] if (c < C and 0 <= h < H and 0 <= w < W) else 0
+        assert yl[n][b][hp][wp][i] == want
+    # round trip: un-reorder, un-split, crop
+    back = y.transpose(0, 1, 4, 2, 3).reshape(N, Cb * cb, H + 2 * pad, W + 2 * pad)
+    np.testing.assert_array_equal(back[:, :C, pad:pad + H, pad:pad + W], x)
+
+
+@pytest.mark.parametrize("name", ["C1", "C2", "C4b"])
+def test_im2col_then_gemm_is_the_convolution(name):
+    cfg = CONFIGS[name]; x, w = cfg.make()
+    A = layouts.im2col(x, cfg.R, cfg.S, cfg.stride, cfg.pad)
+    B = layouts.pack_weights_im2col(w)
+    assert A.shape == (cfg.M, -(-cfg.Kg // 64) * 64) and B.shape == (cfg.K, A.shape[1])
+    got = layouts.gemm_nt(B, A).reshape(cfg.K, cfg.N, cfg.P, cfg.Q).transpose(1, 0, 2, 3)
+    np.testing.assert_array_equal(got, direct.conv2d_int8(x, w, cfg.stride, cfg.pad))
+
+
+def test_im2col_elementwise_small():
+    N, C, H, W, R, S, st, pad = 2, 3, 6, 7, 3, 2, 2, 1
+    x = uniform_int8(62, (N, C, H, W)); xl = x.tolist()
+    A = layouts.im2col(x, R, S, st, pad)
+    P = (H + 2 * pad - R) // st + 1; Q = (W + 2 * pad - S) // st + 1
+    assert A.shape == (N * P * Q, 64)
+    for n, p, q, c, r, s in itertools.product(range(N), range(P), range(Q), range(C), range(R), range(S)):
+        h, w = p * st + r - pad, q * st + s - pad
+        want = xl[n][c][h][w] if (0 <= h < H and 0 <= w < W) else 0
+        assert A[(n * P + p) * Q + q, (c * R + r) * S + s] == want
+    assert not A[:, C * R * S:].any()
+
+
+@pytest.mark.parametrize("dims,cb", [((2, 5, 6, 7, 3, 3, 2, 1, 1), 16), ((1, 40, 5, 5, 6, 3, 3, 2, 1), 16),
+                                     ((1, 40, 5, 5, 6, 3, 3, 1, 2), 32), ((1, 70, 4, 6, 5, 1, 1, 1, 0), 64),
+                                     ((1, 3, 9, 9, 4, 7, 7, 2, 3), 16), ((1, 33, 4, 4, 2, 2, 3, 1, 0), 48)])
+def test_blocked_operands_give_the_convolution(dims, cb):
+    """Implicit GEMM by definition over the packed operands == direct convolution."""
+    N, C, H, W, K, R, S, st, pad = dims
+    x = uniform_int8(63, (N, C, H, W)); w = uniform_int8(64, (K, C, R, S))
+    X = layouts.pack_layout(x, cb, pad); Wq = layouts.pack_weights_blocked(w, cb)
+    Cb = X.shape[1]
+    assert Wq.shape == (K, layouts.packed_depth(C, R, S, cb)) and Wq.shape[1] % 64 == 0
+    P = (H + 2 * pad - R) // st + 1; Q = (W + 2 * pad - S) // st + 1
+    A = np.zeros((N, P, Q, Wq.shape[1]), np.int8)
+    for b, r, s in itertools.product(range(Cb), range(R), range(S)):
+        j = ((b * R + r) * S + s) * cb
+        A[:, :, :, j:j + cb] = X[:, b, r:r + st * (P - 1) + 1:st, s:s + st * (Q - 1) + 1:st, :]
+    got = layouts.gemm_nt(Wq, A.reshape(N * P * Q, -1)).reshape(K, N, P, Q).transpose(1, 0, 2, 3)
+    np.testing.assert_array_equal(got, direct.conv2d_int8(x, w, st, pad))
+    # everything that is not a true weight is zero
+    assert np.count_nonzero(Wq) == np.count_nonzero(w)
+
+
+def test_weight_pack_im2col_is_row_padded_copy():
+    w = uniform_int8(65, (5, 3, 7, 7))
+    B = layouts.pack_weights_im2col(w)
+    assert B.shape == (5, 192)
+    np.testing.assert_array_equal(B[:, :147], w.reshape(5, 147))
+    assert not B[:, 147:].any()

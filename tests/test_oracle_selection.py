@@ -1,0 +1,58 @@
+"""Pins for the candidate-selection overheads (Sec. 4.4), CPU only."""
+import pytest
+
+from oracle import selection as sel
+from paper_2104_04731_amd.inputs import CONFIGS
+
+
+def test_no_padding_means_no_mac_overhead():
+    # every mapped dimension divides the unit: M=N*P*Q=64*..., K=64, C=64
+    o_mac, o_data, _ = sel.overheads(2, 64, 16, 16, 64, 1, 1, 1, 0, sel.PACKED, 64)
+    assert o_mac == 0
+    assert o_data == 2 * (2 * 64 * 16 * 16) + 2 * (64 * 64)
+
+
+@pytest.mark.parametrize("C,cb", [(1, 16), (3, 16), (8, 16), (3, 64), (20, 32)])
+def test_channel_padding_utilisation_law(C, cb):
+    """Useful fraction of the issued MACs is ic / padded ic (Sec. 6.1); the inflation is at
+    most the block size."""
+    # R*S*cpad multiple of 64 and M, K multiples of 32 so that only channel padding counts
+    N, H, W, K, R, S = 1, 32, 32, 32, 2, 2
+    o_mac, _, _ = sel.overheads(N, C, H + R - 1, W + S - 1, K, R, S, 1, 0, sel.PACKED, cb)
+    mac_min = N * H * W * K * C * R * S
+    cpad = -(-C // cb) * cb
+    assert (o_mac + mac_min) * C == mac_min * cpad
+    assert (o_mac + mac_min) <= cb * mac_min
+
+
+def test_stencil_unroll_data_growth():
+    # im2col writes M*depth elements: R*S-fold growth at stride 1 (Table 2 row 1: [N,I] -> [N,I,K])
+    N, C, H, W, K, R, S = 1, 64, 34, 34, 32, 3, 3
+    _, o_data, _ = sel.overheads(N, C, H, W, K, R, S, 1, 0, sel.IM2COL, 0)
+    assert o_data == 2 * (32 * 32 * 576) + 2 * (32 * 576)
+
+
+def test_paper_weights_pick_unroll_for_low_channel_and_blocking_otherwise():
+    """With w = [1,1] (Sec. 6) the MAC term dominates: one- and three-channel layers go to
+    stencil unrolling, many-channel layers stay with channel blocking."""
+    for name, want in [("C3", sel.IM2COL), ("C5", sel.IM2COL), ("C2", sel.PACKED),
+                       ("C4a", sel.PACKED), ("C4b", sel.PACKED), ("C1", sel.PACKED)]:
+        layout, cb, score = sel.select(*CONFIGS[name].dims(), 1.0, 1.0)
+        assert layout == want, name
+        assert score >= 0
+    assert sel.select(*CONFIGS["C2"].dims(), 1.0, 1.0)[1] == 64
+    assert sel.select(*CONFIGS["C1"].dims(), 1.0, 1.0)[1] == 16
+
+
+def test_weight_vector_shifts_the_choice():
+    # a pure data-movement objective never picks the unrolled layout for a 7x7 stem
+    layout, cb, _ = sel.select(*CONFIGS["C3"].dims(), 0.0, 1.0)
+    assert layout != sel.IM2COL
+    # a pure MAC objective does
+    assert sel.select(*CONFIGS["C3"].dims(), 1.0, 0.0)[0] == sel.IM2COL
+
+
+def test_tie_breaks_are_deterministic():
+    # C=64: blocks of 16/32/64 and the single padded block describe equal-cost layouts
+    layout, cb, _ = sel.select(1, 64, 8, 8, 32, 3, 3, 1, 1, 1.0, 1.0)
+    assert (layout, cb) == (sel.PACKED, 64)
