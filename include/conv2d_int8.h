@@ -1,0 +1,143 @@
+/* conv2d_int8 -- int8 2-D convolution on MI355X (gfx950) executed the way
+ * arXiv 2104.04731 frames it: a data-layout rewrite (zero padding, channel
+ * blocking, or stencil unrolling) followed by a tiled int8 x int8 -> int32
+ * matrix-multiply intrinsic (there VTA's GEMM core, here the CDNA4 int8 MFMA).
+ *
+ * C ABI.  Plain pointers and sizes only.
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller; the library
+ *     never frees or keeps it.  `stream` is a hipStream_t passed as void*
+ *     (NULL = the default stream).  All work is enqueued on `stream`; no call
+ *     synchronises with the host.
+ *   - Tensors are dense and contiguous:
+ *       input   in  [N][C][H][W]      int8   (NCHW)
+ *       weights wt  [K][C][R][S]      int8   (KCRS)
+ *       output  out [N][K][P][Q]      int32  (NKPQ)
+ *       P = floor((H + 2 pad - R)/stride) + 1,  Q likewise from W and S.
+ *   - Every function returns a conv_status_t (size queries return bytes, 0 on
+ *     invalid arguments).  Arguments are validated before anything is enqueued,
+ *     so a non-zero status leaves all buffers untouched.  Nothing throws.
+ *   - Calls on different host threads must use different streams AND, for the
+ *     one-shot conv2d_int8, are serialised on the library's cached workspace.
+ *
+ * Operation computed (Sec. 3 tensor expression / Fig. 5 step 1; access [n, i+k]
+ * of Table 2 => cross-correlation; 8-bit operands, 32-bit accumulation, Sec. 5.1):
+ *   out[n][k][p][q] = sum_{c,r,s} in0[n][c][p*stride+r-pad][q*stride+s-pad] * wt[k][c][r][s]
+ * with in0 = in inside the image and 0 outside; operands signed.
+ */
+#ifndef CONV2D_INT8_H
+#define CONV2D_INT8_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CONV_OK = 0,
+    CONV_ERR_INVALID_ARG = 1,   /* null pointer, non-positive extent, kernel larger than padded image */
+    CONV_ERR_UNSUPPORTED = 2,   /* valid problem the library has no path for (e.g. block size) */
+    CONV_ERR_OVERFLOW_RISK = 3, /* C*R*S > 131072: an int32 accumulator could wrap */
+    CONV_ERR_WORKSPACE = 4,     /* caller workspace too small / internal allocation failed */
+    CONV_ERR_DEVICE = 5         /* a HIP call or launch reported an error */
+} conv_status_t;
+
+/* Which rewrite feeds the matrix intrinsic (Table 2; reference mapping of Sec. 5.1). */
+typedef enum {
+    CONV_LAYOUT_AUTO = 0,     /* let select_layout decide */
+    CONV_LAYOUT_PACKED = 1,   /* Pad + Split + Reorder: [N][ceil(C/cb)][H+2pad][W+2pad][cb] */
+    CONV_LAYOUT_IM2COL = 2,   /* Stencil Unroll + Fuse: [N*P*Q][depth], depth index (c,r,s) */
+    CONV_LAYOUT_PAD_ONLY = 3  /* Pad only: one block cb = ceil(C,16), i.e. [N][H+2pad][W+2pad][cb] */
+} conv_layout_t;
+
+typedef struct {
+    int N, C, H, W;   /* input  */
+    int K, R, S;      /* filter */
+    int stride, pad;  /* same in both spatial directions */
+} conv_desc_t;
+
+#define CONV_DEPTH_ALIGN 64 /* fused reduction depth is zero-padded to this (one MFMA k-step, bytes) */
+
+/* ---- one-shot convolution (layout rewrite of input and weights + GEMM stage) ---------
+ * Picks the layout with select_layout, uses a workspace the library caches per device
+ * (grown with hipMalloc when a larger problem arrives, never shrunk). */
+int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                const int8_t *in, const int8_t *wt, int32_t *out, void *stream);
+
+/* ---- explicit form --------------------------------------------------------------------
+ * layout: a conv_layout_t (AUTO allowed).  cb: channel block for PACKED (16, 32 or 64;
+ * 0 = library's choice); ignored for the other layouts.
+ * wt: KCRS weights, or -- if wt_is_packed != 0 -- the output of pack_weights for the
+ * same layout/cb.  workspace: device memory of at least
+ * conv2d_int8_workspace_bytes(desc, layout, cb, wt_is_packed) bytes, 256-byte aligned,
+ * caller-owned, free to reuse once the stream has passed this call. */
+int conv2d_int8_ex(const conv_desc_t *desc, int layout, int cb,
+                   const int8_t *in, const int8_t *wt, int wt_is_packed, int32_t *out,
+                   void *workspace, size_t workspace_bytes, void *stream);
+size_t conv2d_int8_workspace_bytes(const conv_desc_t *desc, int layout, int cb, int wt_is_packed);
+
+/* ---- GEMM stage alone (operands already rewritten; the "Op." column of Table 3) -------
+ * in_packed: output of pack_layout (PACKED / PAD_ONLY) or im2col_int8 (IM2COL);
+ * wt_packed: output of pack_weights.  layout must not be AUTO; cb as above (0 = 64 if
+ * C >= 64 else ceil(C,16) rounded to 16/32/64).
+ * tile: -1 = automatic, else an index < conv2d_int8_num_tiles() (for tuning sweeps);
+ * split_k: 0 = automatic, else the number of depth slices (>= 2 accumulates with int32
+ * atomics after clearing `out`; exact, because integer addition is associative). */
+int conv2d_int8_packed(const conv_desc_t *desc, int layout, int cb,
+                       const int8_t *in_packed, const int8_t *wt_packed, int32_t *out,
+                       int tile, int split_k, void *stream);
+int conv2d_int8_num_tiles(void);
+/* Describes tile `tile`: rows = output channels, cols = output pixels per workgroup. */
+int conv2d_int8_tile_info(int tile, int *rows, int *cols, int *threads);
+
+/* ---- layout rewrites, individually callable (the "Transf." column of Table 3) ---------
+ * pack_layout (Table 2 rows 2-4 on the input, plus the convolution's zero border):
+ *   dst[n][c/cb][h+pad][w+pad][c%cb] = src[n][c][h][w]; zero where c >= C and on the border.
+ *   cb: a multiple of 4, 4 <= cb <= 1024.  dst holds pack_layout_bytes(...) bytes. */
+int pack_layout(int N, int C, int H, int W, int cb, int pad,
+                const int8_t *src, int8_t *dst, void *stream);
+size_t pack_layout_bytes(int N, int C, int H, int W, int cb, int pad);
+
+/* pack_weights (same rewrites on the weights, then Fuse of the reduction dimensions):
+ *   dst[k][j], row length depth = pack_weights_depth(...), zero where no weight maps.
+ *   PACKED / PAD_ONLY: j = ((c/cb * R + r) * S + s) * cb + c%cb   (cb a multiple of 16;
+ *                      PAD_ONLY forces cb = ceil(C,16))
+ *   IM2COL:            j = (c*R + r)*S + s */
+int pack_weights(int K, int C, int R, int S, int layout, int cb,
+                 const int8_t *src, int8_t *dst, void *stream);
+int pack_weights_depth(int C, int R, int S, int layout, int cb);
+size_t pack_weights_bytes(int K, int C, int R, int S, int layout, int cb);
+
+/* im2col_int8 (Table 2 rows 1 and 5; "im2col" of Sec. 6.2):
+ *   dst[(n*P + p)*Q + q][(c*R + r)*S + s] = in0[n][c][p*stride+r-pad][q*stride+s-pad],
+ *   row length kg_pad >= C*R*S (a multiple of 16), zero-filled beyond C*R*S. */
+int im2col_int8(int N, int C, int H, int W, int R, int S, int stride, int pad, int kg_pad,
+                const int8_t *src, int8_t *dst, void *stream);
+size_t im2col_bytes(int N, int C, int H, int W, int R, int S, int stride, int pad, int kg_pad);
+
+/* ---- the matrix intrinsic on its own (Sec. 5.1: C[x][y] += sum_z A[x][z] * B[y][z]) ----
+ * A [X][Z], B [Y][Z] int8 row-major (both depth-contiguous, i.e. B is used transposed),
+ * Cout [X][Y] int32, overwritten.  Z must be a multiple of 64. */
+int gemm_int8_nt(int X, int Y, int Z, const int8_t *A, const int8_t *B, int32_t *Cout,
+                 void *stream);
+
+/* ---- per-shape layout selection (Sec. 4.4), host only, no device work ------------------
+ * score = w_mac * O_MAC + w_data * O_Data, O_MAC = MAC_total - MAC_min (MACs issued after
+ * padding every mapped dimension to the intrinsic minus the MACs of the definition),
+ * O_Data = elements moved by rewrites and GEMM stage minus |in| + |wt| + |out|.
+ * Candidates: PACKED with cb in {64,32,16}, IM2COL, PAD_ONLY.  Ties: fewer rewritten
+ * elements, then lower layout code, then larger cb.  select_layout uses the library's
+ * MI355X weights (seconds per MAC and per byte); the paper's case studies use w = [1,1]. */
+int select_layout(const conv_desc_t *desc, int *layout, int *cb, double *score);
+int select_layout_weighted(const conv_desc_t *desc, double w_mac, double w_data,
+                           int *layout, int *cb, double *score);
+int layout_overheads(const conv_desc_t *desc, int layout, int cb,
+                     int64_t *o_mac, int64_t *o_data, int64_t *rewritten_elems);
+
+const char *conv_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONV2D_INT8_H */

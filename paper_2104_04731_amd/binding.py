@@ -1,0 +1,244 @@
+"""ctypes binding for include/conv2d_int8.h: same names, argument marshalling only.
+
+torch is used for device memory and streams, nothing else.  There is no CPU fallback:
+if the HIP library has not been built, `load()` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_OVERFLOW_RISK, ERR_WORKSPACE, ERR_DEVICE = range(6)
+LAYOUT_AUTO, LAYOUT_PACKED, LAYOUT_IM2COL, LAYOUT_PAD_ONLY = range(4)
+LAYOUT_NAMES = {LAYOUT_AUTO: "auto", LAYOUT_PACKED: "packed", LAYOUT_IM2COL: "im2col",
+                LAYOUT_PAD_ONLY: "pad_only"}
+
+EXPORTS = [
+    "conv2d_int8", "conv2d_int8_ex", "conv2d_int8_workspace_bytes", "conv2d_int8_packed",
+    "conv2d_int8_num_tiles", "conv2d_int8_tile_info", "pack_layout", "pack_layout_bytes",
+    "pack_weights", "pack_weights_depth", "pack_weights_bytes", "im2col_int8", "im2col_bytes",
+    "gemm_int8_nt", "select_layout", "select_layout_weighted", "layout_overheads",
+    "conv_status_string",
+]
+
+
+class ConvDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("N", "C", "H", "W", "K", "R", "S", "stride", "pad")]
+
+
+class ConvError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def load(path: str | None = None):
+    """Load the built library (never builds; never falls back)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = path or _build.LIB
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: run `python -m paper_2104_04731_amd.build` "
+                           "(or __graft_entry__.build()) first")
+    lib = ctypes.CDLL(path)
+    i, vp, sz, dbl = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_double
+    dp, ip = ctypes.POINTER(ConvDesc), ctypes.POINTER(ctypes.c_int)
+    sig = {
+        "conv2d_int8": (i, [i] * 9 + [vp, vp, vp, vp]),
+        "conv2d_int8_ex": (i, [dp, i, i, vp, vp, i, vp, vp, sz, vp]),
+        "conv2d_int8_workspace_bytes": (sz, [dp, i, i, i]),
+        "conv2d_int8_packed": (i, [dp, i, i, vp, vp, vp, i, i, vp]),
+        "conv2d_int8_num_tiles": (i, []),
+        "conv2d_int8_tile_info": (i, [i, ip, ip, ip]),
+        "pack_layout": (i, [i] * 6 + [vp, vp, vp]),
+        "pack_layout_bytes": (sz, [i] * 6),
+        "pack_weights": (i, [i] * 6 + [vp, vp, vp]),
+        "pack_weights_depth": (i, [i] * 5),
+        "pack_weights_bytes": (sz, [i] * 6),
+        "im2col_int8": (i, [i] * 9 + [vp, vp, vp]),
+        "im2col_bytes": (sz, [i] * 9),
+        "gemm_int8_nt": (i, [i, i, i, vp, vp, vp, vp]),
+        "select_layout": (i, [dp, ip, ip, ctypes.POINTER(dbl)]),
+        "select_layout_weighted": (i, [dp, dbl, dbl, ip, ip, ctypes.POINTER(dbl)]),
+        "layout_overheads": (i, [dp, i, i] + [ctypes.POINTER(ctypes.c_int64)] * 3),
+        "conv_status_string": (ctypes.c_char_p, [i]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().conv_status_string(int(status)).decode()
+
+
+def _check(status, what):
+    if status != OK:
+        raise ConvError(status, what)
+
+
+def _stream(stream=None):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _ptr(t: torch.Tensor):
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _desc(N, C, H, W, K, R, S, stride, pad):
+    return ConvDesc(N, C, H, W, K, R, S, stride, pad)
+
+
+def out_hw(H, W, R, S, stride, pad):
+    return (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+
+
+def _require(t, dtype, what):
+    if not (t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError(f"{what} must be a contiguous {dtype} CUDA tensor")
+
+
+# ---- one-shot -------------------------------------------------------------------------------
+def conv2d_int8(x: torch.Tensor, w: torch.Tensor, stride: int, pad: int, out=None, stream=None):
+    _require(x, torch.int8, "input"); _require(w, torch.int8, "weights")
+    N, C, H, W = x.shape
+    K, C2, R, S = w.shape
+    if C2 != C:
+        raise ValueError("channel mismatch")
+    P, Q = out_hw(H, W, R, S, stride, pad)
+    if out is None:
+        out = torch.empty((N, K, max(P, 0), max(Q, 0)), dtype=torch.int32, device=x.device)
+    _check(load().conv2d_int8(N, C, H, W, K, R, S, stride, pad, _ptr(x), _ptr(w), _ptr(out),
+                              _stream(stream)), "conv2d_int8")
+    return out
+
+
+def conv2d_int8_workspace_bytes(dims, layout=LAYOUT_AUTO, cb=0, wt_is_packed=False) -> int:
+    d = _desc(*dims)
+    return int(load().conv2d_int8_workspace_bytes(ctypes.byref(d), layout, cb, int(wt_is_packed)))
+
+
+def conv2d_int8_ex(dims, layout, cb, x, w, out, workspace, wt_is_packed=False, stream=None):
+    d = _desc(*dims)
+    _check(load().conv2d_int8_ex(ctypes.byref(d), layout, cb, _ptr(x), _ptr(w), int(wt_is_packed),
+                                 _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                 _stream(stream)), "conv2d_int8_ex")
+    return out
+
+
+def conv2d_int8_packed(dims, layout, cb, x_packed, w_packed, out, tile=-1, split_k=0, stream=None):
+    d = _desc(*dims)
+    _check(load().conv2d_int8_packed(ctypes.byref(d), layout, cb, _ptr(x_packed), _ptr(w_packed),
+                                     _ptr(out), tile, split_k, _stream(stream)), "conv2d_int8_packed")
+    return out
+
+
+def num_tiles() -> int:
+    return load().conv2d_int8_num_tiles()
+
+
+def tile_info(tile: int):
+    r, c, t = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    _check(load().conv2d_int8_tile_info(tile, ctypes.byref(r), ctypes.byref(c), ctypes.byref(t)),
+           "conv2d_int8_tile_info")
+    return r.value, c.value, t.value
+
+
+# ---- layout rewrites ------------------------------------------------------------------------
+def pack_layout_bytes(N, C, H, W, cb, pad) -> int:
+    return int(load().pack_layout_bytes(N, C, H, W, cb, pad))
+
+
+def pack_layout(x: torch.Tensor, cb: int, pad: int, out=None, stream=None):
+    _require(x, torch.int8, "input")
+    N, C, H, W = x.shape
+    nbytes = pack_layout_bytes(N, C, H, W, cb, pad)
+    if out is None:
+        if nbytes == 0:
+            _check(ERR_UNSUPPORTED, "pack_layout")
+        out = torch.empty((N, (C + cb - 1) // cb, H + 2 * pad, W + 2 * pad, cb), dtype=torch.int8,
+                          device=x.device)
+    _check(load().pack_layout(N, C, H, W, cb, pad, _ptr(x), _ptr(out), _stream(stream)), "pack_layout")
+    return out
+
+
+def pack_weights_depth(C, R, S, layout, cb) -> int:
+    return int(load().pack_weights_depth(C, R, S, layout, cb))
+
+
+def pack_weights_bytes(K, C, R, S, layout, cb) -> int:
+    return int(load().pack_weights_bytes(K, C, R, S, layout, cb))
+
+
+def pack_weights(w: torch.Tensor, layout: int, cb: int, out=None, stream=None):
+    _require(w, torch.int8, "weights")
+    K, C, R, S = w.shape
+    if out is None:
+        depth = pack_weights_depth(C, R, S, layout, cb)
+        if depth == 0:
+            _check(ERR_UNSUPPORTED, "pack_weights")
+        out = torch.empty((K, depth), dtype=torch.int8, device=w.device)
+    _check(load().pack_weights(K, C, R, S, layout, cb, _ptr(w), _ptr(out), _stream(stream)),
+           "pack_weights")
+    return out
+
+
+def im2col_bytes(N, C, H, W, R, S, stride, pad, kg_pad) -> int:
+    return int(load().im2col_bytes(N, C, H, W, R, S, stride, pad, kg_pad))
+
+
+def im2col_int8(x: torch.Tensor, R, S, stride, pad, kg_pad=None, out=None, stream=None):
+    _require(x, torch.int8, "input")
+    N, C, H, W = x.shape
+    if kg_pad is None:
+        kg_pad = (C * R * S + 63) // 64 * 64
+    if out is None:
+        P, Q = out_hw(H, W, R, S, stride, pad)
+        out = torch.empty((N * max(P, 0) * max(Q, 0), kg_pad), dtype=torch.int8, device=x.device)
+    _check(load().im2col_int8(N, C, H, W, R, S, stride, pad, kg_pad, _ptr(x), _ptr(out),
+                              _stream(stream)), "im2col_int8")
+    return out
+
+
+def gemm_int8_nt(A: torch.Tensor, B: torch.Tensor, out=None, stream=None):
+    _require(A, torch.int8, "A"); _require(B, torch.int8, "B")
+    X, Z = A.shape
+    Y, Z2 = B.shape
+    if Z != Z2:
+        raise ValueError("depth mismatch")
+    if out is None:
+        out = torch.empty((X, Y), dtype=torch.int32, device=A.device)
+    _check(load().gemm_int8_nt(X, Y, Z, _ptr(A), _ptr(B), _ptr(out), _stream(stream)), "gemm_int8_nt")
+    return out
+
+
+# ---- selection (host only) --------------------------------------------------------------------
+def select_layout(dims, w_mac=None, w_data=None):
+    d = _desc(*dims)
+    lay, cb, sc = ctypes.c_int(), ctypes.c_int(), ctypes.c_double()
+    if w_mac is None:
+        st = load().select_layout(ctypes.byref(d), ctypes.byref(lay), ctypes.byref(cb), ctypes.byref(sc))
+    else:
+        st = load().select_layout_weighted(ctypes.byref(d), w_mac, w_data, ctypes.byref(lay),
+                                           ctypes.byref(cb), ctypes.byref(sc))
+    _check(st, "select_layout")
+    return lay.value, cb.value, sc.value
+
+
+def layout_overheads(dims, layout, cb):
+    d = _desc(*dims)
+    a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    _check(load().layout_overheads(ctypes.byref(d), layout, cb, ctypes.byref(a), ctypes.byref(b),
+                                   ctypes.byref(c)), "layout_overheads")
+    return a.value, b.value, c.value

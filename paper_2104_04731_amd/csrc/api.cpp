@@ -1,0 +1,355 @@
+// C-ABI glue: argument validation, layout resolution, workspace carving, launch order.
+// Every step of the path runs in the HIP kernels; nothing here touches tensor data.
+#include "../../include/conv2d_int8.h"
+#include "kernels.h"
+
+#include <mutex>
+
+using namespace c2i8;
+
+namespace {
+
+constexpr size_t WS_ALIGN = 256;
+constexpr long long INT_LIMIT = 2147483647LL;
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+int round_up_i(int x, int m) { return (x + m - 1) / m * m; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+int check_desc(const conv_desc_t *d)
+{
+    if (!d) return CONV_ERR_INVALID_ARG;
+    if (d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->K <= 0 || d->R <= 0 || d->S <= 0 ||
+        d->stride <= 0 || d->pad < 0)
+        return CONV_ERR_INVALID_ARG;
+    if (d->R > (long long)d->H + 2LL * d->pad || d->S > (long long)d->W + 2LL * d->pad)
+        return CONV_ERR_INVALID_ARG;
+    if ((long long)d->C * d->R * d->S > 131072LL) return CONV_ERR_OVERFLOW_RISK;
+    const long long Hp = (long long)d->H + 2LL * d->pad, Wp = (long long)d->W + 2LL * d->pad;
+    const long long P = (Hp - d->R) / d->stride + 1, Q = (Wp - d->S) / d->stride + 1;
+    if (Hp > INT_LIMIT || Wp > INT_LIMIT) return CONV_ERR_UNSUPPORTED;
+    if (P * Q > INT_LIMIT || (long long)d->N * P * Q > INT_LIMIT) return CONV_ERR_UNSUPPORTED;
+    return CONV_OK;
+}
+
+struct Plan {
+    int layout, cb, Cb, depth, P, Q, Hp, Wp;
+    long long M;
+    size_t x_bytes, w_bytes;
+};
+
+int default_block(int C)
+{
+    if (C >= 64) return 64;
+    if (C > 32) return 64;
+    if (C > 16) return 32;
+    return 16;
+}
+
+// Resolves AUTO / default block and sizes the rewritten operands.
+int make_plan(const conv_desc_t *d, int layout, int cb, Plan *pl)
+{
+    int rc = check_desc(d);
+    if (rc != CONV_OK) return rc;
+    if (layout == CONV_LAYOUT_AUTO) {
+        rc = select_layout(d, &layout, &cb, nullptr);
+        if (rc != CONV_OK) return rc;
+    }
+    if (layout == CONV_LAYOUT_PAD_ONLY) cb = round_up_i(d->C, 16);
+    else if (layout == CONV_LAYOUT_PACKED) {
+        if (cb == 0) cb = default_block(d->C);
+        if (cb < 16 || cb > 1024 || cb % 16) return CONV_ERR_UNSUPPORTED;
+    } else if (layout == CONV_LAYOUT_IM2COL) cb = 0;
+    else return CONV_ERR_INVALID_ARG;
+
+    pl->layout = layout;
+    pl->cb = cb;
+    pl->Hp = d->H + 2 * d->pad;
+    pl->Wp = d->W + 2 * d->pad;
+    pl->P = (pl->Hp - d->R) / d->stride + 1;
+    pl->Q = (pl->Wp - d->S) / d->stride + 1;
+    pl->M = (long long)d->N * pl->P * pl->Q;
+    if (layout == CONV_LAYOUT_IM2COL) {
+        pl->Cb = 0;
+        pl->depth = round_up_i(d->C * d->R * d->S, CONV_DEPTH_ALIGN);
+        pl->x_bytes = (size_t)pl->M * pl->depth;
+    } else {
+        pl->Cb = (d->C + cb - 1) / cb;
+        const long long real = (long long)pl->Cb * cb * d->R * d->S;
+        if (real > (1LL << 24)) return CONV_ERR_UNSUPPORTED;
+        pl->depth = round_up_i((int)real, CONV_DEPTH_ALIGN);
+        const long long img = (long long)pl->Cb * pl->Hp * pl->Wp * cb;
+        if (img > INT_LIMIT) return CONV_ERR_UNSUPPORTED;  // per-image offsets are 32-bit
+        pl->x_bytes = (size_t)d->N * (size_t)img;
+    }
+    pl->w_bytes = (size_t)d->K * pl->depth;
+    return CONV_OK;
+}
+
+GemmProblem gemm_problem(const conv_desc_t *d, const Plan &pl, const int8_t *x, const int8_t *w,
+                         int32_t *out)
+{
+    GemmProblem g{};
+    g.act = x;
+    g.wq = w;
+    g.out = out;
+    g.K = d->K;
+    g.M = (int)pl.M;
+    g.depth = pl.depth;
+    g.PQ = pl.P * pl.Q;
+    g.Q = pl.Q;
+    g.mode = pl.layout == CONV_LAYOUT_IM2COL ? ACT_MATRIX : ACT_BLOCKED;
+    g.stride = d->stride;
+    g.cb = pl.cb;
+    g.Cb = pl.Cb;
+    g.R = d->R;
+    g.S = d->S;
+    g.Hp = pl.Hp;
+    g.Wp = pl.Wp;
+    return g;
+}
+
+int run_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t st)
+{
+    if (tile >= gemm_num_tiles()) return CONV_ERR_INVALID_ARG;
+    if (split_k < 0) return CONV_ERR_INVALID_ARG;
+    int t = tile, s = split_k;
+    if (!aligned16(g.out) && s == 0) s = 1;  // the clear before a depth split writes 16-byte pieces
+    if (!aligned16(g.out) && s > 1) return CONV_ERR_INVALID_ARG;
+    gemm_pick(g, &t, &s);
+    return launch_gemm(g, t, s, st) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+}
+
+int rewrite_weights(const conv_desc_t *d, const Plan &pl, const int8_t *wt, int8_t *dst, hipStream_t st)
+{
+    hipError_t e;
+    if (pl.layout == CONV_LAYOUT_IM2COL)
+        e = launch_pack_weights_rows(d->K, d->C * d->R * d->S, pl.depth, wt, dst, st);
+    else
+        e = launch_pack_weights_blocked(d->K, d->C, d->R, d->S, pl.cb, pl.depth, wt, dst, st);
+    return e == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+}
+
+int rewrite_input(const conv_desc_t *d, const Plan &pl, const int8_t *in, int8_t *dst, hipStream_t st)
+{
+    hipError_t e;
+    if (pl.layout == CONV_LAYOUT_IM2COL)
+        e = launch_im2col(d->N, d->C, d->H, d->W, d->R, d->S, d->stride, d->pad, pl.P, pl.Q, pl.depth,
+                          in, dst, st);
+    else
+        e = launch_pack_layout(d->N, d->C, d->H, d->W, pl.cb, d->pad, in, dst, st);
+    return e == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+}
+
+// Cached workspace of the one-shot entry point, one per device, grown on demand.
+struct DeviceCache {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+};
+std::mutex g_cache_mutex;
+DeviceCache g_cache[64];
+
+}  // namespace
+
+extern "C" {
+
+const char *conv_status_string(int s)
+{
+    switch (s) {
+        case CONV_OK: return "ok";
+        case CONV_ERR_INVALID_ARG: return "invalid argument";
+        case CONV_ERR_UNSUPPORTED: return "unsupported problem";
+        case CONV_ERR_OVERFLOW_RISK: return "reduction too deep for an int32 accumulator";
+        case CONV_ERR_WORKSPACE: return "workspace too small or allocation failed";
+        case CONV_ERR_DEVICE: return "HIP error";
+    }
+    return "unknown status";
+}
+
+size_t pack_layout_bytes(int N, int C, int H, int W, int cb, int pad)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || pad < 0 || cb < 4 || cb > 1024 || cb % 4) return 0;
+    return (size_t)N * ((C + cb - 1) / cb) * cb * ((size_t)H + 2 * pad) * ((size_t)W + 2 * pad);
+}
+
+int pack_layout(int N, int C, int H, int W, int cb, int pad, const int8_t *src, int8_t *dst,
+                void *stream)
+{
+    if (!src || !dst || N <= 0 || C <= 0 || H <= 0 || W <= 0 || pad < 0) return CONV_ERR_INVALID_ARG;
+    if (cb < 4 || cb > 1024 || cb % 4) return CONV_ERR_UNSUPPORTED;
+    if (!aligned16(dst)) return CONV_ERR_INVALID_ARG;
+    if ((long long)H + 2LL * pad > INT_LIMIT || (long long)W + 2LL * pad > INT_LIMIT)
+        return CONV_ERR_UNSUPPORTED;
+    return launch_pack_layout(N, C, H, W, cb, pad, src, dst, (hipStream_t)stream) == hipSuccess
+               ? CONV_OK : CONV_ERR_DEVICE;
+}
+
+int pack_weights_depth(int C, int R, int S, int layout, int cb)
+{
+    if (C <= 0 || R <= 0 || S <= 0) return 0;
+    long long real;
+    if (layout == CONV_LAYOUT_IM2COL) real = (long long)C * R * S;
+    else if (layout == CONV_LAYOUT_PACKED || layout == CONV_LAYOUT_PAD_ONLY) {
+        if (layout == CONV_LAYOUT_PAD_ONLY) cb = round_up_i(C, 16);
+        if (cb < 16 || cb > 1024 || cb % 16) return 0;
+        real = (long long)((C + cb - 1) / cb) * cb * R * S;
+    } else return 0;
+    if (real > (1LL << 24)) return 0;
+    return round_up_i((int)real, CONV_DEPTH_ALIGN);
+}
+
+size_t pack_weights_bytes(int K, int C, int R, int S, int layout, int cb)
+{
+    if (K <= 0) return 0;
+    return (size_t)K * (size_t)pack_weights_depth(C, R, S, layout, cb);
+}
+
+int pack_weights(int K, int C, int R, int S, int layout, int cb, const int8_t *src, int8_t *dst,
+                 void *stream)
+{
+    if (!src || !dst || K <= 0 || C <= 0 || R <= 0 || S <= 0) return CONV_ERR_INVALID_ARG;
+    if (layout != CONV_LAYOUT_IM2COL && layout != CONV_LAYOUT_PACKED && layout != CONV_LAYOUT_PAD_ONLY)
+        return CONV_ERR_INVALID_ARG;
+    if (!aligned16(dst)) return CONV_ERR_INVALID_ARG;
+    if (layout == CONV_LAYOUT_PAD_ONLY) cb = round_up_i(C, 16);
+    const int depth = pack_weights_depth(C, R, S, layout, cb);
+    if (depth == 0) return CONV_ERR_UNSUPPORTED;
+    hipError_t e;
+    if (layout == CONV_LAYOUT_IM2COL)
+        e = launch_pack_weights_rows(K, C * R * S, depth, src, dst, (hipStream_t)stream);
+    else
+        e = launch_pack_weights_blocked(K, C, R, S, cb, depth, src, dst, (hipStream_t)stream);
+    return e == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+}
+
+size_t im2col_bytes(int N, int C, int H, int W, int R, int S, int stride, int pad, int kg_pad)
+{
+    conv_desc_t d{N, C, H, W, 1, R, S, stride, pad};
+    if (check_desc(&d) != CONV_OK || kg_pad < C * R * S || kg_pad % 16) return 0;
+    const long long P = (H + 2LL * pad - R) / stride + 1, Q = (W + 2LL * pad - S) / stride + 1;
+    return (size_t)N * P * Q * kg_pad;
+}
+
+int im2col_int8(int N, int C, int H, int W, int R, int S, int stride, int pad, int kg_pad,
+                const int8_t *src, int8_t *dst, void *stream)
+{
+    conv_desc_t d{N, C, H, W, 1, R, S, stride, pad};
+    int rc = check_desc(&d);
+    if (rc != CONV_OK) return rc;
+    if (!src || !dst || !aligned16(dst)) return CONV_ERR_INVALID_ARG;
+    if (kg_pad < C * R * S || kg_pad % 16) return CONV_ERR_INVALID_ARG;
+    const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+    return launch_im2col(N, C, H, W, R, S, stride, pad, P, Q, kg_pad, src, dst, (hipStream_t)stream) ==
+                   hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+}
+
+int gemm_int8_nt(int X, int Y, int Z, const int8_t *A, const int8_t *B, int32_t *Cout, void *stream)
+{
+    if (X <= 0 || Y <= 0 || Z <= 0 || !A || !B || !Cout) return CONV_ERR_INVALID_ARG;
+    if (Z % CONV_DEPTH_ALIGN) return CONV_ERR_UNSUPPORTED;
+    if (Z > 131072) return CONV_ERR_OVERFLOW_RISK;
+    if (!aligned16(A) || !aligned16(B)) return CONV_ERR_INVALID_ARG;
+    GemmProblem g{};
+    g.act = B;
+    g.wq = A;
+    g.out = Cout;
+    g.K = X;
+    g.M = Y;
+    g.depth = Z;
+    g.PQ = Y;
+    g.Q = Y;
+    g.mode = ACT_MATRIX;
+    return run_gemm(g, -1, 0, (hipStream_t)stream);
+}
+
+int conv2d_int8_num_tiles(void) { return gemm_num_tiles(); }
+
+int conv2d_int8_tile_info(int tile, int *rows, int *cols, int *threads)
+{
+    if (tile < 0 || tile >= gemm_num_tiles()) return CONV_ERR_INVALID_ARG;
+    TileInfo t = gemm_tile_info(tile);
+    if (rows) *rows = t.rows;
+    if (cols) *cols = t.cols;
+    if (threads) *threads = t.threads;
+    return CONV_OK;
+}
+
+int conv2d_int8_packed(const conv_desc_t *desc, int layout, int cb, const int8_t *in_packed,
+                       const int8_t *wt_packed, int32_t *out, int tile, int split_k, void *stream)
+{
+    if (layout == CONV_LAYOUT_AUTO) return CONV_ERR_INVALID_ARG;
+    Plan pl;
+    int rc = make_plan(desc, layout, cb, &pl);
+    if (rc != CONV_OK) return rc;
+    if (!in_packed || !wt_packed || !out || !aligned16(in_packed) || !aligned16(wt_packed))
+        return CONV_ERR_INVALID_ARG;
+    return run_gemm(gemm_problem(desc, pl, in_packed, wt_packed, out), tile, split_k,
+                    (hipStream_t)stream);
+}
+
+size_t conv2d_int8_workspace_bytes(const conv_desc_t *desc, int layout, int cb, int wt_is_packed)
+{
+    Plan pl;
+    if (make_plan(desc, layout, cb, &pl) != CONV_OK) return 0;
+    return align_up(pl.x_bytes, WS_ALIGN) + (wt_is_packed ? 0 : align_up(pl.w_bytes, WS_ALIGN));
+}
+
+int conv2d_int8_ex(const conv_desc_t *desc, int layout, int cb, const int8_t *in, const int8_t *wt,
+                   int wt_is_packed, int32_t *out, void *workspace, size_t workspace_bytes,
+                   void *stream)
+{
+    Plan pl;
+    int rc = make_plan(desc, layout, cb, &pl);
+    if (rc != CONV_OK) return rc;
+    if (!in || !wt || !out || !workspace) return CONV_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(workspace) % WS_ALIGN) return CONV_ERR_INVALID_ARG;
+    if (wt_is_packed && !aligned16(wt)) return CONV_ERR_INVALID_ARG;
+    const size_t xb = align_up(pl.x_bytes, WS_ALIGN);
+    const size_t need = xb + (wt_is_packed ? 0 : align_up(pl.w_bytes, WS_ALIGN));
+    if (workspace_bytes < need) return CONV_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    int8_t *xq = static_cast<int8_t *>(workspace);
+    const int8_t *wq = wt;
+    if (!wt_is_packed) {
+        int8_t *wdst = xq + xb;
+        rc = rewrite_weights(desc, pl, wt, wdst, st);
+        if (rc != CONV_OK) return rc;
+        wq = wdst;
+    }
+    rc = rewrite_input(desc, pl, in, xq, st);
+    if (rc != CONV_OK) return rc;
+    return run_gemm(gemm_problem(desc, pl, xq, wq, out), -1, 0, st);
+}
+
+int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                const int8_t *in, const int8_t *wt, int32_t *out, void *stream)
+{
+    conv_desc_t d{N, C, H, W, K, R, S, stride, pad};
+    Plan pl;
+    int rc = make_plan(&d, CONV_LAYOUT_AUTO, 0, &pl);
+    if (rc != CONV_OK) return rc;
+    if (!in || !wt || !out) return CONV_ERR_INVALID_ARG;
+    const size_t need = align_up(pl.x_bytes, WS_ALIGN) + align_up(pl.w_bytes, WS_ALIGN);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CONV_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    DeviceCache &c = g_cache[dev];
+    if (c.bytes < need) {
+        // Work already enqueued may still read the old block: drain the device before freeing it.
+        if (c.ptr) {
+            if (hipDeviceSynchronize() != hipSuccess) return CONV_ERR_DEVICE;
+            (void)hipFree(c.ptr);
+            c.ptr = nullptr;
+            c.bytes = 0;
+        }
+        const size_t want = align_up(need + need / 4, 1 << 20);
+        if (hipMalloc(&c.ptr, want) != hipSuccess) {
+            c.ptr = nullptr;
+            return CONV_ERR_WORKSPACE;
+        }
+        c.bytes = want;
+    }
+    return conv2d_int8_ex(&d, pl.layout, pl.cb, in, wt, 0, out, c.ptr, c.bytes, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,51 @@
+// Internal launcher interface between the C-ABI glue and the HIP kernels.
+// Launchers validate nothing: the glue has already checked every argument.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace c2i8 {
+
+// How the GEMM stage finds the depth-contiguous activation row of output pixel m.
+enum ActMode : int {
+    ACT_BLOCKED = 0,  // [N][Cb][Hp][Wp][cb] produced by pack_layout
+    ACT_MATRIX = 1    // [M][depth] produced by im2col (or any row-major matrix)
+};
+
+struct GemmProblem {
+    const int8_t *act;  // activations
+    const int8_t *wq;   // weights [K][depth]
+    int32_t *out;       // [N][K][PQ]
+    int K;              // output channels (GEMM rows)
+    int M;              // output pixels N*P*Q (GEMM columns)
+    int depth;          // fused reduction length, multiple of 64
+    int PQ, Q;          // pixels per image, output width
+    int mode;           // ActMode
+    // ACT_BLOCKED only:
+    int stride, cb, Cb, R, S, Hp, Wp;
+};
+
+struct TileInfo {
+    int rows, cols, threads;
+};
+
+int gemm_num_tiles();
+TileInfo gemm_tile_info(int tile);
+// Chooses tile / split when tile < 0 / split_k <= 0.
+void gemm_pick(const GemmProblem &g, int *tile, int *split_k);
+// split_k > 1 clears `out` first and accumulates with atomics.
+hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t st);
+
+hipError_t launch_pack_layout(int N, int C, int H, int W, int cb, int pad,
+                              const int8_t *src, int8_t *dst, hipStream_t st);
+hipError_t launch_pack_weights_blocked(int K, int C, int R, int S, int cb, int depth,
+                                       const int8_t *src, int8_t *dst, hipStream_t st);
+hipError_t launch_pack_weights_rows(int K, int CRS, int depth,
+                                    const int8_t *src, int8_t *dst, hipStream_t st);
+hipError_t launch_im2col(int N, int C, int H, int W, int R, int S, int stride, int pad,
+                         int P, int Q, int kg_pad,
+                         const int8_t *src, int8_t *dst, hipStream_t st);
+hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t st);
+
+}  // namespace c2i8

@@ -1,0 +1,100 @@
+// Per-shape layout selection: the candidate-selection term of Sec. 4.4 evaluated over the
+// handful of rewrites this library implements (Table 2), instead of over a solver's
+// candidate list.  Host arithmetic only.
+#include "../../include/conv2d_int8.h"
+
+#include <stdint.h>
+
+namespace {
+
+// Extents of the matrix intrinsic the dimensions are padded to (Sec. 4.2.4 rule b):
+// 32 output pixels x 32 output channels per MFMA block, depth in 64-byte steps.
+constexpr int64_t UNIT_PIXELS = 32, UNIT_CHANNELS = 32, UNIT_DEPTH = CONV_DEPTH_ALIGN;
+
+int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+struct Cand {
+    int layout, cb;
+};
+
+}  // namespace
+
+extern "C" int layout_overheads(const conv_desc_t *d, int layout, int cb,
+                                int64_t *o_mac, int64_t *o_data, int64_t *rewritten)
+{
+    if (!d || d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->K <= 0 || d->R <= 0 ||
+        d->S <= 0 || d->stride <= 0 || d->pad < 0 || d->R > d->H + 2 * d->pad ||
+        d->S > d->W + 2 * d->pad)
+        return CONV_ERR_INVALID_ARG;
+    if (layout == CONV_LAYOUT_PAD_ONLY) cb = (int)round_up(d->C, 16);
+    if (layout != CONV_LAYOUT_IM2COL && layout != CONV_LAYOUT_PACKED && layout != CONV_LAYOUT_PAD_ONLY)
+        return CONV_ERR_INVALID_ARG;
+    if (layout != CONV_LAYOUT_IM2COL && (cb <= 0 || cb % 16)) return CONV_ERR_INVALID_ARG;
+
+    const int64_t P = (d->H + 2 * d->pad - d->R) / d->stride + 1;
+    const int64_t Q = (d->W + 2 * d->pad - d->S) / d->stride + 1;
+    const int64_t M = (int64_t)d->N * P * Q;
+    const int64_t taps = (int64_t)d->R * d->S;
+    const int64_t mac_min = M * d->K * d->C * taps;
+    int64_t depth, x_elems;
+    if (layout == CONV_LAYOUT_IM2COL) {
+        depth = round_up(d->C * taps, UNIT_DEPTH);
+        x_elems = M * depth;
+    } else {
+        const int64_t cpad = round_up(d->C, cb);
+        depth = round_up(cpad * taps, UNIT_DEPTH);
+        x_elems = (int64_t)d->N * cpad * (d->H + 2 * d->pad) * (d->W + 2 * d->pad);
+    }
+    const int64_t w_elems = (int64_t)d->K * depth;
+    const int64_t mac_total = round_up(M, UNIT_PIXELS) * round_up(d->K, UNIT_CHANNELS) * depth;
+    if (o_mac) *o_mac = mac_total - mac_min;
+    // rewrite writes X' and W', the GEMM stage reads them again; in, wt, out are the minimum
+    if (o_data) *o_data = 2 * x_elems + 2 * w_elems;
+    if (rewritten) *rewritten = x_elems + w_elems;
+    return CONV_OK;
+}
+
+extern "C" int select_layout_weighted(const conv_desc_t *d, double w_mac, double w_data,
+                                      int *layout, int *cb, double *score)
+{
+    if (!d || !layout || !cb) return CONV_ERR_INVALID_ARG;
+    const Cand cands[] = {{CONV_LAYOUT_PACKED, 64}, {CONV_LAYOUT_PACKED, 32}, {CONV_LAYOUT_PACKED, 16},
+                          {CONV_LAYOUT_IM2COL, 0},  {CONV_LAYOUT_PAD_ONLY, 0}};
+    bool have = false;
+    double best_score = 0;
+    int64_t best_ws = 0;
+    Cand best{0, 0};
+    for (const Cand &c0 : cands) {
+        Cand c = c0;
+        if (c.layout == CONV_LAYOUT_PAD_ONLY) c.cb = (int)round_up(d->C, 16);
+        int64_t om, od, ws;
+        int rc = layout_overheads(d, c.layout, c.cb, &om, &od, &ws);
+        if (rc != CONV_OK) return rc;
+        const double sc = w_mac * (double)om + w_data * (double)od;
+        bool better = !have;
+        if (have) {
+            if (sc != best_score) better = sc < best_score;
+            else if (ws != best_ws) better = ws < best_ws;
+            else if (c.layout != best.layout) better = c.layout < best.layout;
+            else better = c.cb > best.cb;
+        }
+        if (better) {
+            have = true;
+            best_score = sc;
+            best_ws = ws;
+            best = c;
+        }
+    }
+    *layout = best.layout;
+    *cb = best.cb;
+    if (score) *score = best_score;
+    return CONV_OK;
+}
+
+// MI355X weights: seconds per issued MAC at the dense int8 MFMA rate and seconds per moved
+// byte (int8 elements) at the HBM3E rate -- the "used hardware" the paper leaves w to.
+extern "C" int select_layout(const conv_desc_t *d, int *layout, int *cb, double *score)
+{
+    const double w_mac = 1.0 / 2.5165e15, w_data = 1.0 / 8.0e12;
+    return select_layout_weighted(d, w_mac, w_data, layout, cb, score);
+}

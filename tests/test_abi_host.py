@@ -1,0 +1,102 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every declared
+symbol, validates arguments before touching the device, and its layout selector and size
+queries agree with the independently written definitions."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import layouts, selection as sel
+from paper_2104_04731_amd.inputs import CONFIGS, PAPER_SHAPES
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "conv2d_int8.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^\s*(?:const\s+)?(?:int|size_t|char)\s*\*?\s*(\w+)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_header_declares_what_the_binding_lists(lib):
+    assert declared_functions() == sorted(lib.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol(lib):
+    raw = ctypes.CDLL(lib._build.LIB)
+    for name in declared_functions():
+        assert hasattr(raw, name), name
+
+
+ALL_SHAPES = list(CONFIGS.values()) + PAPER_SHAPES
+
+
+@pytest.mark.parametrize("cfg", ALL_SHAPES, ids=lambda c: c.name)
+def test_selector_matches_definition(lib, cfg):
+    for w in [(1.0, 1.0), (1.0, 0.0), (0.0, 1.0), (1.0 / 2.5165e15, 1.0 / 8.0e12), (3.0, 7.0)]:
+        got = lib.select_layout(cfg.dims(), *w)
+        want = sel.select(*cfg.dims(), *w)
+        assert got[:2] == want[:2]
+        assert got[2] == pytest.approx(want[2], rel=1e-12)
+    for layout, cb in sel.candidates(cfg.C):
+        assert lib.layout_overheads(cfg.dims(), layout, cb) == sel.overheads(*cfg.dims(), layout, cb)
+
+
+def test_default_selector_uses_hardware_weights(lib):
+    for cfg in ALL_SHAPES:
+        assert lib.select_layout(cfg.dims())[:2] == \
+            sel.select(*cfg.dims(), 1.0 / 2.5165e15, 1.0 / 8.0e12)[:2]
+
+
+def test_size_queries_match_definitions(lib):
+    for cfg in ALL_SHAPES:
+        N, C, H, W, K, R, S, st, pad = cfg.dims()
+        for cb in (16, 32, 64):
+            Cb = -(-C // cb)
+            assert lib.pack_layout_bytes(N, C, H, W, cb, pad) == N * Cb * cb * (H + 2 * pad) * (W + 2 * pad)
+            assert lib.pack_weights_depth(C, R, S, lib.LAYOUT_PACKED, cb) == layouts.packed_depth(C, R, S, cb)
+        assert lib.pack_weights_depth(C, R, S, lib.LAYOUT_IM2COL, 0) == layouts.ceil_to(C * R * S, 64)
+        assert lib.pack_weights_depth(C, R, S, lib.LAYOUT_PAD_ONLY, 0) == \
+            layouts.packed_depth(C, R, S, layouts.ceil_to(C, 16))
+        kg = layouts.ceil_to(C * R * S, 64)
+        assert lib.im2col_bytes(N, C, H, W, R, S, st, pad, kg) == cfg.M * kg
+        ws = lib.conv2d_int8_workspace_bytes(cfg.dims(), lib.LAYOUT_IM2COL, 0)
+        assert ws >= cfg.M * kg + K * kg
+
+
+def _null_call(lib, dims):
+    """Invalid problems must be rejected before any pointer is used or any launch is made."""
+    raw = lib.load()
+    return raw.conv2d_int8(*dims, None, None, None, None)
+
+
+@pytest.mark.parametrize("dims,want", [
+    ((0, 1, 4, 4, 1, 3, 3, 1, 1), 1), ((1, 1, 4, 4, 1, 3, 3, 0, 1), 1), ((1, 1, 4, 4, 1, 3, 3, 1, -1), 1),
+    ((1, 1, 2, 2, 1, 3, 3, 1, 0), 1), ((1, 1, 4, 4, 1, 7, 3, 1, 1), 1),
+    ((1, 16384, 8, 8, 1, 3, 3, 1, 1), 3),          # C*R*S = 147456 > 131072
+    ((1, 16, 8, 8, 4, 3, 3, 1, 1), 1),             # valid problem, null tensors
+])
+def test_validation_happens_before_device_work(lib, dims, want):
+    assert _null_call(lib, dims) == want
+
+
+def test_ex_and_packed_validation(lib):
+    raw = lib.load()
+    d = lib.ConvDesc(1, 16, 8, 8, 4, 3, 3, 1, 1)
+    assert raw.conv2d_int8_packed(ctypes.byref(d), lib.LAYOUT_AUTO, 0, None, None, None, -1, 0, None) == 1
+    assert raw.conv2d_int8_packed(ctypes.byref(d), lib.LAYOUT_PACKED, 24, None, None, None, -1, 0, None) == 2
+    assert raw.conv2d_int8_packed(ctypes.byref(d), lib.LAYOUT_PACKED, 16, None, None, None, -1, 0, None) == 1
+    assert raw.conv2d_int8_ex(ctypes.byref(d), 7, 0, None, None, 0, None, None, 0, None) == 1
+    assert raw.pack_layout(1, 3, 4, 4, 5, 0, None, None, None) == 1      # null first
+    assert raw.pack_layout_bytes(1, 3, 4, 4, 5, 0) == 0                    # cb not a multiple of 4
+    assert raw.gemm_int8_nt(4, 4, 60, None, None, None, None) == 1
+    assert raw.conv2d_int8_workspace_bytes(None, 0, 0, 0) == 0
+    assert lib.status_string(3).startswith("reduction")
+    assert lib.num_tiles() >= 4
+    for t in range(lib.num_tiles()):
+        r, c, th = lib.tile_info(t)
+        assert r % 32 == 0 and c % 32 == 0 and th % 64 == 0

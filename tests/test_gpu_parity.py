@@ -1,0 +1,227 @@
+"""GPU parity: every kernel, through the C-ABI, against the CPU definitions, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import direct, layouts
+from paper_2104_04731_amd.inputs import CONFIGS, PAPER_SHAPES, ConvShape, uniform_int8
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+_ORACLE_CACHE = {}
+
+
+def oracle_conv(cfg):
+    if cfg.name not in _ORACLE_CACHE:
+        x, w = cfg.make()
+        _ORACLE_CACHE[cfg.name] = (x, w, direct.conv2d_int8(x, w, cfg.stride, cfg.pad))
+    return _ORACLE_CACHE[cfg.name]
+
+
+# ---- layout rewrites ----------------------------------------------------------------------
+@pytest.mark.parametrize("shape,cb,pad", [
+    ((2, 37, 5, 6), 16, 1), ((1, 3, 31, 29), 16, 3), ((3, 64, 14, 14), 64, 1), ((1, 70, 9, 130), 32, 0),
+    ((1, 16, 14, 14), 16, 1), ((2, 5, 7, 7), 4, 2), ((2, 20, 7, 9), 8, 1), ((1, 1, 161, 500), 16, 0),
+    ((1, 100, 3, 3), 112, 2), ((1, 1, 1, 1), 16, 0),
+])
+def test_pack_layout(lib, shape, cb, pad):
+    x = uniform_int8(sum(shape) + cb, shape)
+    got = host(lib.pack_layout(dev(x), cb, pad))
+    np.testing.assert_array_equal(got, layouts.pack_layout(x, cb, pad))
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4a", "C5"])
+def test_pack_layout_configs(lib, name):
+    cfg = CONFIGS[name]
+    x, _ = cfg.make()
+    for cb in (16, 64):
+        np.testing.assert_array_equal(host(lib.pack_layout(dev(x), cb, cfg.pad)),
+                                      layouts.pack_layout(x, cb, cfg.pad))
+
+
+@pytest.mark.parametrize("wshape,cb", [((5, 3, 7, 7), 16), ((16, 16, 3, 3), 16), ((7, 40, 3, 2), 32),
+                                       ((64, 64, 3, 3), 64), ((9, 70, 1, 1), 64), ((3, 33, 2, 3), 48),
+                                       ((32, 1, 20, 5), 16)])
+def test_pack_weights(lib, wshape, cb):
+    w = uniform_int8(sum(wshape), wshape)
+    got = host(lib.pack_weights(dev(w), lib.LAYOUT_PACKED, cb))
+    np.testing.assert_array_equal(got, layouts.pack_weights_blocked(w, cb))
+    got = host(lib.pack_weights(dev(w), lib.LAYOUT_IM2COL, 0))
+    np.testing.assert_array_equal(got, layouts.pack_weights_im2col(w))
+    cbp = layouts.ceil_to(wshape[1], 16)
+    got = host(lib.pack_weights(dev(w), lib.LAYOUT_PAD_ONLY, 0))
+    np.testing.assert_array_equal(got, layouts.pack_weights_blocked(w, cbp))
+
+
+@pytest.mark.parametrize("dims", [(2, 3, 6, 7, 3, 2, 2, 1), (1, 3, 31, 29, 7, 7, 2, 3), (1, 16, 14, 14, 3, 3, 1, 1),
+                                  (2, 1, 41, 50, 20, 5, 2, 0), (1, 5, 9, 9, 1, 1, 1, 0), (1, 2, 5, 5, 7, 7, 1, 1),
+                                  (1, 70, 6, 6, 3, 3, 3, 2)])
+def test_im2col(lib, dims):
+    N, C, H, W, R, S, st, pad = dims
+    x = uniform_int8(sum(dims), (N, C, H, W))
+    got = host(lib.im2col_int8(dev(x), R, S, st, pad))
+    np.testing.assert_array_equal(got, layouts.im2col(x, R, S, st, pad))
+
+
+@pytest.mark.parametrize("name", ["C3", "C5"])
+def test_im2col_configs(lib, name):
+    cfg = CONFIGS[name]
+    x, _ = cfg.make()
+    got = host(lib.im2col_int8(dev(x), cfg.R, cfg.S, cfg.stride, cfg.pad))
+    np.testing.assert_array_equal(got, layouts.im2col(x, cfg.R, cfg.S, cfg.stride, cfg.pad))
+
+
+# ---- the matrix intrinsic -------------------------------------------------------------------
+def test_gemm_unit_hand_example(lib):
+    A = np.zeros((1, 64), np.int8); A[0, :16] = np.arange(1, 17)
+    B = np.zeros((16, 64), np.int8)
+    B[:, :16] = np.array([[y - z for z in range(16)] for y in range(16)])
+    got = host(lib.gemm_int8_nt(dev(A), dev(B)))
+    np.testing.assert_array_equal(got[0], 136 * np.arange(16) - 1360)
+
+
+@pytest.mark.parametrize("X,Y,Z", [(1, 1, 64), (33, 65, 128), (70, 300, 192), (129, 257, 64), (300, 130, 640),
+                                   (16, 196, 192), (512, 100, 2304)])
+def test_gemm_nt(lib, X, Y, Z):
+    A = uniform_int8(X * 7 + Z, (X, Z)); B = uniform_int8(Y * 3 + Z, (Y, Z))
+    np.testing.assert_array_equal(host(lib.gemm_int8_nt(dev(A), dev(B))), layouts.gemm_nt(A, B))
+
+
+def test_gemm_every_tile_and_split(lib):
+    """Each tile shape, with and without a depth split, on a ragged problem spanning several tiles."""
+    X, Y, Z = 300, 530, 448  # 7 depth steps
+    cfg = ConvShape("g", 1, Z, 1, Y, X, 1, 1, 1, 0)
+    A = uniform_int8(901, (X, Z)); B = uniform_int8(902, (Y, Z))
+    want = layouts.gemm_nt(A, B).reshape(1, X, 1, Y)
+    dA, dB = dev(A), dev(B)
+    for tile in range(lib.num_tiles()):
+        for split in (1, 2, 3, 7):
+            out = torch.full((1, X, 1, Y), -7, dtype=torch.int32, device=DEV)
+            # a row-major [Y][Z] matrix is the im2col operand of a 1x1 convolution over Y pixels
+            lib.conv2d_int8_packed(cfg.dims(), lib.LAYOUT_IM2COL, 0, dB, dA, out, tile=tile, split_k=split)
+            np.testing.assert_array_equal(host(out), want, err_msg=f"tile {tile} split {split}")
+
+
+# ---- convolution ----------------------------------------------------------------------------
+LAYOUT_CASES = [("packed", 16), ("packed", 32), ("packed", 64), ("im2col", 0), ("pad_only", 0)]
+
+
+def run_layout(lib, cfg, x, w, lname, cb, tile=-1, split_k=0):
+    lay = {"packed": lib.LAYOUT_PACKED, "im2col": lib.LAYOUT_IM2COL, "pad_only": lib.LAYOUT_PAD_ONLY}[lname]
+    dx, dw = dev(x), dev(w)
+    if lay == lib.LAYOUT_IM2COL:
+        xp = lib.im2col_int8(dx, cfg.R, cfg.S, cfg.stride, cfg.pad)
+    else:
+        cbe = cb if lay == lib.LAYOUT_PACKED else layouts.ceil_to(cfg.C, 16)
+        xp = lib.pack_layout(dx, cbe, cfg.pad)
+    wp = lib.pack_weights(dw, lay, cb)
+    out = torch.full((cfg.N, cfg.K, cfg.P, cfg.Q), 12345, dtype=torch.int32, device=DEV)
+    lib.conv2d_int8_packed(cfg.dims(), lay, cb, xp, wp, out, tile=tile, split_k=split_k)
+    return host(out)
+
+
+@pytest.mark.parametrize("name", list(CONFIGS))
+@pytest.mark.parametrize("lname,cb", LAYOUT_CASES)
+def test_conv_configs_every_layout(lib, name, lname, cb):
+    cfg = CONFIGS[name]
+    x, w, want = oracle_conv(cfg)
+    got = run_layout(lib, cfg, x, w, lname, cb)
+    assert np.array_equal(got, want), f"{name} {lname} cb={cb}: {np.count_nonzero(got != want)} mismatches"
+
+
+@pytest.mark.parametrize("name", list(CONFIGS))
+def test_conv_configs_one_shot(lib, name):
+    cfg = CONFIGS[name]
+    x, w, want = oracle_conv(cfg)
+    got = host(lib.conv2d_int8(dev(x), dev(w), cfg.stride, cfg.pad))
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("name", ["C2", "C4a"])
+def test_conv_every_tile_and_split(lib, name):
+    cfg = CONFIGS[name]
+    x, w, want = oracle_conv(cfg)
+    for tile in range(lib.num_tiles()):
+        for split in (1, 3, 4):
+            got = run_layout(lib, cfg, x, w, "packed", 64, tile=tile, split_k=split)
+            assert np.array_equal(got, want), f"tile {tile} split {split}"
+
+
+@pytest.mark.parametrize("cfg", PAPER_SHAPES, ids=lambda c: c.name)
+def test_conv_paper_table_shapes(lib, cfg):
+    x, w, want = oracle_conv(cfg)
+    got = host(lib.conv2d_int8(dev(x), dev(w), cfg.stride, cfg.pad))
+    assert np.array_equal(got, want)
+    for lname, cb in (("packed", 16), ("im2col", 0)):
+        assert np.array_equal(run_layout(lib, cfg, x, w, lname, cb), want), lname
+
+
+EDGE = [
+    ConvShape("one-pixel", 1, 1, 1, 1, 1, 1, 1, 1, 0), ConvShape("P1Q1", 1, 2, 3, 4, 2, 5, 6, 1, 1),
+    ConvShape("stride3", 2, 5, 10, 11, 3, 3, 2, 3, 1), ConvShape("wide-pad", 1, 3, 4, 4, 2, 3, 3, 1, 3),
+    ConvShape("K1", 1, 17, 6, 6, 1, 3, 3, 1, 1), ConvShape("K33", 3, 33, 5, 7, 33, 2, 2, 2, 0),
+    ConvShape("ragged", 1, 65, 13, 9, 70, 3, 3, 1, 1), ConvShape("tall-kernel", 1, 1, 30, 6, 4, 20, 5, 2, 0),
+]
+
+
+@pytest.mark.parametrize("cfg", EDGE, ids=lambda c: c.name)
+def test_conv_edge_shapes(lib, cfg):
+    x = uniform_int8(77, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(78, (cfg.K, cfg.C, cfg.R, cfg.S))
+    want = direct.conv2d_int8(x, w, cfg.stride, cfg.pad)
+    assert np.array_equal(host(lib.conv2d_int8(dev(x), dev(w), cfg.stride, cfg.pad)), want)
+    for lname, cb in LAYOUT_CASES:
+        assert np.array_equal(run_layout(lib, cfg, x, w, lname, cb), want), lname
+
+
+def test_extreme_values(lib):
+    """-128 * -128 in every tap: catches unsigned operands or a narrow product."""
+    cfg = ConvShape("ext", 1, 64, 8, 8, 32, 3, 3, 1, 1)
+    x = np.full((1, 64, 8, 8), -128, np.int8); w = np.full((32, 64, 3, 3), -128, np.int8)
+    want = direct.conv2d_int8(x, w, 1, 1)
+    assert want.max() == 64 * 9 * 16384
+    assert np.array_equal(host(lib.conv2d_int8(dev(x), dev(w), 1, 1)), want)
+    assert np.array_equal(run_layout(lib, cfg, x, w, "im2col", 0), want)
+
+
+def test_ex_with_caller_workspace_and_prepacked_weights(lib):
+    cfg = CONFIGS["C2"]
+    x, w, want = oracle_conv(cfg)
+    dx, dw = dev(x), dev(w)
+    for lay, cb in ((lib.LAYOUT_PACKED, 64), (lib.LAYOUT_IM2COL, 0), (lib.LAYOUT_AUTO, 0)):
+        ws = torch.empty(lib.conv2d_int8_workspace_bytes(cfg.dims(), lay, cb), dtype=torch.int8, device=DEV)
+        out = torch.empty((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=DEV)
+        lib.conv2d_int8_ex(cfg.dims(), lay, cb, dx, dw, out, ws)
+        assert np.array_equal(host(out), want)
+    wp = lib.pack_weights(dw, lib.LAYOUT_PACKED, 64)
+    ws = torch.empty(lib.conv2d_int8_workspace_bytes(cfg.dims(), lib.LAYOUT_PACKED, 64, True),
+                     dtype=torch.int8, device=DEV)
+    out = torch.empty((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=DEV)
+    lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_PACKED, 64, dx, wp, out, ws, wt_is_packed=True)
+    assert np.array_equal(host(out), want)
+    small = torch.empty(256, dtype=torch.int8, device=DEV)
+    with pytest.raises(lib.ConvError) as e:
+        lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_PACKED, 64, dx, dw, out, small)
+    assert e.value.status == lib.ERR_WORKSPACE
+
+
+def test_non_default_stream(lib):
+    cfg = CONFIGS["C1"]
+    x, w, want = oracle_conv(cfg)
+    s = torch.cuda.Stream()
+    dx, dw = dev(x), dev(w)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        out = lib.conv2d_int8(dx, dw, cfg.stride, cfg.pad)
+    s.synchronize()
+    assert np.array_equal(out.cpu().numpy(), want)
