@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the int8 conv2d hot path (layout rewrite -> int8 MFMA GEMM stage) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps 200] [--warmup 10] [--workload C4] [--no-extras]
+
+A step is one pass of the whole path -- input rewrite, weight rewrite, GEMM stage -- over the
+headline workload, through the one-shot C-ABI call, inputs resident in HBM.  One JSON line is
+printed; `value` is effective int8 TOPS = 2*N*K*P*Q*C*R*S / time with the unpadded op count.
+`per_config` carries, for every benchmark configuration, the operator-only, transform-only
+and combined times (the three columns of the paper's Table 3), `n_scaled` the same kernels at
+a batch size large enough to reach steady state (supplementary).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_OPS = 5.0e15   # dense int8 MFMA, MI355X
+PEAK_HBM_BPS = 8.0e12    # HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="C4", help="C1, C2, C3, C4 (= C4a + C4b), C5")
+    ap.add_argument("--no-extras", action="store_true", help="headline only (for profiling runs)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path shards over batch or output "
+              "channels without any exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2104_04731_amd import binding as lib
+    from paper_2104_04731_amd.inputs import CONFIGS
+
+    lib.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    def timed(fn, steps, warmup):
+        """(wall ms per call, event ms per call) over `steps` back-to-back calls.
+
+        The calls are captured once into a HIP graph and the graph is replayed, so that the
+        timed region holds exactly `steps` passes of device work and no per-call host cost
+        (the kernels here run for microseconds; a Python call costs more than that)."""
+        for _ in range(max(warmup, 1)):
+            fn()                                  # also sizes the library's cached workspace
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(steps):
+                fn()
+        graph.replay()                            # untimed replay: graph upload, caches warm
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+    class Case:
+        """Device buffers and closures for one convolution."""
+
+        def __init__(self, cfg):
+            self.cfg = cfg
+            x, w = cfg.make()
+            self.x = torch.from_numpy(x).to(dev)
+            self.w = torch.from_numpy(w).to(dev)
+            self.out = torch.empty((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=dev)
+            self.layout, self.cb, _ = lib.select_layout(cfg.dims())
+            self.tile, self.split = lib.query_tiling(cfg.dims(), self.layout, self.cb)
+            if self.layout == lib.LAYOUT_IM2COL:
+                self.xp = lib.im2col_int8(self.x, cfg.R, cfg.S, cfg.stride, cfg.pad)
+                self.rewrite = lambda: lib.im2col_int8(self.x, cfg.R, cfg.S, cfg.stride, cfg.pad, out=self.xp)
+            else:
+                self.xp = lib.pack_layout(self.x, self.cb, cfg.pad)
+                self.rewrite = lambda: lib.pack_layout(self.x, self.cb, cfg.pad, out=self.xp)
+            self.wp = lib.pack_weights(self.w, self.layout, self.cb)
+            self.rewrite_w = lambda: lib.pack_weights(self.w, self.layout, self.cb, out=self.wp)
+            self.op = lambda: lib.conv2d_int8_packed(cfg.dims(), self.layout, self.cb, self.xp, self.wp, self.out)
+            self.combined = lambda: lib.conv2d_int8(self.x, self.w, cfg.stride, cfg.pad, out=self.out)
+            self.rewrite_bytes = self.x.numel() + self.xp.numel()   # read once + written once
+
+        def report(self, steps, warmup):
+            cfg = self.cfg
+            _, op = timed(self.op, steps, warmup)
+            _, tr = timed(self.rewrite, steps, warmup)
+            _, trw = timed(self.rewrite_w, steps, warmup)
+            wall, comb = timed(self.combined, steps, warmup)
+            rows, cols = lib.tile_info(self.tile)[:2]
+            return {
+                "name": cfg.name, "layout": lib.LAYOUT_NAMES[self.layout], "cb": self.cb,
+                "tile": f"{rows}x{cols}", "split_k": self.split, "ops": cfg.ops,
+                "op_us": round(op * 1e3, 3), "transf_in_us": round(tr * 1e3, 3),
+                "transf_wt_us": round(trw * 1e3, 3), "combined_us": round(comb * 1e3, 3),
+                "tops_op": round(cfg.ops / (op * 1e-3) / 1e12, 3),
+                "tops_combined": round(cfg.ops / (comb * 1e-3) / 1e12, 3),
+                "pct_mfma_peak_op": round(100 * cfg.ops / (op * 1e-3) / PEAK_INT8_OPS, 3),
+                "transf_in_GBps": round(self.rewrite_bytes / (tr * 1e-3) / 1e9, 1),
+                "pct_hbm_peak_transf": round(100 * self.rewrite_bytes / (tr * 1e-3) / PEAK_HBM_BPS, 2),
+            }
+
+    groups = {"C1": ["C1"], "C2": ["C2"], "C3": ["C3"], "C4": ["C4a", "C4b"], "C5": ["C5"]}
+    if args.workload not in groups:
+        print(f"unknown workload {args.workload}", file=sys.stderr)
+        sys.exit(2)
+    head = [Case(CONFIGS[n]) for n in groups[args.workload]]
+    head_ops = sum(c.cfg.ops for c in head)
+
+    def step():
+        for c in head:
+            c.combined()
+
+    wall_ms, ev_ms = timed(step, args.steps, args.warmup)
+    value = head_ops / (wall_ms * 1e-3) / 1e12
+
+    # dominant kernel of the step: the MFMA GEMM stage of the largest convolution
+    dom = max(head, key=lambda c: c.cfg.ops)
+    _, dom_ms = timed(dom.op, args.steps, args.warmup)
+    achieved = dom.cfg.ops / (dom_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "achieved": round(achieved, 3), "peak": PEAK_INT8_OPS / 1e12,
+                "unit": "TOP/s", "frac": round(achieved * 1e12 / PEAK_INT8_OPS, 5), "traffic": None,
+                "kernel": "igemm_i8_kernel", "config": dom.cfg.name,
+                "launch_us": round(dom_ms * 1e3, 3)}
+
+    result = {
+        "metric": "int8 conv effective TOPS (2*N*K*P*Q*C*R*S / time), layout rewrite + MFMA GEMM stage",
+        "value": round(value, 4), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(wall_ms, 6), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "i8", "data": "synthetic",
+        "config": {"workload": " + ".join(
+            f"{c.cfg.name}: N={c.cfg.N} C={c.cfg.C} H={c.cfg.H} W={c.cfg.W} K={c.cfg.K} "
+            f"{c.cfg.R}x{c.cfg.S} stride {c.cfg.stride} pad {c.cfg.pad}" for c in head),
+            "path": "conv2d_int8 one-shot (input rewrite + weight rewrite + GEMM stage)",
+            "layouts": [lib.LAYOUT_NAMES[c.layout] + (f"/cb{c.cb}" if c.cb else "") for c in head]},
+        "event_ms_per_step": round(ev_ms, 6),
+        "pct_mfma_peak": round(100 * value * 1e12 / PEAK_INT8_OPS, 3),
+        "roofline": roofline,
+    }
+
+    if not args.no_extras:
+        steps = min(args.steps, 200)
+        result["per_config"] = [Case(CONFIGS[n]).report(steps, args.warmup) for n in CONFIGS]
+        result["n_scaled"] = n_scaled(lib, timed, CONFIGS, dev)
+
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline([c.cfg for c in head])
+
+    print(json.dumps(result), flush=True)
+
+
+def n_scaled(lib, timed, CONFIGS, dev):
+    """Supplementary: the same kernels at batch sizes that reach steady state.  Layout kernels
+    move >= 1 GiB (beyond the 256 MB Infinity Cache); the GEMM stage runs tens of waves of tiles."""
+    import torch
+    out = {}
+    # GEMM stage of the deep 3x3 layer at N=512 (operands pre-rewritten)
+    cfg = CONFIGS["C4a"].scaled(512)
+    x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=dev)
+    w = torch.randint(-128, 128, (cfg.K, cfg.C, cfg.R, cfg.S), dtype=torch.int8, device=dev)
+    lay, cb, _ = lib.select_layout(cfg.dims())
+    xp = lib.pack_layout(x, cb, cfg.pad)
+    wp = lib.pack_weights(w, lay, cb)
+    o = torch.empty((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=dev)
+    tile, split = lib.query_tiling(cfg.dims(), lay, cb)
+    _, ms = timed(lambda: lib.conv2d_int8_packed(cfg.dims(), lay, cb, xp, wp, o), 20, 3)
+    rows, cols = lib.tile_info(tile)[:2]
+    out["gemm_stage_C4a_N512"] = {"us": round(ms * 1e3, 2), "tops": round(cfg.ops / (ms * 1e-3) / 1e12, 2),
+                                   "pct_mfma_peak": round(100 * cfg.ops / (ms * 1e-3) / PEAK_INT8_OPS, 2),
+                                   "tile": f"{rows}x{cols}", "split_k": split}
+    _, ms = timed(lambda: lib.pack_layout(x, cb, cfg.pad, out=xp), 20, 3)
+    b = x.numel() + xp.numel()
+    out["pack_layout_C4a_N512"] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),
+                                    "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2)}
+    del x, xp, o
+    # pack_layout of the 64-channel 56x56 layer at N=2048 (~0.9 GiB moved)
+    cfg = CONFIGS["C2"].scaled(2048)
+    x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=dev)
+    xp = lib.pack_layout(x, 64, cfg.pad)
+    _, ms = timed(lambda: lib.pack_layout(x, 64, cfg.pad, out=xp), 10, 2)
+    b = x.numel() + xp.numel()
+    out["pack_layout_C2_N2048"] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),
+                                    "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2)}
+    del x, xp
+    # im2col of the 7x7 stem at N=512 (~1.3 GB moved)
+    cfg = CONFIGS["C3"].scaled(512)
+    x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=dev)
+    xp = lib.im2col_int8(x, cfg.R, cfg.S, cfg.stride, cfg.pad)
+    _, ms = timed(lambda: lib.im2col_int8(x, cfg.R, cfg.S, cfg.stride, cfg.pad, out=xp), 10, 2)
+    b = x.numel() + xp.numel()
+    out["im2col_C3_N512"] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),
+                              "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2)}
+    # a plain device-to-device copy of the same size, for scale
+    y = torch.empty_like(xp)
+    _, ms = timed(lambda: y.copy_(xp), 10, 2)
+    out["copy_reference"] = {"bytes": 2 * xp.numel(), "GBps": round(2 * xp.numel() / (ms * 1e-3) / 1e9, 1)}
+    return out
+
+
+def cpu_baseline(cfgs):
+    """The CPU checker, as it stands, timed on the host cores over the headline workload."""
+    from oracle import direct
+    best = None
+    ops = sum(c.ops for c in cfgs)
+    data = [c.make() for c in cfgs]
+    for _ in range(3):
+        t0 = time.perf_counter()
+        for c, (x, w) in zip(cfgs, data):
+            direct.conv2d_int8(x, w, c.stride, c.pad)
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    return {"value": round(ops / best / 1e12, 6), "unit": "TOPS", "cores": direct.threads(), "kind": "oracle",
+            "sample": "whole headline workload (" + " + ".join(c.name for c in cfgs) + "), best of 3, "
+                      f"{best * 1e3:.1f} ms"}
+
+
+if __name__ == "__main__":
+    main()

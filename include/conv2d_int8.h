@@ -87,9 +87,13 @@ size_t conv2d_int8_workspace_bytes(const conv_desc_t *desc, int layout, int cb, 
 int conv2d_int8_packed(const conv_desc_t *desc, int layout, int cb,
                        const int8_t *in_packed, const int8_t *wt_packed, int32_t *out,
                        int tile, int split_k, void *stream);
+/* The tile and depth split the library would pick for this problem (host only). */
+int conv2d_int8_query_tiling(const conv_desc_t *desc, int layout, int cb, int *tile, int *split_k);
 int conv2d_int8_num_tiles(void);
-/* Describes tile `tile`: rows = output channels, cols = output pixels per workgroup. */
-int conv2d_int8_tile_info(int tile, int *rows, int *cols, int *threads);
+/* Describes tile `tile`: rows = output channels, cols = output pixels per workgroup;
+ * steps = 64-byte depth steps per pipeline stage (a tile with steps = 2 only runs problems
+ * whose depth slices hold an even number of steps; otherwise CONV_ERR_UNSUPPORTED). */
+int conv2d_int8_tile_info(int tile, int *rows, int *cols, int *threads, int *steps);
 
 /* ---- layout rewrites, individually callable (the "Transf." column of Table 3) ---------
  * pack_layout (Table 2 rows 2-4 on the input, plus the convolution's zero border):

@@ -19,7 +19,7 @@ LAYOUT_NAMES = {LAYOUT_AUTO: "auto", LAYOUT_PACKED: "packed", LAYOUT_IM2COL: "im
 
 EXPORTS = [
     "conv2d_int8", "conv2d_int8_ex", "conv2d_int8_workspace_bytes", "conv2d_int8_packed",
-    "conv2d_int8_num_tiles", "conv2d_int8_tile_info", "pack_layout", "pack_layout_bytes",
+    "conv2d_int8_query_tiling", "conv2d_int8_num_tiles", "conv2d_int8_tile_info", "pack_layout", "pack_layout_bytes",
     "pack_weights", "pack_weights_depth", "pack_weights_bytes", "im2col_int8", "im2col_bytes",
     "gemm_int8_nt", "select_layout", "select_layout_weighted", "layout_overheads",
     "conv_status_string",
@@ -56,8 +56,9 @@ def load(path: str | None = None):
         "conv2d_int8_ex": (i, [dp, i, i, vp, vp, i, vp, vp, sz, vp]),
         "conv2d_int8_workspace_bytes": (sz, [dp, i, i, i]),
         "conv2d_int8_packed": (i, [dp, i, i, vp, vp, vp, i, i, vp]),
+        "conv2d_int8_query_tiling": (i, [dp, i, i, ip, ip]),
         "conv2d_int8_num_tiles": (i, []),
-        "conv2d_int8_tile_info": (i, [i, ip, ip, ip]),
+        "conv2d_int8_tile_info": (i, [i, ip, ip, ip, ip]),
         "pack_layout": (i, [i] * 6 + [vp, vp, vp]),
         "pack_layout_bytes": (sz, [i] * 6),
         "pack_weights": (i, [i] * 6 + [vp, vp, vp]),
@@ -144,15 +145,23 @@ def conv2d_int8_packed(dims, layout, cb, x_packed, w_packed, out, tile=-1, split
     return out
 
 
+def query_tiling(dims, layout, cb):
+    d = _desc(*dims)
+    t, s = ctypes.c_int(), ctypes.c_int()
+    _check(load().conv2d_int8_query_tiling(ctypes.byref(d), layout, cb, ctypes.byref(t), ctypes.byref(s)),
+           "conv2d_int8_query_tiling")
+    return t.value, s.value
+
+
 def num_tiles() -> int:
     return load().conv2d_int8_num_tiles()
 
 
 def tile_info(tile: int):
-    r, c, t = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
-    _check(load().conv2d_int8_tile_info(tile, ctypes.byref(r), ctypes.byref(c), ctypes.byref(t)),
-           "conv2d_int8_tile_info")
-    return r.value, c.value, t.value
+    r, c, t, k = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    _check(load().conv2d_int8_tile_info(tile, ctypes.byref(r), ctypes.byref(c), ctypes.byref(t),
+                                        ctypes.byref(k)), "conv2d_int8_tile_info")
+    return r.value, c.value, t.value, k.value
 
 
 # ---- layout rewrites ------------------------------------------------------------------------

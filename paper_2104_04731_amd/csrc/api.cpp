@@ -116,7 +116,7 @@ int run_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t st)
     int t = tile, s = split_k;
     if (!aligned16(g.out) && s == 0) s = 1;  // the clear before a depth split writes 16-byte pieces
     if (!aligned16(g.out) && s > 1) return CONV_ERR_INVALID_ARG;
-    gemm_pick(g, &t, &s);
+    if (!gemm_pick(g, &t, &s)) return CONV_ERR_UNSUPPORTED;
     return launch_gemm(g, t, s, st) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
 }
 
@@ -264,13 +264,14 @@ int gemm_int8_nt(int X, int Y, int Z, const int8_t *A, const int8_t *B, int32_t 
 
 int conv2d_int8_num_tiles(void) { return gemm_num_tiles(); }
 
-int conv2d_int8_tile_info(int tile, int *rows, int *cols, int *threads)
+int conv2d_int8_tile_info(int tile, int *rows, int *cols, int *threads, int *steps)
 {
     if (tile < 0 || tile >= gemm_num_tiles()) return CONV_ERR_INVALID_ARG;
     TileInfo t = gemm_tile_info(tile);
     if (rows) *rows = t.rows;
     if (cols) *cols = t.cols;
     if (threads) *threads = t.threads;
+    if (steps) *steps = t.steps;
     return CONV_OK;
 }
 
@@ -285,6 +286,19 @@ int conv2d_int8_packed(const conv_desc_t *desc, int layout, int cb, const int8_t
         return CONV_ERR_INVALID_ARG;
     return run_gemm(gemm_problem(desc, pl, in_packed, wt_packed, out), tile, split_k,
                     (hipStream_t)stream);
+}
+
+int conv2d_int8_query_tiling(const conv_desc_t *desc, int layout, int cb, int *tile, int *split_k)
+{
+    if (layout == CONV_LAYOUT_AUTO || !tile || !split_k) return CONV_ERR_INVALID_ARG;
+    Plan pl;
+    int rc = make_plan(desc, layout, cb, &pl);
+    if (rc != CONV_OK) return rc;
+    int t = -1, s = 0;
+    gemm_pick(gemm_problem(desc, pl, nullptr, nullptr, nullptr), &t, &s);
+    *tile = t;
+    *split_k = s;
+    return CONV_OK;
 }
 
 size_t conv2d_int8_workspace_bytes(const conv_desc_t *desc, int layout, int cb, int wt_is_packed)

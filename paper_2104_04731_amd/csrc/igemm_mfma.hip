@@ -5,16 +5,21 @@
 // the layout rewrites (Table 2) produce.
 //
 // Workgroup = TK output channels x TM output pixels; depth is walked in 64-byte steps.
-// Per step the TK x 64 B weight tile and TM x 64 B activation tile are staged in LDS as
-// four planes of 16-byte chunks ([chunk][row][16 B]), so both the staging writes and the
-// MFMA operand reads (32 consecutive rows of one plane per half-wave) are contiguous
-// 16-byte accesses.  Global loads for step i+1 are in flight while step i is multiplied
-// (register prefetch, two LDS stages, one barrier per step).
+// Each step's TK x 64 B weight tile and TM x 64 B activation tile travel global -> LDS
+// directly (global_load_lds_dwordx4: no register staging) into a ring of NSTAGE stages, so
+// NSTAGE-1 steps of operand traffic are in flight while one step is multiplied; that depth,
+// not occupancy, is what hides the L2/HBM latency of these small problems.  One wave
+// instruction moves 16 rows x 64 B: four lanes fetch one row's 64 contiguous bytes and the
+// data lands lane-contiguous in LDS.  Which 16-byte chunk of the row a lane fetches is
+// XOR-swizzled with the row index, so the MFMA operand reads (32 consecutive rows of one
+// chunk per half-wave, 16 bytes per lane) touch every LDS bank group equally.
 //
 // The activation row of pixel m is addressed as rowbase(m) + koff[chunk]: for the blocked
 // layout koff walks (channel block, r, s) over the zero-padded image (implicit GEMM, no
 // unrolled matrix in memory); for a row-major matrix (im2col output) it is 16*chunk.
 #include "kernels.h"
+
+#include <type_traits>
 
 namespace c2i8 {
 
@@ -30,6 +35,7 @@ struct GemmArgs {
     long long img_bytes;
     int tiles_k, tiles_m;
     int ksteps_total, ksteps_per_split, split_k;
+    int out_fits_32bit;  // every output byte offset is below 2^32
 };
 
 // Workgroups are dealt round-robin over the 8 XCDs (each with its own L2); give every XCD
@@ -40,22 +46,57 @@ __device__ __forceinline__ int xcd_contiguous_id(int id, int n)
     return x * q + (x < rem ? x : rem) + (id >> 3);
 }
 
-template <int TK, int TM, int WK, int WM, int MODE>
+// 16 bytes per lane from `src` (per-lane address) to LDS byte address lds_base + 16*lane
+// (lds_base wave-uniform).  Completion is tracked by vmcnt; the compiler does not see the
+// LDS write, hence the explicit waits below.
+__device__ __forceinline__ void dma16(const int8_t *src, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_base), "v"(src)
+                 : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_dma_outstanding()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+// All LDS reads of this wave have returned, then the workgroup barrier.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("" : : : "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0), vmcnt and expcnt untouched
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" : : : "memory");
+}
+
+template <int TK, int TM, int WK, int WM, int KS, int NSTAGE, int MODE>
 __global__ void __launch_bounds__(WK *WM * 64) igemm_i8_kernel(const GemmArgs a)
 {
-    constexpr int NT = WK * WM * 64;
+    constexpr int NW = WK * WM, NT = NW * 64;
     constexpr int WTK = TK / WK, WTM = TM / WM;
     constexpr int FK = WTK / 32, FM = WTM / 32;
-    constexpr int LW = (TK * 4 + NT - 1) / NT, LA = (TM * 4 + NT - 1) / NT;
-    constexpr int PW = TK * 16, PA = TM * 16;  // bytes per chunk plane
-    constexpr int STAGE = 4 * (PW + PA);
+    // A ring stage holds KS depth steps: RP bytes of every row.  One transfer instruction
+    // moves RPI rows x RP bytes (LPR lanes per row); with KS = 2 a row piece is one whole
+    // 128-byte cache line.
+    constexpr int RP = 64 * KS, LPR = 4 * KS, RPI = 64 / LPR;
+    constexpr int LW = TK / RPI / NW, LA = TM / RPI / NW;  // transfers per wave and stage
+    constexpr int L = LW + LA;
+    constexpr int WBYTES = TK * RP, STAGE = (TK + TM) * RP;
+    constexpr int NH = 2 * KS;  // 32-deep halves per stage
+    static_assert(KS == 1 || KS == 2, "64 or 128 bytes of depth per stage");
     static_assert(WTK % 32 == 0 && WTM % 32 == 0, "wave tile is made of 32x32 MFMA blocks");
-    static_assert((TK & (TK - 1)) == 0 && (TM & (TM - 1)) == 0, "tile extents are powers of two");
+    static_assert((TK / RPI) % NW == 0 && (TM / RPI) % NW == 0, "transfers divide evenly over waves");
+    static_assert(KS == 1 || NW % 2 == 0, "row swizzle of a transfer must not depend on its slot");
+    static_assert(NSTAGE >= 2 && (NSTAGE - 1) * L <= 63, "vmcnt is a 6-bit counter");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    int *koff = reinterpret_cast<int *>(smem + 2 * STAGE);
+    int *koff = reinterpret_cast<int *>(smem + NSTAGE * STAGE);
+    const unsigned lds0 =
+        (unsigned)(size_t)((__attribute__((address_space(3))) unsigned char *)smem);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wk = wave % WK, wm = wave / WK;
 
     int lid = xcd_contiguous_id(blockIdx.x, gridDim.x);
@@ -66,6 +107,7 @@ __global__ void __launch_bounds__(WK *WM * 64) igemm_i8_kernel(const GemmArgs a)
     const int k0 = tk * TK, m0 = tm * TM;
     const int ks_begin = split * a.ksteps_per_split;
     const int nks = min(a.ksteps_total - ks_begin, a.ksteps_per_split);
+    const int ns = nks / KS;  // stages; the host only picks KS = 2 for an even step count
 
     if (MODE == ACT_BLOCKED) {
         for (int t = tid; t < nks * 4; t += NT) {
@@ -81,58 +123,43 @@ __global__ void __launch_bounds__(WK *WM * 64) igemm_i8_kernel(const GemmArgs a)
         }
     }
 
-    // Per-thread staging slots: (row, chunk) pairs, row fastest across lanes.
+    // Transfer slots.  Slot i of this wave moves rows g*RPI .. g*RPI+RPI-1 (g = i*NW + wave)
+    // of the weight (or activation) tile.  Lane l fetches row g*RPI + l/LPR and lands at 16-byte
+    // position l%LPR of that row in LDS; the chunk it fetches is that position XOR a few row
+    // bits (KS = 1: (row/4)%4, KS = 2: (row/2)%8), which is what spreads the later column-wise
+    // MFMA operand reads over all LDS banks.
+    const int lrow = lane / LPR;
+    const int x = KS == 1 ? ((lane & 3) ^ ((lane >> 4) & 3))
+                          : ((lane & 7) ^ (((wave & 1) << 2) | (lane >> 4)));
     const int8_t *wsrc[LW];
-    int wdst[LW];
     const int8_t *asrc[LA];
-    int adst[LA], achunk[LA];
 #pragma unroll
     for (int i = 0; i < LW; ++i) {
-        const int idx = tid + i * NT, row = idx % TK, chunk = (idx / TK) & 3;
+        const int row = (i * NW + wave) * RPI + lrow;
         const int kk = min(k0 + row, a.K - 1);
-        wsrc[i] = a.wq + (size_t)kk * a.depth + (size_t)(ks_begin * 4 + chunk) * 16;
-        wdst[i] = chunk * PW + row * 16;
+        wsrc[i] = a.wq + (size_t)kk * a.depth + (size_t)ks_begin * 64 + x * 16;
     }
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
-        const int idx = tid + i * NT, row = idx % TM, chunk = (idx / TM) & 3;
+        const int row = (i * NW + wave) * RPI + lrow;
         const int m = min(m0 + row, a.M - 1);
         if (MODE == ACT_MATRIX) {
-            asrc[i] = a.act + (size_t)m * a.depth + (size_t)(ks_begin * 4 + chunk) * 16;
+            asrc[i] = a.act + (size_t)m * a.depth + (size_t)ks_begin * 64 + x * 16;
         } else {
             const int n = m / a.PQ, pq = m - n * a.PQ;
             const int p = pq / a.Q, q = pq - p * a.Q;
             asrc[i] = a.act + (size_t)n * a.img_bytes +
                       ((size_t)(p * a.stride) * a.Wp + (size_t)q * a.stride) * a.cb;
         }
-        achunk[i] = chunk;
-        adst[i] = 4 * PW + chunk * PA + row * 16;
     }
-    constexpr bool WFULL = (TK * 4) % NT == 0, AFULL = (TM * 4) % NT == 0;
-    const bool wlast = WFULL || (tid + (LW - 1) * NT < TK * 4);
-    const bool alast = AFULL || (tid + (LA - 1) * NT < TM * 4);
-
-    v4i wreg[LW], areg[LA];
-    auto fetch = [&](int j) {  // j = step relative to ks_begin
-#pragma unroll
-        for (int i = 0; i < LW; ++i)
-            if (i < LW - 1 || wlast) wreg[i] = *reinterpret_cast<const v4i *>(wsrc[i] + (size_t)j * 64);
-#pragma unroll
-        for (int i = 0; i < LA; ++i)
-            if (i < LA - 1 || alast) {
-                if (MODE == ACT_MATRIX)
-                    areg[i] = *reinterpret_cast<const v4i *>(asrc[i] + (size_t)j * 64);
-                else
-                    areg[i] = *reinterpret_cast<const v4i *>(asrc[i] + koff[j * 4 + achunk[i]]);
-            }
+    // One transfer of stage j (t < LW: weight rows, else activation rows) into ring slot `st`.
+    auto dma_item = [&](int t, int j, unsigned st, size_t aoff) {
+        if (t < LW) dma16(wsrc[t] + (size_t)j * RP, st + t * NW * 1024);
+        else dma16(asrc[t - LW] + aoff, st + WBYTES + (t - LW) * NW * 1024);
     };
-    auto stash = [&](unsigned char *st) {
-#pragma unroll
-        for (int i = 0; i < LW; ++i)
-            if (i < LW - 1 || wlast) *reinterpret_cast<v4i *>(st + wdst[i]) = wreg[i];
-#pragma unroll
-        for (int i = 0; i < LA; ++i)
-            if (i < LA - 1 || alast) *reinterpret_cast<v4i *>(st + adst[i]) = areg[i];
+    auto stage_aoff = [&](int j) -> size_t {
+        if (MODE == ACT_BLOCKED) return (size_t)koff[j * LPR + x];
+        return (size_t)j * RP;
     };
 
     v16i acc[FK][FM];
@@ -144,39 +171,122 @@ __global__ void __launch_bounds__(WK *WM * 64) igemm_i8_kernel(const GemmArgs a)
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
     if (MODE == ACT_BLOCKED) __syncthreads();  // koff visible
-    fetch(0);
-    stash(smem);
-    __syncthreads();
-
-    const int wrow = (wk * WTK + (lane & 31)) * 16;
-    const int arow = 4 * PW + (wm * WTM + (lane & 31)) * 16;
-    for (int j = 0; j < nks; ++j) {
-        unsigned char *cur = smem + (j & 1) * STAGE;
-        unsigned char *nxt = smem + ((j & 1) ^ 1) * STAGE;
-        const bool more = j + 1 < nks;
-        if (more) fetch(j + 1);
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int plane = 2 * h + (lane >> 5);
-            v4i wf[FK], af[FM];
+    for (int j = 0; j < NSTAGE; ++j)
+        if (j < ns) {
+            const unsigned st = lds0 + (unsigned)j * STAGE + (unsigned)wave * 1024u;
+            const size_t aoff = stage_aoff(j);
 #pragma unroll
-            for (int i = 0; i < FK; ++i)
-                wf[i] = *reinterpret_cast<const v4i *>(cur + plane * PW + wrow + i * 512);
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-                af[i] = *reinterpret_cast<const v4i *>(cur + plane * PA + arow + i * 512);
-#pragma unroll
-            for (int i = 0; i < FK; ++i)
-#pragma unroll
-                for (int jm = 0; jm < FM; ++jm)
-                    acc[i][jm] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[i], af[jm], acc[i][jm], 0, 0, 0);
+            for (int t = 0; t < L; ++t) dma_item(t, j, st, aoff);
         }
-        if (more) stash(nxt);
-        __syncthreads();
+
+    // MFMA operand reads: lane l takes row (l%32) of a 32-row block; half h of a stage is
+    // chunk 4*(h/2) + 2*(h%2) + l/32 of that row, at its swizzled position.
+    const int rswz = KS == 1 ? ((lane >> 2) & 3) : ((lane >> 1) & 7);
+    const int wrow = (wk * WTK + (lane & 31)) * RP;
+    const int arow = WBYTES + (wm * WTM + (lane & 31)) * RP;
+    int coff[NH];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) coff[h] = (((h >> 1) * 4 + 2 * (h & 1) + (lane >> 5)) ^ rswz) << 4;
+    // One fragment read (t < FK: weight block t, else activation block t - FK).
+    auto read_item = [&](int t, const unsigned char *st, int co, v4i(&wf)[FK], v4i(&af)[FM]) {
+        if (t < FK) wf[t] = *reinterpret_cast<const v4i *>(st + wrow + t * 32 * RP + co);
+        else af[t - FK] = *reinterpret_cast<const v4i *>(st + arow + (t - FK) * 32 * RP + co);
+    };
+    constexpr int NM = FK * FM, NR = FK + FM;
+
+    // Software pipeline.  The matrix pipe idles whenever a wave does anything else for long,
+    // so every LDS fragment read, every transfer and every address update is slotted between
+    // two MFMAs (an MFMA runs for 32 cycles after issue; the side work issues underneath it),
+    // and the order is pinned.  Fragment sets alternate: half h multiplies set h%2 while the
+    // reads of half h+1 fill the other set.  The last half of a stage also holds the barrier
+    // (everyone has read the stage: its ring slot is free; the next stage has landed), the
+    // transfers of stage j+NSTAGE into the freed slot, and the first reads of stage j+1.
+    v4i wf[2][FK], af[2][FM];
+    if (NSTAGE <= ns) wait_dma_outstanding<(NSTAGE - 1) * L>();
+    else wait_dma_outstanding<0>();
+    lds_barrier();
+#pragma unroll
+    for (int t = 0; t < NR; ++t) read_item(t, smem, coff[0], wf[0], af[0]);
+
+    for (int j = 0; j < ns; ++j) {
+        const unsigned char *cur = smem + (j % NSTAGE) * STAGE;
+#pragma unroll
+        for (int h = 0; h < NH - 1; ++h) {
+#pragma unroll
+            for (int g = 0; g < NM; ++g) {
+                acc[g / FM][g % FM] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                    wf[h & 1][g / FM], af[h & 1][g % FM], acc[g / FM][g % FM], 0, 0, 0);
+#pragma unroll
+                for (int u = g * NR / NM; u < (g + 1) * NR / NM; ++u)
+                    read_item(u, cur, coff[h + 1], wf[(h + 1) & 1], af[(h + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+
+        const int jn = j + NSTAGE;
+        const bool refill = jn < ns;  // uniform
+        const unsigned st = lds0 + (unsigned)(j % NSTAGE) * STAGE + (unsigned)wave * 1024u;
+        const unsigned char *nxt = smem + ((j + 1) % NSTAGE) * STAGE;
+        size_t aoff = 0;
+        if (refill) aoff = stage_aoff(jn);
+        constexpr int NI = L + NR;  // side items of the last half: transfers, then reads
+#pragma unroll
+        for (int g = 0; g < NM; ++g) {
+            acc[g / FM][g % FM] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                wf[1][g / FM], af[1][g % FM], acc[g / FM][g % FM], 0, 0, 0);
+            if (g == 0) {
+                if (refill) wait_dma_outstanding<(NSTAGE - 2) * L>();
+                else wait_dma_outstanding<0>();
+                lds_barrier();
+            }
+#pragma unroll
+            for (int u = g * NI / NM; u < (g + 1) * NI / NM; ++u) {
+                if (u < L) {
+                    if (refill) dma_item(u, jn, st, aoff);
+                } else {
+                    // (after the last stage this reads a stale slot; the values are never used)
+                    read_item(u - L, nxt, coff[0], wf[0], af[0]);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 
     // Epilogue: D block (i, jm): column = lane%32 (pixel), row = 8*(v/4) + 4*(lane/32) + v%4.
     // Consecutive lanes write consecutive pixels of one output plane: 128-byte runs in NKPQ.
+    const bool interior = a.out_fits_32bit && k0 + TK <= a.K && m0 + TM <= a.M;
+    if (interior) {
+        // Whole tile in range: address = uniform row base (scalar registers, advanced by whole
+        // output rows) + one 32-bit per-lane offset per column block; no per-element tests.
+        const size_t rowbytes = (size_t)a.PQ * sizeof(int32_t);
+        char *const obase = reinterpret_cast<char *>(a.out);
+        auto write_tile = [&](auto atomic) {
+#pragma unroll
+            for (int jm = 0; jm < FM; ++jm) {
+                const int m = m0 + wm * WTM + jm * 32 + (lane & 31);
+                const int n = m / a.PQ, pq = m - n * a.PQ;
+                const unsigned lane_off =
+                    ((unsigned)n * a.K * a.PQ + pq + (unsigned)(k0 + wk * WTK + 4 * (lane >> 5)) * a.PQ) * 4u;
+#pragma unroll
+                for (int i = 0; i < FK; ++i) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        char *urow = obase + (size_t)(i * 32 + 8 * (v >> 2) + (v & 3)) * rowbytes;
+                        int32_t *dst = reinterpret_cast<int32_t *>(urow + lane_off);
+                        if (decltype(atomic)::value)
+                            __hip_atomic_fetch_add(dst, acc[i][jm][v], __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+                        else
+                            *dst = acc[i][jm][v];
+                    }
+                }
+            }
+        };
+        if (a.split_k > 1) write_tile(std::true_type{});
+        else write_tile(std::false_type{});
+        return;
+    }
 #pragma unroll
     for (int jm = 0; jm < FM; ++jm) {
         const int m = m0 + wm * WTM + jm * 32 + (lane & 31);
@@ -203,42 +313,52 @@ __global__ void __launch_bounds__(WK *WM * 64) igemm_i8_kernel(const GemmArgs a)
 
 // ---- tile table -----------------------------------------------------------------------
 struct TileDef {
-    int tk, tm, wk, wm;
+    int tk, tm, wk, wm, ks, nstage;
 };
 static const TileDef kTiles[] = {
-    {32, 32, 1, 1},    // 0  tiny problems
-    {64, 64, 2, 2},    // 1
-    {128, 128, 2, 2},  // 2
-    {32, 128, 1, 4},   // 3  few output channels
-    {64, 128, 2, 2},   // 4
-    {64, 256, 1, 4},   // 5
-    {128, 64, 2, 2},   // 6
-    {256, 128, 4, 2},  // 7
-    {128, 256, 2, 4},  // 8
-    {256, 256, 2, 4},  // 9  steady state
+    {32, 32, 1, 1, 1, 8},  // 0
+    {64, 64, 2, 2, 1, 8},  // 1
+    {128, 128, 2, 2, 1, 6},  // 2
+    {32, 128, 1, 2, 1, 8},  // 3
+    {64, 128, 2, 2, 1, 8},  // 4
+    {64, 256, 1, 4, 1, 6},  // 5
+    {128, 64, 2, 2, 1, 8},  // 6
+    {256, 128, 2, 2, 1, 5},  // 7
+    {128, 256, 2, 2, 1, 5},  // 8
+    {256, 256, 2, 2, 1, 4},  // 9
+    {256, 128, 2, 2, 1, 3},  // 10
+    {128, 256, 2, 2, 1, 3},  // 11
+    {128, 128, 2, 2, 1, 4},  // 12
+    {256, 256, 2, 4, 2, 2},  // 13
+    {256, 256, 2, 2, 2, 2},  // 14
+    {256, 128, 2, 2, 2, 3},  // 15
+    {128, 128, 2, 2, 2, 4},  // 16
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
 int gemm_num_tiles() { return kNumTiles; }
 TileInfo gemm_tile_info(int t)
 {
-    return TileInfo{kTiles[t].tk, kTiles[t].tm, kTiles[t].wk * kTiles[t].wm * 64};
+    return TileInfo{kTiles[t].tk, kTiles[t].tm, kTiles[t].wk * kTiles[t].wm * 64, kTiles[t].ks};
 }
 
-template <int TK, int TM, int WK, int WM>
+template <int TK, int TM, int WK, int WM, int KS, int NSTAGE>
 static hipError_t launch_tile(const GemmArgs &a, int mode, hipStream_t st)
 {
     constexpr int NT = WK * WM * 64;
-    constexpr int STAGE = 4 * (TK + TM) * 16;
-    const size_t lds = 2 * (size_t)STAGE + (mode == ACT_BLOCKED ? (size_t)a.ksteps_per_split * 16 : 0);
+    constexpr int STAGE = (TK + TM) * 64 * KS;
+    const size_t lds = (size_t)NSTAGE * STAGE + (mode == ACT_BLOCKED ? (size_t)a.ksteps_per_split * 16 : 0);
     const int grid = a.tiles_k * a.tiles_m * a.split_k;
-    auto kb = igemm_i8_kernel<TK, TM, WK, WM, ACT_BLOCKED>;
-    auto km = igemm_i8_kernel<TK, TM, WK, WM, ACT_MATRIX>;
+    auto kb = igemm_i8_kernel<TK, TM, WK, WM, KS, NSTAGE, ACT_BLOCKED>;
+    auto km = igemm_i8_kernel<TK, TM, WK, WM, KS, NSTAGE, ACT_MATRIX>;
     auto kern = mode == ACT_BLOCKED ? kb : km;
-    if (lds > 64 * 1024) {
+    if (lds > 160 * 1024) return hipErrorInvalidValue;
+    static size_t raised[2] = {0, 0};  // dynamic-LDS ceiling already granted, per kernel
+    if (lds > 64 * 1024 && lds > raised[mode]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
+        raised[mode] = 160 * 1024;
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st, a);
     return hipGetLastError();
@@ -249,9 +369,16 @@ static int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // Rough per-launch time model (cycles) used to pick a tile and a depth split:
 // every CU runs one workgroup at a time; a workgroup's step costs the larger of its MFMA
 // time and its operand-fetch time; split-K adds the atomic traffic of one more output tile.
-void gemm_pick(const GemmProblem &g, int *tile, int *split_k)
+// A tile with 128-byte stages walks the depth two steps at a time: every slice must be even.
+static bool tile_fits(const TileDef &d, int ksteps, int per)
+{
+    return d.ks == 1 || (ksteps % 2 == 0 && per % 2 == 0);
+}
+
+bool gemm_pick(const GemmProblem &g, int *tile, int *split_k)
 {
     const int ksteps = g.depth / 64;
+    bool found = false;
     static const int splits[] = {1, 2, 3, 4, 6, 8, 9, 12, 16};
     double best = 1e300;
     int bt = *tile >= 0 ? *tile : 0, bs = *split_k > 0 ? *split_k : 1;
@@ -263,11 +390,15 @@ void gemm_pick(const GemmProblem &g, int *tile, int *split_k)
         const double mfma = (double)d.tk * d.tm * 64 / (1024.0 * (waves < 4 ? waves : 4));
         const double fetch = (double)(d.tk + d.tm) * 64 / 40.0;
         const double step = mfma > fetch ? mfma : fetch;
-        for (int s : splits) {
-            if (*split_k > 0 && s != *split_k) continue;
+        const int forced[] = {*split_k > ksteps ? ksteps : *split_k};
+        const int *cand = *split_k > 0 ? forced : splits;
+        const int ncand = *split_k > 0 ? 1 : (int)(sizeof(splits) / sizeof(splits[0]));
+        for (int ci = 0; ci < ncand; ++ci) {
+            int s = cand[ci];
             if (s > ksteps) continue;
+            s = ceil_div(ksteps, ceil_div(ksteps, s));  // drop slices that would be empty
             const int per = ceil_div(ksteps, s);
-            if (ceil_div(ksteps, per) != s) continue;  // no empty slices
+            if (!tile_fits(d, ksteps, per)) continue;
             const double rounds = (double)(long long)((tiles * s + 255) / 256);
             const double store = (double)d.tk * d.tm * 4 / (s > 1 ? 24.0 : 64.0);
             const double wg = 3000.0 + per * step + store;
@@ -276,11 +407,13 @@ void gemm_pick(const GemmProblem &g, int *tile, int *split_k)
                 best = total;
                 bt = t;
                 bs = s;
+                found = true;
             }
         }
     }
     *tile = bt;
     *split_k = bs;
+    return found;
 }
 
 hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t st)
@@ -311,21 +444,30 @@ hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t 
     if (split_k > a.ksteps_total) split_k = a.ksteps_total;
     a.ksteps_per_split = ceil_div(a.ksteps_total, split_k);
     a.split_k = ceil_div(a.ksteps_total, a.ksteps_per_split);
+    if (!tile_fits(d, a.ksteps_total, a.ksteps_per_split)) return hipErrorInvalidValue;
+    a.out_fits_32bit = (unsigned long long)g.M * g.K * sizeof(int32_t) < (1ULL << 32);
     if (a.split_k > 1) {
         hipError_t e = launch_fill_zero(g.out, (size_t)g.M * g.K * sizeof(int32_t), st);
         if (e != hipSuccess) return e;
     }
     switch (tile) {
-        case 0: return launch_tile<32, 32, 1, 1>(a, g.mode, st);
-        case 1: return launch_tile<64, 64, 2, 2>(a, g.mode, st);
-        case 2: return launch_tile<128, 128, 2, 2>(a, g.mode, st);
-        case 3: return launch_tile<32, 128, 1, 4>(a, g.mode, st);
-        case 4: return launch_tile<64, 128, 2, 2>(a, g.mode, st);
-        case 5: return launch_tile<64, 256, 1, 4>(a, g.mode, st);
-        case 6: return launch_tile<128, 64, 2, 2>(a, g.mode, st);
-        case 7: return launch_tile<256, 128, 4, 2>(a, g.mode, st);
-        case 8: return launch_tile<128, 256, 2, 4>(a, g.mode, st);
-        case 9: return launch_tile<256, 256, 2, 4>(a, g.mode, st);
+        case 0: return launch_tile<32, 32, 1, 1, 1, 8>(a, g.mode, st);
+        case 1: return launch_tile<64, 64, 2, 2, 1, 8>(a, g.mode, st);
+        case 2: return launch_tile<128, 128, 2, 2, 1, 6>(a, g.mode, st);
+        case 3: return launch_tile<32, 128, 1, 2, 1, 8>(a, g.mode, st);
+        case 4: return launch_tile<64, 128, 2, 2, 1, 8>(a, g.mode, st);
+        case 5: return launch_tile<64, 256, 1, 4, 1, 6>(a, g.mode, st);
+        case 6: return launch_tile<128, 64, 2, 2, 1, 8>(a, g.mode, st);
+        case 7: return launch_tile<256, 128, 2, 2, 1, 5>(a, g.mode, st);
+        case 8: return launch_tile<128, 256, 2, 2, 1, 5>(a, g.mode, st);
+        case 9: return launch_tile<256, 256, 2, 2, 1, 4>(a, g.mode, st);
+        case 10: return launch_tile<256, 128, 2, 2, 1, 3>(a, g.mode, st);
+        case 11: return launch_tile<128, 256, 2, 2, 1, 3>(a, g.mode, st);
+        case 12: return launch_tile<128, 128, 2, 2, 1, 4>(a, g.mode, st);
+        case 13: return launch_tile<256, 256, 2, 4, 2, 2>(a, g.mode, st);
+        case 14: return launch_tile<256, 256, 2, 2, 2, 2>(a, g.mode, st);
+        case 15: return launch_tile<256, 128, 2, 2, 2, 3>(a, g.mode, st);
+        case 16: return launch_tile<128, 128, 2, 2, 2, 4>(a, g.mode, st);
     }
     return hipErrorInvalidValue;
 }

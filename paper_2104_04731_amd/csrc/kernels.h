@@ -27,13 +27,14 @@ struct GemmProblem {
 };
 
 struct TileInfo {
-    int rows, cols, threads;
+    int rows, cols, threads, steps;
 };
 
 int gemm_num_tiles();
 TileInfo gemm_tile_info(int tile);
-// Chooses tile / split when tile < 0 / split_k <= 0.
-void gemm_pick(const GemmProblem &g, int *tile, int *split_k);
+// Chooses tile / split when tile < 0 / split_k <= 0; false if a forced choice cannot run
+// this problem (a tile with 128-byte stages needs an even number of depth steps per slice).
+bool gemm_pick(const GemmProblem &g, int *tile, int *split_k);
 // split_k > 1 clears `out` first and accumulates with atomics.
 hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t st);
 

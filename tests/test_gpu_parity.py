@@ -100,17 +100,26 @@ def test_gemm_nt(lib, X, Y, Z):
 
 def test_gemm_every_tile_and_split(lib):
     """Each tile shape, with and without a depth split, on a ragged problem spanning several tiles."""
-    X, Y, Z = 300, 530, 448  # 7 depth steps
-    cfg = ConvShape("g", 1, Z, 1, Y, X, 1, 1, 1, 0)
-    A = uniform_int8(901, (X, Z)); B = uniform_int8(902, (Y, Z))
-    want = layouts.gemm_nt(A, B).reshape(1, X, 1, Y)
-    dA, dB = dev(A), dev(B)
-    for tile in range(lib.num_tiles()):
-        for split in (1, 2, 3, 7):
-            out = torch.full((1, X, 1, Y), -7, dtype=torch.int32, device=DEV)
-            # a row-major [Y][Z] matrix is the im2col operand of a 1x1 convolution over Y pixels
-            lib.conv2d_int8_packed(cfg.dims(), lib.LAYOUT_IM2COL, 0, dB, dA, out, tile=tile, split_k=split)
-            np.testing.assert_array_equal(host(out), want, err_msg=f"tile {tile} split {split}")
+    for Z, splits in ((512, (1, 2, 4)), (448, (1, 2, 3, 7))):  # 8 and 7 depth steps
+        X, Y = 300, 530
+        cfg = ConvShape("g", 1, Z, 1, Y, X, 1, 1, 1, 0)
+        A = uniform_int8(901 + Z, (X, Z)); B = uniform_int8(902 + Z, (Y, Z))
+        want = layouts.gemm_nt(A, B).reshape(1, X, 1, Y)
+        dA, dB = dev(A), dev(B)
+        for tile in range(lib.num_tiles()):
+            steps = lib.tile_info(tile)[3]
+            for split in splits:
+                out = torch.full((1, X, 1, Y), -7, dtype=torch.int32, device=DEV)
+                per = -(-(Z // 64) // split)
+                runnable = steps == 1 or ((Z // 64) % 2 == 0 and per % 2 == 0)
+                # a row-major [Y][Z] matrix is the im2col operand of a 1x1 convolution over Y pixels
+                if not runnable:
+                    with pytest.raises(lib.ConvError) as e:
+                        lib.conv2d_int8_packed(cfg.dims(), lib.LAYOUT_IM2COL, 0, dB, dA, out, tile=tile, split_k=split)
+                    assert e.value.status == lib.ERR_UNSUPPORTED
+                    continue
+                lib.conv2d_int8_packed(cfg.dims(), lib.LAYOUT_IM2COL, 0, dB, dA, out, tile=tile, split_k=split)
+                np.testing.assert_array_equal(host(out), want, err_msg=f"tile {tile} split {split} Z {Z}")
 
 
 # ---- convolution ----------------------------------------------------------------------------
@@ -152,8 +161,13 @@ def test_conv_configs_one_shot(lib, name):
 def test_conv_every_tile_and_split(lib, name):
     cfg = CONFIGS[name]
     x, w, want = oracle_conv(cfg)
+    ksteps = layouts.packed_depth(cfg.C, cfg.R, cfg.S, 64) // 64
     for tile in range(lib.num_tiles()):
+        steps = lib.tile_info(tile)[3]
         for split in (1, 3, 4):
+            per = -(-ksteps // split)
+            if steps == 2 and (ksteps % 2 or per % 2):
+                continue  # rejected combination, covered by test_gemm_every_tile_and_split
             got = run_layout(lib, cfg, x, w, "packed", 64, tile=tile, split_k=split)
             assert np.array_equal(got, want), f"tile {tile} split {split}"
 
