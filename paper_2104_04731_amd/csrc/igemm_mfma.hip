@@ -333,6 +333,10 @@ static const TileDef kTiles[] = {
     {256, 256, 2, 2, 2, 2},  // 14
     {256, 128, 2, 2, 2, 3},  // 15
     {128, 128, 2, 2, 2, 4},  // 16
+    {64, 64, 2, 2, 2, 4},  // 17
+    {64, 64, 2, 2, 2, 6},  // 18
+    {32, 64, 1, 2, 2, 6},  // 19
+    {64, 128, 2, 2, 2, 4},  // 20
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -468,6 +472,10 @@ hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t 
         case 14: return launch_tile<256, 256, 2, 2, 2, 2>(a, g.mode, st);
         case 15: return launch_tile<256, 128, 2, 2, 2, 3>(a, g.mode, st);
         case 16: return launch_tile<128, 128, 2, 2, 2, 4>(a, g.mode, st);
+        case 17: return launch_tile<64, 64, 2, 2, 2, 4>(a, g.mode, st);
+        case 18: return launch_tile<64, 64, 2, 2, 2, 6>(a, g.mode, st);
+        case 19: return launch_tile<32, 64, 1, 2, 2, 6>(a, g.mode, st);
+        case 20: return launch_tile<64, 128, 2, 2, 2, 4>(a, g.mode, st);
     }
     return hipErrorInvalidValue;
 }

@@ -65,6 +65,89 @@ pack_layout_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
     }
 }
 
+
+// Tiled version for cb % 16 == 0 and H*W % 4 == 0 (every channel plane starts dword-aligned).
+// A workgroup owns TP consecutive padded pixels of one (image, channel block, 64-channel
+// slice).  The interior pixels among them are one contiguous run of the source plane, so each
+// channel contributes one contiguous run of <= TP bytes: it is fetched with dword loads into
+// an LDS tile [channel][pixel], then read back channel-wise so that four lanes write the 64
+// contiguous bytes of one pixel and a wave writes 1 KB of contiguous destination.
+constexpr int PACK_TP = 256;            // padded pixels per workgroup
+constexpr int PACK_CH = 64;             // channels per LDS tile
+constexpr int PACK_PITCH = PACK_TP + 4; // bytes; pitch % 16 == 4 spreads the 16-channel groups over banks
+
+// Number of interior (non-border) pixels with padded flat index < o.
+__device__ __forceinline__ int interior_before(int o, int Wp, int pad, int H, int W)
+{
+    const int hp = o / Wp, wp = o - hp * Wp;
+    const int rows = min(max(hp - pad, 0), H);
+    int n = rows * W;
+    if (hp >= pad && hp < pad + H) n += min(max(wp - pad, 0), W);
+    return n;
+}
+
+__global__ void __launch_bounds__(256)
+pack_layout_tiled_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
+                         int C, int H, int W, int cb, int pad, int Hp, int Wp, int Cb,
+                         int tiles_per_img, int slices /* ceil(cb/64) */)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char tile[PACK_CH * PACK_PITCH];
+    const int HW = H * W, HpWp = Hp * Wp;
+    int bid = blockIdx.x;
+    const int t = bid % tiles_per_img;
+    bid /= tiles_per_img;
+    const int sl = bid % slices;
+    bid /= slices;
+    const int b = bid % Cb;
+    const long long n = bid / Cb;
+    const int o0 = t * PACK_TP, o1 = min(o0 + PACK_TP, HpWp);
+    const int i0 = interior_before(o0, Wp, pad, H, W), i1 = interior_before(o1, Wp, pad, H, W);
+    const int a0 = i0 & ~3;                       // dword-aligned start of the source run
+    const int ndw = (i1 - a0 + 3) >> 2;           // dwords per channel (<= 65)
+    const int c0 = b * cb + sl * PACK_CH;         // first channel of this slice
+    const int nch = min(PACK_CH, cb - sl * PACK_CH);
+    const int8_t *plane0 = src + (n * C + c0) * (long long)HW;
+
+    if (i1 > i0) {
+        for (int idx = threadIdx.x; idx < nch * ndw; idx += 256) {
+            const int cl = idx / ndw, d = idx - cl * ndw;
+            unsigned v = 0;
+            if (c0 + cl < C) {
+                const int i = a0 + 4 * d;
+                const int8_t *p = plane0 + (long long)cl * HW + i;
+                if (i + 4 <= HW) v = *reinterpret_cast<const unsigned *>(p);
+                else {  // last dword of the plane (never taken when H*W % 4 == 0)
+                    for (int k = 0; k < 4; ++k)
+                        if (i + k < HW) v |= (unsigned)(unsigned char)p[k] << (8 * k);
+                }
+            }
+            *reinterpret_cast<unsigned *>(tile + cl * PACK_PITCH + 4 * d) = v;
+        }
+    }
+    __syncthreads();
+
+    const int G = nch / 16;  // 16-channel groups per pixel in this slice
+    int8_t *out0 = dst + (((n * Cb + b) * (long long)HpWp) * cb + sl * PACK_CH);
+    for (int idx = threadIdx.x; idx < (o1 - o0) * G; idx += 256) {
+        const int pl = idx / G, g = idx - pl * G;
+        const int o = o0 + pl;
+        const int hp = o / Wp, wp = o - hp * Wp;
+        v4i ov = {0, 0, 0, 0};
+        if (hp >= pad && hp < pad + H && wp >= pad && wp < pad + W) {
+            const int col = (hp - pad) * W + (wp - pad) - a0;
+            const unsigned char *q = tile + (g * 16) * PACK_PITCH + col;
+            unsigned bytes[16];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) bytes[k] = q[k * PACK_PITCH];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                ov[k] = (int)(bytes[4 * k] | (bytes[4 * k + 1] << 8) | (bytes[4 * k + 2] << 16) |
+                              (bytes[4 * k + 3] << 24));
+        }
+        *reinterpret_cast<v4i *>(out0 + (long long)o * cb + g * 16) = ov;
+    }
+}
+
 static int grid_for(long long work_items, int block)
 {
     long long g = (work_items + block - 1) / block;
@@ -79,6 +162,17 @@ hipError_t launch_pack_layout(int N, int C, int H, int W, int cb, int pad,
 {
     const int Hp = H + 2 * pad, Wp = W + 2 * pad, Cb = (C + cb - 1) / cb;
     const long long pixels = (long long)N * Cb * Hp * Wp;
+    const long long hpwp = (long long)Hp * Wp;
+    if (cb % 16 == 0 && ((long long)H * W) % 4 == 0 && (reinterpret_cast<uintptr_t>(src) & 3) == 0 &&
+        hpwp < (1LL << 30) && (long long)H * W < (1LL << 30)) {
+        const int tiles = (int)((hpwp + PACK_TP - 1) / PACK_TP), slices = (cb + PACK_CH - 1) / PACK_CH;
+        const long long blocks = (long long)N * Cb * slices * tiles;
+        if (blocks < (1LL << 31)) {
+            hipLaunchKernelGGL(pack_layout_tiled_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                               src, dst, C, H, W, cb, pad, Hp, Wp, Cb, tiles, slices);
+            return hipGetLastError();
+        }
+    }
     if (cb % 16 == 0) {
         const long long items = pixels * (cb / 16);
         hipLaunchKernelGGL(pack_layout_kernel<16>, dim3(grid_for(items, 256)), dim3(256), 0, st,
@@ -222,11 +316,101 @@ im2col_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
     }
 }
 
+
+// Tiled version.  A workgroup owns TQ consecutive output pixels of one output row (n, p) and
+// a slice of Cc channels.  The source patch those pixels touch -- rows p*st+r-pad for every
+// r, columns q0*st-pad .. (q0+TQ-1)*st-pad+S-1 -- is staged in LDS with the out-of-image
+// part zero-filled, so building a destination piece needs no bounds tests: walking (c,r,s)
+// in depth order is "+1 byte" inside a kernel row and "+pitch-S+1" at the end of one.
+constexpr int I2C_LDS = 48 * 1024;
+
+__global__ void __launch_bounds__(256)
+im2col_tiled_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
+                    int C, int H, int W, int R, int S, int stride, int pad, int P, int Q,
+                    int kg, int kg_pad, int TQ, int qtiles, int Cc, int cslices, int span, int pitch)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char patch[];
+    int bid = blockIdx.x;
+    const int cs = bid % cslices;
+    bid /= cslices;
+    const int qt = bid % qtiles;
+    bid /= qtiles;
+    const int p = bid % P;
+    const long long n = bid / P;
+    const int q0 = qt * TQ, nq = min(TQ, Q - q0);
+    const int c0 = cs * Cc, nc = min(Cc, C - c0);
+    const int w_lo = q0 * stride - pad, h_lo = p * stride - pad;
+    const int8_t *img = src + (n * C + c0) * (long long)H * W;
+
+    // stage the patch: [nc][R][pitch], bytes beyond `span` in a row are never read
+    const int rows = nc * R;
+    for (int idx = threadIdx.x; idx < rows * span; idx += 256) {
+        const int row = idx / span, col = idx - row * span;
+        const int cl = row / R, r = row - cl * R;
+        const int h = h_lo + r, w = w_lo + col;
+        unsigned char v = 0;
+        if (h >= 0 && h < H && w >= 0 && w < W) v = (unsigned char)img[((long long)cl * H + h) * W + w];
+        patch[row * pitch + col] = v;
+    }
+    __syncthreads();
+
+    // destination pieces of this channel slice: depth range [c0*R*S, (c0+nc)*R*S), plus the
+    // zero tail up to kg_pad for the last slice; slice boundaries are multiples of 16
+    const int RS = R * S;
+    const int j_begin = c0 * RS;
+    const int j_end = (cs == cslices - 1) ? kg_pad : (c0 + nc) * RS;
+    const int chunks = (j_end - j_begin) >> 4;
+    int8_t *out0 = dst + ((n * P + p) * (long long)Q + q0) * kg_pad + j_begin;
+    for (int idx = threadIdx.x; idx < nq * chunks; idx += 256) {
+        const int ql = idx / chunks, ch = idx - ql * chunks;
+        const int jl = ch << 4;  // depth offset inside this slice
+        int s = jl % S, cr = jl / S;  // cr = (c - c0)*R + r
+        int addr = cr * pitch + ql * stride + s;
+        const int valid = kg - j_begin - jl;  // bytes of this piece that are real depth
+        unsigned bytes[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            bytes[k] = k < valid ? patch[addr] : 0u;
+            ++addr;
+            if (++s == S) {
+                s = 0;
+                addr += pitch - S;
+            }
+        }
+        v4i ov;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            ov[k] = (int)(bytes[4 * k] | (bytes[4 * k + 1] << 8) | (bytes[4 * k + 2] << 16) |
+                          (bytes[4 * k + 3] << 24));
+        *reinterpret_cast<v4i *>(out0 + (long long)ql * kg_pad + jl) = ov;
+    }
+}
+
 hipError_t launch_im2col(int N, int C, int H, int W, int R, int S, int stride, int pad,
                          int P, int Q, int kg_pad, const int8_t *src, int8_t *dst, hipStream_t st)
 {
     const long long M = (long long)N * P * Q;
     const long long items = M * (kg_pad / 16);
+    {
+        // tile width: enough pixels that a workgroup writes a few tens of KB, within one row
+        int TQ = (32 * 1024 + kg_pad - 1) / kg_pad;
+        if (TQ > Q) TQ = Q;
+        if (TQ < 1) TQ = 1;
+        const int span = (TQ - 1) * stride + S, pitch = (span + 3) & ~3;
+        // channels per slice: all of them if the patch fits, else a multiple of 16 that does
+        int Cc = C;
+        if ((long long)C * R * pitch > I2C_LDS) Cc = (int)(I2C_LDS / ((long long)R * pitch)) / 16 * 16;
+        const int qtiles = (Q + TQ - 1) / TQ;
+        const long long cslices = Cc > 0 ? (C + Cc - 1) / Cc : 0;
+        const long long blocks = (long long)N * P * qtiles * cslices;
+        if (Cc > 0 && blocks < (1LL << 31) && (long long)C * R * S < (1LL << 24)) {
+            const size_t lds = (size_t)(Cc < C ? Cc : C) * R * pitch;
+            hipLaunchKernelGGL(im2col_tiled_kernel, dim3((unsigned)blocks), dim3(256), lds, st,
+                               src, dst, C, H, W, R, S, stride, pad, P, Q, C * R * S, kg_pad, TQ, qtiles,
+                               Cc, (int)cslices, span, pitch);
+            return hipGetLastError();
+        }
+    }
     hipLaunchKernelGGL(im2col_kernel, dim3(grid_for(items, 256)), dim3(256), 0, st,
                        src, dst, C, H, W, R, S, stride, pad, P, Q, C * R * S, kg_pad, M);
     return hipGetLastError();
