@@ -6,6 +6,7 @@
 namespace c2i8 {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));  // 16 bytes at a dword-aligned address
 
 __device__ __forceinline__ unsigned pack4(int b0, int b1, int b2, int b3)
 {
@@ -103,25 +104,49 @@ pack_layout_tiled_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ ds
     const int o0 = t * PACK_TP, o1 = min(o0 + PACK_TP, HpWp);
     const int i0 = interior_before(o0, Wp, pad, H, W), i1 = interior_before(o1, Wp, pad, H, W);
     const int a0 = i0 & ~3;                       // dword-aligned start of the source run
-    const int ndw = (i1 - a0 + 3) >> 2;           // dwords per channel (<= 65)
     const int c0 = b * cb + sl * PACK_CH;         // first channel of this slice
     const int nch = min(PACK_CH, cb - sl * PACK_CH);
     const int8_t *plane0 = src + (n * C + c0) * (long long)HW;
 
     if (i1 > i0) {
-        for (int idx = threadIdx.x; idx < nch * ndw; idx += 256) {
-            const int cl = idx / ndw, d = idx - cl * ndw;
-            unsigned v = 0;
-            if (c0 + cl < C) {
-                const int i = a0 + 4 * d;
-                const int8_t *p = plane0 + (long long)cl * HW + i;
-                if (i + 4 <= HW) v = *reinterpret_cast<const unsigned *>(p);
-                else {  // last dword of the plane (never taken when H*W % 4 == 0)
-                    for (int k = 0; k < 4; ++k)
-                        if (i + k < HW) v |= (unsigned)(unsigned char)p[k] << (8 * k);
+        // thread = (channel, quarter of the run): four 16-byte loads (+ the 4-byte tail) are all
+        // in flight before the first LDS write, so one round trip covers the whole tile
+        const int cl = threadIdx.x >> 2, qd = threadIdx.x & 3;
+        const bool live = cl < nch && c0 + cl < C;
+        const int clc = min(c0 + cl, C - 1) - c0;  // dead lanes read a valid channel, then discard
+        const int8_t *base = plane0 + (long long)clc * HW + a0;
+        const int8_t *p = base + 64 * qd;
+        v4i v[4];
+        unsigned tail = 0;
+        if (a0 + PACK_PITCH <= HW) {  // uniform: the whole 260-byte window lies inside the plane
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[k] = *reinterpret_cast<const v4i_a4 *>(p + 16 * k);
+            tail = *reinterpret_cast<const unsigned *>(base + 256);
+        } else {  // last tile of a plane: dword by dword, guarded
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                v4i t = {0, 0, 0, 0};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = a0 + 64 * qd + 16 * k + 4 * e;
+                    if (i + 4 <= HW) t[e] = *reinterpret_cast<const int *>(p + 16 * k + 4 * e);
                 }
+                v[k] = t;
             }
-            *reinterpret_cast<unsigned *>(tile + cl * PACK_PITCH + 4 * d) = v;
+            if (a0 + 260 <= HW) tail = *reinterpret_cast<const unsigned *>(base + 256);
+        }
+        if (!live) {
+            tail = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[k] = v4i{0, 0, 0, 0};
+        }
+        if (cl < nch) {
+            unsigned *row = reinterpret_cast<unsigned *>(tile + cl * PACK_PITCH + 64 * qd);
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) row[4 * k + e] = (unsigned)v[k][e];
+            if (qd == 3) row[16] = tail;
         }
     }
     __syncthreads();
@@ -322,59 +347,84 @@ im2col_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
 // r, columns q0*st-pad .. (q0+TQ-1)*st-pad+S-1 -- is staged in LDS with the out-of-image
 // part zero-filled, so building a destination piece needs no bounds tests: walking (c,r,s)
 // in depth order is "+1 byte" inside a kernel row and "+pitch-S+1" at the end of one.
+// Index splits use multiply-high by a host-computed reciprocal (exact for the small ranges
+// involved), and the patch loads are issued eight at a time before any is consumed.
 constexpr int I2C_LDS = 48 * 1024;
 
+struct I2cArgs {
+    int C, H, W, R, S, stride, pad, P, Q, kg, kg_pad;
+    int TQ, qtiles, Cc, cslices, span, pitch;
+    unsigned m_span, m_R, m_S;  // ceil(2^32 / d)
+};
+
+// n / d for magic = ceil(2^32 / d) truncated to 32 bits (0 encodes d == 1)
+__device__ __forceinline__ int fast_div(int n, unsigned magic)
+{
+    return magic ? (int)__umulhi((unsigned)n, magic) : n;
+}
+
 __global__ void __launch_bounds__(256)
-im2col_tiled_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
-                    int C, int H, int W, int R, int S, int stride, int pad, int P, int Q,
-                    int kg, int kg_pad, int TQ, int qtiles, int Cc, int cslices, int span, int pitch)
+im2col_tiled_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst, const I2cArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char patch[];
     int bid = blockIdx.x;
-    const int cs = bid % cslices;
-    bid /= cslices;
-    const int qt = bid % qtiles;
-    bid /= qtiles;
-    const int p = bid % P;
-    const long long n = bid / P;
-    const int q0 = qt * TQ, nq = min(TQ, Q - q0);
-    const int c0 = cs * Cc, nc = min(Cc, C - c0);
-    const int w_lo = q0 * stride - pad, h_lo = p * stride - pad;
-    const int8_t *img = src + (n * C + c0) * (long long)H * W;
+    const int cs = bid % a.cslices;
+    bid /= a.cslices;
+    const int qt = bid % a.qtiles;
+    bid /= a.qtiles;
+    const int p = bid % a.P;
+    const long long n = bid / a.P;
+    const int q0 = qt * a.TQ, nq = min(a.TQ, a.Q - q0);
+    const int c0 = cs * a.Cc, nc = min(a.Cc, a.C - c0);
+    const int w_lo = q0 * a.stride - a.pad, h_lo = p * a.stride - a.pad;
+    const int8_t *img = src + (n * a.C + c0) * (long long)a.H * a.W;
 
-    // stage the patch: [nc][R][pitch], bytes beyond `span` in a row are never read
-    const int rows = nc * R;
-    for (int idx = threadIdx.x; idx < rows * span; idx += 256) {
-        const int row = idx / span, col = idx - row * span;
-        const int cl = row / R, r = row - cl * R;
-        const int h = h_lo + r, w = w_lo + col;
-        unsigned char v = 0;
-        if (h >= 0 && h < H && w >= 0 && w < W) v = (unsigned char)img[((long long)cl * H + h) * W + w];
-        patch[row * pitch + col] = v;
+    // stage the patch: [nc][R][pitch]; bytes beyond `span` in a row are never read
+    const int total = nc * a.R * a.span;
+    for (int base = 0; base < total; base += 256 * 8) {
+        unsigned char v[8];
+        int at[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int idx = min(base + u * 256 + (int)threadIdx.x, total - 1);
+            const int row = fast_div(idx, a.m_span), col = idx - row * a.span;
+            const int cl = fast_div(row, a.m_R), r = row - cl * a.R;
+            const int h = h_lo + r, w = w_lo + col;
+            const bool inside = h >= 0 && h < a.H && w >= 0 && w < a.W;
+            const long long off = inside ? ((long long)cl * a.H + h) * a.W + w : 0;  // always valid
+            const unsigned char x = (unsigned char)img[off];
+            v[u] = inside ? x : (unsigned char)0;
+            at[u] = row * a.pitch + col;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (base + u * 256 + (int)threadIdx.x < total) patch[at[u]] = v[u];
     }
     __syncthreads();
 
     // destination pieces of this channel slice: depth range [c0*R*S, (c0+nc)*R*S), plus the
     // zero tail up to kg_pad for the last slice; slice boundaries are multiples of 16
-    const int RS = R * S;
+    const int RS = a.R * a.S;
     const int j_begin = c0 * RS;
-    const int j_end = (cs == cslices - 1) ? kg_pad : (c0 + nc) * RS;
+    const int j_end = (cs == a.cslices - 1) ? a.kg_pad : (c0 + nc) * RS;
     const int chunks = (j_end - j_begin) >> 4;
-    int8_t *out0 = dst + ((n * P + p) * (long long)Q + q0) * kg_pad + j_begin;
+    const unsigned m_chunks = (unsigned)((0x100000000ULL + chunks - 1) / chunks);
+    int8_t *out0 = dst + ((n * a.P + p) * (long long)a.Q + q0) * a.kg_pad + j_begin;
     for (int idx = threadIdx.x; idx < nq * chunks; idx += 256) {
-        const int ql = idx / chunks, ch = idx - ql * chunks;
+        const int ql = fast_div(idx, m_chunks), ch = idx - ql * chunks;
         const int jl = ch << 4;  // depth offset inside this slice
-        int s = jl % S, cr = jl / S;  // cr = (c - c0)*R + r
-        int addr = cr * pitch + ql * stride + s;
-        const int valid = kg - j_begin - jl;  // bytes of this piece that are real depth
+        const int cr = fast_div(jl, a.m_S);  // (c - c0)*R + r
+        int s = jl - cr * a.S;
+        int addr = cr * a.pitch + ql * a.stride + s;
+        const int valid = a.kg - j_begin - jl;  // bytes of this piece that are real depth
         unsigned bytes[16];
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
             bytes[k] = k < valid ? patch[addr] : 0u;
             ++addr;
-            if (++s == S) {
+            if (++s == a.S) {
                 s = 0;
-                addr += pitch - S;
+                addr += a.pitch - a.S;
             }
         }
         v4i ov;
@@ -382,7 +432,7 @@ im2col_tiled_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
         for (int k = 0; k < 4; ++k)
             ov[k] = (int)(bytes[4 * k] | (bytes[4 * k + 1] << 8) | (bytes[4 * k + 2] << 16) |
                           (bytes[4 * k + 3] << 24));
-        *reinterpret_cast<v4i *>(out0 + (long long)ql * kg_pad + jl) = ov;
+        *reinterpret_cast<v4i *>(out0 + (long long)ql * a.kg_pad + jl) = ov;
     }
 }
 
@@ -395,19 +445,29 @@ hipError_t launch_im2col(int N, int C, int H, int W, int R, int S, int stride, i
         // tile width: enough pixels that a workgroup writes a few tens of KB, within one row
         int TQ = (32 * 1024 + kg_pad - 1) / kg_pad;
         if (TQ > Q) TQ = Q;
+        if (TQ > 256) TQ = 256;
         if (TQ < 1) TQ = 1;
-        const int span = (TQ - 1) * stride + S, pitch = (span + 3) & ~3;
+        const long long span64 = (long long)(TQ - 1) * stride + S;
+        const int span = (int)span64, pitch = (span + 3) & ~3;
         // channels per slice: all of them if the patch fits, else a multiple of 16 that does
         int Cc = C;
         if ((long long)C * R * pitch > I2C_LDS) Cc = (int)(I2C_LDS / ((long long)R * pitch)) / 16 * 16;
         const int qtiles = (Q + TQ - 1) / TQ;
         const long long cslices = Cc > 0 ? (C + Cc - 1) / Cc : 0;
         const long long blocks = (long long)N * P * qtiles * cslices;
-        if (Cc > 0 && blocks < (1LL << 31) && (long long)C * R * S < (1LL << 24)) {
+        // multiply-high index splits are exact while dividend * divisor < 2^32
+        const bool small = span64 < 65536 && S < 1024 && R < 65536 && (long long)C * R * S < (1LL << 20) &&
+                           kg_pad < (1 << 19);
+        if (Cc > 0 && small && blocks < (1LL << 31)) {
+            I2cArgs a;
+            a.C = C; a.H = H; a.W = W; a.R = R; a.S = S; a.stride = stride; a.pad = pad; a.P = P; a.Q = Q;
+            a.kg = C * R * S; a.kg_pad = kg_pad; a.TQ = TQ; a.qtiles = qtiles; a.Cc = Cc;
+            a.cslices = (int)cslices; a.span = span; a.pitch = pitch;
+            a.m_span = (unsigned)((0x100000000ULL + span - 1) / span);
+            a.m_R = (unsigned)((0x100000000ULL + R - 1) / R);
+            a.m_S = (unsigned)((0x100000000ULL + S - 1) / S);
             const size_t lds = (size_t)(Cc < C ? Cc : C) * R * pitch;
-            hipLaunchKernelGGL(im2col_tiled_kernel, dim3((unsigned)blocks), dim3(256), lds, st,
-                               src, dst, C, H, W, R, S, stride, pad, P, Q, C * R * S, kg_pad, TQ, qtiles,
-                               Cc, (int)cslices, span, pitch);
+            hipLaunchKernelGGL(im2col_tiled_kernel, dim3((unsigned)blocks), dim3(256), lds, st, src, dst, a);
             return hipGetLastError();
         }
     }
