@@ -324,14 +324,25 @@ int conv2d_int8_ex(const conv_desc_t *desc, int layout, int cb, const int8_t *in
     hipStream_t st = (hipStream_t)stream;
     int8_t *xq = static_cast<int8_t *>(workspace);
     const int8_t *wq = wt;
+    bool rewritten = false;
     if (!wt_is_packed) {
         int8_t *wdst = xq + xb;
-        rc = rewrite_weights(desc, pl, wt, wdst, st);
-        if (rc != CONV_OK) return rc;
         wq = wdst;
+        // both rewrites in one launch when the tiled input kernels apply
+        hipError_t e = launch_rewrite_fused(pl.layout == CONV_LAYOUT_IM2COL, desc->N, desc->C, desc->H,
+                                            desc->W, desc->K, desc->R, desc->S, desc->stride, desc->pad,
+                                            pl.P, pl.Q, pl.cb, pl.depth, in, xq, wt, wdst, st);
+        if (e == hipSuccess) rewritten = true;
+        else if (e != hipErrorNotSupported) return CONV_ERR_DEVICE;
+        else {
+            rc = rewrite_weights(desc, pl, wt, wdst, st);
+            if (rc != CONV_OK) return rc;
+        }
     }
-    rc = rewrite_input(desc, pl, in, xq, st);
-    if (rc != CONV_OK) return rc;
+    if (!rewritten) {
+        rc = rewrite_input(desc, pl, in, xq, st);
+        if (rc != CONV_OK) return rc;
+    }
     return run_gemm(gemm_problem(desc, pl, xq, wq, out), -1, 0, st);
 }
 

@@ -370,15 +370,18 @@ static hipError_t launch_tile(const GemmArgs &a, int mode, hipStream_t st)
 
 static int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// Rough per-launch time model (cycles) used to pick a tile and a depth split:
-// every CU runs one workgroup at a time; a workgroup's step costs the larger of its MFMA
-// time and its operand-fetch time; split-K adds the atomic traffic of one more output tile.
 // A tile with 128-byte stages walks the depth two steps at a time: every slice must be even.
 static bool tile_fits(const TileDef &d, int ksteps, int per)
 {
     return d.ks == 1 || (ksteps % 2 == 0 && per % 2 == 0);
 }
 
+// Per-launch time model (core cycles) used to pick a tile and a depth split.  Constants are
+// measured on MI355X: a lone wave moves about 5.5 B/clk global->LDS, a CU saturates near
+// 38 B/clk (44 with whole-cache-line pieces), the matrix pipe sustains about 80 % of its
+// issue rate inside the main loop, a 64-deep step of a lone workgroup cannot finish faster
+// than its barrier + LDS + MFMA latency chain, and when every CU stores at once the output
+// drains at about 11 B/clk per CU.
 bool gemm_pick(const GemmProblem &g, int *tile, int *split_k)
 {
     const int ksteps = g.depth / 64;
@@ -391,9 +394,16 @@ bool gemm_pick(const GemmProblem &g, int *tile, int *split_k)
         const TileDef &d = kTiles[t];
         const int waves = d.wk * d.wm;
         const double tiles = (double)ceil_div(g.K, d.tk) * ceil_div(g.M, d.tm);
-        const double mfma = (double)d.tk * d.tm * 64 / (1024.0 * (waves < 4 ? waves : 4));
-        const double fetch = (double)(d.tk + d.tm) * 64 / 40.0;
-        const double step = mfma > fetch ? mfma : fetch;
+        const double lds = (double)d.nstage * (d.tk + d.tm) * 64 * d.ks + 2048;
+        const int acc = d.tk * d.tm / (waves * 64);  // accumulator registers per lane
+        int cap = (int)(160.0 * 1024 / lds);
+        const int reg_cap = acc > 128 ? 1 : acc > 64 ? 2 : 4;  // 512 registers per lane and SIMD
+        const int wave_cap = waves >= 8 ? reg_cap / 2 : reg_cap;
+        if (cap > wave_cap) cap = wave_cap;
+        if (cap < 1) cap = 1;
+        const double mfma = (double)d.tk * d.tm * 64 / 4096.0 / 0.8;
+        const double bytes = (double)(d.tk + d.tm) * 64;
+        const double lat = d.ks == 2 ? 180.0 : 260.0;
         const int forced[] = {*split_k > ksteps ? ksteps : *split_k};
         const int *cand = *split_k > 0 ? forced : splits;
         const int ncand = *split_k > 0 ? 1 : (int)(sizeof(splits) / sizeof(splits[0]));
@@ -403,10 +413,19 @@ bool gemm_pick(const GemmProblem &g, int *tile, int *split_k)
             s = ceil_div(ksteps, ceil_div(ksteps, s));  // drop slices that would be empty
             const int per = ceil_div(ksteps, s);
             if (!tile_fits(d, ksteps, per)) continue;
-            const double rounds = (double)(long long)((tiles * s + 255) / 256);
-            const double store = (double)d.tk * d.tm * 4 / (s > 1 ? 24.0 : 64.0);
+            const double wgs = tiles * s;
+            int res = (int)((wgs + 255) / 256);  // workgroups sharing a CU
+            if (res > cap) res = cap;
+            double dma = (d.ks == 2 ? 6.3 : 5.5) * waves * res;
+            const double dma_max = d.ks == 2 ? 44.0 : 38.0;
+            if (dma > dma_max) dma = dma_max;
+            double step = lat;
+            if (res * mfma > step) step = res * mfma;
+            if (res * bytes / dma > step) step = res * bytes / dma;
+            const double store = res * (double)d.tk * d.tm * 4 / (s > 1 ? 6.0 : 11.0);
             const double wg = 3000.0 + per * step + store;
-            const double total = rounds * wg + (s > 1 ? 4000.0 : 0.0);
+            const double rounds = (double)(long long)((wgs + 256.0 * res - 1) / (256.0 * res));
+            const double total = rounds * wg + (s > 1 ? 6000.0 : 0.0);
             if (total < best) {
                 best = total;
                 bt = t;

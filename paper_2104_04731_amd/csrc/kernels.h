@@ -47,6 +47,11 @@ hipError_t launch_pack_weights_rows(int K, int CRS, int depth,
 hipError_t launch_im2col(int N, int C, int H, int W, int R, int S, int stride, int pad,
                          int P, int Q, int kg_pad,
                          const int8_t *src, int8_t *dst, hipStream_t st);
+// Input rewrite (pack_layout or im2col) and weight rewrite as one grid; hipErrorNotSupported
+// if the problem needs the general (separately launched) kernels.
+hipError_t launch_rewrite_fused(bool im2col, int N, int C, int H, int W, int K, int R, int S, int stride,
+                                int pad, int P, int Q, int cb, int depth, const int8_t *in, int8_t *xq,
+                                const int8_t *wt, int8_t *wq, hipStream_t st);
 hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t st);
 
 }  // namespace c2i8

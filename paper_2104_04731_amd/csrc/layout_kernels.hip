@@ -87,18 +87,22 @@ __device__ __forceinline__ int interior_before(int o, int Wp, int pad, int H, in
     return n;
 }
 
-__global__ void __launch_bounds__(256)
-pack_layout_tiled_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
-                         int C, int H, int W, int cb, int pad, int Hp, int Wp, int Cb,
-                         int tiles_per_img, int slices /* ceil(cb/64) */)
+struct PackArgs {
+    const int8_t *src;
+    int8_t *dst;
+    int C, H, W, cb, pad, Hp, Wp, Cb, tiles_per_img, slices /* ceil(cb/64) */;
+};
+
+__device__ __forceinline__ void pack_layout_tiled_body(const PackArgs &a, int bid, unsigned char *tile)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char tile[PACK_CH * PACK_PITCH];
-    const int HW = H * W, HpWp = Hp * Wp;
-    int bid = blockIdx.x;
-    const int t = bid % tiles_per_img;
-    bid /= tiles_per_img;
-    const int sl = bid % slices;
-    bid /= slices;
+    const int8_t *__restrict__ src = a.src;
+    int8_t *__restrict__ dst = a.dst;
+    const int C = a.C, H = a.H, W = a.W, cb = a.cb, pad = a.pad, Wp = a.Wp, Cb = a.Cb;
+    const int HW = H * W, HpWp = a.Hp * Wp;
+    const int t = bid % a.tiles_per_img;
+    bid /= a.tiles_per_img;
+    const int sl = bid % a.slices;
+    bid /= a.slices;
     const int b = bid % Cb;
     const long long n = bid / Cb;
     const int o0 = t * PACK_TP, o1 = min(o0 + PACK_TP, HpWp);
@@ -173,6 +177,12 @@ pack_layout_tiled_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ ds
     }
 }
 
+__global__ void __launch_bounds__(256) pack_layout_tiled_kernel(const PackArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char tile[PACK_CH * PACK_PITCH];
+    pack_layout_tiled_body(a, blockIdx.x, tile);
+}
+
 static int grid_for(long long work_items, int block)
 {
     long long g = (work_items + block - 1) / block;
@@ -182,19 +192,32 @@ static int grid_for(long long work_items, int block)
     return (int)g;
 }
 
+// Fills `a` and the workgroup count if the tiled kernel can run this problem.
+static bool plan_pack_tiled(int N, int C, int H, int W, int cb, int pad, const int8_t *src, int8_t *dst,
+                            PackArgs *a, long long *blocks)
+{
+    const int Hp = H + 2 * pad, Wp = W + 2 * pad, Cb = (C + cb - 1) / cb;
+    const long long hpwp = (long long)Hp * Wp;
+    if (!(cb % 16 == 0 && ((long long)H * W) % 4 == 0 && (reinterpret_cast<uintptr_t>(src) & 3) == 0 &&
+          hpwp < (1LL << 30) && (long long)H * W < (1LL << 30)))
+        return false;
+    const int tiles = (int)((hpwp + PACK_TP - 1) / PACK_TP), slices = (cb + PACK_CH - 1) / PACK_CH;
+    *blocks = (long long)N * Cb * slices * tiles;
+    if (*blocks >= (1LL << 31)) return false;
+    *a = PackArgs{src, dst, C, H, W, cb, pad, Hp, Wp, Cb, tiles, slices};
+    return true;
+}
+
 hipError_t launch_pack_layout(int N, int C, int H, int W, int cb, int pad,
                               const int8_t *src, int8_t *dst, hipStream_t st)
 {
     const int Hp = H + 2 * pad, Wp = W + 2 * pad, Cb = (C + cb - 1) / cb;
     const long long pixels = (long long)N * Cb * Hp * Wp;
-    const long long hpwp = (long long)Hp * Wp;
-    if (cb % 16 == 0 && ((long long)H * W) % 4 == 0 && (reinterpret_cast<uintptr_t>(src) & 3) == 0 &&
-        hpwp < (1LL << 30) && (long long)H * W < (1LL << 30)) {
-        const int tiles = (int)((hpwp + PACK_TP - 1) / PACK_TP), slices = (cb + PACK_CH - 1) / PACK_CH;
-        const long long blocks = (long long)N * Cb * slices * tiles;
-        if (blocks < (1LL << 31)) {
-            hipLaunchKernelGGL(pack_layout_tiled_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
-                               src, dst, C, H, W, cb, pad, Hp, Wp, Cb, tiles, slices);
+    {
+        PackArgs a;
+        long long blocks;
+        if (plan_pack_tiled(N, C, H, W, cb, pad, src, dst, &a, &blocks)) {
+            hipLaunchKernelGGL(pack_layout_tiled_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
             return hipGetLastError();
         }
     }
@@ -216,15 +239,21 @@ hipError_t launch_pack_layout(int N, int C, int H, int W, int cb, int pad,
 
 // ---- pack_weights -----------------------------------------------------------------------
 // Blocked: dst[k][((b*R + r)*S + s)*cb + ci] = src[k][b*cb+ci][r][s]; one thread per 16 B.
-__global__ void __launch_bounds__(256)
-pack_weights_blocked_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
-                            int K, int C, int R, int S, int cb, int depth, int nreal)
+struct WeightArgs {
+    const int8_t *src;
+    int8_t *dst;
+    int K, C, R, S, cb, depth, nreal;  // cb == 0: row-padded copy (depth order of KCRS itself)
+};
+
+__device__ __forceinline__ void pack_weights_blocked_body(const WeightArgs &a, int vbid, int vgrid)
 {
+    const int8_t *__restrict__ src = a.src;
+    int8_t *__restrict__ dst = a.dst;
+    const int K = a.K, C = a.C, cb = a.cb, depth = a.depth, nreal = a.nreal;
     const int chunks = depth / 16;
     const long long total = (long long)K * chunks;
-    const int g16 = cb / 16, RS = R * S;
-    for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < total;
-         t += (long long)gridDim.x * blockDim.x) {
+    const int g16 = cb / 16, RS = a.R * a.S;
+    for (long long t = (long long)vbid * 256 + threadIdx.x; t < total; t += (long long)vgrid * 256) {
         const int ch = (int)(t % chunks);
         const long long k = t / chunks;
         int v[16];
@@ -248,26 +277,36 @@ pack_weights_blocked_kernel(const int8_t *__restrict__ src, int8_t *__restrict__
     }
 }
 
+__global__ void __launch_bounds__(256) pack_weights_blocked_kernel(const WeightArgs a)
+{
+    pack_weights_blocked_body(a, blockIdx.x, gridDim.x);
+}
+
+static WeightArgs weight_args_blocked(int K, int C, int R, int S, int cb, int depth,
+                                      const int8_t *src, int8_t *dst)
+{
+    const int Cb = (C + cb - 1) / cb;
+    return WeightArgs{src, dst, K, C, R, S, cb, depth, Cb * R * S * (cb / 16)};
+}
+
 hipError_t launch_pack_weights_blocked(int K, int C, int R, int S, int cb, int depth,
                                        const int8_t *src, int8_t *dst, hipStream_t st)
 {
-    const int Cb = (C + cb - 1) / cb;
-    const int nreal = Cb * R * S * (cb / 16);
     const long long items = (long long)K * (depth / 16);
     hipLaunchKernelGGL(pack_weights_blocked_kernel, dim3(grid_for(items, 256)), dim3(256), 0, st,
-                       src, dst, K, C, R, S, cb, depth, nreal);
+                       weight_args_blocked(K, C, R, S, cb, depth, src, dst));
     return hipGetLastError();
 }
 
 // Row-padded copy: dst[k][j] = j < CRS ? src[k][j] : 0 (the (c,r,s) order is KCRS itself).
-__global__ void __launch_bounds__(256)
-pack_weights_rows_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
-                         int K, int CRS, int depth)
+__device__ __forceinline__ void pack_weights_rows_body(const WeightArgs &a, int vbid, int vgrid)
 {
+    const int8_t *__restrict__ src = a.src;
+    int8_t *__restrict__ dst = a.dst;
+    const int K = a.K, CRS = a.C * a.R * a.S, depth = a.depth;
     const int chunks = depth / 16;
     const long long total = (long long)K * chunks;
-    for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < total;
-         t += (long long)gridDim.x * blockDim.x) {
+    for (long long t = (long long)vbid * 256 + threadIdx.x; t < total; t += (long long)vgrid * 256) {
         const int ch = (int)(t % chunks);
         const long long k = t / chunks;
         const int8_t *s = src + k * CRS + ch * 16;
@@ -283,12 +322,18 @@ pack_weights_rows_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ ds
     }
 }
 
+__global__ void __launch_bounds__(256) pack_weights_rows_kernel(const WeightArgs a)
+{
+    pack_weights_rows_body(a, blockIdx.x, gridDim.x);
+}
+
 hipError_t launch_pack_weights_rows(int K, int CRS, int depth, const int8_t *src, int8_t *dst,
                                     hipStream_t st)
 {
     const long long items = (long long)K * (depth / 16);
+    // the row copy only needs the product C*R*S: pass it as C with R = S = 1
     hipLaunchKernelGGL(pack_weights_rows_kernel, dim3(grid_for(items, 256)), dim3(256), 0, st,
-                       src, dst, K, CRS, depth);
+                       WeightArgs{src, dst, K, CRS, 1, 1, 0, depth, 0});
     return hipGetLastError();
 }
 
@@ -352,6 +397,8 @@ im2col_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
 constexpr int I2C_LDS = 48 * 1024;
 
 struct I2cArgs {
+    const int8_t *src;
+    int8_t *dst;
     int C, H, W, R, S, stride, pad, P, Q, kg, kg_pad;
     int TQ, qtiles, Cc, cslices, span, pitch;
     unsigned m_span, m_R, m_S;  // ceil(2^32 / d)
@@ -363,11 +410,10 @@ __device__ __forceinline__ int fast_div(int n, unsigned magic)
     return magic ? (int)__umulhi((unsigned)n, magic) : n;
 }
 
-__global__ void __launch_bounds__(256)
-im2col_tiled_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst, const I2cArgs a)
+__device__ __forceinline__ void im2col_tiled_body(const I2cArgs &a, int bid, unsigned char *patch)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char patch[];
-    int bid = blockIdx.x;
+    const int8_t *__restrict__ src = a.src;
+    int8_t *__restrict__ dst = a.dst;
     const int cs = bid % a.cslices;
     bid /= a.cslices;
     const int qt = bid % a.qtiles;
@@ -436,43 +482,123 @@ im2col_tiled_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst, co
     }
 }
 
+__global__ void __launch_bounds__(256) im2col_tiled_kernel(const I2cArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char patch[];
+    im2col_tiled_body(a, blockIdx.x, patch);
+}
+
+// Fills `a`, the workgroup count and the LDS bytes if the tiled kernel can run this problem.
+static bool plan_im2col_tiled(int N, int C, int H, int W, int R, int S, int stride, int pad, int P, int Q,
+                              int kg_pad, const int8_t *src, int8_t *dst, I2cArgs *out, long long *blocks,
+                              size_t *lds)
+{
+    // tile width: enough pixels that a workgroup writes a few tens of KB, within one row
+    int TQ = (32 * 1024 + kg_pad - 1) / kg_pad;
+    if (TQ > Q) TQ = Q;
+    if (TQ > 256) TQ = 256;
+    // small problems: narrower tiles so that there are a few workgroups per CU
+    const long long rows = (long long)N * P;
+    if (rows * ((Q + TQ - 1) / TQ) < 2048) {
+        const long long want = (2048 + rows - 1) / rows;
+        int narrow = (int)((Q + want - 1) / want);
+        if (narrow < 16) narrow = 16;
+        if (narrow < TQ) TQ = narrow;
+    }
+    if (TQ < 1) TQ = 1;
+    const long long span64 = (long long)(TQ - 1) * stride + S;
+    const int span = (int)span64, pitch = (span + 3) & ~3;
+    // channels per slice: all of them if the patch fits, else a multiple of 16 that does
+    int Cc = C;
+    if ((long long)C * R * pitch > I2C_LDS) Cc = (int)(I2C_LDS / ((long long)R * pitch)) / 16 * 16;
+    if (Cc <= 0) return false;
+    const int qtiles = (Q + TQ - 1) / TQ;
+    const long long cslices = (C + Cc - 1) / Cc;
+    *blocks = (long long)N * P * qtiles * cslices;
+    // multiply-high index splits are exact while dividend * divisor < 2^32
+    const bool small = span64 < 65536 && S < 1024 && R < 65536 && (long long)C * R * S < (1LL << 20) &&
+                       kg_pad < (1 << 19);
+    if (!small || *blocks >= (1LL << 31)) return false;
+    I2cArgs a;
+    a.src = src; a.dst = dst;
+    a.C = C; a.H = H; a.W = W; a.R = R; a.S = S; a.stride = stride; a.pad = pad; a.P = P; a.Q = Q;
+    a.kg = C * R * S; a.kg_pad = kg_pad; a.TQ = TQ; a.qtiles = qtiles; a.Cc = Cc;
+    a.cslices = (int)cslices; a.span = span; a.pitch = pitch;
+    a.m_span = (unsigned)((0x100000000ULL + span - 1) / span);
+    a.m_R = (unsigned)((0x100000000ULL + R - 1) / R);
+    a.m_S = (unsigned)((0x100000000ULL + S - 1) / S);
+    *out = a;
+    *lds = (size_t)(Cc < C ? Cc : C) * R * pitch;
+    return true;
+}
+
 hipError_t launch_im2col(int N, int C, int H, int W, int R, int S, int stride, int pad,
                          int P, int Q, int kg_pad, const int8_t *src, int8_t *dst, hipStream_t st)
 {
     const long long M = (long long)N * P * Q;
     const long long items = M * (kg_pad / 16);
     {
-        // tile width: enough pixels that a workgroup writes a few tens of KB, within one row
-        int TQ = (32 * 1024 + kg_pad - 1) / kg_pad;
-        if (TQ > Q) TQ = Q;
-        if (TQ > 256) TQ = 256;
-        if (TQ < 1) TQ = 1;
-        const long long span64 = (long long)(TQ - 1) * stride + S;
-        const int span = (int)span64, pitch = (span + 3) & ~3;
-        // channels per slice: all of them if the patch fits, else a multiple of 16 that does
-        int Cc = C;
-        if ((long long)C * R * pitch > I2C_LDS) Cc = (int)(I2C_LDS / ((long long)R * pitch)) / 16 * 16;
-        const int qtiles = (Q + TQ - 1) / TQ;
-        const long long cslices = Cc > 0 ? (C + Cc - 1) / Cc : 0;
-        const long long blocks = (long long)N * P * qtiles * cslices;
-        // multiply-high index splits are exact while dividend * divisor < 2^32
-        const bool small = span64 < 65536 && S < 1024 && R < 65536 && (long long)C * R * S < (1LL << 20) &&
-                           kg_pad < (1 << 19);
-        if (Cc > 0 && small && blocks < (1LL << 31)) {
-            I2cArgs a;
-            a.C = C; a.H = H; a.W = W; a.R = R; a.S = S; a.stride = stride; a.pad = pad; a.P = P; a.Q = Q;
-            a.kg = C * R * S; a.kg_pad = kg_pad; a.TQ = TQ; a.qtiles = qtiles; a.Cc = Cc;
-            a.cslices = (int)cslices; a.span = span; a.pitch = pitch;
-            a.m_span = (unsigned)((0x100000000ULL + span - 1) / span);
-            a.m_R = (unsigned)((0x100000000ULL + R - 1) / R);
-            a.m_S = (unsigned)((0x100000000ULL + S - 1) / S);
-            const size_t lds = (size_t)(Cc < C ? Cc : C) * R * pitch;
-            hipLaunchKernelGGL(im2col_tiled_kernel, dim3((unsigned)blocks), dim3(256), lds, st, src, dst, a);
+        I2cArgs a;
+        long long blocks;
+        size_t lds;
+        if (plan_im2col_tiled(N, C, H, W, R, S, stride, pad, P, Q, kg_pad, src, dst, &a, &blocks, &lds)) {
+            hipLaunchKernelGGL(im2col_tiled_kernel, dim3((unsigned)blocks), dim3(256), lds, st, a);
             return hipGetLastError();
         }
     }
     hipLaunchKernelGGL(im2col_kernel, dim3(grid_for(items, 256)), dim3(256), 0, st,
                        src, dst, C, H, W, R, S, stride, pad, P, Q, C * R * S, kg_pad, M);
+    return hipGetLastError();
+}
+
+// ---- input rewrite + weight rewrite in one launch ----------------------------------------
+// The two rewrites of a convolution are independent; for the small layers this library is
+// measured on, a kernel launch costs more than either of them, so the one-shot path runs
+// them as two workgroup ranges of a single grid.
+struct FusedArgs {
+    int in_blocks, w_blocks, in_is_im2col, w_is_blocked;
+    PackArgs pk;
+    I2cArgs ic;
+    WeightArgs wt;
+};
+
+__global__ void __launch_bounds__(256) rewrite_fused_kernel(const FusedArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int bid = blockIdx.x;
+    if (bid < a.in_blocks) {
+        if (a.in_is_im2col) im2col_tiled_body(a.ic, bid, lds);
+        else pack_layout_tiled_body(a.pk, bid, lds);
+    } else {
+        if (a.w_is_blocked) pack_weights_blocked_body(a.wt, bid - a.in_blocks, a.w_blocks);
+        else pack_weights_rows_body(a.wt, bid - a.in_blocks, a.w_blocks);
+    }
+}
+
+// Returns hipErrorNotSupported when the tiled input kernels cannot take the problem; the
+// caller then launches the two rewrites separately.
+hipError_t launch_rewrite_fused(bool im2col, int N, int C, int H, int W, int K, int R, int S, int stride,
+                                int pad, int P, int Q, int cb, int depth, const int8_t *in, int8_t *xq,
+                                const int8_t *wt, int8_t *wq, hipStream_t st)
+{
+    FusedArgs a{};
+    long long blocks = 0;
+    size_t lds = PACK_CH * PACK_PITCH;
+    if (im2col) {
+        if (!plan_im2col_tiled(N, C, H, W, R, S, stride, pad, P, Q, depth, in, xq, &a.ic, &blocks, &lds))
+            return hipErrorNotSupported;
+        a.wt = WeightArgs{wt, wq, K, C * R * S, 1, 1, 0, depth, 0};
+    } else {
+        if (!plan_pack_tiled(N, C, H, W, cb, pad, in, xq, &a.pk, &blocks)) return hipErrorNotSupported;
+        a.wt = weight_args_blocked(K, C, R, S, cb, depth, wt, wq);
+    }
+    const long long w_items = (long long)K * (depth / 16);
+    a.in_blocks = (int)blocks;
+    a.w_blocks = grid_for(w_items, 256);
+    a.in_is_im2col = im2col;
+    a.w_is_blocked = !im2col;
+    if (blocks + a.w_blocks >= (1LL << 31)) return hipErrorNotSupported;
+    hipLaunchKernelGGL(rewrite_fused_kernel, dim3((unsigned)(blocks + a.w_blocks)), dim3(256), lds, st, a);
     return hipGetLastError();
 }
 

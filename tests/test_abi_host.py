@@ -37,7 +37,7 @@ ALL_SHAPES = list(CONFIGS.values()) + PAPER_SHAPES
 
 @pytest.mark.parametrize("cfg", ALL_SHAPES, ids=lambda c: c.name)
 def test_selector_matches_definition(lib, cfg):
-    for w in [(1.0, 1.0), (1.0, 0.0), (0.0, 1.0), (1.0 / 2.5165e15, 1.0 / 8.0e12), (3.0, 7.0)]:
+    for w in [(1.0, 1.0), (1.0, 0.0), (0.0, 1.0), (1.0 / 0.6e15, 1.0 / 4.0e12), (3.0, 7.0)]:
         got = lib.select_layout(cfg.dims(), *w)
         want = sel.select(*cfg.dims(), *w)
         assert got[:2] == want[:2]
@@ -49,7 +49,7 @@ def test_selector_matches_definition(lib, cfg):
 def test_default_selector_uses_hardware_weights(lib):
     for cfg in ALL_SHAPES:
         assert lib.select_layout(cfg.dims())[:2] == \
-            sel.select(*cfg.dims(), 1.0 / 2.5165e15, 1.0 / 8.0e12)[:2]
+            sel.select(*cfg.dims(), 1.0 / 0.6e15, 1.0 / 4.0e12)[:2]
 
 
 def test_size_queries_match_definitions(lib):
