@@ -30,9 +30,12 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="C4", help="C1, C2, C3, C4 (= C4a + C4b), C5")
+    ap.add_argument("--workload", default="C4", help="C1, C2, C3, C4 (= C4a + C4b), C4a, C4b, C5")
     ap.add_argument("--no-extras", action="store_true", help="headline only (for profiling runs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (a known-size reference for "
+                         "scaling hardware byte counters in profiler runs)")
     return ap.parse_args()
 
 
@@ -117,7 +120,15 @@ def main():
                 "pct_hbm_peak_transf": round(100 * self.rewrite_bytes / (tr * 1e-3) / PEAK_HBM_BPS, 2),
             }
 
-    groups = {"C1": ["C1"], "C2": ["C2"], "C3": ["C3"], "C4": ["C4a", "C4b"], "C5": ["C5"]}
+    if args.calibration_copy:
+        src = torch.zeros(256 << 20, dtype=torch.int8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    groups = {"C1": ["C1"], "C2": ["C2"], "C3": ["C3"], "C4": ["C4a", "C4b"], "C4a": ["C4a"], "C4b": ["C4b"],
+              "C5": ["C5"]}
     if args.workload not in groups:
         print(f"unknown workload {args.workload}", file=sys.stderr)
         sys.exit(2)

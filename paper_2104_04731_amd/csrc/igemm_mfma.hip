@@ -36,6 +36,7 @@ struct GemmArgs {
     int tiles_k, tiles_m;
     int ksteps_total, ksteps_per_split, split_k;
     int out_fits_32bit;  // every output byte offset is below 2^32
+    int m_fastest;       // tile order inside an XCD
 };
 
 // Workgroups are dealt round-robin over the 8 XCDs (each with its own L2); give every XCD
@@ -100,10 +101,19 @@ __global__ void __launch_bounds__(WK *WM * 64) igemm_i8_kernel(const GemmArgs a)
     const int wk = wave % WK, wm = wave / WK;
 
     int lid = xcd_contiguous_id(blockIdx.x, gridDim.x);
-    const int tk = lid % a.tiles_k;
-    lid /= a.tiles_k;
-    const int tm = lid % a.tiles_m;
-    const int split = lid / a.tiles_m;
+    int tk, tm;
+    if (a.m_fastest) {  // consecutive tiles share a weight tile (few output channels per XCD)
+        tm = lid % a.tiles_m;
+        lid /= a.tiles_m;
+        tk = lid % a.tiles_k;
+        lid /= a.tiles_k;
+    } else {            // consecutive tiles share an activation tile
+        tk = lid % a.tiles_k;
+        lid /= a.tiles_k;
+        tm = lid % a.tiles_m;
+        lid /= a.tiles_m;
+    }
+    const int split = lid;
     const int k0 = tk * TK, m0 = tm * TM;
     const int ks_begin = split * a.ksteps_per_split;
     const int nks = min(a.ksteps_total - ks_begin, a.ksteps_per_split);
@@ -469,6 +479,27 @@ hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t 
     a.split_k = ceil_div(a.ksteps_total, a.ksteps_per_split);
     if (!tile_fits(d, a.ksteps_total, a.ksteps_per_split)) return hipErrorInvalidValue;
     a.out_fits_32bit = (unsigned long long)g.M * g.K * sizeof(int32_t) < (1ULL << 32);
+    {
+        // Each XCD has its own L2 and gets a contiguous eighth of the tile list: order the
+        // list so that the operand rows one XCD has to pull in are as few as possible.
+        const long long per_xcd = ((long long)a.tiles_k * a.tiles_m + 7) / 8;
+        auto rows = [&](long long fast, long long slow, double fast_rows, double slow_rows) {
+            const long long nf = per_xcd < fast ? per_xcd : fast;
+            long long nsl = (per_xcd + fast - 1) / fast + 1;
+            if (nsl > slow) nsl = slow;
+            return nf * fast_rows + nsl * slow_rows;
+        };
+        // an implicit-GEMM pixel row re-reads each input byte R*S/stride^2 times: its unique
+        // bytes are that much smaller than a weight row's
+        double reuse = 1.0;
+        if (g.mode == ACT_BLOCKED) {
+            reuse = (double)g.R * g.S / ((double)g.stride * g.stride);
+            if (reuse < 1.0) reuse = 1.0;
+        }
+        const double k_fast = rows(a.tiles_k, a.tiles_m, d.tk, d.tm / reuse);
+        const double m_fast = rows(a.tiles_m, a.tiles_k, d.tm / reuse, d.tk);
+        a.m_fastest = m_fast < k_fast;
+    }
     if (a.split_k > 1) {
         hipError_t e = launch_fill_zero(g.out, (size_t)g.M * g.K * sizeof(int32_t), st);
         if (e != hipSuccess) return e;

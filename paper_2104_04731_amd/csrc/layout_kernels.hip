@@ -8,6 +8,15 @@ namespace c2i8 {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));  // 16 bytes at a dword-aligned address
 
+// Workgroups are dealt round-robin over the 8 XCDs (each with its own L2).  Mapping the
+// hardware id to a logical id that is contiguous per XCD makes neighbouring tiles -- which
+// share source cache lines (pack) or whole source rows (im2col) -- run behind the same L2.
+__device__ __forceinline__ int xcd_contiguous(int id, int n)
+{
+    const int x = id & 7, q = n >> 3, rem = n & 7;
+    return x * q + (x < rem ? x : rem) + (id >> 3);
+}
+
 __device__ __forceinline__ unsigned pack4(int b0, int b1, int b2, int b3)
 {
     return (unsigned)(b0 & 0xFF) | ((unsigned)(b1 & 0xFF) << 8) | ((unsigned)(b2 & 0xFF) << 16) |
@@ -180,7 +189,7 @@ __device__ __forceinline__ void pack_layout_tiled_body(const PackArgs &a, int bi
 __global__ void __launch_bounds__(256) pack_layout_tiled_kernel(const PackArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned char tile[PACK_CH * PACK_PITCH];
-    pack_layout_tiled_body(a, blockIdx.x, tile);
+    pack_layout_tiled_body(a, xcd_contiguous(blockIdx.x, gridDim.x), tile);
 }
 
 static int grid_for(long long work_items, int block)
@@ -402,6 +411,7 @@ struct I2cArgs {
     int C, H, W, R, S, stride, pad, P, Q, kg, kg_pad;
     int TQ, qtiles, Cc, cslices, span, pitch;
     unsigned m_span, m_R, m_S;  // ceil(2^32 / d)
+    int use_recipe;
 };
 
 // n / d for magic = ceil(2^32 / d) truncated to 32 bits (0 encodes d == 1)
@@ -410,7 +420,7 @@ __device__ __forceinline__ int fast_div(int n, unsigned magic)
     return magic ? (int)__umulhi((unsigned)n, magic) : n;
 }
 
-__device__ __forceinline__ void im2col_tiled_body(const I2cArgs &a, int bid, unsigned char *patch)
+__device__ __forceinline__ void im2col_tiled_body(const I2cArgs &a, int bid, unsigned char *lds)
 {
     const int8_t *__restrict__ src = a.src;
     int8_t *__restrict__ dst = a.dst;
@@ -425,28 +435,41 @@ __device__ __forceinline__ void im2col_tiled_body(const I2cArgs &a, int bid, uns
     const int w_lo = q0 * a.stride - a.pad, h_lo = p * a.stride - a.pad;
     const int8_t *img = src + (n * a.C + c0) * (long long)a.H * a.W;
 
-    // stage the patch: [nc][R][pitch]; bytes beyond `span` in a row are never read
-    const int total = nc * a.R * a.span;
-    for (int base = 0; base < total; base += 256 * 8) {
-        unsigned char v[8];
-        int at[8];
+    // LDS: [4 B slack][patch: nc*R rows x pitch][zero run][recipe table]
+    constexpr int PBASE = 4;
+    unsigned char *patch = lds + PBASE;
+    const int rows = nc * a.R;
+    const int zoff = PBASE + rows * a.pitch;
+
+    // stage the patch four columns at a time, without branches: one (unaligned) dword load
+    // from the column window clamped into the image row, shifted so that the bytes that fall
+    // outside the row become the zero padding
+    const int pd = a.pitch >> 2;  // dwords per patch row
+    const int total = rows * pd;
+    const unsigned m_pd = (unsigned)((0x100000000ULL + pd - 1) / pd);
+    for (int base = 0; base < total; base += 256 * 4) {
+        unsigned v[4];
+        int at[4];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < 4; ++u) {
             const int idx = min(base + u * 256 + (int)threadIdx.x, total - 1);
-            const int row = fast_div(idx, a.m_span), col = idx - row * a.span;
+            const int row = fast_div(idx, m_pd), c4 = idx - row * pd;
             const int cl = fast_div(row, a.m_R), r = row - cl * a.R;
-            const int h = h_lo + r, w = w_lo + col;
-            const bool inside = h >= 0 && h < a.H && w >= 0 && w < a.W;
-            const long long off = inside ? ((long long)cl * a.H + h) * a.W + w : 0;  // always valid
-            const unsigned char x = (unsigned char)img[off];
-            v[u] = inside ? x : (unsigned char)0;
-            at[u] = row * a.pitch + col;
+            const int h = h_lo + r, w = w_lo + 4 * c4;
+            const int hc = min(max(h, 0), a.H - 1), wc = min(max(w, 0), a.W - 4);  // W >= 4 (host-checked)
+            unsigned x;
+            __builtin_memcpy(&x, img + ((long long)cl * a.H + hc) * a.W + wc, 4);
+            const int d = wc - w;  // > 0: window starts left of the row, < 0: it runs past the end
+            const unsigned sh = (unsigned)(d > 0 ? d : -d) * 8u;
+            unsigned y = d >= 0 ? (x << (sh & 31u)) : (x >> (sh & 31u));
+            if (sh >= 32u || h != hc) y = 0u;
+            v[u] = y;
+            at[u] = row * a.pitch + 4 * c4;
         }
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-            if (base + u * 256 + (int)threadIdx.x < total) patch[at[u]] = v[u];
+        for (int u = 0; u < 4; ++u)
+            if (base + u * 256 + (int)threadIdx.x < total) *reinterpret_cast<unsigned *>(patch + at[u]) = v[u];
     }
-    __syncthreads();
 
     // destination pieces of this channel slice: depth range [c0*R*S, (c0+nc)*R*S), plus the
     // zero tail up to kg_pad for the last slice; slice boundaries are multiples of 16
@@ -456,20 +479,71 @@ __device__ __forceinline__ void im2col_tiled_body(const I2cArgs &a, int bid, uns
     const int chunks = (j_end - j_begin) >> 4;
     const unsigned m_chunks = (unsigned)((0x100000000ULL + chunks - 1) / chunks);
     int8_t *out0 = dst + ((n * a.P + p) * (long long)a.Q + q0) * a.kg_pad + j_begin;
+
+    if (a.use_recipe) {
+        // Every destination dword is at most two byte runs of the patch (S >= 4): a run inside
+        // one kernel row, then the start of the next row or the zero tail.  The recipe -- where
+        // each run starts and how many bytes the first one gives -- depends on the depth only,
+        // so it is tabulated once; a pixel adds q*stride.  A run is fetched as two aligned
+        // dwords and one byte-align; the two runs are merged under a byte mask.
+        const int zsz = (((a.TQ - 1) * a.stride + 12) + 3) & ~3;
+        for (int i = threadIdx.x; i < (zsz >> 2); i += 256) *reinterpret_cast<unsigned *>(lds + zoff + 4 * i) = 0u;
+        if (threadIdx.x == 0) *reinterpret_cast<unsigned *>(lds) = 0u;
+        uint2 *rec = reinterpret_cast<uint2 *>(lds + ((zoff + zsz + 7) & ~7));
+        const int ndw = (j_end - j_begin) >> 2;
+        for (int dd = threadIdx.x; dd < ndw; dd += 256) {
+            const int j0 = dd << 2;
+            unsigned o0 = (unsigned)zoff, n0 = 4, w1 = (unsigned)zoff;
+            if (j_begin + j0 < a.kg) {
+                const int cr = fast_div(j0, a.m_S), sx = j0 - cr * a.S;
+                o0 = (unsigned)(PBASE + cr * a.pitch + sx);
+                n0 = (unsigned)min(4, a.S - sx);
+                w1 = o0;
+                if (n0 < 4) {
+                    const unsigned o1 = (j_begin + j0 + (int)n0 < a.kg) ? (unsigned)(PBASE + (cr + 1) * a.pitch)
+                                                                        : (unsigned)zoff;
+                    w1 = o1 - n0;
+                }
+            }
+            rec[dd] = make_uint2(o0 | (n0 << 24), w1);
+        }
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < nq * chunks; idx += 256) {
+            const int ql = fast_div(idx, m_chunks), ch = idx - ql * chunks;
+            const unsigned px = (unsigned)(ql * a.stride);
+            v4i ov;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const uint2 e = rec[ch * 4 + d];
+                const unsigned n0 = e.x >> 24;
+                const unsigned a0 = (e.x & 0xFFFFFFu) + px, a1 = e.y + px;
+                const unsigned *p0 = reinterpret_cast<const unsigned *>(lds + (a0 & ~3u));
+                const unsigned *p1 = reinterpret_cast<const unsigned *>(lds + (a1 & ~3u));
+                const unsigned v0 = __builtin_amdgcn_alignbyte(p0[1], p0[0], a0 & 3u);
+                const unsigned v1 = __builtin_amdgcn_alignbyte(p1[1], p1[0], a1 & 3u);
+                const unsigned mask = n0 >= 4 ? 0xFFFFFFFFu : ((1u << (8 * n0)) - 1u);
+                ov[d] = (int)((v0 & mask) | (v1 & ~mask));
+            }
+            *reinterpret_cast<v4i *>(out0 + (long long)ql * a.kg_pad + (ch << 4)) = ov;
+        }
+        return;
+    }
+
+    __syncthreads();
     for (int idx = threadIdx.x; idx < nq * chunks; idx += 256) {
         const int ql = fast_div(idx, m_chunks), ch = idx - ql * chunks;
         const int jl = ch << 4;  // depth offset inside this slice
         const int cr = fast_div(jl, a.m_S);  // (c - c0)*R + r
-        int s = jl - cr * a.S;
-        int addr = cr * a.pitch + ql * a.stride + s;
+        int sx = jl - cr * a.S;
+        int addr = cr * a.pitch + ql * a.stride + sx;
         const int valid = a.kg - j_begin - jl;  // bytes of this piece that are real depth
         unsigned bytes[16];
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
             bytes[k] = k < valid ? patch[addr] : 0u;
             ++addr;
-            if (++s == a.S) {
-                s = 0;
+            if (++sx == a.S) {
+                sx = 0;
                 addr += a.pitch - a.S;
             }
         }
@@ -485,7 +559,7 @@ __device__ __forceinline__ void im2col_tiled_body(const I2cArgs &a, int bid, uns
 __global__ void __launch_bounds__(256) im2col_tiled_kernel(const I2cArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char patch[];
-    im2col_tiled_body(a, blockIdx.x, patch);
+    im2col_tiled_body(a, xcd_contiguous(blockIdx.x, gridDim.x), patch);
 }
 
 // Fills `a`, the workgroup count and the LDS bytes if the tiled kernel can run this problem.
@@ -512,6 +586,8 @@ static bool plan_im2col_tiled(int N, int C, int H, int W, int R, int S, int stri
     int Cc = C;
     if ((long long)C * R * pitch > I2C_LDS) Cc = (int)(I2C_LDS / ((long long)R * pitch)) / 16 * 16;
     if (Cc <= 0) return false;
+    if (W < 4) return false;  // the staging loads take 4 bytes of one image row
+    if ((long long)C * H * W >= (1LL << 40)) return false;
     const int qtiles = (Q + TQ - 1) / TQ;
     const long long cslices = (C + Cc - 1) / Cc;
     *blocks = (long long)N * P * qtiles * cslices;
@@ -519,6 +595,12 @@ static bool plan_im2col_tiled(int N, int C, int H, int W, int R, int S, int stri
     const bool small = span64 < 65536 && S < 1024 && R < 65536 && (long long)C * R * S < (1LL << 20) &&
                        kg_pad < (1 << 19);
     if (!small || *blocks >= (1LL << 31)) return false;
+    // LDS: 4 B slack + patch + zero run + (recipe path) 8 B per destination dword of a slice
+    const long long patch_bytes = 4 + (long long)(Cc < C ? Cc : C) * R * pitch;
+    const long long zsz = ((((long long)TQ - 1) * stride + 12) + 3) & ~3LL;
+    const long long slice_depth = cslices == 1 ? kg_pad : (long long)Cc * R * S + 64;
+    const long long with_recipe = ((patch_bytes + zsz + 7) & ~7LL) + 2 * slice_depth;
+    const bool recipe = S >= 4 && with_recipe <= 60 * 1024;
     I2cArgs a;
     a.src = src; a.dst = dst;
     a.C = C; a.H = H; a.W = W; a.R = R; a.S = S; a.stride = stride; a.pad = pad; a.P = P; a.Q = Q;
@@ -527,8 +609,9 @@ static bool plan_im2col_tiled(int N, int C, int H, int W, int R, int S, int stri
     a.m_span = (unsigned)((0x100000000ULL + span - 1) / span);
     a.m_R = (unsigned)((0x100000000ULL + R - 1) / R);
     a.m_S = (unsigned)((0x100000000ULL + S - 1) / S);
+    a.use_recipe = recipe;
     *out = a;
-    *lds = (size_t)(Cc < C ? Cc : C) * R * pitch;
+    *lds = (size_t)(recipe ? with_recipe : patch_bytes + 8);
     return true;
 }
 
@@ -567,8 +650,9 @@ __global__ void __launch_bounds__(256) rewrite_fused_kernel(const FusedArgs a)
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int bid = blockIdx.x;
     if (bid < a.in_blocks) {
-        if (a.in_is_im2col) im2col_tiled_body(a.ic, bid, lds);
-        else pack_layout_tiled_body(a.pk, bid, lds);
+        const int lid = xcd_contiguous(bid, a.in_blocks);
+        if (a.in_is_im2col) im2col_tiled_body(a.ic, lid, lds);
+        else pack_layout_tiled_body(a.pk, lid, lds);
     } else {
         if (a.w_is_blocked) pack_weights_blocked_body(a.wt, bid - a.in_blocks, a.w_blocks);
         else pack_weights_rows_body(a.wt, bid - a.in_blocks, a.w_blocks);
