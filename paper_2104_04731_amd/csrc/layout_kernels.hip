@@ -100,6 +100,7 @@ struct PackArgs {
     const int8_t *src;
     int8_t *dst;
     int C, H, W, cb, pad, Hp, Wp, Cb, tiles_per_img, slices /* ceil(cb/64) */;
+    int tp;  // padded pixels per workgroup: 256 for >= 64 channels per slice, 512 for 32, 1024 for 16
 };
 
 __device__ __forceinline__ void pack_layout_tiled_body(const PackArgs &a, int bid, unsigned char *tile)
@@ -114,7 +115,8 @@ __device__ __forceinline__ void pack_layout_tiled_body(const PackArgs &a, int bi
     bid /= a.slices;
     const int b = bid % Cb;
     const long long n = bid / Cb;
-    const int o0 = t * PACK_TP, o1 = min(o0 + PACK_TP, HpWp);
+    const int TP = a.tp, pitch = TP + 4, tpq = TP >> 6;  // tpq threads share one channel row
+    const int o0 = t * TP, o1 = min(o0 + TP, HpWp);
     const int i0 = interior_before(o0, Wp, pad, H, W), i1 = interior_before(o1, Wp, pad, H, W);
     const int a0 = i0 & ~3;                       // dword-aligned start of the source run
     const int c0 = b * cb + sl * PACK_CH;         // first channel of this slice
@@ -122,44 +124,37 @@ __device__ __forceinline__ void pack_layout_tiled_body(const PackArgs &a, int bi
     const int8_t *plane0 = src + (n * C + c0) * (long long)HW;
 
     if (i1 > i0) {
-        // thread = (channel, quarter of the run): four 16-byte loads (+ the 4-byte tail) are all
-        // in flight before the first LDS write, so one round trip covers the whole tile
-        const int cl = threadIdx.x >> 2, qd = threadIdx.x & 3;
+        // thread = (channel, 64-byte piece of the run): four 16-byte loads (+ the 4-byte tail)
+        // are all in flight before the first LDS write, so one round trip covers the tile
+        const int cl = threadIdx.x / tpq, qd = threadIdx.x - cl * tpq;
         const bool live = cl < nch && c0 + cl < C;
-        const int clc = min(c0 + cl, C - 1) - c0;  // dead lanes read a valid channel, then discard
-        const int8_t *base = plane0 + (long long)clc * HW + a0;
-        const int8_t *p = base + 64 * qd;
-        v4i v[4];
+        v4i v[4] = {v4i{0, 0, 0, 0}, v4i{0, 0, 0, 0}, v4i{0, 0, 0, 0}, v4i{0, 0, 0, 0}};
         unsigned tail = 0;
-        if (a0 + PACK_PITCH <= HW) {  // uniform: the whole 260-byte window lies inside the plane
+        if (live) {
+            const int8_t *base = plane0 + (long long)cl * HW + a0;
+            const int8_t *p = base + 64 * qd;
+            if (a0 + pitch <= HW) {  // uniform: the whole window lies inside the plane
 #pragma unroll
-            for (int k = 0; k < 4; ++k) v[k] = *reinterpret_cast<const v4i_a4 *>(p + 16 * k);
-            tail = *reinterpret_cast<const unsigned *>(base + 256);
-        } else {  // last tile of a plane: dword by dword, guarded
+                for (int k = 0; k < 4; ++k) v[k] = *reinterpret_cast<const v4i_a4 *>(p + 16 * k);
+                tail = *reinterpret_cast<const unsigned *>(base + TP);
+            } else {  // last tile of a plane: dword by dword, guarded
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                v4i t = {0, 0, 0, 0};
+                for (int k = 0; k < 4; ++k)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int i = a0 + 64 * qd + 16 * k + 4 * e;
-                    if (i + 4 <= HW) t[e] = *reinterpret_cast<const int *>(p + 16 * k + 4 * e);
-                }
-                v[k] = t;
+                    for (int e = 0; e < 4; ++e) {
+                        const int i = a0 + 64 * qd + 16 * k + 4 * e;
+                        if (i + 4 <= HW) v[k][e] = *reinterpret_cast<const int *>(p + 16 * k + 4 * e);
+                    }
+                if (a0 + TP + 4 <= HW) tail = *reinterpret_cast<const unsigned *>(base + TP);
             }
-            if (a0 + 260 <= HW) tail = *reinterpret_cast<const unsigned *>(base + 256);
-        }
-        if (!live) {
-            tail = 0;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) v[k] = v4i{0, 0, 0, 0};
         }
         if (cl < nch) {
-            unsigned *row = reinterpret_cast<unsigned *>(tile + cl * PACK_PITCH + 64 * qd);
+            unsigned *row = reinterpret_cast<unsigned *>(tile + cl * pitch + 64 * qd);
 #pragma unroll
             for (int k = 0; k < 4; ++k)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) row[4 * k + e] = (unsigned)v[k][e];
-            if (qd == 3) row[16] = tail;
+            if (qd == tpq - 1) row[16] = tail;
         }
     }
     __syncthreads();
@@ -173,10 +168,10 @@ __device__ __forceinline__ void pack_layout_tiled_body(const PackArgs &a, int bi
         v4i ov = {0, 0, 0, 0};
         if (hp >= pad && hp < pad + H && wp >= pad && wp < pad + W) {
             const int col = (hp - pad) * W + (wp - pad) - a0;
-            const unsigned char *q = tile + (g * 16) * PACK_PITCH + col;
+            const unsigned char *q = tile + (g * 16) * pitch + col;
             unsigned bytes[16];
 #pragma unroll
-            for (int k = 0; k < 16; ++k) bytes[k] = q[k * PACK_PITCH];
+            for (int k = 0; k < 16; ++k) bytes[k] = q[k * pitch];
 #pragma unroll
             for (int k = 0; k < 4; ++k)
                 ov[k] = (int)(bytes[4 * k] | (bytes[4 * k + 1] << 8) | (bytes[4 * k + 2] << 16) |
@@ -210,10 +205,11 @@ static bool plan_pack_tiled(int N, int C, int H, int W, int cb, int pad, const i
     if (!(cb % 16 == 0 && ((long long)H * W) % 4 == 0 && (reinterpret_cast<uintptr_t>(src) & 3) == 0 &&
           hpwp < (1LL << 30) && (long long)H * W < (1LL << 30)))
         return false;
-    const int tiles = (int)((hpwp + PACK_TP - 1) / PACK_TP), slices = (cb + PACK_CH - 1) / PACK_CH;
+    const int tp = cb == 16 ? 4 * PACK_TP : cb == 32 ? 2 * PACK_TP : PACK_TP;  // tp * channels <= 16 K
+    const int tiles = (int)((hpwp + tp - 1) / tp), slices = (cb + PACK_CH - 1) / PACK_CH;
     *blocks = (long long)N * Cb * slices * tiles;
     if (*blocks >= (1LL << 31)) return false;
-    *a = PackArgs{src, dst, C, H, W, cb, pad, Hp, Wp, Cb, tiles, slices};
+    *a = PackArgs{src, dst, C, H, W, cb, pad, Hp, Wp, Cb, tiles, slices, tp};
     return true;
 }
 
