@@ -71,10 +71,15 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("" : : : "memory");
 }
 
-template <int TK, int TM, int WK, int WM, int KS, int NSTAGE, int MODE>
-__global__ void __launch_bounds__(WK *WM * 64) igemm_i8_kernel(const GemmArgs a)
+// HELP extra waves per workgroup only move operands (they issue their share of the transfers
+// and keep the barriers, no MFMA): a wave moves about 1 KB per 140-180 cycles through the
+// global->LDS path whatever the queue depth, so small tiles, whose four MFMA waves would be
+// starved at ~25 B/clk per CU, are fed by eight issuing waves instead.
+template <int TK, int TM, int WK, int WM, int KS, int NSTAGE, int HELP, int MODE>
+__global__ void __launch_bounds__((WK * WM + HELP) * 64) igemm_i8_kernel(const GemmArgs a)
 {
-    constexpr int NW = WK * WM, NT = NW * 64;
+    constexpr int NWM = WK * WM;           // waves that multiply
+    constexpr int NW = NWM + HELP, NT = NW * 64;  // waves that transfer (all of them)
     constexpr int WTK = TK / WK, WTM = TM / WM;
     constexpr int FK = WTK / 32, FM = WTM / 32;
     // A ring stage holds KS depth steps: RP bytes of every row.  One transfer instruction
@@ -190,6 +195,27 @@ __global__ void __launch_bounds__(WK *WM * 64) igemm_i8_kernel(const GemmArgs a)
             for (int t = 0; t < L; ++t) dma_item(t, j, st, aoff);
         }
 
+    if (HELP > 0 && wave >= NWM) {
+        // transfer-only wave: same waits, barriers and refills as the multiplying waves
+        if (NSTAGE <= ns) wait_dma_outstanding<(NSTAGE - 1) * L>();
+        else wait_dma_outstanding<0>();
+        lds_barrier();
+        for (int j = 0; j < ns; ++j) {
+            const int jn = j + NSTAGE;
+            const bool refill = jn < ns;
+            if (refill) wait_dma_outstanding<(NSTAGE - 2) * L>();
+            else wait_dma_outstanding<0>();
+            lds_barrier();
+            if (refill) {
+                const unsigned st = lds0 + (unsigned)(j % NSTAGE) * STAGE + (unsigned)wave * 1024u;
+                const size_t aoff = stage_aoff(jn);
+#pragma unroll
+                for (int t = 0; t < L; ++t) dma_item(t, jn, st, aoff);
+            }
+        }
+        return;
+    }
+
     // MFMA operand reads: lane l takes row (l%32) of a 32-row block; half h of a stage is
     // chunk 4*(h/2) + 2*(h%2) + l/32 of that row, at its swizzled position.
     const int rswz = KS == 1 ? ((lane >> 2) & 3) : ((lane >> 1) & 7);
@@ -205,62 +231,126 @@ __global__ void __launch_bounds__(WK *WM * 64) igemm_i8_kernel(const GemmArgs a)
     };
     constexpr int NM = FK * FM, NR = FK + FM;
 
-    // Software pipeline.  The matrix pipe idles whenever a wave does anything else for long,
-    // so every LDS fragment read, every transfer and every address update is slotted between
-    // two MFMAs (an MFMA runs for 32 cycles after issue; the side work issues underneath it),
-    // and the order is pinned.  Fragment sets alternate: half h multiplies set h%2 while the
-    // reads of half h+1 fill the other set.  The last half of a stage also holds the barrier
-    // (everyone has read the stage: its ring slot is free; the next stage has landed), the
-    // transfers of stage j+NSTAGE into the freed slot, and the first reads of stage j+1.
-    v4i wf[2][FK], af[2][FM];
-    if (NSTAGE <= ns) wait_dma_outstanding<(NSTAGE - 1) * L>();
-    else wait_dma_outstanding<0>();
-    lds_barrier();
+    if constexpr (FK * FM <= 2) {
+        // Small wave tiles: one or two MFMAs per 32-deep half cannot cover an LDS read, so the
+        // fragments of a whole stage are read one stage ahead (two register sets of NH halves),
+        // and the halves alternate between two accumulators to halve the dependent MFMA chain.
+        v4i wq[2][NH][FK], aq[2][NH][FM];
+        v16i acc2[FK][FM];
 #pragma unroll
-    for (int t = 0; t < NR; ++t) read_item(t, smem, coff[0], wf[0], af[0]);
+        for (int i = 0; i < FK; ++i)
+#pragma unroll
+            for (int j = 0; j < FM; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc2[i][j][v] = 0;
+        if (NSTAGE <= ns) wait_dma_outstanding<(NSTAGE - 1) * L>();
+        else wait_dma_outstanding<0>();
+        lds_barrier();
+#pragma unroll
+        for (int h = 0; h < NH; ++h)
+#pragma unroll
+            for (int t = 0; t < NR; ++t) read_item(t, smem, coff[h], wq[0][h], aq[0][h]);
+        for (int j = 0; j < ns; j += 2) {
+#pragma unroll
+            for (int par = 0; par < 2; ++par) {  // stage j + par multiplies set `par`
+                const int jj = j + par;
+                if (jj < ns) {
+                    const int jn = jj + NSTAGE;
+                    const bool refill = jn < ns;
+                    if (refill) wait_dma_outstanding<(NSTAGE - 2) * L>();
+                    else wait_dma_outstanding<0>();
+                    lds_barrier();  // stage jj+1 has landed; everyone holds stage jj in registers
+                    if (refill) {
+                        const unsigned st = lds0 + (unsigned)(jj % NSTAGE) * STAGE + (unsigned)wave * 1024u;
+                        const size_t aoff = stage_aoff(jn);
+#pragma unroll
+                        for (int t = 0; t < L; ++t) dma_item(t, jn, st, aoff);
+                    }
+                    // (after the last stage this reads a stale slot; the values are never used)
+                    const unsigned char *nxt = smem + ((jj + 1) % NSTAGE) * STAGE;
+#pragma unroll
+                    for (int h = 0; h < NH; ++h)
+#pragma unroll
+                        for (int t = 0; t < NR; ++t) read_item(t, nxt, coff[h], wq[par ^ 1][h], aq[par ^ 1][h]);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int h = 0; h < NH; ++h)
+#pragma unroll
+                        for (int g = 0; g < NM; ++g) {
+                            if (h & 1)
+                                acc2[g / FM][g % FM] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                                    wq[par][h][g / FM], aq[par][h][g % FM], acc2[g / FM][g % FM], 0, 0, 0);
+                            else
+                                acc[g / FM][g % FM] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                                    wq[par][h][g / FM], aq[par][h][g % FM], acc[g / FM][g % FM], 0, 0, 0);
+                        }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < FK; ++i)
+#pragma unroll
+            for (int j = 0; j < FM; ++j) acc[i][j] += acc2[i][j];
+    } else {
+        // Software pipeline.  The matrix pipe idles whenever a wave does anything else for long,
+        // so every LDS fragment read, every transfer and every address update is slotted between
+        // two MFMAs (an MFMA runs for 32 cycles after issue; the side work issues underneath it),
+        // and the order is pinned.  Fragment sets alternate: half h multiplies set h%2 while the
+        // reads of half h+1 fill the other set.  The last half of a stage also holds the barrier
+        // (everyone has read the stage: its ring slot is free; the next stage has landed), the
+        // transfers of stage j+NSTAGE into the freed slot, and the first reads of stage j+1.
+        v4i wf[2][FK], af[2][FM];
+        if (NSTAGE <= ns) wait_dma_outstanding<(NSTAGE - 1) * L>();
+        else wait_dma_outstanding<0>();
+        lds_barrier();
+    #pragma unroll
+        for (int t = 0; t < NR; ++t) read_item(t, smem, coff[0], wf[0], af[0]);
 
-    for (int j = 0; j < ns; ++j) {
-        const unsigned char *cur = smem + (j % NSTAGE) * STAGE;
-#pragma unroll
-        for (int h = 0; h < NH - 1; ++h) {
-#pragma unroll
+        for (int j = 0; j < ns; ++j) {
+            const unsigned char *cur = smem + (j % NSTAGE) * STAGE;
+    #pragma unroll
+            for (int h = 0; h < NH - 1; ++h) {
+    #pragma unroll
+                for (int g = 0; g < NM; ++g) {
+                    acc[g / FM][g % FM] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                        wf[h & 1][g / FM], af[h & 1][g % FM], acc[g / FM][g % FM], 0, 0, 0);
+    #pragma unroll
+                    for (int u = g * NR / NM; u < (g + 1) * NR / NM; ++u)
+                        read_item(u, cur, coff[h + 1], wf[(h + 1) & 1], af[(h + 1) & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+
+            const int jn = j + NSTAGE;
+            const bool refill = jn < ns;  // uniform
+            const unsigned st = lds0 + (unsigned)(j % NSTAGE) * STAGE + (unsigned)wave * 1024u;
+            const unsigned char *nxt = smem + ((j + 1) % NSTAGE) * STAGE;
+            size_t aoff = 0;
+            if (refill) aoff = stage_aoff(jn);
+            constexpr int NI = L + NR;  // side items of the last half: transfers, then reads
+    #pragma unroll
             for (int g = 0; g < NM; ++g) {
                 acc[g / FM][g % FM] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                    wf[h & 1][g / FM], af[h & 1][g % FM], acc[g / FM][g % FM], 0, 0, 0);
-#pragma unroll
-                for (int u = g * NR / NM; u < (g + 1) * NR / NM; ++u)
-                    read_item(u, cur, coff[h + 1], wf[(h + 1) & 1], af[(h + 1) & 1]);
+                    wf[1][g / FM], af[1][g % FM], acc[g / FM][g % FM], 0, 0, 0);
+                if (g == 0) {
+                    if (refill) wait_dma_outstanding<(NSTAGE - 2) * L>();
+                    else wait_dma_outstanding<0>();
+                    lds_barrier();
+                }
+    #pragma unroll
+                for (int u = g * NI / NM; u < (g + 1) * NI / NM; ++u) {
+                    if (u < L) {
+                        if (refill) dma_item(u, jn, st, aoff);
+                    } else {
+                        // (after the last stage this reads a stale slot; the values are never used)
+                        read_item(u - L, nxt, coff[0], wf[0], af[0]);
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
 
-        const int jn = j + NSTAGE;
-        const bool refill = jn < ns;  // uniform
-        const unsigned st = lds0 + (unsigned)(j % NSTAGE) * STAGE + (unsigned)wave * 1024u;
-        const unsigned char *nxt = smem + ((j + 1) % NSTAGE) * STAGE;
-        size_t aoff = 0;
-        if (refill) aoff = stage_aoff(jn);
-        constexpr int NI = L + NR;  // side items of the last half: transfers, then reads
-#pragma unroll
-        for (int g = 0; g < NM; ++g) {
-            acc[g / FM][g % FM] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
-                wf[1][g / FM], af[1][g % FM], acc[g / FM][g % FM], 0, 0, 0);
-            if (g == 0) {
-                if (refill) wait_dma_outstanding<(NSTAGE - 2) * L>();
-                else wait_dma_outstanding<0>();
-                lds_barrier();
-            }
-#pragma unroll
-            for (int u = g * NI / NM; u < (g + 1) * NI / NM; ++u) {
-                if (u < L) {
-                    if (refill) dma_item(u, jn, st, aoff);
-                } else {
-                    // (after the last stage this reads a stale slot; the values are never used)
-                    read_item(u - L, nxt, coff[0], wf[0], af[0]);
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
     }
 
     // Epilogue: D block (i, jm): column = lane%32 (pixel), row = 8*(v/4) + 4*(lane/32) + v%4.
@@ -323,48 +413,55 @@ __global__ void __launch_bounds__(WK *WM * 64) igemm_i8_kernel(const GemmArgs a)
 
 // ---- tile table -----------------------------------------------------------------------
 struct TileDef {
-    int tk, tm, wk, wm, ks, nstage;
+    int tk, tm, wk, wm, ks, nstage, help;
 };
 static const TileDef kTiles[] = {
-    {32, 32, 1, 1, 1, 8},  // 0
-    {64, 64, 2, 2, 1, 8},  // 1
-    {128, 128, 2, 2, 1, 6},  // 2
-    {32, 128, 1, 2, 1, 8},  // 3
-    {64, 128, 2, 2, 1, 8},  // 4
-    {64, 256, 1, 4, 1, 6},  // 5
-    {128, 64, 2, 2, 1, 8},  // 6
-    {256, 128, 2, 2, 1, 5},  // 7
-    {128, 256, 2, 2, 1, 5},  // 8
-    {256, 256, 2, 2, 1, 4},  // 9
-    {256, 128, 2, 2, 1, 3},  // 10
-    {128, 256, 2, 2, 1, 3},  // 11
-    {128, 128, 2, 2, 1, 4},  // 12
-    {256, 256, 2, 4, 2, 2},  // 13
-    {256, 256, 2, 2, 2, 2},  // 14
-    {256, 128, 2, 2, 2, 3},  // 15
-    {128, 128, 2, 2, 2, 4},  // 16
-    {64, 64, 2, 2, 2, 4},  // 17
-    {64, 64, 2, 2, 2, 6},  // 18
-    {32, 64, 1, 2, 2, 6},  // 19
-    {64, 128, 2, 2, 2, 4},  // 20
+    {32, 32, 1, 1, 1, 8, 0},  // 0
+    {64, 64, 2, 2, 1, 8, 0},  // 1
+    {128, 128, 2, 2, 1, 6, 0},  // 2
+    {32, 128, 1, 2, 1, 8, 0},  // 3
+    {64, 128, 2, 2, 1, 8, 0},  // 4
+    {64, 256, 1, 4, 1, 6, 0},  // 5
+    {128, 64, 2, 2, 1, 8, 0},  // 6
+    {256, 128, 2, 2, 1, 5, 0},  // 7
+    {128, 256, 2, 2, 1, 5, 0},  // 8
+    {256, 256, 2, 2, 1, 4, 0},  // 9
+    {256, 128, 2, 2, 1, 3, 0},  // 10
+    {128, 256, 2, 2, 1, 3, 0},  // 11
+    {128, 128, 2, 2, 1, 4, 0},  // 12
+    {256, 256, 2, 4, 2, 2, 0},  // 13
+    {256, 256, 2, 2, 2, 2, 0},  // 14
+    {256, 128, 2, 2, 2, 3, 0},  // 15
+    {128, 128, 2, 2, 2, 4, 0},  // 16
+    {64, 64, 2, 2, 2, 4, 0},  // 17
+    {64, 64, 2, 2, 2, 6, 0},  // 18
+    {32, 64, 1, 2, 2, 6, 0},  // 19
+    {64, 128, 2, 2, 2, 4, 0},  // 20
+    {64, 64, 2, 2, 2, 4, 4},  // 21
+    {64, 64, 2, 2, 2, 8, 4},  // 22
+    {128, 128, 2, 2, 2, 4, 4},  // 23
+    {64, 128, 2, 2, 2, 4, 4},  // 24
+    {128, 64, 2, 2, 2, 4, 4},  // 25
+    {256, 128, 2, 2, 2, 3, 4},  // 26
+    {128, 256, 2, 2, 2, 3, 4},  // 27
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
 int gemm_num_tiles() { return kNumTiles; }
 TileInfo gemm_tile_info(int t)
 {
-    return TileInfo{kTiles[t].tk, kTiles[t].tm, kTiles[t].wk * kTiles[t].wm * 64, kTiles[t].ks};
+    return TileInfo{kTiles[t].tk, kTiles[t].tm, (kTiles[t].wk * kTiles[t].wm + kTiles[t].help) * 64, kTiles[t].ks};
 }
 
-template <int TK, int TM, int WK, int WM, int KS, int NSTAGE>
+template <int TK, int TM, int WK, int WM, int KS, int NSTAGE, int HELP>
 static hipError_t launch_tile(const GemmArgs &a, int mode, hipStream_t st)
 {
-    constexpr int NT = WK * WM * 64;
+    constexpr int NT = (WK * WM + HELP) * 64;
     constexpr int STAGE = (TK + TM) * 64 * KS;
     const size_t lds = (size_t)NSTAGE * STAGE + (mode == ACT_BLOCKED ? (size_t)a.ksteps_per_split * 16 : 0);
     const int grid = a.tiles_k * a.tiles_m * a.split_k;
-    auto kb = igemm_i8_kernel<TK, TM, WK, WM, KS, NSTAGE, ACT_BLOCKED>;
-    auto km = igemm_i8_kernel<TK, TM, WK, WM, KS, NSTAGE, ACT_MATRIX>;
+    auto kb = igemm_i8_kernel<TK, TM, WK, WM, KS, NSTAGE, HELP, ACT_BLOCKED>;
+    auto km = igemm_i8_kernel<TK, TM, WK, WM, KS, NSTAGE, HELP, ACT_MATRIX>;
     auto kern = mode == ACT_BLOCKED ? kb : km;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     static size_t raised[2] = {0, 0};  // dynamic-LDS ceiling already granted, per kernel
@@ -402,10 +499,10 @@ bool gemm_pick(const GemmProblem &g, int *tile, int *split_k)
     for (int t = 0; t < kNumTiles; ++t) {
         if (*tile >= 0 && t != *tile) continue;
         const TileDef &d = kTiles[t];
-        const int waves = d.wk * d.wm;
+        const int mwaves = d.wk * d.wm, waves = mwaves + d.help;
         const double tiles = (double)ceil_div(g.K, d.tk) * ceil_div(g.M, d.tm);
         const double lds = (double)d.nstage * (d.tk + d.tm) * 64 * d.ks + 2048;
-        const int acc = d.tk * d.tm / (waves * 64);  // accumulator registers per lane
+        const int acc = d.tk * d.tm / (mwaves * 64);  // accumulator registers per lane
         int cap = (int)(160.0 * 1024 / lds);
         const int reg_cap = acc > 128 ? 1 : acc > 64 ? 2 : 4;  // 512 registers per lane and SIMD
         const int wave_cap = waves >= 8 ? reg_cap / 2 : reg_cap;
@@ -505,27 +602,34 @@ hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t 
         if (e != hipSuccess) return e;
     }
     switch (tile) {
-        case 0: return launch_tile<32, 32, 1, 1, 1, 8>(a, g.mode, st);
-        case 1: return launch_tile<64, 64, 2, 2, 1, 8>(a, g.mode, st);
-        case 2: return launch_tile<128, 128, 2, 2, 1, 6>(a, g.mode, st);
-        case 3: return launch_tile<32, 128, 1, 2, 1, 8>(a, g.mode, st);
-        case 4: return launch_tile<64, 128, 2, 2, 1, 8>(a, g.mode, st);
-        case 5: return launch_tile<64, 256, 1, 4, 1, 6>(a, g.mode, st);
-        case 6: return launch_tile<128, 64, 2, 2, 1, 8>(a, g.mode, st);
-        case 7: return launch_tile<256, 128, 2, 2, 1, 5>(a, g.mode, st);
-        case 8: return launch_tile<128, 256, 2, 2, 1, 5>(a, g.mode, st);
-        case 9: return launch_tile<256, 256, 2, 2, 1, 4>(a, g.mode, st);
-        case 10: return launch_tile<256, 128, 2, 2, 1, 3>(a, g.mode, st);
-        case 11: return launch_tile<128, 256, 2, 2, 1, 3>(a, g.mode, st);
-        case 12: return launch_tile<128, 128, 2, 2, 1, 4>(a, g.mode, st);
-        case 13: return launch_tile<256, 256, 2, 4, 2, 2>(a, g.mode, st);
-        case 14: return launch_tile<256, 256, 2, 2, 2, 2>(a, g.mode, st);
-        case 15: return launch_tile<256, 128, 2, 2, 2, 3>(a, g.mode, st);
-        case 16: return launch_tile<128, 128, 2, 2, 2, 4>(a, g.mode, st);
-        case 17: return launch_tile<64, 64, 2, 2, 2, 4>(a, g.mode, st);
-        case 18: return launch_tile<64, 64, 2, 2, 2, 6>(a, g.mode, st);
-        case 19: return launch_tile<32, 64, 1, 2, 2, 6>(a, g.mode, st);
-        case 20: return launch_tile<64, 128, 2, 2, 2, 4>(a, g.mode, st);
+        case 0: return launch_tile<32, 32, 1, 1, 1, 8, 0>(a, g.mode, st);
+        case 1: return launch_tile<64, 64, 2, 2, 1, 8, 0>(a, g.mode, st);
+        case 2: return launch_tile<128, 128, 2, 2, 1, 6, 0>(a, g.mode, st);
+        case 3: return launch_tile<32, 128, 1, 2, 1, 8, 0>(a, g.mode, st);
+        case 4: return launch_tile<64, 128, 2, 2, 1, 8, 0>(a, g.mode, st);
+        case 5: return launch_tile<64, 256, 1, 4, 1, 6, 0>(a, g.mode, st);
+        case 6: return launch_tile<128, 64, 2, 2, 1, 8, 0>(a, g.mode, st);
+        case 7: return launch_tile<256, 128, 2, 2, 1, 5, 0>(a, g.mode, st);
+        case 8: return launch_tile<128, 256, 2, 2, 1, 5, 0>(a, g.mode, st);
+        case 9: return launch_tile<256, 256, 2, 2, 1, 4, 0>(a, g.mode, st);
+        case 10: return launch_tile<256, 128, 2, 2, 1, 3, 0>(a, g.mode, st);
+        case 11: return launch_tile<128, 256, 2, 2, 1, 3, 0>(a, g.mode, st);
+        case 12: return launch_tile<128, 128, 2, 2, 1, 4, 0>(a, g.mode, st);
+        case 13: return launch_tile<256, 256, 2, 4, 2, 2, 0>(a, g.mode, st);
+        case 14: return launch_tile<256, 256, 2, 2, 2, 2, 0>(a, g.mode, st);
+        case 15: return launch_tile<256, 128, 2, 2, 2, 3, 0>(a, g.mode, st);
+        case 16: return launch_tile<128, 128, 2, 2, 2, 4, 0>(a, g.mode, st);
+        case 17: return launch_tile<64, 64, 2, 2, 2, 4, 0>(a, g.mode, st);
+        case 18: return launch_tile<64, 64, 2, 2, 2, 6, 0>(a, g.mode, st);
+        case 19: return launch_tile<32, 64, 1, 2, 2, 6, 0>(a, g.mode, st);
+        case 20: return launch_tile<64, 128, 2, 2, 2, 4, 0>(a, g.mode, st);
+        case 21: return launch_tile<64, 64, 2, 2, 2, 4, 4>(a, g.mode, st);
+        case 22: return launch_tile<64, 64, 2, 2, 2, 8, 4>(a, g.mode, st);
+        case 23: return launch_tile<128, 128, 2, 2, 2, 4, 4>(a, g.mode, st);
+        case 24: return launch_tile<64, 128, 2, 2, 2, 4, 4>(a, g.mode, st);
+        case 25: return launch_tile<128, 64, 2, 2, 2, 4, 4>(a, g.mode, st);
+        case 26: return launch_tile<256, 128, 2, 2, 2, 3, 4>(a, g.mode, st);
+        case 27: return launch_tile<128, 256, 2, 2, 2, 3, 4>(a, g.mode, st);
     }
     return hipErrorInvalidValue;
 }
