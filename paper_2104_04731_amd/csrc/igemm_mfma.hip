@@ -75,11 +75,18 @@ __device__ __forceinline__ void lds_barrier()
 // and keep the barriers, no MFMA): a wave moves about 1 KB per 140-180 cycles through the
 // global->LDS path whatever the queue depth, so small tiles, whose four MFMA waves would be
 // starved at ~25 B/clk per CU, are fed by eight issuing waves instead.
-template <int TK, int TM, int WK, int WM, int KS, int NSTAGE, int HELP, int MODE>
-__global__ void __launch_bounds__((WK * WM + HELP) * 64) igemm_i8_kernel(const GemmArgs a)
+//
+// DS = 2 (small wave tiles only) runs two groups of WK x WM multiplying waves on the same
+// output tile, each on its half of every stage's depth; the second group's accumulators are
+// added to the first's through LDS before the epilogue.  A 32x32 wave tile reads 4 KB of LDS
+// per 64 MFMA cycles, and four waves alone reach only ~100 B/clk of LDS bandwidth where eight
+// reach ~190: the second group doubles what a small tile can multiply per cycle.
+template <int TK, int TM, int WK, int WM, int KS, int NSTAGE, int HELP, int DS, int MODE>
+__global__ void __launch_bounds__((WK * WM * DS + HELP) * 64) igemm_i8_kernel(const GemmArgs a)
 {
-    constexpr int NWM = WK * WM;           // waves that multiply
-    constexpr int NW = NWM + HELP, NT = NW * 64;  // waves that transfer (all of them)
+    constexpr int NWM = WK * WM;           // waves of one multiplying group
+    constexpr int NWC = NWM * DS;          // waves that multiply
+    constexpr int NW = NWC + HELP, NT = NW * 64;  // waves that transfer (all of them)
     constexpr int WTK = TK / WK, WTM = TM / WM;
     constexpr int FK = WTK / 32, FM = WTM / 32;
     // A ring stage holds KS depth steps: RP bytes of every row.  One transfer instruction
@@ -91,6 +98,7 @@ __global__ void __launch_bounds__((WK * WM + HELP) * 64) igemm_i8_kernel(const G
     constexpr int WBYTES = TK * RP, STAGE = (TK + TM) * RP;
     constexpr int NH = 2 * KS;  // 32-deep halves per stage
     static_assert(KS == 1 || KS == 2, "64 or 128 bytes of depth per stage");
+    static_assert(DS == 1 || (DS == 2 && (TK / WK / 32) * (TM / WM / 32) <= 2), "depth groups: small wave tiles only");
     static_assert(WTK % 32 == 0 && WTM % 32 == 0, "wave tile is made of 32x32 MFMA blocks");
     static_assert((TK / RPI) % NW == 0 && (TM / RPI) % NW == 0, "transfers divide evenly over waves");
     static_assert(KS == 1 || NW % 2 == 0, "row swizzle of a transfer must not depend on its slot");
@@ -103,7 +111,8 @@ __global__ void __launch_bounds__((WK * WM + HELP) * 64) igemm_i8_kernel(const G
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wk = wave % WK, wm = wave / WK;
+    const int grp = DS == 1 ? 0 : wave / NWM;  // depth group of this wave
+    const int wk = (wave % NWM) % WK, wm = (wave % NWM) / WK;
 
     int lid = xcd_contiguous_id(blockIdx.x, gridDim.x);
     int tk, tm;
@@ -195,7 +204,7 @@ __global__ void __launch_bounds__((WK * WM + HELP) * 64) igemm_i8_kernel(const G
             for (int t = 0; t < L; ++t) dma_item(t, j, st, aoff);
         }
 
-    if (HELP > 0 && wave >= NWM) {
+    if (HELP > 0 && wave >= NWC) {
         // transfer-only wave: same waits, barriers and refills as the multiplying waves
         if (NSTAGE <= ns) wait_dma_outstanding<(NSTAGE - 1) * L>();
         else wait_dma_outstanding<0>();
@@ -233,9 +242,11 @@ __global__ void __launch_bounds__((WK * WM + HELP) * 64) igemm_i8_kernel(const G
 
     if constexpr (FK * FM <= 2) {
         // Small wave tiles: one or two MFMAs per 32-deep half cannot cover an LDS read, so the
-        // fragments of a whole stage are read one stage ahead (two register sets of NH halves),
-        // and the halves alternate between two accumulators to halve the dependent MFMA chain.
-        v4i wq[2][NH][FK], aq[2][NH][FM];
+        // fragments of a whole stage are read one stage ahead (two register sets), and the
+        // halves alternate between two accumulators to halve the dependent MFMA chain.
+        constexpr int NHG = NH / DS;   // halves of a stage this wave multiplies
+        const int h0 = grp * NHG;      // ... starting at this one
+        v4i wq[2][NHG][FK], aq[2][NHG][FM];
         v16i acc2[FK][FM];
 #pragma unroll
         for (int i = 0; i < FK; ++i)
@@ -243,13 +254,17 @@ __global__ void __launch_bounds__((WK * WM + HELP) * 64) igemm_i8_kernel(const G
             for (int j = 0; j < FM; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc2[i][j][v] = 0;
+        int co[NHG];
+#pragma unroll
+        for (int h = 0; h < NHG; ++h) co[h] = DS == 1 ? coff[h] : (grp ? coff[(NHG + h) % NH] : coff[h]);
+        (void)h0;
         if (NSTAGE <= ns) wait_dma_outstanding<(NSTAGE - 1) * L>();
         else wait_dma_outstanding<0>();
         lds_barrier();
 #pragma unroll
-        for (int h = 0; h < NH; ++h)
+        for (int h = 0; h < NHG; ++h)
 #pragma unroll
-            for (int t = 0; t < NR; ++t) read_item(t, smem, coff[h], wq[0][h], aq[0][h]);
+            for (int t = 0; t < NR; ++t) read_item(t, smem, co[h], wq[0][h], aq[0][h]);
         for (int j = 0; j < ns; j += 2) {
 #pragma unroll
             for (int par = 0; par < 2; ++par) {  // stage j + par multiplies set `par`
@@ -269,12 +284,12 @@ __global__ void __launch_bounds__((WK * WM + HELP) * 64) igemm_i8_kernel(const G
                     // (after the last stage this reads a stale slot; the values are never used)
                     const unsigned char *nxt = smem + ((jj + 1) % NSTAGE) * STAGE;
 #pragma unroll
-                    for (int h = 0; h < NH; ++h)
+                    for (int h = 0; h < NHG; ++h)
 #pragma unroll
-                        for (int t = 0; t < NR; ++t) read_item(t, nxt, coff[h], wq[par ^ 1][h], aq[par ^ 1][h]);
+                        for (int t = 0; t < NR; ++t) read_item(t, nxt, co[h], wq[par ^ 1][h], aq[par ^ 1][h]);
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int h = 0; h < NH; ++h)
+                    for (int h = 0; h < NHG; ++h)
 #pragma unroll
                         for (int g = 0; g < NM; ++g) {
                             if (h & 1)
@@ -292,6 +307,33 @@ __global__ void __launch_bounds__((WK * WM + HELP) * 64) igemm_i8_kernel(const G
         for (int i = 0; i < FK; ++i)
 #pragma unroll
             for (int j = 0; j < FM; ++j) acc[i][j] += acc2[i][j];
+        if constexpr (DS == 2) {
+            // second group -> LDS -> first group (the ring is idle: every transfer has landed
+            // and, after this barrier, every fragment read has returned)
+            lds_barrier();
+            v4i *xch = reinterpret_cast<v4i *>(smem) + (wave % NWM) * NM * 256;
+            if (grp == 1) {
+#pragma unroll
+                for (int g = 0; g < NM; ++g)
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        v4i t;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) t[e] = acc[g / FM][g % FM][4 * q4 + e];
+                        xch[(g * 4 + q4) * 64 + lane] = t;
+                    }
+            }
+            lds_barrier();
+            if (grp == 1) return;
+#pragma unroll
+            for (int g = 0; g < NM; ++g)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const v4i t = xch[(g * 4 + q4) * 64 + lane];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[g / FM][g % FM][4 * q4 + e] += t[e];
+                }
+        }
     } else {
         // Software pipeline.  The matrix pipe idles whenever a wave does anything else for long,
         // so every LDS fragment read, every transfer and every address update is slotted between
@@ -413,55 +455,61 @@ __global__ void __launch_bounds__((WK * WM + HELP) * 64) igemm_i8_kernel(const G
 
 // ---- tile table -----------------------------------------------------------------------
 struct TileDef {
-    int tk, tm, wk, wm, ks, nstage, help;
+    int tk, tm, wk, wm, ks, nstage, help, ds;
 };
 static const TileDef kTiles[] = {
-    {32, 32, 1, 1, 1, 8, 0},  // 0
-    {64, 64, 2, 2, 1, 8, 0},  // 1
-    {128, 128, 2, 2, 1, 6, 0},  // 2
-    {32, 128, 1, 2, 1, 8, 0},  // 3
-    {64, 128, 2, 2, 1, 8, 0},  // 4
-    {64, 256, 1, 4, 1, 6, 0},  // 5
-    {128, 64, 2, 2, 1, 8, 0},  // 6
-    {256, 128, 2, 2, 1, 5, 0},  // 7
-    {128, 256, 2, 2, 1, 5, 0},  // 8
-    {256, 256, 2, 2, 1, 4, 0},  // 9
-    {256, 128, 2, 2, 1, 3, 0},  // 10
-    {128, 256, 2, 2, 1, 3, 0},  // 11
-    {128, 128, 2, 2, 1, 4, 0},  // 12
-    {256, 256, 2, 4, 2, 2, 0},  // 13
-    {256, 256, 2, 2, 2, 2, 0},  // 14
-    {256, 128, 2, 2, 2, 3, 0},  // 15
-    {128, 128, 2, 2, 2, 4, 0},  // 16
-    {64, 64, 2, 2, 2, 4, 0},  // 17
-    {64, 64, 2, 2, 2, 6, 0},  // 18
-    {32, 64, 1, 2, 2, 6, 0},  // 19
-    {64, 128, 2, 2, 2, 4, 0},  // 20
-    {64, 64, 2, 2, 2, 4, 4},  // 21
-    {64, 64, 2, 2, 2, 8, 4},  // 22
-    {128, 128, 2, 2, 2, 4, 4},  // 23
-    {64, 128, 2, 2, 2, 4, 4},  // 24
-    {128, 64, 2, 2, 2, 4, 4},  // 25
-    {256, 128, 2, 2, 2, 3, 4},  // 26
-    {128, 256, 2, 2, 2, 3, 4},  // 27
+    {32, 32, 1, 1, 1, 8, 0, 1},  // 0
+    {64, 64, 2, 2, 1, 8, 0, 1},  // 1
+    {128, 128, 2, 2, 1, 6, 0, 1},  // 2
+    {32, 128, 1, 2, 1, 8, 0, 1},  // 3
+    {64, 128, 2, 2, 1, 8, 0, 1},  // 4
+    {64, 256, 1, 4, 1, 6, 0, 1},  // 5
+    {128, 64, 2, 2, 1, 8, 0, 1},  // 6
+    {256, 128, 2, 2, 1, 5, 0, 1},  // 7
+    {128, 256, 2, 2, 1, 5, 0, 1},  // 8
+    {256, 256, 2, 2, 1, 4, 0, 1},  // 9
+    {256, 128, 2, 2, 1, 3, 0, 1},  // 10
+    {128, 256, 2, 2, 1, 3, 0, 1},  // 11
+    {128, 128, 2, 2, 1, 4, 0, 1},  // 12
+    {256, 256, 2, 4, 2, 2, 0, 1},  // 13
+    {256, 256, 2, 2, 2, 2, 0, 1},  // 14
+    {256, 128, 2, 2, 2, 3, 0, 1},  // 15
+    {128, 128, 2, 2, 2, 4, 0, 1},  // 16
+    {64, 64, 2, 2, 2, 4, 0, 1},  // 17
+    {64, 64, 2, 2, 2, 6, 0, 1},  // 18
+    {32, 64, 1, 2, 2, 6, 0, 1},  // 19
+    {64, 128, 2, 2, 2, 4, 0, 1},  // 20
+    {64, 64, 2, 2, 2, 4, 4, 1},  // 21
+    {64, 64, 2, 2, 2, 8, 4, 1},  // 22
+    {128, 128, 2, 2, 2, 4, 4, 1},  // 23
+    {64, 128, 2, 2, 2, 4, 4, 1},  // 24
+    {128, 64, 2, 2, 2, 4, 4, 1},  // 25
+    {256, 128, 2, 2, 2, 3, 4, 1},  // 26
+    {128, 256, 2, 2, 2, 3, 4, 1},  // 27
+    {64, 64, 2, 2, 2, 4, 0, 2},  // 28
+    {64, 64, 2, 2, 2, 6, 0, 2},  // 29
+    {64, 128, 2, 2, 2, 4, 0, 2},  // 30
+    {128, 64, 2, 2, 2, 4, 0, 2},  // 31
+    {32, 64, 1, 2, 2, 6, 0, 2},  // 32
+    {32, 32, 1, 1, 2, 8, 0, 2},  // 33
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
 int gemm_num_tiles() { return kNumTiles; }
 TileInfo gemm_tile_info(int t)
 {
-    return TileInfo{kTiles[t].tk, kTiles[t].tm, (kTiles[t].wk * kTiles[t].wm + kTiles[t].help) * 64, kTiles[t].ks};
+    return TileInfo{kTiles[t].tk, kTiles[t].tm, (kTiles[t].wk * kTiles[t].wm * kTiles[t].ds + kTiles[t].help) * 64, kTiles[t].ks};
 }
 
-template <int TK, int TM, int WK, int WM, int KS, int NSTAGE, int HELP>
+template <int TK, int TM, int WK, int WM, int KS, int NSTAGE, int HELP, int DS>
 static hipError_t launch_tile(const GemmArgs &a, int mode, hipStream_t st)
 {
-    constexpr int NT = (WK * WM + HELP) * 64;
+    constexpr int NT = (WK * WM * DS + HELP) * 64;
     constexpr int STAGE = (TK + TM) * 64 * KS;
     const size_t lds = (size_t)NSTAGE * STAGE + (mode == ACT_BLOCKED ? (size_t)a.ksteps_per_split * 16 : 0);
     const int grid = a.tiles_k * a.tiles_m * a.split_k;
-    auto kb = igemm_i8_kernel<TK, TM, WK, WM, KS, NSTAGE, HELP, ACT_BLOCKED>;
-    auto km = igemm_i8_kernel<TK, TM, WK, WM, KS, NSTAGE, HELP, ACT_MATRIX>;
+    auto kb = igemm_i8_kernel<TK, TM, WK, WM, KS, NSTAGE, HELP, DS, ACT_BLOCKED>;
+    auto km = igemm_i8_kernel<TK, TM, WK, WM, KS, NSTAGE, HELP, DS, ACT_MATRIX>;
     auto kern = mode == ACT_BLOCKED ? kb : km;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     static size_t raised[2] = {0, 0};  // dynamic-LDS ceiling already granted, per kernel
@@ -499,7 +547,7 @@ bool gemm_pick(const GemmProblem &g, int *tile, int *split_k)
     for (int t = 0; t < kNumTiles; ++t) {
         if (*tile >= 0 && t != *tile) continue;
         const TileDef &d = kTiles[t];
-        const int mwaves = d.wk * d.wm, waves = mwaves + d.help;
+        const int mwaves = d.wk * d.wm, waves = mwaves * d.ds + d.help;
         const double tiles = (double)ceil_div(g.K, d.tk) * ceil_div(g.M, d.tm);
         const double lds = (double)d.nstage * (d.tk + d.tm) * 64 * d.ks + 2048;
         const int acc = d.tk * d.tm / (mwaves * 64);  // accumulator registers per lane
@@ -602,34 +650,40 @@ hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t 
         if (e != hipSuccess) return e;
     }
     switch (tile) {
-        case 0: return launch_tile<32, 32, 1, 1, 1, 8, 0>(a, g.mode, st);
-        case 1: return launch_tile<64, 64, 2, 2, 1, 8, 0>(a, g.mode, st);
-        case 2: return launch_tile<128, 128, 2, 2, 1, 6, 0>(a, g.mode, st);
-        case 3: return launch_tile<32, 128, 1, 2, 1, 8, 0>(a, g.mode, st);
-        case 4: return launch_tile<64, 128, 2, 2, 1, 8, 0>(a, g.mode, st);
-        case 5: return launch_tile<64, 256, 1, 4, 1, 6, 0>(a, g.mode, st);
-        case 6: return launch_tile<128, 64, 2, 2, 1, 8, 0>(a, g.mode, st);
-        case 7: return launch_tile<256, 128, 2, 2, 1, 5, 0>(a, g.mode, st);
-        case 8: return launch_tile<128, 256, 2, 2, 1, 5, 0>(a, g.mode, st);
-        case 9: return launch_tile<256, 256, 2, 2, 1, 4, 0>(a, g.mode, st);
-        case 10: return launch_tile<256, 128, 2, 2, 1, 3, 0>(a, g.mode, st);
-        case 11: return launch_tile<128, 256, 2, 2, 1, 3, 0>(a, g.mode, st);
-        case 12: return launch_tile<128, 128, 2, 2, 1, 4, 0>(a, g.mode, st);
-        case 13: return launch_tile<256, 256, 2, 4, 2, 2, 0>(a, g.mode, st);
-        case 14: return launch_tile<256, 256, 2, 2, 2, 2, 0>(a, g.mode, st);
-        case 15: return launch_tile<256, 128, 2, 2, 2, 3, 0>(a, g.mode, st);
-        case 16: return launch_tile<128, 128, 2, 2, 2, 4, 0>(a, g.mode, st);
-        case 17: return launch_tile<64, 64, 2, 2, 2, 4, 0>(a, g.mode, st);
-        case 18: return launch_tile<64, 64, 2, 2, 2, 6, 0>(a, g.mode, st);
-        case 19: return launch_tile<32, 64, 1, 2, 2, 6, 0>(a, g.mode, st);
-        case 20: return launch_tile<64, 128, 2, 2, 2, 4, 0>(a, g.mode, st);
-        case 21: return launch_tile<64, 64, 2, 2, 2, 4, 4>(a, g.mode, st);
-        case 22: return launch_tile<64, 64, 2, 2, 2, 8, 4>(a, g.mode, st);
-        case 23: return launch_tile<128, 128, 2, 2, 2, 4, 4>(a, g.mode, st);
-        case 24: return launch_tile<64, 128, 2, 2, 2, 4, 4>(a, g.mode, st);
-        case 25: return launch_tile<128, 64, 2, 2, 2, 4, 4>(a, g.mode, st);
-        case 26: return launch_tile<256, 128, 2, 2, 2, 3, 4>(a, g.mode, st);
-        case 27: return launch_tile<128, 256, 2, 2, 2, 3, 4>(a, g.mode, st);
+        case 0: return launch_tile<32, 32, 1, 1, 1, 8, 0, 1>(a, g.mode, st);
+        case 1: return launch_tile<64, 64, 2, 2, 1, 8, 0, 1>(a, g.mode, st);
+        case 2: return launch_tile<128, 128, 2, 2, 1, 6, 0, 1>(a, g.mode, st);
+        case 3: return launch_tile<32, 128, 1, 2, 1, 8, 0, 1>(a, g.mode, st);
+        case 4: return launch_tile<64, 128, 2, 2, 1, 8, 0, 1>(a, g.mode, st);
+        case 5: return launch_tile<64, 256, 1, 4, 1, 6, 0, 1>(a, g.mode, st);
+        case 6: return launch_tile<128, 64, 2, 2, 1, 8, 0, 1>(a, g.mode, st);
+        case 7: return launch_tile<256, 128, 2, 2, 1, 5, 0, 1>(a, g.mode, st);
+        case 8: return launch_tile<128, 256, 2, 2, 1, 5, 0, 1>(a, g.mode, st);
+        case 9: return launch_tile<256, 256, 2, 2, 1, 4, 0, 1>(a, g.mode, st);
+        case 10: return launch_tile<256, 128, 2, 2, 1, 3, 0, 1>(a, g.mode, st);
+        case 11: return launch_tile<128, 256, 2, 2, 1, 3, 0, 1>(a, g.mode, st);
+        case 12: return launch_tile<128, 128, 2, 2, 1, 4, 0, 1>(a, g.mode, st);
+        case 13: return launch_tile<256, 256, 2, 4, 2, 2, 0, 1>(a, g.mode, st);
+        case 14: return launch_tile<256, 256, 2, 2, 2, 2, 0, 1>(a, g.mode, st);
+        case 15: return launch_tile<256, 128, 2, 2, 2, 3, 0, 1>(a, g.mode, st);
+        case 16: return launch_tile<128, 128, 2, 2, 2, 4, 0, 1>(a, g.mode, st);
+        case 17: return launch_tile<64, 64, 2, 2, 2, 4, 0, 1>(a, g.mode, st);
+        case 18: return launch_tile<64, 64, 2, 2, 2, 6, 0, 1>(a, g.mode, st);
+        case 19: return launch_tile<32, 64, 1, 2, 2, 6, 0, 1>(a, g.mode, st);
+        case 20: return launch_tile<64, 128, 2, 2, 2, 4, 0, 1>(a, g.mode, st);
+        case 21: return launch_tile<64, 64, 2, 2, 2, 4, 4, 1>(a, g.mode, st);
+        case 22: return launch_tile<64, 64, 2, 2, 2, 8, 4, 1>(a, g.mode, st);
+        case 23: return launch_tile<128, 128, 2, 2, 2, 4, 4, 1>(a, g.mode, st);
+        case 24: return launch_tile<64, 128, 2, 2, 2, 4, 4, 1>(a, g.mode, st);
+        case 25: return launch_tile<128, 64, 2, 2, 2, 4, 4, 1>(a, g.mode, st);
+        case 26: return launch_tile<256, 128, 2, 2, 2, 3, 4, 1>(a, g.mode, st);
+        case 27: return launch_tile<128, 256, 2, 2, 2, 3, 4, 1>(a, g.mode, st);
+        case 28: return launch_tile<64, 64, 2, 2, 2, 4, 0, 2>(a, g.mode, st);
+        case 29: return launch_tile<64, 64, 2, 2, 2, 6, 0, 2>(a, g.mode, st);
+        case 30: return launch_tile<64, 128, 2, 2, 2, 4, 0, 2>(a, g.mode, st);
+        case 31: return launch_tile<128, 64, 2, 2, 2, 4, 0, 2>(a, g.mode, st);
+        case 32: return launch_tile<32, 64, 1, 2, 2, 6, 0, 2>(a, g.mode, st);
+        case 33: return launch_tile<32, 32, 1, 1, 2, 8, 0, 2>(a, g.mode, st);
     }
     return hipErrorInvalidValue;
 }
