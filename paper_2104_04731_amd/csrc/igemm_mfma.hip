@@ -71,6 +71,14 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("" : : : "memory");
 }
 
+// How many of the transfer slots u*nq/l + off (u < l) come before slot qb.
+constexpr int slots_before(int l, int nq, int off, int qb)
+{
+    int n = 0;
+    for (int u = 0; u < l; ++u) n += (u * nq / l + off < qb) ? 1 : 0;
+    return n;
+}
+
 // HELP extra waves per workgroup only move operands (they issue their share of the transfers
 // and keep the barriers, no MFMA): a wave moves about 1 KB per 140-180 cycles through the
 // global->LDS path whatever the queue depth, so small tiles, whose four MFMA waves would be
@@ -81,8 +89,12 @@ __device__ __forceinline__ void lds_barrier()
 // added to the first's through LDS before the epilogue.  A 32x32 wave tile reads 4 KB of LDS
 // per 64 MFMA cycles, and four waves alone reach only ~100 B/clk of LDS bandwidth where eight
 // reach ~190: the second group doubles what a small tile can multiply per cycle.
-template <int TK, int TM, int WK, int WM, int KS, int NSTAGE, int HELP, int DS, int MODE>
-__global__ void __launch_bounds__((WK * WM * DS + HELP) * 64) igemm_i8_kernel(const GemmArgs a)
+//
+// WPC > 1 caps the registers so that WPC workgroups fit one CU: while one of them waits at a
+// barrier or drains its output tile, the matrix pipe works for the other.
+template <int TK, int TM, int WK, int WM, int KS, int NSTAGE, int HELP, int DS, int WPC, int MODE>
+__global__ void __launch_bounds__((WK * WM * DS + HELP) * 64, (WK * WM * DS + HELP + 3) / 4 * WPC)
+    igemm_i8_kernel(const GemmArgs a)
 {
     constexpr int NWM = WK * WM;           // waves of one multiplying group
     constexpr int NWC = NWM * DS;          // waves that multiply
@@ -194,9 +206,17 @@ __global__ void __launch_bounds__((WK * WM * DS + HELP) * 64) igemm_i8_kernel(co
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
+    // Transfers issued back to back stall the issuing wave (one instruction occupies it for
+    // well over a hundred cycles), and with them its MFMAs.  Large wave tiles therefore spread
+    // the transfers of one stage over all the MFMAs of a stage (SPREAD): stage j+NSTAGE-1 is
+    // fetched, one transfer every few MFMAs, while stage j is multiplied, into the ring slot
+    // that stage j-1 left; the prologue then fills only NSTAGE-1 slots.
+    constexpr bool SPREAD = NSTAGE >= 3 && HELP == 0 && (WTK / 32) * (WTM / 32) > 2;
+    constexpr int PRO = SPREAD ? NSTAGE - 1 : NSTAGE;  // stages fetched before the loop
+
     if (MODE == ACT_BLOCKED) __syncthreads();  // koff visible
 #pragma unroll
-    for (int j = 0; j < NSTAGE; ++j)
+    for (int j = 0; j < PRO; ++j)
         if (j < ns) {
             const unsigned st = lds0 + (unsigned)j * STAGE + (unsigned)wave * 1024u;
             const size_t aoff = stage_aoff(j);
@@ -334,6 +354,60 @@ __global__ void __launch_bounds__((WK * WM * DS + HELP) * 64) igemm_i8_kernel(co
                     for (int e = 0; e < 4; ++e) acc[g / FM][g % FM][4 * q4 + e] += t[e];
                 }
         }
+    } else if constexpr (SPREAD) {
+        // Software pipeline, transfers spread.  Slot q = h*NM + g of a stage is one MFMA plus its
+        // side work: a share of the fragment reads of the next half, and transfer u of stage
+        // j+NSTAGE-1 when u*NQ/L == q.  The barrier sits after the first MFMA of the last half:
+        // by then every wave holds the last fragments of stage j in registers (its ring slot is
+        // free for iteration j+1 to refill) and stage j+1 has landed.
+        // The two waves that share a SIMD (w and w + 4) take their transfer slots half a
+        // spacing apart, so that one of them can always feed the matrix pipe.
+        constexpr int NQ = NH * NM, QB = (NH - 1) * NM;
+        constexpr int OFF = NW > 4 ? NQ / L / 2 : 0;
+        constexpr int DB = slots_before(L, NQ, 0, QB);  // transfers of an iteration issued before its barrier
+        static_assert(slots_before(L, NQ, OFF, QB) == DB, "both wave groups issue the same count before the barrier");
+        const bool late = OFF > 0 && ((wave >> 2) & 1);
+        v4i wf[2][FK], af[2][FM];
+        if (PRO <= ns) wait_dma_outstanding<(PRO - 1) * L>();
+        else wait_dma_outstanding<0>();
+        lds_barrier();
+#pragma unroll
+        for (int t = 0; t < NR; ++t) read_item(t, smem, coff[0], wf[0], af[0]);
+
+        for (int j = 0; j < ns; ++j) {
+            const unsigned char *cur = smem + (j % NSTAGE) * STAGE;
+            const unsigned char *nxt = smem + ((j + 1) % NSTAGE) * STAGE;
+            const int jn = j + NSTAGE - 1;
+            const bool refill = jn < ns;  // uniform
+            const unsigned st = lds0 + (unsigned)(jn % NSTAGE) * STAGE + (unsigned)wave * 1024u;
+            size_t aoff = 0;
+            if (refill) aoff = stage_aoff(jn);
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+#pragma unroll
+                for (int g = 0; g < NM; ++g) {
+                    const int q = h * NM + g;
+                    acc[g / FM][g % FM] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
+                        wf[h & 1][g / FM], af[h & 1][g % FM], acc[g / FM][g % FM], 0, 0, 0);
+                    if (q == QB) {
+                        // stage j+1 landed: everything issued after it may still be in flight
+                        if (refill) wait_dma_outstanding<(NSTAGE - 3) * L + DB>();
+                        else wait_dma_outstanding<0>();
+                        lds_barrier();
+                    }
+#pragma unroll
+                    for (int u = 0; u < L; ++u) {
+                        if (u * NQ / L == q && refill && !late) dma_item(u, jn, st, aoff);
+                        if (OFF > 0 && u * NQ / L + OFF == q && refill && late) dma_item(u, jn, st, aoff);
+                    }
+                    // (after the last stage the reads hit a stale slot; the values are never used)
+#pragma unroll
+                    for (int u = g * NR / NM; u < (g + 1) * NR / NM; ++u)
+                        read_item(u, h == NH - 1 ? nxt : cur, coff[(h + 1) % NH], wf[(h + 1) & 1], af[(h + 1) & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
     } else {
         // Software pipeline.  The matrix pipe idles whenever a wave does anything else for long,
         // so every LDS fragment read, every transfer and every address update is slotted between
@@ -455,43 +529,50 @@ __global__ void __launch_bounds__((WK * WM * DS + HELP) * 64) igemm_i8_kernel(co
 
 // ---- tile table -----------------------------------------------------------------------
 struct TileDef {
-    int tk, tm, wk, wm, ks, nstage, help, ds;
+    int tk, tm, wk, wm, ks, nstage, help, ds, wpc;
 };
 static const TileDef kTiles[] = {
-    {32, 32, 1, 1, 1, 8, 0, 1},  // 0
-    {64, 64, 2, 2, 1, 8, 0, 1},  // 1
-    {128, 128, 2, 2, 1, 6, 0, 1},  // 2
-    {32, 128, 1, 2, 1, 8, 0, 1},  // 3
-    {64, 128, 2, 2, 1, 8, 0, 1},  // 4
-    {64, 256, 1, 4, 1, 6, 0, 1},  // 5
-    {128, 64, 2, 2, 1, 8, 0, 1},  // 6
-    {256, 128, 2, 2, 1, 5, 0, 1},  // 7
-    {128, 256, 2, 2, 1, 5, 0, 1},  // 8
-    {256, 256, 2, 2, 1, 4, 0, 1},  // 9
-    {256, 128, 2, 2, 1, 3, 0, 1},  // 10
-    {128, 256, 2, 2, 1, 3, 0, 1},  // 11
-    {128, 128, 2, 2, 1, 4, 0, 1},  // 12
-    {256, 256, 2, 4, 2, 2, 0, 1},  // 13
-    {256, 256, 2, 2, 2, 2, 0, 1},  // 14
-    {256, 128, 2, 2, 2, 3, 0, 1},  // 15
-    {128, 128, 2, 2, 2, 4, 0, 1},  // 16
-    {64, 64, 2, 2, 2, 4, 0, 1},  // 17
-    {64, 64, 2, 2, 2, 6, 0, 1},  // 18
-    {32, 64, 1, 2, 2, 6, 0, 1},  // 19
-    {64, 128, 2, 2, 2, 4, 0, 1},  // 20
-    {64, 64, 2, 2, 2, 4, 4, 1},  // 21
-    {64, 64, 2, 2, 2, 8, 4, 1},  // 22
-    {128, 128, 2, 2, 2, 4, 4, 1},  // 23
-    {64, 128, 2, 2, 2, 4, 4, 1},  // 24
-    {128, 64, 2, 2, 2, 4, 4, 1},  // 25
-    {256, 128, 2, 2, 2, 3, 4, 1},  // 26
-    {128, 256, 2, 2, 2, 3, 4, 1},  // 27
-    {64, 64, 2, 2, 2, 4, 0, 2},  // 28
-    {64, 64, 2, 2, 2, 6, 0, 2},  // 29
-    {64, 128, 2, 2, 2, 4, 0, 2},  // 30
-    {128, 64, 2, 2, 2, 4, 0, 2},  // 31
-    {32, 64, 1, 2, 2, 6, 0, 2},  // 32
-    {32, 32, 1, 1, 2, 8, 0, 2},  // 33
+    {32, 32, 1, 1, 1, 8, 0, 1, 1},  // 0
+    {64, 64, 2, 2, 1, 8, 0, 1, 1},  // 1
+    {128, 128, 2, 2, 1, 6, 0, 1, 1},  // 2
+    {32, 128, 1, 2, 1, 8, 0, 1, 1},  // 3
+    {64, 128, 2, 2, 1, 8, 0, 1, 1},  // 4
+    {64, 256, 1, 4, 1, 6, 0, 1, 1},  // 5
+    {128, 64, 2, 2, 1, 8, 0, 1, 1},  // 6
+    {256, 128, 2, 2, 1, 5, 0, 1, 1},  // 7
+    {128, 256, 2, 2, 1, 5, 0, 1, 1},  // 8
+    {256, 256, 2, 2, 1, 4, 0, 1, 1},  // 9
+    {256, 128, 2, 2, 1, 3, 0, 1, 1},  // 10
+    {128, 256, 2, 2, 1, 3, 0, 1, 1},  // 11
+    {128, 128, 2, 2, 1, 4, 0, 1, 1},  // 12
+    {256, 256, 2, 4, 2, 2, 0, 1, 1},  // 13
+    {256, 256, 2, 2, 2, 2, 0, 1, 1},  // 14
+    {256, 128, 2, 2, 2, 3, 0, 1, 1},  // 15
+    {128, 128, 2, 2, 2, 4, 0, 1, 1},  // 16
+    {64, 64, 2, 2, 2, 4, 0, 1, 1},  // 17
+    {64, 64, 2, 2, 2, 6, 0, 1, 1},  // 18
+    {32, 64, 1, 2, 2, 6, 0, 1, 1},  // 19
+    {64, 128, 2, 2, 2, 4, 0, 1, 1},  // 20
+    {64, 64, 2, 2, 2, 4, 4, 1, 1},  // 21
+    {64, 64, 2, 2, 2, 8, 4, 1, 1},  // 22
+    {128, 128, 2, 2, 2, 4, 4, 1, 1},  // 23
+    {64, 128, 2, 2, 2, 4, 4, 1, 1},  // 24
+    {128, 64, 2, 2, 2, 4, 4, 1, 1},  // 25
+    {256, 128, 2, 2, 2, 3, 4, 1, 1},  // 26
+    {128, 256, 2, 2, 2, 3, 4, 1, 1},  // 27
+    {64, 64, 2, 2, 2, 4, 0, 2, 1},  // 28
+    {64, 64, 2, 2, 2, 6, 0, 2, 1},  // 29
+    {64, 128, 2, 2, 2, 4, 0, 2, 1},  // 30
+    {128, 64, 2, 2, 2, 4, 0, 2, 1},  // 31
+    {32, 64, 1, 2, 2, 6, 0, 2, 1},  // 32
+    {32, 32, 1, 1, 2, 8, 0, 2, 1},  // 33
+    {128, 256, 2, 4, 1, 3, 0, 1, 2},  // 34
+    {256, 128, 4, 2, 1, 3, 0, 1, 2},  // 35
+    {128, 128, 2, 2, 1, 4, 0, 1, 2},  // 36
+    {128, 128, 2, 2, 2, 2, 0, 1, 2},  // 37
+    {256, 256, 2, 4, 1, 4, 0, 1, 1},  // 38
+    {256, 256, 4, 2, 1, 4, 0, 1, 1},  // 39
+    {256, 256, 2, 4, 1, 3, 0, 1, 1},  // 40
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -501,15 +582,15 @@ TileInfo gemm_tile_info(int t)
     return TileInfo{kTiles[t].tk, kTiles[t].tm, (kTiles[t].wk * kTiles[t].wm * kTiles[t].ds + kTiles[t].help) * 64, kTiles[t].ks};
 }
 
-template <int TK, int TM, int WK, int WM, int KS, int NSTAGE, int HELP, int DS>
+template <int TK, int TM, int WK, int WM, int KS, int NSTAGE, int HELP, int DS, int WPC = 1>
 static hipError_t launch_tile(const GemmArgs &a, int mode, hipStream_t st)
 {
     constexpr int NT = (WK * WM * DS + HELP) * 64;
     constexpr int STAGE = (TK + TM) * 64 * KS;
     const size_t lds = (size_t)NSTAGE * STAGE + (mode == ACT_BLOCKED ? (size_t)a.ksteps_per_split * 16 : 0);
     const int grid = a.tiles_k * a.tiles_m * a.split_k;
-    auto kb = igemm_i8_kernel<TK, TM, WK, WM, KS, NSTAGE, HELP, DS, ACT_BLOCKED>;
-    auto km = igemm_i8_kernel<TK, TM, WK, WM, KS, NSTAGE, HELP, DS, ACT_MATRIX>;
+    auto kb = igemm_i8_kernel<TK, TM, WK, WM, KS, NSTAGE, HELP, DS, WPC, ACT_BLOCKED>;
+    auto km = igemm_i8_kernel<TK, TM, WK, WM, KS, NSTAGE, HELP, DS, WPC, ACT_MATRIX>;
     auto kern = mode == ACT_BLOCKED ? kb : km;
     if (lds > 160 * 1024) return hipErrorInvalidValue;
     static size_t raised[2] = {0, 0};  // dynamic-LDS ceiling already granted, per kernel
@@ -684,6 +765,13 @@ hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t 
         case 31: return launch_tile<128, 64, 2, 2, 2, 4, 0, 2>(a, g.mode, st);
         case 32: return launch_tile<32, 64, 1, 2, 2, 6, 0, 2>(a, g.mode, st);
         case 33: return launch_tile<32, 32, 1, 1, 2, 8, 0, 2>(a, g.mode, st);
+        case 34: return launch_tile<128, 256, 2, 4, 1, 3, 0, 1, 2>(a, g.mode, st);
+        case 35: return launch_tile<256, 128, 4, 2, 1, 3, 0, 1, 2>(a, g.mode, st);
+        case 36: return launch_tile<128, 128, 2, 2, 1, 4, 0, 1, 2>(a, g.mode, st);
+        case 37: return launch_tile<128, 128, 2, 2, 2, 2, 0, 1, 2>(a, g.mode, st);
+        case 38: return launch_tile<256, 256, 2, 4, 1, 4, 0, 1, 1>(a, g.mode, st);
+        case 39: return launch_tile<256, 256, 4, 2, 1, 4, 0, 1, 1>(a, g.mode, st);
+        case 40: return launch_tile<256, 256, 2, 4, 1, 3, 0, 1, 1>(a, g.mode, st);
     }
     return hipErrorInvalidValue;
 }
