@@ -253,12 +253,17 @@ __global__ void __launch_bounds__((WK * WM * DS + HELP) * 64, (WK * WM * DS + HE
     int coff[NH];
 #pragma unroll
     for (int h = 0; h < NH; ++h) coff[h] = (((h >> 1) * 4 + 2 * (h & 1) + (lane >> 5)) ^ rswz) << 4;
-    // One fragment read (t < FK: weight block t, else activation block t - FK).
+    // One fragment read, in the order the MFMAs of a half (g = i*FM + j) first need them:
+    // weight block 0, every activation block, then the remaining weight blocks.
     auto read_item = [&](int t, const unsigned char *st, int co, v4i(&wf)[FK], v4i(&af)[FM]) {
-        if (t < FK) wf[t] = *reinterpret_cast<const v4i *>(st + wrow + t * 32 * RP + co);
-        else af[t - FK] = *reinterpret_cast<const v4i *>(st + arow + (t - FK) * 32 * RP + co);
+        if (t == 0) wf[0] = *reinterpret_cast<const v4i *>(st + wrow + co);
+        else if (t <= FM) af[t - 1] = *reinterpret_cast<const v4i *>(st + arow + (t - 1) * 32 * RP + co);
+        else wf[t - FM] = *reinterpret_cast<const v4i *>(st + wrow + (t - FM) * 32 * RP + co);
     };
     constexpr int NM = FK * FM, NR = FK + FM;
+    // Read t of the next half is issued right after MFMA read_slot(t) of this one: as early as
+    // the MFMA count allows, so that the last of them has landed when the next half begins.
+    auto read_slot = [](int t) constexpr { return NR > NM ? (t > NR - NM ? t - (NR - NM) : 0) : t; };
 
     if constexpr (FK * FM <= 2) {
         // Small wave tiles: one or two MFMAs per 32-deep half cannot cover an LDS read, so the
@@ -402,8 +407,9 @@ __global__ void __launch_bounds__((WK * WM * DS + HELP) * 64, (WK * WM * DS + HE
                     }
                     // (after the last stage the reads hit a stale slot; the values are never used)
 #pragma unroll
-                    for (int u = g * NR / NM; u < (g + 1) * NR / NM; ++u)
-                        read_item(u, h == NH - 1 ? nxt : cur, coff[(h + 1) % NH], wf[(h + 1) & 1], af[(h + 1) & 1]);
+                    for (int u = 0; u < NR; ++u)
+                        if (read_slot(u) == g)
+                            read_item(u, h == NH - 1 ? nxt : cur, coff[(h + 1) % NH], wf[(h + 1) & 1], af[(h + 1) & 1]);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -432,8 +438,8 @@ __global__ void __launch_bounds__((WK * WM * DS + HELP) * 64, (WK * WM * DS + HE
                     acc[g / FM][g % FM] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
                         wf[h & 1][g / FM], af[h & 1][g % FM], acc[g / FM][g % FM], 0, 0, 0);
     #pragma unroll
-                    for (int u = g * NR / NM; u < (g + 1) * NR / NM; ++u)
-                        read_item(u, cur, coff[h + 1], wf[(h + 1) & 1], af[(h + 1) & 1]);
+                    for (int u = 0; u < NR; ++u)
+                        if (read_slot(u) == g) read_item(u, cur, coff[h + 1], wf[(h + 1) & 1], af[(h + 1) & 1]);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -444,7 +450,6 @@ __global__ void __launch_bounds__((WK * WM * DS + HELP) * 64, (WK * WM * DS + HE
             const unsigned char *nxt = smem + ((j + 1) % NSTAGE) * STAGE;
             size_t aoff = 0;
             if (refill) aoff = stage_aoff(jn);
-            constexpr int NI = L + NR;  // side items of the last half: transfers, then reads
     #pragma unroll
             for (int g = 0; g < NM; ++g) {
                 acc[g / FM][g % FM] = __builtin_amdgcn_mfma_i32_32x32x32_i8(
@@ -454,15 +459,14 @@ __global__ void __launch_bounds__((WK * WM * DS + HELP) * 64, (WK * WM * DS + HE
                     else wait_dma_outstanding<0>();
                     lds_barrier();
                 }
+                // side items of the last half: the first reads of stage j+1 (after the last stage
+                // they hit a stale slot; the values are never used) and the transfers
     #pragma unroll
-                for (int u = g * NI / NM; u < (g + 1) * NI / NM; ++u) {
-                    if (u < L) {
-                        if (refill) dma_item(u, jn, st, aoff);
-                    } else {
-                        // (after the last stage this reads a stale slot; the values are never used)
-                        read_item(u - L, nxt, coff[0], wf[0], af[0]);
-                    }
-                }
+                for (int u = 0; u < NR; ++u)
+                    if (read_slot(u) == g) read_item(u, nxt, coff[0], wf[0], af[0]);
+    #pragma unroll
+                for (int u = g * L / NM; u < (g + 1) * L / NM; ++u)
+                    if (refill) dma_item(u, jn, st, aoff);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
