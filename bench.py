@@ -24,6 +24,29 @@ sys.path.insert(0, ROOT)
 PEAK_INT8_OPS = 5.0e15   # dense int8 MFMA, MI355X
 PEAK_HBM_BPS = 8.0e12    # HBM3E
 
+# HBM-side bytes per launch of the dominant kernel (the GEMM stage on C4a), from the two
+# rocprofv3 counter runs summarised in profiles/conv2d_int8_C4_hbm_counters.txt (FETCH_SIZE and
+# WRITE_SIZE, each scaled by what the same counter reads for a 256 MiB device copy).  They
+# describe the kernel source whose hash is recorded here; for any other source `traffic` is null.
+TRAFFIC = {
+    "source": "paper_2104_04731_amd/csrc/igemm_mfma.hip",
+    "sha256": "",
+    "fetch_bytes": None,
+    "write_bytes": None,
+}
+
+
+def measured_traffic():
+    import hashlib
+    try:
+        with open(os.path.join(ROOT, TRAFFIC["source"]), "rb") as f:
+            h = hashlib.sha256(f.read()).hexdigest()
+    except OSError:
+        return None
+    if h != TRAFFIC["sha256"] or TRAFFIC["fetch_bytes"] is None:
+        return None
+    return TRAFFIC["fetch_bytes"] + TRAFFIC["write_bytes"]
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -153,7 +176,7 @@ def main():
     _, dom_ms = timed(dom.op, args.steps, args.warmup)
     achieved = dom.cfg.ops / (dom_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 3), "peak": PEAK_INT8_OPS / 1e12,
-                "unit": "TOP/s", "frac": round(achieved * 1e12 / PEAK_INT8_OPS, 5), "traffic": None,
+                "unit": "TOP/s", "frac": round(achieved * 1e12 / PEAK_INT8_OPS, 5), "traffic": measured_traffic(),
                 "kernel": "igemm_i8_kernel", "config": dom.cfg.name,
                 "launch_us": round(dom_ms * 1e3, 3)}
 

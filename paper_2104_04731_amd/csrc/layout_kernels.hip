@@ -686,7 +686,7 @@ __device__ __forceinline__ void im2col_tiled_body(const I2cArgs &a, int bid, uns
                 const unsigned mask = n0 >= 4 ? 0xFFFFFFFFu : ((1u << (8 * n0)) - 1u);
                 ov[d] = (int)((v0 & mask) | (v1 & ~mask));
             }
-            *reinterpret_cast<v4i *>(out0 + (long long)ql * a.kg_pad + (ch << 4)) = ov;
+            __builtin_nontemporal_store(ov, reinterpret_cast<v4i *>(out0 + (long long)ql * a.kg_pad + (ch << 4)));
         }
         return;
     }
