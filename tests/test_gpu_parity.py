@@ -41,6 +41,18 @@ def test_pack_layout(lib, shape, cb, pad):
     np.testing.assert_array_equal(got, layouts.pack_layout(x, cb, pad))
 
 
+@pytest.mark.parametrize("shape,cb,pad", [
+    ((2, 70, 6, 10), 64, 2), ((1, 130, 14, 14), 128, 1), ((3, 64, 8, 8), 64, 0), ((1, 64, 5, 4), 64, 3),
+    ((2, 200, 9, 12), 64, 1), ((1, 64, 56, 56), 64, 1), ((2, 64, 1, 4), 64, 1), ((1, 65, 16, 20), 192, 1),
+])
+def test_pack_layout_64_channel_slices(lib, shape, cb, pad):
+    """Shapes the wave-tiled kernel takes: partial last chunk, dead channels, several slices per block,
+    row ends inside a chunk, top and bottom border rows wider than a chunk."""
+    x = uniform_int8(sum(shape) + cb + pad, shape)
+    got = host(lib.pack_layout(dev(x), cb, pad))
+    np.testing.assert_array_equal(got, layouts.pack_layout(x, cb, pad))
+
+
 @pytest.mark.parametrize("name", ["C2", "C3", "C4a", "C5"])
 def test_pack_layout_configs(lib, name):
     cfg = CONFIGS[name]
@@ -239,3 +251,44 @@ def test_non_default_stream(lib):
         out = lib.conv2d_int8(dx, dw, cfg.stride, cfg.pad)
     s.synchronize()
     assert np.array_equal(out.cpu().numpy(), want)
+
+
+# ---- the batch-scaled shapes bench.py times (supplementary section): sampled images -------------
+def _sample_images(N):
+    return sorted({0, N // 2 - 1, N - 1})
+
+
+def test_batch_scaled_gemm_stage_sampled_images(lib):
+    """C4a at N=2048 in the configuration bench.py times: whole output planes of sampled images
+    against the direct convolution of those images (images are independent)."""
+    cfg = CONFIGS["C4a"].scaled(2048)
+    g = torch.Generator(device=DEV); g.manual_seed(4242)
+    x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=DEV, generator=g)
+    w = torch.randint(-128, 128, (cfg.K, cfg.C, cfg.R, cfg.S), dtype=torch.int8, device=DEV, generator=g)
+    lay, cb, _ = lib.select_layout(cfg.dims())
+    xp = lib.pack_layout(x, cb, cfg.pad)
+    wp = lib.pack_weights(w, lay, cb)
+    out = torch.empty((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=DEV)
+    lib.conv2d_int8_packed(cfg.dims(), lay, cb, xp, wp, out)
+    wh = host(w)
+    for n in _sample_images(cfg.N):
+        want = direct.conv2d_int8(host(x[n:n + 1]), wh, cfg.stride, cfg.pad)
+        assert np.array_equal(host(out[n:n + 1]), want), n
+        assert np.array_equal(host(xp[n:n + 1]), layouts.pack_layout(host(x[n:n + 1]), cb, cfg.pad)), n
+
+
+def test_batch_scaled_layout_kernels_sampled_images(lib):
+    g = torch.Generator(device=DEV); g.manual_seed(4243)
+    cfg = CONFIGS["C2"].scaled(2048)
+    x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=DEV, generator=g)
+    xp = lib.pack_layout(x, 64, cfg.pad)
+    for n in _sample_images(cfg.N):
+        assert np.array_equal(host(xp[n:n + 1]), layouts.pack_layout(host(x[n:n + 1]), 64, cfg.pad)), n
+    del x, xp
+    cfg = CONFIGS["C3"].scaled(512)
+    x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=DEV, generator=g)
+    a = lib.im2col_int8(x, cfg.R, cfg.S, cfg.stride, cfg.pad)
+    per = cfg.P * cfg.Q
+    for n in _sample_images(cfg.N):
+        want = layouts.im2col(host(x[n:n + 1]), cfg.R, cfg.S, cfg.stride, cfg.pad)
+        assert np.array_equal(host(a[n * per:(n + 1) * per]), want), n
