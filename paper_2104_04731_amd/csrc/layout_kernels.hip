@@ -733,12 +733,13 @@ static bool plan_im2col_tiled(int N, int C, int H, int W, int R, int S, int stri
     int TQ = (32 * 1024 + kg_pad - 1) / kg_pad;
     if (TQ > Q) TQ = Q;
     if (TQ > 256) TQ = 256;
-    // small problems: narrower tiles so that there are a few workgroups per CU
+    // small problems: narrower tiles until there are about two workgroups per CU (measured:
+    // narrower than that costs more in repeated patch staging than the extra workgroups gain)
     const long long rows = (long long)N * P;
-    if (rows * ((Q + TQ - 1) / TQ) < 2048) {
-        const long long want = (2048 + rows - 1) / rows;
+    if (rows * ((Q + TQ - 1) / TQ) < 512) {
+        const long long want = (512 + rows - 1) / rows;
         int narrow = (int)((Q + want - 1) / want);
-        if (narrow < 16) narrow = 16;
+        if (narrow < 32) narrow = 32;
         if (narrow < TQ) TQ = narrow;
     }
     if (TQ < 1) TQ = 1;
