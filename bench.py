@@ -30,9 +30,9 @@ PEAK_HBM_BPS = 8.0e12    # HBM3E
 # describe the kernel source whose hash is recorded here; for any other source `traffic` is null.
 TRAFFIC = {
     "source": "paper_2104_04731_amd/csrc/igemm_mfma.hip",
-    "sha256": "",
-    "fetch_bytes": None,
-    "write_bytes": None,
+    "sha256": "bfefb8f0a0d8256dbd55f5103df4c8239ec344c3bc073cf4f89cb592a3a7b493",
+    "fetch_bytes": 5476589,
+    "write_bytes": 3211264,
 }
 
 
