@@ -17,7 +17,10 @@
  *     invalid arguments).  Arguments are validated before anything is enqueued,
  *     so a non-zero status leaves all buffers untouched.  Nothing throws.
  *   - Calls on different host threads must use different streams AND, for the
- *     one-shot conv2d_int8, are serialised on the library's cached workspace.
+ *     one-shot conv2d_int8, are serialised on the library's cached workspace:
+ *     two conv2d_int8 calls on one device must not run concurrently (one stream,
+ *     or streams ordered by events).  conv2d_int8 is also the one exception to
+ *     "no host synchronisation": growing its workspace drains the device once.
  *
  * Operation computed (Sec. 3 tensor expression / Fig. 5 step 1; access [n, i+k]
  * of Table 2 => cross-correlation; 8-bit operands, 32-bit accumulation, Sec. 5.1):
@@ -61,7 +64,8 @@ typedef struct {
 
 /* ---- one-shot convolution (layout rewrite of input and weights + GEMM stage) ---------
  * Picks the layout with select_layout, uses a workspace the library caches per device
- * (grown with hipMalloc when a larger problem arrives, never shrunk). */
+ * (grown with hipMalloc when a larger problem arrives, never shrunk: make the first call for
+ * a problem size outside stream capture).  Two launches: both rewrites, then the GEMM stage. */
 int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                 const int8_t *in, const int8_t *wt, int32_t *out, void *stream);
 

@@ -102,9 +102,10 @@ constexpr int slots_before(int l, int nq, int off, int qb)
 //
 // WPC > 1 caps the registers so that WPC workgroups fit one CU: while one of them waits at a
 // barrier or drains its output tile, the matrix pipe works for the other.
-template <int TK, int TM, int WK, int WM, int KS, int NSTAGE, int HELP, int DS, int WPC, int MODE>
-__global__ void __launch_bounds__((WK * WM * DS + HELP) * 64, (WK * WM * DS + HELP + 3) / 4 * WPC)
-    igemm_i8_kernel(const GemmArgs a)
+//
+// The body is a device function of (logical workgroup id, workgroup count, LDS base).
+template <int TK, int TM, int WK, int WM, int KS, int NSTAGE, int HELP, int DS, int MODE>
+__device__ __forceinline__ void igemm_body(const GemmArgs &a, int block_id, int nblocks, unsigned char *smem)
 {
     constexpr int NWM = WK * WM;           // waves of one multiplying group
     constexpr int NWC = NWM * DS;          // waves that multiply
@@ -126,7 +127,6 @@ __global__ void __launch_bounds__((WK * WM * DS + HELP) * 64, (WK * WM * DS + HE
     static_assert(KS == 1 || NW % 2 == 0, "row swizzle of a transfer must not depend on its slot");
     static_assert(NSTAGE >= 2 && (NSTAGE - 1) * L <= 63, "vmcnt is a 6-bit counter");
 
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     int *koff = reinterpret_cast<int *>(smem + NSTAGE * STAGE);
     const unsigned lds0 =
         (unsigned)(size_t)((__attribute__((address_space(3))) unsigned char *)smem);
@@ -136,7 +136,7 @@ __global__ void __launch_bounds__((WK * WM * DS + HELP) * 64, (WK * WM * DS + HE
     const int grp = DS == 1 ? 0 : wave / NWM;  // depth group of this wave
     const int wk = (wave % NWM) % WK, wm = (wave % NWM) / WK;
 
-    int lid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+    int lid = xcd_contiguous_id(block_id, nblocks);
     int tk, tm;
     if (a.m_fastest) {  // consecutive tiles share a weight tile (few output channels per XCD)
         const int q1 = div_magic(lid, a.tiles_m, a.mg_tiles_m);
@@ -541,6 +541,14 @@ __global__ void __launch_bounds__((WK * WM * DS + HELP) * 64, (WK * WM * DS + HE
     }
 }
 
+template <int TK, int TM, int WK, int WM, int KS, int NSTAGE, int HELP, int DS, int WPC, int MODE>
+__global__ void __launch_bounds__((WK * WM * DS + HELP) * 64, (WK * WM * DS + HELP + 3) / 4 * WPC)
+    igemm_i8_kernel(const GemmArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    igemm_body<TK, TM, WK, WM, KS, NSTAGE, HELP, DS, MODE>(a, blockIdx.x, gridDim.x, smem);
+}
+
 // ---- tile table -----------------------------------------------------------------------
 struct TileDef {
     int tk, tm, wk, wm, ks, nstage, help, ds, wpc;
@@ -691,7 +699,8 @@ bool gemm_pick(const GemmProblem &g, int *tile, int *split_k)
     return found;
 }
 
-hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t st)
+// Fills the kernel's argument block; false if the tile cannot walk this depth in whole stages.
+static bool make_gemm_args(const GemmProblem &g, int tile, int split_k, GemmArgs *out)
 {
     const TileDef &d = kTiles[tile];
     GemmArgs a;
@@ -719,7 +728,7 @@ hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t 
     if (split_k > a.ksteps_total) split_k = a.ksteps_total;
     a.ksteps_per_split = ceil_div(a.ksteps_total, split_k);
     a.split_k = ceil_div(a.ksteps_total, a.ksteps_per_split);
-    if (!tile_fits(d, a.ksteps_total, a.ksteps_per_split)) return hipErrorInvalidValue;
+    if (!tile_fits(d, a.ksteps_total, a.ksteps_per_split)) return false;
     a.out_fits_32bit = (unsigned long long)g.M * g.K * sizeof(int32_t) < (1ULL << 32);
     {
         // Each XCD has its own L2 and gets a contiguous eighth of the tile list: order the
@@ -750,6 +759,14 @@ hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t 
     a.mg_Q = magic(g.Q);
     a.mg_tiles_k = magic(a.tiles_k);
     a.mg_tiles_m = magic(a.tiles_m);
+    *out = a;
+    return true;
+}
+
+hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t st)
+{
+    GemmArgs a;
+    if (!make_gemm_args(g, tile, split_k, &a)) return hipErrorInvalidValue;
     if (a.split_k > 1) {
         hipError_t e = launch_fill_zero(g.out, (size_t)g.M * g.K * sizeof(int32_t), st);
         if (e != hipSuccess) return e;

@@ -2,41 +2,9 @@
 // (zero padding included) is written exactly once, in 16-byte pieces, and source reads run
 // along the contiguous W axis across the lanes of a wave.
 #include "kernels.h"
+#include "rewrite_bodies.h"
 
 namespace c2i8 {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));  // 16 bytes at a dword-aligned address
-
-// Workgroups are dealt round-robin over the 8 XCDs (each with its own L2).  Mapping the
-// hardware id to a logical id that is contiguous per XCD makes neighbouring tiles -- which
-// share source cache lines (pack) or whole source rows (im2col) -- run behind the same L2.
-__device__ __forceinline__ int xcd_contiguous(int id, int n)
-{
-    const int x = id & 7, q = n >> 3, rem = n & 7;
-    return x * q + (x < rem ? x : rem) + (id >> 3);
-}
-
-__device__ __forceinline__ unsigned pack4(int b0, int b1, int b2, int b3)
-{
-    return (unsigned)(b0 & 0xFF) | ((unsigned)(b1 & 0xFF) << 8) | ((unsigned)(b2 & 0xFF) << 16) |
-           ((unsigned)(b3 & 0xFF) << 24);
-}
-
-// n / d for magic = ceil(2^32 / d) truncated to 32 bits (0 encodes d == 1); exact while
-// n * d < 2^32
-__device__ __forceinline__ int fast_div(int n, unsigned magic)
-{
-    return magic ? (int)__umulhi((unsigned)n, magic) : n;
-}
-// The same for any 0 <= n < 2^31: the estimate is never low and at most one too high.
-__device__ __forceinline__ int fast_div_any(int n, int d, unsigned magic)
-{
-    int q = fast_div(n, magic);
-    if ((long long)q * d > n) --q;
-    return q;
-}
-static unsigned magic_for(long long d) { return (unsigned)((0x100000000ULL + (unsigned long long)d - 1) / (unsigned long long)d); }
 
 // ---- pack_layout: NCHW -> [N][Cb][Hp][Wp][cb] -------------------------------------------
 // One thread produces VEC = min(cb,16) channel-contiguous bytes of one padded pixel.
@@ -202,153 +170,12 @@ __global__ void __launch_bounds__(256) pack_layout_tiled_kernel(const PackArgs a
     pack_layout_tiled_body(a, xcd_contiguous(blockIdx.x, gridDim.x), tile);
 }
 
-// Wave-tiled version for 64-channel slices (cb % 64 == 0).  The unit of work is one wave:
-// 64 consecutive SOURCE pixels of the 64 channel planes of a slice (4 KB in, 4 KB out), with
-// no workgroup barrier anywhere -- the four waves of a workgroup only share a launch.
-//   in:  lane = (16-byte piece of the 64-byte run, channel l/4 + 16k): four loads per lane,
-//        each wave instruction covering whole 64-byte runs of 16 channels;
-//   LDS: a private [64 channels][17 dwords] tile per wave (odd pitch: the row-wise writes
-//        and the column-wise reads below are conflict-free);
-//   out: lane = (16-channel group g = l%4, dword column l/4): the dwords of four consecutive
-//        pixels from 16 channels, transposed with byte permutes into the four pixels' 16
-//        channel-contiguous bytes; the four lanes of a pixel write its 64 bytes side by side;
-//   border: the lane that writes the last pixel of an image row also zeroes the 2*pad border
-//        pixels that follow it in the padded order (right border + next row's left border);
-//        the waves holding the first and the last pixel of a plane zero the top and bottom rows.
-// Working in source order means there is no mapping from padded index back to the image.
-struct PackWaveArgs {
-    const int8_t *src;
-    int8_t *dst;
-    int C, H, W, cb, pad, Hp, Wp, Cb, slices, chunks;  // chunks = ceil(H*W / 64)
-    long long waves;
-    unsigned m_W, m_chunks, m_slices, m_Cb;
-};
-constexpr int PW_PITCH = 17;                      // dwords per channel row
-constexpr int PW_LDS = 64 * PW_PITCH * 4;         // bytes per wave
-
-__device__ __forceinline__ void pack_layout_wave_body(const PackWaveArgs &a, long long wid, unsigned *tile)
-{
-    const int C = a.C, H = a.H, W = a.W, cb = a.cb, pad = a.pad, Wp = a.Wp;
-    const int HW = H * W, HpWp = a.Hp * Wp;
-    const int lane = threadIdx.x & 63;
-    // wid = ((n*Cb + b)*slices + sl)*chunks + chunk
-    const int id = (int)wid;
-    const int q1 = fast_div_any(id, a.chunks, a.m_chunks), chunk = id - q1 * a.chunks;
-    const int q2 = fast_div_any(q1, a.slices, a.m_slices), sl = q1 - q2 * a.slices;
-    const int q3 = fast_div_any(q2, a.Cb, a.m_Cb), b = q2 - q3 * a.Cb;
-    const long long n = q3;
-    const int c0 = b * cb + sl * 64;
-    const int s0 = chunk * 64;  // first source pixel
-    const int8_t *plane0 = a.src + (n * C + c0) * (long long)HW + s0;
-    int8_t *out0 = a.dst + ((n * a.Cb + b) * (long long)HpWp) * cb + sl * 64;
-
-    {
-        const int p = lane & 3, chq = lane >> 2;
-        const bool whole = s0 + 64 <= HW;  // uniform
-        v4i v[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int ch = chq + 16 * k;
-            v[k] = v4i{0, 0, 0, 0};
-            if (c0 + ch < C) {
-                const int8_t *q = plane0 + (long long)ch * HW + 16 * p;
-                if (whole) {
-                    v[k] = *reinterpret_cast<const v4i_a4 *>(q);
-                } else {  // last chunk of a plane: dword by dword, guarded
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (s0 + 16 * p + 4 * e + 4 <= HW) v[k][e] = *reinterpret_cast<const int *>(q + 4 * e);
-                }
-            }
-        }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            unsigned *row = tile + (chq + 16 * k) * PW_PITCH + 4 * p;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) row[e] = (unsigned)v[k][e];
-        }
-    }
-    // same wave on both sides: the LDS executes a wave's accesses in order
-    __builtin_amdgcn_wave_barrier();
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_wave_barrier();
-
-    const v4i zero = {0, 0, 0, 0};
-    {
-        const int g = lane & 3, cq = lane >> 2;
-        const unsigned *col = tile + (g * 16) * PW_PITCH + cq;
-        unsigned d[16];
-#pragma unroll
-        for (int c = 0; c < 16; ++c) d[c] = col[c * PW_PITCH];
-        // o[j][q] = byte j of d[4q .. 4q+3]: pixel j, channels 4q .. 4q+3
-        v4i o[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const unsigned t0 = __builtin_amdgcn_perm(d[4 * q + 1], d[4 * q], 0x05010400u);
-            const unsigned t1 = __builtin_amdgcn_perm(d[4 * q + 1], d[4 * q], 0x07030602u);
-            const unsigned t2 = __builtin_amdgcn_perm(d[4 * q + 3], d[4 * q + 2], 0x05010400u);
-            const unsigned t3 = __builtin_amdgcn_perm(d[4 * q + 3], d[4 * q + 2], 0x07030602u);
-            o[0][q] = (int)__builtin_amdgcn_perm(t2, t0, 0x05040100u);
-            o[1][q] = (int)__builtin_amdgcn_perm(t2, t0, 0x07060302u);
-            o[2][q] = (int)__builtin_amdgcn_perm(t3, t1, 0x05040100u);
-            o[3][q] = (int)__builtin_amdgcn_perm(t3, t1, 0x07060302u);
-        }
-        const int i = s0 + 4 * cq;
-        const int h = fast_div(i, a.m_W), w = i - h * W;
-        int8_t *row_end = nullptr;  // W >= 4: at most one of the four pixels ends an image row
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (i + j < HW) {
-                int wj = w + j, hj = h;
-                if (wj >= W) {
-                    wj -= W;
-                    ++hj;
-                }
-                int8_t *dp = out0 + ((long long)(hj + pad) * Wp + wj + pad) * cb + g * 16;
-                *reinterpret_cast<v4i *>(dp) = o[j];
-                if (wj == W - 1 && hj < H - 1) row_end = dp;
-            }
-        }
-        if (row_end)  // the border pixels up to the next image row
-            for (int z = 1; z <= 2 * pad; ++z) *reinterpret_cast<v4i *>(row_end + (long long)z * cb) = zero;
-    }
-    if (pad > 0) {
-        // border rows above the first and below the last pixel of the plane: four lanes per pixel
-        const int top = pad * Wp + pad, bottom0 = (pad + H - 1) * Wp + pad + W;
-        if (chunk == 0)
-            for (int idx = lane; idx < top * 4; idx += 64)
-                *reinterpret_cast<v4i *>(out0 + (long long)(idx >> 2) * cb + (idx & 3) * 16) = zero;
-        if (chunk == a.chunks - 1)
-            for (int idx = lane; idx < (HpWp - bottom0) * 4; idx += 64)
-                *reinterpret_cast<v4i *>(out0 + (long long)(bottom0 + (idx >> 2)) * cb + (idx & 3) * 16) = zero;
-    }
-}
-
 __global__ void __launch_bounds__(256) pack_layout_wave_kernel(const PackWaveArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned tile[4 * PW_LDS / 4];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const long long wid = (long long)xcd_contiguous(blockIdx.x, gridDim.x) * 4 + wave;
     if (wid < a.waves) pack_layout_wave_body(a, wid, tile + wave * (PW_LDS / 4));
-}
-
-// Fills `a` and the workgroup count if the wave-tiled kernel can run this problem.
-static bool plan_pack_wave(int N, int C, int H, int W, int cb, int pad, const int8_t *src, int8_t *dst,
-                           PackWaveArgs *a, long long *blocks)
-{
-    const int Hp = H + 2 * pad, Wp = W + 2 * pad, Cb = (C + cb - 1) / cb;
-    const long long hw = (long long)H * W;
-    if (!(cb % 64 == 0 && hw % 4 == 0 && (reinterpret_cast<uintptr_t>(src) & 3) == 0 && W >= 4 &&
-          hw * W < (1LL << 32) && (long long)Hp * Wp < (1LL << 30)))  // multiply-high split by W stays exact
-        return false;
-    const int slices = cb / 64;
-    const long long chunks = (hw + 63) / 64;
-    const long long waves = (long long)N * Cb * slices * chunks;
-    if (waves >= (1LL << 31)) return false;
-    *blocks = (waves + 3) / 4;
-    *a = PackWaveArgs{src, dst, C, H, W, cb, pad, Hp, Wp, Cb, slices, (int)chunks, waves,
-                      magic_for(W), magic_for(chunks), magic_for(slices), magic_for(Cb)};
-    return true;
 }
 
 static int grid_for(long long work_items, int block)
@@ -415,61 +242,16 @@ hipError_t launch_pack_layout(int N, int C, int H, int W, int cb, int pad,
 }
 
 // ---- pack_weights -----------------------------------------------------------------------
-// Blocked: dst[k][((b*R + r)*S + s)*cb + ci] = src[k][b*cb+ci][r][s]; one thread per 16 B.
-struct WeightArgs {
-    const int8_t *src;
-    int8_t *dst;
-    int K, C, R, S, cb, depth, nreal;  // cb == 0: row-padded copy (depth order of KCRS itself)
-};
-
-__device__ __forceinline__ void pack_weights_blocked_body(const WeightArgs &a, int vbid, int vgrid)
-{
-    const int8_t *__restrict__ src = a.src;
-    int8_t *__restrict__ dst = a.dst;
-    const int K = a.K, C = a.C, cb = a.cb, depth = a.depth, nreal = a.nreal;
-    const int chunks = depth / 16;
-    const long long total = (long long)K * chunks;
-    const int g16 = cb / 16, RS = a.R * a.S;
-    for (long long t = (long long)vbid * 256 + threadIdx.x; t < total; t += (long long)vgrid * 256) {
-        const int ch = (int)(t % chunks);
-        const long long k = t / chunks;
-        int v[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) v[i] = 0;
-        if (ch < nreal) {
-            const int sub = ch % g16, tap = ch / g16;
-            const int rs = tap % RS, b = tap / RS;
-            const int c0 = b * cb + sub * 16;
-            const int8_t *s = src + (k * C + c0) * RS + rs;
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-                if (c0 + i < C) v[i] = s[i * RS];
-        }
-        v4i o;
-        o[0] = pack4(v[0], v[1], v[2], v[3]);
-        o[1] = pack4(v[4], v[5], v[6], v[7]);
-        o[2] = pack4(v[8], v[9], v[10], v[11]);
-        o[3] = pack4(v[12], v[13], v[14], v[15]);
-        *reinterpret_cast<v4i *>(dst + k * depth + (long long)ch * 16) = o;
-    }
-}
-
 __global__ void __launch_bounds__(256) pack_weights_blocked_kernel(const WeightArgs a)
 {
-    pack_weights_blocked_body(a, blockIdx.x, gridDim.x);
-}
-
-static WeightArgs weight_args_blocked(int K, int C, int R, int S, int cb, int depth,
-                                      const int8_t *src, int8_t *dst)
-{
-    const int Cb = (C + cb - 1) / cb;
-    return WeightArgs{src, dst, K, C, R, S, cb, depth, Cb * R * S * (cb / 16)};
+    pack_weights_blocked_body(a, blockIdx.x, gridDim.x, 256);
 }
 
 hipError_t launch_pack_weights_blocked(int K, int C, int R, int S, int cb, int depth,
                                        const int8_t *src, int8_t *dst, hipStream_t st)
 {
     const long long items = (long long)K * (depth / 16);
+    if (items >= (1LL << 31)) return hipErrorInvalidValue;
     hipLaunchKernelGGL(pack_weights_blocked_kernel, dim3(grid_for(items, 256)), dim3(256), 0, st,
                        weight_args_blocked(K, C, R, S, cb, depth, src, dst));
     return hipGetLastError();
@@ -482,11 +264,10 @@ __device__ __forceinline__ void pack_weights_rows_body(const WeightArgs &a, int 
     int8_t *__restrict__ dst = a.dst;
     const int K = a.K, CRS = a.C * a.R * a.S, depth = a.depth;
     const int chunks = depth / 16;
-    const long long total = (long long)K * chunks;
-    for (long long t = (long long)vbid * 256 + threadIdx.x; t < total; t += (long long)vgrid * 256) {
-        const int ch = (int)(t % chunks);
-        const long long k = t / chunks;
-        const int8_t *s = src + k * CRS + ch * 16;
+    const int total = K * chunks;  // < 2^31 (launcher-checked)
+    for (int t = vbid * 256 + (int)threadIdx.x; t < total; t += vgrid * 256) {
+        const int k = fast_div_any(t, chunks, a.m_chunks), ch = t - k * chunks;
+        const int8_t *s = src + (long long)k * CRS + ch * 16;
         int v[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) v[i] = (ch * 16 + i < CRS) ? s[i] : 0;
@@ -495,7 +276,7 @@ __device__ __forceinline__ void pack_weights_rows_body(const WeightArgs &a, int 
         o[1] = pack4(v[4], v[5], v[6], v[7]);
         o[2] = pack4(v[8], v[9], v[10], v[11]);
         o[3] = pack4(v[12], v[13], v[14], v[15]);
-        *reinterpret_cast<v4i *>(dst + k * depth + (long long)ch * 16) = o;
+        *reinterpret_cast<v4i *>(dst + (long long)k * depth + (long long)ch * 16) = o;
     }
 }
 
@@ -508,9 +289,10 @@ hipError_t launch_pack_weights_rows(int K, int CRS, int depth, const int8_t *src
                                     hipStream_t st)
 {
     const long long items = (long long)K * (depth / 16);
+    if (items >= (1LL << 31)) return hipErrorInvalidValue;
     // the row copy only needs the product C*R*S: pass it as C with R = S = 1
     hipLaunchKernelGGL(pack_weights_rows_kernel, dim3(grid_for(items, 256)), dim3(256), 0, st,
-                       WeightArgs{src, dst, K, CRS, 1, 1, 0, depth, 0});
+                       WeightArgs{src, dst, K, CRS, 1, 1, 0, depth, 0, magic_for(depth / 16), 0u, 0u});
     return hipGetLastError();
 }
 
@@ -826,7 +608,7 @@ __global__ void __launch_bounds__(256) rewrite_fused_kernel(const FusedArgs a)
             pack_layout_tiled_body(a.pk, lid, lds);
         }
     } else {
-        if (a.w_is_blocked) pack_weights_blocked_body(a.wt, bid - a.in_blocks, a.w_blocks);
+        if (a.w_is_blocked) pack_weights_blocked_body(a.wt, bid - a.in_blocks, a.w_blocks, 256);
         else pack_weights_rows_body(a.wt, bid - a.in_blocks, a.w_blocks);
     }
 }
@@ -843,7 +625,7 @@ hipError_t launch_rewrite_fused(bool im2col, int N, int C, int H, int W, int K, 
     if (im2col) {
         if (!plan_im2col_tiled(N, C, H, W, R, S, stride, pad, P, Q, depth, in, xq, &a.ic, &blocks, &lds))
             return hipErrorNotSupported;
-        a.wt = WeightArgs{wt, wq, K, C * R * S, 1, 1, 0, depth, 0};
+        a.wt = WeightArgs{wt, wq, K, C * R * S, 1, 1, 0, depth, 0, magic_for(depth / 16), 0u, 0u};
     } else {
         if (plan_pack_wave(N, C, H, W, cb, pad, in, xq, &a.pw, &blocks)) {
             a.in_is_wave = 1;
@@ -854,6 +636,7 @@ hipError_t launch_rewrite_fused(bool im2col, int N, int C, int H, int W, int K, 
         a.wt = weight_args_blocked(K, C, R, S, cb, depth, wt, wq);
     }
     const long long w_items = (long long)K * (depth / 16);
+    if (w_items >= (1LL << 31)) return hipErrorNotSupported;
     a.in_blocks = (int)blocks;
     a.w_blocks = grid_for(w_items, 256);
     a.in_is_im2col = im2col;

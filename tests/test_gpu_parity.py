@@ -292,3 +292,46 @@ def test_batch_scaled_layout_kernels_sampled_images(lib):
     for n in _sample_images(cfg.N):
         want = layouts.im2col(host(x[n:n + 1]), cfg.R, cfg.S, cfg.stride, cfg.pad)
         assert np.array_equal(host(a[n * per:(n + 1) * per]), want), n
+
+
+# ---- the one-shot path called repeatedly and under graph replay ------------------------------------
+def test_one_shot_back_to_back_and_mixed_shapes(lib):
+    """Consecutive one-shot calls share the library's cached workspace: alternate shapes and layouts,
+    twice over, and check every result afterwards."""
+    names = ["C4a", "C2", "C1", "C4b", "C3", "C4a", "C4b", "C2"]
+    data = {n: oracle_conv(CONFIGS[n]) for n in set(names)}
+    dev_in = {n: (dev(data[n][0]), dev(data[n][1])) for n in data}
+    outs = []
+    for _ in range(2):
+        for n in names:
+            cfg = CONFIGS[n]
+            outs.append((n, lib.conv2d_int8(dev_in[n][0], dev_in[n][1], cfg.stride, cfg.pad)))
+    for n, o in outs:
+        assert np.array_equal(host(o), data[n][2]), n
+
+
+def test_one_shot_graph_replay(lib):
+    """The benchmark replays captured one-shot calls: every replay must give the eager result, also with
+    other work of the process in between."""
+    cfgs = [CONFIGS["C4a"], CONFIGS["C4b"], CONFIGS["C2"]]
+    data = [oracle_conv(c) for c in cfgs]
+    ins = [(dev(x), dev(w)) for x, w, _ in data]
+    outs = [torch.empty((c.N, c.K, c.P, c.Q), dtype=torch.int32, device=DEV) for c in cfgs]
+    for c, (x, w), o in zip(cfgs, ins, outs):
+        lib.conv2d_int8(x, w, c.stride, c.pad, out=o)       # eager first: sizes the cached workspace
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(3):
+            for c, (x, w), o in zip(cfgs, ins, outs):
+                lib.conv2d_int8(x, w, c.stride, c.pad, out=o)
+    for rep in range(4):
+        for o in outs:
+            o.fill_(-1)
+        g.replay()
+        torch.cuda.synchronize()
+        for (x, w, want), o in zip(data, outs):
+            assert np.array_equal(o.cpu().numpy(), want), rep
+        # eager work between replays, through the same path
+        e = lib.conv2d_int8(ins[0][0], ins[0][1], cfgs[0].stride, cfgs[0].pad)
+        assert np.array_equal(host(e), data[0][2])
