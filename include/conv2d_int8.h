@@ -95,9 +95,12 @@ int conv2d_int8_packed(const conv_desc_t *desc, int layout, int cb,
 int conv2d_int8_query_tiling(const conv_desc_t *desc, int layout, int cb, int *tile, int *split_k);
 int conv2d_int8_num_tiles(void);
 /* Describes tile `tile`: rows = output channels, cols = output pixels per workgroup;
- * steps = 64-byte depth steps per pipeline stage (a tile with steps = 2 only runs problems
- * whose depth slices hold an even number of steps; otherwise CONV_ERR_UNSUPPORTED). */
+ * steps = 64-byte depth steps per pipeline stage (a tile only runs problems whose depth
+ * slices hold a whole number of stages; otherwise CONV_ERR_UNSUPPORTED). */
 int conv2d_int8_tile_info(int tile, int *rows, int *cols, int *threads, int *steps);
+/* Would conv2d_int8_packed accept this forced tile (>= 0) and split_k (>= 1) for this
+ * problem?  CONV_OK or CONV_ERR_UNSUPPORTED (host only). */
+int conv2d_int8_tile_applies(const conv_desc_t *desc, int layout, int cb, int tile, int split_k);
 
 /* ---- layout rewrites, individually callable (the "Transf." column of Table 3) ---------
  * pack_layout (Table 2 rows 2-4 on the input, plus the convolution's zero border):

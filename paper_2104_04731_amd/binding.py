@@ -19,7 +19,8 @@ LAYOUT_NAMES = {LAYOUT_AUTO: "auto", LAYOUT_PACKED: "packed", LAYOUT_IM2COL: "im
 
 EXPORTS = [
     "conv2d_int8", "conv2d_int8_ex", "conv2d_int8_workspace_bytes", "conv2d_int8_packed",
-    "conv2d_int8_query_tiling", "conv2d_int8_num_tiles", "conv2d_int8_tile_info", "pack_layout", "pack_layout_bytes",
+    "conv2d_int8_query_tiling", "conv2d_int8_num_tiles", "conv2d_int8_tile_info",
+    "conv2d_int8_tile_applies", "pack_layout", "pack_layout_bytes",
     "pack_weights", "pack_weights_depth", "pack_weights_bytes", "im2col_int8", "im2col_bytes",
     "gemm_int8_nt", "select_layout", "select_layout_weighted", "layout_overheads",
     "conv_status_string",
@@ -57,6 +58,7 @@ def load(path: str | None = None):
         "conv2d_int8_workspace_bytes": (sz, [dp, i, i, i]),
         "conv2d_int8_packed": (i, [dp, i, i, vp, vp, vp, i, i, vp]),
         "conv2d_int8_query_tiling": (i, [dp, i, i, ip, ip]),
+        "conv2d_int8_tile_applies": (i, [dp, i, i, i, i]),
         "conv2d_int8_num_tiles": (i, []),
         "conv2d_int8_tile_info": (i, [i, ip, ip, ip, ip]),
         "pack_layout": (i, [i] * 6 + [vp, vp, vp]),
@@ -143,6 +145,12 @@ def conv2d_int8_packed(dims, layout, cb, x_packed, w_packed, out, tile=-1, split
     _check(load().conv2d_int8_packed(ctypes.byref(d), layout, cb, _ptr(x_packed), _ptr(w_packed),
                                      _ptr(out), tile, split_k, _stream(stream)), "conv2d_int8_packed")
     return out
+
+
+def tile_applies(dims, layout, cb, tile, split_k=1):
+    """True if conv2d_int8_packed would accept this forced tile and depth split."""
+    d = _desc(*dims)
+    return load().conv2d_int8_tile_applies(ctypes.byref(d), layout, cb, tile, split_k) == OK
 
 
 def query_tiling(dims, layout, cb):

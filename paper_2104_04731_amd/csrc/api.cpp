@@ -301,6 +301,17 @@ int conv2d_int8_query_tiling(const conv_desc_t *desc, int layout, int cb, int *t
     return CONV_OK;
 }
 
+int conv2d_int8_tile_applies(const conv_desc_t *desc, int layout, int cb, int tile, int split_k)
+{
+    if (layout == CONV_LAYOUT_AUTO || tile < 0 || tile >= gemm_num_tiles() || split_k < 1)
+        return CONV_ERR_INVALID_ARG;
+    Plan pl;
+    int rc = make_plan(desc, layout, cb, &pl);
+    if (rc != CONV_OK) return rc;
+    int t = tile, s = split_k;
+    return gemm_pick(gemm_problem(desc, pl, nullptr, nullptr, nullptr), &t, &s) ? CONV_OK : CONV_ERR_UNSUPPORTED;
+}
+
 size_t conv2d_int8_workspace_bytes(const conv_desc_t *desc, int layout, int cb, int wt_is_packed)
 {
     Plan pl;

@@ -120,11 +120,12 @@ __device__ __forceinline__ void igemm_body(const GemmArgs &a, int block_id, int 
     constexpr int L = LW + LA;
     constexpr int WBYTES = TK * RP, STAGE = (TK + TM) * RP;
     constexpr int NH = 2 * KS;  // 32-deep halves per stage
-    static_assert(KS == 1 || KS == 2, "64 or 128 bytes of depth per stage");
+    static_assert(KS == 1 || KS == 2 || KS == 4, "64, 128 or 256 bytes of depth per stage");
     static_assert(DS == 1 || (DS == 2 && (TK / WK / 32) * (TM / WM / 32) <= 2), "depth groups: small wave tiles only");
     static_assert(WTK % 32 == 0 && WTM % 32 == 0, "wave tile is made of 32x32 MFMA blocks");
     static_assert((TK / RPI) % NW == 0 && (TM / RPI) % NW == 0, "transfers divide evenly over waves");
-    static_assert(KS == 1 || NW % 2 == 0, "row swizzle of a transfer must not depend on its slot");
+    static_assert(KS == 1 || (KS == 2 && NW % 2 == 0) || (KS == 4 && NW % 4 == 0),
+                  "row swizzle of a transfer must not depend on its slot");
     static_assert(NSTAGE >= 2 && (NSTAGE - 1) * L <= 63, "vmcnt is a 6-bit counter");
 
     int *koff = reinterpret_cast<int *>(smem + NSTAGE * STAGE);
@@ -172,11 +173,12 @@ __device__ __forceinline__ void igemm_body(const GemmArgs &a, int block_id, int 
     // Transfer slots.  Slot i of this wave moves rows g*RPI .. g*RPI+RPI-1 (g = i*NW + wave)
     // of the weight (or activation) tile.  Lane l fetches row g*RPI + l/LPR and lands at 16-byte
     // position l%LPR of that row in LDS; the chunk it fetches is that position XOR a few row
-    // bits (KS = 1: (row/4)%4, KS = 2: (row/2)%8), which is what spreads the later column-wise
-    // MFMA operand reads over all LDS banks.
+    // bits (KS = 1: (row/4)%4, KS = 2: (row/2)%8, KS = 4: row%16), which is what spreads the later
+    // column-wise MFMA operand reads over all LDS banks.
     const int lrow = lane / LPR;
-    const int x = KS == 1 ? ((lane & 3) ^ ((lane >> 4) & 3))
-                          : ((lane & 7) ^ (((wave & 1) << 2) | (lane >> 4)));
+    const int x = KS == 1   ? ((lane & 3) ^ ((lane >> 4) & 3))
+                  : KS == 2 ? ((lane & 7) ^ (((wave & 1) << 2) | (lane >> 4)))
+                            : ((lane & 15) ^ (((wave & 3) << 2) | (lane >> 4)));
     const int8_t *wsrc[LW];
     const int8_t *asrc[LA];
 #pragma unroll
@@ -257,7 +259,7 @@ __device__ __forceinline__ void igemm_body(const GemmArgs &a, int block_id, int 
 
     // MFMA operand reads: lane l takes row (l%32) of a 32-row block; half h of a stage is
     // chunk 4*(h/2) + 2*(h%2) + l/32 of that row, at its swizzled position.
-    const int rswz = KS == 1 ? ((lane >> 2) & 3) : ((lane >> 1) & 7);
+    const int rswz = KS == 1 ? ((lane >> 2) & 3) : KS == 2 ? ((lane >> 1) & 7) : (lane & 15);
     const int wrow = (wk * WTK + (lane & 31)) * RP;
     const int arow = WBYTES + (wm * WTM + (lane & 31)) * RP;
     int coff[NH];
@@ -595,6 +597,10 @@ static const TileDef kTiles[] = {
     {256, 256, 2, 4, 1, 4, 0, 1, 1},  // 38
     {256, 256, 4, 2, 1, 4, 0, 1, 1},  // 39
     {256, 256, 2, 4, 1, 3, 0, 1, 1},  // 40
+    {64, 64, 2, 2, 4, 4, 4, 1, 1},  // 41
+    {64, 64, 2, 2, 4, 4, 0, 2, 1},  // 42
+    {64, 64, 2, 2, 4, 3, 4, 1, 1},  // 43
+    {64, 64, 2, 2, 4, 4, 0, 1, 1},  // 44
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
@@ -628,10 +634,11 @@ static hipError_t launch_tile(const GemmArgs &a, int mode, hipStream_t st)
 
 static int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// A tile with 128-byte stages walks the depth two steps at a time: every slice must be even.
+// A tile with 128- or 256-byte stages walks the depth two or four steps at a time: every slice
+// must be a whole number of stages.
 static bool tile_fits(const TileDef &d, int ksteps, int per)
 {
-    return d.ks == 1 || (ksteps % 2 == 0 && per % 2 == 0);
+    return d.ks == 1 || (ksteps % d.ks == 0 && per % d.ks == 0);
 }
 
 // Per-launch time model (core cycles) used to pick a tile and a depth split.  Its constants
@@ -662,7 +669,7 @@ bool gemm_pick(const GemmProblem &g, int *tile, int *split_k)
         if (cap < 1) cap = 1;
         const double mfma = (double)d.tk * d.tm * 64 / 4096.0 / 0.6;
         const double bytes = (double)(d.tk + d.tm) * 64;
-        const double lat = d.ks == 2 ? 180.0 : 350.0;
+        const double lat = d.ks == 1 ? 350.0 : 360.0 / d.ks;  // barrier-to-barrier chain, per 64-deep step
         const int forced[] = {*split_k > ksteps ? ksteps : *split_k};
         const int *cand = *split_k > 0 ? forced : splits;
         const int ncand = *split_k > 0 ? 1 : (int)(sizeof(splits) / sizeof(splits[0]));
@@ -675,8 +682,8 @@ bool gemm_pick(const GemmProblem &g, int *tile, int *split_k)
             const double wgs = tiles * s;
             int res = (int)((wgs + 255) / 256);  // workgroups sharing a CU
             if (res > cap) res = cap;
-            double dma = (d.ks == 2 ? 5.5 : 6.5) * waves * res;
-            const double dma_max = d.ks == 2 ? 44.0 : 38.0;
+            double dma = (d.ks >= 2 ? 5.5 : 6.5) * waves * res;
+            const double dma_max = d.ks >= 2 ? 44.0 : 38.0;
             if (dma > dma_max) dma = dma_max;
             double step = lat;
             if (res * mfma > step) step = res * mfma;
@@ -813,6 +820,10 @@ hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t 
         case 38: return launch_tile<256, 256, 2, 4, 1, 4, 0, 1, 1>(a, g.mode, st);
         case 39: return launch_tile<256, 256, 4, 2, 1, 4, 0, 1, 1>(a, g.mode, st);
         case 40: return launch_tile<256, 256, 2, 4, 1, 3, 0, 1, 1>(a, g.mode, st);
+        case 41: return launch_tile<64, 64, 2, 2, 4, 4, 4, 1, 1>(a, g.mode, st);
+        case 42: return launch_tile<64, 64, 2, 2, 4, 4, 0, 2, 1>(a, g.mode, st);
+        case 43: return launch_tile<64, 64, 2, 2, 4, 3, 4, 1, 1>(a, g.mode, st);
+        case 44: return launch_tile<64, 64, 2, 2, 4, 4, 0, 1, 1>(a, g.mode, st);
     }
     return hipErrorInvalidValue;
 }

@@ -99,4 +99,4 @@ def test_ex_and_packed_validation(lib):
     assert lib.num_tiles() >= 4
     for t in range(lib.num_tiles()):
         r, c, th, steps = lib.tile_info(t)
-        assert r % 32 == 0 and c % 32 == 0 and th % 64 == 0 and steps in (1, 2)
+        assert r % 32 == 0 and c % 32 == 0 and th % 64 == 0 and steps in (1, 2, 4)

@@ -123,7 +123,9 @@ def test_gemm_every_tile_and_split(lib):
             for split in splits:
                 out = torch.full((1, X, 1, Y), -7, dtype=torch.int32, device=DEV)
                 per = -(-(Z // 64) // split)
-                runnable = steps == 1 or ((Z // 64) % 2 == 0 and per % 2 == 0)
+                rule = (Z // 64) % steps == 0 and per % steps == 0   # whole stages per slice
+                runnable = lib.tile_applies(cfg.dims(), lib.LAYOUT_IM2COL, 0, tile, split)
+                assert runnable == rule
                 # a row-major [Y][Z] matrix is the im2col operand of a 1x1 convolution over Y pixels
                 if not runnable:
                     with pytest.raises(lib.ConvError) as e:
@@ -178,10 +180,34 @@ def test_conv_every_tile_and_split(lib, name):
         steps = lib.tile_info(tile)[3]
         for split in (1, 3, 4):
             per = -(-ksteps // split)
-            if steps == 2 and (ksteps % 2 or per % 2):
+            if ksteps % steps or per % steps:
                 continue  # rejected combination, covered by test_gemm_every_tile_and_split
+            assert lib.tile_applies(cfg.dims(), lib.LAYOUT_PACKED, 64, tile, split)
             got = run_layout(lib, cfg, x, w, "packed", 64, tile=tile, split_k=split)
             assert np.array_equal(got, want), f"tile {tile} split {split}"
+
+
+BLOCK64 = [
+    ConvShape("k-tail", 3, 128, 9, 9, 70, 3, 3, 1, 1), ConvShape("5x5-stride2", 1, 128, 13, 11, 64, 5, 5, 2, 2),
+    ConvShape("1x5", 2, 128, 6, 20, 33, 1, 5, 1, 0), ConvShape("3x3-odd-blocks", 2, 192, 7, 7, 64, 3, 3, 1, 1),
+    ConvShape("two-images-per-tile", 9, 64, 5, 5, 40, 2, 3, 1, 1), ConvShape("too-wide", 1, 128, 4, 140, 64, 3, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("cfg", BLOCK64, ids=lambda c: c.name)
+def test_conv_every_applicable_tile_64_channel_blocks(lib, cfg):
+    """Every tile that accepts the problem, on small 64-channel-block shapes: ragged output channels
+    and pixels, strides, tiles crossing image boundaries, odd and even step counts, one wide row."""
+    x = uniform_int8(311, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(312, (cfg.K, cfg.C, cfg.R, cfg.S))
+    want = direct.conv2d_int8(x, w, cfg.stride, cfg.pad)
+    ran = 0
+    for tile in range(lib.num_tiles()):
+        if not lib.tile_applies(cfg.dims(), lib.LAYOUT_PACKED, 64, tile, 1):
+            continue
+        ran += 1
+        got = run_layout(lib, cfg, x, w, "packed", 64, tile=tile, split_k=1)
+        assert np.array_equal(got, want), f"tile {tile}: {np.count_nonzero(got != want)} mismatches"
+    assert ran >= 10
 
 
 @pytest.mark.parametrize("cfg", PAPER_SHAPES, ids=lambda c: c.name)
