@@ -114,7 +114,10 @@ def main():
             self.out = torch.empty((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=dev)
             self.layout, self.cb, _ = lib.select_layout(cfg.dims())
             self.tile, self.split = lib.query_tiling(cfg.dims(), self.layout, self.cb)
-            if self.layout == lib.LAYOUT_IM2COL:
+            if self.layout == lib.LAYOUT_IMPLICIT:   # no input rewrite exists: the GEMM stage reads NCHW
+                self.xp = self.x
+                self.rewrite = None
+            elif self.layout == lib.LAYOUT_IM2COL:
                 self.xp = lib.im2col_int8(self.x, cfg.R, cfg.S, cfg.stride, cfg.pad)
                 self.rewrite = lambda: lib.im2col_int8(self.x, cfg.R, cfg.S, cfg.stride, cfg.pad, out=self.xp)
             else:
@@ -124,25 +127,25 @@ def main():
             self.rewrite_w = lambda: lib.pack_weights(self.w, self.layout, self.cb, out=self.wp)
             self.op = lambda: lib.conv2d_int8_packed(cfg.dims(), self.layout, self.cb, self.xp, self.wp, self.out)
             self.combined = lambda: lib.conv2d_int8(self.x, self.w, cfg.stride, cfg.pad, out=self.out)
-            self.rewrite_bytes = self.x.numel() + self.xp.numel()   # read once + written once
+            self.rewrite_bytes = self.x.numel() + self.xp.numel() if self.rewrite else 0   # read once + written once
 
         def report(self, steps, warmup):
             cfg = self.cfg
             _, op = timed(self.op, steps, warmup)
-            _, tr = timed(self.rewrite, steps, warmup)
+            tr = timed(self.rewrite, steps, warmup)[1] if self.rewrite else None
             _, trw = timed(self.rewrite_w, steps, warmup)
             wall, comb = timed(self.combined, steps, warmup)
-            rows, cols = lib.tile_info(self.tile)[:2]
+            rows, cols = lib.tile_info(self.tile)[:2] if self.tile >= 0 else (min(64, -(-cfg.K // 32) * 32), 128)
             return {
                 "name": cfg.name, "layout": lib.LAYOUT_NAMES[self.layout], "cb": self.cb,
                 "tile": f"{rows}x{cols}", "split_k": self.split, "ops": cfg.ops,
-                "op_us": round(op * 1e3, 3), "transf_in_us": round(tr * 1e3, 3),
+                "op_us": round(op * 1e3, 3), "transf_in_us": round(tr * 1e3, 3) if tr else None,
                 "transf_wt_us": round(trw * 1e3, 3), "combined_us": round(comb * 1e3, 3),
                 "tops_op": round(cfg.ops / (op * 1e-3) / 1e12, 3),
                 "tops_combined": round(cfg.ops / (comb * 1e-3) / 1e12, 3),
                 "pct_mfma_peak_op": round(100 * cfg.ops / (op * 1e-3) / PEAK_INT8_OPS, 3),
-                "transf_in_GBps": round(self.rewrite_bytes / (tr * 1e-3) / 1e9, 1),
-                "pct_hbm_peak_transf": round(100 * self.rewrite_bytes / (tr * 1e-3) / PEAK_HBM_BPS, 2),
+                "transf_in_GBps": round(self.rewrite_bytes / (tr * 1e-3) / 1e9, 1) if tr else None,
+                "pct_hbm_peak_transf": round(100 * self.rewrite_bytes / (tr * 1e-3) / PEAK_HBM_BPS, 2) if tr else None,
             }
 
     if args.calibration_copy:

@@ -51,7 +51,15 @@ typedef enum {
     CONV_LAYOUT_AUTO = 0,     /* let select_layout decide */
     CONV_LAYOUT_PACKED = 1,   /* Pad + Split + Reorder: [N][ceil(C/cb)][H+2pad][W+2pad][cb] */
     CONV_LAYOUT_IM2COL = 2,   /* Stencil Unroll + Fuse: [N*P*Q][depth], depth index (c,r,s) */
-    CONV_LAYOUT_PAD_ONLY = 3  /* Pad only: one block cb = ceil(C,16), i.e. [N][H+2pad][W+2pad][cb] */
+    CONV_LAYOUT_PAD_ONLY = 3, /* Pad only: one block cb = ceil(C,16), i.e. [N][H+2pad][W+2pad][cb] */
+    CONV_LAYOUT_IMPLICIT = 4  /* Stencil Unroll + Fuse applied inside the GEMM stage: the input stays NCHW,
+                                 nothing rewritten is stored; depth index (c, r, s) with every kernel row
+                                 padded to S4 = ceil(S,4) taps.  Exists for the low-channel layers whose
+                                 unrolled matrix is many times the input (Sec. 6.2); applies when
+                                 ceil(C*R*S4, 64) <= 256, W >= 4 and the input window of one tile --
+                                 C*((PT-1)*stride + R) rows of ceil((QT-1)*stride + S4 + 3, 4) bytes, with
+                                 PT x QT = 1x128 output pixels if Q > 64, 2x64 if Q > 32, else 4x32 --
+                                 fits 40 KB; otherwise CONV_ERR_UNSUPPORTED. */
 } conv_layout_t;
 
 typedef struct {
@@ -65,7 +73,8 @@ typedef struct {
 /* ---- one-shot convolution (layout rewrite of input and weights + GEMM stage) ---------
  * Picks the layout with select_layout, uses a workspace the library caches per device
  * (grown with hipMalloc when a larger problem arrives, never shrunk: make the first call for
- * a problem size outside stream capture).  Two launches: both rewrites, then the GEMM stage. */
+ * a problem size outside stream capture).  Two launches: both rewrites, then the GEMM stage;
+ * one launch and no workspace when the choice is IMPLICIT. */
 int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                 const int8_t *in, const int8_t *wt, int32_t *out, void *stream);
 
@@ -75,23 +84,26 @@ int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int
  * wt: KCRS weights, or -- if wt_is_packed != 0 -- the output of pack_weights for the
  * same layout/cb.  workspace: device memory of at least
  * conv2d_int8_workspace_bytes(desc, layout, cb, wt_is_packed) bytes, 256-byte aligned,
- * caller-owned, free to reuse once the stream has passed this call. */
+ * caller-owned, free to reuse once the stream has passed this call (may be NULL when that
+ * size is 0, as it is for IMPLICIT, which reads `in` and either form of `wt` directly). */
 int conv2d_int8_ex(const conv_desc_t *desc, int layout, int cb,
                    const int8_t *in, const int8_t *wt, int wt_is_packed, int32_t *out,
                    void *workspace, size_t workspace_bytes, void *stream);
 size_t conv2d_int8_workspace_bytes(const conv_desc_t *desc, int layout, int cb, int wt_is_packed);
 
 /* ---- GEMM stage alone (operands already rewritten; the "Op." column of Table 3) -------
- * in_packed: output of pack_layout (PACKED / PAD_ONLY) or im2col_int8 (IM2COL);
- * wt_packed: output of pack_weights.  layout must not be AUTO; cb as above (0 = 64 if
+ * in_packed: output of pack_layout (PACKED / PAD_ONLY) or im2col_int8 (IM2COL), or the NCHW
+ * input itself (IMPLICIT); wt_packed: output of pack_weights.  layout must not be AUTO; cb as above (0 = 64 if
  * C >= 64 else ceil(C,16) rounded to 16/32/64).
  * tile: -1 = automatic, else an index < conv2d_int8_num_tiles() (for tuning sweeps);
  * split_k: 0 = automatic, else the number of depth slices (>= 2 accumulates with int32
- * atomics after clearing `out`; exact, because integer addition is associative). */
+ * atomics after clearing `out`; exact, because integer addition is associative).
+ * IMPLICIT has one kernel shape per problem: tile must be -1 and split_k 0 or 1. */
 int conv2d_int8_packed(const conv_desc_t *desc, int layout, int cb,
                        const int8_t *in_packed, const int8_t *wt_packed, int32_t *out,
                        int tile, int split_k, void *stream);
-/* The tile and depth split the library would pick for this problem (host only). */
+/* The tile and depth split the library would pick for this problem (host only);
+ * tile = -1, split_k = 1 for IMPLICIT. */
 int conv2d_int8_query_tiling(const conv_desc_t *desc, int layout, int cb, int *tile, int *split_k);
 int conv2d_int8_num_tiles(void);
 /* Describes tile `tile`: rows = output channels, cols = output pixels per workgroup;
@@ -114,7 +126,8 @@ size_t pack_layout_bytes(int N, int C, int H, int W, int cb, int pad);
  *   dst[k][j], row length depth = pack_weights_depth(...), zero where no weight maps.
  *   PACKED / PAD_ONLY: j = ((c/cb * R + r) * S + s) * cb + c%cb   (cb a multiple of 16;
  *                      PAD_ONLY forces cb = ceil(C,16))
- *   IM2COL:            j = (c*R + r)*S + s */
+ *   IM2COL:            j = (c*R + r)*S + s
+ *   IMPLICIT:          j = (c*R + r)*S4 + s,  S4 = ceil(S,4) */
 int pack_weights(int K, int C, int R, int S, int layout, int cb,
                  const int8_t *src, int8_t *dst, void *stream);
 int pack_weights_depth(int C, int R, int S, int layout, int cb);
@@ -137,7 +150,9 @@ int gemm_int8_nt(int X, int Y, int Z, const int8_t *A, const int8_t *B, int32_t 
  * score = w_mac * O_MAC + w_data * O_Data, O_MAC = MAC_total - MAC_min (MACs issued after
  * padding every mapped dimension to the intrinsic minus the MACs of the definition),
  * O_Data = elements moved by rewrites and GEMM stage minus |in| + |wt| + |out|.
- * Candidates: PACKED with cb in {64,32,16}, IM2COL, PAD_ONLY.  Ties: fewer rewritten
+ * Candidates: PACKED with cb in {64,32,16}, IM2COL, PAD_ONLY, and IMPLICIT where it applies
+ * (no rewritten elements, O_Data = 0; MAC_total = N*P*ceil(Q,32) * ceil(K,32) * ceil(C*R*S4,64):
+ * pixels are padded per output row, kernel rows to S4).  Ties: fewer rewritten
  * elements, then lower layout code, then larger cb.  select_layout uses the library's
  * MI355X weights (seconds per MAC and per byte); the paper's case studies use w = [1,1]. */
 int select_layout(const conv_desc_t *desc, int *layout, int *cb, double *score);

@@ -8,7 +8,9 @@ numpy slicing; no blocking or fusion beyond what the map itself states.
                 a multiple of the block, split, and the block moved innermost);
                 the spatial zero border of the convolution is materialised too.
   pack_weights  the same rewrites on the weights, then Fuse (Table 2 row 5) of the
-                reduction dimensions into one GEMM depth, zero-padded to `kalign`.
+                reduction dimensions into one GEMM depth, zero-padded to `kalign`
+                (for the stencil unroll done inside the GEMM stage: every kernel row
+                first padded to a multiple of four taps).
   im2col        Stencil Unroll + Fuse (Table 2 rows 1 and 5; "im2col" in Sec. 6.2).
   gemm_nt       the matrix unit of Sec. 5.1: C[x][y] += sum_z A[x][z] * B[y][z].
 """
@@ -53,6 +55,17 @@ def pack_weights_im2col(w: np.ndarray, kalign: int = 64) -> np.ndarray:
     y = np.zeros((K, ceil_to(C * R * S, kalign)), dtype=w.dtype)
     y[:, :C * R * S] = w.reshape(K, C * R * S)
     return y
+
+
+def pack_weights_implicit(w: np.ndarray, kalign: int = 64) -> np.ndarray:
+    """[K,C,R,S] -> [K, depth]; depth index j = (c*R + r)*S4 + s with S4 = ceil(S,4), zero-padded."""
+    K, C, R, S = w.shape
+    S4 = ceil_to(S, 4)
+    y = np.zeros((K, C * R, S4), dtype=w.dtype)
+    y[:, :, :S] = w.reshape(K, C * R, S)
+    out = np.zeros((K, ceil_to(C * R * S4, kalign)), dtype=w.dtype)
+    out[:, :C * R * S4] = y.reshape(K, C * R * S4)
+    return out
 
 
 def im2col(x: np.ndarray, R: int, S: int, stride: int, pad: int,

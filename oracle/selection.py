@@ -15,11 +15,19 @@ Reading of the terms (the paper gives only their names):
                (|in| + |X'|) + (|wt| + |W'|) + (|X'| + |W'| + |out|)
                with X' the rewritten input and W' the rewritten weights.
 Candidates: channel blocks cb in {16,32,64} (pad + split + reorder), a single padded
-block cb = ceil(C,16) (pad only), and stencil unroll (im2col).
+block cb = ceil(C,16) (pad only), stencil unroll (im2col), and stencil unroll done inside
+the GEMM stage (implicit): nothing is rewritten, so X' = in and W' = wt are read once and
+O_Data = 0; the unit's pixel extent is filled from one output row at a time and every
+kernel row is padded to whole dwords, S4 = ceil(S,4):
+               MAC_total = N*P*ceil(Q,x) * ceil(K,y) * ceil(C*R*S4, z).
+It is a candidate only inside the domain the interface states for it: padded depth at
+most 256, W >= 4, and the input window of one tile -- C*((PT-1)*stride + R) rows of
+ceil((QT-1)*stride + S4 + 3, 4) bytes, PT x QT = 1x128 if Q > 64, 2x64 if Q > 32, else
+4x32 -- within 40 KB.
 """
 from __future__ import annotations
 
-PACKED, IM2COL, PAD_ONLY = 1, 2, 3
+PACKED, IM2COL, PAD_ONLY, IMPLICIT = 1, 2, 3, 4
 UNIT_X, UNIT_Y, UNIT_Z = 32, 32, 64  # pixels, output channels, depth
 
 
@@ -27,10 +35,23 @@ def _ceil(x, m):
     return -(-x // m) * m
 
 
-def candidates(C):
+def implicit_applies(N, C, H, W, K, R, S, stride, pad):
+    Q = (W + 2 * pad - S) // stride + 1
+    S4 = _ceil(S, 4)
+    if _ceil(C * R * S4, UNIT_Z) > 256 or W < 4:
+        return False
+    PT, QT = (1, 128) if Q > 64 else (2, 64) if Q > 32 else (4, 32)
+    rows = (PT - 1) * stride + R
+    row_bytes = _ceil((QT - 1) * stride + S4 + 3, 4)
+    return max(rows, row_bytes, C * rows * row_bytes) <= 40 * 1024
+
+
+def candidates(C, dims=None):
     out = [(PACKED, cb) for cb in (64, 32, 16)]
     out.append((IM2COL, 0))
     out.append((PAD_ONLY, _ceil(C, 16)))
+    if dims is not None and implicit_applies(*dims):
+        out.append((IMPLICIT, 0))
     return out
 
 
@@ -39,6 +60,9 @@ def overheads(N, C, H, W, K, R, S, stride, pad, layout, cb):
     Q = (W + 2 * pad - S) // stride + 1
     M = N * P * Q
     mac_min = M * K * C * R * S
+    if layout == IMPLICIT:
+        depth = _ceil(C * R * _ceil(S, 4), UNIT_Z)
+        return N * P * _ceil(Q, UNIT_X) * _ceil(K, UNIT_Y) * depth - mac_min, 0, 0
     if layout == IM2COL:
         depth = _ceil(C * R * S, UNIT_Z)
         x_elems = M * depth
@@ -58,7 +82,7 @@ def select(N, C, H, W, K, R, S, stride, pad, w_mac, w_data):
 
     Ties: fewer rewritten elements, then lower layout code, then larger block."""
     best = None
-    for layout, cb in candidates(C):
+    for layout, cb in candidates(C, (N, C, H, W, K, R, S, stride, pad)):
         o_mac, o_data, ws = overheads(N, C, H, W, K, R, S, stride, pad, layout, cb)
         score = w_mac * o_mac + w_data * o_data
         key = (score, ws, layout, -cb)

@@ -13,9 +13,9 @@ import torch
 from . import build as _build
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_OVERFLOW_RISK, ERR_WORKSPACE, ERR_DEVICE = range(6)
-LAYOUT_AUTO, LAYOUT_PACKED, LAYOUT_IM2COL, LAYOUT_PAD_ONLY = range(4)
+LAYOUT_AUTO, LAYOUT_PACKED, LAYOUT_IM2COL, LAYOUT_PAD_ONLY, LAYOUT_IMPLICIT = range(5)
 LAYOUT_NAMES = {LAYOUT_AUTO: "auto", LAYOUT_PACKED: "packed", LAYOUT_IM2COL: "im2col",
-                LAYOUT_PAD_ONLY: "pad_only"}
+                LAYOUT_PAD_ONLY: "pad_only", LAYOUT_IMPLICIT: "implicit"}
 
 EXPORTS = [
     "conv2d_int8", "conv2d_int8_ex", "conv2d_int8_workspace_bytes", "conv2d_int8_packed",
@@ -134,9 +134,10 @@ def conv2d_int8_workspace_bytes(dims, layout=LAYOUT_AUTO, cb=0, wt_is_packed=Fal
 
 def conv2d_int8_ex(dims, layout, cb, x, w, out, workspace, wt_is_packed=False, stream=None):
     d = _desc(*dims)
+    ws_ptr = _ptr(workspace) if workspace is not None else ctypes.c_void_p(0)
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(load().conv2d_int8_ex(ctypes.byref(d), layout, cb, _ptr(x), _ptr(w), int(wt_is_packed),
-                                 _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(),
-                                 _stream(stream)), "conv2d_int8_ex")
+                                 _ptr(out), ws_ptr, ws_bytes, _stream(stream)), "conv2d_int8_ex")
     return out
 
 

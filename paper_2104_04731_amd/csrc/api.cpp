@@ -38,6 +38,13 @@ struct Plan {
     size_t x_bytes, w_bytes;
 };
 
+WindowProblem window_problem(const conv_desc_t *d, const Plan &pl, const int8_t *x, const int8_t *w,
+                             int32_t *out, int wt_rewritten)
+{
+    return WindowProblem{x, w, out, d->N, d->C, d->H, d->W, d->K, pl.P, pl.Q, d->R, d->S, d->stride, d->pad,
+                         wt_rewritten};
+}
+
 int default_block(int C)
 {
     if (C >= 64) return 64;
@@ -59,7 +66,7 @@ int make_plan(const conv_desc_t *d, int layout, int cb, Plan *pl)
     else if (layout == CONV_LAYOUT_PACKED) {
         if (cb == 0) cb = default_block(d->C);
         if (cb < 16 || cb > 1024 || cb % 16) return CONV_ERR_UNSUPPORTED;
-    } else if (layout == CONV_LAYOUT_IM2COL) cb = 0;
+    } else if (layout == CONV_LAYOUT_IM2COL || layout == CONV_LAYOUT_IMPLICIT) cb = 0;
     else return CONV_ERR_INVALID_ARG;
 
     pl->layout = layout;
@@ -69,6 +76,14 @@ int make_plan(const conv_desc_t *d, int layout, int cb, Plan *pl)
     pl->P = (pl->Hp - d->R) / d->stride + 1;
     pl->Q = (pl->Wp - d->S) / d->stride + 1;
     pl->M = (long long)d->N * pl->P * pl->Q;
+    if (layout == CONV_LAYOUT_IMPLICIT) {
+        pl->Cb = 0;
+        pl->depth = window_depth(d->C, d->R, d->S);
+        if (!window_fits(window_problem(d, *pl, nullptr, nullptr, nullptr, 0))) return CONV_ERR_UNSUPPORTED;
+        pl->x_bytes = 0;  // nothing is rewritten: the GEMM stage reads the input and either weight form
+        pl->w_bytes = 0;
+        return CONV_OK;
+    }
     if (layout == CONV_LAYOUT_IM2COL) {
         pl->Cb = 0;
         pl->depth = round_up_i(d->C * d->R * d->S, CONV_DEPTH_ALIGN);
@@ -188,6 +203,7 @@ int pack_weights_depth(int C, int R, int S, int layout, int cb)
 {
     if (C <= 0 || R <= 0 || S <= 0) return 0;
     long long real;
+    if (layout == CONV_LAYOUT_IMPLICIT) return window_depth(C, R, S);
     if (layout == CONV_LAYOUT_IM2COL) real = (long long)C * R * S;
     else if (layout == CONV_LAYOUT_PACKED || layout == CONV_LAYOUT_PAD_ONLY) {
         if (layout == CONV_LAYOUT_PAD_ONLY) cb = round_up_i(C, 16);
@@ -208,14 +224,17 @@ int pack_weights(int K, int C, int R, int S, int layout, int cb, const int8_t *s
                  void *stream)
 {
     if (!src || !dst || K <= 0 || C <= 0 || R <= 0 || S <= 0) return CONV_ERR_INVALID_ARG;
-    if (layout != CONV_LAYOUT_IM2COL && layout != CONV_LAYOUT_PACKED && layout != CONV_LAYOUT_PAD_ONLY)
+    if (layout != CONV_LAYOUT_IM2COL && layout != CONV_LAYOUT_PACKED && layout != CONV_LAYOUT_PAD_ONLY &&
+        layout != CONV_LAYOUT_IMPLICIT)
         return CONV_ERR_INVALID_ARG;
     if (!aligned16(dst)) return CONV_ERR_INVALID_ARG;
     if (layout == CONV_LAYOUT_PAD_ONLY) cb = round_up_i(C, 16);
     const int depth = pack_weights_depth(C, R, S, layout, cb);
     if (depth == 0) return CONV_ERR_UNSUPPORTED;
     hipError_t e;
-    if (layout == CONV_LAYOUT_IM2COL)
+    if (layout == CONV_LAYOUT_IMPLICIT)
+        e = launch_pack_weights_window(K, C, R, S, src, dst, (hipStream_t)stream);
+    else if (layout == CONV_LAYOUT_IM2COL)
         e = launch_pack_weights_rows(K, C * R * S, depth, src, dst, (hipStream_t)stream);
     else
         e = launch_pack_weights_blocked(K, C, R, S, cb, depth, src, dst, (hipStream_t)stream);
@@ -282,6 +301,12 @@ int conv2d_int8_packed(const conv_desc_t *desc, int layout, int cb, const int8_t
     Plan pl;
     int rc = make_plan(desc, layout, cb, &pl);
     if (rc != CONV_OK) return rc;
+    if (pl.layout == CONV_LAYOUT_IMPLICIT) {
+        if (!in_packed || !wt_packed || !out) return CONV_ERR_INVALID_ARG;
+        if (tile != -1 || (split_k != 0 && split_k != 1)) return CONV_ERR_UNSUPPORTED;
+        return launch_window_conv(window_problem(desc, pl, in_packed, wt_packed, out, 1), (hipStream_t)stream) ==
+                       hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+    }
     if (!in_packed || !wt_packed || !out || !aligned16(in_packed) || !aligned16(wt_packed))
         return CONV_ERR_INVALID_ARG;
     return run_gemm(gemm_problem(desc, pl, in_packed, wt_packed, out), tile, split_k,
@@ -294,8 +319,8 @@ int conv2d_int8_query_tiling(const conv_desc_t *desc, int layout, int cb, int *t
     Plan pl;
     int rc = make_plan(desc, layout, cb, &pl);
     if (rc != CONV_OK) return rc;
-    int t = -1, s = 0;
-    gemm_pick(gemm_problem(desc, pl, nullptr, nullptr, nullptr), &t, &s);
+    int t = -1, s = pl.layout == CONV_LAYOUT_IMPLICIT ? 1 : 0;
+    if (pl.layout != CONV_LAYOUT_IMPLICIT) gemm_pick(gemm_problem(desc, pl, nullptr, nullptr, nullptr), &t, &s);
     *tile = t;
     *split_k = s;
     return CONV_OK;
@@ -308,6 +333,7 @@ int conv2d_int8_tile_applies(const conv_desc_t *desc, int layout, int cb, int ti
     Plan pl;
     int rc = make_plan(desc, layout, cb, &pl);
     if (rc != CONV_OK) return rc;
+    if (pl.layout == CONV_LAYOUT_IMPLICIT) return CONV_ERR_UNSUPPORTED;
     int t = tile, s = split_k;
     return gemm_pick(gemm_problem(desc, pl, nullptr, nullptr, nullptr), &t, &s) ? CONV_OK : CONV_ERR_UNSUPPORTED;
 }
@@ -326,7 +352,11 @@ int conv2d_int8_ex(const conv_desc_t *desc, int layout, int cb, const int8_t *in
     Plan pl;
     int rc = make_plan(desc, layout, cb, &pl);
     if (rc != CONV_OK) return rc;
-    if (!in || !wt || !out || !workspace) return CONV_ERR_INVALID_ARG;
+    if (!in || !wt || !out) return CONV_ERR_INVALID_ARG;
+    if (pl.layout == CONV_LAYOUT_IMPLICIT)
+        return launch_window_conv(window_problem(desc, pl, in, wt, out, wt_is_packed ? 1 : 0),
+                                  (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+    if (!workspace) return CONV_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(workspace) % WS_ALIGN) return CONV_ERR_INVALID_ARG;
     if (wt_is_packed && !aligned16(wt)) return CONV_ERR_INVALID_ARG;
     const size_t xb = align_up(pl.x_bytes, WS_ALIGN);
@@ -365,6 +395,7 @@ int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int
     int rc = make_plan(&d, CONV_LAYOUT_AUTO, 0, &pl);
     if (rc != CONV_OK) return rc;
     if (!in || !wt || !out) return CONV_ERR_INVALID_ARG;
+    if (pl.layout == CONV_LAYOUT_IMPLICIT) return conv2d_int8_ex(&d, pl.layout, 0, in, wt, 0, out, nullptr, 0, stream);
     const size_t need = align_up(pl.x_bytes, WS_ALIGN) + align_up(pl.w_bytes, WS_ALIGN);
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CONV_ERR_DEVICE;

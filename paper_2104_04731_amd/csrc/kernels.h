@@ -54,4 +54,17 @@ hipError_t launch_rewrite_fused(bool im2col, int N, int C, int H, int W, int K, 
                                 const int8_t *wt, int8_t *wq, hipStream_t st);
 hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t st);
 
+// GEMM stage that unrolls the stencil itself from the NCHW input (no rewritten activations).
+struct WindowProblem {
+    const int8_t *in;   // [N][C][H][W]
+    const int8_t *wt;   // KCRS, or (wt_rewritten) [K][depth] with depth index (c*R + r)*ceil(S,4) + s
+    int32_t *out;       // [N][K][P][Q]
+    int N, C, H, W, K, P, Q, R, S, stride, pad;
+    int wt_rewritten;
+};
+int window_depth(int C, int R, int S);          // 0 if the padded depth exceeds what the kernel unrolls
+bool window_fits(const WindowProblem &g);       // depth, image width and LDS window within the kernel's limits
+hipError_t launch_window_conv(const WindowProblem &g, hipStream_t st);
+hipError_t launch_pack_weights_window(int K, int C, int R, int S, const int8_t *src, int8_t *dst, hipStream_t st);
+
 }  // namespace c2i8

@@ -1,7 +1,9 @@
 // Per-shape layout selection: the candidate-selection term of Sec. 4.4 evaluated over the
 // handful of rewrites this library implements (Table 2), instead of over a solver's
-// candidate list.  Host arithmetic only.
+// candidate list.  Host arithmetic only (the one call into the kernel side asks whether the
+// stencil-unrolling GEMM stage takes the shape).
 #include "../../include/conv2d_int8.h"
+#include "kernels.h"
 
 #include <stdint.h>
 
@@ -26,16 +28,29 @@ extern "C" int layout_overheads(const conv_desc_t *d, int layout, int cb,
         d->S <= 0 || d->stride <= 0 || d->pad < 0 || d->R > d->H + 2 * d->pad ||
         d->S > d->W + 2 * d->pad)
         return CONV_ERR_INVALID_ARG;
+    const int64_t P = ((int64_t)d->H + 2 * (int64_t)d->pad - d->R) / d->stride + 1;
+    const int64_t Q = ((int64_t)d->W + 2 * (int64_t)d->pad - d->S) / d->stride + 1;
+    const int64_t M = (int64_t)d->N * P * Q;
+    const int64_t taps = (int64_t)d->R * d->S;
+    const int64_t mac_min = M * d->K * d->C * taps;
+    if (layout == CONV_LAYOUT_IMPLICIT) {
+        // nothing rewritten, nothing moved twice; pixels padded per output row, kernel rows to dwords
+        if (P > 2147483647LL || Q > 2147483647LL) return CONV_ERR_UNSUPPORTED;
+        const c2i8::WindowProblem g{nullptr, nullptr, nullptr, d->N, d->C, d->H, d->W, d->K, (int)P, (int)Q,
+                                    d->R, d->S, d->stride, d->pad, 0};
+        if (!c2i8::window_fits(g)) return CONV_ERR_UNSUPPORTED;
+        const int64_t depth = round_up((int64_t)d->C * d->R * round_up(d->S, 4), UNIT_DEPTH);
+        const int64_t mac_total = (int64_t)d->N * P * round_up(Q, UNIT_PIXELS) * round_up(d->K, UNIT_CHANNELS) * depth;
+        if (o_mac) *o_mac = mac_total - mac_min;
+        if (o_data) *o_data = 0;
+        if (rewritten) *rewritten = 0;
+        return CONV_OK;
+    }
     if (layout == CONV_LAYOUT_PAD_ONLY) cb = (int)round_up(d->C, 16);
     if (layout != CONV_LAYOUT_IM2COL && layout != CONV_LAYOUT_PACKED && layout != CONV_LAYOUT_PAD_ONLY)
         return CONV_ERR_INVALID_ARG;
     if (layout != CONV_LAYOUT_IM2COL && (cb <= 0 || cb % 16)) return CONV_ERR_INVALID_ARG;
 
-    const int64_t P = (d->H + 2 * d->pad - d->R) / d->stride + 1;
-    const int64_t Q = (d->W + 2 * d->pad - d->S) / d->stride + 1;
-    const int64_t M = (int64_t)d->N * P * Q;
-    const int64_t taps = (int64_t)d->R * d->S;
-    const int64_t mac_min = M * d->K * d->C * taps;
     int64_t depth, x_elems;
     if (layout == CONV_LAYOUT_IM2COL) {
         depth = round_up(d->C * taps, UNIT_DEPTH);
@@ -59,7 +74,7 @@ extern "C" int select_layout_weighted(const conv_desc_t *d, double w_mac, double
 {
     if (!d || !layout || !cb) return CONV_ERR_INVALID_ARG;
     const Cand cands[] = {{CONV_LAYOUT_PACKED, 64}, {CONV_LAYOUT_PACKED, 32}, {CONV_LAYOUT_PACKED, 16},
-                          {CONV_LAYOUT_IM2COL, 0},  {CONV_LAYOUT_PAD_ONLY, 0}};
+                          {CONV_LAYOUT_IM2COL, 0},  {CONV_LAYOUT_PAD_ONLY, 0},  {CONV_LAYOUT_IMPLICIT, 0}};
     bool have = false;
     double best_score = 0;
     int64_t best_ws = 0;
@@ -69,6 +84,7 @@ extern "C" int select_layout_weighted(const conv_desc_t *d, double w_mac, double
         if (c.layout == CONV_LAYOUT_PAD_ONLY) c.cb = (int)round_up(d->C, 16);
         int64_t om, od, ws;
         int rc = layout_overheads(d, c.layout, c.cb, &om, &od, &ws);
+        if (rc == CONV_ERR_UNSUPPORTED && c.layout == CONV_LAYOUT_IMPLICIT) continue;  // outside its domain
         if (rc != CONV_OK) return rc;
         const double sc = w_mac * (double)om + w_data * (double)od;
         bool better = !have;

@@ -1,0 +1,328 @@
+// GEMM stage that unrolls the stencil itself: the input stays NCHW and no rewritten copy of
+// it is ever stored (Stencil Unroll + Fuse of Table 2 applied on the fly, for the layers whose
+// unrolled matrix is many times the input -- the data growth Sec. 6.2 reports for it).
+//
+// Depth order.  The fused reduction index is j = (c*R + r)*S4 + s with S4 = ceil(S, 4): a kernel
+// row is padded to whole dwords (the extra taps meet zero weights), the depth to a multiple of
+// 64.  A dword of depth is then four horizontally adjacent input bytes of one (c, r) row, which
+// in NCHW are contiguous in memory -- no byte gathering anywhere.
+//
+// One workgroup (4 waves) computes PT x QT output pixels of one image for up to 64 output
+// channels:
+//   1. window: the C * ((PT-1)*stride + R) input rows the tile touches, as wide as the tile's
+//      pixels reach, are copied into LDS with the zero border filled in (dword loads from a
+//      column clamped into the image row, shifted so that what falls outside becomes zero);
+//   2. weights: the tile's rows of the weight operand -- KCRS itself, or the output of the weight
+//      rewrite for this layout -- are copied into LDS in the padded depth order (a dword load at
+//      any byte address, cut off at the end of its kernel row);
+//   3. a table, one entry per depth dword: its offset in the window;
+//   4. each wave owns 32 pixels of one output row: its MFMA activation operand for a 32-deep
+//      step is four dwords at pixel*stride + table offset (any byte alignment: an aligned pair
+//      and a byte-align each), its weight operand 16 bytes of weight row lane%32.
+//      v_mfma_i32_32x32x32_i8, channels x pixels;
+//   5. the D block (column = pixel = lane%32) goes straight to NKPQ: 128-byte runs per channel.
+#include "kernels.h"
+#include "rewrite_bodies.h"
+
+namespace c2i8 {
+
+namespace {
+
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+struct WindowArgs {
+    const int8_t *in;
+    const int8_t *wt;
+    int32_t *out;
+    int C, H, W, K, P, Q, R, stride, pad;
+    int PT, qshift;        // output rows per tile; tile columns QT = 32 << qshift, PT << qshift = 4
+    int RW;                // window rows per channel: (PT-1)*stride + R
+    int pitch;             // bytes per window row, a multiple of 4
+    int tiles_q, tiles_p;  // tiles per image
+    int CR, nd;            // C*R; dwords per kernel row: ceil(S, 4) / 4
+    int w_S, w_row;        // weight operand: bytes per kernel row (S, or 4*nd once rewritten) and per channel
+    int w_pitch;           // bytes per channel in LDS: depth + 16 (the 32 rows a wave reads start in different banks)
+    int win_bytes, wl_bytes;  // LDS bytes of the window and of the weight rows (multiples of 16)
+    int out_small;         // 4*K*P*Q < 2^32
+    unsigned m_wd, m_RW, m_nd, m_R, m_tiles_q, m_tiles_p;
+};
+
+__device__ __forceinline__ unsigned load_u32(const void *p)  // any alignment
+{
+    unsigned x;
+    __builtin_memcpy(&x, p, 4);
+    return x;
+}
+
+template <int NKK, int NKB>
+__global__ void __launch_bounds__(256) conv_window_kernel(const WindowArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char *win = smem;
+    unsigned char *wl = smem + a.win_bytes;
+    int *tab = reinterpret_cast<int *>(smem + a.win_bytes + a.wl_bytes);  // [NKK*8]
+    constexpr int ND = NKK * 8;  // depth dwords
+    constexpr int KB = 32 * NKB;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l31 = lane & 31, half = lane >> 5;
+
+    const int lid = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int t1 = fast_div_any(lid, a.tiles_q, a.m_tiles_q), tq = lid - t1 * a.tiles_q;
+    const int n = fast_div_any(t1, a.tiles_p, a.m_tiles_p), tp = t1 - n * a.tiles_p;
+    const int p0 = tp * a.PT, q0 = tq << (5 + a.qshift), k0 = blockIdx.y * KB;
+    const int h_lo = p0 * a.stride - a.pad;
+    const int w_first = q0 * a.stride - a.pad;
+    const int w_lo = (w_first >> 2) << 2;  // rounded down, also when negative
+    const int delta = w_first - w_lo;
+
+    // Every global load of a thread is issued before the first LDS store, so that a workgroup
+    // pays one memory round trip for both operands.
+    // 2. weight rows k0 .. k0+KB-1 (those below K), brought into the padded depth order on the way:
+    //    LDS dword d of a row holds the (up to) four taps s0 .. s0+3 of kernel row cr = d / nd.
+    //    A thread keeps one d and walks down the rows.
+    constexpr int RPP = 256 / ND;                  // rows per pass
+    constexpr int WMAX = (KB + RPP - 1) / RPP;     // passes
+    const int rows = min(KB, a.K - k0);
+    const int8_t *wsrc = a.wt + (size_t)k0 * a.w_row;
+    const int last = rows * a.w_row - 4;  // offset of the last whole dword of these rows
+    const int r0 = tid / ND, d = tid - r0 * ND;
+    const int wcr = fast_div(d, a.m_nd), ws0 = 4 * (d - wcr * a.nd);
+    const int left = a.w_S - ws0;  // weight bytes of this kernel row from s0 on
+    const bool real = wcr < a.CR && left > 0;
+    const unsigned mask = !real ? 0u : left >= 4 ? 0xFFFFFFFFu : (1u << (8 * (left & 3))) - 1u;
+    const int coff = wcr * a.w_S + ws0;
+    unsigned wv[WMAX];
+    if (r0 < RPP && last >= 0) {
+#pragma unroll
+        for (int u = 0; u < WMAX; ++u) {
+            const int row = min(r0 + u * RPP, rows - 1);
+            const int off = real ? row * a.w_row + coff : 0;
+            wv[u] = load_u32(wsrc + min(off, last));  // a dword that would run past the rows is fetched lower
+        }
+    }
+    // 1. window
+    {
+        const int8_t *img = a.in + (size_t)n * a.C * a.H * a.W;
+        const int wd = a.pitch >> 2, total = a.C * a.RW * wd;
+        for (int base = 0; base < total; base += 256 * 8) {
+            unsigned v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = min(base + u * 256 + tid, total - 1);
+                const int row = fast_div_any(idx, wd, a.m_wd), c4 = idx - row * wd;
+                const int c = fast_div_any(row, a.RW, a.m_RW), rr = row - c * a.RW;
+                const int h = h_lo + rr, w = w_lo + 4 * c4;
+                const int hc = min(max(h, 0), a.H - 1), wc = min(max(w, 0), a.W - 4);  // W >= 4
+                const unsigned x = load_u32(img + ((size_t)c * a.H + hc) * a.W + wc);
+                const int dd = wc - w;  // > 0: the dword starts left of the row, < 0: it runs past its end
+                const unsigned sh = (unsigned)(dd > 0 ? dd : -dd) * 8u;
+                unsigned y = dd >= 0 ? (x << (sh & 31u)) : (x >> (sh & 31u));
+                if (sh >= 32u || h != hc) y = 0u;
+                v[u] = y;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (base + u * 256 + tid < total) *reinterpret_cast<unsigned *>(win + 4 * (base + u * 256 + tid)) = v[u];
+        }
+    }
+    if (r0 < RPP) {
+        if (last >= 0) {
+#pragma unroll
+            for (int u = 0; u < WMAX; ++u) {
+                const int row = r0 + u * RPP;
+                if (row < rows) {
+                    const int off = real ? row * a.w_row + coff : 0;
+                    const unsigned x = (wv[u] >> (8 * (off - min(off, last)))) & mask;
+                    *reinterpret_cast<unsigned *>(wl + row * a.w_pitch + 4 * d) = x;
+                }
+            }
+        } else {  // fewer than four weight bytes in all
+            for (int row = r0; row < rows; row += RPP) {
+                unsigned x = 0;
+                const int off = row * a.w_row + coff;
+                if (real)
+                    for (int b = 0; off + b < rows * a.w_row; ++b) x |= (unsigned)(unsigned char)wsrc[off + b] << (8 * b);
+                *reinterpret_cast<unsigned *>(wl + row * a.w_pitch + 4 * d) = x & mask;
+            }
+        }
+    }
+    // 3. table: where depth dword d starts in the window, relative to a pixel's first byte
+    if (tid < ND) {
+        const int cr = fast_div(tid, a.m_nd), s0 = 4 * (tid - cr * a.nd);
+        const int c = fast_div(cr, a.m_R), r = cr - c * a.R;
+        tab[tid] = cr < a.CR ? (c * a.RW + r) * a.pitch + s0 : 0;
+    }
+    __syncthreads();
+
+    // 4. MFMA.  A pixel's four bytes start at any byte of the window: two aligned dwords and a
+    //    byte-align (unaligned LDS reads are served one lane at a time).
+    const int pw = wave >> a.qshift, qw = wave & ((1 << a.qshift) - 1);
+    const int abyte = (pw * a.stride) * a.pitch + delta + (qw * 32 + l31) * a.stride;
+    const unsigned char *wbase = wl + l31 * a.w_pitch + half * 16;
+    v16i acc[NKB];
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[kb][v] = 0;
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) {
+        const v4i ta = *reinterpret_cast<const v4i *>(tab + kk * 8 + half * 4);
+        v4i af;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int at = abyte + ta[i];
+            const unsigned *pp = reinterpret_cast<const unsigned *>(win + (at & ~3));
+            af[i] = (int)__builtin_amdgcn_alignbyte(pp[1], pp[0], (unsigned)at & 3u);
+        }
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) {
+            const v4i wf = *reinterpret_cast<const v4i *>(wbase + kb * 32 * a.w_pitch + kk * 32);
+            acc[kb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, af, acc[kb], 0, 0, 0);
+        }
+    }
+
+    // 5. D block: column = lane%32 = pixel, row = 8*(v/4) + 4*(lane/32) + v%4 = channel
+    const int p = p0 + pw, q = q0 + qw * 32 + l31;
+    if (p >= a.P || q >= a.Q) return;
+    const size_t PQ = (size_t)a.P * a.Q;
+    int32_t *outn = a.out + (size_t)n * a.K * PQ;
+    if (a.out_small) {  // byte offsets inside an image's planes fit 32 bits: one add per store
+        const unsigned PQ4 = (unsigned)PQ * 4u;
+        const unsigned o = (unsigned)(k0 + 4 * half) * PQ4 + ((unsigned)p * a.Q + q) * 4u;
+        char *ob = reinterpret_cast<char *>(outn);
+        const bool full = k0 + KB <= a.K;
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int kr = kb * 32 + 8 * (v >> 2) + (v & 3);
+                if (full || k0 + 4 * half + kr < a.K)
+                    *reinterpret_cast<int32_t *>(ob + (o + (unsigned)kr * PQ4)) = acc[kb][v];
+            }
+        return;
+    }
+    int32_t *base = outn + (size_t)p * a.Q + q;
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int k = k0 + kb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+            if (k < a.K) base[(size_t)k * PQ] = acc[kb][v];
+        }
+}
+
+// dst[k][(cr*nd + d)*4 + b] = src[k][cr*S + 4*d + b] inside the kernel row, else 0; one thread per dword
+__global__ void __launch_bounds__(256) pack_weights_window_kernel(const int8_t *src, int8_t *dst, int K, int CR,
+                                                                  int S, int nd, int depth, unsigned m_nd)
+{
+    const int dd = depth >> 2;
+    const long long total = (long long)K * dd;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+        const int k = (int)(i / dd), d = (int)(i - (long long)k * dd);
+        const int cr = fast_div(d, m_nd), s0 = 4 * (d - cr * nd);
+        unsigned x = 0;
+        if (cr < CR)
+            for (int b = 0; b < 4 && s0 + b < S; ++b)
+                x |= (unsigned)(unsigned char)src[((size_t)k * CR + cr) * S + s0 + b] << (8 * b);
+        reinterpret_cast<unsigned *>(dst)[i] = x;
+    }
+}
+
+}  // namespace
+
+int window_depth(int C, int R, int S)
+{
+    const long long real = (long long)C * R * ((S + 3) / 4 * 4);
+    if (real > 256) return 0;
+    return (int)((real + 63) / 64 * 64);
+}
+
+constexpr long long WINDOW_LIMIT = 40 * 1024;  // bytes of LDS the input window of a tile may take
+
+// Tile shape by output width, window geometry and the LDS it needs.
+static bool window_plan(const WindowProblem &g, WindowArgs *a)
+{
+    const int depth = window_depth(g.C, g.R, g.S);
+    if (depth == 0 || g.W < 4) return false;
+    WindowArgs w{};
+    w.in = g.in;
+    w.wt = g.wt;
+    w.out = g.out;
+    w.C = g.C; w.H = g.H; w.W = g.W; w.K = g.K; w.P = g.P; w.Q = g.Q; w.R = g.R;
+    w.stride = g.stride; w.pad = g.pad;
+    w.qshift = g.Q > 64 ? 2 : g.Q > 32 ? 1 : 0;
+    w.PT = 4 >> w.qshift;
+    const int QT = 32 << w.qshift;
+    const int S4 = (g.S + 3) / 4 * 4;
+    const long long RW = (long long)(w.PT - 1) * g.stride + g.R;
+    const long long pitch = (((long long)(QT - 1) * g.stride + S4 + 3) + 3) / 4 * 4;
+    if (RW > WINDOW_LIMIT || pitch > WINDOW_LIMIT || g.C * RW * pitch > WINDOW_LIMIT) return false;
+    w.RW = (int)RW;
+    const long long win = (g.C * RW * pitch + 4 + 15) / 16 * 16;  // + the dword after the last one (read, never used)
+    w.CR = g.C * g.R;
+    w.nd = S4 / 4;
+    w.w_S = g.wt_rewritten ? S4 : g.S;
+    w.w_row = g.wt_rewritten ? depth : g.C * g.R * g.S;
+    w.w_pitch = depth + 16;
+    const int kb = g.K > 32 ? 64 : 32;
+    const long long wlb = (long long)kb * w.w_pitch;
+    if (win + 8 + wlb + depth > 64 * 1024) return false;  // cannot happen within the limits above
+    w.pitch = (int)pitch;
+    w.win_bytes = (int)win;
+    w.wl_bytes = (int)wlb;
+    w.tiles_q = (g.Q + QT - 1) / QT;
+    w.tiles_p = (g.P + w.PT - 1) / w.PT;
+    if ((long long)g.N * w.tiles_p * w.tiles_q > 2147483647LL || (g.K + kb - 1) / kb > 65535) return false;
+    w.m_wd = magic_for(pitch / 4);
+    w.m_RW = magic_for(w.RW);
+    w.m_nd = magic_for(w.nd);
+    w.m_R = magic_for(g.R);
+    w.m_tiles_q = magic_for(w.tiles_q);
+    w.m_tiles_p = magic_for(w.tiles_p);
+    w.out_small = 4LL * g.K * g.P * g.Q < (1LL << 32);
+    if (a) *a = w;
+    return true;
+}
+
+bool window_fits(const WindowProblem &g) { return window_plan(g, nullptr); }
+
+template <int NKK>
+static hipError_t launch_window_nkk(const WindowArgs &a, dim3 grid, size_t lds, hipStream_t st)
+{
+    if (a.K > 32) hipLaunchKernelGGL((conv_window_kernel<NKK, 2>), grid, dim3(256), lds, st, a);
+    else hipLaunchKernelGGL((conv_window_kernel<NKK, 1>), grid, dim3(256), lds, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_window_conv(const WindowProblem &g, hipStream_t st)
+{
+    WindowArgs a;
+    if (!window_plan(g, &a)) return hipErrorInvalidValue;
+    const int depth = window_depth(g.C, g.R, g.S);
+    const int kb = g.K > 32 ? 64 : 32;
+    const dim3 grid((unsigned)(g.N * a.tiles_p * a.tiles_q), (unsigned)((g.K + kb - 1) / kb));
+    const size_t lds = (size_t)a.win_bytes + a.wl_bytes + (size_t)depth;
+    switch (depth / 32) {
+        case 2: return launch_window_nkk<2>(a, grid, lds, st);
+        case 4: return launch_window_nkk<4>(a, grid, lds, st);
+        case 6: return launch_window_nkk<6>(a, grid, lds, st);
+        case 8: return launch_window_nkk<8>(a, grid, lds, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_pack_weights_window(int K, int C, int R, int S, const int8_t *src, int8_t *dst, hipStream_t st)
+{
+    const int depth = window_depth(C, R, S);
+    if (depth == 0) return hipErrorInvalidValue;
+    const int nd = (S + 3) / 4;
+    const long long total = (long long)K * (depth / 4);
+    const int blocks = (int)((total + 255) / 256 < 4096 ? (total + 255) / 256 : 4096);
+    hipLaunchKernelGGL(pack_weights_window_kernel, dim3(blocks), dim3(256), 0, st, src, dst, K, C * R, S, nd, depth,
+                       magic_for(nd));
+    return hipGetLastError();
+}
+
+}  // namespace c2i8

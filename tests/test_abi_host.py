@@ -42,7 +42,7 @@ def test_selector_matches_definition(lib, cfg):
         want = sel.select(*cfg.dims(), *w)
         assert got[:2] == want[:2]
         assert got[2] == pytest.approx(want[2], rel=1e-12)
-    for layout, cb in sel.candidates(cfg.C):
+    for layout, cb in sel.candidates(cfg.C, cfg.dims()):
         assert lib.layout_overheads(cfg.dims(), layout, cb) == sel.overheads(*cfg.dims(), layout, cb)
 
 
@@ -100,3 +100,31 @@ def test_ex_and_packed_validation(lib):
     for t in range(lib.num_tiles()):
         r, c, th, steps = lib.tile_info(t)
         assert r % 32 == 0 and c % 32 == 0 and th % 64 == 0 and steps in (1, 2, 4)
+
+
+IMPLICIT_DOMAIN = [(1, 1, 8, 3, 4, 3, 3, 1, 1), (1, 16, 64, 4000, 4, 4, 4, 40, 0), (1, 1, 64, 4000, 4, 4, 4, 40, 0),
+                   (1, 16, 9, 9, 8, 4, 4, 1, 0), (1, 17, 9, 9, 8, 4, 4, 1, 0), (2, 3, 40, 40, 8, 3, 3, 2, 1),
+                   (1, 4, 30, 70, 8, 5, 5, 3, 2), (1, 64, 8, 200, 8, 1, 1, 5, 0), (1, 2, 300, 9, 8, 30, 4, 1, 0)]
+
+
+@pytest.mark.parametrize("dims", IMPLICIT_DOMAIN + [c.dims() for c in ALL_SHAPES], ids=str)
+def test_gemm_stage_unroll_domain_and_sizes(lib, dims):
+    """Where the library accepts the layout is where the stated rule says; its weight rewrite has the
+    stated depth; it needs no workspace."""
+    N, C, H, W, K, R, S, st, pad = dims
+    ok = sel.implicit_applies(*dims)
+    d = lib.ConvDesc(*dims)
+    raw = lib.load()
+    a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    rc = raw.layout_overheads(ctypes.byref(d), lib.LAYOUT_IMPLICIT, 0, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    assert rc == (lib.OK if ok else lib.ERR_UNSUPPORTED)
+    if ok:
+        assert (a.value, b.value, c.value) == sel.overheads(*dims, sel.IMPLICIT, 0)
+        assert lib.conv2d_int8_workspace_bytes(dims, lib.LAYOUT_IMPLICIT, 0) == 0
+        assert lib.query_tiling(dims, lib.LAYOUT_IMPLICIT, 0) == (-1, 1)
+        assert not lib.tile_applies(dims, lib.LAYOUT_IMPLICIT, 0, 0, 1)
+    S4 = -(-S // 4) * 4
+    depth = -(-C * R * S4 // 64) * 64
+    assert lib.pack_weights_depth(C, R, S, lib.LAYOUT_IMPLICIT, 0) == (depth if depth <= 256 else 0)
+    for w in [(1.0, 1.0), (0.0, 1.0), (1.0 / 0.6e15, 1.0 / 4.0e12)]:
+        assert lib.select_layout(dims, *w)[:2] == sel.select(*dims, *w)[:2]

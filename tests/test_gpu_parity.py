@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import direct, layouts
+from oracle import direct, layouts, selection
 from paper_2104_04731_amd.inputs import CONFIGS, PAPER_SHAPES, ConvShape, uniform_int8
 
 pytestmark = pytest.mark.gpu
@@ -72,6 +72,13 @@ def test_pack_weights(lib, wshape, cb):
     got = host(lib.pack_weights(dev(w), lib.LAYOUT_IM2COL, 0))
     np.testing.assert_array_equal(got, layouts.pack_weights_im2col(w))
     cbp = layouts.ceil_to(wshape[1], 16)
+    if layouts.ceil_to(w.shape[1] * w.shape[2] * layouts.ceil_to(w.shape[3], 4), 64) <= 256:
+        got = host(lib.pack_weights(dev(w), lib.LAYOUT_IMPLICIT, 0))
+        np.testing.assert_array_equal(got, layouts.pack_weights_implicit(w))
+    else:
+        with pytest.raises(lib.ConvError) as e:
+            lib.pack_weights(dev(w), lib.LAYOUT_IMPLICIT, 0)
+        assert e.value.status == lib.ERR_UNSUPPORTED
     got = host(lib.pack_weights(dev(w), lib.LAYOUT_PAD_ONLY, 0))
     np.testing.assert_array_equal(got, layouts.pack_weights_blocked(w, cbp))
 
@@ -361,3 +368,71 @@ def test_one_shot_graph_replay(lib):
         # eager work between replays, through the same path
         e = lib.conv2d_int8(ins[0][0], ins[0][1], cfgs[0].stride, cfgs[0].pad)
         assert np.array_equal(host(e), data[0][2])
+
+
+# ---- stencil unroll inside the GEMM stage ---------------------------------------------------
+def run_implicit(lib, cfg, x, w, rewritten, dx=None):
+    dx = dev(x) if dx is None else dx
+    out = torch.full((cfg.N, cfg.K, cfg.P, cfg.Q), 4321, dtype=torch.int32, device=DEV)
+    if rewritten:
+        lib.conv2d_int8_packed(cfg.dims(), lib.LAYOUT_IMPLICIT, 0, dx, lib.pack_weights(dev(w), lib.LAYOUT_IMPLICIT, 0), out)
+    else:
+        lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_IMPLICIT, 0, dx, dev(w), out, None)
+    return host(out)
+
+
+@pytest.mark.parametrize("name", list(CONFIGS))
+def test_implicit_configs(lib, name):
+    cfg = CONFIGS[name]
+    x, w, want = oracle_conv(cfg)
+    if not selection.implicit_applies(*cfg.dims()):
+        out = torch.zeros((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=DEV)
+        with pytest.raises(lib.ConvError) as e:
+            lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_IMPLICIT, 0, dev(x), dev(w), out, None)
+        assert e.value.status == lib.ERR_UNSUPPORTED
+        return
+    for rewritten in (False, True):
+        got = run_implicit(lib, cfg, x, w, rewritten)
+        assert np.array_equal(got, want), f"{name} rewritten={rewritten}: {np.count_nonzero(got != want)} mismatches"
+
+
+IMPLICIT_SHAPES = [
+    ConvShape("row-tile-tail", 2, 3, 20, 150, 64, 7, 7, 2, 3), ConvShape("two-row-tile", 2, 3, 11, 90, 33, 3, 3, 2, 1),
+    ConvShape("four-row-tile", 3, 4, 10, 30, 70, 3, 3, 1, 1), ConvShape("odd-width", 1, 2, 9, 13, 5, 3, 5, 1, 2),
+    ConvShape("width-4", 1, 1, 6, 4, 3, 2, 2, 1, 1), ConvShape("1x1", 2, 5, 7, 9, 130, 1, 1, 1, 0),
+    ConvShape("1x1-stride3", 1, 32, 10, 40, 8, 1, 1, 3, 0), ConvShape("tall", 1, 1, 40, 21, 32, 20, 5, 2, 0),
+    ConvShape("wide-kernel", 1, 2, 6, 40, 9, 2, 9, 3, 4), ConvShape("deep-256", 1, 16, 8, 19, 40, 4, 4, 1, 2),
+    ConvShape("one-pixel-out", 1, 3, 7, 7, 2, 7, 7, 1, 0), ConvShape("big-pad", 1, 1, 5, 6, 4, 3, 3, 2, 5),
+    ConvShape("one-weight", 1, 1, 4, 4, 1, 1, 1, 1, 0),
+]
+
+
+@pytest.mark.parametrize("cfg", IMPLICIT_SHAPES, ids=lambda c: c.name)
+def test_implicit_shapes(lib, cfg):
+    """All three tile shapes with ragged ends, strides, wide borders, image widths that are not a multiple
+    of four, kernel rows of 1 to 9 taps, several output-channel blocks, both weight forms."""
+    assert selection.implicit_applies(*cfg.dims())
+    x = uniform_int8(411, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(412, (cfg.K, cfg.C, cfg.R, cfg.S))
+    want = direct.conv2d_int8(x, w, cfg.stride, cfg.pad)
+    for rewritten in (False, True):
+        got = run_implicit(lib, cfg, x, w, rewritten)
+        assert np.array_equal(got, want), f"rewritten={rewritten}: {np.count_nonzero(got != want)} mismatches"
+
+
+def test_implicit_unaligned_operands_and_forced_tiles(lib):
+    cfg = ConvShape("unaligned", 2, 3, 12, 16, 5, 3, 3, 1, 1)
+    x = uniform_int8(421, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(422, (cfg.K, cfg.C, cfg.R, cfg.S))
+    want = direct.conv2d_int8(x, w, cfg.stride, cfg.pad)
+    for off in (1, 2, 3):   # operands that start at any byte
+        bx = torch.zeros(x.size + 8, dtype=torch.int8, device=DEV); bw = torch.zeros(w.size + 8, dtype=torch.int8, device=DEV)
+        dx = bx[off:off + x.size].view(x.shape); dw = bw[off:off + w.size].view(w.shape)
+        dx.copy_(dev(x)); dw.copy_(dev(w))
+        out = torch.zeros((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=DEV)
+        lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_IMPLICIT, 0, dx, dw, out, None)
+        assert np.array_equal(host(out), want), off
+    out = torch.zeros((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=DEV)
+    wp = lib.pack_weights(dev(w), lib.LAYOUT_IMPLICIT, 0)
+    for tile, split in ((0, 1), (-1, 2)):
+        with pytest.raises(lib.ConvError) as e:
+            lib.conv2d_int8_packed(cfg.dims(), lib.LAYOUT_IMPLICIT, 0, dev(x), wp, out, tile=tile, split_k=split)
+        assert e.value.status == lib.ERR_UNSUPPORTED

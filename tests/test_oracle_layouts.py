@@ -96,3 +96,28 @@ def test_weight_pack_im2col_is_row_padded_copy():
     assert B.shape == (5, 192)
     np.testing.assert_array_equal(B[:, :147], w.reshape(5, 147))
     assert not B[:, 147:].any()
+
+
+@pytest.mark.parametrize("dims", [(2, 3, 9, 9, 4, 7, 7, 2, 3), (1, 1, 23, 12, 3, 20, 5, 2, 0),
+                                  (1, 5, 6, 8, 2, 3, 3, 1, 1), (1, 2, 5, 7, 3, 1, 1, 1, 0), (1, 3, 6, 9, 2, 2, 9, 3, 2)])
+def test_row_padded_weights_give_the_convolution(dims):
+    """Stencil unroll in the depth order (c, r, s') with kernel rows padded to four taps: the GEMM of
+    the padded weights with the matching unrolled input (padded taps read whatever lies right of
+    the window -- here the next real columns or zero -- and meet zero weights) == direct convolution."""
+    N, C, H, W, K, R, S, st, pad = dims
+    x = uniform_int8(66, (N, C, H, W)); w = uniform_int8(67, (K, C, R, S))
+    B = layouts.pack_weights_implicit(w)
+    S4 = -(-S // 4) * 4
+    assert B.shape == (K, -(-C * R * S4 // 64) * 64)
+    P = (H + 2 * pad - R) // st + 1; Q = (W + 2 * pad - S) // st + 1
+    x0 = np.zeros((N, C, H + 2 * pad, W + 2 * pad + S4), np.int8)      # room right of the last window
+    x0[:, :, pad:pad + H, pad:pad + W] = x
+    x0[:, :, :, W + 2 * pad:] = 77                                       # must not matter
+    A = np.zeros((N, P, Q, B.shape[1]), np.int8)
+    for c, r, s in itertools.product(range(C), range(R), range(S4)):
+        A[:, :, :, (c * R + r) * S4 + s] = x0[:, c, r:r + st * (P - 1) + 1:st, s:s + st * (Q - 1) + 1:st]
+    got = layouts.gemm_nt(B, A.reshape(N * P * Q, -1)).reshape(K, N, P, Q).transpose(1, 0, 2, 3)
+    np.testing.assert_array_equal(got, direct.conv2d_int8(x, w, st, pad))
+    # the true weights, each once, in (c, r, s) order; zeros elsewhere
+    assert np.count_nonzero(B) == np.count_nonzero(w)
+    np.testing.assert_array_equal(B[:, :C * R * S4].reshape(K, C * R, S4)[:, :, :S].reshape(K, C, R, S), w)

@@ -56,3 +56,35 @@ def test_tie_breaks_are_deterministic():
     # C=64: blocks of 16/32/64 and the single padded block describe equal-cost layouts
     layout, cb, _ = sel.select(1, 64, 8, 8, 32, 3, 3, 1, 1, 1.0, 1.0)
     assert (layout, cb) == (sel.PACKED, 64)
+
+
+def test_unrolling_inside_the_gemm_stage_moves_nothing_twice():
+    """Its only overhead is the matrix unit's padding: kernel rows to four taps, the depth to 64,
+    each output row to 32 pixels, output channels to 32."""
+    N, C, H, W, K, R, S = 2, 2, 10, 35, 32, 4, 4           # P=7, Q=32: nothing to pad but the depth
+    o_mac, o_data, rewritten = sel.overheads(N, C, H, W, K, R, S, 1, 0, sel.IMPLICIT, 0)
+    assert (o_data, rewritten) == (0, 0)
+    assert o_mac == N * 7 * 32 * K * (64 - C * R * S)
+    # 7-tap rows are issued as 8: useful fraction 7/8 when everything else divides
+    o_mac, _, _ = sel.overheads(1, 8, 8, 38, 32, 1, 7, 1, 0, sel.IMPLICIT, 0)   # Q=32, depth 8*1*8=64
+    mac_min = 8 * 32 * 32 * 8 * 7
+    assert (o_mac + mac_min) * 7 == mac_min * 8
+
+
+def test_domain_of_unrolling_inside_the_gemm_stage():
+    assert sel.implicit_applies(*CONFIGS["C3"].dims()) and sel.implicit_applies(*CONFIGS["C5"].dims())
+    assert sel.implicit_applies(*CONFIGS["C1"].dims())                       # 16*3*4 = 192 deep
+    for name in ("C2", "C4a", "C4b"):                                         # 768, 3072, 2048 deep
+        assert not sel.implicit_applies(*CONFIGS[name].dims())
+        assert (sel.IMPLICIT, 0) not in sel.candidates(CONFIGS[name].C, CONFIGS[name].dims())
+    assert not sel.implicit_applies(1, 1, 8, 3, 4, 3, 3, 1, 1)                # three-pixel rows
+    assert not sel.implicit_applies(1, 16, 64, 4000, 4, 4, 4, 40, 0)          # 16 channels x 4 rows x 5 KB
+    assert sel.implicit_applies(1, 1, 64, 4000, 4, 4, 4, 40, 0)
+
+
+def test_hardware_weights_send_low_channel_layers_to_the_gemm_stage_unroll():
+    """With seconds per MAC and per moved byte as weights, writing and re-reading the unrolled matrix
+    costs far more than the padded MACs: C3 and C5 leave im2col; the paper's w = [1,1] keeps it."""
+    for name in ("C3", "C5"):
+        assert sel.select(*CONFIGS[name].dims(), 1.0 / 0.6e15, 1.0 / 4.0e12)[0] == sel.IMPLICIT
+        assert sel.select(*CONFIGS[name].dims(), 1.0, 1.0)[0] == sel.IM2COL
