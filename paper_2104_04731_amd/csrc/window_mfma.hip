@@ -44,6 +44,8 @@ struct WindowArgs {
     int w_pitch;           // bytes per channel in LDS: depth + 16 (the 32 rows a wave reads start in different banks)
     int win_bytes, wl_bytes;  // LDS bytes of the window and of the weight rows (multiples of 16)
     int out_small;         // 4*K*P*Q < 2^32
+    int in_small;          // C*H*W < 2^31
+    int wide_out;          // Q % 4 == 0 and out 16-byte aligned: 16-byte stores
     unsigned m_wd, m_RW, m_nd, m_R, m_tiles_q, m_tiles_p;
 };
 
@@ -99,7 +101,7 @@ __global__ void __launch_bounds__(256) conv_window_kernel(const WindowArgs a)
         for (int u = 0; u < WMAX; ++u) {
             const int row = min(r0 + u * RPP, rows - 1);
             const int off = real ? row * a.w_row + coff : 0;
-            wv[u] = load_u32(wsrc + min(off, last));  // a dword that would run past the rows is fetched lower
+            wv[u] = load_u32(wsrc + (unsigned)min(off, last));  // a dword that would run past the rows is fetched lower
         }
     }
     // 1. window
@@ -110,12 +112,15 @@ __global__ void __launch_bounds__(256) conv_window_kernel(const WindowArgs a)
             unsigned v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
+                if (base + u * 256 >= total) break;  // the same for every thread
                 const int idx = min(base + u * 256 + tid, total - 1);
-                const int row = fast_div_any(idx, wd, a.m_wd), c4 = idx - row * wd;
-                const int c = fast_div_any(row, a.RW, a.m_RW), rr = row - c * a.RW;
+                // exact: idx, row < 10240 and wd, RW <= 40960 keep n*d below 2^32
+                const int row = fast_div(idx, a.m_wd), c4 = idx - row * wd;
+                const int c = fast_div(row, a.m_RW), rr = row - c * a.RW;
                 const int h = h_lo + rr, w = w_lo + 4 * c4;
                 const int hc = min(max(h, 0), a.H - 1), wc = min(max(w, 0), a.W - 4);  // W >= 4
-                const unsigned x = load_u32(img + ((size_t)c * a.H + hc) * a.W + wc);
+                const unsigned x = a.in_small ? load_u32(img + (unsigned)((c * a.H + hc) * a.W + wc))
+                                              : load_u32(img + ((size_t)c * a.H + hc) * a.W + wc);
                 const int dd = wc - w;  // > 0: the dword starts left of the row, < 0: it runs past its end
                 const unsigned sh = (unsigned)(dd > 0 ? dd : -dd) * 8u;
                 unsigned y = dd >= 0 ? (x << (sh & 31u)) : (x >> (sh & 31u));
@@ -133,8 +138,8 @@ __global__ void __launch_bounds__(256) conv_window_kernel(const WindowArgs a)
             for (int u = 0; u < WMAX; ++u) {
                 const int row = r0 + u * RPP;
                 if (row < rows) {
-                    const int off = real ? row * a.w_row + coff : 0;
-                    const unsigned x = (wv[u] >> (8 * (off - min(off, last)))) & mask;
+                    const int over = row * a.w_row + coff - last;  // > 0 only at the very end of the rows
+                    const unsigned x = (wv[u] >> (8 * (unsigned)max(over, 0))) & mask;
                     *reinterpret_cast<unsigned *>(wl + row * a.w_pitch + 4 * d) = x;
                 }
             }
@@ -160,6 +165,8 @@ __global__ void __launch_bounds__(256) conv_window_kernel(const WindowArgs a)
     //    byte-align (unaligned LDS reads are served one lane at a time).
     const int pw = wave >> a.qshift, qw = wave & ((1 << a.qshift) - 1);
     const int abyte = (pw * a.stride) * a.pitch + delta + (qw * 32 + l31) * a.stride;
+    const unsigned char *a4 = win + (abyte & ~3);  // table offsets are multiples of 4: the byte shift is the lane's own
+    const unsigned ash = (unsigned)abyte & 3u;
     const unsigned char *wbase = wl + l31 * a.w_pitch + half * 16;
     v16i acc[NKB];
 #pragma unroll
@@ -172,9 +179,8 @@ __global__ void __launch_bounds__(256) conv_window_kernel(const WindowArgs a)
         v4i af;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int at = abyte + ta[i];
-            const unsigned *pp = reinterpret_cast<const unsigned *>(win + (at & ~3));
-            af[i] = (int)__builtin_amdgcn_alignbyte(pp[1], pp[0], (unsigned)at & 3u);
+            const unsigned *pp = reinterpret_cast<const unsigned *>(a4 + ta[i]);
+            af[i] = (int)__builtin_amdgcn_alignbyte(pp[1], pp[0], ash);
         }
 #pragma unroll
         for (int kb = 0; kb < NKB; ++kb) {
@@ -184,10 +190,34 @@ __global__ void __launch_bounds__(256) conv_window_kernel(const WindowArgs a)
     }
 
     // 5. D block: column = lane%32 = pixel, row = 8*(v/4) + 4*(lane/32) + v%4 = channel
-    const int p = p0 + pw, q = q0 + qw * 32 + l31;
-    if (p >= a.P || q >= a.Q) return;
     const size_t PQ = (size_t)a.P * a.Q;
     int32_t *outn = a.out + (size_t)n * a.K * PQ;
+    if (a.wide_out) {
+        // Q a multiple of 4 and `out` 16-byte aligned: each wave turns its 32x32 block around in LDS
+        // (rows of 36 dwords) so that a lane stores four consecutive pixels of one channel -- 16-byte
+        // stores, eight 128-byte runs per instruction instead of two
+        __syncthreads();  // every wave is done with the window and the weights
+        int *T = reinterpret_cast<int *>(smem) + wave * (32 * 36);
+        const int tr = lane >> 3, tg = lane & 7;
+        const int pp = p0 + pw, qq = q0 + qw * 32 + 4 * tg;
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) T[(8 * (v >> 2) + 4 * half + (v & 3)) * 36 + l31] = acc[kb][v];
+            __builtin_amdgcn_wave_barrier();  // LDS serves a wave's accesses in order: no wait beyond the compiler's own
+            int32_t *dst = outn + (size_t)(k0 + kb * 32 + tr) * PQ + (size_t)pp * a.Q + qq;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const v4i t = *reinterpret_cast<const v4i *>(T + (tr + 8 * j) * 36 + 4 * tg);
+                if (pp < a.P && qq < a.Q && k0 + kb * 32 + tr + 8 * j < a.K)
+                    *reinterpret_cast<v4i *>(dst + (size_t)(8 * j) * PQ) = t;
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        return;
+    }
+    const int p = p0 + pw, q = q0 + qw * 32 + l31;
+    if (p >= a.P || q >= a.Q) return;
     if (a.out_small) {  // byte offsets inside an image's planes fit 32 bits: one add per store
         const unsigned PQ4 = (unsigned)PQ * 4u;
         const unsigned o = (unsigned)(k0 + 4 * half) * PQ4 + ((unsigned)p * a.Q + q) * 4u;
@@ -282,6 +312,8 @@ static bool window_plan(const WindowProblem &g, WindowArgs *a)
     w.m_tiles_q = magic_for(w.tiles_q);
     w.m_tiles_p = magic_for(w.tiles_p);
     w.out_small = 4LL * g.K * g.P * g.Q < (1LL << 32);
+    w.in_small = (long long)g.C * g.H * g.W < (1LL << 31);
+    w.wide_out = g.Q % 4 == 0 && (reinterpret_cast<uintptr_t>(g.out) & 15) == 0;
     if (a) *a = w;
     return true;
 }
@@ -303,7 +335,8 @@ hipError_t launch_window_conv(const WindowProblem &g, hipStream_t st)
     const int depth = window_depth(g.C, g.R, g.S);
     const int kb = g.K > 32 ? 64 : 32;
     const dim3 grid((unsigned)(g.N * a.tiles_p * a.tiles_q), (unsigned)((g.K + kb - 1) / kb));
-    const size_t lds = (size_t)a.win_bytes + a.wl_bytes + (size_t)depth;
+    size_t lds = (size_t)a.win_bytes + a.wl_bytes + (size_t)depth;
+    if (lds < 4 * 32 * 36 * 4) lds = 4 * 32 * 36 * 4;  // the output blocks of the four waves, turned around
     switch (depth / 32) {
         case 2: return launch_window_nkk<2>(a, grid, lds, st);
         case 4: return launch_window_nkk<4>(a, grid, lds, st);
