@@ -59,7 +59,10 @@ typedef enum {
                                  ceil(C*R*S4, 64) <= 256, W >= 4 and the input window of one tile --
                                  C*((PT-1)*stride + R) rows of ceil((QT-1)*stride + S4 + 3, 4) bytes, with
                                  PT x QT = 1x128 output pixels if Q > 64, 2x64 if Q > 32, else 4x32 --
-                                 fits 40 KB; otherwise CONV_ERR_UNSUPPORTED. */
+                                 fits 40 KB.  1x1 kernels over C % 64 == 0 channels take a second form of
+                                 it (a workgroup turns its 32 pixels into depth-contiguous rows in LDS;
+                                 depth index c, weights as they are): stride 1, pad 0, C <= 512 and
+                                 H*W % 4 == 0.  Outside these domains: CONV_ERR_UNSUPPORTED. */
 } conv_layout_t;
 
 typedef struct {
@@ -127,7 +130,7 @@ size_t pack_layout_bytes(int N, int C, int H, int W, int cb, int pad);
  *   PACKED / PAD_ONLY: j = ((c/cb * R + r) * S + s) * cb + c%cb   (cb a multiple of 16;
  *                      PAD_ONLY forces cb = ceil(C,16))
  *   IM2COL:            j = (c*R + r)*S + s
- *   IMPLICIT:          j = (c*R + r)*S4 + s,  S4 = ceil(S,4) */
+ *   IMPLICIT:          j = (c*R + r)*S4 + s,  S4 = ceil(S,4); for R = S = 1 and C % 64 == 0: j = c, depth = C */
 int pack_weights(int K, int C, int R, int S, int layout, int cb,
                  const int8_t *src, int8_t *dst, void *stream);
 int pack_weights_depth(int C, int R, int S, int layout, int cb);
@@ -152,7 +155,8 @@ int gemm_int8_nt(int X, int Y, int Z, const int8_t *A, const int8_t *B, int32_t 
  * O_Data = elements moved by rewrites and GEMM stage minus |in| + |wt| + |out|.
  * Candidates: PACKED with cb in {64,32,16}, IM2COL, PAD_ONLY, and IMPLICIT where it applies
  * (no rewritten elements, O_Data = 0; MAC_total = N*P*ceil(Q,32) * ceil(K,32) * ceil(C*R*S4,64):
- * pixels are padded per output row, kernel rows to S4).  Ties: fewer rewritten
+ * pixels are padded per output row, kernel rows to S4; in its 1x1 form
+ * MAC_total = N*ceil(P*Q,32) * ceil(K,32) * C).  Ties: fewer rewritten
  * elements, then lower layout code, then larger cb.  select_layout uses the library's
  * MI355X weights (seconds per MAC and per byte); the paper's case studies use w = [1,1]. */
 int select_layout(const conv_desc_t *desc, int *layout, int *cb, double *score);

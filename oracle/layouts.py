@@ -60,6 +60,8 @@ def pack_weights_im2col(w: np.ndarray, kalign: int = 64) -> np.ndarray:
 def pack_weights_implicit(w: np.ndarray, kalign: int = 64) -> np.ndarray:
     """[K,C,R,S] -> [K, depth]; depth index j = (c*R + r)*S4 + s with S4 = ceil(S,4), zero-padded."""
     K, C, R, S = w.shape
+    if R == 1 and S == 1 and C % 64 == 0:   # 1x1 over whole 64-channel multiples: [K][C] as it is
+        return w.reshape(K, C).copy()
     S4 = ceil_to(S, 4)
     y = np.zeros((K, C * R, S4), dtype=w.dtype)
     y[:, :, :S] = w.reshape(K, C * R, S)

@@ -23,7 +23,10 @@ kernel row is padded to whole dwords, S4 = ceil(S,4):
 It is a candidate only inside the domain the interface states for it: padded depth at
 most 256, W >= 4, and the input window of one tile -- C*((PT-1)*stride + R) rows of
 ceil((QT-1)*stride + S4 + 3, 4) bytes, PT x QT = 1x128 if Q > 64, 2x64 if Q > 32, else
-4x32 -- within 40 KB.
+4x32 -- within 40 KB.  A 1x1 kernel over C % 64 == 0 channels takes the layout's second
+form (pixels of an image turned into depth-contiguous rows on the fly, weights as they
+are): stride 1, no padding, C <= 512, H*W a multiple of 4;
+               MAC_total = N*ceil(P*Q,x) * ceil(K,y) * C.
 """
 from __future__ import annotations
 
@@ -35,7 +38,14 @@ def _ceil(x, m):
     return -(-x // m) * m
 
 
+def implicit_pointwise(C, R, S):
+    """1x1 kernels over whole 64-channel multiples take the second form of the layout."""
+    return R == 1 and S == 1 and C % 64 == 0
+
+
 def implicit_applies(N, C, H, W, K, R, S, stride, pad):
+    if implicit_pointwise(C, R, S):
+        return stride == 1 and pad == 0 and C <= 512 and (H * W) % 4 == 0
     Q = (W + 2 * pad - S) // stride + 1
     S4 = _ceil(S, 4)
     if _ceil(C * R * S4, UNIT_Z) > 256 or W < 4:
@@ -61,6 +71,8 @@ def overheads(N, C, H, W, K, R, S, stride, pad, layout, cb):
     M = N * P * Q
     mac_min = M * K * C * R * S
     if layout == IMPLICIT:
+        if implicit_pointwise(C, R, S):
+            return N * _ceil(P * Q, UNIT_X) * _ceil(K, UNIT_Y) * C - mac_min, 0, 0
         depth = _ceil(C * R * _ceil(S, 4), UNIT_Z)
         return N * P * _ceil(Q, UNIT_X) * _ceil(K, UNIT_Y) * depth - mac_min, 0, 0
     if layout == IM2COL:

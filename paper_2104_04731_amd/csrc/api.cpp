@@ -34,6 +34,7 @@ int check_desc(const conv_desc_t *d)
 
 struct Plan {
     int layout, cb, Cb, depth, P, Q, Hp, Wp;
+    int pointwise;  // IMPLICIT only: the 1x1 kernel takes it (else the window kernel)
     long long M;
     size_t x_bytes, w_bytes;
 };
@@ -43,6 +44,12 @@ WindowProblem window_problem(const conv_desc_t *d, const Plan &pl, const int8_t 
 {
     return WindowProblem{x, w, out, d->N, d->C, d->H, d->W, d->K, pl.P, pl.Q, d->R, d->S, d->stride, d->pad,
                          wt_rewritten};
+}
+
+int run_implicit(const Plan &pl, const WindowProblem &g, hipStream_t st)
+{
+    const hipError_t e = pl.pointwise ? launch_pointwise_conv(g, st) : launch_window_conv(g, st);
+    return e == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
 }
 
 int default_block(int C)
@@ -70,6 +77,7 @@ int make_plan(const conv_desc_t *d, int layout, int cb, Plan *pl)
     else return CONV_ERR_INVALID_ARG;
 
     pl->layout = layout;
+    pl->pointwise = 0;
     pl->cb = cb;
     pl->Hp = d->H + 2 * d->pad;
     pl->Wp = d->W + 2 * d->pad;
@@ -78,8 +86,10 @@ int make_plan(const conv_desc_t *d, int layout, int cb, Plan *pl)
     pl->M = (long long)d->N * pl->P * pl->Q;
     if (layout == CONV_LAYOUT_IMPLICIT) {
         pl->Cb = 0;
-        pl->depth = window_depth(d->C, d->R, d->S);
-        if (!window_fits(window_problem(d, *pl, nullptr, nullptr, nullptr, 0))) return CONV_ERR_UNSUPPORTED;
+        pl->pointwise = pointwise_shape(d->C, d->R, d->S);
+        pl->depth = pl->pointwise ? d->C : window_depth(d->C, d->R, d->S);
+        const WindowProblem wp = window_problem(d, *pl, nullptr, nullptr, nullptr, 0);
+        if (!(pl->pointwise ? pointwise_fits(wp) : window_fits(wp))) return CONV_ERR_UNSUPPORTED;
         pl->x_bytes = 0;  // nothing is rewritten: the GEMM stage reads the input and either weight form
         pl->w_bytes = 0;
         return CONV_OK;
@@ -203,7 +213,7 @@ int pack_weights_depth(int C, int R, int S, int layout, int cb)
 {
     if (C <= 0 || R <= 0 || S <= 0) return 0;
     long long real;
-    if (layout == CONV_LAYOUT_IMPLICIT) return window_depth(C, R, S);
+    if (layout == CONV_LAYOUT_IMPLICIT) return pointwise_shape(C, R, S) ? (C <= 512 ? C : 0) : window_depth(C, R, S);
     if (layout == CONV_LAYOUT_IM2COL) real = (long long)C * R * S;
     else if (layout == CONV_LAYOUT_PACKED || layout == CONV_LAYOUT_PAD_ONLY) {
         if (layout == CONV_LAYOUT_PAD_ONLY) cb = round_up_i(C, 16);
@@ -232,7 +242,9 @@ int pack_weights(int K, int C, int R, int S, int layout, int cb, const int8_t *s
     const int depth = pack_weights_depth(C, R, S, layout, cb);
     if (depth == 0) return CONV_ERR_UNSUPPORTED;
     hipError_t e;
-    if (layout == CONV_LAYOUT_IMPLICIT)
+    if (layout == CONV_LAYOUT_IMPLICIT && pointwise_shape(C, R, S))
+        e = launch_pack_weights_rows(K, C, depth, src, dst, (hipStream_t)stream);  // [K][C] as it is
+    else if (layout == CONV_LAYOUT_IMPLICIT)
         e = launch_pack_weights_window(K, C, R, S, src, dst, (hipStream_t)stream);
     else if (layout == CONV_LAYOUT_IM2COL)
         e = launch_pack_weights_rows(K, C * R * S, depth, src, dst, (hipStream_t)stream);
@@ -304,8 +316,7 @@ int conv2d_int8_packed(const conv_desc_t *desc, int layout, int cb, const int8_t
     if (pl.layout == CONV_LAYOUT_IMPLICIT) {
         if (!in_packed || !wt_packed || !out) return CONV_ERR_INVALID_ARG;
         if (tile != -1 || (split_k != 0 && split_k != 1)) return CONV_ERR_UNSUPPORTED;
-        return launch_window_conv(window_problem(desc, pl, in_packed, wt_packed, out, 1), (hipStream_t)stream) ==
-                       hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+        return run_implicit(pl, window_problem(desc, pl, in_packed, wt_packed, out, 1), (hipStream_t)stream);
     }
     if (!in_packed || !wt_packed || !out || !aligned16(in_packed) || !aligned16(wt_packed))
         return CONV_ERR_INVALID_ARG;
@@ -354,8 +365,7 @@ int conv2d_int8_ex(const conv_desc_t *desc, int layout, int cb, const int8_t *in
     if (rc != CONV_OK) return rc;
     if (!in || !wt || !out) return CONV_ERR_INVALID_ARG;
     if (pl.layout == CONV_LAYOUT_IMPLICIT)
-        return launch_window_conv(window_problem(desc, pl, in, wt, out, wt_is_packed ? 1 : 0),
-                                  (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+        return run_implicit(pl, window_problem(desc, pl, in, wt, out, wt_is_packed ? 1 : 0), (hipStream_t)stream);
     if (!workspace) return CONV_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(workspace) % WS_ALIGN) return CONV_ERR_INVALID_ARG;
     if (wt_is_packed && !aligned16(wt)) return CONV_ERR_INVALID_ARG;

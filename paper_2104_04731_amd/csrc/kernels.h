@@ -66,5 +66,10 @@ int window_depth(int C, int R, int S);          // 0 if the padded depth exceeds
 bool window_fits(const WindowProblem &g);       // depth, image width and LDS window within the kernel's limits
 hipError_t launch_window_conv(const WindowProblem &g, hipStream_t st);
 hipError_t launch_pack_weights_window(int K, int C, int R, int S, const int8_t *src, int8_t *dst, hipStream_t st);
+// The same for 1x1 convolutions over whole 64-channel multiples: a workgroup turns its pixels
+// around in LDS; the weights are used as they are ([K][C]).
+inline bool pointwise_shape(int C, int R, int S) { return R == 1 && S == 1 && C % 64 == 0; }
+bool pointwise_fits(const WindowProblem &g);    // stride 1, no padding, C <= 512, H*W a multiple of 4
+hipError_t launch_pointwise_conv(const WindowProblem &g, hipStream_t st);
 
 }  // namespace c2i8

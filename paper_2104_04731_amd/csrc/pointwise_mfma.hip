@@ -1,0 +1,165 @@
+// GEMM stage for 1x1 convolutions (stride 1, no padding) that reads NCHW itself.
+//
+// A 1x1 convolution is out[n] = W [K x C] * X[n] [C x HW]: the weights are depth-contiguous as
+// they are, but an image is depth-major, the pixels contiguous.  Channel blocking (Pad + Split +
+// Reorder of Table 2) exists to turn that around; here a workgroup turns its own 32 pixels
+// around in LDS instead, so nothing rewritten is stored and the layer is one launch.
+//
+// One workgroup (4 waves) = 32 consecutive pixels of one image x 128 output channels:
+//   1. each wave fetches the MFMA weight operands of its 32 output channels straight into
+//      registers (16 bytes of row lane%32 per 32-deep step; rows are 16-byte multiples);
+//   2. a thread fetches four channel rows x four pixels (one dword each), transposes the 4x4
+//      bytes with eight v_perm_b32 and writes each pixel's four channels into the LDS tile
+//      XT[pixel][channel] (pitch C + 16 bytes: 32 rows start in different bank groups);
+//   3. v_mfma_i32_32x32x32_i8, channels x pixels, activation operand = 16 bytes of XT row lane%32;
+//   4. the D block (column = pixel = lane%32) goes straight to NKPQ in 128-byte runs.
+// All global loads of a thread are issued before its first LDS store.
+#include "kernels.h"
+#include "rewrite_bodies.h"
+
+namespace c2i8 {
+
+namespace {
+
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+struct PointArgs {
+    const int8_t *in;
+    const int8_t *wt;
+    int32_t *out;
+    int C, HW, K, tiles;  // tiles of 32 pixels per image
+    unsigned m_tiles;
+};
+
+__device__ __forceinline__ unsigned ld_u32(const void *p)  // any alignment
+{
+    unsigned x;
+    __builtin_memcpy(&x, p, 4);
+    return x;
+}
+__device__ __forceinline__ v4i ld_v4(const void *p)  // any alignment
+{
+    v4i x;
+    __builtin_memcpy(&x, p, 16);
+    return x;
+}
+
+template <int NKK>  // C = 32 * NKK
+__global__ void __launch_bounds__(256) conv_pointwise_kernel(const PointArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int C = 32 * NKK, PITCH = C + 16;
+    constexpr int QUADS = C / 4;                  // groups of four channels
+    constexpr int PASSES = (QUADS + 31) / 32;     // 256 threads = 8 pixel groups x 32 quads per pass
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l31 = lane & 31, half = lane >> 5;
+    const int lid = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int n = fast_div_any(lid, a.tiles, a.m_tiles), px0 = (lid - n * a.tiles) * 32;
+    const int k0 = blockIdx.y * 128 + wave * 32;
+
+    // 1. weights (waves past the last output channel compute on row K-1 and store nothing)
+    v4i wf[NKK];
+    {
+        const int8_t *row = a.wt + (size_t)min(k0 + l31, a.K - 1) * C + half * 16;
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) wf[kk] = ld_v4(row + kk * 32);
+    }
+    // 2. activations: pixels px0 + 4g .. +3 (HW is a multiple of 4: a group is inside the image or past it)
+    const int g = tid & 7, cq = tid >> 3;
+    const int px = min(px0 + 4 * g, a.HW - 4);
+    const int8_t *img = a.in + (size_t)n * C * a.HW + px;
+    unsigned xv[PASSES][4];
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) {
+        const int q = min(cq + 32 * ps, QUADS - 1);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) xv[ps][j] = ld_u32(img + (size_t)(4 * q + j) * a.HW);
+    }
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) {
+        const int q = cq + 32 * ps;
+        if (q < QUADS) {
+            // rows = channels 4q .. 4q+3, bytes = pixels: out_i = byte i of each row
+            const unsigned lo01 = __builtin_amdgcn_perm(xv[ps][1], xv[ps][0], 0x05010400u);
+            const unsigned hi01 = __builtin_amdgcn_perm(xv[ps][1], xv[ps][0], 0x07030602u);
+            const unsigned lo23 = __builtin_amdgcn_perm(xv[ps][3], xv[ps][2], 0x05010400u);
+            const unsigned hi23 = __builtin_amdgcn_perm(xv[ps][3], xv[ps][2], 0x07030602u);
+            unsigned *dst = reinterpret_cast<unsigned *>(smem + (4 * g) * PITCH + 4 * q);
+            dst[0 * PITCH / 4] = __builtin_amdgcn_perm(lo23, lo01, 0x05040100u);
+            dst[1 * PITCH / 4] = __builtin_amdgcn_perm(lo23, lo01, 0x07060302u);
+            dst[2 * PITCH / 4] = __builtin_amdgcn_perm(hi23, hi01, 0x05040100u);
+            dst[3 * PITCH / 4] = __builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
+        }
+    }
+    __syncthreads();
+
+    // 3. MFMA
+    v16i acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0;
+    const unsigned char *xrow = smem + l31 * PITCH + half * 16;
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) {
+        const v4i xf = *reinterpret_cast<const v4i *>(xrow + kk * 32);
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[kk], xf, acc, 0, 0, 0);
+    }
+
+    // 4. D block: column = lane%32 = pixel, row = 8*(v/4) + 4*(lane/32) + v%4 = channel
+    const int p = px0 + l31;
+    if (p >= a.HW) return;
+    int32_t *base = a.out + ((size_t)n * a.K + k0 + 4 * half) * a.HW + p;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int kr = 8 * (v >> 2) + (v & 3);
+        if (k0 + 4 * half + kr < a.K) base[(size_t)kr * a.HW] = acc[v];
+    }
+}
+
+template <int NKK>
+hipError_t launch_nkk(const PointArgs &a, dim3 grid, hipStream_t st)
+{
+    hipLaunchKernelGGL((conv_pointwise_kernel<NKK>), grid, dim3(256), (size_t)32 * (32 * NKK + 16), st, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool pointwise_fits(const WindowProblem &g)
+{
+    if (g.R != 1 || g.S != 1 || g.stride != 1 || g.pad != 0) return false;
+    if (g.C % 64 != 0 || g.C > 512) return false;
+    const long long HW = (long long)g.H * g.W;
+    if (HW % 4 != 0 || HW > 2147483647LL) return false;
+    const long long tiles = (HW + 31) / 32;
+    return (long long)g.N * tiles <= 2147483647LL && (g.K + 127) / 128 <= 65535;
+}
+
+hipError_t launch_pointwise_conv(const WindowProblem &g, hipStream_t st)
+{
+    if (!pointwise_fits(g)) return hipErrorInvalidValue;
+    PointArgs a{};
+    a.in = g.in;
+    a.wt = g.wt;
+    a.out = g.out;
+    a.C = g.C;
+    a.HW = g.H * g.W;
+    a.K = g.K;
+    a.tiles = (a.HW + 31) / 32;
+    a.m_tiles = magic_for(a.tiles);
+    const dim3 grid((unsigned)(g.N * a.tiles), (unsigned)((g.K + 127) / 128));
+    switch (g.C / 32) {
+        case 2: return launch_nkk<2>(a, grid, st);
+        case 4: return launch_nkk<4>(a, grid, st);
+        case 6: return launch_nkk<6>(a, grid, st);
+        case 8: return launch_nkk<8>(a, grid, st);
+        case 10: return launch_nkk<10>(a, grid, st);
+        case 12: return launch_nkk<12>(a, grid, st);
+        case 14: return launch_nkk<14>(a, grid, st);
+        case 16: return launch_nkk<16>(a, grid, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace c2i8

@@ -38,9 +38,13 @@ extern "C" int layout_overheads(const conv_desc_t *d, int layout, int cb,
         if (P > 2147483647LL || Q > 2147483647LL) return CONV_ERR_UNSUPPORTED;
         const c2i8::WindowProblem g{nullptr, nullptr, nullptr, d->N, d->C, d->H, d->W, d->K, (int)P, (int)Q,
                                     d->R, d->S, d->stride, d->pad, 0};
-        if (!c2i8::window_fits(g)) return CONV_ERR_UNSUPPORTED;
-        const int64_t depth = round_up((int64_t)d->C * d->R * round_up(d->S, 4), UNIT_DEPTH);
-        const int64_t mac_total = (int64_t)d->N * P * round_up(Q, UNIT_PIXELS) * round_up(d->K, UNIT_CHANNELS) * depth;
+        const bool pointwise = c2i8::pointwise_shape(d->C, d->R, d->S);
+        if (!(pointwise ? c2i8::pointwise_fits(g) : c2i8::window_fits(g))) return CONV_ERR_UNSUPPORTED;
+        // 1x1 over whole 64-channel multiples: pixels padded per image, depth as it is
+        const int64_t depth = pointwise ? d->C : round_up((int64_t)d->C * d->R * round_up(d->S, 4), UNIT_DEPTH);
+        const int64_t pixels = pointwise ? (int64_t)d->N * round_up(P * Q, UNIT_PIXELS)
+                                         : (int64_t)d->N * P * round_up(Q, UNIT_PIXELS);
+        const int64_t mac_total = pixels * round_up(d->K, UNIT_CHANNELS) * depth;
         if (o_mac) *o_mac = mac_total - mac_min;
         if (o_data) *o_data = 0;
         if (rewritten) *rewritten = 0;

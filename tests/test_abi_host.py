@@ -104,7 +104,9 @@ def test_ex_and_packed_validation(lib):
 
 IMPLICIT_DOMAIN = [(1, 1, 8, 3, 4, 3, 3, 1, 1), (1, 16, 64, 4000, 4, 4, 4, 40, 0), (1, 1, 64, 4000, 4, 4, 4, 40, 0),
                    (1, 16, 9, 9, 8, 4, 4, 1, 0), (1, 17, 9, 9, 8, 4, 4, 1, 0), (2, 3, 40, 40, 8, 3, 3, 2, 1),
-                   (1, 4, 30, 70, 8, 5, 5, 3, 2), (1, 64, 8, 200, 8, 1, 1, 5, 0), (1, 2, 300, 9, 8, 30, 4, 1, 0)]
+                   (1, 4, 30, 70, 8, 5, 5, 3, 2), (1, 64, 8, 200, 8, 1, 1, 5, 0), (1, 2, 300, 9, 8, 30, 4, 1, 0),
+                   (2, 64, 6, 6, 8, 1, 1, 1, 0), (2, 512, 14, 14, 128, 1, 1, 1, 0), (1, 576, 4, 4, 8, 1, 1, 1, 0),
+                   (1, 128, 5, 5, 8, 1, 1, 1, 0), (1, 128, 6, 6, 8, 1, 1, 1, 1), (1, 32, 6, 6, 8, 1, 1, 1, 0)]
 
 
 @pytest.mark.parametrize("dims", IMPLICIT_DOMAIN + [c.dims() for c in ALL_SHAPES], ids=str)
@@ -123,8 +125,12 @@ def test_gemm_stage_unroll_domain_and_sizes(lib, dims):
         assert lib.conv2d_int8_workspace_bytes(dims, lib.LAYOUT_IMPLICIT, 0) == 0
         assert lib.query_tiling(dims, lib.LAYOUT_IMPLICIT, 0) == (-1, 1)
         assert not lib.tile_applies(dims, lib.LAYOUT_IMPLICIT, 0, 0, 1)
-    S4 = -(-S // 4) * 4
-    depth = -(-C * R * S4 // 64) * 64
-    assert lib.pack_weights_depth(C, R, S, lib.LAYOUT_IMPLICIT, 0) == (depth if depth <= 256 else 0)
+    if sel.implicit_pointwise(C, R, S):
+        depth, limit = C, 512
+    else:
+        depth, limit = -(-C * R * (-(-S // 4) * 4) // 64) * 64, 256
+    assert lib.pack_weights_depth(C, R, S, lib.LAYOUT_IMPLICIT, 0) == (depth if depth <= limit else 0)
+    if depth <= limit:
+        assert layouts.pack_weights_implicit(np.zeros((2, C, R, S), np.int8)).shape == (2, depth)
     for w in [(1.0, 1.0), (0.0, 1.0), (1.0 / 0.6e15, 1.0 / 4.0e12)]:
         assert lib.select_layout(dims, *w)[:2] == sel.select(*dims, *w)[:2]

@@ -404,6 +404,10 @@ IMPLICIT_SHAPES = [
     ConvShape("wide-kernel", 1, 2, 6, 40, 9, 2, 9, 3, 4), ConvShape("deep-256", 1, 16, 8, 19, 40, 4, 4, 1, 2),
     ConvShape("one-pixel-out", 1, 3, 7, 7, 2, 7, 7, 1, 0), ConvShape("big-pad", 1, 1, 5, 6, 4, 3, 3, 2, 5),
     ConvShape("one-weight", 1, 1, 4, 4, 1, 1, 1, 1, 0),
+    # 1x1 over whole 64-channel multiples (pixels turned around in LDS): ragged pixel and channel ends
+    ConvShape("pw-64", 2, 64, 6, 6, 8, 1, 1, 1, 0), ConvShape("pw-192", 3, 192, 10, 14, 130, 1, 1, 1, 0),
+    ConvShape("pw-512", 1, 512, 2, 2, 33, 1, 1, 1, 0), ConvShape("pw-320", 2, 320, 8, 16, 256, 1, 1, 1, 0),
+    ConvShape("pw-448-wide", 1, 448, 1, 100, 5, 1, 1, 1, 0),
 ]
 
 

@@ -121,3 +121,9 @@ def test_row_padded_weights_give_the_convolution(dims):
     # the true weights, each once, in (c, r, s) order; zeros elsewhere
     assert np.count_nonzero(B) == np.count_nonzero(w)
     np.testing.assert_array_equal(B[:, :C * R * S4].reshape(K, C * R, S4)[:, :, :S].reshape(K, C, R, S), w)
+
+
+def test_pointwise_weights_are_the_weights():
+    w = uniform_int8(68, (5, 128, 1, 1))
+    np.testing.assert_array_equal(layouts.pack_weights_implicit(w), w.reshape(5, 128))
+    assert layouts.pack_weights_implicit(uniform_int8(69, (5, 32, 1, 1))).shape == (5, 128)   # 32 channels: padded taps

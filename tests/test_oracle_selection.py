@@ -74,9 +74,10 @@ def test_unrolling_inside_the_gemm_stage_moves_nothing_twice():
 def test_domain_of_unrolling_inside_the_gemm_stage():
     assert sel.implicit_applies(*CONFIGS["C3"].dims()) and sel.implicit_applies(*CONFIGS["C5"].dims())
     assert sel.implicit_applies(*CONFIGS["C1"].dims())                       # 16*3*4 = 192 deep
-    for name in ("C2", "C4a", "C4b"):                                         # 768, 3072, 2048 deep
+    for name in ("C2", "C4a"):                                                # 768, 3072 deep
         assert not sel.implicit_applies(*CONFIGS[name].dims())
         assert (sel.IMPLICIT, 0) not in sel.candidates(CONFIGS[name].C, CONFIGS[name].dims())
+    assert sel.implicit_applies(*CONFIGS["C4b"].dims())                      # 1x1 form: depth = C = 512
     assert not sel.implicit_applies(1, 1, 8, 3, 4, 3, 3, 1, 1)                # three-pixel rows
     assert not sel.implicit_applies(1, 16, 64, 4000, 4, 4, 4, 40, 0)          # 16 channels x 4 rows x 5 KB
     assert sel.implicit_applies(1, 1, 64, 4000, 4, 4, 4, 40, 0)
@@ -88,3 +89,18 @@ def test_hardware_weights_send_low_channel_layers_to_the_gemm_stage_unroll():
     for name in ("C3", "C5"):
         assert sel.select(*CONFIGS[name].dims(), 1.0 / 0.6e15, 1.0 / 4.0e12)[0] == sel.IMPLICIT
         assert sel.select(*CONFIGS[name].dims(), 1.0, 1.0)[0] == sel.IM2COL
+
+
+def test_pointwise_form_of_the_gemm_stage_unroll():
+    """1x1 over whole 64-channel multiples: no kernel-row padding, pixels padded per image."""
+    N, C, H, W, K = 8, 512, 14, 14, 128
+    o_mac, o_data, rewritten = sel.overheads(N, C, H, W, K, 1, 1, 1, 0, sel.IMPLICIT, 0)
+    assert (o_data, rewritten) == (0, 0)
+    assert o_mac == N * (224 - 196) * K * C                        # 196 pixels issued as 7 x 32
+    assert sel.overheads(2, 64, 8, 8, 32, 1, 1, 1, 0, sel.IMPLICIT, 0)[0] == 0
+    for dims in [(1, 128, 6, 6, 8, 1, 1, 2, 0), (1, 128, 6, 6, 8, 1, 1, 1, 1), (1, 576, 4, 4, 8, 1, 1, 1, 0),
+                 (1, 128, 5, 5, 8, 1, 1, 1, 0)]:                   # stride, padding, depth, pixel count
+        assert not sel.implicit_applies(*dims)
+    # the hardware weights prefer it to channel blocking (nothing moved twice); w = [1,1] does not
+    assert sel.select(*CONFIGS["C4b"].dims(), 1.0 / 0.6e15, 1.0 / 4.0e12)[0] == sel.IMPLICIT
+    assert sel.select(*CONFIGS["C4b"].dims(), 1.0, 1.0)[0] == sel.PACKED
