@@ -3,7 +3,8 @@
 
     python bench.py [--gpus 1] [--steps 200] [--warmup 10] [--workload C4] [--no-extras]
 
-A step is one pass of the whole path -- input rewrite, weight rewrite, GEMM stage -- over the
+A step is one pass of the whole path -- input rewrite, weight rewrite, GEMM stage, or for the
+shapes where the library picks it the GEMM stage that applies the rewrite itself -- over the
 headline workload, through the one-shot C-ABI call, inputs resident in HBM.  One JSON line is
 printed; `value` is effective int8 TOPS = 2*N*K*P*Q*C*R*S / time with the unpadded op count.
 `per_config` carries, for every benchmark configuration, the operator-only, transform-only
@@ -146,6 +147,7 @@ def main():
                 "pct_mfma_peak_op": round(100 * cfg.ops / (op * 1e-3) / PEAK_INT8_OPS, 3),
                 "transf_in_GBps": round(self.rewrite_bytes / (tr * 1e-3) / 1e9, 1) if tr else None,
                 "pct_hbm_peak_transf": round(100 * self.rewrite_bytes / (tr * 1e-3) / PEAK_HBM_BPS, 2) if tr else None,
+                "combined_GBps": round((self.x.numel() + self.w.numel() + 4 * self.out.numel()) / (comb * 1e-3) / 1e9, 1),
             }
 
     if args.calibration_copy:
@@ -191,7 +193,8 @@ def main():
         "config": {"workload": " + ".join(
             f"{c.cfg.name}: N={c.cfg.N} C={c.cfg.C} H={c.cfg.H} W={c.cfg.W} K={c.cfg.K} "
             f"{c.cfg.R}x{c.cfg.S} stride {c.cfg.stride} pad {c.cfg.pad}" for c in head),
-            "path": "conv2d_int8 one-shot (input rewrite + weight rewrite + GEMM stage)",
+            "path": "conv2d_int8 one-shot, layout picked per shape: input rewrite + weight rewrite + GEMM stage, "
+                    "or (implicit) the rewrite applied inside the GEMM stage",
             "layouts": [lib.LAYOUT_NAMES[c.layout] + (f"/cb{c.cb}" if c.cb else "") for c in head]},
         "event_ms_per_step": round(ev_ms, 6),
         "pct_mfma_peak": round(100 * value * 1e12 / PEAK_INT8_OPS, 3),
@@ -251,6 +254,23 @@ def n_scaled(lib, timed, CONFIGS, dev):
     b = x.numel() + xp.numel()
     out["im2col_C3_N512"] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),
                               "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2)}
+    del x, xp
+    # the stencil-unrolling GEMM stage (whole convolution, one launch, nothing rewritten): the 7x7 stem at
+    # N=512 and the 1x1 layer at N=2048; bytes = input + weights + int32 output, each once
+    for key, name, scale in (("implicit_conv_C3_N512", "C3", 512), ("implicit_conv_C4b_N2048", "C4b", 2048)):
+        cfg = CONFIGS[name].scaled(scale)
+        x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=dev)
+        w = torch.randint(-128, 128, (cfg.K, cfg.C, cfg.R, cfg.S), dtype=torch.int8, device=dev)
+        o = torch.empty((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=dev)
+        _, ms = timed(lambda: lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_IMPLICIT, 0, x, w, o, None), 10, 2)
+        b = x.numel() + w.numel() + 4 * o.numel()
+        out[key] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),
+                    "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2),
+                    "tops": round(cfg.ops / (ms * 1e-3) / 1e12, 2)}
+        del x, w, o
+    cfg = CONFIGS["C3"].scaled(512)
+    x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=dev)
+    xp = lib.im2col_int8(x, cfg.R, cfg.S, cfg.stride, cfg.pad)
     # a plain device-to-device copy of the same size, for scale
     y = torch.empty_like(xp)
     _, ms = timed(lambda: y.copy_(xp), 10, 2)

@@ -28,6 +28,7 @@ struct PointArgs {
     const int8_t *wt;
     int32_t *out;
     int C, HW, K, tiles;  // tiles of 32 pixels per image
+    int ntiles;           // N * tiles
     unsigned m_tiles;
 };
 
@@ -55,8 +56,6 @@ __global__ void __launch_bounds__(256) conv_pointwise_kernel(const PointArgs a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l31 = lane & 31, half = lane >> 5;
-    const int lid = xcd_contiguous(blockIdx.x, gridDim.x);
-    const int n = fast_div_any(lid, a.tiles, a.m_tiles), px0 = (lid - n * a.tiles) * 32;
     const int k0 = blockIdx.y * 128 + wave * 32;
 
     // 1. weights (waves past the last output channel compute on row K-1 and store nothing)
@@ -66,8 +65,11 @@ __global__ void __launch_bounds__(256) conv_pointwise_kernel(const PointArgs a)
 #pragma unroll
         for (int kk = 0; kk < NKK; ++kk) wf[kk] = ld_v4(row + kk * 32);
     }
-    // 2. activations: pixels px0 + 4g .. +3 (HW is a multiple of 4: a group is inside the image or past it)
+    // A workgroup keeps its weight operands in registers and walks over pixel tiles gridDim.x apart.
     const int g = tid & 7, cq = tid >> 3;
+    for (int lid = xcd_contiguous(blockIdx.x, gridDim.x); lid < a.ntiles; lid += gridDim.x) {
+    const int n = fast_div_any(lid, a.tiles, a.m_tiles), px0 = (lid - n * a.tiles) * 32;
+    // 2. activations: pixels px0 + 4g .. +3 (HW is a multiple of 4: a group is inside the image or past it)
     const int px = min(px0 + 4 * g, a.HW - 4);
     const int8_t *img = a.in + (size_t)n * C * a.HW + px;
     unsigned xv[PASSES][4];
@@ -108,12 +110,16 @@ __global__ void __launch_bounds__(256) conv_pointwise_kernel(const PointArgs a)
 
     // 4. D block: column = lane%32 = pixel, row = 8*(v/4) + 4*(lane/32) + v%4 = channel
     const int p = px0 + l31;
-    if (p >= a.HW) return;
-    int32_t *base = a.out + ((size_t)n * a.K + k0 + 4 * half) * a.HW + p;
+    if (p < a.HW) {
+        int32_t *base = a.out + ((size_t)n * a.K + k0 + 4 * half) * a.HW + p;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int kr = 8 * (v >> 2) + (v & 3);
-        if (k0 + 4 * half + kr < a.K) base[(size_t)kr * a.HW] = acc[v];
+        for (int v = 0; v < 16; ++v) {
+            const int kr = 8 * (v >> 2) + (v & 3);
+            if (k0 + 4 * half + kr < a.K) base[(size_t)kr * a.HW] = acc[v];
+        }
+    }
+    if (lid + (int)gridDim.x >= a.ntiles) break;
+    __syncthreads();  // the next tile's pixels replace these in LDS
     }
 }
 
@@ -148,7 +154,11 @@ hipError_t launch_pointwise_conv(const WindowProblem &g, hipStream_t st)
     a.K = g.K;
     a.tiles = (a.HW + 31) / 32;
     a.m_tiles = magic_for(a.tiles);
-    const dim3 grid((unsigned)(g.N * a.tiles), (unsigned)((g.K + 127) / 128));
+    a.ntiles = g.N * a.tiles;
+    const int kgroups = (g.K + 127) / 128;
+    int wgs = 256 * 4 / kgroups;  // about four workgroups fit a CU
+    if (wgs < 256) wgs = 256;
+    const dim3 grid((unsigned)(a.ntiles < wgs ? a.ntiles : wgs), (unsigned)kgroups);
     switch (g.C / 32) {
         case 2: return launch_nkk<2>(a, grid, st);
         case 4: return launch_nkk<4>(a, grid, st);

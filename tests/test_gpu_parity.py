@@ -327,6 +327,23 @@ def test_batch_scaled_layout_kernels_sampled_images(lib):
         assert np.array_equal(host(a[n * per:(n + 1) * per]), want), n
 
 
+def test_batch_scaled_implicit_sampled_images(lib):
+    """The stencil-unrolling GEMM stage at the batch sizes the benchmark times (C3 at N=512, C4b at
+    N=2048): whole output planes of sampled images against the direct convolution of those images."""
+    g = torch.Generator(device=DEV); g.manual_seed(4244)
+    for name, scale in (("C3", 512), ("C4b", 2048)):
+        cfg = CONFIGS[name].scaled(scale)
+        x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=DEV, generator=g)
+        w = torch.randint(-128, 128, (cfg.K, cfg.C, cfg.R, cfg.S), dtype=torch.int8, device=DEV, generator=g)
+        out = torch.empty((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=DEV)
+        lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_IMPLICIT, 0, x, w, out, None)
+        wh = host(w)
+        for n in _sample_images(cfg.N):
+            want = direct.conv2d_int8(host(x[n:n + 1]), wh, cfg.stride, cfg.pad)
+            assert np.array_equal(host(out[n:n + 1]), want), (name, n)
+        del x, out
+
+
 # ---- the one-shot path called repeatedly and under graph replay ------------------------------------
 def test_one_shot_back_to_back_and_mixed_shapes(lib):
     """Consecutive one-shot calls share the library's cached workspace: alternate shapes and layouts,
