@@ -13,6 +13,10 @@ numpy slicing; no blocking or fusion beyond what the map itself states.
                 first padded to a multiple of four taps).
   im2col        Stencil Unroll + Fuse (Table 2 rows 1 and 5; "im2col" in Sec. 6.2).
   gemm_nt       the matrix unit of Sec. 5.1: C[x][y] += sum_z A[x][z] * B[y][z].
+  image_pack    Image Pack of Table 2 (row 1, the alternative to Stencil Unroll for strides
+                above one: [N, I] => [N*s, I/s] with the access function unchanged): the s*s
+                stride phases of the padded image become channels, and a stride-s convolution
+                becomes a stride-1 convolution with the kernel phase-split the same way.
 """
 from __future__ import annotations
 
@@ -92,3 +96,43 @@ def gemm_nt(A: np.ndarray, B: np.ndarray) -> np.ndarray:
     C = A.astype(np.int64) @ B.astype(np.int64).T
     assert np.all(np.abs(C) < 2 ** 31)
     return C.astype(np.int32)
+
+
+def image_pack_dims(N, C, H, W, K, R, S, stride, pad):
+    """The stride-1, pad-0 problem an image-packed convolution turns into."""
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    R2, S2 = -(-R // stride), -(-S // stride)
+    return (N, C * stride * stride, P + R2 - 1, Q + S2 - 1, K, R2, S2, 1, 0)
+
+
+def image_pack(x: np.ndarray, R: int, S: int, stride: int, pad: int) -> np.ndarray:
+    """[N,C,H,W] -> [N, C*s*s, H2, W2]; X2[n][(c*s + a)*s + b][i][j] = x0[n][c][s*i + a][s*j + b]
+    with x0 the zero-padded image continued by zeros."""
+    N, C, H, W = x.shape
+    s = stride
+    _, C2, H2, W2, _, _, _, _, _ = image_pack_dims(N, C, H, W, 1, R, S, stride, pad)
+    x0 = np.zeros((N, C, max(H + 2 * pad, s * H2), max(W + 2 * pad, s * W2)), dtype=x.dtype)
+    x0[:, :, pad:pad + H, pad:pad + W] = x
+    y = np.zeros((N, C2, H2, W2), dtype=x.dtype)
+    for c in range(C):
+        for a in range(s):
+            for b in range(s):
+                y[:, (c * s + a) * s + b] = x0[:, c, a:a + s * H2:s, b:b + s * W2:s]
+    return y
+
+
+def image_pack_weights(w: np.ndarray, stride: int) -> np.ndarray:
+    """[K,C,R,S] -> [K, C*s*s, ceil(R/s), ceil(S/s)]; W2[k][(c*s + a)*s + b][r][t] = w[k][c][s*r + a][s*t + b],
+    zero where s*r + a >= R or s*t + b >= S."""
+    K, C, R, S = w.shape
+    s = stride
+    R2, S2 = -(-R // s), -(-S // s)
+    w0 = np.zeros((K, C, s * R2, s * S2), dtype=w.dtype)
+    w0[:, :, :R, :S] = w
+    y = np.zeros((K, C * s * s, R2, S2), dtype=w.dtype)
+    for c in range(C):
+        for a in range(s):
+            for b in range(s):
+                y[:, (c * s + a) * s + b] = w0[:, c, a::s, b::s]
+    return y

@@ -127,3 +127,32 @@ def test_pointwise_weights_are_the_weights():
     w = uniform_int8(68, (5, 128, 1, 1))
     np.testing.assert_array_equal(layouts.pack_weights_implicit(w), w.reshape(5, 128))
     assert layouts.pack_weights_implicit(uniform_int8(69, (5, 32, 1, 1))).shape == (5, 128)   # 32 channels: padded taps
+
+
+@pytest.mark.parametrize("dims", [(2, 3, 9, 9, 4, 7, 7, 2, 3), (1, 1, 23, 12, 3, 20, 5, 2, 0), (1, 2, 10, 11, 3, 3, 3, 3, 1),
+                                  (1, 4, 8, 8, 2, 2, 2, 2, 0), (2, 2, 7, 9, 3, 1, 1, 2, 0), (1, 3, 12, 10, 2, 5, 4, 3, 2),
+                                  (1, 2, 6, 6, 2, 3, 3, 1, 1), (1, 1, 9, 9, 1, 4, 4, 4, 0)])
+def test_image_pack_turns_a_strided_convolution_into_a_dense_one(dims):
+    """Image Pack (Table 2): stride phases become channels; the stride-1 convolution of the packed
+    image with the phase-split kernel is the strided convolution."""
+    N, C, H, W, K, R, S, st, pad = dims
+    x = uniform_int8(70, (N, C, H, W)); w = uniform_int8(71, (K, C, R, S))
+    x2 = layouts.image_pack(x, R, S, st, pad); w2 = layouts.image_pack_weights(w, st)
+    d2 = layouts.image_pack_dims(*dims)
+    assert x2.shape == d2[:4] and w2.shape == (K, d2[1], d2[5], d2[6]) and d2[7:] == (1, 0)
+    np.testing.assert_array_equal(direct.conv2d_int8(x2, w2, 1, 0), direct.conv2d_int8(x, w, st, pad))
+    # every weight appears exactly once; the packed image holds every input byte a window can touch
+    assert np.count_nonzero(w2) == np.count_nonzero(w)
+    assert sorted(np.abs(w2[w2 != 0]).tolist()) == sorted(np.abs(w[w != 0]).tolist())
+
+
+def test_image_pack_elementwise_small():
+    N, C, H, W, R, S, st, pad = 1, 2, 7, 8, 3, 5, 2, 1
+    x = (np.arange(N * C * H * W) % 120 + 1).astype(np.int8).reshape(N, C, H, W); xl = x.tolist()
+    y = layouts.image_pack(x, R, S, st, pad)
+    _, C2, H2, W2 = y.shape
+    assert (C2, H2, W2) == (C * 4, 4 + 2 - 1, 3 + 3 - 1)       # P=4, Q=3, R2=2, S2=3
+    for c, a, b, i, j in itertools.product(range(C), range(st), range(st), range(H2), range(W2)):
+        h, wcol = st * i + a - pad, st * j + b - pad
+        want = xl[0][c][h][wcol] if (0 <= h < H and 0 <= wcol < W) else 0
+        assert y[0, (c * st + a) * st + b, i, j] == want
