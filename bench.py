@@ -299,6 +299,13 @@ def n_scaled(lib, timed, CONFIGS, dev):
     cfg = CONFIGS["C3"].scaled(512)
     x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=dev)
     xp = lib.im2col_int8(x, cfg.R, cfg.S, cfg.stride, cfg.pad)
+    # Image Pack of the same stem (stride phases to channels): bytes = input + packed image
+    x2 = lib.image_pack_int8(cfg.dims(), x)
+    _, ms = timed(lambda: lib.image_pack_int8(cfg.dims(), x, out=x2), 10, 2)
+    b = x.numel() + x2.numel()
+    out["image_pack_C3_N512"] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),
+                                 "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2)}
+    del x2
     # a plain device-to-device copy of the same size, for scale
     y = torch.empty_like(xp)
     _, ms = timed(lambda: y.copy_(xp), 10, 2)

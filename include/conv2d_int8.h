@@ -52,7 +52,7 @@ typedef enum {
     CONV_LAYOUT_PACKED = 1,   /* Pad + Split + Reorder: [N][ceil(C/cb)][H+2pad][W+2pad][cb] */
     CONV_LAYOUT_IM2COL = 2,   /* Stencil Unroll + Fuse: [N*P*Q][depth], depth index (c,r,s) */
     CONV_LAYOUT_PAD_ONLY = 3, /* Pad only: one block cb = ceil(C,16), i.e. [N][H+2pad][W+2pad][cb] */
-    CONV_LAYOUT_IMPLICIT = 4  /* Stencil Unroll + Fuse applied inside the GEMM stage: the input stays NCHW,
+    CONV_LAYOUT_IMPLICIT = 4, /* Stencil Unroll + Fuse applied inside the GEMM stage: the input stays NCHW,
                                  nothing rewritten is stored; depth index (c, r, s) with every kernel row
                                  padded to S4 = ceil(S,4) taps.  Exists for the low-channel layers whose
                                  unrolled matrix is many times the input (Sec. 6.2); applies when
@@ -63,6 +63,14 @@ typedef enum {
                                  it (a workgroup turns its 32 pixels into depth-contiguous rows in LDS;
                                  depth index c, weights as they are): stride 1, pad 0, C <= 512 and
                                  H*W % 4 == 0.  Outside these domains: CONV_ERR_UNSUPPORTED. */
+    CONV_LAYOUT_IMAGE_PACK = 5 /* Image Pack (Table 2 row 1, for strides s > 1): the s*s stride phases of the
+                                 zero-padded image become channels, the kernel is split the same way, and the
+                                 convolution becomes the stride-1, pad-0 problem of image_pack_desc, which
+                                 then runs in an inner layout: cb = 0 -> IMPLICIT, cb = 16/32/64 -> PACKED
+                                 with that block.  Accepted by conv2d_int8_ex, conv2d_int8_workspace_bytes,
+                                 layout_overheads and the selectors only (two rewrites in a row are not one
+                                 GEMM-stage operand); stride 1 or an inner layout that does not apply:
+                                 CONV_ERR_UNSUPPORTED. */
 } conv_layout_t;
 
 typedef struct {
@@ -143,6 +151,18 @@ int im2col_int8(int N, int C, int H, int W, int R, int S, int stride, int pad, i
                 const int8_t *src, int8_t *dst, void *stream);
 size_t im2col_bytes(int N, int C, int H, int W, int R, int S, int stride, int pad, int kg_pad);
 
+/* image_pack_int8 / image_pack_weights (Table 2 row 1, Image Pack: [N, I] => [N*s, I/s]):
+ *   packed problem (image_pack_desc): N, C2 = C*s*s, H2 = P + R2 - 1, W2 = Q + S2 - 1, K,
+ *   R2 = ceil(R/s), S2 = ceil(S/s), stride 1, pad 0 -- its output is the output of `desc`.
+ *   dst[n][(c*s + a)*s + b][i][j] = in0[n][c][s*i + a - pad][s*j + b - pad]      (a, b < s; 0 outside the image)
+ *   wdst[k][(c*s + a)*s + b][r][t] = wt[k][c][s*r + a][s*t + b]                   (0 where s*r + a >= R or s*t + b >= S)
+ *   stride 1: CONV_ERR_UNSUPPORTED.  dst must be 4-byte aligned. */
+int image_pack_desc(const conv_desc_t *desc, conv_desc_t *packed);
+size_t image_pack_bytes(const conv_desc_t *desc);
+size_t image_pack_weights_bytes(const conv_desc_t *desc);
+int image_pack_int8(const conv_desc_t *desc, const int8_t *src, int8_t *dst, void *stream);
+int image_pack_weights(const conv_desc_t *desc, const int8_t *src, int8_t *dst, void *stream);
+
 /* ---- the matrix intrinsic on its own (Sec. 5.1: C[x][y] += sum_z A[x][z] * B[y][z]) ----
  * A [X][Z], B [Y][Z] int8 row-major (both depth-contiguous, i.e. B is used transposed),
  * Cout [X][Y] int32, overwritten.  Z must be a multiple of 64. */
@@ -156,7 +176,9 @@ int gemm_int8_nt(int X, int Y, int Z, const int8_t *A, const int8_t *B, int32_t 
  * Candidates: PACKED with cb in {64,32,16}, IM2COL, PAD_ONLY, and IMPLICIT where it applies
  * (no rewritten elements, O_Data = 0; MAC_total = N*P*ceil(Q,32) * ceil(K,32) * ceil(C*R*S4,64):
  * pixels are padded per output row, kernel rows to S4; in its 1x1 form
- * MAC_total = N*ceil(P*Q,32) * ceil(K,32) * C).  Ties: fewer rewritten
+ * MAC_total = N*ceil(P*Q,32) * ceil(K,32) * C), and for strides above one IMAGE_PACK with inner
+ * cb in {0,16,32,64} (the inner layout's terms on the packed problem, measured against the MACs
+ * of the original definition, plus 2*(|X2| + |W2|) moved elements for the pack itself).  Ties: fewer rewritten
  * elements, then lower layout code, then larger cb.  select_layout uses the library's
  * MI355X weights (seconds per MAC and per byte); the paper's case studies use w = [1,1]. */
 int select_layout(const conv_desc_t *desc, int *layout, int *cb, double *score);

@@ -27,10 +27,12 @@ ceil((QT-1)*stride + S4 + 3, 4) bytes, PT x QT = 1x128 if Q > 64, 2x64 if Q > 32
 form (pixels of an image turned into depth-contiguous rows on the fly, weights as they
 are): stride 1, no padding, C <= 512, H*W a multiple of 4;
                MAC_total = N*ceil(P*Q,x) * ceil(K,y) * C.
+For strides above one, Image Pack (Table 2: the stride phases become channels) followed by
+one of the stride-1 layouts on the packed problem is a candidate too.
 """
 from __future__ import annotations
 
-PACKED, IM2COL, PAD_ONLY, IMPLICIT = 1, 2, 3, 4
+PACKED, IM2COL, PAD_ONLY, IMPLICIT, IMAGE_PACK = 1, 2, 3, 4, 5
 UNIT_X, UNIT_Y, UNIT_Z = 32, 32, 64  # pixels, output channels, depth
 
 
@@ -62,7 +64,21 @@ def candidates(C, dims=None):
     out.append((PAD_ONLY, _ceil(C, 16)))
     if dims is not None and implicit_applies(*dims):
         out.append((IMPLICIT, 0))
+    if dims is not None and dims[7] > 1:                     # Image Pack exists for strides above one
+        d2 = image_pack_dims(*dims)
+        if d2[1] * d2[5] * d2[6] <= 131072:
+            if implicit_applies(*d2):
+                out.append((IMAGE_PACK, 0))                  # inner layout: unrolled inside the GEMM stage
+            out += [(IMAGE_PACK, cb) for cb in (64, 32, 16)]  # inner layout: channel blocks
     return out
+
+
+def image_pack_dims(N, C, H, W, K, R, S, stride, pad):
+    """The stride-1, pad-0 problem whose channels are the stride phases (Table 2, Image Pack)."""
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    R2, S2 = -(-R // stride), -(-S // stride)
+    return (N, C * stride * stride, P + R2 - 1, Q + S2 - 1, K, R2, S2, 1, 0)
 
 
 def overheads(N, C, H, W, K, R, S, stride, pad, layout, cb):
@@ -70,6 +86,15 @@ def overheads(N, C, H, W, K, R, S, stride, pad, layout, cb):
     Q = (W + 2 * pad - S) // stride + 1
     M = N * P * Q
     mac_min = M * K * C * R * S
+    if layout == IMAGE_PACK:
+        # the packed problem in its inner layout (cb = 0: IMPLICIT, else PACKED with that block); its
+        # zero kernel taps count as overhead against the original definition; the pack itself writes
+        # X2 and W2, which the inner stage reads again
+        d2 = image_pack_dims(N, C, H, W, K, R, S, stride, pad)
+        o_mac, o_data, rewritten = overheads(*d2, IMPLICIT if cb == 0 else PACKED, cb)
+        x2 = d2[0] * d2[1] * d2[2] * d2[3]
+        w2 = K * d2[1] * d2[5] * d2[6]
+        return o_mac + M * K * d2[1] * d2[5] * d2[6] - mac_min, o_data + 2 * (x2 + w2), rewritten + x2 + w2
     if layout == IMPLICIT:
         if implicit_pointwise(C, R, S):
             return N * _ceil(P * Q, UNIT_X) * _ceil(K, UNIT_Y) * C - mac_min, 0, 0

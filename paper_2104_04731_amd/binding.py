@@ -13,15 +13,17 @@ import torch
 from . import build as _build
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_OVERFLOW_RISK, ERR_WORKSPACE, ERR_DEVICE = range(6)
-LAYOUT_AUTO, LAYOUT_PACKED, LAYOUT_IM2COL, LAYOUT_PAD_ONLY, LAYOUT_IMPLICIT = range(5)
+LAYOUT_AUTO, LAYOUT_PACKED, LAYOUT_IM2COL, LAYOUT_PAD_ONLY, LAYOUT_IMPLICIT, LAYOUT_IMAGE_PACK = range(6)
 LAYOUT_NAMES = {LAYOUT_AUTO: "auto", LAYOUT_PACKED: "packed", LAYOUT_IM2COL: "im2col",
-                LAYOUT_PAD_ONLY: "pad_only", LAYOUT_IMPLICIT: "implicit"}
+                LAYOUT_PAD_ONLY: "pad_only", LAYOUT_IMPLICIT: "implicit",
+                LAYOUT_IMAGE_PACK: "image_pack"}
 
 EXPORTS = [
     "conv2d_int8", "conv2d_int8_ex", "conv2d_int8_workspace_bytes", "conv2d_int8_packed",
     "conv2d_int8_query_tiling", "conv2d_int8_num_tiles", "conv2d_int8_tile_info",
     "conv2d_int8_tile_applies", "pack_layout", "pack_layout_bytes",
     "pack_weights", "pack_weights_depth", "pack_weights_bytes", "im2col_int8", "im2col_bytes",
+    "image_pack_desc", "image_pack_bytes", "image_pack_weights_bytes", "image_pack_int8", "image_pack_weights",
     "gemm_int8_nt", "select_layout", "select_layout_weighted", "layout_overheads",
     "conv_status_string",
 ]
@@ -68,6 +70,11 @@ def load(path: str | None = None):
         "pack_weights_bytes": (sz, [i] * 6),
         "im2col_int8": (i, [i] * 9 + [vp, vp, vp]),
         "im2col_bytes": (sz, [i] * 9),
+        "image_pack_desc": (i, [dp, dp]),
+        "image_pack_bytes": (sz, [dp]),
+        "image_pack_weights_bytes": (sz, [dp]),
+        "image_pack_int8": (i, [dp, vp, vp, vp]),
+        "image_pack_weights": (i, [dp, vp, vp, vp]),
         "gemm_int8_nt": (i, [i, i, i, vp, vp, vp, vp]),
         "select_layout": (i, [dp, ip, ip, ctypes.POINTER(dbl)]),
         "select_layout_weighted": (i, [dp, dbl, dbl, ip, ip, ctypes.POINTER(dbl)]),
@@ -226,6 +233,33 @@ def im2col_int8(x: torch.Tensor, R, S, stride, pad, kg_pad=None, out=None, strea
         out = torch.empty((N * max(P, 0) * max(Q, 0), kg_pad), dtype=torch.int8, device=x.device)
     _check(load().im2col_int8(N, C, H, W, R, S, stride, pad, kg_pad, _ptr(x), _ptr(out),
                               _stream(stream)), "im2col_int8")
+    return out
+
+
+def image_pack_desc(dims):
+    """The stride-1, pad-0 problem (N, C2, H2, W2, K, R2, S2, 1, 0) an image-packed convolution turns into."""
+    d, d2 = _desc(*dims), ConvDesc()
+    _check(load().image_pack_desc(ctypes.byref(d), ctypes.byref(d2)), "image_pack_desc")
+    return tuple(getattr(d2, f) for f, _ in ConvDesc._fields_)
+
+
+def image_pack_int8(dims, x: torch.Tensor, out=None, stream=None):
+    _require(x, torch.int8, "input")
+    d = _desc(*dims)
+    if out is None:
+        N, C2, H2, W2 = image_pack_desc(dims)[:4]
+        out = torch.empty((N, C2, H2, W2), dtype=torch.int8, device=x.device)
+    _check(load().image_pack_int8(ctypes.byref(d), _ptr(x), _ptr(out), _stream(stream)), "image_pack_int8")
+    return out
+
+
+def image_pack_weights(dims, w: torch.Tensor, out=None, stream=None):
+    _require(w, torch.int8, "weights")
+    d = _desc(*dims)
+    if out is None:
+        _, C2, _, _, K, R2, S2, _, _ = image_pack_desc(dims)
+        out = torch.empty((K, C2, R2, S2), dtype=torch.int8, device=w.device)
+    _check(load().image_pack_weights(ctypes.byref(d), _ptr(w), _ptr(out), _stream(stream)), "image_pack_weights")
     return out
 
 

@@ -69,6 +69,7 @@ int make_plan(const conv_desc_t *d, int layout, int cb, Plan *pl)
         rc = select_layout(d, &layout, &cb, nullptr);
         if (rc != CONV_OK) return rc;
     }
+    if (layout == CONV_LAYOUT_IMAGE_PACK) return CONV_ERR_UNSUPPORTED;  // two stages: not a single plan
     if (layout == CONV_LAYOUT_PAD_ONLY) cb = round_up_i(d->C, 16);
     else if (layout == CONV_LAYOUT_PACKED) {
         if (cb == 0) cb = default_block(d->C);
@@ -109,6 +110,43 @@ int make_plan(const conv_desc_t *d, int layout, int cb, Plan *pl)
     }
     pl->w_bytes = (size_t)d->K * pl->depth;
     return CONV_OK;
+}
+
+// Image Pack: the equivalent stride-1, pad-0 problem, the sizes of its two rewritten operands, and
+// the layout the stride-1 convolution then runs in (cb = 0: IMPLICIT, else PACKED with that block).
+struct PackedProblem {
+    conv_desc_t d2;
+    size_t x2_bytes, w2_bytes;
+    int inner_layout, inner_cb;
+};
+
+int image_pack_problem(const conv_desc_t *d, int cb, PackedProblem *pp)
+{
+    int rc = check_desc(d);
+    if (rc != CONV_OK) return rc;
+    if (d->stride < 2) return CONV_ERR_UNSUPPORTED;  // nothing to pack
+    const long long s = d->stride;
+    const long long C2 = (long long)d->C * s * s;
+    const long long R2 = (d->R + s - 1) / s, S2 = (d->S + s - 1) / s;
+    const long long P = ((long long)d->H + 2LL * d->pad - d->R) / s + 1, Q = ((long long)d->W + 2LL * d->pad - d->S) / s + 1;
+    const long long H2 = P + R2 - 1, W2 = Q + S2 - 1;
+    if (C2 > INT_LIMIT || H2 > INT_LIMIT || W2 > INT_LIMIT || C2 * R2 * S2 > 131072LL) return CONV_ERR_UNSUPPORTED;
+    pp->d2 = conv_desc_t{d->N, (int)C2, (int)H2, (int)W2, d->K, (int)R2, (int)S2, 1, 0};
+    pp->x2_bytes = (size_t)d->N * (size_t)C2 * (size_t)H2 * (size_t)W2;
+    pp->w2_bytes = (size_t)d->K * (size_t)C2 * (size_t)R2 * (size_t)S2;
+    pp->inner_layout = cb == 0 ? CONV_LAYOUT_IMPLICIT : CONV_LAYOUT_PACKED;
+    pp->inner_cb = cb;
+    Plan inner;
+    return make_plan(&pp->d2, pp->inner_layout, pp->inner_cb, &inner);
+}
+
+// AUTO -> the selector's choice (which may be IMAGE_PACK with its inner block in *cb).
+int resolve_layout(const conv_desc_t *d, int *layout, int *cb)
+{
+    if (*layout != CONV_LAYOUT_AUTO) return CONV_OK;
+    int rc = check_desc(d);
+    if (rc != CONV_OK) return rc;
+    return select_layout(d, layout, cb, nullptr);
 }
 
 GemmProblem gemm_problem(const conv_desc_t *d, const Plan &pl, const int8_t *x, const int8_t *w,
@@ -274,6 +312,48 @@ int im2col_int8(int N, int C, int H, int W, int R, int S, int stride, int pad, i
                    hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
 }
 
+int image_pack_desc(const conv_desc_t *desc, conv_desc_t *packed)
+{
+    if (!packed) return CONV_ERR_INVALID_ARG;
+    PackedProblem pp;
+    int rc = image_pack_problem(desc, 16, &pp);
+    if (rc != CONV_OK) return rc;
+    *packed = pp.d2;
+    return CONV_OK;
+}
+
+size_t image_pack_bytes(const conv_desc_t *desc)
+{
+    PackedProblem pp;
+    return image_pack_problem(desc, 16, &pp) == CONV_OK ? pp.x2_bytes : 0;
+}
+
+size_t image_pack_weights_bytes(const conv_desc_t *desc)
+{
+    PackedProblem pp;
+    return image_pack_problem(desc, 16, &pp) == CONV_OK ? pp.w2_bytes : 0;
+}
+
+int image_pack_int8(const conv_desc_t *desc, const int8_t *src, int8_t *dst, void *stream)
+{
+    PackedProblem pp;
+    int rc = image_pack_problem(desc, 16, &pp);
+    if (rc != CONV_OK) return rc;
+    if (!src || !dst || (reinterpret_cast<uintptr_t>(dst) & 3)) return CONV_ERR_INVALID_ARG;
+    return launch_image_pack(desc->N, desc->C, desc->H, desc->W, desc->stride, desc->pad, pp.d2.H, pp.d2.W, src, dst,
+                             (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+}
+
+int image_pack_weights(const conv_desc_t *desc, const int8_t *src, int8_t *dst, void *stream)
+{
+    PackedProblem pp;
+    int rc = image_pack_problem(desc, 16, &pp);
+    if (rc != CONV_OK) return rc;
+    if (!src || !dst) return CONV_ERR_INVALID_ARG;
+    return launch_image_pack_weights(desc->K, desc->C, desc->R, desc->S, desc->stride, src, dst,
+                                     (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+}
+
 int gemm_int8_nt(int X, int Y, int Z, const int8_t *A, const int8_t *B, int32_t *Cout, void *stream)
 {
     if (X <= 0 || Y <= 0 || Z <= 0 || !A || !B || !Cout) return CONV_ERR_INVALID_ARG;
@@ -351,6 +431,13 @@ int conv2d_int8_tile_applies(const conv_desc_t *desc, int layout, int cb, int ti
 
 size_t conv2d_int8_workspace_bytes(const conv_desc_t *desc, int layout, int cb, int wt_is_packed)
 {
+    if (resolve_layout(desc, &layout, &cb) != CONV_OK) return 0;
+    if (layout == CONV_LAYOUT_IMAGE_PACK) {
+        PackedProblem pp;
+        if (wt_is_packed || image_pack_problem(desc, cb, &pp) != CONV_OK) return 0;
+        return align_up(pp.x2_bytes, WS_ALIGN) + align_up(pp.w2_bytes, WS_ALIGN) +
+               conv2d_int8_workspace_bytes(&pp.d2, pp.inner_layout, pp.inner_cb, 0);
+    }
     Plan pl;
     if (make_plan(desc, layout, cb, &pl) != CONV_OK) return 0;
     return align_up(pl.x_bytes, WS_ALIGN) + (wt_is_packed ? 0 : align_up(pl.w_bytes, WS_ALIGN));
@@ -360,8 +447,30 @@ int conv2d_int8_ex(const conv_desc_t *desc, int layout, int cb, const int8_t *in
                    int wt_is_packed, int32_t *out, void *workspace, size_t workspace_bytes,
                    void *stream)
 {
+    int rc = resolve_layout(desc, &layout, &cb);
+    if (rc != CONV_OK) return rc;
+    if (layout == CONV_LAYOUT_IMAGE_PACK) {
+        // rewrite both operands into the stride-1 problem, then run that problem in its inner layout
+        PackedProblem pp;
+        rc = image_pack_problem(desc, cb, &pp);
+        if (rc != CONV_OK) return rc;
+        if (wt_is_packed) return CONV_ERR_UNSUPPORTED;
+        if (!in || !wt || !out || !workspace) return CONV_ERR_INVALID_ARG;
+        if (reinterpret_cast<uintptr_t>(workspace) % WS_ALIGN) return CONV_ERR_INVALID_ARG;
+        const size_t xb = align_up(pp.x2_bytes, WS_ALIGN), wb = align_up(pp.w2_bytes, WS_ALIGN);
+        const size_t inner = conv2d_int8_workspace_bytes(&pp.d2, pp.inner_layout, pp.inner_cb, 0);
+        if (workspace_bytes < xb + wb + inner) return CONV_ERR_WORKSPACE;
+        int8_t *x2 = static_cast<int8_t *>(workspace), *w2 = x2 + xb;
+        hipStream_t st = (hipStream_t)stream;
+        if (launch_image_pack(desc->N, desc->C, desc->H, desc->W, desc->stride, desc->pad, pp.d2.H, pp.d2.W, in, x2,
+                              st) != hipSuccess ||
+            launch_image_pack_weights(desc->K, desc->C, desc->R, desc->S, desc->stride, wt, w2, st) != hipSuccess)
+            return CONV_ERR_DEVICE;
+        return conv2d_int8_ex(&pp.d2, pp.inner_layout, pp.inner_cb, x2, w2, 0, out, inner ? w2 + wb : nullptr, inner,
+                              stream);
+    }
     Plan pl;
-    int rc = make_plan(desc, layout, cb, &pl);
+    rc = make_plan(desc, layout, cb, &pl);
     if (rc != CONV_OK) return rc;
     if (!in || !wt || !out) return CONV_ERR_INVALID_ARG;
     if (pl.layout == CONV_LAYOUT_IMPLICIT)
@@ -401,12 +510,15 @@ int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int
                 const int8_t *in, const int8_t *wt, int32_t *out, void *stream)
 {
     conv_desc_t d{N, C, H, W, K, R, S, stride, pad};
-    Plan pl;
-    int rc = make_plan(&d, CONV_LAYOUT_AUTO, 0, &pl);
+    int layout = CONV_LAYOUT_AUTO, cb = 0;
+    int rc = resolve_layout(&d, &layout, &cb);
     if (rc != CONV_OK) return rc;
     if (!in || !wt || !out) return CONV_ERR_INVALID_ARG;
-    if (pl.layout == CONV_LAYOUT_IMPLICIT) return conv2d_int8_ex(&d, pl.layout, 0, in, wt, 0, out, nullptr, 0, stream);
-    const size_t need = align_up(pl.x_bytes, WS_ALIGN) + align_up(pl.w_bytes, WS_ALIGN);
+    const size_t need = conv2d_int8_workspace_bytes(&d, layout, cb, 0);
+    if (need == 0) {  // IMPLICIT: nothing to stage (any other layout reports its problem here)
+        if (layout != CONV_LAYOUT_IMPLICIT) return CONV_ERR_UNSUPPORTED;
+        return conv2d_int8_ex(&d, layout, 0, in, wt, 0, out, nullptr, 0, stream);
+    }
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CONV_ERR_DEVICE;
     std::lock_guard<std::mutex> lock(g_cache_mutex);
@@ -426,7 +538,7 @@ int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int
         }
         c.bytes = want;
     }
-    return conv2d_int8_ex(&d, pl.layout, pl.cb, in, wt, 0, out, c.ptr, c.bytes, stream);
+    return conv2d_int8_ex(&d, layout, cb, in, wt, 0, out, c.ptr, c.bytes, stream);
 }
 
 }  // extern "C"

@@ -53,6 +53,11 @@ hipError_t launch_rewrite_fused(bool im2col, int N, int C, int H, int W, int K, 
                                 int pad, int P, int Q, int cb, int depth, const int8_t *in, int8_t *xq,
                                 const int8_t *wt, int8_t *wq, hipStream_t st);
 hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t st);
+// Image Pack: the stride phases of the zero-padded image (and of the kernel) become channels.
+hipError_t launch_image_pack(int N, int C, int H, int W, int stride, int pad, int H2, int W2,
+                             const int8_t *src, int8_t *dst, hipStream_t st);
+hipError_t launch_image_pack_weights(int K, int C, int R, int S, int stride, const int8_t *src, int8_t *dst,
+                                     hipStream_t st);
 
 // GEMM stage that unrolls the stencil itself from the NCHW input (no rewritten activations).
 struct WindowProblem {

@@ -646,6 +646,156 @@ hipError_t launch_rewrite_fused(bool im2col, int N, int C, int H, int W, int K, 
     return hipGetLastError();
 }
 
+// ---- Image Pack (Table 2, row 1: the stride phases of the padded image become channels) -----
+// dst[n][(c*s + a)*s + b][i][j] = in0[n][c][s*i + a - pad][s*j + b - pad]; one thread per four
+// consecutive destination bytes (any alignment of rows; the flat tail is written byte-wise)
+struct ImagePackArgs {
+    const int8_t *src;
+    int8_t *dst;
+    int C, H, W, s, pad, C2, H2, W2;
+    long long total;  // N * C2 * H2 * W2
+    unsigned m_W2, m_H2, m_C2;
+};
+
+// Stride 2, fewer than 2^31 destination bytes: a destination dword is every second byte of an
+// 8-byte source window -- two dword loads at any byte address and one byte permute -- unless
+// the window touches the border, a row end or the tensor's tail (then byte by byte).
+__global__ void __launch_bounds__(256) image_pack_s2_kernel(const ImagePackArgs a)
+{
+    const int ndw = (int)((a.total + 3) / 4);
+    for (int t = blockIdx.x * 256 + threadIdx.x; t < ndw; t += gridDim.x * 256) {
+        const int e0 = 4 * t;
+        const int row = fast_div_any(e0, a.W2, a.m_W2), j0 = e0 - row * a.W2;
+        const int nc = fast_div_any(row, a.H2, a.m_H2), i = row - nc * a.H2;
+        const int n = fast_div_any(nc, a.C2, a.m_C2), c2 = nc - n * a.C2;
+        const int b = c2 & 1, aa = (c2 >> 1) & 1, c = c2 >> 2;
+        const int h = 2 * i + aa - a.pad, w0 = 2 * j0 + b - a.pad;
+        if (j0 + 4 <= a.W2 && h >= 0 && h < a.H && w0 >= 0 && w0 + 8 <= a.W) {
+            const int8_t *p = a.src + (((size_t)n * a.C + c) * a.H + h) * a.W + w0;
+            unsigned lo, hi;
+            __builtin_memcpy(&lo, p, 4);
+            __builtin_memcpy(&hi, p + 4, 4);
+            *reinterpret_cast<unsigned *>(a.dst + e0) = __builtin_amdgcn_perm(hi, lo, 0x06040200u);
+            continue;
+        }
+        // general path for this dword: it may run over a row end into the next row / channel / image
+        int j = j0, ii = i, cc2 = c2;
+        long long nn = n;
+        unsigned v = 0;
+        int nb = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if ((long long)e0 + u < a.total) {
+                const int bb = cc2 & 1, a2 = (cc2 >> 1) & 1, c1 = cc2 >> 2;
+                const int hh = 2 * ii + a2 - a.pad, ww = 2 * j + bb - a.pad;
+                int x = 0;
+                if (hh >= 0 && hh < a.H && ww >= 0 && ww < a.W) x = a.src[((nn * a.C + c1) * a.H + hh) * a.W + ww];
+                v |= (unsigned)(x & 0xFF) << (8 * u);
+                ++nb;
+                if (++j == a.W2) {
+                    j = 0;
+                    if (++ii == a.H2) {
+                        ii = 0;
+                        if (++cc2 == a.C2) {
+                            cc2 = 0;
+                            ++nn;
+                        }
+                    }
+                }
+            }
+        }
+        if (nb == 4) *reinterpret_cast<unsigned *>(a.dst + e0) = v;
+        else
+            for (int u = 0; u < nb; ++u) a.dst[e0 + u] = (int8_t)(v >> (8 * u));
+    }
+}
+
+__global__ void __launch_bounds__(256) image_pack_kernel(const ImagePackArgs a)
+{
+    const long long ndw = (a.total + 3) / 4;
+    for (long long t = (long long)blockIdx.x * 256 + threadIdx.x; t < ndw; t += (long long)gridDim.x * 256) {
+        const long long e0 = 4 * t;
+        int j = (int)(e0 % a.W2);
+        long long rest = e0 / a.W2;
+        int i = (int)(rest % a.H2);
+        rest /= a.H2;
+        int c2 = (int)(rest % a.C2);
+        long long n = rest / a.C2;
+        unsigned v = 0;
+        int nb = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (e0 + u < a.total) {
+                const int b = c2 % a.s, ca = c2 / a.s, aa = ca % a.s, c = ca / a.s;
+                const int h = a.s * i + aa - a.pad, w = a.s * j + b - a.pad;
+                int x = 0;
+                if (h >= 0 && h < a.H && w >= 0 && w < a.W) x = a.src[((n * a.C + c) * a.H + h) * a.W + w];
+                v |= (unsigned)(x & 0xFF) << (8 * u);
+                ++nb;
+                if (++j == a.W2) {
+                    j = 0;
+                    if (++i == a.H2) {
+                        i = 0;
+                        if (++c2 == a.C2) {
+                            c2 = 0;
+                            ++n;
+                        }
+                    }
+                }
+            }
+        }
+        if (nb == 4) *reinterpret_cast<unsigned *>(a.dst + e0) = v;
+        else
+            for (int u = 0; u < nb; ++u) a.dst[e0 + u] = (int8_t)(v >> (8 * u));
+    }
+}
+
+// dst[k][(c*s + a)*s + b][r][t] = src[k][c][s*r + a][s*t + b] inside the kernel, else 0; one thread per byte
+__global__ void __launch_bounds__(256) image_pack_weights_kernel(const int8_t *src, int8_t *dst, int K, int C, int R,
+                                                                 int S, int s, int R2, int S2)
+{
+    const long long total = (long long)K * C * s * s * R2 * S2;
+    for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
+        const int t = (int)(e % S2);
+        long long rest = e / S2;
+        const int r = (int)(rest % R2);
+        rest /= R2;
+        const int b = (int)(rest % s);
+        rest /= s;
+        const int aa = (int)(rest % s);
+        rest /= s;
+        const int c = (int)(rest % C);
+        const long long k = rest / C;
+        const int rr = s * r + aa, ss = s * t + b;
+        dst[e] = (rr < R && ss < S) ? src[((k * C + c) * R + rr) * S + ss] : (int8_t)0;
+    }
+}
+
+hipError_t launch_image_pack(int N, int C, int H, int W, int stride, int pad, int H2, int W2,
+                             const int8_t *src, int8_t *dst, hipStream_t st)
+{
+    ImagePackArgs a{src, dst, C, H, W, stride, pad, C * stride * stride, H2, W2, 0, 0u, 0u, 0u};
+    a.total = (long long)N * a.C2 * H2 * W2;
+    a.m_W2 = magic_for(W2);
+    a.m_H2 = magic_for(H2);
+    a.m_C2 = magic_for(a.C2);
+    if (stride == 2 && a.total < (1LL << 31) - 4)
+        hipLaunchKernelGGL(image_pack_s2_kernel, dim3(grid_for((a.total + 3) / 4, 256)), dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL(image_pack_kernel, dim3(grid_for((a.total + 3) / 4, 256)), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_image_pack_weights(int K, int C, int R, int S, int stride, const int8_t *src, int8_t *dst,
+                                     hipStream_t st)
+{
+    const int R2 = (R + stride - 1) / stride, S2 = (S + stride - 1) / stride;
+    const long long total = (long long)K * C * stride * stride * R2 * S2;
+    hipLaunchKernelGGL(image_pack_weights_kernel, dim3(grid_for(total, 256)), dim3(256), 0, st, src, dst, K, C, R, S,
+                       stride, R2, S2);
+    return hipGetLastError();
+}
+
 // ---- zero fill (a kernel, not a memset node, so that callers may capture it) --------------
 __global__ void __launch_bounds__(256) fill_zero_kernel(v4i *dst, long long n16, int8_t *tail, int ntail)
 {

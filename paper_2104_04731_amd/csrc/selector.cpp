@@ -33,6 +33,22 @@ extern "C" int layout_overheads(const conv_desc_t *d, int layout, int cb,
     const int64_t M = (int64_t)d->N * P * Q;
     const int64_t taps = (int64_t)d->R * d->S;
     const int64_t mac_min = M * d->K * d->C * taps;
+    if (layout == CONV_LAYOUT_IMAGE_PACK) {
+        // the packed stride-1 problem in its inner layout, against the MACs of the original definition
+        conv_desc_t d2;
+        int rc = image_pack_desc(d, &d2);
+        if (rc != CONV_OK) return rc;
+        if (cb != 0 && cb != 16 && cb != 32 && cb != 64) return CONV_ERR_INVALID_ARG;
+        int64_t om, od, rw;
+        rc = layout_overheads(&d2, cb == 0 ? CONV_LAYOUT_IMPLICIT : CONV_LAYOUT_PACKED, cb, &om, &od, &rw);
+        if (rc != CONV_OK) return rc;
+        const int64_t inner_min = M * d->K * d2.C * d2.R * d2.S;  // includes the zero taps of the split kernel
+        const int64_t x2 = (int64_t)d2.N * d2.C * d2.H * d2.W, w2 = (int64_t)d2.K * d2.C * d2.R * d2.S;
+        if (o_mac) *o_mac = om + inner_min - mac_min;
+        if (o_data) *o_data = od + 2 * (x2 + w2);
+        if (rewritten) *rewritten = rw + x2 + w2;
+        return CONV_OK;
+    }
     if (layout == CONV_LAYOUT_IMPLICIT) {
         // nothing rewritten, nothing moved twice; pixels padded per output row, kernel rows to dwords
         if (P > 2147483647LL || Q > 2147483647LL) return CONV_ERR_UNSUPPORTED;
@@ -78,7 +94,9 @@ extern "C" int select_layout_weighted(const conv_desc_t *d, double w_mac, double
 {
     if (!d || !layout || !cb) return CONV_ERR_INVALID_ARG;
     const Cand cands[] = {{CONV_LAYOUT_PACKED, 64}, {CONV_LAYOUT_PACKED, 32}, {CONV_LAYOUT_PACKED, 16},
-                          {CONV_LAYOUT_IM2COL, 0},  {CONV_LAYOUT_PAD_ONLY, 0},  {CONV_LAYOUT_IMPLICIT, 0}};
+                          {CONV_LAYOUT_IM2COL, 0},  {CONV_LAYOUT_PAD_ONLY, 0},  {CONV_LAYOUT_IMPLICIT, 0},
+                          {CONV_LAYOUT_IMAGE_PACK, 0}, {CONV_LAYOUT_IMAGE_PACK, 64}, {CONV_LAYOUT_IMAGE_PACK, 32},
+                          {CONV_LAYOUT_IMAGE_PACK, 16}};
     bool have = false;
     double best_score = 0;
     int64_t best_ws = 0;
@@ -88,7 +106,8 @@ extern "C" int select_layout_weighted(const conv_desc_t *d, double w_mac, double
         if (c.layout == CONV_LAYOUT_PAD_ONLY) c.cb = (int)round_up(d->C, 16);
         int64_t om, od, ws;
         int rc = layout_overheads(d, c.layout, c.cb, &om, &od, &ws);
-        if (rc == CONV_ERR_UNSUPPORTED && c.layout == CONV_LAYOUT_IMPLICIT) continue;  // outside its domain
+        if (rc == CONV_ERR_UNSUPPORTED && (c.layout == CONV_LAYOUT_IMPLICIT || c.layout == CONV_LAYOUT_IMAGE_PACK))
+            continue;  // outside its domain
         if (rc != CONV_OK) return rc;
         const double sc = w_mac * (double)om + w_data * (double)od;
         bool better = !have;

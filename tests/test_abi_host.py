@@ -134,3 +134,32 @@ def test_gemm_stage_unroll_domain_and_sizes(lib, dims):
         assert layouts.pack_weights_implicit(np.zeros((2, C, R, S), np.int8)).shape == (2, depth)
     for w in [(1.0, 1.0), (0.0, 1.0), (1.0 / 0.6e15, 1.0 / 4.0e12)]:
         assert lib.select_layout(dims, *w)[:2] == sel.select(*dims, *w)[:2]
+
+
+@pytest.mark.parametrize("dims", [(1, 4, 16, 16, 32, 2, 2, 2, 0), (2, 3, 40, 40, 8, 7, 7, 2, 3), (1, 1, 41, 50, 32, 20, 5, 2, 0),
+                                  (1, 16, 17, 17, 32, 3, 3, 3, 1), (1, 64, 9, 9, 8, 1, 1, 2, 0), (1, 2, 9, 9, 8, 3, 3, 1, 1)],
+                         ids=str)
+def test_image_pack_problem_and_sizes(lib, dims):
+    N, C, H, W, K, R, S, st, pad = dims
+    d = lib.ConvDesc(*dims)
+    raw = lib.load()
+    if st == 1:
+        assert raw.image_pack_bytes(ctypes.byref(d)) == 0
+        assert raw.image_pack_desc(ctypes.byref(d), ctypes.byref(lib.ConvDesc())) == lib.ERR_UNSUPPORTED
+        assert lib.conv2d_int8_workspace_bytes(dims, lib.LAYOUT_IMAGE_PACK, 16) == 0
+        return
+    d2 = layouts.image_pack_dims(*dims)
+    assert lib.image_pack_desc(dims) == d2 == sel.image_pack_dims(*dims)
+    assert raw.image_pack_bytes(ctypes.byref(d)) == d2[0] * d2[1] * d2[2] * d2[3]
+    assert raw.image_pack_weights_bytes(ctypes.byref(d)) == K * d2[1] * d2[5] * d2[6]
+    for cb in (0, 16, 64):
+        if cb == 0 and not sel.implicit_applies(*d2):
+            continue
+        assert lib.layout_overheads(dims, lib.LAYOUT_IMAGE_PACK, cb) == sel.overheads(*dims, sel.IMAGE_PACK, cb)
+        inner = lib.conv2d_int8_workspace_bytes(d2, lib.LAYOUT_IMPLICIT if cb == 0 else lib.LAYOUT_PACKED, cb)
+        up = lambda v: -(-v // 256) * 256
+        assert lib.conv2d_int8_workspace_bytes(dims, lib.LAYOUT_IMAGE_PACK, cb) == \
+            up(d2[0] * d2[1] * d2[2] * d2[3]) + up(K * d2[1] * d2[5] * d2[6]) + inner
+    # the GEMM-stage entry points take single-stage layouts only
+    assert raw.conv2d_int8_packed(ctypes.byref(d), lib.LAYOUT_IMAGE_PACK, 16, None, None, None, -1, 0, None) != lib.OK
+    assert lib.pack_weights_depth(C, R, S, lib.LAYOUT_IMAGE_PACK, 16) == 0

@@ -457,3 +457,44 @@ def test_implicit_unaligned_operands_and_forced_tiles(lib):
         with pytest.raises(lib.ConvError) as e:
             lib.conv2d_int8_packed(cfg.dims(), lib.LAYOUT_IMPLICIT, 0, dev(x), wp, out, tile=tile, split_k=split)
         assert e.value.status == lib.ERR_UNSUPPORTED
+
+
+# ---- Image Pack (stride phases become channels) ----------------------------------------------
+IMAGE_PACK_SHAPES = [
+    ConvShape("ip-7x7-s2", 2, 3, 21, 23, 8, 7, 7, 2, 3), ConvShape("ip-20x5-s2", 1, 1, 41, 50, 32, 20, 5, 2, 0),
+    ConvShape("ip-3x3-s3", 1, 16, 17, 19, 33, 3, 3, 3, 1), ConvShape("ip-1x1-s2", 2, 64, 9, 9, 8, 1, 1, 2, 0),
+    ConvShape("ip-2x2-s2", 1, 4, 16, 16, 32, 2, 2, 2, 0), ConvShape("ip-5x4-s4", 1, 2, 30, 13, 5, 5, 4, 4, 2),
+]
+
+
+@pytest.mark.parametrize("cfg", IMAGE_PACK_SHAPES + [CONFIGS["C3"], CONFIGS["C5"]], ids=lambda c: c.name)
+def test_image_pack(lib, cfg):
+    """Both rewrites against their index maps, then the whole two-stage path in each inner layout."""
+    x = uniform_int8(511, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(512, (cfg.K, cfg.C, cfg.R, cfg.S))
+    np.testing.assert_array_equal(host(lib.image_pack_int8(cfg.dims(), dev(x))),
+                                  layouts.image_pack(x, cfg.R, cfg.S, cfg.stride, cfg.pad))
+    np.testing.assert_array_equal(host(lib.image_pack_weights(cfg.dims(), dev(w))), layouts.image_pack_weights(w, cfg.stride))
+    want = direct.conv2d_int8(x, w, cfg.stride, cfg.pad)
+    d2 = layouts.image_pack_dims(*cfg.dims())
+    ran = 0
+    for cb in (0, 16, 64):
+        nbytes = lib.conv2d_int8_workspace_bytes(cfg.dims(), lib.LAYOUT_IMAGE_PACK, cb)
+        out = torch.full((cfg.N, cfg.K, cfg.P, cfg.Q), -3, dtype=torch.int32, device=DEV)
+        if cb == 0 and not selection.implicit_applies(*d2):
+            assert nbytes == 0
+            with pytest.raises(lib.ConvError) as e:
+                lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_IMAGE_PACK, cb, dev(x), dev(w), out,
+                                   torch.empty(1 << 20, dtype=torch.int8, device=DEV))
+            assert e.value.status == lib.ERR_UNSUPPORTED
+            continue
+        ws = torch.empty(nbytes + 256, dtype=torch.int8, device=DEV)
+        ws = ws[(-ws.data_ptr()) % 256:]
+        lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_IMAGE_PACK, cb, dev(x), dev(w), out, ws)
+        assert np.array_equal(host(out), want), f"inner cb {cb}: {np.count_nonzero(host(out) != want)} mismatches"
+        ran += 1
+    assert ran >= 2
+    # a workspace one byte short is refused before anything runs
+    with pytest.raises(lib.ConvError) as e:
+        lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_IMAGE_PACK, 16, dev(x), dev(w), out,
+                           ws[:lib.conv2d_int8_workspace_bytes(cfg.dims(), lib.LAYOUT_IMAGE_PACK, 16) - 1])
+    assert e.value.status == lib.ERR_WORKSPACE

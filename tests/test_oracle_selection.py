@@ -104,3 +104,24 @@ def test_pointwise_form_of_the_gemm_stage_unroll():
     # the hardware weights prefer it to channel blocking (nothing moved twice); w = [1,1] does not
     assert sel.select(*CONFIGS["C4b"].dims(), 1.0 / 0.6e15, 1.0 / 4.0e12)[0] == sel.IMPLICIT
     assert sel.select(*CONFIGS["C4b"].dims(), 1.0, 1.0)[0] == sel.PACKED
+
+
+def test_image_pack_candidate():
+    """Image Pack exists for strides above one; its cost is the packed problem's plus the pack's own
+    traffic; on a unit that strides for free it never beats the direct layouts of these shapes."""
+    dims = (1, 4, 16, 16, 32, 2, 2, 2, 0)                     # 2x2 stride 2: no zero taps, P = Q = 8
+    assert sel.image_pack_dims(*dims) == (1, 16, 8, 8, 32, 1, 1, 1, 0)
+    o_mac, o_data, rewritten = sel.overheads(*dims, sel.IMAGE_PACK, 16)
+    x2, w2 = 16 * 8 * 8, 32 * 16
+    inner = sel.overheads(1, 16, 8, 8, 32, 1, 1, 1, 0, sel.PACKED, 16)
+    assert (o_mac, o_data, rewritten) == (inner[0], inner[1] + 2 * (x2 + w2), inner[2] + x2 + w2)
+    # 3x3 stride 2: the split kernel has 4x4 = 16 taps for 9 weights
+    dims = (1, 16, 17, 17, 32, 3, 3, 2, 0)
+    d2 = sel.image_pack_dims(*dims)
+    assert d2 == (1, 64, 9, 9, 32, 2, 2, 1, 0)
+    o_mac, _, _ = sel.overheads(*dims, sel.IMAGE_PACK, 64)
+    assert o_mac == 64 * 32 * (64 * 4) - 64 * 32 * 16 * 9      # 64 pixels; depth 256 issued for 144 useful
+    assert all(lay != sel.IMAGE_PACK for lay, _ in sel.candidates(16, (1, 16, 17, 17, 32, 3, 3, 1, 0)))
+    for name in ("C3", "C5"):
+        for w in ((1.0, 1.0), (1.0 / 0.6e15, 1.0 / 4.0e12), (0.0, 1.0), (1.0, 0.0)):
+            assert sel.select(*CONFIGS[name].dims(), *w)[0] != sel.IMAGE_PACK
