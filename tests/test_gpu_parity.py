@@ -498,3 +498,50 @@ def test_image_pack(lib, cfg):
         lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_IMAGE_PACK, 16, dev(x), dev(w), out,
                            ws[:lib.conv2d_int8_workspace_bytes(cfg.dims(), lib.LAYOUT_IMAGE_PACK, 16) - 1])
     assert e.value.status == lib.ERR_WORKSPACE
+
+
+# ---- seeded random shapes through the kernels that stage their own operands -----------------------
+def _random_shapes(seed, count, want):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        N = int(rng.integers(1, 4)); C = int(rng.choice([1, 2, 3, 4, 5, 8, 16, 64, 128])); K = int(rng.choice([1, 7, 32, 40, 65, 130]))
+        R = int(rng.integers(1, 8)); S = int(rng.integers(1, 10)); st = int(rng.integers(1, 5)); pad = int(rng.integers(0, 5))
+        H = int(rng.integers(1, 24)); W = int(rng.integers(1, 150))
+        if R > H + 2 * pad or S > W + 2 * pad:
+            continue
+        dims = (N, C, H, W, K, R, S, st, pad)
+        if want(dims):
+            out.append(ConvShape(f"r{len(out)}", *dims))
+    return out
+
+
+def test_implicit_random_shapes(lib):
+    shapes = _random_shapes(9001, 60, lambda d: selection.implicit_applies(*d) and d[0] * d[4] * d[2] * d[3] < 400000)
+    rng = np.random.default_rng(9003)   # the 1x1 form has a narrow domain: drawn from inside it
+    while len(shapes) < 75:
+        dims = (int(rng.integers(1, 4)), 64 * int(rng.integers(1, 9)), int(rng.integers(1, 12)), int(rng.integers(1, 40)),
+                int(rng.choice([1, 31, 32, 100, 129, 260])), 1, 1, 1, 0)
+        if selection.implicit_applies(*dims):
+            shapes.append(ConvShape(f"p{len(shapes)}", *dims))
+    for cfg in shapes:
+        x = uniform_int8(cfg.H * 131 + cfg.W, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(cfg.K * 17 + cfg.C, (cfg.K, cfg.C, cfg.R, cfg.S))
+        want = direct.conv2d_int8(x, w, cfg.stride, cfg.pad)
+        for rewritten in (False, True):
+            got = run_implicit(lib, cfg, x, w, rewritten)
+            assert np.array_equal(got, want), f"{cfg.dims()} rewritten={rewritten}: {np.count_nonzero(got != want)} mismatches"
+
+
+def test_image_pack_random_shapes(lib):
+    shapes = _random_shapes(9002, 30, lambda d: d[7] > 1 and d[1] <= 16 and d[0] * d[4] * d[2] * d[3] < 400000)
+    for cfg in shapes:
+        x = uniform_int8(cfg.H * 31 + cfg.W, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(cfg.K * 7 + cfg.C, (cfg.K, cfg.C, cfg.R, cfg.S))
+        np.testing.assert_array_equal(host(lib.image_pack_int8(cfg.dims(), dev(x))),
+                                      layouts.image_pack(x, cfg.R, cfg.S, cfg.stride, cfg.pad), err_msg=str(cfg.dims()))
+        np.testing.assert_array_equal(host(lib.image_pack_weights(cfg.dims(), dev(w))),
+                                      layouts.image_pack_weights(w, cfg.stride), err_msg=str(cfg.dims()))
+        nbytes = lib.conv2d_int8_workspace_bytes(cfg.dims(), lib.LAYOUT_IMAGE_PACK, 16)
+        ws = torch.empty(nbytes + 256, dtype=torch.int8, device=DEV); ws = ws[(-ws.data_ptr()) % 256:]
+        out = torch.full((cfg.N, cfg.K, cfg.P, cfg.Q), -3, dtype=torch.int32, device=DEV)
+        lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_IMAGE_PACK, 16, dev(x), dev(w), out, ws)
+        assert np.array_equal(host(out), direct.conv2d_int8(x, w, cfg.stride, cfg.pad)), cfg.dims()
