@@ -37,6 +37,17 @@ def pack_layout(x: np.ndarray, cb: int, pad: int) -> np.ndarray:
     return y
 
 
+def pack_layout_nhwc(x: np.ndarray, cb: int, pad: int) -> np.ndarray:
+    """The same rewrite from an NHWC source (Sec. 5.2: the free dimensions of the source may be in any
+    order): [N,H,W,C] -> [N, ceil(C/cb), H+2pad, W+2pad, cb]; y[n][c//cb][h+pad][w+pad][c%cb] = x[n][h][w][c]."""
+    N, H, W, C = x.shape
+    Cb = (C + cb - 1) // cb
+    y = np.zeros((N, Cb, H + 2 * pad, W + 2 * pad, cb), dtype=x.dtype)
+    for c in range(C):
+        y[:, c // cb, pad:pad + H, pad:pad + W, c % cb] = x[:, :, :, c]
+    return y
+
+
 def packed_depth(C: int, R: int, S: int, cb: int, kalign: int = 64) -> int:
     return ceil_to(((C + cb - 1) // cb) * R * S * cb, kalign)
 

@@ -156,3 +156,17 @@ def test_image_pack_elementwise_small():
         h, wcol = st * i + a - pad, st * j + b - pad
         want = xl[0][c][h][wcol] if (0 <= h < H and 0 <= wcol < W) else 0
         assert y[0, (c * st + a) * st + b, i, j] == want
+
+
+def test_pack_layout_from_nhwc_source():
+    """Same destination as from NCHW: only the source's dimension order differs; element by element too."""
+    N, C, H, W, cb, pad = 2, 37, 4, 5, 16, 1
+    x = uniform_int8(72, (N, C, H, W))
+    xh = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+    y = layouts.pack_layout_nhwc(xh, cb, pad)
+    np.testing.assert_array_equal(y, layouts.pack_layout(x, cb, pad))
+    xl = xh.tolist(); Cb = -(-C // cb)
+    for n, b, hp, wp, i in itertools.product(range(N), range(Cb), range(H + 2 * pad), range(W + 2 * pad), range(cb)):
+        c, h, w = b * cb + i, hp - pad, wp - pad
+        want = xl[n][h][w][c] if (c < C and 0 <= h < H and 0 <= w < W) else 0
+        assert y[n][b][hp][wp][i] == want
