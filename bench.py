@@ -273,7 +273,12 @@ def n_scaled(lib, timed, CONFIGS, dev):
     b = x.numel() + xp.numel()
     out["pack_layout_C2_N2048"] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),
                                     "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2)}
-    del x, xp
+    # the same rewrite from an NHWC source (the source-layout experiment of the paper's Sec. 5.2)
+    xh = x.permute(0, 2, 3, 1).contiguous()
+    _, ms = timed(lambda: lib.pack_layout_nhwc(xh, 64, cfg.pad, out=xp), 10, 2)
+    out["pack_layout_nhwc_C2_N2048"] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),
+                                         "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2)}
+    del x, xp, xh
     # im2col of the 7x7 stem at N=512 (~1.3 GB moved)
     cfg = CONFIGS["C3"].scaled(512)
     x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=dev)

@@ -132,6 +132,11 @@ int conv2d_int8_tile_applies(const conv_desc_t *desc, int layout, int cb, int ti
 int pack_layout(int N, int C, int H, int W, int cb, int pad,
                 const int8_t *src, int8_t *dst, void *stream);
 size_t pack_layout_bytes(int N, int C, int H, int W, int cb, int pad);
+/* The same rewrite from an NHWC source (Sec. 5.2: the dimensions the embedding leaves free may be in
+ * any order in the source): dst as above, dst[n][c/cb][h+pad][w+pad][c%cb] = src[n][h][w][c];
+ * cb a multiple of 16.  The GEMM stage and the NKPQ result are unchanged. */
+int pack_layout_nhwc(int N, int C, int H, int W, int cb, int pad,
+                     const int8_t *src, int8_t *dst, void *stream);
 
 /* pack_weights (same rewrites on the weights, then Fuse of the reduction dimensions):
  *   dst[k][j], row length depth = pack_weights_depth(...), zero where no weight maps.

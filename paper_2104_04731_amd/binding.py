@@ -21,7 +21,7 @@ LAYOUT_NAMES = {LAYOUT_AUTO: "auto", LAYOUT_PACKED: "packed", LAYOUT_IM2COL: "im
 EXPORTS = [
     "conv2d_int8", "conv2d_int8_ex", "conv2d_int8_workspace_bytes", "conv2d_int8_packed",
     "conv2d_int8_query_tiling", "conv2d_int8_num_tiles", "conv2d_int8_tile_info",
-    "conv2d_int8_tile_applies", "pack_layout", "pack_layout_bytes",
+    "conv2d_int8_tile_applies", "pack_layout", "pack_layout_bytes", "pack_layout_nhwc",
     "pack_weights", "pack_weights_depth", "pack_weights_bytes", "im2col_int8", "im2col_bytes",
     "image_pack_desc", "image_pack_bytes", "image_pack_weights_bytes", "image_pack_int8", "image_pack_weights",
     "gemm_int8_nt", "select_layout", "select_layout_weighted", "layout_overheads",
@@ -65,6 +65,7 @@ def load(path: str | None = None):
         "conv2d_int8_tile_info": (i, [i, ip, ip, ip, ip]),
         "pack_layout": (i, [i] * 6 + [vp, vp, vp]),
         "pack_layout_bytes": (sz, [i] * 6),
+        "pack_layout_nhwc": (i, [i] * 6 + [vp, vp, vp]),
         "pack_weights": (i, [i] * 6 + [vp, vp, vp]),
         "pack_weights_depth": (i, [i] * 5),
         "pack_weights_bytes": (sz, [i] * 6),
@@ -195,6 +196,19 @@ def pack_layout(x: torch.Tensor, cb: int, pad: int, out=None, stream=None):
         out = torch.empty((N, (C + cb - 1) // cb, H + 2 * pad, W + 2 * pad, cb), dtype=torch.int8,
                           device=x.device)
     _check(load().pack_layout(N, C, H, W, cb, pad, _ptr(x), _ptr(out), _stream(stream)), "pack_layout")
+    return out
+
+
+def pack_layout_nhwc(x: torch.Tensor, cb: int, pad: int, out=None, stream=None):
+    """x: [N, H, W, C] int8."""
+    _require(x, torch.int8, "input")
+    N, H, W, C = x.shape
+    if out is None:
+        if pack_layout_bytes(N, C, H, W, cb, pad) == 0 or cb % 16:
+            _check(ERR_UNSUPPORTED, "pack_layout_nhwc")
+        out = torch.empty((N, (C + cb - 1) // cb, H + 2 * pad, W + 2 * pad, cb), dtype=torch.int8,
+                          device=x.device)
+    _check(load().pack_layout_nhwc(N, C, H, W, cb, pad, _ptr(x), _ptr(out), _stream(stream)), "pack_layout_nhwc")
     return out
 
 

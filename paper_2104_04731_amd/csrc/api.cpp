@@ -247,6 +247,17 @@ int pack_layout(int N, int C, int H, int W, int cb, int pad, const int8_t *src, 
                ? CONV_OK : CONV_ERR_DEVICE;
 }
 
+int pack_layout_nhwc(int N, int C, int H, int W, int cb, int pad, const int8_t *src, int8_t *dst, void *stream)
+{
+    if (!src || !dst || N <= 0 || C <= 0 || H <= 0 || W <= 0 || pad < 0) return CONV_ERR_INVALID_ARG;
+    if (cb < 16 || cb > 1024 || cb % 16) return CONV_ERR_UNSUPPORTED;
+    if (!aligned16(dst)) return CONV_ERR_INVALID_ARG;
+    if ((long long)H + 2LL * pad > INT_LIMIT || (long long)W + 2LL * pad > INT_LIMIT)
+        return CONV_ERR_UNSUPPORTED;
+    return launch_pack_layout_nhwc(N, C, H, W, cb, pad, src, dst, (hipStream_t)stream) == hipSuccess
+               ? CONV_OK : CONV_ERR_DEVICE;
+}
+
 int pack_weights_depth(int C, int R, int S, int layout, int cb)
 {
     if (C <= 0 || R <= 0 || S <= 0) return 0;

@@ -40,6 +40,8 @@ hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t 
 
 hipError_t launch_pack_layout(int N, int C, int H, int W, int cb, int pad,
                               const int8_t *src, int8_t *dst, hipStream_t st);
+hipError_t launch_pack_layout_nhwc(int N, int C, int H, int W, int cb, int pad,
+                                   const int8_t *src, int8_t *dst, hipStream_t st);  // cb % 16 == 0
 hipError_t launch_pack_weights_blocked(int K, int C, int R, int S, int cb, int depth,
                                        const int8_t *src, int8_t *dst, hipStream_t st);
 hipError_t launch_pack_weights_rows(int K, int CRS, int depth,

@@ -646,6 +646,68 @@ hipError_t launch_rewrite_fused(bool im2col, int N, int C, int H, int W, int K, 
     return hipGetLastError();
 }
 
+// ---- channel blocking from an NHWC source (Sec. 5.2: source layouts other than NCHW) -------
+// dst[n][c/cb][h+pad][w+pad][c%cb] = src[n][h][w][c]: the channels of a pixel are already
+// contiguous, so a destination 16-byte piece is one 16-byte load (any alignment), the tail of a
+// pixel's channels byte by byte, zero on the border and past C.  One thread per 16 bytes.
+struct PackNhwcArgs {
+    const int8_t *src;
+    int8_t *dst;
+    int C, H, W, cb, pad, Hp, Wp, Cb, g16;
+    long long total;  // 16-byte pieces
+    unsigned m_g16, m_Wp, m_Hp, m_Cb;
+};
+
+__global__ void __launch_bounds__(256) pack_layout_nhwc_kernel(const PackNhwcArgs a)
+{
+    for (long long t = (long long)blockIdx.x * 256 + threadIdx.x; t < a.total; t += (long long)gridDim.x * 256) {
+        int c16, wp, hp, b;
+        long long n;
+        if (a.total < (1LL << 31)) {
+            const int i0 = (int)t;
+            const int i1 = fast_div_any(i0, a.g16, a.m_g16); c16 = i0 - i1 * a.g16;
+            const int i2 = fast_div_any(i1, a.Wp, a.m_Wp); wp = i1 - i2 * a.Wp;
+            const int i3 = fast_div_any(i2, a.Hp, a.m_Hp); hp = i2 - i3 * a.Hp;
+            const int i4 = fast_div_any(i3, a.Cb, a.m_Cb); b = i3 - i4 * a.Cb;
+            n = i4;
+        } else {
+            long long r = t;
+            c16 = (int)(r % a.g16); r /= a.g16;
+            wp = (int)(r % a.Wp); r /= a.Wp;
+            hp = (int)(r % a.Hp); r /= a.Hp;
+            b = (int)(r % a.Cb); n = r / a.Cb;
+        }
+        const int c0 = b * a.cb + c16 * 16, h = hp - a.pad, w = wp - a.pad;
+        v4i v = {0, 0, 0, 0};
+        if (h >= 0 && h < a.H && w >= 0 && w < a.W && c0 < a.C) {
+            const int8_t *p = a.src + ((n * a.H + h) * a.W + w) * a.C + c0;
+            if (c0 + 16 <= a.C) {
+                __builtin_memcpy(&v, p, 16);
+            } else {
+                unsigned char bytes[16] = {0};
+                for (int i = 0; c0 + i < a.C; ++i) bytes[i] = (unsigned char)p[i];
+                __builtin_memcpy(&v, bytes, 16);
+            }
+        }
+        reinterpret_cast<v4i *>(a.dst)[t] = v;
+    }
+}
+
+hipError_t launch_pack_layout_nhwc(int N, int C, int H, int W, int cb, int pad, const int8_t *src, int8_t *dst,
+                                   hipStream_t st)
+{
+    PackNhwcArgs a{};
+    a.src = src; a.dst = dst;
+    a.C = C; a.H = H; a.W = W; a.cb = cb; a.pad = pad;
+    a.Hp = H + 2 * pad; a.Wp = W + 2 * pad;
+    a.Cb = (C + cb - 1) / cb;
+    a.g16 = cb / 16;
+    a.total = (long long)N * a.Cb * a.Hp * a.Wp * a.g16;
+    a.m_g16 = magic_for(a.g16); a.m_Wp = magic_for(a.Wp); a.m_Hp = magic_for(a.Hp); a.m_Cb = magic_for(a.Cb);
+    hipLaunchKernelGGL(pack_layout_nhwc_kernel, dim3(grid_for(a.total, 256)), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
 // ---- Image Pack (Table 2, row 1: the stride phases of the padded image become channels) -----
 // dst[n][(c*s + a)*s + b][i][j] = in0[n][c][s*i + a - pad][s*j + b - pad]; one thread per four
 // consecutive destination bytes (any alignment of rows; the flat tail is written byte-wise)

@@ -53,6 +53,23 @@ def test_pack_layout_64_channel_slices(lib, shape, cb, pad):
     np.testing.assert_array_equal(got, layouts.pack_layout(x, cb, pad))
 
 
+@pytest.mark.parametrize("shape,cb,pad", [
+    ((2, 37, 5, 6), 16, 1), ((1, 3, 31, 29), 16, 3), ((3, 64, 14, 14), 64, 1), ((1, 70, 9, 130), 32, 0),
+    ((1, 256, 14, 14), 64, 1), ((2, 20, 7, 9), 48, 2), ((1, 1, 16, 50), 16, 0), ((1, 130, 3, 3), 128, 1),
+])
+def test_pack_layout_nhwc_source(lib, shape, cb, pad):
+    """Channel blocking from an NHWC source: same destination as from NCHW, for whole and ragged channel
+    counts (16-byte pieces, byte tails, dead channels) and at an odd source alignment."""
+    x = uniform_int8(sum(shape) + cb, shape)                      # NCHW values ...
+    xh = np.ascontiguousarray(x.transpose(0, 2, 3, 1))             # ... stored NHWC
+    want = layouts.pack_layout_nhwc(xh, cb, pad)
+    np.testing.assert_array_equal(host(lib.pack_layout_nhwc(dev(xh), cb, pad)), want)
+    np.testing.assert_array_equal(want, layouts.pack_layout(x, cb, pad))
+    buf = torch.zeros(xh.size + 8, dtype=torch.int8, device=DEV)
+    dx = buf[3:3 + xh.size].view(xh.shape); dx.copy_(dev(xh))
+    np.testing.assert_array_equal(host(lib.pack_layout_nhwc(dx, cb, pad)), want)
+
+
 @pytest.mark.parametrize("name", ["C2", "C3", "C4a", "C5"])
 def test_pack_layout_configs(lib, name):
     cfg = CONFIGS[name]
