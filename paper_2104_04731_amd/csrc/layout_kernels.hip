@@ -719,37 +719,56 @@ struct ImagePackArgs {
     unsigned m_W2, m_H2, m_C2;
 };
 
-// Stride 2: one thread per 16 consecutive bytes of a destination row (rows = (n, c2, i), fewer
-// than 2^31 pieces in all).  The piece is every second byte of a 32-byte source window: two
-// 16-byte loads at any byte address and four byte permutes -- unless the window touches the
-// border or the row's end (then byte by byte).
-__global__ void __launch_bounds__(256) image_pack_s2_kernel(const ImagePackArgs a, int cpr, unsigned m_cpr, int items)
+// Stride 2, fewer than 2^31 destination bytes: a destination dword is every second byte of an
+// 8-byte source window -- two dword loads at any byte address and one byte permute -- unless
+// the window touches the border, a row end or the tensor's tail (then byte by byte).
+__global__ void __launch_bounds__(256) image_pack_s2_kernel(const ImagePackArgs a)
 {
-    for (int t = blockIdx.x * 256 + threadIdx.x; t < items; t += gridDim.x * 256) {
-        const int row = fast_div_any(t, cpr, m_cpr), j0 = (t - row * cpr) * 16;
+    const int ndw = (int)((a.total + 3) / 4);
+    for (int t = blockIdx.x * 256 + threadIdx.x; t < ndw; t += gridDim.x * 256) {
+        const int e0 = 4 * t;
+        const int row = fast_div_any(e0, a.W2, a.m_W2), j0 = e0 - row * a.W2;
         const int nc = fast_div_any(row, a.H2, a.m_H2), i = row - nc * a.H2;
         const int n = fast_div_any(nc, a.C2, a.m_C2), c2 = nc - n * a.C2;
         const int b = c2 & 1, aa = (c2 >> 1) & 1, c = c2 >> 2;
         const int h = 2 * i + aa - a.pad, w0 = 2 * j0 + b - a.pad;
-        const int nv = min(16, a.W2 - j0);
-        int8_t *d = a.dst + (size_t)row * a.W2 + j0;
-        const bool hin = h >= 0 && h < a.H;
-        const int8_t *srow = a.src + (((size_t)n * a.C + c) * a.H + (hin ? h : 0)) * a.W;
-        if (nv == 16 && hin && w0 >= 0 && w0 + 32 <= a.W) {
-            v4i lo, hi, o;
-            __builtin_memcpy(&lo, srow + w0, 16);
-            __builtin_memcpy(&hi, srow + w0 + 16, 16);
-            o[0] = (int)__builtin_amdgcn_perm((unsigned)lo[1], (unsigned)lo[0], 0x06040200u);
-            o[1] = (int)__builtin_amdgcn_perm((unsigned)lo[3], (unsigned)lo[2], 0x06040200u);
-            o[2] = (int)__builtin_amdgcn_perm((unsigned)hi[1], (unsigned)hi[0], 0x06040200u);
-            o[3] = (int)__builtin_amdgcn_perm((unsigned)hi[3], (unsigned)hi[2], 0x06040200u);
-            __builtin_memcpy(d, &o, 16);
+        if (j0 + 4 <= a.W2 && h >= 0 && h < a.H && w0 >= 0 && w0 + 8 <= a.W) {
+            const int8_t *p = a.src + (((size_t)n * a.C + c) * a.H + h) * a.W + w0;
+            unsigned lo, hi;
+            __builtin_memcpy(&lo, p, 4);
+            __builtin_memcpy(&hi, p + 4, 4);
+            *reinterpret_cast<unsigned *>(a.dst + e0) = __builtin_amdgcn_perm(hi, lo, 0x06040200u);
             continue;
         }
-        for (int u = 0; u < nv; ++u) {
-            const int w = w0 + 2 * u;
-            d[u] = (hin && w >= 0 && w < a.W) ? srow[w] : (int8_t)0;
+        // general path for this dword: it may run over a row end into the next row / channel / image
+        int j = j0, ii = i, cc2 = c2;
+        long long nn = n;
+        unsigned v = 0;
+        int nb = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if ((long long)e0 + u < a.total) {
+                const int bb = cc2 & 1, a2 = (cc2 >> 1) & 1, c1 = cc2 >> 2;
+                const int hh = 2 * ii + a2 - a.pad, ww = 2 * j + bb - a.pad;
+                int x = 0;
+                if (hh >= 0 && hh < a.H && ww >= 0 && ww < a.W) x = a.src[((nn * a.C + c1) * a.H + hh) * a.W + ww];
+                v |= (unsigned)(x & 0xFF) << (8 * u);
+                ++nb;
+                if (++j == a.W2) {
+                    j = 0;
+                    if (++ii == a.H2) {
+                        ii = 0;
+                        if (++cc2 == a.C2) {
+                            cc2 = 0;
+                            ++nn;
+                        }
+                    }
+                }
+            }
         }
+        if (nb == 4) *reinterpret_cast<unsigned *>(a.dst + e0) = v;
+        else
+            for (int u = 0; u < nb; ++u) a.dst[e0 + u] = (int8_t)(v >> (8 * u));
     }
 }
 
@@ -823,11 +842,8 @@ hipError_t launch_image_pack(int N, int C, int H, int W, int stride, int pad, in
     a.m_W2 = magic_for(W2);
     a.m_H2 = magic_for(H2);
     a.m_C2 = magic_for(a.C2);
-    const int cpr = (W2 + 15) / 16;  // 16-byte pieces per destination row
-    const long long items = (long long)N * a.C2 * H2 * cpr;
-    if (stride == 2 && items < (1LL << 31))
-        hipLaunchKernelGGL(image_pack_s2_kernel, dim3(grid_for(items, 256)), dim3(256), 0, st, a, cpr, magic_for(cpr),
-                           (int)items);
+    if (stride == 2 && a.total < (1LL << 31) - 4)
+        hipLaunchKernelGGL(image_pack_s2_kernel, dim3(grid_for((a.total + 3) / 4, 256)), dim3(256), 0, st, a);
     else
         hipLaunchKernelGGL(image_pack_kernel, dim3(grid_for((a.total + 3) / 4, 256)), dim3(256), 0, st, a);
     return hipGetLastError();
