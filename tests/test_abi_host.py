@@ -163,3 +163,37 @@ def test_image_pack_problem_and_sizes(lib, dims):
     # the GEMM-stage entry points take single-stage layouts only
     assert raw.conv2d_int8_packed(ctypes.byref(d), lib.LAYOUT_IMAGE_PACK, 16, None, None, None, -1, 0, None) != lib.OK
     assert lib.pack_weights_depth(C, R, S, lib.LAYOUT_IMAGE_PACK, 16) == 0
+
+
+def test_validation_of_the_newer_entry_points(lib):
+    """Every argument is checked before anything is enqueued: these calls pass null or bad arguments and
+    must return a status without touching a device."""
+    raw = lib.load()
+    d = lib.ConvDesc(1, 3, 16, 16, 8, 3, 3, 2, 1)
+    d2 = lib.ConvDesc()
+    assert raw.pack_layout_nhwc(1, 3, 4, 4, 16, 0, None, None, None) == lib.ERR_INVALID_ARG
+    assert raw.pack_layout_nhwc(1, 3, 4, 4, 8, 0, ctypes.c_void_p(256), ctypes.c_void_p(256), None) == lib.ERR_UNSUPPORTED
+    assert raw.pack_layout_nhwc(1, 0, 4, 4, 16, 0, ctypes.c_void_p(256), ctypes.c_void_p(256), None) == lib.ERR_INVALID_ARG
+    assert raw.image_pack_desc(ctypes.byref(d), None) == lib.ERR_INVALID_ARG
+    assert raw.image_pack_desc(None, ctypes.byref(d2)) == lib.ERR_INVALID_ARG
+    assert raw.image_pack_int8(ctypes.byref(d), None, None, None) == lib.ERR_INVALID_ARG
+    assert raw.image_pack_int8(ctypes.byref(d), ctypes.c_void_p(256), ctypes.c_void_p(258), None) == lib.ERR_INVALID_ARG  # dst % 4
+    assert raw.image_pack_weights(ctypes.byref(d), None, ctypes.c_void_p(256), None) == lib.ERR_INVALID_ARG
+    assert raw.image_pack_bytes(None) == 0 and raw.image_pack_weights_bytes(None) == 0
+    # IMAGE_PACK: only the two-stage entry points take it; a bad inner block is an invalid argument
+    a = ctypes.c_int64()
+    assert raw.layout_overheads(ctypes.byref(d), lib.LAYOUT_IMAGE_PACK, 24, ctypes.byref(a), None, None) == lib.ERR_INVALID_ARG
+    assert raw.conv2d_int8_ex(ctypes.byref(d), lib.LAYOUT_IMAGE_PACK, 16, None, None, 0, None, None, 0, None) == lib.ERR_INVALID_ARG
+    assert raw.conv2d_int8_ex(ctypes.byref(d), lib.LAYOUT_IMAGE_PACK, 16, ctypes.c_void_p(256), ctypes.c_void_p(256), 1,
+                              ctypes.c_void_p(256), ctypes.c_void_p(256), 1 << 30, None) == lib.ERR_UNSUPPORTED   # packed weights
+    assert raw.conv2d_int8_ex(ctypes.byref(d), lib.LAYOUT_IMAGE_PACK, 16, ctypes.c_void_p(256), ctypes.c_void_p(256), 0,
+                              ctypes.c_void_p(256), ctypes.c_void_p(256), 16, None) == lib.ERR_WORKSPACE
+    # IMPLICIT: forced tiles and splits, null operands
+    d3 = lib.ConvDesc(1, 3, 16, 16, 8, 3, 3, 1, 1)
+    assert raw.conv2d_int8_packed(ctypes.byref(d3), lib.LAYOUT_IMPLICIT, 0, None, None, None, -1, 0, None) == lib.ERR_INVALID_ARG
+    assert raw.conv2d_int8_packed(ctypes.byref(d3), lib.LAYOUT_IMPLICIT, 0, ctypes.c_void_p(256), ctypes.c_void_p(256),
+                                  ctypes.c_void_p(256), 3, 1, None) == lib.ERR_UNSUPPORTED
+    assert raw.conv2d_int8_ex(ctypes.byref(d3), lib.LAYOUT_IMPLICIT, 0, None, None, 0, None, None, 0, None) == lib.ERR_INVALID_ARG
+    big = lib.ConvDesc(1, 256, 14, 14, 8, 3, 3, 1, 1)
+    assert raw.conv2d_int8_ex(ctypes.byref(big), lib.LAYOUT_IMPLICIT, 0, ctypes.c_void_p(256), ctypes.c_void_p(256), 0,
+                              ctypes.c_void_p(256), None, 0, None) == lib.ERR_UNSUPPORTED
