@@ -147,3 +147,13 @@ def image_pack_weights(w: np.ndarray, stride: int) -> np.ndarray:
             for b in range(s):
                 y[:, (c * s + a) * s + b] = w0[:, c, a::s, b::s]
     return y
+
+
+def unpack_nhwc(out: np.ndarray) -> np.ndarray:
+    """Tensor unpacking for an NHWC consumer (Sec. 5.1 benchmark step, Sec. 5.2 layout):
+    [N,K,P,Q] -> [N,P,Q,K]; y[n][p][q][k] = out[n][k][p][q]."""
+    N, K, P, Q = out.shape
+    y = np.zeros((N, P, Q, K), dtype=out.dtype)
+    for k in range(K):
+        y[:, :, :, k] = out[:, k]
+    return y

@@ -170,3 +170,12 @@ def test_pack_layout_from_nhwc_source():
         c, h, w = b * cb + i, hp - pad, wp - pad
         want = xl[n][h][w][c] if (c < C and 0 <= h < H and 0 <= w < W) else 0
         assert y[n][b][hp][wp][i] == want
+
+
+def test_unpack_nhwc_elementwise():
+    o = (np.arange(2 * 5 * 3 * 4, dtype=np.int32) * 7919 - 100000).reshape(2, 5, 3, 4)
+    y = layouts.unpack_nhwc(o)
+    assert y.shape == (2, 3, 4, 5)
+    ol = o.tolist()
+    for n, k, p, q in itertools.product(range(2), range(5), range(3), range(4)):
+        assert y[n, p, q, k] == ol[n][k][p][q]
