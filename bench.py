@@ -264,7 +264,13 @@ def n_scaled(lib, timed, CONFIGS, dev):
     b = x.numel() + xp.numel()
     out["pack_layout_C4a_N2048"] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),
                                     "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2)}
-    del x, xp, o
+    # unpacking the NKPQ result for an NHWC consumer (int32, read once + written once)
+    oh = lib.unpack_nhwc_int32(o)
+    _, ms = timed(lambda: lib.unpack_nhwc_int32(o, out=oh), 10, 2)
+    b = 8 * o.numel()
+    out["unpack_nhwc_C4a_N2048"] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),
+                                    "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2)}
+    del x, xp, o, oh
     # pack_layout of the 64-channel 56x56 layer at N=2048 (~0.9 GiB moved)
     cfg = CONFIGS["C2"].scaled(2048)
     x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=dev)

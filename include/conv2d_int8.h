@@ -89,6 +89,12 @@ typedef struct {
 int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                 const int8_t *in, const int8_t *wt, int32_t *out, void *stream);
 
+/* The same for NHWC tensors (Sec. 5.2): in [N][H][W][C], wt KCRS, out [N][P][Q][K] int32.  Channel
+ * blocking straight from the NHWC source (pack_layout_nhwc), the GEMM stage into an NKPQ staging tensor
+ * in the cached workspace, then unpack_nhwc_int32: four launches.  Same workspace rules as conv2d_int8. */
+int conv2d_int8_nhwc(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                     const int8_t *in, const int8_t *wt, int32_t *out, void *stream);
+
 /* ---- explicit form --------------------------------------------------------------------
  * layout: a conv_layout_t (AUTO allowed).  cb: channel block for PACKED (16, 32 or 64;
  * 0 = library's choice); ignored for the other layouts.
@@ -137,6 +143,10 @@ size_t pack_layout_bytes(int N, int C, int H, int W, int cb, int pad);
  * cb a multiple of 16.  The GEMM stage and the NKPQ result are unchanged. */
 int pack_layout_nhwc(int N, int C, int H, int W, int cb, int pad,
                      const int8_t *src, int8_t *dst, void *stream);
+
+/* Tensor unpacking for an NHWC consumer (the last step of the benchmark of Sec. 5.1 in the layout
+ * of Sec. 5.2): dst[n][p][q][k] = src[n][k][p][q], int32. */
+int unpack_nhwc_int32(int N, int K, int P, int Q, const int32_t *src, int32_t *dst, void *stream);
 
 /* pack_weights (same rewrites on the weights, then Fuse of the reduction dimensions):
  *   dst[k][j], row length depth = pack_weights_depth(...), zero where no weight maps.

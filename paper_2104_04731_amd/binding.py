@@ -19,7 +19,7 @@ LAYOUT_NAMES = {LAYOUT_AUTO: "auto", LAYOUT_PACKED: "packed", LAYOUT_IM2COL: "im
                 LAYOUT_IMAGE_PACK: "image_pack"}
 
 EXPORTS = [
-    "conv2d_int8", "conv2d_int8_ex", "conv2d_int8_workspace_bytes", "conv2d_int8_packed",
+    "conv2d_int8", "conv2d_int8_nhwc", "unpack_nhwc_int32", "conv2d_int8_ex", "conv2d_int8_workspace_bytes", "conv2d_int8_packed",
     "conv2d_int8_query_tiling", "conv2d_int8_num_tiles", "conv2d_int8_tile_info",
     "conv2d_int8_tile_applies", "pack_layout", "pack_layout_bytes", "pack_layout_nhwc",
     "pack_weights", "pack_weights_depth", "pack_weights_bytes", "im2col_int8", "im2col_bytes",
@@ -56,6 +56,8 @@ def load(path: str | None = None):
     dp, ip = ctypes.POINTER(ConvDesc), ctypes.POINTER(ctypes.c_int)
     sig = {
         "conv2d_int8": (i, [i] * 9 + [vp, vp, vp, vp]),
+        "conv2d_int8_nhwc": (i, [i] * 9 + [vp, vp, vp, vp]),
+        "unpack_nhwc_int32": (i, [i] * 4 + [vp, vp, vp]),
         "conv2d_int8_ex": (i, [dp, i, i, vp, vp, i, vp, vp, sz, vp]),
         "conv2d_int8_workspace_bytes": (sz, [dp, i, i, i]),
         "conv2d_int8_packed": (i, [dp, i, i, vp, vp, vp, i, i, vp]),
@@ -132,6 +134,31 @@ def conv2d_int8(x: torch.Tensor, w: torch.Tensor, stride: int, pad: int, out=Non
         out = torch.empty((N, K, max(P, 0), max(Q, 0)), dtype=torch.int32, device=x.device)
     _check(load().conv2d_int8(N, C, H, W, K, R, S, stride, pad, _ptr(x), _ptr(w), _ptr(out),
                               _stream(stream)), "conv2d_int8")
+    return out
+
+
+def conv2d_int8_nhwc(x: torch.Tensor, w: torch.Tensor, stride: int, pad: int, out=None, stream=None):
+    """x: [N, H, W, C] int8, w: KCRS int8 -> [N, P, Q, K] int32."""
+    _require(x, torch.int8, "input"); _require(w, torch.int8, "weights")
+    N, H, W, C = x.shape
+    K, C2, R, S = w.shape
+    if C2 != C:
+        raise ValueError("channel mismatch")
+    P, Q = out_hw(H, W, R, S, stride, pad)
+    if out is None:
+        out = torch.empty((N, max(P, 0), max(Q, 0), K), dtype=torch.int32, device=x.device)
+    _check(load().conv2d_int8_nhwc(N, C, H, W, K, R, S, stride, pad, _ptr(x), _ptr(w), _ptr(out),
+                                   _stream(stream)), "conv2d_int8_nhwc")
+    return out
+
+
+def unpack_nhwc_int32(x: torch.Tensor, out=None, stream=None):
+    """[N, K, P, Q] int32 -> [N, P, Q, K] int32."""
+    _require(x, torch.int32, "NKPQ tensor")
+    N, K, P, Q = x.shape
+    if out is None:
+        out = torch.empty((N, P, Q, K), dtype=torch.int32, device=x.device)
+    _check(load().unpack_nhwc_int32(N, K, P, Q, _ptr(x), _ptr(out), _stream(stream)), "unpack_nhwc_int32")
     return out
 
 

@@ -258,6 +258,14 @@ int pack_layout_nhwc(int N, int C, int H, int W, int cb, int pad, const int8_t *
                ? CONV_OK : CONV_ERR_DEVICE;
 }
 
+int unpack_nhwc_int32(int N, int K, int P, int Q, const int32_t *src, int32_t *dst, void *stream)
+{
+    if (!src || !dst || N <= 0 || K <= 0 || P <= 0 || Q <= 0) return CONV_ERR_INVALID_ARG;
+    if ((long long)P * Q > INT_LIMIT) return CONV_ERR_UNSUPPORTED;
+    return launch_unpack_nhwc(N, K, (long long)P * Q, src, dst, (hipStream_t)stream) == hipSuccess ? CONV_OK
+                                                                                                  : CONV_ERR_DEVICE;
+}
+
 int pack_weights_depth(int C, int R, int S, int layout, int cb)
 {
     if (C <= 0 || R <= 0 || S <= 0) return 0;
@@ -550,6 +558,48 @@ int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int
         c.bytes = want;
     }
     return conv2d_int8_ex(&d, layout, cb, in, wt, 0, out, c.ptr, c.bytes, stream);
+}
+
+int conv2d_int8_nhwc(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                     const int8_t *in, const int8_t *wt, int32_t *out, void *stream)
+{
+    // channel blocking straight from the NHWC source, the usual GEMM stage into an NKPQ staging
+    // tensor in the workspace, then unpacking to NHWC
+    conv_desc_t d{N, C, H, W, K, R, S, stride, pad};
+    Plan pl;
+    int rc = make_plan(&d, CONV_LAYOUT_PACKED, 0, &pl);
+    if (rc != CONV_OK) return rc;
+    if (!in || !wt || !out) return CONV_ERR_INVALID_ARG;
+    const size_t xb = align_up(pl.x_bytes, WS_ALIGN), wb = align_up(pl.w_bytes, WS_ALIGN);
+    const size_t ob = align_up((size_t)pl.M * d.K * sizeof(int32_t), WS_ALIGN);
+    const size_t need = xb + wb + ob;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CONV_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    DeviceCache &c = g_cache[dev];
+    if (c.bytes < need) {
+        if (c.ptr) {
+            if (hipDeviceSynchronize() != hipSuccess) return CONV_ERR_DEVICE;
+            (void)hipFree(c.ptr);
+            c.ptr = nullptr;
+            c.bytes = 0;
+        }
+        const size_t want = align_up(need + need / 4, 1 << 20);
+        if (hipMalloc(&c.ptr, want) != hipSuccess) {
+            c.ptr = nullptr;
+            return CONV_ERR_WORKSPACE;
+        }
+        c.bytes = want;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    int8_t *xq = static_cast<int8_t *>(c.ptr), *wq = xq + xb;
+    int32_t *nkpq = reinterpret_cast<int32_t *>(wq + wb);
+    if (launch_pack_layout_nhwc(N, C, H, W, pl.cb, pad, in, xq, st) != hipSuccess) return CONV_ERR_DEVICE;
+    rc = rewrite_weights(&d, pl, wt, wq, st);
+    if (rc != CONV_OK) return rc;
+    rc = run_gemm(gemm_problem(&d, pl, xq, wq, nkpq), -1, 0, st);
+    if (rc != CONV_OK) return rc;
+    return launch_unpack_nhwc(N, K, (long long)pl.P * pl.Q, nkpq, out, st) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
 }
 
 }  // extern "C"

@@ -562,3 +562,21 @@ def test_image_pack_random_shapes(lib):
         out = torch.full((cfg.N, cfg.K, cfg.P, cfg.Q), -3, dtype=torch.int32, device=DEV)
         lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_IMAGE_PACK, 16, dev(x), dev(w), out, ws)
         assert np.array_equal(host(out), direct.conv2d_int8(x, w, cfg.stride, cfg.pad)), cfg.dims()
+
+
+# ---- NHWC tensors -------------------------------------------------------------------------------
+@pytest.mark.parametrize("shape", [(2, 5, 3, 4), (1, 64, 14, 14), (3, 33, 7, 9), (1, 1, 1, 1), (2, 130, 1, 37)])
+def test_unpack_nhwc(lib, shape):
+    o = (np.arange(int(np.prod(shape)), dtype=np.int64) * 2654435761 % (1 << 31) - (1 << 30)).astype(np.int32).reshape(shape)
+    np.testing.assert_array_equal(host(lib.unpack_nhwc_int32(dev(o))), layouts.unpack_nhwc(o))
+
+
+@pytest.mark.parametrize("cfg", [CONFIGS["C1"], CONFIGS["C2"], CONFIGS["C4a"], CONFIGS["C4b"], CONFIGS["C3"],
+                                 ConvShape("nhwc-ragged", 2, 37, 9, 11, 21, 3, 2, 2, 1)], ids=lambda c: c.name)
+def test_conv_nhwc_one_shot(lib, cfg):
+    """NHWC in, NHWC out: the NCHW definition seen through transposed views."""
+    x = uniform_int8(611, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(612, (cfg.K, cfg.C, cfg.R, cfg.S))
+    want = layouts.unpack_nhwc(direct.conv2d_int8(x, w, cfg.stride, cfg.pad))
+    xh = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+    got = host(lib.conv2d_int8_nhwc(dev(xh), dev(w), cfg.stride, cfg.pad))
+    assert got.shape == want.shape and np.array_equal(got, want)
