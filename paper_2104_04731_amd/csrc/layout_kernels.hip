@@ -709,31 +709,33 @@ hipError_t launch_pack_layout_nhwc(int N, int C, int H, int W, int cb, int pad, 
 }
 
 // ---- unpacking for an NHWC consumer: [N][K][PQ] int32 -> [N][PQ][K] ---------------------------
-// 32x32 tiles through LDS (pitch 33: the row-wise writes and column-wise reads are both
-// conflict-free); reads run along pixels, writes along channels, 128-byte runs on both sides.
+// Tiles of 64 channels x 32 pixels through LDS (pitch 33: the pixel-wise writes and the
+// channel-wise reads are both conflict-free); reads run along pixels in 128-byte runs, writes
+// along channels in 256-byte runs.
 __global__ void __launch_bounds__(256) unpack_nhwc_kernel(const int32_t *src, int32_t *dst, int K, int PQ,
                                                           int tiles_k, int tiles_p, long long ntiles)
 {
-    __shared__ int32_t tile[32][33];
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    __shared__ int32_t tile[64][33];
+    const int rx = threadIdx.x & 31, ry = threadIdx.x >> 5;  // read:  32 pixels x 8 channel rows per pass
+    const int wx = threadIdx.x & 63, wy = threadIdx.x >> 6;  // write: 64 channels x 4 pixel rows per pass
     for (long long t = blockIdx.x; t < ntiles; t += gridDim.x) {
         const int tp = (int)(t % tiles_p);
         const long long r = t / tiles_p;
         const int tk = (int)(r % tiles_k);
         const long long n = r / tiles_k;
-        const int k0 = tk * 32, p0 = tp * 32;
+        const int k0 = tk * 64, p0 = tp * 32;
         const int32_t *s = src + (size_t)n * K * PQ;
         int32_t *d = dst + (size_t)n * PQ * K;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int k = k0 + ty + 8 * i, p = p0 + tx;
-            if (k < K && p < PQ) tile[ty + 8 * i][tx] = s[(size_t)k * PQ + p];
+        for (int i = 0; i < 8; ++i) {
+            const int k = k0 + ry + 8 * i, p = p0 + rx;
+            if (k < K && p < PQ) tile[ry + 8 * i][rx] = s[(size_t)k * PQ + p];
         }
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int p = p0 + ty + 8 * i, k = k0 + tx;
-            if (k < K && p < PQ) d[(size_t)p * K + k] = tile[tx][ty + 8 * i];
+        for (int i = 0; i < 8; ++i) {
+            const int p = p0 + wy + 4 * i, k = k0 + wx;
+            if (k < K && p < PQ) d[(size_t)p * K + k] = tile[wx][wy + 4 * i];
         }
         __syncthreads();
     }
@@ -741,7 +743,7 @@ __global__ void __launch_bounds__(256) unpack_nhwc_kernel(const int32_t *src, in
 
 hipError_t launch_unpack_nhwc(int N, int K, long long PQ, const int32_t *src, int32_t *dst, hipStream_t st)
 {
-    const int tiles_k = (K + 31) / 32, tiles_p = (int)((PQ + 31) / 32);
+    const int tiles_k = (K + 63) / 64, tiles_p = (int)((PQ + 31) / 32);
     const long long ntiles = (long long)N * tiles_k * tiles_p;
     hipLaunchKernelGGL(unpack_nhwc_kernel, dim3(grid_for(ntiles * 256, 256)), dim3(256), 0, st, src, dst, K, (int)PQ,
                        tiles_k, tiles_p, ntiles);
