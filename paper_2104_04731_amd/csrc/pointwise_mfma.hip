@@ -13,7 +13,8 @@
 //      XT[pixel][channel] (pitch C + 16 bytes: 32 rows start in different bank groups);
 //   3. v_mfma_i32_32x32x32_i8, channels x pixels, activation operand = 16 bytes of XT row lane%32;
 //   4. the D block (column = pixel = lane%32) goes straight to NKPQ in 128-byte runs.
-// All global loads of a thread are issued before its first LDS store.
+// All global loads of a thread are issued before its first LDS store; a workgroup that has more
+// than one tile keeps its weight operands and fetches the next tile's pixels during the current one.
 #include "kernels.h"
 #include "rewrite_bodies.h"
 
@@ -67,18 +68,24 @@ __global__ void __launch_bounds__(256) conv_pointwise_kernel(const PointArgs a)
     }
     // A workgroup keeps its weight operands in registers and walks over pixel tiles gridDim.x apart.
     const int g = tid & 7, cq = tid >> 3;
-    for (int lid = xcd_contiguous(blockIdx.x, gridDim.x); lid < a.ntiles; lid += gridDim.x) {
-    const int n = fast_div_any(lid, a.tiles, a.m_tiles), px0 = (lid - n * a.tiles) * 32;
-    // 2. activations: pixels px0 + 4g .. +3 (HW is a multiple of 4: a group is inside the image or past it)
-    const int px = min(px0 + 4 * g, a.HW - 4);
-    const int8_t *img = a.in + (size_t)n * C * a.HW + px;
+    // The next tile's pixels are fetched while this tile is multiplied and stored.
     unsigned xv[PASSES][4];
+    // 2. activations: pixels px0 + 4g .. +3 (HW is a multiple of 4: a group is inside the image or past it)
+    auto fetch = [&](int tile) {
+        const int n = fast_div_any(tile, a.tiles, a.m_tiles), px0 = (tile - n * a.tiles) * 32;
+        const int px = min(px0 + 4 * g, a.HW - 4);
+        const int8_t *img = a.in + (size_t)n * C * a.HW + px;
 #pragma unroll
-    for (int ps = 0; ps < PASSES; ++ps) {
-        const int q = min(cq + 32 * ps, QUADS - 1);
+        for (int ps = 0; ps < PASSES; ++ps) {
+            const int q = min(cq + 32 * ps, QUADS - 1);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) xv[ps][j] = ld_u32(img + (size_t)(4 * q + j) * a.HW);
-    }
+            for (int j = 0; j < 4; ++j) xv[ps][j] = ld_u32(img + (size_t)(4 * q + j) * a.HW);
+        }
+    };
+    const int lid0 = xcd_contiguous(blockIdx.x, gridDim.x);
+    if (lid0 < a.ntiles) fetch(lid0);
+    for (int lid = lid0; lid < a.ntiles; lid += gridDim.x) {
+    const int n = fast_div_any(lid, a.tiles, a.m_tiles), px0 = (lid - n * a.tiles) * 32;
 #pragma unroll
     for (int ps = 0; ps < PASSES; ++ps) {
         const int q = cq + 32 * ps;
@@ -96,6 +103,7 @@ __global__ void __launch_bounds__(256) conv_pointwise_kernel(const PointArgs a)
         }
     }
     __syncthreads();
+    if (lid + (int)gridDim.x < a.ntiles) fetch(lid + (int)gridDim.x);
 
     // 3. MFMA
     v16i acc;
