@@ -157,3 +157,16 @@ def unpack_nhwc(out: np.ndarray) -> np.ndarray:
     for k in range(K):
         y[:, :, :, k] = out[:, k]
     return y
+
+
+def requant(x: np.ndarray, shift: int, relu: bool) -> np.ndarray:
+    """Activation between two int8 layers, as the accelerator's ALU does it (Sec. 5.1: shift, min, max
+    on the 32-bit accumulator): rounding right shift (half rounds towards +infinity),
+    optional max(., 0), then clipping to int8.  y = clip(relu(floor(x / 2^shift + 1/2)), -128, 127)."""
+    assert 0 <= shift <= 31
+    v = x.astype(np.int64)
+    if shift > 0:
+        v = (v + (1 << (shift - 1))) >> shift     # arithmetic shift = floor division by 2^shift
+    if relu:
+        v = np.maximum(v, 0)
+    return np.clip(v, -128, 127).astype(np.int8)

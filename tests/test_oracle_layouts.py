@@ -179,3 +179,30 @@ def test_unpack_nhwc_elementwise():
     ol = o.tolist()
     for n, k, p, q in itertools.product(range(2), range(5), range(3), range(4)):
         assert y[n, p, q, k] == ol[n][k][p][q]
+
+
+def test_requant_against_exact_rational_arithmetic():
+    """floor(x / 2^s + 1/2) computed with Python integers and Fractions, every case of sign and tie."""
+    from fractions import Fraction
+    import math
+    xs = [0, 1, -1, 2, -2, 3, -3, 7, 8, -8, 9, 127, 128, 129, -127, -128, -129, 255, 256, -255, -256, 1000, -1000,
+          16383, 16384, -16384, 37748736, -37748736, 2 ** 31 - 1, -2 ** 31]
+    xs += [v * 8 + d for v in range(-20, 21) for d in (-4, -3, 0, 3, 4, 5)]       # ties at shift 3: d = +-4
+    x = np.array(xs, dtype=np.int32)
+    for shift in (0, 1, 3, 4, 8, 17, 31):
+        for relu in (False, True):
+            got = layouts.requant(x, shift, relu).tolist()
+            for v, g in zip(xs, got):
+                r = math.floor(Fraction(v, 2 ** shift) + Fraction(1, 2))
+                if relu:
+                    r = max(r, 0)
+                assert g == min(max(r, -128), 127), (v, shift, relu)
+    # monotone, and the identity on int8 values when nothing is shifted
+    ramp = np.arange(-70000, 70000, 7, dtype=np.int32)
+    for shift in (0, 5, 9):
+        y = layouts.requant(ramp, shift, False).astype(np.int32)
+        assert np.all(np.diff(y) >= 0)
+    small = np.arange(-128, 128, dtype=np.int32)
+    np.testing.assert_array_equal(layouts.requant(small, 0, False), small.astype(np.int8))
+    np.testing.assert_array_equal(layouts.requant(small, 0, True), np.maximum(small, 0).astype(np.int8))
+    assert layouts.requant(np.array([4, -4, 12, -12], np.int32), 3, False).tolist() == [1, 0, 2, -1]   # ties go up
