@@ -194,6 +194,25 @@ def main():
         two_stage = {"ms_per_step": round(ts_ms, 6), "value": round(head_ops / (ts_ms * 1e-3) / 1e12, 4),
                      "layouts": ["packed/cb64"] * len(head)}
 
+    # config 4 read as a chain (the second layer consumes the first one's activated output): convolution,
+    # activation + the next layer's channel blocking in one pass, weight rewrite, GEMM stage -- reported
+    # beside `value`, which times the two layers on independent inputs
+    chained = None
+    if args.workload == "C4":
+        a4, b4 = head
+        xq = lib.requant_pack_layout(a4.out, 64, b4.cfg.pad, 9, True)
+        wq = lib.pack_weights(b4.w, lib.LAYOUT_PACKED, 64)
+
+        def step_chained():
+            a4.combined()
+            lib.requant_pack_layout(a4.out, 64, b4.cfg.pad, 9, True, out=xq)
+            lib.pack_weights(b4.w, lib.LAYOUT_PACKED, 64, out=wq)
+            lib.conv2d_int8_packed(b4.cfg.dims(), lib.LAYOUT_PACKED, 64, xq, wq, b4.out)
+
+        ch_ms, _ = timed(step_chained, args.steps, args.warmup)
+        chained = {"ms_per_step": round(ch_ms, 6), "value": round(head_ops / (ch_ms * 1e-3) / 1e12, 4),
+                   "path": "conv2d_int8(C4a) -> requant_pack_layout(shift 9, relu) -> pack_weights -> GEMM stage(C4b)"}
+
     # dominant kernel of the step: the MFMA GEMM stage of the largest convolution
     dom = max(head, key=lambda c: c.cfg.ops)
     _, dom_ms = timed(dom.op, args.steps, args.warmup)
@@ -226,6 +245,7 @@ def main():
         "event_ms_per_step": round(ev_ms, 6),
         "pct_mfma_peak": round(100 * value * 1e12 / PEAK_INT8_OPS, 3),
         "rewrite_then_gemm_only": two_stage,
+        "chained_with_activation": chained,
         "roofline": roofline,
     }
 
@@ -270,7 +290,13 @@ def n_scaled(lib, timed, CONFIGS, dev):
     b = 8 * o.numel()
     out["unpack_nhwc_C4a_N2048"] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),
                                     "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2)}
-    del x, xp, o, oh
+    # activation + the next layer's channel blocking in one pass (int32 read once, int8 blocks written once)
+    xq = lib.requant_pack_layout(o, 64, 0, 9, True)
+    _, ms = timed(lambda: lib.requant_pack_layout(o, 64, 0, 9, True, out=xq), 10, 2)
+    b = 4 * o.numel() + xq.numel()
+    out["requant_pack_C4a_N2048"] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),
+                                     "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2)}
+    del x, xp, o, oh, xq
     # pack_layout of the 64-channel 56x56 layer at N=2048 (~0.9 GiB moved)
     cfg = CONFIGS["C2"].scaled(2048)
     x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=dev)

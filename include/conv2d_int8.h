@@ -144,6 +144,19 @@ size_t pack_layout_bytes(int N, int C, int H, int W, int cb, int pad);
 int pack_layout_nhwc(int N, int C, int H, int W, int cb, int pad,
                      const int8_t *src, int8_t *dst, void *stream);
 
+/* Activation between two int8 layers -- the step between convolution and unpacking in the benchmark
+ * of Sec. 5.1, done there by the accelerator's ALU (shift, min, max).  The paper gives no formula; here
+ *   y = clip(relu ? max(r, 0) : r, -128, 127),  r = floor(x / 2^shift + 1/2)   (0 <= shift <= 31)
+ * requant_int8: same element order, int32 -> int8, `count` elements.
+ * requant_pack_layout: the activation and the next layer's channel blocking in one pass -- from an NKPQ
+ *   int32 result straight to what pack_layout would make of its int8 image:
+ *   dst[n][k/cb][p+pad][q+pad][k%cb] = y(src[n][k][p][q]), zero where k >= K and on the border;
+ *   cb a multiple of 16; dst holds pack_layout_bytes(N, K, P, Q, cb, pad) bytes, 16-byte aligned.
+ *   Its output feeds conv2d_int8_packed (PACKED, cb) of the next layer directly. */
+int requant_int8(long long count, const int32_t *src, int8_t *dst, int shift, int relu, void *stream);
+int requant_pack_layout(int N, int K, int P, int Q, int cb, int pad, int shift, int relu,
+                        const int32_t *src, int8_t *dst, void *stream);
+
 /* Tensor unpacking for an NHWC consumer (the last step of the benchmark of Sec. 5.1 in the layout
  * of Sec. 5.2): dst[n][p][q][k] = src[n][k][p][q], int32. */
 int unpack_nhwc_int32(int N, int K, int P, int Q, const int32_t *src, int32_t *dst, void *stream);

@@ -19,7 +19,7 @@ LAYOUT_NAMES = {LAYOUT_AUTO: "auto", LAYOUT_PACKED: "packed", LAYOUT_IM2COL: "im
                 LAYOUT_IMAGE_PACK: "image_pack"}
 
 EXPORTS = [
-    "conv2d_int8", "conv2d_int8_nhwc", "unpack_nhwc_int32", "conv2d_int8_ex", "conv2d_int8_workspace_bytes", "conv2d_int8_packed",
+    "conv2d_int8", "conv2d_int8_nhwc", "unpack_nhwc_int32", "requant_int8", "requant_pack_layout", "conv2d_int8_ex", "conv2d_int8_workspace_bytes", "conv2d_int8_packed",
     "conv2d_int8_query_tiling", "conv2d_int8_num_tiles", "conv2d_int8_tile_info",
     "conv2d_int8_tile_applies", "pack_layout", "pack_layout_bytes", "pack_layout_nhwc",
     "pack_weights", "pack_weights_depth", "pack_weights_bytes", "im2col_int8", "im2col_bytes",
@@ -58,6 +58,8 @@ def load(path: str | None = None):
         "conv2d_int8": (i, [i] * 9 + [vp, vp, vp, vp]),
         "conv2d_int8_nhwc": (i, [i] * 9 + [vp, vp, vp, vp]),
         "unpack_nhwc_int32": (i, [i] * 4 + [vp, vp, vp]),
+        "requant_int8": (i, [ctypes.c_longlong, vp, vp, i, i, vp]),
+        "requant_pack_layout": (i, [i] * 8 + [vp, vp, vp]),
         "conv2d_int8_ex": (i, [dp, i, i, vp, vp, i, vp, vp, sz, vp]),
         "conv2d_int8_workspace_bytes": (sz, [dp, i, i, i]),
         "conv2d_int8_packed": (i, [dp, i, i, vp, vp, vp, i, i, vp]),
@@ -159,6 +161,28 @@ def unpack_nhwc_int32(x: torch.Tensor, out=None, stream=None):
     if out is None:
         out = torch.empty((N, P, Q, K), dtype=torch.int32, device=x.device)
     _check(load().unpack_nhwc_int32(N, K, P, Q, _ptr(x), _ptr(out), _stream(stream)), "unpack_nhwc_int32")
+    return out
+
+
+def requant_int8(x: torch.Tensor, shift: int, relu: bool, out=None, stream=None):
+    """int32 tensor -> int8 tensor of the same shape: clip(relu(floor(x / 2^shift + 1/2)))."""
+    _require(x, torch.int32, "accumulator tensor")
+    if out is None:
+        out = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    _check(load().requant_int8(x.numel(), _ptr(x), _ptr(out), shift, int(relu), _stream(stream)), "requant_int8")
+    return out
+
+
+def requant_pack_layout(x: torch.Tensor, cb: int, pad: int, shift: int, relu: bool, out=None, stream=None):
+    """[N, K, P, Q] int32 -> [N, ceil(K/cb), P+2pad, Q+2pad, cb] int8: activation + the next layer's blocking."""
+    _require(x, torch.int32, "accumulator tensor")
+    N, K, P, Q = x.shape
+    if out is None:
+        if cb % 16:
+            _check(ERR_UNSUPPORTED, "requant_pack_layout")
+        out = torch.empty((N, (K + cb - 1) // cb, P + 2 * pad, Q + 2 * pad, cb), dtype=torch.int8, device=x.device)
+    _check(load().requant_pack_layout(N, K, P, Q, cb, pad, shift, int(relu), _ptr(x), _ptr(out), _stream(stream)),
+           "requant_pack_layout")
     return out
 
 

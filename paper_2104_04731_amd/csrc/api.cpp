@@ -258,6 +258,24 @@ int pack_layout_nhwc(int N, int C, int H, int W, int cb, int pad, const int8_t *
                ? CONV_OK : CONV_ERR_DEVICE;
 }
 
+int requant_int8(long long count, const int32_t *src, int8_t *dst, int shift, int relu, void *stream)
+{
+    if (!src || !dst || count <= 0 || shift < 0 || shift > 31) return CONV_ERR_INVALID_ARG;
+    return launch_requant(count, src, dst, shift, relu != 0, (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+}
+
+int requant_pack_layout(int N, int K, int P, int Q, int cb, int pad, int shift, int relu, const int32_t *src,
+                        int8_t *dst, void *stream)
+{
+    if (!src || !dst || N <= 0 || K <= 0 || P <= 0 || Q <= 0 || pad < 0 || shift < 0 || shift > 31)
+        return CONV_ERR_INVALID_ARG;
+    if (cb < 16 || cb > 1024 || cb % 16) return CONV_ERR_UNSUPPORTED;
+    if (!aligned16(dst)) return CONV_ERR_INVALID_ARG;
+    if ((long long)P + 2LL * pad > INT_LIMIT || (long long)Q + 2LL * pad > INT_LIMIT) return CONV_ERR_UNSUPPORTED;
+    return launch_requant_pack(N, K, P, Q, cb, pad, shift, relu != 0, src, dst, (hipStream_t)stream) == hipSuccess
+               ? CONV_OK : CONV_ERR_DEVICE;
+}
+
 int unpack_nhwc_int32(int N, int K, int P, int Q, const int32_t *src, int32_t *dst, void *stream)
 {
     if (!src || !dst || N <= 0 || K <= 0 || P <= 0 || Q <= 0) return CONV_ERR_INVALID_ARG;

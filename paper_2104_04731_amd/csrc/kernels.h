@@ -42,6 +42,9 @@ hipError_t launch_pack_layout(int N, int C, int H, int W, int cb, int pad,
                               const int8_t *src, int8_t *dst, hipStream_t st);
 hipError_t launch_pack_layout_nhwc(int N, int C, int H, int W, int cb, int pad,
                                    const int8_t *src, int8_t *dst, hipStream_t st);  // cb % 16 == 0
+hipError_t launch_requant(long long count, const int32_t *src, int8_t *dst, int shift, int relu, hipStream_t st);
+hipError_t launch_requant_pack(int N, int K, int P, int Q, int cb, int pad, int shift, int relu, const int32_t *src,
+                               int8_t *dst, hipStream_t st);
 hipError_t launch_unpack_nhwc(int N, int K, long long PQ, const int32_t *src, int32_t *dst, hipStream_t st);
 hipError_t launch_pack_weights_blocked(int K, int C, int R, int S, int cb, int depth,
                                        const int8_t *src, int8_t *dst, hipStream_t st);

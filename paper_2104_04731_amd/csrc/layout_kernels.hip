@@ -750,6 +750,105 @@ hipError_t launch_unpack_nhwc(int N, int K, long long PQ, const int32_t *src, in
     return hipGetLastError();
 }
 
+// ---- activation between two int8 layers (Sec. 5.1: the accelerator's ALU; the benchmark's step
+// between convolution and unpacking): rounding right shift, optional max(., 0), clip to int8 -------
+__device__ __forceinline__ int requant1(int x, int shift, int relu)
+{
+    // floor(x / 2^shift + 1/2) without leaving 32 bits: floor(x / 2^shift) + bit (shift-1) of x
+    int v = shift > 0 ? (x >> shift) + ((x >> (shift - 1)) & 1) : x;
+    if (relu) v = max(v, 0);
+    return min(max(v, -128), 127);
+}
+
+// same element order, int32 -> int8; one thread per 16 elements
+__global__ void __launch_bounds__(256) requant_kernel(const int32_t *src, int8_t *dst, long long count, int shift, int relu)
+{
+    const long long n16 = (count + 15) / 16;
+    for (long long t = (long long)blockIdx.x * 256 + threadIdx.x; t < n16; t += (long long)gridDim.x * 256) {
+        const long long e0 = 16 * t;
+        if (e0 + 16 <= count) {
+            v4i o;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                v4i x;
+                __builtin_memcpy(&x, src + e0 + 4 * j, 16);
+                o[j] = (int)pack4(requant1(x[0], shift, relu), requant1(x[1], shift, relu), requant1(x[2], shift, relu),
+                                  requant1(x[3], shift, relu));
+            }
+            __builtin_memcpy(dst + e0, &o, 16);
+        } else {
+            for (long long e = e0; e < count; ++e) dst[e] = (int8_t)requant1(src[e], shift, relu);
+        }
+    }
+}
+
+// activation and the next layer's channel blocking in one pass:
+// dst[n][k/cb][p+pad][q+pad][k%cb] = requant(src[n][k][p][q]); zero where k >= K and on the border.
+// One thread per 16 destination bytes (16 channels of one pixel: 16 loads a plane apart).
+struct RequantPackArgs {
+    const int32_t *src;
+    int8_t *dst;
+    int K, P, Q, cb, pad, Hp, Wp, Cb, g16, shift, relu;
+    long long total;
+    unsigned m_g16, m_Wp, m_Hp, m_Cb;
+};
+
+__global__ void __launch_bounds__(256) requant_pack_kernel(const RequantPackArgs a)
+{
+    const size_t PQ = (size_t)a.P * a.Q;
+    for (long long t = (long long)blockIdx.x * 256 + threadIdx.x; t < a.total; t += (long long)gridDim.x * 256) {
+        int c16, wp, hp, b;
+        long long n;
+        if (a.total < (1LL << 31)) {
+            const int i0 = (int)t;
+            const int i1 = fast_div_any(i0, a.g16, a.m_g16); c16 = i0 - i1 * a.g16;
+            const int i2 = fast_div_any(i1, a.Wp, a.m_Wp); wp = i1 - i2 * a.Wp;
+            const int i3 = fast_div_any(i2, a.Hp, a.m_Hp); hp = i2 - i3 * a.Hp;
+            const int i4 = fast_div_any(i3, a.Cb, a.m_Cb); b = i3 - i4 * a.Cb;
+            n = i4;
+        } else {
+            long long r = t;
+            c16 = (int)(r % a.g16); r /= a.g16;
+            wp = (int)(r % a.Wp); r /= a.Wp;
+            hp = (int)(r % a.Hp); r /= a.Hp;
+            b = (int)(r % a.Cb); n = r / a.Cb;
+        }
+        const int k0 = b * a.cb + c16 * 16, p = hp - a.pad, q = wp - a.pad;
+        v4i o = {0, 0, 0, 0};
+        if (p >= 0 && p < a.P && q >= 0 && q < a.Q && k0 < a.K) {
+            const int32_t *s = a.src + ((size_t)n * a.K + k0) * PQ + (size_t)p * a.Q + q;
+            int v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[i] = k0 + i < a.K ? requant1(s[(size_t)i * PQ], a.shift, a.relu) : 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) o[j] = (int)pack4(v[4 * j], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]);
+        }
+        reinterpret_cast<v4i *>(a.dst)[t] = o;
+    }
+}
+
+hipError_t launch_requant(long long count, const int32_t *src, int8_t *dst, int shift, int relu, hipStream_t st)
+{
+    hipLaunchKernelGGL(requant_kernel, dim3(grid_for((count + 15) / 16, 256)), dim3(256), 0, st, src, dst, count, shift,
+                       relu);
+    return hipGetLastError();
+}
+
+hipError_t launch_requant_pack(int N, int K, int P, int Q, int cb, int pad, int shift, int relu, const int32_t *src,
+                               int8_t *dst, hipStream_t st)
+{
+    RequantPackArgs a{};
+    a.src = src; a.dst = dst;
+    a.K = K; a.P = P; a.Q = Q; a.cb = cb; a.pad = pad; a.shift = shift; a.relu = relu;
+    a.Hp = P + 2 * pad; a.Wp = Q + 2 * pad;
+    a.Cb = (K + cb - 1) / cb;
+    a.g16 = cb / 16;
+    a.total = (long long)N * a.Cb * a.Hp * a.Wp * a.g16;
+    a.m_g16 = magic_for(a.g16); a.m_Wp = magic_for(a.Wp); a.m_Hp = magic_for(a.Hp); a.m_Cb = magic_for(a.Cb);
+    hipLaunchKernelGGL(requant_pack_kernel, dim3(grid_for(a.total, 256)), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
 // ---- Image Pack (Table 2, row 1: the stride phases of the padded image become channels) -----
 // dst[n][(c*s + a)*s + b][i][j] = in0[n][c][s*i + a - pad][s*j + b - pad]; one thread per four
 // consecutive destination bytes (any alignment of rows; the flat tail is written byte-wise)

@@ -580,3 +580,37 @@ def test_conv_nhwc_one_shot(lib, cfg):
     xh = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
     got = host(lib.conv2d_int8_nhwc(dev(xh), dev(w), cfg.stride, cfg.pad))
     assert got.shape == want.shape and np.array_equal(got, want)
+
+
+# ---- activation between layers -------------------------------------------------------------------
+@pytest.mark.parametrize("shift,relu", [(0, False), (0, True), (1, False), (7, True), (10, False), (31, False)])
+def test_requant(lib, shift, relu):
+    rng = np.random.default_rng(700 + shift)
+    x = rng.integers(-2 ** 31, 2 ** 31, size=(3, 5, 7, 11), dtype=np.int64).astype(np.int32)
+    x.reshape(-1)[:8] = [0, -1, 2 ** 31 - 1, -2 ** 31, 1 << max(shift - 1, 0), -(1 << max(shift - 1, 0)), 127 << shift if shift < 24 else 5, -128]
+    small = rng.integers(-(300 << min(shift, 20)), 300 << min(shift, 20), size=x.shape, dtype=np.int64).astype(np.int32)
+    for t in (x, small):
+        np.testing.assert_array_equal(host(lib.requant_int8(dev(t), shift, relu)), layouts.requant(t, shift, relu))
+        for cb, pad in ((16, 1), (64, 0)):
+            want = layouts.pack_layout(layouts.requant(t, shift, relu), cb, pad)
+            np.testing.assert_array_equal(host(lib.requant_pack_layout(dev(t), cb, pad, shift, relu)), want)
+
+
+def test_chained_layers_stay_blocked(lib):
+    """C4a, activation, C4b with the intermediate never leaving the blocked layout: the second layer's GEMM
+    stage consumes what requant_pack_layout wrote.  Checked against convolution, activation, convolution
+    by definition."""
+    a, b = CONFIGS["C4a"], CONFIGS["C4b"]
+    assert (a.N, a.K, a.P, a.Q) == (b.N, b.C, b.H, b.W)
+    x, w1, mid = oracle_conv(a)
+    w2 = uniform_int8(801, (b.K, b.C, b.R, b.S))
+    shift, relu = 9, True
+    act = layouts.requant(mid, shift, relu)
+    assert 0 < np.count_nonzero(act) and act.max() == 127 and len(np.unique(act)) > 100   # the activation is exercised
+    want = direct.conv2d_int8(act, w2, b.stride, b.pad)
+    out1 = lib.conv2d_int8(dev(x), dev(w1), a.stride, a.pad)
+    xq = lib.requant_pack_layout(out1, 64, b.pad, shift, relu)
+    wq = lib.pack_weights(dev(w2), lib.LAYOUT_PACKED, 64)
+    out2 = torch.empty((b.N, b.K, b.P, b.Q), dtype=torch.int32, device=DEV)
+    lib.conv2d_int8_packed(b.dims(), lib.LAYOUT_PACKED, 64, xq, wq, out2)
+    assert np.array_equal(host(out2), want)
