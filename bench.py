@@ -32,7 +32,7 @@ PEAK_HBM_BPS = 8.0e12    # HBM3E
 TRAFFIC = {
     "source": "paper_2104_04731_amd/csrc/igemm_mfma.hip",
     "sha256": "6ad1e9aa9702ea1639df2c5381bbbcfec980e722d86ea08890d267ed2e3f1387",
-    "fetch_bytes": 5478824,
+    "fetch_bytes": 5478848,
     "write_bytes": 3211264,
 }
 
