@@ -32,7 +32,7 @@ PEAK_HBM_BPS = 8.0e12    # HBM3E
 TRAFFIC = {
     "source": "paper_2104_04731_amd/csrc/igemm_mfma.hip",
     "sha256": "6ad1e9aa9702ea1639df2c5381bbbcfec980e722d86ea08890d267ed2e3f1387",
-    "fetch_bytes": 5478848,
+    "fetch_bytes": 5478897,
     "write_bytes": 3211264,
 }
 
@@ -179,7 +179,7 @@ def main():
     # the same step with every convolution forced through stored rewrites (channel blocking, block 64,
     # caller workspace): input rewrite + weight rewrite, then the GEMM stage -- reported beside `value`
     two_stage = None
-    if any(c.layout == lib.LAYOUT_IMPLICIT for c in head):
+    if not args.no_extras and any(c.layout == lib.LAYOUT_IMPLICIT for c in head):
         ws = []
         for c in head:
             nb = lib.conv2d_int8_workspace_bytes(c.cfg.dims(), lib.LAYOUT_PACKED, 64)
@@ -198,7 +198,7 @@ def main():
     # activation + the next layer's channel blocking in one pass, weight rewrite, GEMM stage -- reported
     # beside `value`, which times the two layers on independent inputs
     chained = None
-    if args.workload == "C4":
+    if not args.no_extras and args.workload == "C4":
         a4, b4 = head
         xq = lib.requant_pack_layout(a4.out, 64, b4.cfg.pad, 9, True)
         wq = lib.pack_weights(b4.w, lib.LAYOUT_PACKED, 64)
