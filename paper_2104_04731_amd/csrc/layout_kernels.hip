@@ -267,10 +267,13 @@ __device__ __forceinline__ void pack_weights_rows_body(const WeightArgs &a, int 
     const int total = K * chunks;  // < 2^31 (launcher-checked)
     for (int t = vbid * 256 + (int)threadIdx.x; t < total; t += vgrid * 256) {
         const int k = fast_div_any(t, chunks, a.m_chunks), ch = t - k * chunks;
-        const int8_t *s = src + (long long)k * CRS + ch * 16;
+        const int8_t *s = src + (long long)k * CRS;
         int v[16];
+        // sixteen loads with no branch between them (positions past the row re-read its last byte)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) v[i] = (ch * 16 + i < CRS) ? s[i] : 0;
+        for (int i = 0; i < 16; ++i) v[i] = s[min(ch * 16 + i, CRS - 1)];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = ch * 16 + i < CRS ? v[i] : 0;
         v4i o;
         o[0] = pack4(v[0], v[1], v[2], v[3]);
         o[1] = pack4(v[4], v[5], v[6], v[7]);
@@ -321,13 +324,13 @@ im2col_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
         int s = j % S, cr = j / S;
         int r = cr % R, c = cr / R;
         int v[16];
+        bool in[16];
+        // the sixteen loads first, from coordinates clamped into the image (no branch between them)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int h = h0 + r, w = w0 + s;
-            int x = 0;
-            if (j + i < kg && h >= 0 && h < H && w >= 0 && w < W)
-                x = img[((long long)c * H + h) * W + w];
-            v[i] = x;
+            in[i] = j + i < kg && h >= 0 && h < H && w >= 0 && w < W;
+            v[i] = img[((long long)min(c, C - 1) * H + min(max(h, 0), H - 1)) * W + min(max(w, 0), W - 1)];
             if (++s == S) {
                 s = 0;
                 if (++r == R) {
@@ -336,6 +339,8 @@ im2col_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
                 }
             }
         }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = in[i] ? v[i] : 0;
         v4i o;
         o[0] = pack4(v[0], v[1], v[2], v[3]);
         o[1] = pack4(v[4], v[5], v[6], v[7]);
@@ -726,11 +731,13 @@ __global__ void __launch_bounds__(256) unpack_nhwc_kernel(const int32_t *src, in
         const int k0 = tk * 64, p0 = tp * 32;
         const int32_t *s = src + (size_t)n * K * PQ;
         int32_t *d = dst + (size_t)n * PQ * K;
+        // all eight loads first (indices clamped into the plane: no branch between the loads); what the
+        // clamped ones fetch lands in tile cells that are never written out
+        int32_t v[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int k = k0 + ry + 8 * i, p = p0 + rx;
-            if (k < K && p < PQ) tile[ry + 8 * i][rx] = s[(size_t)k * PQ + p];
-        }
+        for (int i = 0; i < 8; ++i) v[i] = s[(size_t)min(k0 + ry + 8 * i, K - 1) * PQ + min(p0 + rx, PQ - 1)];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) tile[ry + 8 * i][rx] = v[i];
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -817,9 +824,12 @@ __global__ void __launch_bounds__(256) requant_pack_kernel(const RequantPackArgs
         v4i o = {0, 0, 0, 0};
         if (p >= 0 && p < a.P && q >= 0 && q < a.Q && k0 < a.K) {
             const int32_t *s = a.src + ((size_t)n * a.K + k0) * PQ + (size_t)p * a.Q + q;
-            int v[16];
+            int x[16], v[16];
+            // all sixteen loads first (channels past K re-read the last one: no branch between the loads)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) v[i] = k0 + i < a.K ? requant1(s[(size_t)i * PQ], a.shift, a.relu) : 0;
+            for (int i = 0; i < 16; ++i) x[i] = s[(size_t)min(i, a.K - 1 - k0) * PQ];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[i] = k0 + i < a.K ? requant1(x[i], a.shift, a.relu) : 0;
 #pragma unroll
             for (int j = 0; j < 4; ++j) o[j] = (int)pack4(v[4 * j], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]);
         }
@@ -927,27 +937,31 @@ __global__ void __launch_bounds__(256) image_pack_kernel(const ImagePackArgs a)
         long long n = rest / a.C2;
         unsigned v = 0;
         int nb = 0;
+        // the four loads first, from coordinates clamped into the tensor (no branch between them)
+        int x[4];
+        bool in[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            if (e0 + u < a.total) {
-                const int b = c2 % a.s, ca = c2 / a.s, aa = ca % a.s, c = ca / a.s;
-                const int h = a.s * i + aa - a.pad, w = a.s * j + b - a.pad;
-                int x = 0;
-                if (h >= 0 && h < a.H && w >= 0 && w < a.W) x = a.src[((n * a.C + c) * a.H + h) * a.W + w];
-                v |= (unsigned)(x & 0xFF) << (8 * u);
-                ++nb;
-                if (++j == a.W2) {
-                    j = 0;
-                    if (++i == a.H2) {
-                        i = 0;
-                        if (++c2 == a.C2) {
-                            c2 = 0;
-                            ++n;
-                        }
+            const int b = c2 % a.s, ca = c2 / a.s, aa = ca % a.s, c = ca / a.s;
+            const int h = a.s * i + aa - a.pad, w = a.s * j + b - a.pad;
+            const bool live = e0 + u < a.total;
+            in[u] = live && h >= 0 && h < a.H && w >= 0 && w < a.W;
+            const long long nn = live ? n : 0;
+            x[u] = a.src[((nn * a.C + (live ? c : 0)) * a.H + min(max(h, 0), a.H - 1)) * a.W + min(max(w, 0), a.W - 1)];
+            nb += live;
+            if (++j == a.W2) {
+                j = 0;
+                if (++i == a.H2) {
+                    i = 0;
+                    if (++c2 == a.C2) {
+                        c2 = 0;
+                        ++n;
                     }
                 }
             }
         }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v |= (unsigned)((in[u] ? x[u] : 0) & 0xFF) << (8 * u);
         if (nb == 4) *reinterpret_cast<unsigned *>(a.dst + e0) = v;
         else
             for (int u = 0; u < nb; ++u) a.dst[e0 + u] = (int8_t)(v >> (8 * u));
