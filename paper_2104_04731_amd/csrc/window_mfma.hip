@@ -108,29 +108,39 @@ __global__ void __launch_bounds__(256) conv_window_kernel(const WindowArgs a)
     {
         const int8_t *img = a.in + (size_t)n * a.C * a.H * a.W;
         const int wd = a.pitch >> 2, total = a.C * a.RW * wd;
-        for (int base = 0; base < total; base += 256 * 8) {
-            unsigned v[8];
+        auto stage_pass = [&](int base) {
+            // the loads of a pass first, nothing that needs their data in between (a use right after each
+            // load makes the compiler wait for it: eight memory round trips in a row instead of one)
+            // (all eight always: past the window's end they re-read its last dword -- a load under a
+            // condition, even a uniform one, is waited for where the branches join)
+            unsigned x[8], fix[8];  // fix: bits 0-4 left shift, 8-12 right shift, bit 16 = all zero
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                if (base + u * 256 >= total) break;  // the same for every thread
                 const int idx = min(base + u * 256 + tid, total - 1);
                 // exact: idx, row < 10240 and wd, RW <= 40960 keep n*d below 2^32
-                const int row = fast_div(idx, a.m_wd), c4 = idx - row * wd;
-                const int c = fast_div(row, a.m_RW), rr = row - c * a.RW;
+                const int row = (int)__umulhi((unsigned)idx, a.m_wd), c4 = idx - row * wd;  // wd >= 2
+                const unsigned chi = __umulhi((unsigned)row, a.m_RW);
+                const int c = a.RW == 1 ? row : (int)chi, rr = row - c * a.RW;
                 const int h = h_lo + rr, w = w_lo + 4 * c4;
                 const int hc = min(max(h, 0), a.H - 1), wc = min(max(w, 0), a.W - 4);  // W >= 4
-                const unsigned x = a.in_small ? load_u32(img + (unsigned)((c * a.H + hc) * a.W + wc))
-                                              : load_u32(img + ((size_t)c * a.H + hc) * a.W + wc);
+                x[u] = load_u32(img + ((size_t)c * a.H + hc) * a.W + wc);
                 const int dd = wc - w;  // > 0: the dword starts left of the row, < 0: it runs past its end
                 const unsigned sh = (unsigned)(dd > 0 ? dd : -dd) * 8u;
-                unsigned y = dd >= 0 ? (x << (sh & 31u)) : (x >> (sh & 31u));
-                if (sh >= 32u || h != hc) y = 0u;
-                v[u] = y;
+                fix[u] = (dd > 0 ? (sh & 31u) : 0u) | ((dd < 0 ? (sh & 31u) : 0u) << 8) |
+                         ((sh >= 32u || h != hc) ? 0x10000u : 0u);
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u)
-                if (base + u * 256 + tid < total) *reinterpret_cast<unsigned *>(win + 4 * (base + u * 256 + tid)) = v[u];
-        }
+                if (base + u * 256 + tid < total) {
+                    const unsigned y = (x[u] << (fix[u] & 31u)) >> ((fix[u] >> 8) & 31u);
+                    *reinterpret_cast<unsigned *>(win + 4 * (base + u * 256 + tid)) = (fix[u] & 0x10000u) ? 0u : y;
+                }
+        };
+        // windows of up to 8 KB -- the usual case -- in straight-line code: a loop header would make the
+        // compiler drain the weight loads above before the first window load
+        if (total <= 256 * 8) stage_pass(0);
+        else
+            for (int base = 0; base < total; base += 256 * 8) stage_pass(base);
     }
     if (r0 < RPP) {
         if (last >= 0) {
