@@ -31,6 +31,8 @@ def _load():
         lib = ctypes.CDLL(build())
         lib.oracle_conv2d_int8.restype = ctypes.c_int
         lib.oracle_conv2d_int8.argtypes = [ctypes.c_int] * 9 + [ctypes.c_void_p] * 3
+        lib.oracle_conv2d_int8_dilated.restype = ctypes.c_int
+        lib.oracle_conv2d_int8_dilated.argtypes = [ctypes.c_int] * 10 + [ctypes.c_void_p] * 3
         lib.oracle_threads.restype = ctypes.c_int
         lib.oracle_set_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -65,4 +67,29 @@ def conv2d_int8(x: np.ndarray, w: np.ndarray, stride: int, pad: int) -> np.ndarr
                                     x.ctypes.data, w.ctypes.data, out.ctypes.data)
     if rc != 0:
         raise ValueError("oracle_conv2d_int8: invalid arguments")
+    return out
+
+
+def out_hw_dilated(H, W, R, S, stride, pad, dilation):
+    return ((H + 2 * pad - dilation * (R - 1) - 1) // stride + 1,
+            (W + 2 * pad - dilation * (S - 1) - 1) // stride + 1)
+
+
+def conv2d_int8_dilated(x: np.ndarray, w: np.ndarray, stride: int, pad: int, dilation: int) -> np.ndarray:
+    """Dilated convolution (Sec. 6.1): x [N,C,H,W] int8, w [K,C,R,S] int8 -> [N,K,P,Q] int32,
+    kernel tap (r, s) reading the padded input at (p*stride + r*dilation, q*stride + s*dilation)."""
+    assert x.dtype == np.int8 and w.dtype == np.int8
+    N, C, H, W = x.shape
+    K, C2, R, S = w.shape
+    assert C == C2
+    x = np.ascontiguousarray(x)
+    w = np.ascontiguousarray(w)
+    P, Q = out_hw_dilated(H, W, R, S, stride, pad, dilation)
+    if P <= 0 or Q <= 0:
+        raise ValueError("spread kernel larger than padded input")
+    out = np.empty((N, K, P, Q), dtype=np.int32)
+    rc = _load().oracle_conv2d_int8_dilated(N, C, H, W, K, R, S, stride, pad, dilation,
+                                            x.ctypes.data, w.ctypes.data, out.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle_conv2d_int8_dilated: invalid arguments")
     return out

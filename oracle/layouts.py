@@ -170,3 +170,42 @@ def requant(x: np.ndarray, shift: int, relu: bool) -> np.ndarray:
     if relu:
         v = np.maximum(v, 0)
     return np.clip(v, -128, 127).astype(np.int8)
+
+
+def dilation_dims(N, C, H, W, K, R, S, pad, dilation):
+    """The dense stride-1, pad-0 problem a dilated stride-1 convolution turns into (Sec. 6.1; Table 2
+    row 1, Image Pack [N, I] => [N*s, I/s] on both image axes): d*d sub-images per image."""
+    d = dilation
+    return (N * d * d, C, -(-(H + 2 * pad) // d), -(-(W + 2 * pad) // d), K, R, S, 1, 0)
+
+
+def dilation_pack(x: np.ndarray, pad: int, dilation: int) -> np.ndarray:
+    """[N,C,H,W] -> [N*d*d, C, H2, W2]; X2[(n*d + a)*d + b][c][i][j] = x0[n][c][d*i + a][d*j + b] with x0
+    the zero-padded image continued by zeros: sub-image (a, b) holds the pixels whose padded row is a
+    and whose padded column is b modulo d, the only ones one output pixel of that phase ever reads."""
+    N, C, H, W = x.shape
+    d = dilation
+    H2, W2 = -(-(H + 2 * pad) // d), -(-(W + 2 * pad) // d)
+    x0 = np.zeros((N, C, d * H2, d * W2), dtype=x.dtype)
+    x0[:, :, pad:pad + H, pad:pad + W] = x
+    y = np.zeros((N * d * d, C, H2, W2), dtype=x.dtype)
+    for n in range(N):
+        for a in range(d):
+            for b in range(d):
+                y[(n * d + a) * d + b] = x0[n, :, a::d, b::d]
+    return y
+
+
+def dilation_unpack(o2: np.ndarray, dilation: int, P: int, Q: int) -> np.ndarray:
+    """Interleaving the sub-images' results back (Sec. 6.1): [N*d*d, K, P2, Q2] -> [N, K, P, Q];
+    out[n][k][d*i + a][d*j + b] = O2[(n*d + a)*d + b][k][i][j] for d*i + a < P, d*j + b < Q."""
+    d = dilation
+    N2, K, P2, Q2 = o2.shape
+    N = N2 // (d * d)
+    out = np.zeros((N, K, P, Q), dtype=o2.dtype)
+    for n in range(N):
+        for a in range(d):
+            for b in range(d):
+                sub = out[n, :, a::d, b::d]
+                sub[...] = o2[(n * d + a) * d + b][:, :sub.shape[1], :sub.shape[2]]
+    return out

@@ -172,3 +172,89 @@ def test_config_table_matches_definition():
     for k, (P, Q, ops) in want.items():
         c = CONFIGS[k]
         assert (c.P, c.Q, c.ops) == (P, Q, ops)
+
+
+# ---- dilated convolution (Sec. 6.1) ---------------------------------------------------------
+
+def brute_dilated(x, w, stride, pad, d):
+    """Independent evaluator: per output, list the in-bounds (input, weight) pairs, sum products."""
+    N, C, H, W = x.shape
+    K, _, R, S = w.shape
+    P = (H + 2 * pad - d * (R - 1) - 1) // stride + 1
+    Q = (W + 2 * pad - d * (S - 1) - 1) // stride + 1
+    xl, wl = x.tolist(), w.tolist()
+    out = np.zeros((N, K, P, Q), dtype=np.int64)
+    for n, k, p, q in itertools.product(range(N), range(K), range(P), range(Q)):
+        for c, r, s in itertools.product(range(C), range(R), range(S)):
+            h, ww = p * stride + r * d - pad, q * stride + s * d - pad
+            if 0 <= h < H and 0 <= ww < W:
+                out[n, k, p, q] += xl[n][c][h][ww] * wl[k][c][r][s]
+    return out
+
+
+def spread_kernel(w, d):
+    """The stencil blown up with zeros to the dilated access pattern (the paper's own reference
+    implementation of a dilated convolution, Sec. 6.1)."""
+    K, C, R, S = w.shape
+    ws = np.zeros((K, C, d * (R - 1) + 1, d * (S - 1) + 1), dtype=w.dtype)
+    ws[:, :, ::d, ::d] = w
+    return ws
+
+
+DILATED_TINY = []
+_rng = np.random.RandomState(11)
+while len(DILATED_TINY) < 40:
+    N = int(_rng.choice([1, 2])); C = int(_rng.choice([1, 2, 3])); K = int(_rng.choice([1, 2, 3]))
+    H = int(_rng.randint(3, 12)); W = int(_rng.randint(3, 12))
+    R = int(_rng.randint(1, 4)); S = int(_rng.randint(1, 4))
+    d = int(_rng.randint(1, 4)); pad = int(_rng.randint(0, 4)); stride = int(_rng.randint(1, 3))
+    if d * (R - 1) + 1 <= H + 2 * pad and d * (S - 1) + 1 <= W + 2 * pad:
+        DILATED_TINY.append((N, C, H, W, K, R, S, stride, pad, d))
+
+
+@pytest.mark.parametrize("shape", DILATED_TINY)
+def test_dilated_matches_brute_force(shape):
+    N, C, H, W, K, R, S, stride, pad, d = shape
+    x = uniform_int8(31 + H, (N, C, H, W))
+    w = uniform_int8(47 + W, (K, C, R, S))
+    np.testing.assert_array_equal(direct.conv2d_int8_dilated(x, w, stride, pad, d), brute_dilated(x, w, stride, pad, d))
+
+
+@pytest.mark.parametrize("shape", DILATED_TINY[:20] + [(2, 5, 23, 31, 7, 3, 3, 1, 2, 2), (1, 4, 40, 37, 6, 3, 2, 1, 4, 4),
+                                                       (1, 3, 30, 30, 4, 5, 5, 2, 6, 3)])
+def test_dilated_equals_dense_with_spread_kernel(shape):
+    """Pins the dilated loop nest to the (independently pinned) dense one."""
+    N, C, H, W, K, R, S, stride, pad, d = shape
+    x = uniform_int8(5, (N, C, H, W))
+    w = uniform_int8(6, (K, C, R, S))
+    np.testing.assert_array_equal(direct.conv2d_int8_dilated(x, w, stride, pad, d),
+                                  direct.conv2d_int8(x, spread_kernel(w, d), stride, pad))
+
+
+def test_dilation_one_is_the_dense_convolution():
+    x = uniform_int8(1, (2, 3, 9, 11))
+    w = uniform_int8(2, (4, 3, 3, 2))
+    for stride, pad in ((1, 0), (2, 1), (1, 2)):
+        np.testing.assert_array_equal(direct.conv2d_int8_dilated(x, w, stride, pad, 1), direct.conv2d_int8(x, w, stride, pad))
+
+
+def test_dilated_delta_kernel_shifts_by_dilation():
+    """A kernel that is 1 at tap (r, s) and 0 elsewhere reads the padded input at offset (d*r, d*s)."""
+    x = uniform_int8(3, (1, 1, 8, 9))
+    d, pad, R, S = 3, 2, 3, 2
+    x0 = np.zeros((8 + 2 * pad, 9 + 2 * pad), dtype=np.int32)
+    x0[pad:pad + 8, pad:pad + 9] = x[0, 0]
+    P, Q = direct.out_hw_dilated(8, 9, R, S, 1, pad, d)
+    for r in range(R):
+        for s in range(S):
+            w = np.zeros((1, 1, R, S), dtype=np.int8)
+            w[0, 0, r, s] = 1
+            out = direct.conv2d_int8_dilated(x, w, 1, pad, d)
+            np.testing.assert_array_equal(out[0, 0], x0[d * r:d * r + P, d * s:d * s + Q])
+
+
+def test_dilated_rejects_spread_kernel_larger_than_image():
+    x = uniform_int8(1, (1, 1, 4, 4))
+    w = uniform_int8(2, (1, 1, 3, 3))
+    with pytest.raises(ValueError):
+        direct.conv2d_int8_dilated(x, w, 1, 0, 2)   # spread extent 5 > 4

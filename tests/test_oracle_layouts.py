@@ -206,3 +206,59 @@ def test_requant_against_exact_rational_arithmetic():
     np.testing.assert_array_equal(layouts.requant(small, 0, False), small.astype(np.int8))
     np.testing.assert_array_equal(layouts.requant(small, 0, True), np.maximum(small, 0).astype(np.int8))
     assert layouts.requant(np.array([4, -4, 12, -12], np.int32), 3, False).tolist() == [1, 0, 2, -1]   # ties go up
+
+
+# ---- dilation as Image Pack into the batch (Sec. 6.1, Table 2 row 1) ---------------------------
+
+DILATION_SHAPES = [
+    # N, C, H, W, K, R, S, pad, d
+    (1, 1, 7, 7, 1, 3, 3, 0, 2),
+    (2, 3, 9, 10, 4, 3, 3, 2, 2),
+    (1, 2, 11, 8, 3, 2, 3, 3, 3),
+    (1, 4, 13, 17, 2, 3, 3, 4, 4),
+    (2, 1, 6, 5, 2, 1, 1, 1, 2),
+    (1, 2, 10, 10, 2, 3, 1, 0, 3),
+]
+
+
+@pytest.mark.parametrize("shape", DILATION_SHAPES)
+def test_dilation_pack_conv_unpack_is_the_dilated_convolution(shape):
+    N, C, H, W, K, R, S, pad, d = shape
+    x = uniform_int8(21, (N, C, H, W))
+    w = uniform_int8(22, (K, C, R, S))
+    want = direct.conv2d_int8_dilated(x, w, 1, pad, d)
+    N2, C2, H2, W2, K2, R2, S2, st2, pad2 = layouts.dilation_dims(N, C, H, W, K, R, S, pad, d)
+    x2 = layouts.dilation_pack(x, pad, d)
+    assert x2.shape == (N2, C2, H2, W2) and (K2, R2, S2, st2, pad2) == (K, R, S, 1, 0)
+    o2 = direct.conv2d_int8(x2, w, 1, 0)
+    got = layouts.dilation_unpack(o2, d, want.shape[2], want.shape[3])
+    np.testing.assert_array_equal(got, want)
+
+
+@pytest.mark.parametrize("shape", DILATION_SHAPES[:4])
+def test_dilation_pack_element_by_element(shape):
+    N, C, H, W, K, R, S, pad, d = shape
+    x = uniform_int8(23, (N, C, H, W))
+    x2 = layouts.dilation_pack(x, pad, d)
+    H2, W2 = x2.shape[2], x2.shape[3]
+    for n2, c, i, j in itertools.product(range(N * d * d), range(C), range(H2), range(W2)):
+        n, a, b = n2 // (d * d), (n2 // d) % d, n2 % d
+        h, ww = d * i + a - pad, d * j + b - pad
+        want = int(x[n, c, h, ww]) if 0 <= h < H and 0 <= ww < W else 0
+        assert int(x2[n2, c, i, j]) == want
+
+
+def test_dilation_pack_keeps_every_input_element_once():
+    x = np.arange(1, 2 * 3 * 5 * 7 + 1, dtype=np.int64).reshape(2, 3, 5, 7)
+    x2 = layouts.dilation_pack(x, 1, 3)
+    vals = np.sort(x2[x2 != 0])
+    np.testing.assert_array_equal(vals, np.arange(1, x.size + 1))
+
+
+def test_dilation_unpack_element_by_element():
+    d, N, K, P, Q = 3, 2, 2, 7, 8
+    P2, Q2 = 4, 3   # larger than ceil(P/d), ceil(Q/d) = 3, 3 in one axis: surplus rows are dropped
+    o2 = np.arange(N * d * d * K * P2 * Q2, dtype=np.int32).reshape(N * d * d, K, P2, Q2)
+    out = layouts.dilation_unpack(o2, d, P, Q)
+    for n, k, p, q in itertools.product(range(N), range(K), range(P), range(Q)):
+        assert out[n, k, p, q] == o2[(n * d + p % d) * d + q % d, k, p // d, q // d]
