@@ -97,7 +97,7 @@ int conv2d_int8_nhwc(int N, int C, int H, int W, int K, int R, int S, int stride
 
 /* ---- explicit form --------------------------------------------------------------------
  * layout: a conv_layout_t (AUTO allowed).  cb: channel block for PACKED (16, 32 or 64;
- * 0 = library's choice); ignored for the other layouts.
+ * 0 = library's choice); the inner layout's block for IMAGE_PACK; ignored for the other layouts.
  * wt: KCRS weights, or -- if wt_is_packed != 0 -- the output of pack_weights for the
  * same layout/cb.  workspace: device memory of at least
  * conv2d_int8_workspace_bytes(desc, layout, cb, wt_is_packed) bytes, 256-byte aligned,
@@ -190,6 +190,34 @@ size_t image_pack_bytes(const conv_desc_t *desc);
 size_t image_pack_weights_bytes(const conv_desc_t *desc);
 int image_pack_int8(const conv_desc_t *desc, const int8_t *src, int8_t *dst, void *stream);
 int image_pack_weights(const conv_desc_t *desc, const int8_t *src, int8_t *dst, void *stream);
+
+/* ---- dilated convolution (Sec. 6.1: packed into independent dense convolutions, then interleaved back)
+ * Operation (stride 1, dilation d >= 2; desc->stride must be 1):
+ *   out[n][k][p][q] = sum_{c,r,s} in0[n][c][p + r*d - pad][q + s*d - pad] * wt[k][c][r][s],
+ *   P = H + 2 pad - d*(R-1), Q likewise; in0 as above.
+ * One output pixel reads only padded-input pixels whose row and column agree with its own modulo d, so
+ * the d*d phases are dense convolutions of their own: Image Pack (Table 2 row 1, [N, I] => [N*s, I/s])
+ * applied to both image axes moves them into the batch,
+ *   dilation_pack_int8:    dst[(n*d + a)*d + b][c][i][j] = in0[n][c][d*i + a - pad][d*j + b - pad],
+ *                          dst int8 [N*d*d][C][H2][W2], H2 = ceil((H + 2 pad)/d), W2 likewise
+ *                          (dilation_pack_bytes bytes; zeros where the padded image ends),
+ *   dilated_desc:          the dense problem on it: N*d*d, C, H2, W2, K, R, S, stride 1, pad 0
+ *                          (weights unchanged -- nothing is inflated, the point made in Sec. 6.1),
+ *   dilation_unpack_int32: dst[n][k][d*i + a][d*j + b] = src[(n*d + a)*d + b][k][i][j] for d*i + a < P,
+ *                          d*j + b < Q; src int32 [N*d*d][K][H2-R+1][W2-S+1], dst int32 [N][K][P][Q].
+ * conv2d_int8_dilated runs the three steps: layout / cb choose how the dense problem runs (any
+ * conv_layout_t that applies to it, AUTO allowed); workspace as for conv2d_int8_ex, of at least
+ * conv2d_int8_dilated_workspace_bytes(desc, dilation, layout, cb) bytes (sub-images, their results, and the
+ * dense problem's own workspace).  Errors: a spread kernel larger than the padded image is
+ * CONV_ERR_INVALID_ARG; stride != 1, d < 2 or d > 64 are CONV_ERR_UNSUPPORTED; size queries return 0. */
+int dilated_desc(const conv_desc_t *desc, int dilation, conv_desc_t *inner);
+size_t dilation_pack_bytes(const conv_desc_t *desc, int dilation);
+int dilation_pack_int8(const conv_desc_t *desc, int dilation, const int8_t *src, int8_t *dst, void *stream);
+int dilation_unpack_int32(const conv_desc_t *desc, int dilation, const int32_t *src, int32_t *dst, void *stream);
+size_t conv2d_int8_dilated_workspace_bytes(const conv_desc_t *desc, int dilation, int layout, int cb);
+int conv2d_int8_dilated(const conv_desc_t *desc, int dilation, int layout, int cb,
+                        const int8_t *in, const int8_t *wt, int32_t *out,
+                        void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---- the matrix intrinsic on its own (Sec. 5.1: C[x][y] += sum_z A[x][z] * B[y][z]) ----
  * A [X][Z], B [Y][Z] int8 row-major (both depth-contiguous, i.e. B is used transposed),

@@ -24,6 +24,8 @@ EXPORTS = [
     "conv2d_int8_tile_applies", "pack_layout", "pack_layout_bytes", "pack_layout_nhwc",
     "pack_weights", "pack_weights_depth", "pack_weights_bytes", "im2col_int8", "im2col_bytes",
     "image_pack_desc", "image_pack_bytes", "image_pack_weights_bytes", "image_pack_int8", "image_pack_weights",
+    "dilated_desc", "dilation_pack_bytes", "dilation_pack_int8", "dilation_unpack_int32",
+    "conv2d_int8_dilated_workspace_bytes", "conv2d_int8_dilated",
     "gemm_int8_nt", "select_layout", "select_layout_weighted", "layout_overheads",
     "conv_status_string",
 ]
@@ -80,6 +82,12 @@ def load(path: str | None = None):
         "image_pack_weights_bytes": (sz, [dp]),
         "image_pack_int8": (i, [dp, vp, vp, vp]),
         "image_pack_weights": (i, [dp, vp, vp, vp]),
+        "dilated_desc": (i, [dp, i, dp]),
+        "dilation_pack_bytes": (sz, [dp, i]),
+        "dilation_pack_int8": (i, [dp, i, vp, vp, vp]),
+        "dilation_unpack_int32": (i, [dp, i, vp, vp, vp]),
+        "conv2d_int8_dilated_workspace_bytes": (sz, [dp, i, i, i]),
+        "conv2d_int8_dilated": (i, [dp, i, i, i, vp, vp, vp, vp, sz, vp]),
         "gemm_int8_nt": (i, [i, i, i, vp, vp, vp, vp]),
         "select_layout": (i, [dp, ip, ip, ctypes.POINTER(dbl)]),
         "select_layout_weighted": (i, [dp, dbl, dbl, ip, ip, ctypes.POINTER(dbl)]),
@@ -325,6 +333,61 @@ def image_pack_weights(dims, w: torch.Tensor, out=None, stream=None):
         _, C2, _, _, K, R2, S2, _, _ = image_pack_desc(dims)
         out = torch.empty((K, C2, R2, S2), dtype=torch.int8, device=w.device)
     _check(load().image_pack_weights(ctypes.byref(d), _ptr(w), _ptr(out), _stream(stream)), "image_pack_weights")
+    return out
+
+
+def dilated_desc(dims, dilation):
+    """The dense stride-1, pad-0 problem (N*d*d, C, H2, W2, K, R, S, 1, 0) a dilated convolution turns into."""
+    d, d2 = _desc(*dims), ConvDesc()
+    _check(load().dilated_desc(ctypes.byref(d), int(dilation), ctypes.byref(d2)), "dilated_desc")
+    return tuple(getattr(d2, f) for f, _ in ConvDesc._fields_)
+
+
+def dilated_out_hw(dims, dilation):
+    N, C, H, W, K, R, S, stride, pad = dims
+    return H + 2 * pad - dilation * (R - 1), W + 2 * pad - dilation * (S - 1)
+
+
+def dilation_pack_int8(dims, dilation, x: torch.Tensor, out=None, stream=None):
+    _require(x, torch.int8, "input")
+    d = _desc(*dims)
+    if out is None:
+        N2, C, H2, W2 = dilated_desc(dims, dilation)[:4]
+        out = torch.empty((N2, C, H2, W2), dtype=torch.int8, device=x.device)
+    _check(load().dilation_pack_int8(ctypes.byref(d), int(dilation), _ptr(x), _ptr(out), _stream(stream)),
+           "dilation_pack_int8")
+    return out
+
+
+def dilation_unpack_int32(dims, dilation, o2: torch.Tensor, out=None, stream=None):
+    _require(o2, torch.int32, "sub-image results")
+    d = _desc(*dims)
+    if out is None:
+        P, Q = dilated_out_hw(dims, dilation)
+        out = torch.empty((dims[0], dims[4], P, Q), dtype=torch.int32, device=o2.device)
+    _check(load().dilation_unpack_int32(ctypes.byref(d), int(dilation), _ptr(o2), _ptr(out), _stream(stream)),
+           "dilation_unpack_int32")
+    return out
+
+
+def conv2d_int8_dilated_workspace_bytes(dims, dilation, layout=LAYOUT_AUTO, cb=0) -> int:
+    return int(load().conv2d_int8_dilated_workspace_bytes(ctypes.byref(_desc(*dims)), int(dilation), int(layout), int(cb)))
+
+
+def conv2d_int8_dilated(dims, dilation, x: torch.Tensor, w: torch.Tensor, layout=LAYOUT_AUTO, cb=0, out=None,
+                        workspace=None, stream=None):
+    """Stride-1 convolution with dilation >= 2: sub-images into the batch, dense convolution, interleave."""
+    _require(x, torch.int8, "input"); _require(w, torch.int8, "weights")
+    d = _desc(*dims)
+    if out is None:
+        P, Q = dilated_out_hw(dims, dilation)
+        out = torch.empty((dims[0], dims[4], max(P, 0), max(Q, 0)), dtype=torch.int32, device=x.device)
+    if workspace is None:
+        need = conv2d_int8_dilated_workspace_bytes(dims, dilation, layout, cb)
+        workspace = torch.empty(need + 256, dtype=torch.int8, device=x.device)
+        workspace = workspace[(-workspace.data_ptr()) % 256:]
+    _check(load().conv2d_int8_dilated(ctypes.byref(d), int(dilation), int(layout), int(cb), _ptr(x), _ptr(w), _ptr(out),
+                                      _ptr(workspace), workspace.numel(), _stream(stream)), "conv2d_int8_dilated")
     return out
 
 

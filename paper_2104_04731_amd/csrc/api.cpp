@@ -140,6 +140,41 @@ int image_pack_problem(const conv_desc_t *d, int cb, PackedProblem *pp)
     return make_plan(&pp->d2, pp->inner_layout, pp->inner_cb, &inner);
 }
 
+// Dilation (stride 1) as Image Pack into the batch: the dense stride-1, pad-0 problem on the d*d
+// sub-images of every padded image, and the sizes of the sub-image tensor and of its result.
+struct DilatedProblem {
+    conv_desc_t d2;
+    int P, Q;  // extents of the dilated convolution's own output
+    size_t x2_bytes, o2_bytes;
+};
+
+int dilated_problem(const conv_desc_t *d, int dilation, DilatedProblem *dp)
+{
+    if (!d) return CONV_ERR_INVALID_ARG;
+    if (d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->K <= 0 || d->R <= 0 || d->S <= 0 || d->stride <= 0 ||
+        d->pad < 0 || dilation <= 0)
+        return CONV_ERR_INVALID_ARG;
+    const long long dl = dilation;
+    const long long Hp = (long long)d->H + 2LL * d->pad, Wp = (long long)d->W + 2LL * d->pad;
+    const long long Re = dl * (d->R - 1) + 1, Se = dl * (d->S - 1) + 1;  // extent of the spread kernel
+    if (Re > Hp || Se > Wp) return CONV_ERR_INVALID_ARG;
+    if (d->stride != 1 || dilation < 2 || dilation > 64) return CONV_ERR_UNSUPPORTED;  // 1: nothing to pack
+    if (Hp > INT_LIMIT || Wp > INT_LIMIT) return CONV_ERR_UNSUPPORTED;
+    const long long N2 = (long long)d->N * dl * dl;
+    const long long H2 = (Hp + dl - 1) / dl, W2 = (Wp + dl - 1) / dl;
+    if (N2 > INT_LIMIT || H2 * W2 > INT_LIMIT) return CONV_ERR_UNSUPPORTED;
+    dp->d2 = conv_desc_t{(int)N2, d->C, (int)H2, (int)W2, d->K, d->R, d->S, 1, 0};
+    int rc = check_desc(&dp->d2);
+    if (rc != CONV_OK) return rc;
+    dp->P = (int)(Hp - Re + 1);
+    dp->Q = (int)(Wp - Se + 1);
+    if ((long long)dp->P * dp->Q > INT_LIMIT) return CONV_ERR_UNSUPPORTED;
+    const long long P2 = H2 - d->R + 1, Q2 = W2 - d->S + 1;
+    dp->x2_bytes = (size_t)N2 * d->C * (size_t)(H2 * W2);
+    dp->o2_bytes = (size_t)N2 * d->K * (size_t)(P2 * Q2) * sizeof(int32_t);
+    return CONV_OK;
+}
+
 // AUTO -> the selector's choice (which may be IMAGE_PACK with its inner block in *cb).
 int resolve_layout(const conv_desc_t *d, int *layout, int *cb)
 {
@@ -389,6 +424,81 @@ int image_pack_weights(const conv_desc_t *desc, const int8_t *src, int8_t *dst, 
     if (!src || !dst) return CONV_ERR_INVALID_ARG;
     return launch_image_pack_weights(desc->K, desc->C, desc->R, desc->S, desc->stride, src, dst,
                                      (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+}
+
+int dilated_desc(const conv_desc_t *desc, int dilation, conv_desc_t *inner)
+{
+    if (!inner) return CONV_ERR_INVALID_ARG;
+    DilatedProblem dp;
+    int rc = dilated_problem(desc, dilation, &dp);
+    if (rc != CONV_OK) return rc;
+    *inner = dp.d2;
+    return CONV_OK;
+}
+
+size_t dilation_pack_bytes(const conv_desc_t *desc, int dilation)
+{
+    DilatedProblem dp;
+    return dilated_problem(desc, dilation, &dp) == CONV_OK ? dp.x2_bytes : 0;
+}
+
+int dilation_pack_int8(const conv_desc_t *desc, int dilation, const int8_t *src, int8_t *dst, void *stream)
+{
+    DilatedProblem dp;
+    int rc = dilated_problem(desc, dilation, &dp);
+    if (rc != CONV_OK) return rc;
+    if (!src || !dst) return CONV_ERR_INVALID_ARG;
+    const hipError_t e = launch_dilation_pack(desc->N, desc->C, desc->H, desc->W, desc->pad, dilation, dp.d2.H, dp.d2.W,
+                                              src, dst, (hipStream_t)stream);
+    return e == hipSuccess ? CONV_OK : e == hipErrorInvalidValue ? CONV_ERR_UNSUPPORTED : CONV_ERR_DEVICE;
+}
+
+int dilation_unpack_int32(const conv_desc_t *desc, int dilation, const int32_t *src, int32_t *dst, void *stream)
+{
+    DilatedProblem dp;
+    int rc = dilated_problem(desc, dilation, &dp);
+    if (rc != CONV_OK) return rc;
+    if (!src || !dst) return CONV_ERR_INVALID_ARG;
+    const hipError_t e = launch_dilation_unpack(desc->N, desc->K, dp.P, dp.Q, dilation, dp.d2.H - desc->R + 1,
+                                                dp.d2.W - desc->S + 1, src, dst, (hipStream_t)stream);
+    return e == hipSuccess ? CONV_OK : e == hipErrorInvalidValue ? CONV_ERR_UNSUPPORTED : CONV_ERR_DEVICE;
+}
+
+size_t conv2d_int8_dilated_workspace_bytes(const conv_desc_t *desc, int dilation, int layout, int cb)
+{
+    DilatedProblem dp;
+    if (dilated_problem(desc, dilation, &dp) != CONV_OK) return 0;
+    if (resolve_layout(&dp.d2, &layout, &cb) != CONV_OK) return 0;
+    Plan pl;
+    if (make_plan(&dp.d2, layout, cb, &pl) != CONV_OK) return 0;
+    const size_t inner = conv2d_int8_workspace_bytes(&dp.d2, layout, cb, 0);
+    return align_up(dp.x2_bytes, WS_ALIGN) + align_up(dp.o2_bytes, WS_ALIGN) + inner;
+}
+
+int conv2d_int8_dilated(const conv_desc_t *desc, int dilation, int layout, int cb, const int8_t *in, const int8_t *wt,
+                        int32_t *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    DilatedProblem dp;
+    int rc = dilated_problem(desc, dilation, &dp);
+    if (rc != CONV_OK) return rc;
+    rc = resolve_layout(&dp.d2, &layout, &cb);
+    if (rc != CONV_OK) return rc;
+    if (!in || !wt || !out || !workspace || (reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)))
+        return CONV_ERR_INVALID_ARG;
+    Plan pl;
+    rc = make_plan(&dp.d2, layout, cb, &pl);  // the dense problem runs in one single-stage layout
+    if (rc != CONV_OK) return rc;
+    const size_t inner = conv2d_int8_workspace_bytes(&dp.d2, layout, cb, 0);
+    const size_t xb = align_up(dp.x2_bytes, WS_ALIGN), ob = align_up(dp.o2_bytes, WS_ALIGN);
+    if (workspace_bytes < xb + ob + inner) return CONV_ERR_WORKSPACE;
+    int8_t *x2 = static_cast<int8_t *>(workspace);
+    int32_t *o2 = reinterpret_cast<int32_t *>(x2 + xb);
+    void *ws = inner ? static_cast<void *>(x2 + xb + ob) : nullptr;
+    rc = dilation_pack_int8(desc, dilation, in, x2, stream);
+    if (rc != CONV_OK) return rc;
+    rc = conv2d_int8_ex(&dp.d2, layout, cb, x2, wt, 0, o2, ws, inner, stream);
+    if (rc != CONV_OK) return rc;
+    return dilation_unpack_int32(desc, dilation, o2, out, stream);
 }
 
 int gemm_int8_nt(int X, int Y, int Z, const int8_t *A, const int8_t *B, int32_t *Cout, void *stream)

@@ -62,6 +62,12 @@ hipError_t launch_fill_zero(void *dst, size_t bytes, hipStream_t st);
 // Image Pack: the stride phases of the zero-padded image (and of the kernel) become channels.
 hipError_t launch_image_pack(int N, int C, int H, int W, int stride, int pad, int H2, int W2,
                              const int8_t *src, int8_t *dst, hipStream_t st);
+// Dilation as Image Pack into the batch (Sec. 6.1): the d*d phases of the zero-padded image become
+// sub-images [N*d*d][C][H2][W2]; their results [N*d*d][K][P2][Q2] are interleaved back into [N][K][P][Q].
+hipError_t launch_dilation_pack(int N, int C, int H, int W, int pad, int d, int H2, int W2, const int8_t *src,
+                                int8_t *dst, hipStream_t st);
+hipError_t launch_dilation_unpack(int N, int K, int P, int Q, int d, int P2, int Q2, const int32_t *src, int32_t *dst,
+                                  hipStream_t st);
 hipError_t launch_image_pack_weights(int K, int C, int R, int S, int stride, const int8_t *src, int8_t *dst,
                                      hipStream_t st);
 

@@ -1014,6 +1014,131 @@ hipError_t launch_image_pack_weights(int K, int C, int R, int S, int stride, con
     return hipGetLastError();
 }
 
+// ---- dilation as Image Pack into the batch (Sec. 6.1; Table 2 row 1, [N, I] => [N*s, I/s]) --------
+// A stride-1 convolution with dilation d reads, for one output pixel, only padded-input pixels whose
+// row and column agree with the output pixel's modulo d.  The d*d phases are therefore independent
+// dense convolutions on sub-images, which go into the batch:
+//   dst[(n*d + a)*d + b][c][i][j] = x0[n][c][d*i + a][d*j + b]       (x0: zero-padded, continued by zeros)
+// and their results are interleaved back:
+//   out[n][k][d*i + a][d*j + b] = src[(n*d + a)*d + b][k][i][j].
+struct DilationArgs {
+    const void *src;
+    void *dst;
+    int C, H, W, pad, d, H2, W2;   // pack: source image and sub-image extents
+    int K, P, Q, P2, Q2;           // unpack: output and sub-result extents
+    int chunks;                    // blocks per plane
+    long long planes;
+    unsigned m_chunks, m_C, m_dd, m_d, m_W2, m_K, m_Q;
+};
+
+// One block = 1024 consecutive bytes of one sub-image plane (n2, c); a thread makes four of them.
+__global__ void __launch_bounds__(256) dilation_pack_kernel(const DilationArgs a, const int words)
+{
+    const int8_t *src = static_cast<const int8_t *>(a.src);
+    int8_t *dst = static_cast<int8_t *>(a.dst);
+    const int plane_sz = a.H2 * a.W2;
+    const int nblocks = (int)(a.planes * a.chunks);   // the launcher keeps this below 2^31
+    for (int bid = blockIdx.x; bid < nblocks; bid += gridDim.x) {
+        const int plane = fast_div_any(bid, a.chunks, a.m_chunks), chunk = bid - plane * a.chunks;
+        const int n2 = fast_div_any(plane, a.C, a.m_C), c = plane - n2 * a.C;
+        const int dd = a.d * a.d;
+        const int n = fast_div_any(n2, dd, a.m_dd), ab = n2 - n * dd;
+        const int pa = fast_div_any(ab, a.d, a.m_d), pb = ab - pa * a.d;
+        const int8_t *img = src + ((long long)n * a.C + c) * a.H * a.W;
+        const int e0 = chunk * 1024 + 4 * (int)threadIdx.x;
+        int i = fast_div_any(min(e0, plane_sz - 1), a.W2, a.m_W2), j = min(e0, plane_sz - 1) - i * a.W2;
+        // the four loads first, from coordinates clamped into the image
+        int x[4];
+        bool in[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int h = a.d * i + pa - a.pad, w = a.d * j + pb - a.pad;
+            in[u] = e0 + u < plane_sz && h >= 0 && h < a.H && w >= 0 && w < a.W;
+            x[u] = img[min(max(h, 0), a.H - 1) * a.W + min(max(w, 0), a.W - 1)];
+            if (++j == a.W2) {
+                j = 0;
+                ++i;
+            }
+        }
+        unsigned v = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v |= (unsigned)((in[u] ? x[u] : 0) & 0xFF) << (8 * u);
+        int8_t *o = dst + (long long)plane * plane_sz + e0;
+        if (words && e0 + 3 < plane_sz) *reinterpret_cast<unsigned *>(o) = v;
+        else
+            for (int u = 0; u < 4; ++u)
+                if (e0 + u < plane_sz) o[u] = (int8_t)(v >> (8 * u));
+    }
+}
+
+// One block = 1024 consecutive elements of one output plane (n, k); a thread moves four of them, 256 apart.
+__global__ void __launch_bounds__(256) dilation_unpack_kernel(const DilationArgs a)
+{
+    const int32_t *src = static_cast<const int32_t *>(a.src);
+    int32_t *dst = static_cast<int32_t *>(a.dst);
+    const int plane_sz = a.P * a.Q;
+    const long long sub_sz = (long long)a.P2 * a.Q2;
+    const int nblocks = (int)(a.planes * a.chunks);   // the launcher keeps this below 2^31
+    for (int bid = blockIdx.x; bid < nblocks; bid += gridDim.x) {
+        const int plane = fast_div_any(bid, a.chunks, a.m_chunks), chunk = bid - plane * a.chunks;
+        const long long n = fast_div_any(plane, a.K, a.m_K);
+        const int k = plane - (int)n * a.K;
+        int32_t v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = min(chunk * 1024 + 256 * u + (int)threadIdx.x, plane_sz - 1);
+            const int p = fast_div_any(e, a.Q, a.m_Q), q = e - p * a.Q;
+            const int i = fast_div_any(p, a.d, a.m_d), pa = p - i * a.d;
+            const int j = fast_div_any(q, a.d, a.m_d), pb = q - j * a.d;
+            v[u] = src[(((n * a.d + pa) * a.d + pb) * a.K + k) * sub_sz + (long long)i * a.Q2 + j];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = chunk * 1024 + 256 * u + (int)threadIdx.x;
+            if (e < plane_sz) dst[(long long)plane * plane_sz + e] = v[u];
+        }
+    }
+}
+
+hipError_t launch_dilation_pack(int N, int C, int H, int W, int pad, int d, int H2, int W2, const int8_t *src,
+                                int8_t *dst, hipStream_t st)
+{
+    DilationArgs a{};
+    a.src = src;
+    a.dst = dst;
+    a.C = C, a.H = H, a.W = W, a.pad = pad, a.d = d, a.H2 = H2, a.W2 = W2;
+    a.planes = (long long)N * d * d * C;
+    a.chunks = (int)(((long long)H2 * W2 + 1023) / 1024);
+    if (a.planes * a.chunks > 2147483647LL) return hipErrorInvalidValue;
+    a.m_chunks = magic_for(a.chunks);
+    a.m_C = magic_for(C);
+    a.m_dd = magic_for(d * d);
+    a.m_d = magic_for(d);
+    a.m_W2 = magic_for(W2);
+    // dword stores when every plane starts on a dword
+    const int words = ((long long)H2 * W2) % 4 == 0 && (reinterpret_cast<uintptr_t>(dst) & 3) == 0;
+    hipLaunchKernelGGL(dilation_pack_kernel, dim3(grid_for(a.planes * a.chunks * 256, 256)), dim3(256), 0, st, a, words);
+    return hipGetLastError();
+}
+
+hipError_t launch_dilation_unpack(int N, int K, int P, int Q, int d, int P2, int Q2, const int32_t *src, int32_t *dst,
+                                  hipStream_t st)
+{
+    DilationArgs a{};
+    a.src = src;
+    a.dst = dst;
+    a.d = d, a.K = K, a.P = P, a.Q = Q, a.P2 = P2, a.Q2 = Q2;
+    a.planes = (long long)N * K;
+    a.chunks = (int)(((long long)P * Q + 1023) / 1024);
+    if (a.planes * a.chunks > 2147483647LL) return hipErrorInvalidValue;
+    a.m_chunks = magic_for(a.chunks);
+    a.m_K = magic_for(K);
+    a.m_Q = magic_for(Q);
+    a.m_d = magic_for(d);
+    hipLaunchKernelGGL(dilation_unpack_kernel, dim3(grid_for(a.planes * a.chunks * 256, 256)), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
 // ---- zero fill (a kernel, not a memset node, so that callers may capture it) --------------
 __global__ void __launch_bounds__(256) fill_zero_kernel(v4i *dst, long long n16, int8_t *tail, int ntail)
 {

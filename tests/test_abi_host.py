@@ -8,7 +8,7 @@ import re
 import numpy as np
 import pytest
 
-from oracle import layouts, selection as sel
+from oracle import direct, layouts, selection as sel
 from paper_2104_04731_amd.inputs import CONFIGS, PAPER_SHAPES
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -197,3 +197,54 @@ def test_validation_of_the_newer_entry_points(lib):
     big = lib.ConvDesc(1, 256, 14, 14, 8, 3, 3, 1, 1)
     assert raw.conv2d_int8_ex(ctypes.byref(big), lib.LAYOUT_IMPLICIT, 0, ctypes.c_void_p(256), ctypes.c_void_p(256), 0,
                               ctypes.c_void_p(256), None, 0, None) == lib.ERR_UNSUPPORTED
+
+
+# ---- dilated convolution: problem arithmetic and argument checks (no device work) ----------------
+@pytest.mark.parametrize("case", [((1, 1, 7, 7, 1, 3, 3, 1, 0), 2), ((2, 3, 9, 10, 4, 3, 3, 1, 2), 2), ((1, 2, 11, 8, 3, 2, 3, 1, 3), 3),
+                                  ((4, 64, 28, 28, 64, 3, 3, 1, 2), 2), ((1, 16, 33, 65, 8, 3, 3, 1, 4), 4)], ids=str)
+def test_dilated_problem_and_sizes(lib, case):
+    dims, d = case
+    N, C, H, W, K, R, S, st, pad = dims
+    raw = lib.load()
+    desc = lib.ConvDesc(*dims)
+    d2 = layouts.dilation_dims(N, C, H, W, K, R, S, pad, d)
+    assert lib.dilated_desc(dims, d) == d2
+    assert raw.dilation_pack_bytes(ctypes.byref(desc), d) == d2[0] * d2[1] * d2[2] * d2[3]
+    P, Q = direct.out_hw_dilated(H, W, R, S, 1, pad, d)
+    assert lib.dilated_out_hw(dims, d) == (P, Q)
+    up = lambda v: -(-v // 256) * 256
+    for layout, cb in ((lib.LAYOUT_PACKED, 16), (lib.LAYOUT_IM2COL, 0), (lib.LAYOUT_AUTO, 0)):
+        il, icb = (layout, cb) if layout != lib.LAYOUT_AUTO else lib.select_layout(d2)[:2]
+        inner = lib.conv2d_int8_workspace_bytes(d2, il, icb)
+        o2 = d2[0] * K * (d2[2] - R + 1) * (d2[3] - S + 1) * 4
+        assert lib.conv2d_int8_dilated_workspace_bytes(dims, d, layout, cb) == up(d2[0] * d2[1] * d2[2] * d2[3]) + up(o2) + inner
+
+
+def test_dilated_validation(lib):
+    raw = lib.load()
+    ok = lib.ConvDesc(1, 3, 16, 16, 8, 3, 3, 1, 2)
+    d2 = lib.ConvDesc()
+    p = ctypes.c_void_p(256)
+    assert raw.dilated_desc(ctypes.byref(ok), 2, ctypes.byref(d2)) == lib.OK
+    assert raw.dilated_desc(ctypes.byref(ok), 2, None) == lib.ERR_INVALID_ARG
+    assert raw.dilated_desc(None, 2, ctypes.byref(d2)) == lib.ERR_INVALID_ARG
+    assert raw.dilated_desc(ctypes.byref(ok), 0, ctypes.byref(d2)) == lib.ERR_INVALID_ARG
+    assert raw.dilated_desc(ctypes.byref(ok), 1, ctypes.byref(d2)) == lib.ERR_UNSUPPORTED      # nothing to pack
+    assert raw.dilated_desc(ctypes.byref(ok), 65, ctypes.byref(d2)) == lib.ERR_INVALID_ARG     # spread kernel 129 > 20
+    assert raw.dilated_desc(ctypes.byref(lib.ConvDesc(1, 3, 200, 200, 8, 2, 2, 1, 0)), 65, ctypes.byref(d2)) == lib.ERR_UNSUPPORTED
+    assert raw.dilated_desc(ctypes.byref(lib.ConvDesc(1, 3, 16, 16, 8, 3, 3, 2, 2)), 2, ctypes.byref(d2)) == lib.ERR_UNSUPPORTED  # stride
+    assert raw.dilated_desc(ctypes.byref(lib.ConvDesc(1, 3, 4, 4, 8, 3, 3, 1, 0)), 2, ctypes.byref(d2)) == lib.ERR_INVALID_ARG   # extent 5 > 4
+    assert raw.dilation_pack_bytes(None, 2) == 0 and raw.dilation_pack_bytes(ctypes.byref(ok), 1) == 0
+    assert raw.dilation_pack_int8(ctypes.byref(ok), 2, None, p, None) == lib.ERR_INVALID_ARG
+    assert raw.dilation_pack_int8(ctypes.byref(ok), 2, p, None, None) == lib.ERR_INVALID_ARG
+    assert raw.dilation_unpack_int32(ctypes.byref(ok), 2, None, p, None) == lib.ERR_INVALID_ARG
+    assert raw.dilation_unpack_int32(ctypes.byref(ok), 1, p, p, None) == lib.ERR_UNSUPPORTED
+    assert raw.conv2d_int8_dilated_workspace_bytes(ctypes.byref(ok), 2, 99, 0) == 0
+    assert raw.conv2d_int8_dilated_workspace_bytes(ctypes.byref(ok), 1, lib.LAYOUT_PACKED, 16) == 0
+    need = raw.conv2d_int8_dilated_workspace_bytes(ctypes.byref(ok), 2, lib.LAYOUT_PACKED, 16)
+    assert need > 0
+    assert raw.conv2d_int8_dilated(ctypes.byref(ok), 2, lib.LAYOUT_PACKED, 16, None, p, p, p, need, None) == lib.ERR_INVALID_ARG
+    assert raw.conv2d_int8_dilated(ctypes.byref(ok), 2, lib.LAYOUT_PACKED, 16, p, p, p, None, need, None) == lib.ERR_INVALID_ARG
+    assert raw.conv2d_int8_dilated(ctypes.byref(ok), 2, lib.LAYOUT_PACKED, 16, p, p, p, ctypes.c_void_p(264), need, None) == lib.ERR_INVALID_ARG
+    assert raw.conv2d_int8_dilated(ctypes.byref(ok), 2, lib.LAYOUT_PACKED, 16, p, p, p, p, need - 1, None) == lib.ERR_WORKSPACE
+    assert raw.conv2d_int8_dilated(ctypes.byref(ok), 2, lib.LAYOUT_PACKED, 24, p, p, p, p, need, None) == lib.ERR_UNSUPPORTED

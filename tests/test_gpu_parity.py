@@ -614,3 +614,60 @@ def test_chained_layers_stay_blocked(lib):
     out2 = torch.empty((b.N, b.K, b.P, b.Q), dtype=torch.int32, device=DEV)
     lib.conv2d_int8_packed(b.dims(), lib.LAYOUT_PACKED, 64, xq, wq, out2)
     assert np.array_equal(host(out2), want)
+
+
+# ---- dilated convolution: sub-images into the batch, dense convolution, interleaving (Sec. 6.1) ------------
+DILATED_SHAPES = [
+    # (N, C, H, W, K, R, S, stride, pad), dilation
+    ((4, 64, 28, 28, 64, 3, 3, 1, 2), 2),     # "same"-size 3x3, dilation 2
+    ((2, 16, 33, 65, 40, 3, 3, 1, 4), 4),     # sub-images one row short of each other (41 x 73 padded)
+    ((1, 3, 37, 41, 8, 5, 3, 1, 0), 3),       # low channel count, no padding
+    ((2, 1, 9, 50, 32, 2, 2, 1, 1), 2),
+    ((1, 128, 14, 14, 130, 3, 3, 1, 2), 2),   # ragged output channels
+    ((1, 2, 6, 5, 2, 1, 1, 1, 1), 2),         # 1x1: the dilation changes nothing but the route
+    ((1, 4, 20, 20, 4, 3, 3, 1, 7), 7),       # a plane smaller than one block, odd extents
+]
+
+
+@pytest.mark.parametrize("case", DILATED_SHAPES, ids=str)
+def test_dilated_convolution(lib, case):
+    dims, d = case
+    N, C, H, W, K, R, S, st, pad = dims
+    x = uniform_int8(901, (N, C, H, W)); w = uniform_int8(902, (K, C, R, S))
+    # the two rewrites against their index maps
+    x2 = lib.dilation_pack_int8(dims, d, dev(x))
+    np.testing.assert_array_equal(host(x2), layouts.dilation_pack(x, pad, d))
+    d2 = layouts.dilation_dims(N, C, H, W, K, R, S, pad, d)
+    P, Q = direct.out_hw_dilated(H, W, R, S, 1, pad, d)
+    P2, Q2 = d2[2] - R + 1, d2[3] - S + 1
+    o2 = (np.arange(d2[0] * K * P2 * Q2, dtype=np.int64) * 2654435761 % (1 << 31) - (1 << 30)).astype(np.int32).reshape(d2[0], K, P2, Q2)
+    np.testing.assert_array_equal(host(lib.dilation_unpack_int32(dims, d, dev(o2))), layouts.dilation_unpack(o2, d, P, Q))
+    # the whole path against the definition, in every layout the dense problem can run in
+    want = direct.conv2d_int8_dilated(x, w, 1, pad, d)
+    ran = 0
+    for layout, cb in ((lib.LAYOUT_AUTO, 0), (lib.LAYOUT_PACKED, 16), (lib.LAYOUT_PACKED, 64), (lib.LAYOUT_IM2COL, 0),
+                       (lib.LAYOUT_PAD_ONLY, 0), (lib.LAYOUT_IMPLICIT, 0)):
+        if layout == lib.LAYOUT_IMPLICIT and not selection.implicit_applies(*d2):
+            assert lib.conv2d_int8_dilated_workspace_bytes(dims, d, layout, cb) == 0
+            continue
+        out = torch.full((N, K, P, Q), -3, dtype=torch.int32, device=DEV)
+        lib.conv2d_int8_dilated(dims, d, dev(x), dev(w), layout, cb, out=out)
+        assert np.array_equal(host(out), want), f"{lib.LAYOUT_NAMES[layout]} cb {cb}: {np.count_nonzero(host(out) != want)} mismatches"
+        ran += 1
+    assert ran >= 5
+    # the paper's reference for a dilated layer -- the kernel spread out with zeros, run densely -- agrees
+    ws = np.zeros((K, C, d * (R - 1) + 1, d * (S - 1) + 1), dtype=np.int8)
+    ws[:, :, ::d, ::d] = w
+    assert np.array_equal(host(lib.conv2d_int8(dev(x), dev(ws), 1, pad)), want)
+
+
+def test_dilation_pack_unaligned_destination(lib):
+    """Planes of odd size, and a destination that does not start on a dword: byte stores."""
+    dims, d = (2, 3, 9, 7, 4, 3, 3, 1, 1), 2
+    x = uniform_int8(903, dims[:4])
+    want = layouts.dilation_pack(x, 1, d)
+    buf = torch.zeros(want.size + 16, dtype=torch.int8, device=DEV)
+    for off in (0, 1, 2, 3):
+        view = buf[off:off + want.size].view(want.shape)
+        lib.dilation_pack_int8(dims, d, dev(x), out=view)
+        np.testing.assert_array_equal(host(view), want)
