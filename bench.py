@@ -343,6 +343,40 @@ def n_scaled(lib, timed, CONFIGS, dev):
     out["image_pack_C3_N512"] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),
                                  "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2)}
     del x2
+    # Dilated 3x3 (dilation 2, "same" size) over 64 channels of 28x28: the packed route against the
+    # paper's reference for it, the kernel spread out with zeros and run densely (Sec. 6.1); then its
+    # two layout kernels at a batch that fills the chip.
+    dil = 2
+    for key, n in (("dilated_3x3_d2_N4", 4), ("dilated_3x3_d2_N1024", 1024)):
+        dims = (n, 64, 28, 28, 64, 3, 3, 1, 2)
+        xd = torch.randint(-128, 128, dims[:4], dtype=torch.int8, device=dev)
+        wd = torch.randint(-128, 128, (64, 64, 3, 3), dtype=torch.int8, device=dev)
+        wsp = torch.zeros((64, 64, 5, 5), dtype=torch.int8, device=dev)
+        wsp[:, :, ::dil, ::dil] = wd
+        od = torch.empty((n, 64, 28, 28), dtype=torch.int32, device=dev)
+        need = lib.conv2d_int8_dilated_workspace_bytes(dims, dil)
+        wsb = torch.empty(need + 256, dtype=torch.int8, device=dev)
+        wsb = wsb[(-wsb.data_ptr()) % 256:]
+        _, ms_p = timed(lambda: lib.conv2d_int8_dilated(dims, dil, xd, wd, out=od, workspace=wsb), 10, 2)
+        _, ms_s = timed(lambda: lib.conv2d_int8(xd, wsp, 1, 2, out=od), 10, 2)
+        ops = 2 * n * 64 * 28 * 28 * 64 * 9
+        entry = {"packed_us": round(ms_p * 1e3, 2), "spread_kernel_us": round(ms_s * 1e3, 2),
+                 "packed_tops": round(ops / (ms_p * 1e-3) / 1e12, 2), "spread_kernel_tops": round(ops / (ms_s * 1e-3) / 1e12, 2)}
+        if n > 4:
+            x2 = lib.dilation_pack_int8(dims, dil, xd)
+            _, ms = timed(lambda: lib.dilation_pack_int8(dims, dil, xd, out=x2), 10, 2)
+            b = xd.numel() + x2.numel()
+            entry["dilation_pack"] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),
+                                      "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2)}
+            d2 = lib.dilated_desc(dims, dil)
+            o2 = torch.empty((d2[0], 64, d2[2] - 2, d2[3] - 2), dtype=torch.int32, device=dev)
+            _, ms = timed(lambda: lib.dilation_unpack_int32(dims, dil, o2, out=od), 10, 2)
+            b = 4 * (o2.numel() + od.numel())
+            entry["dilation_unpack"] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),
+                                        "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2)}
+            del x2, o2
+        out[key] = entry
+        del xd, wd, wsp, od, wsb
     # a plain device-to-device copy of the same size, for scale
     y = torch.empty_like(xp)
     _, ms = timed(lambda: y.copy_(xp), 10, 2)

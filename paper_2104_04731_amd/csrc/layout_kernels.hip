@@ -859,6 +859,9 @@ hipError_t launch_requant_pack(int N, int K, int P, int Q, int cb, int pad, int 
     return hipGetLastError();
 }
 
+static hipError_t launch_phase_split(int N, int C, int H, int W, int pad, int s, int H2, int W2, long long pn, long long pc,
+                                     long long pa, long long pb, const int8_t *src, int8_t *dst, hipStream_t st);
+
 // ---- Image Pack (Table 2, row 1: the stride phases of the padded image become channels) -----
 // dst[n][(c*s + a)*s + b][i][j] = in0[n][c][s*i + a - pad][s*j + b - pad]; one thread per four
 // consecutive destination bytes (any alignment of rows; the flat tail is written byte-wise)
@@ -997,6 +1000,9 @@ hipError_t launch_image_pack(int N, int C, int H, int W, int stride, int pad, in
     a.m_W2 = magic_for(W2);
     a.m_H2 = magic_for(H2);
     a.m_C2 = magic_for(a.C2);
+    const hipError_t e = launch_phase_split(N, C, H, W, pad, stride, H2, W2, (long long)C * stride * stride,
+                                            (long long)stride * stride, stride, 1, src, dst, st);
+    if (e != hipErrorNotSupported) return e;
     if (stride == 2 && a.total < (1LL << 31) - 4)
         hipLaunchKernelGGL(image_pack_s2_kernel, dim3(grid_for((a.total + 3) / 4, 256)), dim3(256), 0, st, a);
     else
@@ -1103,6 +1109,9 @@ __global__ void __launch_bounds__(256) dilation_unpack_kernel(const DilationArgs
 hipError_t launch_dilation_pack(int N, int C, int H, int W, int pad, int d, int H2, int W2, const int8_t *src,
                                 int8_t *dst, hipStream_t st)
 {
+    const hipError_t e = launch_phase_split(N, C, H, W, pad, d, H2, W2, (long long)d * d * C, 1, (long long)d * C, C,
+                                            src, dst, st);
+    if (e != hipErrorNotSupported) return e;
     DilationArgs a{};
     a.src = src;
     a.dst = dst;
@@ -1136,6 +1145,187 @@ hipError_t launch_dilation_unpack(int N, int K, int P, int Q, int d, int P2, int
     a.m_Q = magic_for(Q);
     a.m_d = magic_for(d);
     hipLaunchKernelGGL(dilation_unpack_kernel, dim3(grid_for(a.planes * a.chunks * 256, 256)), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+// ---- Image Pack through LDS: both forms of Table 2 row 1 (phases to channels, phases to batch) ------
+// dst plane (n, c, a, b) [H2][W2]:  dst[i][j] = in0[n][c][s*i + a - pad][s*j + b - pad], zero outside the image;
+// the plane's index is n*pn + c*pc + a*pa + b*pb, which is all that differs between the stride form
+// ([N][(c*s + a)*s + b]) and the dilation form ([(n*s + a)*s + b][c]).
+// A workgroup owns destination rows [i0, i0 + RI) of the s*s planes of one (n, c): that is the
+// contiguous source rows s*i0 - pad .. of one image plane.  It loads them with dword loads at any byte
+// address into a zero-padded LDS tile (row r, byte x = padded row s*i0 + r, padded column x), then every
+// thread gathers destination dwords from the tile, four bytes s apart, and stores them: the strided
+// access happens in LDS, both sides of HBM see whole lines.
+struct PhaseSplitArgs {
+    const int8_t *src;
+    int8_t *dst;
+    int C, H, W, pad, s, H2, W2;
+    long long pn, pc, pa, pb;   // destination plane index = n*pn + c*pc + a*pa + b*pb
+    long long src_bytes;        // N*C*H*W
+    int RI, chunks, TPd;        // destination rows per workgroup, workgroups per plane, tile pitch in dwords
+    int G, planes;              // whole (n, c) planes per workgroup (1 when a plane is cut into chunks), N*C
+    int nblocks;
+    unsigned m_chunks, m_C, m_TPd, m_W2, m_ndw, m_rows, m_ss, m_s;
+};
+
+__global__ void __launch_bounds__(256) phase_split_kernel(const PhaseSplitArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x;
+    constexpr int U = 4;   // 16-byte loads in flight per thread
+    const int TP = 4 * a.TPd, TC = a.TPd / 4;   // tile pitch in bytes (a multiple of 16), 16-byte pieces per row
+    for (int bid = blockIdx.x; bid < a.nblocks; bid += gridDim.x) {
+        const int grp = fast_div_any(bid, a.chunks, a.m_chunks), chunk = bid - grp * a.chunks;
+        const int pl0 = grp * a.G, np = min(a.G, a.planes - pl0);
+        const int i0 = chunk * a.RI, ri = min(a.RI, a.H2 - i0);
+        const int rows = a.s * ri;            // tile rows per plane
+        // 1. source rows to the tile: plane gp of the group, tile row r, 16-byte piece t
+        const int ntile = np * rows * TC;
+        const unsigned m_rows = ri == a.RI ? a.m_rows : magic_for_device(rows);
+        for (int base = 0; base < ntile; base += U * 256) {
+            v4i v[U];
+            int hh[U], w0[U];
+            long long want[U];
+            bool moved[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {   // the loads first, from addresses clamped into the tensor
+                const int idx = min(base + 256 * u + tid, ntile - 1);
+                const int row = fast_div(idx, a.m_TPd), t = idx - row * TC;   // tile-sized operands: exact
+                const int gp = fast_div(row, m_rows), r = row - gp * rows;
+                hh[u] = a.s * i0 + r - a.pad;
+                w0[u] = 16 * t - a.pad;
+                want[u] = ((long long)(pl0 + gp) * a.H + min(max(hh[u], 0), a.H - 1)) * a.W + w0[u];
+                const long long at = min(max(want[u], 0LL), a.src_bytes - 16);
+                moved[u] = at != want[u];
+                __builtin_memcpy(&v[u], a.src + at, 16);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int idx = base + 256 * u + tid;
+                if (moved[u]) {   // the tensor's first or last bytes: byte by byte
+                    asm volatile("" ::: "memory");   // stays a branch: only the first and last workgroup come here
+                    unsigned x[4] = {0u, 0u, 0u, 0u}, b[16];
+#pragma unroll
+                    for (int k = 0; k < 16; ++k)   // sixteen independent loads, then the selection
+                        b[k] = (unsigned char)a.src[min(max(want[u] + k, 0LL), a.src_bytes - 1)];
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        const long long p = want[u] + k;
+                        x[k >> 2] |= (p >= 0 && p < a.src_bytes ? b[k] : 0u) << (8 * (k & 3));
+                    }
+                    v[u] = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
+                }
+                // bytes [lo, hi) of the piece lie inside the image row
+                const int lo = min(max(-w0[u], 0), 16), hi = min(max(a.W - w0[u], 0), 16);
+                const bool rowok = hh[u] >= 0 && hh[u] < a.H;
+                v4i x;
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const int l = min(max(lo - 4 * m, 0), 4), h = min(max(hi - 4 * m, 0), 4);
+                    const unsigned keep = (rowok && h > l) ? (0xFFFFFFFFu >> ((32 - 8 * h) & 31)) & (0xFFFFFFFFu << ((8 * l) & 31)) : 0u;
+                    x[m] = (int)((unsigned)v[u][m] & keep);
+                }
+                if (idx < ntile) *reinterpret_cast<v4i *>(smem + (size_t)idx * 16) = x;
+            }
+        }
+        __syncthreads();
+        // 2. destination.  The rows [i0, i0 + ri) of one phase's plane are `flat` consecutive bytes; a thread
+        // makes sixteen of them, a 16-byte piece aligned in memory (a plane may start at any byte: the first
+        // and the last piece of the range can be partial, and are then written in smaller units).
+        const int flat = ri * a.W2, npc = (flat + 15) / 16 + 1, ss = a.s * a.s, nitems = np * ss * npc;
+        const unsigned m_npc = ri == a.RI ? a.m_ndw : magic_for_device(npc);
+        for (int item = tid; item < nitems; item += 256) {
+            const int q = fast_div(item, m_npc), g = item - q * npc;   // tile-sized operands: exact
+            const int gp = fast_div(q, a.m_ss), ph = q - gp * ss;
+            const int pa = fast_div(ph, a.m_s), pb = ph - pa * a.s;
+            const int pl = pl0 + gp, n = fast_div_any(pl, a.C, a.m_C), c = pl - n * a.C;
+            int8_t *o = a.dst + ((long long)n * a.pn + (long long)c * a.pc + pa * a.pa + pb * a.pb) * ((long long)a.H2 * a.W2) +
+                        (long long)i0 * a.W2;
+            const int f0 = 16 * g - (int)(reinterpret_cast<uintptr_t>(o) & 15);
+            if (f0 >= flat) continue;
+            const int fs = max(f0, 0);
+            int il = fast_div(fs, a.m_W2), j = fs - il * a.W2;
+            const unsigned char *sub = smem + (gp * rows) * TP + pb;
+            unsigned v[4];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const int fm = f0 + 4 * m;
+                if (fm >= 0 && fm + 3 < flat && j + 3 < a.W2) {   // a whole dword inside one row: bytes s apart
+                    const unsigned char *b = sub + (a.s * il + pa) * TP + a.s * j;
+                    v[m] = (unsigned)b[0] | (unsigned)b[a.s] << 8 | (unsigned)b[2 * a.s] << 16 | (unsigned)b[3 * a.s] << 24;
+                    j += 4;
+                    if (j == a.W2) {
+                        j = 0;
+                        ++il;
+                    }
+                } else {
+                    v[m] = 0;
+                    for (int k = 0; k < 4; ++k) {
+                        if (fm + k < 0 || fm + k >= flat) continue;
+                        v[m] |= (unsigned)sub[(a.s * il + pa) * TP + a.s * j] << (8 * k);
+                        if (++j == a.W2) {
+                            j = 0;
+                            ++il;
+                        }
+                    }
+                }
+            }
+            if (f0 >= 0 && f0 + 15 < flat) *reinterpret_cast<v4i *>(o + f0) = v4i{(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
+            else
+                for (int m = 0; m < 4; ++m) {
+                    const int fm = f0 + 4 * m;
+                    if (fm >= 0 && fm + 3 < flat) *reinterpret_cast<unsigned *>(o + fm) = v[m];
+                    else
+                        for (int k = 0; k < 4; ++k)
+                            if (fm + k >= 0 && fm + k < flat) o[fm + k] = (int8_t)(v[m] >> (8 * k));
+                }
+        }
+        __syncthreads();  // the tile is reused
+    }
+}
+
+// Returns hipErrorNotSupported when a tile of one destination row does not fit LDS (the callers then
+// use their element-wise kernels).
+static hipError_t launch_phase_split(int N, int C, int H, int W, int pad, int s, int H2, int W2, long long pn, long long pc,
+                                     long long pa, long long pb, const int8_t *src, int8_t *dst, hipStream_t st)
+{
+    PhaseSplitArgs a{};
+    a.src = src, a.dst = dst;
+    a.C = C, a.H = H, a.W = W, a.pad = pad, a.s = s, a.H2 = H2, a.W2 = W2;
+    a.pn = pn, a.pc = pc, a.pa = pa, a.pb = pb;
+    a.src_bytes = (long long)N * C * H * W;
+    if (a.src_bytes < 16 || (long long)N * C > 2147483647LL) return hipErrorNotSupported;
+    a.planes = N * C;
+    const long long pitch = ((long long)s * W2 + 15) / 16 * 16;
+    const long long budget = 16 * 1024;    // per workgroup: eight of them share a compute unit
+    long long ri = budget / (pitch * s);   // destination rows whose s*ri source rows fit the budget
+    if (ri < 1) return hipErrorNotSupported;
+    a.G = 1;
+    if (ri >= H2) {
+        ri = H2;
+        long long g = budget / (pitch * s * H2);
+        // enough workgroups to fill the chip come first
+        while (g > 1 && (a.planes + g - 1) / g < 256 * 8) g /= 2;
+        a.G = (int)(g < 1 ? 1 : g > 64 ? 64 : g);
+    }
+    a.RI = (int)ri;
+    a.chunks = (H2 + a.RI - 1) / a.RI;
+    a.TPd = (int)(pitch / 4);
+    const long long nblocks = (long long)((a.planes + a.G - 1) / a.G) * a.chunks;
+    if (nblocks > 2147483647LL) return hipErrorNotSupported;
+    a.nblocks = (int)nblocks;
+    a.m_chunks = magic_for(a.chunks);
+    a.m_C = magic_for(C);
+    a.m_TPd = magic_for(a.TPd / 4);   // 16-byte pieces per tile row
+    a.m_W2 = magic_for(W2);
+    a.m_ndw = magic_for(((long long)a.RI * W2 + 15) / 16 + 1);   // 16-byte pieces per phase and chunk
+    a.m_rows = magic_for((long long)s * a.RI);
+    a.m_ss = magic_for((long long)s * s);
+    a.m_s = magic_for(s);
+    const size_t lds = (size_t)a.G * s * a.RI * pitch;
+    const int grid = a.nblocks < 256 * 16 ? a.nblocks : 256 * 16;
+    hipLaunchKernelGGL(phase_split_kernel, dim3(grid), dim3(256), lds, st, a);
     return hipGetLastError();
 }
 

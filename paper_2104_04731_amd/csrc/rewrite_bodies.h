@@ -37,6 +37,10 @@ __device__ __forceinline__ int fast_div_any(int n, int d, unsigned magic)
     if ((long long)q * d > n) --q;
     return q;
 }
+__device__ __forceinline__ unsigned magic_for_device(int d)  // the same constant, made on the device
+{
+    return d == 1 ? 0u : (unsigned)(0xFFFFFFFFu / (unsigned)d) + 1u;
+}
 static inline unsigned magic_for(long long d) { return (unsigned)((0x100000000ULL + (unsigned long long)d - 1) / (unsigned long long)d); }
 
 // Wave-tiled version for 64-channel slices (cb % 64 == 0).  The unit of work is one wave:
