@@ -481,6 +481,9 @@ IMAGE_PACK_SHAPES = [
     ConvShape("ip-7x7-s2", 2, 3, 21, 23, 8, 7, 7, 2, 3), ConvShape("ip-20x5-s2", 1, 1, 41, 50, 32, 20, 5, 2, 0),
     ConvShape("ip-3x3-s3", 1, 16, 17, 19, 33, 3, 3, 3, 1), ConvShape("ip-1x1-s2", 2, 64, 9, 9, 8, 1, 1, 2, 0),
     ConvShape("ip-2x2-s2", 1, 4, 16, 16, 32, 2, 2, 2, 0), ConvShape("ip-5x4-s4", 1, 2, 30, 13, 5, 5, 4, 4, 2),
+    ConvShape("ip-tiny", 1, 1, 3, 4, 2, 2, 2, 2, 1),          # fewer than 16 source bytes: the element-wise kernel
+    ConvShape("ip-wide", 1, 1, 5, 16500, 2, 3, 3, 2, 1),      # a row too wide for the LDS tile: the element-wise kernel
+    ConvShape("ip-tall", 1, 2, 400, 150, 4, 3, 3, 2, 1),      # planes cut into several row chunks
 ]
 
 
@@ -626,6 +629,9 @@ DILATED_SHAPES = [
     ((1, 128, 14, 14, 130, 3, 3, 1, 2), 2),   # ragged output channels
     ((1, 2, 6, 5, 2, 1, 1, 1, 1), 2),         # 1x1: the dilation changes nothing but the route
     ((1, 4, 20, 20, 4, 3, 3, 1, 7), 7),       # a plane smaller than one block, odd extents
+    ((1, 2, 301, 203, 3, 3, 3, 1, 1), 2),     # planes cut into several row chunks, odd plane size
+    ((1, 1, 3, 5, 2, 2, 2, 1, 1), 2),         # fewer than 16 source bytes: the element-wise kernel
+    ((1, 1, 4, 8300, 2, 1, 3, 1, 0), 2),      # a row too wide for the LDS tile: the element-wise kernel
 ]
 
 
