@@ -24,6 +24,7 @@ EXPORTS = [
     "conv2d_int8_tile_applies", "pack_layout", "pack_layout_bytes", "pack_layout_nhwc",
     "pack_weights", "pack_weights_depth", "pack_weights_bytes", "im2col_int8", "im2col_bytes",
     "image_pack_desc", "image_pack_bytes", "image_pack_weights_bytes", "image_pack_int8", "image_pack_weights",
+    "conv2d_int8_packed_requant",
     "dilated_desc", "dilation_pack_bytes", "dilation_pack_int8", "dilation_unpack_int32",
     "conv2d_int8_dilated_workspace_bytes", "conv2d_int8_dilated",
     "gemm_int8_nt", "select_layout", "select_layout_weighted", "layout_overheads",
@@ -82,6 +83,7 @@ def load(path: str | None = None):
         "image_pack_weights_bytes": (sz, [dp]),
         "image_pack_int8": (i, [dp, vp, vp, vp]),
         "image_pack_weights": (i, [dp, vp, vp, vp]),
+        "conv2d_int8_packed_requant": (i, [dp, i, i, vp, vp, vp, i, i, i, i, vp]),
         "dilated_desc": (i, [dp, i, dp]),
         "dilation_pack_bytes": (sz, [dp, i]),
         "dilation_pack_int8": (i, [dp, i, vp, vp, vp]),
@@ -333,6 +335,19 @@ def image_pack_weights(dims, w: torch.Tensor, out=None, stream=None):
         _, C2, _, _, K, R2, S2, _, _ = image_pack_desc(dims)
         out = torch.empty((K, C2, R2, S2), dtype=torch.int8, device=w.device)
     _check(load().image_pack_weights(ctypes.byref(d), _ptr(w), _ptr(out), _stream(stream)), "image_pack_weights")
+    return out
+
+
+def conv2d_int8_packed_requant(dims, layout, cb, x_packed: torch.Tensor, w_packed: torch.Tensor, out_cb, out_pad, shift, relu,
+                               out=None, stream=None):
+    """GEMM stage with the activation in its epilogue: returns the next layer's blocked int8 input."""
+    N, C, H, W, K, R, S, stride, pad = dims
+    if out is None:
+        P, Q = out_hw(H, W, R, S, stride, pad)
+        out = torch.empty((N, -(-K // out_cb), P + 2 * out_pad, Q + 2 * out_pad, out_cb), dtype=torch.int8, device=x_packed.device)
+    _check(load().conv2d_int8_packed_requant(ctypes.byref(_desc(*dims)), int(layout), int(cb), _ptr(x_packed), _ptr(w_packed),
+                                             _ptr(out), int(out_cb), int(out_pad), int(shift), int(bool(relu)),
+                                             _stream(stream)), "conv2d_int8_packed_requant")
     return out
 
 

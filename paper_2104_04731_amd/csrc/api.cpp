@@ -551,6 +551,38 @@ int conv2d_int8_packed(const conv_desc_t *desc, int layout, int cb, const int8_t
                     (hipStream_t)stream);
 }
 
+int conv2d_int8_packed_requant(const conv_desc_t *desc, int layout, int cb, const int8_t *in_packed,
+                               const int8_t *wt_packed, int8_t *out_blocked, int out_cb, int out_pad, int shift, int relu,
+                               void *stream)
+{
+    if (layout == CONV_LAYOUT_AUTO) return CONV_ERR_INVALID_ARG;
+    Plan pl;
+    int rc = make_plan(desc, layout, cb, &pl);
+    if (rc != CONV_OK) return rc;
+    if (pl.layout == CONV_LAYOUT_IMPLICIT) return CONV_ERR_UNSUPPORTED;  // those kernels have their own epilogue
+    if (!in_packed || !wt_packed || !out_blocked || out_pad < 0 || shift < 0 || shift > 31) return CONV_ERR_INVALID_ARG;
+    if (!aligned16(in_packed) || !aligned16(wt_packed) || !aligned16(out_blocked)) return CONV_ERR_INVALID_ARG;
+    if (out_cb != 16 && out_cb != 32 && out_cb != 64) return CONV_ERR_UNSUPPORTED;
+    const long long Hq = (long long)pl.P + 2LL * out_pad, Wq = (long long)pl.Q + 2LL * out_pad;
+    const long long Cbq = (desc->K + out_cb - 1) / out_cb;
+    if (Hq > INT_LIMIT || Wq > INT_LIMIT) return CONV_ERR_UNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    // the kernel writes the real channels of the interior pixels; whatever else the blocked tensor has is zero
+    if (out_pad > 0 || desc->K % out_cb != 0) {
+        const size_t bytes = (size_t)desc->N * (size_t)Cbq * (size_t)Hq * (size_t)Wq * (size_t)out_cb;
+        if (launch_fill_zero(out_blocked, bytes, st) != hipSuccess) return CONV_ERR_DEVICE;
+    }
+    GemmProblem g = gemm_problem(desc, pl, in_packed, wt_packed, nullptr);
+    g.act_out = out_blocked;
+    g.act_shift = shift;
+    g.act_relu = relu != 0;
+    g.o_cb = out_cb;
+    g.o_pad = out_pad;
+    int t = -1, s = 1;
+    if (!gemm_pick(g, &t, &s)) return CONV_ERR_UNSUPPORTED;
+    return launch_gemm(g, t, 1, st) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+}
+
 int conv2d_int8_query_tiling(const conv_desc_t *desc, int layout, int cb, int *tile, int *split_k)
 {
     if (layout == CONV_LAYOUT_AUTO || !tile || !split_k) return CONV_ERR_INVALID_ARG;

@@ -38,7 +38,20 @@ struct GemmArgs {
     int out_fits_32bit;  // every output byte offset is below 2^32
     int m_fastest;       // tile order inside an XCD
     unsigned mg_g16, mg_S, mg_R, mg_PQ, mg_Q, mg_tiles_k, mg_tiles_m;  // ceil(2^32 / d), 0 for d == 1
+    // Activation fused into the epilogue (null: the int32 result goes to `out`): the next layer's
+    // channel-blocked input [N][o_Cb][o_Hp][o_Wp][1 << o_cb_log2], int8.
+    int8_t *act_out;
+    int act_shift, act_relu, o_cb_log2, o_pad, o_Hp, o_Wp, o_Cb;
 };
+
+// The ALU step between two int8 layers (Sec. 5.1): rounding right shift, optional max(., 0), clip.
+__device__ __forceinline__ int epilogue_requant(int x, int shift, int relu)
+{
+    // floor(x / 2^shift + 1/2) without leaving 32 bits: floor(x / 2^shift) + bit (shift-1) of x
+    int v = shift > 0 ? (x >> shift) + ((x >> (shift - 1)) & 1) : x;
+    if (relu) v = max(v, 0);
+    return min(max(v, -128), 127);
+}
 
 // n / d for 0 <= n < 2^31 with magic = ceil(2^32 / d) truncated to 32 bits (0 encodes d == 1):
 // the multiply-high estimate is never low and at most one too high.
@@ -487,6 +500,40 @@ __device__ __forceinline__ void igemm_body(const GemmArgs &a, int block_id, int 
 
     // Epilogue: D block (i, jm): column = lane%32 (pixel), row = 8*(v/4) + 4*(lane/32) + v%4.
     // Consecutive lanes write consecutive pixels of one output plane: 128-byte runs in NKPQ.
+    if (a.act_out) {
+        // Fused activation: the four values v%4 of a lane are four consecutive output channels of one
+        // pixel -- one dword of that pixel's channel-contiguous run in the next layer's blocked input.
+        const int o_cb = 1 << a.o_cb_log2;
+#pragma unroll
+        for (int jm = 0; jm < FM; ++jm) {
+            const int m = m0 + wm * WTM + jm * 32 + (lane & 31);
+            if (m >= a.M) continue;
+            const int n = div_magic(m, a.PQ, a.mg_PQ), pq = m - n * a.PQ;
+            const int p = div_magic(pq, a.Q, a.mg_Q), q = pq - p * a.Q;
+            const size_t pix = (size_t)(p + a.o_pad) * a.o_Wp + q + a.o_pad;
+            const size_t plane = (size_t)a.o_Hp * a.o_Wp;
+#pragma unroll
+            for (int i = 0; i < FK; ++i) {
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg) {
+                    const int k = k0 + wk * WTK + i * 32 + 8 * vg + 4 * (lane >> 5);
+                    if (k >= a.K) continue;
+                    int y[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) y[t] = epilogue_requant(acc[i][jm][4 * vg + t], a.act_shift, a.act_relu);
+                    int8_t *dst = a.act_out + ((((size_t)n * a.o_Cb + (k >> a.o_cb_log2)) * plane + pix) << a.o_cb_log2) +
+                                  (k & (o_cb - 1));
+                    if (k + 3 < a.K)
+                        *reinterpret_cast<unsigned *>(dst) = (unsigned)(y[0] & 0xFF) | (unsigned)(y[1] & 0xFF) << 8 |
+                                                             (unsigned)(y[2] & 0xFF) << 16 | (unsigned)(y[3] & 0xFF) << 24;
+                    else
+                        for (int t = 0; t < 4; ++t)
+                            if (k + t < a.K) dst[t] = (int8_t)y[t];
+                }
+            }
+        }
+        return;
+    }
     const bool interior = a.out_fits_32bit && k0 + TK <= a.K && m0 + TM <= a.M;
     if (interior) {
         // Whole tile in range: address = uniform row base (scalar registers, advanced by whole
@@ -714,6 +761,15 @@ static bool make_gemm_args(const GemmProblem &g, int tile, int split_k, GemmArgs
     a.act = g.act;
     a.wq = g.wq;
     a.out = g.out;
+    a.act_out = g.act_out;
+    a.act_shift = g.act_shift;
+    a.act_relu = g.act_relu;
+    a.o_cb_log2 = 0;
+    while ((1 << a.o_cb_log2) < g.o_cb) ++a.o_cb_log2;
+    a.o_pad = g.o_pad;
+    a.o_Hp = g.PQ / g.Q + 2 * g.o_pad;
+    a.o_Wp = g.Q + 2 * g.o_pad;
+    a.o_Cb = g.o_cb > 0 ? (g.K + g.o_cb - 1) / g.o_cb : 0;
     a.K = g.K;
     a.M = g.M;
     a.depth = g.depth;
@@ -774,6 +830,7 @@ hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t 
 {
     GemmArgs a;
     if (!make_gemm_args(g, tile, split_k, &a)) return hipErrorInvalidValue;
+    if (a.act_out && a.split_k > 1) return hipErrorInvalidValue;  // the activation needs the whole sum
     if (a.split_k > 1) {
         hipError_t e = launch_fill_zero(g.out, (size_t)g.M * g.K * sizeof(int32_t), st);
         if (e != hipSuccess) return e;

@@ -24,6 +24,11 @@ struct GemmProblem {
     int mode;           // ActMode
     // ACT_BLOCKED only:
     int stride, cb, Cb, R, S, Hp, Wp;
+    // Fused activation (act_out != null; split_k must be 1): instead of the int32 result, the GEMM stage
+    // writes requant(result) as the next layer's blocked input [N][ceil(K/o_cb)][P+2 o_pad][Q+2 o_pad][o_cb],
+    // o_cb a power of two >= 4; borders and channel padding are not written (the caller clears them).
+    int8_t *act_out;
+    int act_shift, act_relu, o_cb, o_pad;
 };
 
 struct TileInfo {

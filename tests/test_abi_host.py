@@ -248,3 +248,19 @@ def test_dilated_validation(lib):
     assert raw.conv2d_int8_dilated(ctypes.byref(ok), 2, lib.LAYOUT_PACKED, 16, p, p, p, ctypes.c_void_p(264), need, None) == lib.ERR_INVALID_ARG
     assert raw.conv2d_int8_dilated(ctypes.byref(ok), 2, lib.LAYOUT_PACKED, 16, p, p, p, p, need - 1, None) == lib.ERR_WORKSPACE
     assert raw.conv2d_int8_dilated(ctypes.byref(ok), 2, lib.LAYOUT_PACKED, 24, p, p, p, p, need, None) == lib.ERR_UNSUPPORTED
+
+
+def test_fused_activation_validation(lib):
+    raw = lib.load()
+    d = lib.ConvDesc(1, 64, 14, 14, 128, 3, 3, 1, 1)
+    p = ctypes.c_void_p(256)
+    call = lambda layout=lib.LAYOUT_PACKED, cb=64, x=p, w=p, o=p, ocb=64, opad=0, shift=8, relu=1: \
+        raw.conv2d_int8_packed_requant(ctypes.byref(d), layout, cb, x, w, o, ocb, opad, shift, relu, None)
+    assert call(layout=lib.LAYOUT_AUTO) == lib.ERR_INVALID_ARG
+    assert call(x=None) == lib.ERR_INVALID_ARG and call(w=None) == lib.ERR_INVALID_ARG and call(o=None) == lib.ERR_INVALID_ARG
+    assert call(o=ctypes.c_void_p(260)) == lib.ERR_INVALID_ARG
+    assert call(shift=32) == lib.ERR_INVALID_ARG and call(shift=-1) == lib.ERR_INVALID_ARG and call(opad=-1) == lib.ERR_INVALID_ARG
+    assert call(ocb=24) == lib.ERR_UNSUPPORTED and call(ocb=128) == lib.ERR_UNSUPPORTED
+    assert call(cb=24) == lib.ERR_UNSUPPORTED
+    d1 = lib.ConvDesc(1, 64, 14, 14, 128, 1, 1, 1, 0)   # IMPLICIT applies to it, but has its own epilogue
+    assert raw.conv2d_int8_packed_requant(ctypes.byref(d1), lib.LAYOUT_IMPLICIT, 0, p, p, p, 64, 0, 8, 1, None) == lib.ERR_UNSUPPORTED

@@ -677,3 +677,43 @@ def test_dilation_pack_unaligned_destination(lib):
         view = buf[off:off + want.size].view(want.shape)
         lib.dilation_pack_int8(dims, d, dev(x), out=view)
         np.testing.assert_array_equal(host(view), want)
+
+
+# ---- activation fused into the GEMM stage's epilogue ------------------------------------------------------
+FUSED_ACT_SHAPES = [
+    ConvShape("fa-3x3", 2, 64, 14, 14, 128, 3, 3, 1, 1), ConvShape("fa-ragged", 1, 20, 9, 11, 37, 3, 2, 1, 1),
+    ConvShape("fa-stride", 2, 16, 17, 15, 65, 3, 3, 2, 1), ConvShape("fa-1x1", 1, 128, 7, 7, 256, 1, 1, 1, 0),
+    ConvShape("fa-k3", 1, 8, 6, 5, 3, 3, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("cfg", FUSED_ACT_SHAPES + [CONFIGS["C1"], CONFIGS["C2"], CONFIGS["C4a"]], ids=lambda c: c.name)
+def test_gemm_stage_with_fused_activation(lib, cfg):
+    x = uniform_int8(931, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(932, (cfg.K, cfg.C, cfg.R, cfg.S))
+    conv = direct.conv2d_int8(x, w, cfg.stride, cfg.pad)
+    for layout, cb in ((lib.LAYOUT_PACKED, 16), (lib.LAYOUT_PACKED, 64), (lib.LAYOUT_IM2COL, 0)):
+        xp = lib.im2col_int8(dev(x), cfg.R, cfg.S, cfg.stride, cfg.pad) if layout == lib.LAYOUT_IM2COL else lib.pack_layout(dev(x), cb, cfg.pad)
+        wp = lib.pack_weights(dev(w), layout, cb)
+        for out_cb, out_pad, shift, relu in ((64, 0, 9, True), (16, 1, 7, False), (32, 2, 0, True)):
+            want = layouts.pack_layout(layouts.requant(conv, shift, relu), out_cb, out_pad)
+            out = torch.full(want.shape, 77, dtype=torch.int8, device=DEV)   # stale contents must not survive
+            lib.conv2d_int8_packed_requant(cfg.dims(), layout, cb, xp, wp, out_cb, out_pad, shift, relu, out=out)
+            got = host(out)
+            assert np.array_equal(got, want), f"{lib.LAYOUT_NAMES[layout]} cb {cb} -> cb {out_cb} pad {out_pad} shift {shift}: " \
+                                              f"{np.count_nonzero(got != want)} mismatches"
+
+
+def test_chained_layers_with_fused_activation(lib):
+    """C4a with the activation in its epilogue hands C4b its blocked input directly: two GEMM-stage launches."""
+    a, b = CONFIGS["C4a"], CONFIGS["C4b"]
+    x, w1, mid = oracle_conv(a)
+    w2 = uniform_int8(801, (b.K, b.C, b.R, b.S))
+    shift, relu = 9, True
+    want = direct.conv2d_int8(layouts.requant(mid, shift, relu), w2, b.stride, b.pad)
+    xq1 = lib.pack_layout(dev(x), 64, a.pad)
+    wq1 = lib.pack_weights(dev(w1), lib.LAYOUT_PACKED, 64)
+    xq2 = lib.conv2d_int8_packed_requant(a.dims(), lib.LAYOUT_PACKED, 64, xq1, wq1, 64, b.pad, shift, relu)
+    wq2 = lib.pack_weights(dev(w2), lib.LAYOUT_PACKED, 64)
+    out2 = torch.empty((b.N, b.K, b.P, b.Q), dtype=torch.int32, device=DEV)
+    lib.conv2d_int8_packed(b.dims(), lib.LAYOUT_PACKED, 64, xq2, wq2, out2)
+    assert np.array_equal(host(out2), want)
