@@ -24,7 +24,7 @@ EXPORTS = [
     "conv2d_int8_tile_applies", "pack_layout", "pack_layout_bytes", "pack_layout_nhwc",
     "pack_weights", "pack_weights_depth", "pack_weights_bytes", "im2col_int8", "im2col_bytes",
     "image_pack_desc", "image_pack_bytes", "image_pack_weights_bytes", "image_pack_int8", "image_pack_weights",
-    "conv2d_int8_packed_requant",
+    "conv2d_int8_packed_requant", "mfma_probe_int8",
     "dilated_desc", "dilation_pack_bytes", "dilation_pack_int8", "dilation_unpack_int32",
     "conv2d_int8_dilated_workspace_bytes", "conv2d_int8_dilated",
     "gemm_int8_nt", "select_layout", "select_layout_weighted", "layout_overheads",
@@ -90,6 +90,7 @@ def load(path: str | None = None):
         "dilation_unpack_int32": (i, [dp, i, vp, vp, vp]),
         "conv2d_int8_dilated_workspace_bytes": (sz, [dp, i, i, i]),
         "conv2d_int8_dilated": (i, [dp, i, i, i, vp, vp, vp, vp, sz, vp]),
+        "mfma_probe_int8": (i, [i, i, vp, vp]),
         "gemm_int8_nt": (i, [i, i, i, vp, vp, vp, vp]),
         "select_layout": (i, [dp, ip, ip, ctypes.POINTER(dbl)]),
         "select_layout_weighted": (i, [dp, dbl, dbl, ip, ip, ctypes.POINTER(dbl)]),
@@ -404,6 +405,14 @@ def conv2d_int8_dilated(dims, dilation, x: torch.Tensor, w: torch.Tensor, layout
     _check(load().conv2d_int8_dilated(ctypes.byref(d), int(dilation), int(layout), int(cb), _ptr(x), _ptr(w), _ptr(out),
                                       _ptr(workspace), workspace.numel(), _stream(stream)), "conv2d_int8_dilated")
     return out
+
+
+def mfma_probe_int8(blocks: int, iters: int, out=None, stream=None, device="cuda:0"):
+    """Register-resident MFMA loop; returns (checksums, operations issued)."""
+    if out is None:
+        out = torch.empty(blocks * 256, dtype=torch.int32, device=device)
+    _check(load().mfma_probe_int8(int(blocks), int(iters), _ptr(out), _stream(stream)), "mfma_probe_int8")
+    return out, 2 * 32768 * 16 * int(iters) * int(blocks)
 
 
 def gemm_int8_nt(A: torch.Tensor, B: torch.Tensor, out=None, stream=None):

@@ -501,6 +501,12 @@ int conv2d_int8_dilated(const conv_desc_t *desc, int dilation, int layout, int c
     return dilation_unpack_int32(desc, dilation, o2, out, stream);
 }
 
+int mfma_probe_int8(int blocks, int iters, int32_t *out, void *stream)
+{
+    if (blocks <= 0 || blocks > (1 << 20) || iters <= 0 || !out) return CONV_ERR_INVALID_ARG;
+    return launch_mfma_probe(blocks, iters, out, (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+}
+
 int gemm_int8_nt(int X, int Y, int Z, const int8_t *A, const int8_t *B, int32_t *Cout, void *stream)
 {
     if (X <= 0 || Y <= 0 || Z <= 0 || !A || !B || !Cout) return CONV_ERR_INVALID_ARG;

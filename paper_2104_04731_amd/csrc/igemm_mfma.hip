@@ -885,4 +885,44 @@ hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t 
     return hipErrorInvalidValue;
 }
 
+// ---- MFMA-only probe: what the matrix cores sustain with nothing else in the way ---------------------
+// Every wave keeps four independent 32x32 accumulators and issues v_mfma_i32_32x32x32_i8 back to back
+// on register-resident operands (pseudo-random bytes made from the lane id).  No LDS, no global loads;
+// one store per lane at the end keeps the work alive.
+__global__ void __launch_bounds__(256) mfma_probe_kernel(int iters, int32_t *out)
+{
+    const unsigned id = blockIdx.x * 256u + threadIdx.x;
+    v4i a, b;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        unsigned x = (id * 4u + (unsigned)t) * 2654435761u;
+        x ^= x >> 15;
+        x *= 2246822519u;
+        x ^= x >> 13;
+        a[t] = (int)x;
+        b[t] = (int)(x * 3266489917u + 374761393u);
+    }
+    v16i acc[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[g][v] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) acc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[g], 0, 0, 0);
+    }
+    int sum = 0;
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sum += acc[g][v];
+    out[id] = sum;
+}
+
+hipError_t launch_mfma_probe(int blocks, int iters, int32_t *out, hipStream_t st)
+{
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(256), 0, st, iters, out);
+    return hipGetLastError();
+}
+
 }  // namespace c2i8

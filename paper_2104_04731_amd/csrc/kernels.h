@@ -43,6 +43,9 @@ bool gemm_pick(const GemmProblem &g, int *tile, int *split_k);
 // split_k > 1 clears `out` first and accumulates with atomics.
 hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t st);
 
+// blocks x 4 waves x iters x 4 MFMA 32x32x32 i8 on register operands; out: blocks * 256 int32
+hipError_t launch_mfma_probe(int blocks, int iters, int32_t *out, hipStream_t st);
+
 hipError_t launch_pack_layout(int N, int C, int H, int W, int cb, int pad,
                               const int8_t *src, int8_t *dst, hipStream_t st);
 hipError_t launch_pack_layout_nhwc(int N, int C, int H, int W, int cb, int pad,

@@ -717,3 +717,13 @@ def test_chained_layers_with_fused_activation(lib):
     out2 = torch.empty((b.N, b.K, b.P, b.Q), dtype=torch.int32, device=DEV)
     lib.conv2d_int8_packed(b.dims(), lib.LAYOUT_PACKED, 64, xq2, wq2, out2)
     assert np.array_equal(host(out2), want)
+
+
+def test_mfma_probe_is_linear_in_its_iteration_count(lib):
+    """The probe adds the same operand product every iteration: checksums scale with the count (mod 2^32)."""
+    one, ops1 = lib.mfma_probe_int8(4, 1)
+    three, ops3 = lib.mfma_probe_int8(4, 3)
+    a, b = host(one).astype(np.int64), host(three).astype(np.int64)
+    assert ops3 == 3 * ops1 == 3 * 2 * 32768 * 16 * 4
+    assert np.count_nonzero(a) > a.size // 2
+    assert np.array_equal((3 * a) & 0xFFFFFFFF, b & 0xFFFFFFFF)
