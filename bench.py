@@ -402,9 +402,17 @@ def n_scaled(lib, timed, CONFIGS, dev):
         wsb = wsb[(-wsb.data_ptr()) % 256:]
         _, ms_p = timed(lambda: lib.conv2d_int8_dilated(dims, dil, xd, wd, out=od, workspace=wsb), 10, 2)
         _, ms_s = timed(lambda: lib.conv2d_int8(xd, wsp, 1, 2, out=od), 10, 2)
+        # and with the dilation as an address multiplier of the GEMM stage (no Image Pack at all)
+        nd = lib.conv2d_int8_workspace_bytes(dims, lib.LAYOUT_PACKED, 64)
+        wsd = torch.empty(nd + 256, dtype=torch.int8, device=dev)
+        wsd = wsd[(-wsd.data_ptr()) % 256:]
+        _, ms_d = timed(lambda: lib.conv2d_int8_dilated_direct(dims, dil, xd, wd, 64, out=od, workspace=wsd), 10, 2)
         ops = 2 * n * 64 * 28 * 28 * 64 * 9
         entry = {"packed_us": round(ms_p * 1e3, 2), "spread_kernel_us": round(ms_s * 1e3, 2),
-                 "packed_tops": round(ops / (ms_p * 1e-3) / 1e12, 2), "spread_kernel_tops": round(ops / (ms_s * 1e-3) / 1e12, 2)}
+                 "address_multiplier_us": round(ms_d * 1e3, 2),
+                 "packed_tops": round(ops / (ms_p * 1e-3) / 1e12, 2), "spread_kernel_tops": round(ops / (ms_s * 1e-3) / 1e12, 2),
+                 "address_multiplier_tops": round(ops / (ms_d * 1e-3) / 1e12, 2)}
+        del wsd
         if n > 4:
             x2 = lib.dilation_pack_int8(dims, dil, xd)
             _, ms = timed(lambda: lib.dilation_pack_int8(dims, dil, xd, out=x2), 10, 2)

@@ -218,8 +218,9 @@ int image_pack_weights(const conv_desc_t *desc, const int8_t *src, int8_t *dst, 
  *                          d*j + b < Q; src int32 [N*d*d][K][H2-R+1][W2-S+1], dst int32 [N][K][P][Q].
  * conv2d_int8_dilated runs the three steps: layout / cb choose how the dense problem runs (any
  * conv_layout_t that applies to it, AUTO allowed); workspace as for conv2d_int8_ex, of at least
- * conv2d_int8_dilated_workspace_bytes(desc, dilation, layout, cb) bytes (sub-images, their results, and the
- * dense problem's own workspace).  Errors: a spread kernel larger than the padded image is
+ * conv2d_int8_dilated_workspace_bytes(desc, dilation, layout, cb) bytes (sub-images and the dense problem's
+ * own workspace; with PACKED, PAD_ONLY and IM2COL the GEMM stage's epilogue writes the interleaved positions
+ * itself -- three launches -- and only IMPLICIT stores the sub-images' results and interleaves in a pass of its own).  Errors: a spread kernel larger than the padded image is
  * CONV_ERR_INVALID_ARG; stride != 1, d < 2 or d > 64 are CONV_ERR_UNSUPPORTED; size queries return 0. */
 int dilated_desc(const conv_desc_t *desc, int dilation, conv_desc_t *inner);
 size_t dilation_pack_bytes(const conv_desc_t *desc, int dilation);
@@ -229,6 +230,18 @@ size_t conv2d_int8_dilated_workspace_bytes(const conv_desc_t *desc, int dilation
 int conv2d_int8_dilated(const conv_desc_t *desc, int dilation, int layout, int cb,
                         const int8_t *in, const int8_t *wt, int32_t *out,
                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* The same operation without Image Pack: channel blocking of the image as it is (PACKED, block cb: 16, 32, 64
+ * or 0 = library's choice) and a GEMM stage whose kernel taps are read `dilation` pixels apart -- on a machine
+ * whose GEMM stage computes its operand addresses itself, a dilation is an address multiplier like a stride
+ * (not the paper's route: there the intrinsic's operand must be a dense box, Sec. 4.2).  Any stride >= 1 and
+ * dilation >= 1: out[n][k][p][q] = sum in0[n][c][p*stride + r*dilation - pad][q*stride + s*dilation - pad] * wt[k][c][r][s],
+ * P = floor((H + 2 pad - dilation*(R-1) - 1)/stride) + 1.  Workspace as for conv2d_int8_ex, at least
+ * conv2d_int8_dilated_direct_workspace_bytes(desc, dilation, cb) bytes.  Two launches. */
+size_t conv2d_int8_dilated_direct_workspace_bytes(const conv_desc_t *desc, int dilation, int cb);
+int conv2d_int8_dilated_direct(const conv_desc_t *desc, int dilation, int cb,
+                               const int8_t *in, const int8_t *wt, int32_t *out,
+                               void *workspace, size_t workspace_bytes, void *stream);
 
 /* Measurement aid: the int8 MFMA rate the chip sustains with nothing else in the way.  blocks workgroups of
  * four waves each issue iters x 4 v_mfma_i32_32x32x32_i8 (the GEMM unit of Sec. 5.1, 32 x 32 x 32 per

@@ -27,6 +27,7 @@ EXPORTS = [
     "conv2d_int8_packed_requant", "mfma_probe_int8",
     "dilated_desc", "dilation_pack_bytes", "dilation_pack_int8", "dilation_unpack_int32",
     "conv2d_int8_dilated_workspace_bytes", "conv2d_int8_dilated",
+    "conv2d_int8_dilated_direct_workspace_bytes", "conv2d_int8_dilated_direct",
     "gemm_int8_nt", "select_layout", "select_layout_weighted", "layout_overheads",
     "conv_status_string",
 ]
@@ -91,6 +92,8 @@ def load(path: str | None = None):
         "conv2d_int8_dilated_workspace_bytes": (sz, [dp, i, i, i]),
         "conv2d_int8_dilated": (i, [dp, i, i, i, vp, vp, vp, vp, sz, vp]),
         "mfma_probe_int8": (i, [i, i, vp, vp]),
+        "conv2d_int8_dilated_direct_workspace_bytes": (sz, [dp, i, i]),
+        "conv2d_int8_dilated_direct": (i, [dp, i, i, vp, vp, vp, vp, sz, vp]),
         "gemm_int8_nt": (i, [i, i, i, vp, vp, vp, vp]),
         "select_layout": (i, [dp, ip, ip, ctypes.POINTER(dbl)]),
         "select_layout_weighted": (i, [dp, dbl, dbl, ip, ip, ctypes.POINTER(dbl)]),
@@ -404,6 +407,24 @@ def conv2d_int8_dilated(dims, dilation, x: torch.Tensor, w: torch.Tensor, layout
         workspace = workspace[(-workspace.data_ptr()) % 256:]
     _check(load().conv2d_int8_dilated(ctypes.byref(d), int(dilation), int(layout), int(cb), _ptr(x), _ptr(w), _ptr(out),
                                       _ptr(workspace), workspace.numel(), _stream(stream)), "conv2d_int8_dilated")
+    return out
+
+
+def conv2d_int8_dilated_direct(dims, dilation, x: torch.Tensor, w: torch.Tensor, cb=0, out=None, workspace=None, stream=None):
+    """Dilated convolution (any stride) with the dilation as an address multiplier of the GEMM stage."""
+    _require(x, torch.int8, "input"); _require(w, torch.int8, "weights")
+    N, C, H, W, K, R, S, stride, pad = dims
+    d = _desc(*dims)
+    if out is None:
+        P = (H + 2 * pad - dilation * (R - 1) - 1) // stride + 1
+        Q = (W + 2 * pad - dilation * (S - 1) - 1) // stride + 1
+        out = torch.empty((N, K, max(P, 0), max(Q, 0)), dtype=torch.int32, device=x.device)
+    if workspace is None:
+        need = int(load().conv2d_int8_dilated_direct_workspace_bytes(ctypes.byref(d), int(dilation), int(cb)))
+        workspace = torch.empty(need + 256, dtype=torch.int8, device=x.device)
+        workspace = workspace[(-workspace.data_ptr()) % 256:]
+    _check(load().conv2d_int8_dilated_direct(ctypes.byref(d), int(dilation), int(cb), _ptr(x), _ptr(w), _ptr(out),
+                                             _ptr(workspace), workspace.numel(), _stream(stream)), "conv2d_int8_dilated_direct")
     return out
 
 

@@ -472,7 +472,9 @@ size_t conv2d_int8_dilated_workspace_bytes(const conv_desc_t *desc, int dilation
     Plan pl;
     if (make_plan(&dp.d2, layout, cb, &pl) != CONV_OK) return 0;
     const size_t inner = conv2d_int8_workspace_bytes(&dp.d2, layout, cb, 0);
-    return align_up(dp.x2_bytes, WS_ALIGN) + align_up(dp.o2_bytes, WS_ALIGN) + inner;
+    // the GEMM stage interleaves in its epilogue; only IMPLICIT stores the sub-images' results
+    const size_t ob = pl.layout == CONV_LAYOUT_IMPLICIT ? align_up(dp.o2_bytes, WS_ALIGN) : 0;
+    return align_up(dp.x2_bytes, WS_ALIGN) + ob + inner;
 }
 
 int conv2d_int8_dilated(const conv_desc_t *desc, int dilation, int layout, int cb, const int8_t *in, const int8_t *wt,
@@ -489,16 +491,84 @@ int conv2d_int8_dilated(const conv_desc_t *desc, int dilation, int layout, int c
     rc = make_plan(&dp.d2, layout, cb, &pl);  // the dense problem runs in one single-stage layout
     if (rc != CONV_OK) return rc;
     const size_t inner = conv2d_int8_workspace_bytes(&dp.d2, layout, cb, 0);
-    const size_t xb = align_up(dp.x2_bytes, WS_ALIGN), ob = align_up(dp.o2_bytes, WS_ALIGN);
+    const bool stored = pl.layout == CONV_LAYOUT_IMPLICIT;  // else the GEMM stage's epilogue interleaves
+    const size_t xb = align_up(dp.x2_bytes, WS_ALIGN), ob = stored ? align_up(dp.o2_bytes, WS_ALIGN) : 0;
     if (workspace_bytes < xb + ob + inner) return CONV_ERR_WORKSPACE;
     int8_t *x2 = static_cast<int8_t *>(workspace);
-    int32_t *o2 = reinterpret_cast<int32_t *>(x2 + xb);
     void *ws = inner ? static_cast<void *>(x2 + xb + ob) : nullptr;
     rc = dilation_pack_int8(desc, dilation, in, x2, stream);
     if (rc != CONV_OK) return rc;
-    rc = conv2d_int8_ex(&dp.d2, layout, cb, x2, wt, 0, o2, ws, inner, stream);
+    if (stored) {
+        int32_t *o2 = reinterpret_cast<int32_t *>(x2 + xb);
+        rc = conv2d_int8_ex(&dp.d2, layout, cb, x2, wt, 0, o2, ws, inner, stream);
+        if (rc != CONV_OK) return rc;
+        return dilation_unpack_int32(desc, dilation, o2, out, stream);
+    }
+    // both rewrites of the dense problem, then its GEMM stage writing the dilated layer's own output
+    hipStream_t st = (hipStream_t)stream;
+    int8_t *xq = static_cast<int8_t *>(ws), *wq = xq + align_up(pl.x_bytes, WS_ALIGN);
+    const conv_desc_t &e2 = dp.d2;
+    const hipError_t e = launch_rewrite_fused(pl.layout == CONV_LAYOUT_IM2COL, e2.N, e2.C, e2.H, e2.W, e2.K, e2.R, e2.S,
+                                              e2.stride, e2.pad, pl.P, pl.Q, pl.cb, pl.depth, x2, xq, wt, wq, st);
+    if (e == hipErrorNotSupported) {
+        rc = rewrite_weights(&dp.d2, pl, wt, wq, st);
+        if (rc != CONV_OK) return rc;
+        rc = rewrite_input(&dp.d2, pl, x2, xq, st);
+        if (rc != CONV_OK) return rc;
+    } else if (e != hipSuccess) return CONV_ERR_DEVICE;
+    GemmProblem g = gemm_problem(&dp.d2, pl, xq, wq, out);
+    g.il_d = dilation;
+    g.il_P = dp.P;
+    g.il_Q = dp.Q;
+    int t = -1, s = 1;
+    if (!gemm_pick(g, &t, &s)) return CONV_ERR_UNSUPPORTED;
+    return launch_gemm(g, t, 1, st) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+}
+
+// Dilation as an address multiplier: the plan of the undilated problem with the dilated layer's output extents.
+static int direct_dilated_plan(const conv_desc_t *desc, int dilation, int cb, Plan *pl)
+{
+    if (!desc || dilation <= 0) return CONV_ERR_INVALID_ARG;
+    int rc = make_plan(desc, CONV_LAYOUT_PACKED, cb, pl);
     if (rc != CONV_OK) return rc;
-    return dilation_unpack_int32(desc, dilation, o2, out, stream);
+    const long long Re = (long long)dilation * (desc->R - 1) + 1, Se = (long long)dilation * (desc->S - 1) + 1;
+    if (Re > pl->Hp || Se > pl->Wp) return CONV_ERR_INVALID_ARG;
+    pl->P = (int)((pl->Hp - Re) / desc->stride + 1);
+    pl->Q = (int)((pl->Wp - Se) / desc->stride + 1);
+    pl->M = (long long)desc->N * pl->P * pl->Q;
+    return CONV_OK;
+}
+
+size_t conv2d_int8_dilated_direct_workspace_bytes(const conv_desc_t *desc, int dilation, int cb)
+{
+    Plan pl;
+    if (direct_dilated_plan(desc, dilation, cb, &pl) != CONV_OK) return 0;
+    return align_up(pl.x_bytes, WS_ALIGN) + align_up(pl.w_bytes, WS_ALIGN);
+}
+
+int conv2d_int8_dilated_direct(const conv_desc_t *desc, int dilation, int cb, const int8_t *in, const int8_t *wt,
+                               int32_t *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    Plan pl;
+    int rc = direct_dilated_plan(desc, dilation, cb, &pl);
+    if (rc != CONV_OK) return rc;
+    if (!in || !wt || !out || !workspace || (reinterpret_cast<uintptr_t>(workspace) & (WS_ALIGN - 1)))
+        return CONV_ERR_INVALID_ARG;
+    const size_t xb = align_up(pl.x_bytes, WS_ALIGN);
+    if (workspace_bytes < xb + align_up(pl.w_bytes, WS_ALIGN)) return CONV_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    int8_t *xq = static_cast<int8_t *>(workspace), *wq = xq + xb;
+    const hipError_t e = launch_rewrite_fused(false, desc->N, desc->C, desc->H, desc->W, desc->K, desc->R, desc->S,
+                                              desc->stride, desc->pad, pl.P, pl.Q, pl.cb, pl.depth, in, xq, wt, wq, st);
+    if (e == hipErrorNotSupported) {
+        rc = rewrite_weights(desc, pl, wt, wq, st);
+        if (rc != CONV_OK) return rc;
+        rc = rewrite_input(desc, pl, in, xq, st);
+        if (rc != CONV_OK) return rc;
+    } else if (e != hipSuccess) return CONV_ERR_DEVICE;
+    GemmProblem g = gemm_problem(desc, pl, xq, wq, out);
+    g.dil = dilation;
+    return run_gemm(g, -1, 0, st);
 }
 
 int mfma_probe_int8(int blocks, int iters, int32_t *out, void *stream)

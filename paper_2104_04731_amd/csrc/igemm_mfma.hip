@@ -42,6 +42,12 @@ struct GemmArgs {
     // channel-blocked input [N][o_Cb][o_Hp][o_Wp][1 << o_cb_log2], int8.
     int8_t *act_out;
     int act_shift, act_relu, o_cb_log2, o_pad, o_Hp, o_Wp, o_Cb;
+    // Interleaving epilogue (il_d >= 2): the problem is the dense convolution on the il_d^2 sub-images of a
+    // dilated layer (image n2 = (n*il_d + a)*il_d + b); result pixel (i, j) of it is pixel
+    // (il_d*i + a, il_d*j + b) of image n in `out` [.][K][il_P][il_Q], or nothing if that lies outside.
+    int il_d, il_P, il_Q;
+    unsigned mg_il_dd, mg_il_d;
+    int dil;  // ACT_BLOCKED: distance between kernel taps in the padded image (1 = dense kernel)
 };
 
 // The ALU step between two int8 layers (Sec. 5.1): rounding right shift, optional max(., 0), clip.
@@ -177,7 +183,7 @@ __device__ __forceinline__ void igemm_body(const GemmArgs &a, int block_id, int 
                 const int tap = div_magic(gt, a.g16, a.mg_g16), sub = gt - tap * a.g16;
                 const int rb = div_magic(tap, a.S, a.mg_S), s = tap - rb * a.S;
                 const int b = div_magic(rb, a.R, a.mg_R), r = rb - b * a.R;
-                off = ((b * a.Hp + r) * a.Wp + s) * a.cb + sub * 16;
+                off = ((b * a.Hp + r * a.dil) * a.Wp + s * a.dil) * a.cb + sub * 16;  // tap (r, s), taps dil apart
             }
             koff[t] = off;
         }
@@ -534,6 +540,31 @@ __device__ __forceinline__ void igemm_body(const GemmArgs &a, int block_id, int 
         }
         return;
     }
+    if (a.il_d) {
+        const size_t il_PQ = (size_t)a.il_P * a.il_Q;
+#pragma unroll
+        for (int jm = 0; jm < FM; ++jm) {
+            const int m = m0 + wm * WTM + jm * 32 + (lane & 31);
+            if (m >= a.M) continue;
+            const int n2 = div_magic(m, a.PQ, a.mg_PQ), pq = m - n2 * a.PQ;
+            const int si = div_magic(pq, a.Q, a.mg_Q), sj = pq - si * a.Q;
+            const int dd = a.il_d * a.il_d;
+            const int n = div_magic(n2, dd, a.mg_il_dd), ab = n2 - n * dd;
+            const int pa = div_magic(ab, a.il_d, a.mg_il_d), pb = ab - pa * a.il_d;
+            const int p = a.il_d * si + pa, q = a.il_d * sj + pb;
+            if (p >= a.il_P || q >= a.il_Q) continue;   // a sub-image row or column past the real output
+            int32_t *base = a.out + (size_t)n * a.K * il_PQ + (size_t)p * a.il_Q + q;
+#pragma unroll
+            for (int i = 0; i < FK; ++i) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int k = k0 + wk * WTK + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                    if (k < a.K) base[(size_t)k * il_PQ] = acc[i][jm][v];
+                }
+            }
+        }
+        return;
+    }
     const bool interior = a.out_fits_32bit && k0 + TK <= a.K && m0 + TM <= a.M;
     if (interior) {
         // Whole tile in range: address = uniform row base (scalar registers, advanced by whole
@@ -770,6 +801,11 @@ static bool make_gemm_args(const GemmProblem &g, int tile, int split_k, GemmArgs
     a.o_Hp = g.PQ / g.Q + 2 * g.o_pad;
     a.o_Wp = g.Q + 2 * g.o_pad;
     a.o_Cb = g.o_cb > 0 ? (g.K + g.o_cb - 1) / g.o_cb : 0;
+    a.dil = g.dil > 0 ? g.dil : 1;
+    a.il_d = g.il_d;
+    a.il_P = g.il_P;
+    a.il_Q = g.il_Q;
+
     a.K = g.K;
     a.M = g.M;
     a.depth = g.depth;
@@ -820,6 +856,8 @@ static bool make_gemm_args(const GemmProblem &g, int tile, int split_k, GemmArgs
     a.mg_R = magic(g.R);
     a.mg_PQ = magic(g.PQ);
     a.mg_Q = magic(g.Q);
+    a.mg_il_dd = g.il_d ? magic(g.il_d * g.il_d) : 0;
+    a.mg_il_d = g.il_d ? magic(g.il_d) : 0;
     a.mg_tiles_k = magic(a.tiles_k);
     a.mg_tiles_m = magic(a.tiles_m);
     *out = a;
@@ -831,6 +869,7 @@ hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t 
     GemmArgs a;
     if (!make_gemm_args(g, tile, split_k, &a)) return hipErrorInvalidValue;
     if (a.act_out && a.split_k > 1) return hipErrorInvalidValue;  // the activation needs the whole sum
+    if (a.il_d && a.split_k > 1) return hipErrorInvalidValue;     // `out` has another shape than the clear assumes
     if (a.split_k > 1) {
         hipError_t e = launch_fill_zero(g.out, (size_t)g.M * g.K * sizeof(int32_t), st);
         if (e != hipSuccess) return e;

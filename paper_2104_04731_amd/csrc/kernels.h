@@ -29,6 +29,11 @@ struct GemmProblem {
     // o_cb a power of two >= 4; borders and channel padding are not written (the caller clears them).
     int8_t *act_out;
     int act_shift, act_relu, o_cb, o_pad;
+    // Interleaving epilogue (il_d >= 2; split_k must be 1): this problem is the dense convolution on the
+    // il_d^2 sub-images per image of a dilated layer, and `out` is that layer's own [N][K][il_P][il_Q].
+    int il_d, il_P, il_Q;
+    // ACT_BLOCKED: kernel taps `dil` pixels apart (0 or 1: dense); PQ and Q are then the dilated layer's own
+    int dil;
 };
 
 struct TileInfo {

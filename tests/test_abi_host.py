@@ -217,7 +217,9 @@ def test_dilated_problem_and_sizes(lib, case):
         il, icb = (layout, cb) if layout != lib.LAYOUT_AUTO else lib.select_layout(d2)[:2]
         inner = lib.conv2d_int8_workspace_bytes(d2, il, icb)
         o2 = d2[0] * K * (d2[2] - R + 1) * (d2[3] - S + 1) * 4
-        assert lib.conv2d_int8_dilated_workspace_bytes(dims, d, layout, cb) == up(d2[0] * d2[1] * d2[2] * d2[3]) + up(o2) + inner
+        # the sub-images' results are stored only when the dense problem runs in IMPLICIT
+        assert lib.conv2d_int8_dilated_workspace_bytes(dims, d, layout, cb) == \
+            up(d2[0] * d2[1] * d2[2] * d2[3]) + (up(o2) if il == lib.LAYOUT_IMPLICIT else 0) + inner
 
 
 def test_dilated_validation(lib):
@@ -264,3 +266,20 @@ def test_fused_activation_validation(lib):
     assert call(cb=24) == lib.ERR_UNSUPPORTED
     d1 = lib.ConvDesc(1, 64, 14, 14, 128, 1, 1, 1, 0)   # IMPLICIT applies to it, but has its own epilogue
     assert raw.conv2d_int8_packed_requant(ctypes.byref(d1), lib.LAYOUT_IMPLICIT, 0, p, p, p, 64, 0, 8, 1, None) == lib.ERR_UNSUPPORTED
+
+
+def test_direct_dilated_validation(lib):
+    raw = lib.load()
+    ok = lib.ConvDesc(1, 3, 16, 16, 8, 3, 3, 2, 2)
+    p = ctypes.c_void_p(256)
+    need = raw.conv2d_int8_dilated_direct_workspace_bytes(ctypes.byref(ok), 2, 16)
+    assert need == lib.conv2d_int8_workspace_bytes((1, 3, 16, 16, 8, 3, 3, 2, 2), lib.LAYOUT_PACKED, 16)
+    assert raw.conv2d_int8_dilated_direct_workspace_bytes(ctypes.byref(ok), 0, 16) == 0
+    assert raw.conv2d_int8_dilated_direct_workspace_bytes(ctypes.byref(ok), 10, 16) == 0    # spread extent 21 > 20
+    assert raw.conv2d_int8_dilated_direct_workspace_bytes(None, 2, 16) == 0
+    call = lambda dil=2, cb=16, x=p, w=p, o=p, ws=p, nb=need: raw.conv2d_int8_dilated_direct(ctypes.byref(ok), dil, cb, x, w, o, ws, nb, None)
+    assert call(dil=0) == lib.ERR_INVALID_ARG and call(dil=10) == lib.ERR_INVALID_ARG
+    assert call(x=None) == lib.ERR_INVALID_ARG and call(ws=None) == lib.ERR_INVALID_ARG
+    assert call(ws=ctypes.c_void_p(264)) == lib.ERR_INVALID_ARG
+    assert call(nb=need - 1) == lib.ERR_WORKSPACE
+    assert call(cb=24) == lib.ERR_UNSUPPORTED

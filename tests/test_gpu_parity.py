@@ -727,3 +727,20 @@ def test_mfma_probe_is_linear_in_its_iteration_count(lib):
     assert ops3 == 3 * ops1 == 3 * 2 * 32768 * 16 * 4
     assert np.count_nonzero(a) > a.size // 2
     assert np.array_equal((3 * a) & 0xFFFFFFFF, b & 0xFFFFFFFF)
+
+
+DIRECT_DILATED = DILATED_SHAPES[:8] + [((2, 16, 33, 40, 24, 3, 3, 2, 3), 3), ((1, 70, 21, 19, 9, 2, 3, 3, 2), 2),
+                                       ((1, 8, 12, 12, 4, 3, 3, 1, 1), 1)]
+
+
+@pytest.mark.parametrize("case", DIRECT_DILATED, ids=str)
+def test_dilated_convolution_as_an_address_multiplier(lib, case):
+    """Strides and dilations together, against the definition."""
+    dims, d = case
+    N, C, H, W, K, R, S, st, pad = dims
+    x = uniform_int8(941, (N, C, H, W)); w = uniform_int8(942, (K, C, R, S))
+    want = direct.conv2d_int8_dilated(x, w, st, pad, d)
+    for cb in (0, 16, 64):
+        out = torch.full(want.shape, -3, dtype=torch.int32, device=DEV)
+        lib.conv2d_int8_dilated_direct(dims, d, dev(x), dev(w), cb, out=out)
+        assert np.array_equal(host(out), want), f"cb {cb}: {np.count_nonzero(host(out) != want)} mismatches"
