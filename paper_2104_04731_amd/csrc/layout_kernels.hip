@@ -723,7 +723,10 @@ __global__ void __launch_bounds__(256) unpack_nhwc_kernel(const int32_t *src, in
     __shared__ int32_t tile[64][33];
     const int rx = threadIdx.x & 31, ry = threadIdx.x >> 5;  // read:  32 pixels x 8 channel rows per pass
     const int wx = threadIdx.x & 63, wy = threadIdx.x >> 6;  // write: 64 channels x 4 pixel rows per pass
-    for (long long t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    // neighbouring tiles share the cache lines at their common edge (a row of pixels is not a multiple of
+    // a line): workgroups that run side by side in one XCD, behind one L2, take neighbouring tiles
+    // (L2 fetches 1.13x the source instead of 2x; the time is the same, a plain copy's)
+    for (long long t = xcd_contiguous(blockIdx.x, gridDim.x); t < ntiles; t += gridDim.x) {
         const int tp = (int)(t % tiles_p);
         const long long r = t / tiles_p;
         const int tk = (int)(r % tiles_k);
