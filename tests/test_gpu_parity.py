@@ -744,3 +744,18 @@ def test_dilated_convolution_as_an_address_multiplier(lib, case):
         out = torch.full(want.shape, -3, dtype=torch.int32, device=DEV)
         lib.conv2d_int8_dilated_direct(dims, d, dev(x), dev(w), cb, out=out)
         assert np.array_equal(host(out), want), f"cb {cb}: {np.count_nonzero(host(out) != want)} mismatches"
+
+
+@pytest.mark.parametrize("dims", [(520, 64, 14, 14, 40, 1, 1, 1, 0), (300, 128, 14, 14, 200, 1, 1, 1, 0),
+                                  (140, 64, 30, 30, 32, 1, 1, 1, 0), (64, 192, 56, 56, 33, 1, 1, 1, 0),
+                                  (512, 64, 2, 106, 16, 1, 1, 1, 0)], ids=str)
+def test_pointwise_batch_form(lib, dims):
+    """Batches large enough for the 1x1 kernel that owns up to 224 pixels of an image per workgroup:
+    whole 14x14 images, several pixel ranges per image with a short last one, ragged output channels."""
+    cfg = ConvShape("pw-batch", *dims)
+    assert selection.implicit_applies(*dims)
+    x = uniform_int8(951, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(952, (cfg.K, cfg.C, 1, 1))
+    want = direct.conv2d_int8(x, w, 1, 0)
+    for rewritten in (False, True):
+        got = run_implicit(lib, cfg, x, w, rewritten)
+        assert np.array_equal(got, want), f"rewritten={rewritten}: {np.count_nonzero(got != want)} mismatches"
