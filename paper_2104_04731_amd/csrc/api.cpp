@@ -806,8 +806,11 @@ int conv2d_int8_nhwc(int N, int C, int H, int W, int K, int R, int S, int stride
     int rc = make_plan(&d, CONV_LAYOUT_PACKED, 0, &pl);
     if (rc != CONV_OK) return rc;
     if (!in || !wt || !out) return CONV_ERR_INVALID_ARG;
+    // The GEMM stage's epilogue writes NHWC itself (a lane's four values are four consecutive channels of a
+    // pixel); only a result that does not start on 16 bytes goes through an NKPQ staging tensor and a pass.
+    const bool direct = aligned16(out);
     const size_t xb = align_up(pl.x_bytes, WS_ALIGN), wb = align_up(pl.w_bytes, WS_ALIGN);
-    const size_t ob = align_up((size_t)pl.M * d.K * sizeof(int32_t), WS_ALIGN);
+    const size_t ob = direct ? 0 : align_up((size_t)pl.M * d.K * sizeof(int32_t), WS_ALIGN);
     const size_t need = xb + wb + ob;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CONV_ERR_DEVICE;
@@ -833,6 +836,11 @@ int conv2d_int8_nhwc(int N, int C, int H, int W, int K, int R, int S, int stride
     if (launch_pack_layout_nhwc(N, C, H, W, pl.cb, pad, in, xq, st) != hipSuccess) return CONV_ERR_DEVICE;
     rc = rewrite_weights(&d, pl, wt, wq, st);
     if (rc != CONV_OK) return rc;
+    if (direct) {
+        GemmProblem g = gemm_problem(&d, pl, xq, wq, out);
+        g.out_nhwc = 1;
+        return run_gemm(g, -1, 0, st);
+    }
     rc = run_gemm(gemm_problem(&d, pl, xq, wq, nkpq), -1, 0, st);
     if (rc != CONV_OK) return rc;
     return launch_unpack_nhwc(N, K, (long long)pl.P * pl.Q, nkpq, out, st) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;

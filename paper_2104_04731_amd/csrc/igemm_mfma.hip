@@ -48,6 +48,7 @@ struct GemmArgs {
     int il_d, il_P, il_Q;
     unsigned mg_il_dd, mg_il_d;
     int dil;  // ACT_BLOCKED: distance between kernel taps in the padded image (1 = dense kernel)
+    int out_nhwc;  // `out` is [N][P][Q][K] instead of [N][K][P][Q]
 };
 
 // The ALU step between two int8 layers (Sec. 5.1): rounding right shift, optional max(., 0), clip.
@@ -540,6 +541,37 @@ __device__ __forceinline__ void igemm_body(const GemmArgs &a, int block_id, int 
         }
         return;
     }
+    if (a.out_nhwc) {
+        // NHWC result: the four values v%4 of a lane are four consecutive channels of one pixel, 16 bytes of
+        // that pixel's channel run (aligned when K % 4 == 0; a depth split adds them one by one)
+#pragma unroll
+        for (int jm = 0; jm < FM; ++jm) {
+            const int m = m0 + wm * WTM + jm * 32 + (lane & 31);
+            if (m >= a.M) continue;
+            int32_t *pix = a.out + (size_t)m * a.K;
+#pragma unroll
+            for (int i = 0; i < FK; ++i) {
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg) {
+                    const int k = k0 + wk * WTK + i * 32 + 8 * vg + 4 * (lane >> 5);
+                    if (k >= a.K) continue;
+                    if (a.split_k > 1) {
+                        for (int t = 0; t < 4; ++t)
+                            if (k + t < a.K)
+                                __hip_atomic_fetch_add(pix + k + t, acc[i][jm][4 * vg + t], __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+                    } else if (k + 3 < a.K && (a.K & 3) == 0) {
+                        *reinterpret_cast<v4i *>(pix + k) =
+                            v4i{acc[i][jm][4 * vg], acc[i][jm][4 * vg + 1], acc[i][jm][4 * vg + 2], acc[i][jm][4 * vg + 3]};
+                    } else {
+                        for (int t = 0; t < 4; ++t)
+                            if (k + t < a.K) pix[k + t] = acc[i][jm][4 * vg + t];
+                    }
+                }
+            }
+        }
+        return;
+    }
     if (a.il_d) {
         const size_t il_PQ = (size_t)a.il_P * a.il_Q;
 #pragma unroll
@@ -802,6 +834,7 @@ static bool make_gemm_args(const GemmProblem &g, int tile, int split_k, GemmArgs
     a.o_Wp = g.Q + 2 * g.o_pad;
     a.o_Cb = g.o_cb > 0 ? (g.K + g.o_cb - 1) / g.o_cb : 0;
     a.dil = g.dil > 0 ? g.dil : 1;
+    a.out_nhwc = g.out_nhwc;
     a.il_d = g.il_d;
     a.il_P = g.il_P;
     a.il_Q = g.il_Q;

@@ -34,6 +34,7 @@ struct GemmProblem {
     int il_d, il_P, il_Q;
     // ACT_BLOCKED: kernel taps `dil` pixels apart (0 or 1: dense); PQ and Q are then the dilated layer's own
     int dil;
+    int out_nhwc;  // `out` is [N][PQ][K] (channels innermost) instead of [N][K][PQ]; a depth split clears the same bytes
 };
 
 struct TileInfo {

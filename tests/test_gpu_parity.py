@@ -575,14 +575,21 @@ def test_unpack_nhwc(lib, shape):
 
 
 @pytest.mark.parametrize("cfg", [CONFIGS["C1"], CONFIGS["C2"], CONFIGS["C4a"], CONFIGS["C4b"], CONFIGS["C3"],
-                                 ConvShape("nhwc-ragged", 2, 37, 9, 11, 21, 3, 2, 2, 1)], ids=lambda c: c.name)
+                                 ConvShape("nhwc-ragged", 2, 37, 9, 11, 21, 3, 2, 2, 1),
+                                 ConvShape("nhwc-deep", 1, 256, 7, 7, 64, 3, 3, 1, 1),      # small and deep: a depth split
+                                 ConvShape("nhwc-k130", 1, 32, 12, 12, 130, 3, 3, 1, 1)], ids=lambda c: c.name)
 def test_conv_nhwc_one_shot(lib, cfg):
-    """NHWC in, NHWC out: the NCHW definition seen through transposed views."""
+    """NHWC in, NHWC out: the NCHW definition seen through transposed views.  The GEMM stage writes NHWC
+    itself; a result that does not start on 16 bytes takes the staging tensor and the unpacking pass."""
     x = uniform_int8(611, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(612, (cfg.K, cfg.C, cfg.R, cfg.S))
     want = layouts.unpack_nhwc(direct.conv2d_int8(x, w, cfg.stride, cfg.pad))
     xh = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
     got = host(lib.conv2d_int8_nhwc(dev(xh), dev(w), cfg.stride, cfg.pad))
     assert got.shape == want.shape and np.array_equal(got, want)
+    buf = torch.full((want.size + 4,), -3, dtype=torch.int32, device=DEV)
+    view = buf[1:1 + want.size].view(want.shape)
+    lib.conv2d_int8_nhwc(dev(xh), dev(w), cfg.stride, cfg.pad, out=view)
+    assert np.array_equal(host(view), want) and int(buf[0]) == -3 and int(buf[-1]) == -3
 
 
 # ---- activation between layers -------------------------------------------------------------------
