@@ -766,3 +766,42 @@ def test_pointwise_batch_form(lib, dims):
     for rewritten in (False, True):
         got = run_implicit(lib, cfg, x, w, rewritten)
         assert np.array_equal(got, want), f"rewritten={rewritten}: {np.count_nonzero(got != want)} mismatches"
+
+
+# ---- seeded random shapes through the routes added around the GEMM stage's epilogue ---------------------------
+def test_dilated_random_shapes(lib):
+    rng = np.random.default_rng(9101)
+    done = 0
+    while done < 40:
+        N = int(rng.integers(1, 4)); C = int(rng.choice([1, 3, 8, 16, 40, 64])); K = int(rng.choice([1, 7, 32, 65]))
+        R = int(rng.integers(1, 5)); S = int(rng.integers(1, 5)); d = int(rng.integers(2, 6)); pad = int(rng.integers(0, 6))
+        st = int(rng.integers(1, 4)); H = int(rng.integers(1, 40)); W = int(rng.integers(1, 70))
+        if d * (R - 1) + 1 > H + 2 * pad or d * (S - 1) + 1 > W + 2 * pad:
+            continue
+        x = uniform_int8(H * 37 + W, (N, C, H, W)); w = uniform_int8(K * 11 + C, (K, C, R, S))
+        dims = (N, C, H, W, K, R, S, st, pad)
+        want = direct.conv2d_int8_dilated(x, w, st, pad, d)
+        got = host(lib.conv2d_int8_dilated_direct(dims, d, dev(x), dev(w)))
+        assert np.array_equal(got, want), f"address multiplier {dims} d={d}"
+        if st == 1:
+            np.testing.assert_array_equal(host(lib.dilation_pack_int8(dims, d, dev(x))), layouts.dilation_pack(x, pad, d), err_msg=str((dims, d)))
+            for layout, cb in ((lib.LAYOUT_AUTO, 0), (lib.LAYOUT_PACKED, 16), (lib.LAYOUT_IM2COL, 0)):
+                got = host(lib.conv2d_int8_dilated(dims, d, dev(x), dev(w), layout, cb))
+                assert np.array_equal(got, want), f"image pack route {dims} d={d} {lib.LAYOUT_NAMES[layout]}"
+        done += 1
+
+
+def test_fused_activation_and_nhwc_random_shapes(lib):
+    shapes = _random_shapes(9102, 30, lambda d: d[0] * d[4] * d[2] * d[3] < 300000)
+    rng = np.random.default_rng(9103)
+    for cfg in shapes:
+        x = uniform_int8(cfg.H * 13 + cfg.W, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(cfg.K * 5 + cfg.C, (cfg.K, cfg.C, cfg.R, cfg.S))
+        conv = direct.conv2d_int8(x, w, cfg.stride, cfg.pad)
+        xh = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+        assert np.array_equal(host(lib.conv2d_int8_nhwc(dev(xh), dev(w), cfg.stride, cfg.pad)), layouts.unpack_nhwc(conv)), cfg.dims()
+        cb = int(rng.choice([16, 32, 64])); out_cb = int(rng.choice([16, 32, 64])); out_pad = int(rng.integers(0, 3))
+        shift = int(rng.integers(0, 14)); relu = bool(rng.integers(0, 2))
+        xp = lib.pack_layout(dev(x), cb, cfg.pad); wp = lib.pack_weights(dev(w), lib.LAYOUT_PACKED, cb)
+        want = layouts.pack_layout(layouts.requant(conv, shift, relu), out_cb, out_pad)
+        got = host(lib.conv2d_int8_packed_requant(cfg.dims(), lib.LAYOUT_PACKED, cb, xp, wp, out_cb, out_pad, shift, relu))
+        assert np.array_equal(got, want), (cfg.dims(), cb, out_cb, out_pad, shift, relu)
