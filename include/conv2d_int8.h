@@ -161,9 +161,9 @@ int requant_pack_layout(int N, int K, int P, int Q, int cb, int pad, int shift, 
 /* The same activation fused into the GEMM stage's epilogue (the ALU step behind the GEMM core, Sec. 5.1):
  * out_blocked = requant_pack_layout(conv2d_int8_packed(...)) without the int32 tensor ever being stored --
  * int8 [N][ceil(K/out_cb)][P + 2 out_pad][Q + 2 out_pad][out_cb], the next layer's PACKED input with its
- * spatial padding out_pad.  in_packed, wt_packed, layout, cb as for conv2d_int8_packed (PACKED, PAD_ONLY or
- * IM2COL; IMPLICIT: CONV_ERR_UNSUPPORTED); out_cb 16, 32 or 64; shift 0..31; all three pointers 16-byte
- * aligned.  One launch; a second one before it (a clear of out_blocked) when out_pad > 0 or K % out_cb != 0.
+ * spatial padding out_pad.  in_packed, wt_packed, layout, cb as for conv2d_int8_packed (with IMPLICIT:
+ * the NCHW input itself and the output of pack_weights); out_cb 16, 32 or 64; shift 0..31; all three
+ * pointers 16-byte aligned (IMPLICIT: out_blocked only).  One launch; a second one before it (a clear of out_blocked) when out_pad > 0 or K % out_cb != 0.
  * The whole depth is summed before the activation (no depth split). */
 int conv2d_int8_packed_requant(const conv_desc_t *desc, int layout, int cb,
                                const int8_t *in_packed, const int8_t *wt_packed, int8_t *out_blocked,

@@ -43,7 +43,7 @@ WindowProblem window_problem(const conv_desc_t *d, const Plan &pl, const int8_t 
                              int32_t *out, int wt_rewritten)
 {
     return WindowProblem{x, w, out, d->N, d->C, d->H, d->W, d->K, pl.P, pl.Q, d->R, d->S, d->stride, d->pad,
-                         wt_rewritten};
+                         wt_rewritten, ActOut{}};
 }
 
 int run_implicit(const Plan &pl, const WindowProblem &g, hipStream_t st)
@@ -635,9 +635,9 @@ int conv2d_int8_packed_requant(const conv_desc_t *desc, int layout, int cb, cons
     Plan pl;
     int rc = make_plan(desc, layout, cb, &pl);
     if (rc != CONV_OK) return rc;
-    if (pl.layout == CONV_LAYOUT_IMPLICIT) return CONV_ERR_UNSUPPORTED;  // those kernels have their own epilogue
     if (!in_packed || !wt_packed || !out_blocked || out_pad < 0 || shift < 0 || shift > 31) return CONV_ERR_INVALID_ARG;
-    if (!aligned16(in_packed) || !aligned16(wt_packed) || !aligned16(out_blocked)) return CONV_ERR_INVALID_ARG;
+    const bool implicit = pl.layout == CONV_LAYOUT_IMPLICIT;  // reads the NCHW input and either weight form as they are
+    if ((!implicit && (!aligned16(in_packed) || !aligned16(wt_packed))) || !aligned16(out_blocked)) return CONV_ERR_INVALID_ARG;
     if (out_cb != 16 && out_cb != 32 && out_cb != 64) return CONV_ERR_UNSUPPORTED;
     const long long Hq = (long long)pl.P + 2LL * out_pad, Wq = (long long)pl.Q + 2LL * out_pad;
     const long long Cbq = (desc->K + out_cb - 1) / out_cb;
@@ -647,6 +647,13 @@ int conv2d_int8_packed_requant(const conv_desc_t *desc, int layout, int cb, cons
     if (out_pad > 0 || desc->K % out_cb != 0) {
         const size_t bytes = (size_t)desc->N * (size_t)Cbq * (size_t)Hq * (size_t)Wq * (size_t)out_cb;
         if (launch_fill_zero(out_blocked, bytes, st) != hipSuccess) return CONV_ERR_DEVICE;
+    }
+    if (implicit) {
+        WindowProblem wp = window_problem(desc, pl, in_packed, wt_packed, nullptr, 1);
+        int lg = 0;
+        while ((1 << lg) < out_cb) ++lg;
+        wp.act = ActOut{out_blocked, shift, relu != 0, lg, out_pad, (int)Hq, (int)Wq, (int)Cbq};
+        return run_implicit(pl, wp, st);
     }
     GemmProblem g = gemm_problem(desc, pl, in_packed, wt_packed, nullptr);
     g.act_out = out_blocked;

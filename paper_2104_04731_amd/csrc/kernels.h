@@ -86,12 +86,21 @@ hipError_t launch_image_pack_weights(int K, int C, int R, int S, int stride, con
                                      hipStream_t st);
 
 // GEMM stage that unrolls the stencil itself from the NCHW input (no rewritten activations).
+// Activation in a kernel's epilogue: instead of the int32 result, requant(result) goes out as the next
+// layer's channel-blocked int8 input [N][Cb][Hp][Wp][1 << cb_log2] (interior pixels and real channels only;
+// the caller clears the rest).  out == nullptr: off.
+struct ActOut {
+    int8_t *out;
+    int shift, relu, cb_log2, pad, Hp, Wp, Cb;
+};
+
 struct WindowProblem {
     const int8_t *in;   // [N][C][H][W]
     const int8_t *wt;   // KCRS, or (wt_rewritten) [K][depth] with depth index (c*R + r)*ceil(S,4) + s
     int32_t *out;       // [N][K][P][Q]
     int N, C, H, W, K, P, Q, R, S, stride, pad;
     int wt_rewritten;
+    ActOut act;
 };
 int window_depth(int C, int R, int S);          // 0 if the padded depth exceeds what the kernel unrolls
 bool window_fits(const WindowProblem &g);       // depth, image width and LDS window within the kernel's limits

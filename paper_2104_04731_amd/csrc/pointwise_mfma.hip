@@ -31,6 +31,9 @@ struct PointArgs {
     int C, HW, K, tiles;  // tiles of 32 pixels per image
     int ntiles;           // N * tiles
     unsigned m_tiles;
+    int W;                // image width (the activation epilogue needs a pixel's row and column)
+    unsigned m_W;
+    ActOut act;           // activation epilogue (act.out != null): `out` is not written
 };
 
 __device__ __forceinline__ unsigned ld_u32(const void *p)  // any alignment
@@ -46,7 +49,7 @@ __device__ __forceinline__ v4i ld_v4(const void *p)  // any alignment
     return x;
 }
 
-template <int NKK>  // C = 32 * NKK
+template <int NKK, bool ACT>  // C = 32 * NKK; ACT: the activation epilogue (a kernel of its own: the plain one stays as lean as it was)
 __global__ void __launch_bounds__(256) conv_pointwise_kernel(const PointArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -118,7 +121,15 @@ __global__ void __launch_bounds__(256) conv_pointwise_kernel(const PointArgs a)
 
     // 4. D block: column = lane%32 = pixel, row = 8*(v/4) + 4*(lane/32) + v%4 = channel
     const int p = px0 + l31;
-    if (p < a.HW) {
+    if (ACT) {
+        if (p < a.HW) {
+            const int py = fast_div_any(p, a.W, a.m_W), qx = p - py * a.W;
+#pragma unroll
+            for (int vg = 0; vg < 4; ++vg)
+                act_store4(a.act, n, py, qx, k0 + 8 * vg + 4 * half, a.K, acc[4 * vg], acc[4 * vg + 1], acc[4 * vg + 2],
+                           acc[4 * vg + 3]);
+        }
+    } else if (p < a.HW) {
         int32_t *base = a.out + ((size_t)n * a.K + k0 + 4 * half) * a.HW + p;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -148,6 +159,9 @@ struct PointImageArgs {
     int32_t *out;
     int C, HW, K, ptiles;   // ptiles = ranges of 224 pixels per image
     unsigned m_ptiles;
+    int W;
+    unsigned m_W;
+    ActOut act;             // activation epilogue (act.out != null): `out` is not written
 };
 
 __global__ void __launch_bounds__(256) conv_pointwise_image_kernel(const PointImageArgs a)
@@ -227,6 +241,19 @@ __global__ void __launch_bounds__(256) conv_pointwise_image_kernel(const PointIm
     }
 
     // D block b: column = lane%32 = pixel px0 + 32 b + lane%32, row = 8*(v/4) + 4*(lane/32) + v%4 = channel
+    if (a.act.out) {
+#pragma unroll
+        for (int b = 0; b < IMG_PXB; ++b) {
+            if (32 * b + l31 < npx) {
+                const int p = px0 + 32 * b + l31, py = fast_div_any(p, a.W, a.m_W), qx = p - py * a.W;
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg)
+                    act_store4(a.act, n, py, qx, k0 + 8 * vg + 4 * half, a.K, acc[b][4 * vg], acc[b][4 * vg + 1],
+                               acc[b][4 * vg + 2], acc[b][4 * vg + 3]);
+            }
+        }
+        return;
+    }
     int32_t *obase = a.out + ((size_t)n * a.K + k0 + 4 * half) * a.HW + px0 + l31;
 #pragma unroll
     for (int b = 0; b < IMG_PXB; ++b) {
@@ -260,6 +287,9 @@ static hipError_t launch_pointwise_image(const WindowProblem &g, hipStream_t st)
     a.K = g.K;
     a.ptiles = (a.HW + IMG_PX - 1) / IMG_PX;
     a.m_ptiles = magic_for(a.ptiles);
+    a.W = g.W;
+    a.m_W = magic_for(g.W);
+    a.act = g.act;
     const dim3 grid((unsigned)(g.N * a.ptiles), (unsigned)((g.K + 127) / 128));
     hipLaunchKernelGGL(conv_pointwise_image_kernel, grid, dim3(256), (size_t)2 * IMG_PX * IMG_PITCH, st, a);
     return hipGetLastError();
@@ -268,7 +298,8 @@ static hipError_t launch_pointwise_image(const WindowProblem &g, hipStream_t st)
 template <int NKK>
 hipError_t launch_nkk(const PointArgs &a, dim3 grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((conv_pointwise_kernel<NKK>), grid, dim3(256), (size_t)32 * (32 * NKK + 16), st, a);
+    if (a.act.out) hipLaunchKernelGGL((conv_pointwise_kernel<NKK, true>), grid, dim3(256), (size_t)32 * (32 * NKK + 16), st, a);
+    else hipLaunchKernelGGL((conv_pointwise_kernel<NKK, false>), grid, dim3(256), (size_t)32 * (32 * NKK + 16), st, a);
     return hipGetLastError();
 }
 
@@ -298,6 +329,9 @@ hipError_t launch_pointwise_conv(const WindowProblem &g, hipStream_t st)
     a.tiles = (a.HW + 31) / 32;
     a.m_tiles = magic_for(a.tiles);
     a.ntiles = g.N * a.tiles;
+    a.W = g.W;
+    a.m_W = magic_for(g.W);
+    a.act = g.act;
     const int kgroups = (g.K + 127) / 128;
     int wgs = 256 * 4 / kgroups;  // about four workgroups fit a CU
     if (wgs < 256) wgs = 256;

@@ -37,6 +37,29 @@ __device__ __forceinline__ int fast_div_any(int n, int d, unsigned magic)
     if ((long long)q * d > n) --q;
     return q;
 }
+// The ALU step between two int8 layers (Sec. 5.1): rounding right shift, optional max(., 0), clip to int8.
+__device__ __forceinline__ int act_requant(int x, int shift, int relu)
+{
+    // floor(x / 2^shift + 1/2) without leaving 32 bits: floor(x / 2^shift) + bit (shift-1) of x
+    int v = shift > 0 ? (x >> shift) + ((x >> (shift - 1)) & 1) : x;
+    if (relu) v = max(v, 0);
+    return min(max(v, -128), 127);
+}
+// Four consecutive output channels k .. k+3 of pixel (n, p, q) -- what one lane holds in v%4 of an MFMA
+// result block -- activated and stored as one dword of the blocked tensor (bytes past channel K-1 are not written).
+__device__ __forceinline__ void act_store4(const ActOut &e, int n, int p, int q, int k, int K, int x0, int x1, int x2, int x3)
+{
+    if (k >= K) return;
+    const size_t pix = ((size_t)n * e.Cb + (k >> e.cb_log2)) * e.Hp * e.Wp + (size_t)(p + e.pad) * e.Wp + (q + e.pad);
+    int8_t *dst = e.out + (pix << e.cb_log2) + (k & ((1 << e.cb_log2) - 1));
+    const int y[4] = {act_requant(x0, e.shift, e.relu), act_requant(x1, e.shift, e.relu), act_requant(x2, e.shift, e.relu),
+                      act_requant(x3, e.shift, e.relu)};
+    if (k + 3 < K) *reinterpret_cast<unsigned *>(dst) = pack4(y[0], y[1], y[2], y[3]);
+    else
+        for (int t = 0; t < 4; ++t)
+            if (k + t < K) dst[t] = (int8_t)y[t];
+}
+
 __device__ __forceinline__ unsigned magic_for_device(int d)  // the same constant, made on the device
 {
     return d == 1 ? 0u : (unsigned)(0xFFFFFFFFu / (unsigned)d) + 1u;

@@ -46,6 +46,7 @@ struct WindowArgs {
     int out_small;         // 4*K*P*Q < 2^32
     int in_small;          // C*H*W < 2^31
     int wide_out;          // Q % 4 == 0 and out 16-byte aligned: 16-byte stores
+    ActOut act;            // activation epilogue (act.out != null): `out` is not written
     unsigned m_wd, m_RW, m_nd, m_R, m_tiles_q, m_tiles_p;
 };
 
@@ -56,7 +57,7 @@ __device__ __forceinline__ unsigned load_u32(const void *p)  // any alignment
     return x;
 }
 
-template <int NKK, int NKB>
+template <int NKK, int NKB, bool ACT>  // ACT: the activation epilogue, a kernel of its own
 __global__ void __launch_bounds__(256) conv_window_kernel(const WindowArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -200,6 +201,18 @@ __global__ void __launch_bounds__(256) conv_window_kernel(const WindowArgs a)
     }
 
     // 5. D block: column = lane%32 = pixel, row = 8*(v/4) + 4*(lane/32) + v%4 = channel
+    if (ACT) {
+        const int p = p0 + pw, q = q0 + qw * 32 + l31;
+        if (p < a.P && q < a.Q) {
+#pragma unroll
+            for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg)
+                    act_store4(a.act, n, p, q, k0 + kb * 32 + 8 * vg + 4 * half, a.K, acc[kb][4 * vg], acc[kb][4 * vg + 1],
+                               acc[kb][4 * vg + 2], acc[kb][4 * vg + 3]);
+        }
+        return;
+    }
     const size_t PQ = (size_t)a.P * a.Q;
     int32_t *outn = a.out + (size_t)n * a.K * PQ;
     if (a.wide_out) {
@@ -324,6 +337,7 @@ static bool window_plan(const WindowProblem &g, WindowArgs *a)
     w.out_small = 4LL * g.K * g.P * g.Q < (1LL << 32);
     w.in_small = (long long)g.C * g.H * g.W < (1LL << 31);
     w.wide_out = g.Q % 4 == 0 && (reinterpret_cast<uintptr_t>(g.out) & 15) == 0;
+    w.act = g.act;
     if (a) *a = w;
     return true;
 }
@@ -333,8 +347,11 @@ bool window_fits(const WindowProblem &g) { return window_plan(g, nullptr); }
 template <int NKK>
 static hipError_t launch_window_nkk(const WindowArgs &a, dim3 grid, size_t lds, hipStream_t st)
 {
-    if (a.K > 32) hipLaunchKernelGGL((conv_window_kernel<NKK, 2>), grid, dim3(256), lds, st, a);
-    else hipLaunchKernelGGL((conv_window_kernel<NKK, 1>), grid, dim3(256), lds, st, a);
+    if (a.act.out) {
+        if (a.K > 32) hipLaunchKernelGGL((conv_window_kernel<NKK, 2, true>), grid, dim3(256), lds, st, a);
+        else hipLaunchKernelGGL((conv_window_kernel<NKK, 1, true>), grid, dim3(256), lds, st, a);
+    } else if (a.K > 32) hipLaunchKernelGGL((conv_window_kernel<NKK, 2, false>), grid, dim3(256), lds, st, a);
+    else hipLaunchKernelGGL((conv_window_kernel<NKK, 1, false>), grid, dim3(256), lds, st, a);
     return hipGetLastError();
 }
 

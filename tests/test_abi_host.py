@@ -264,7 +264,7 @@ def test_fused_activation_validation(lib):
     assert call(shift=32) == lib.ERR_INVALID_ARG and call(shift=-1) == lib.ERR_INVALID_ARG and call(opad=-1) == lib.ERR_INVALID_ARG
     assert call(ocb=24) == lib.ERR_UNSUPPORTED and call(ocb=128) == lib.ERR_UNSUPPORTED
     assert call(cb=24) == lib.ERR_UNSUPPORTED
-    d1 = lib.ConvDesc(1, 64, 14, 14, 128, 1, 1, 1, 0)   # IMPLICIT applies to it, but has its own epilogue
+    d1 = lib.ConvDesc(1, 64, 14, 14, 128, 3, 3, 1, 1)   # outside IMPLICIT's domain
     assert raw.conv2d_int8_packed_requant(ctypes.byref(d1), lib.LAYOUT_IMPLICIT, 0, p, p, p, 64, 0, 8, 1, None) == lib.ERR_UNSUPPORTED
 
 

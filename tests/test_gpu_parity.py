@@ -805,3 +805,20 @@ def test_fused_activation_and_nhwc_random_shapes(lib):
         want = layouts.pack_layout(layouts.requant(conv, shift, relu), out_cb, out_pad)
         got = host(lib.conv2d_int8_packed_requant(cfg.dims(), lib.LAYOUT_PACKED, cb, xp, wp, out_cb, out_pad, shift, relu))
         assert np.array_equal(got, want), (cfg.dims(), cb, out_cb, out_pad, shift, relu)
+
+
+@pytest.mark.parametrize("cfg", [CONFIGS["C1"], CONFIGS["C3"], CONFIGS["C5"], CONFIGS["C4b"],
+                                 ConvShape("ia-ragged", 2, 3, 19, 37, 21, 5, 3, 2, 2), ConvShape("ia-1x1", 3, 128, 6, 10, 70, 1, 1, 1, 0),
+                                 ConvShape("ia-batch", 300, 64, 14, 14, 40, 1, 1, 1, 0)], ids=lambda c: c.name)
+def test_implicit_kernels_with_fused_activation(lib, cfg):
+    """The two kernels that read NCHW themselves, with the activation in their epilogue."""
+    assert selection.implicit_applies(*cfg.dims())
+    x = uniform_int8(961, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(962, (cfg.K, cfg.C, cfg.R, cfg.S))
+    conv = direct.conv2d_int8(x, w, cfg.stride, cfg.pad)
+    wp = lib.pack_weights(dev(w), lib.LAYOUT_IMPLICIT, 0)
+    for out_cb, out_pad, shift, relu in ((64, 0, 6, True), (16, 1, 4, False), (32, 2, 0, True)):
+        want = layouts.pack_layout(layouts.requant(conv, shift, relu), out_cb, out_pad)
+        out = torch.full(want.shape, 77, dtype=torch.int8, device=DEV)
+        lib.conv2d_int8_packed_requant(cfg.dims(), lib.LAYOUT_IMPLICIT, 0, dev(x), wp, out_cb, out_pad, shift, relu, out=out)
+        got = host(out)
+        assert np.array_equal(got, want), f"-> cb {out_cb} pad {out_pad} shift {shift}: {np.count_nonzero(got != want)} mismatches"
