@@ -31,8 +31,8 @@ PEAK_HBM_BPS = 8.0e12    # HBM3E
 # describe the kernel source whose hash is recorded here; for any other source `traffic` is null.
 TRAFFIC = {
     "source": "paper_2104_04731_amd/csrc/igemm_mfma.hip",
-    "sha256": "6ad1e9aa9702ea1639df2c5381bbbcfec980e722d86ea08890d267ed2e3f1387",
-    "fetch_bytes": 5478897,
+    "sha256": "66cd608e8587ba878638eac8fbe3ec0abc046880b61c37a592aad70347a376ec",
+    "fetch_bytes": 5517443,
     "write_bytes": 3211264,
 }
 
