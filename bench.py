@@ -68,8 +68,8 @@ def parse():
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (the path shards over batch or output "
-              "channels without any exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: one GPU only (the path would shard over batch or output channels without any "
+              "exchange, so several GPUs are several independent runs); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
