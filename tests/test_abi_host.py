@@ -283,3 +283,11 @@ def test_direct_dilated_validation(lib):
     assert call(ws=ctypes.c_void_p(264)) == lib.ERR_INVALID_ARG
     assert call(nb=need - 1) == lib.ERR_WORKSPACE
     assert call(cb=24) == lib.ERR_UNSUPPORTED
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: any other count ends with a message and a non-zero status before anything is imported."""
+    import subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
+    assert r.returncode != 0 and "one GPU only" in r.stderr and r.stdout.strip() == ""
