@@ -312,6 +312,15 @@ def n_scaled(lib, timed, CONFIGS, dev):
     out["gemm_stage_C4a_N2048"] = {"us": round(ms * 1e3, 2), "tops": round(cfg.ops / (ms * 1e-3) / 1e12, 2),
                                    "pct_mfma_peak": round(100 * cfg.ops / (ms * 1e-3) / PEAK_INT8_OPS, 2),
                                    "tile": f"{rows}x{cols}", "split_k": split}
+    # the same stage with the other two epilogues: an NHWC int32 result (16-byte stores, 2 KB runs per pixel
+    # instead of 128-byte runs per channel) and the activation (int8, the next layer's blocked input)
+    onh = torch.empty((cfg.N, cfg.P, cfg.Q, cfg.K), dtype=torch.int32, device=dev)
+    _, ms_n = timed(lambda: lib.conv2d_int8_packed_nhwc(cfg.dims(), lay, cb, xp, wp, onh), 20, 3)
+    xact = lib.conv2d_int8_packed_requant(cfg.dims(), lay, cb, xp, wp, 64, 0, 9, True)
+    _, ms_a = timed(lambda: lib.conv2d_int8_packed_requant(cfg.dims(), lay, cb, xp, wp, 64, 0, 9, True, out=xact), 20, 3)
+    out["gemm_stage_C4a_N2048"]["nhwc_result_us"] = round(ms_n * 1e3, 2)
+    out["gemm_stage_C4a_N2048"]["activation_epilogue_us"] = round(ms_a * 1e3, 2)
+    del onh, xact
     _, ms = timed(lambda: lib.pack_layout(x, cb, cfg.pad, out=xp), 20, 3)
     b = x.numel() + xp.numel()
     out["pack_layout_C4a_N2048"] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),

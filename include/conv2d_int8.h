@@ -158,6 +158,14 @@ int requant_int8(long long count, const int32_t *src, int8_t *dst, int shift, in
 int requant_pack_layout(int N, int K, int P, int Q, int cb, int pad, int shift, int relu,
                         const int32_t *src, int8_t *dst, void *stream);
 
+/* The GEMM stage with an NHWC result (Sec. 5.2): as conv2d_int8_packed, but out_nhwc is int32 [N][P][Q][K],
+ * written by the epilogue itself (a lane of the MFMA result holds four consecutive channels of a pixel:
+ * 16-byte stores when K % 4 == 0).  PACKED, PAD_ONLY or IM2COL (IMPLICIT: CONV_ERR_UNSUPPORTED); all three
+ * pointers 16-byte aligned. */
+int conv2d_int8_packed_nhwc(const conv_desc_t *desc, int layout, int cb,
+                            const int8_t *in_packed, const int8_t *wt_packed, int32_t *out_nhwc,
+                            int tile, int split_k, void *stream);
+
 /* The same activation fused into the GEMM stage's epilogue (the ALU step behind the GEMM core, Sec. 5.1):
  * out_blocked = requant_pack_layout(conv2d_int8_packed(...)) without the int32 tensor ever being stored --
  * int8 [N][ceil(K/out_cb)][P + 2 out_pad][Q + 2 out_pad][out_cb], the next layer's PACKED input with its

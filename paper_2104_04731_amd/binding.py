@@ -24,7 +24,7 @@ EXPORTS = [
     "conv2d_int8_tile_applies", "pack_layout", "pack_layout_bytes", "pack_layout_nhwc",
     "pack_weights", "pack_weights_depth", "pack_weights_bytes", "im2col_int8", "im2col_bytes",
     "image_pack_desc", "image_pack_bytes", "image_pack_weights_bytes", "image_pack_int8", "image_pack_weights",
-    "conv2d_int8_packed_requant", "mfma_probe_int8",
+    "conv2d_int8_packed_requant", "conv2d_int8_packed_nhwc", "mfma_probe_int8",
     "dilated_desc", "dilation_pack_bytes", "dilation_pack_int8", "dilation_unpack_int32",
     "conv2d_int8_dilated_workspace_bytes", "conv2d_int8_dilated",
     "conv2d_int8_dilated_direct_workspace_bytes", "conv2d_int8_dilated_direct",
@@ -85,6 +85,7 @@ def load(path: str | None = None):
         "image_pack_int8": (i, [dp, vp, vp, vp]),
         "image_pack_weights": (i, [dp, vp, vp, vp]),
         "conv2d_int8_packed_requant": (i, [dp, i, i, vp, vp, vp, i, i, i, i, vp]),
+        "conv2d_int8_packed_nhwc": (i, [dp, i, i, vp, vp, vp, i, i, vp]),
         "dilated_desc": (i, [dp, i, dp]),
         "dilation_pack_bytes": (sz, [dp, i]),
         "dilation_pack_int8": (i, [dp, i, vp, vp, vp]),
@@ -218,6 +219,14 @@ def conv2d_int8_packed(dims, layout, cb, x_packed, w_packed, out, tile=-1, split
     d = _desc(*dims)
     _check(load().conv2d_int8_packed(ctypes.byref(d), layout, cb, _ptr(x_packed), _ptr(w_packed),
                                      _ptr(out), tile, split_k, _stream(stream)), "conv2d_int8_packed")
+    return out
+
+
+def conv2d_int8_packed_nhwc(dims, layout, cb, x_packed, w_packed, out, tile=-1, split_k=0, stream=None):
+    """GEMM stage writing int32 [N][P][Q][K]."""
+    d = _desc(*dims)
+    _check(load().conv2d_int8_packed_nhwc(ctypes.byref(d), layout, cb, _ptr(x_packed), _ptr(w_packed),
+                                          _ptr(out), tile, split_k, _stream(stream)), "conv2d_int8_packed_nhwc")
     return out
 
 

@@ -627,6 +627,21 @@ int conv2d_int8_packed(const conv_desc_t *desc, int layout, int cb, const int8_t
                     (hipStream_t)stream);
 }
 
+int conv2d_int8_packed_nhwc(const conv_desc_t *desc, int layout, int cb, const int8_t *in_packed,
+                            const int8_t *wt_packed, int32_t *out_nhwc, int tile, int split_k, void *stream)
+{
+    if (layout == CONV_LAYOUT_AUTO) return CONV_ERR_INVALID_ARG;
+    Plan pl;
+    int rc = make_plan(desc, layout, cb, &pl);
+    if (rc != CONV_OK) return rc;
+    if (pl.layout == CONV_LAYOUT_IMPLICIT) return CONV_ERR_UNSUPPORTED;  // those kernels write NKPQ
+    if (!in_packed || !wt_packed || !out_nhwc || !aligned16(in_packed) || !aligned16(wt_packed) || !aligned16(out_nhwc))
+        return CONV_ERR_INVALID_ARG;
+    GemmProblem g = gemm_problem(desc, pl, in_packed, wt_packed, out_nhwc);
+    g.out_nhwc = 1;
+    return run_gemm(g, tile, split_k, (hipStream_t)stream);
+}
+
 int conv2d_int8_packed_requant(const conv_desc_t *desc, int layout, int cb, const int8_t *in_packed,
                                const int8_t *wt_packed, int8_t *out_blocked, int out_cb, int out_pad, int shift, int relu,
                                void *stream)

@@ -822,3 +822,16 @@ def test_implicit_kernels_with_fused_activation(lib, cfg):
         lib.conv2d_int8_packed_requant(cfg.dims(), lib.LAYOUT_IMPLICIT, 0, dev(x), wp, out_cb, out_pad, shift, relu, out=out)
         got = host(out)
         assert np.array_equal(got, want), f"-> cb {out_cb} pad {out_pad} shift {shift}: {np.count_nonzero(got != want)} mismatches"
+
+
+@pytest.mark.parametrize("cfg", [CONFIGS["C2"], CONFIGS["C4a"], ConvShape("pn-ragged", 2, 20, 9, 11, 37, 3, 2, 1, 1)], ids=lambda c: c.name)
+def test_gemm_stage_with_nhwc_result(lib, cfg):
+    x = uniform_int8(971, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(972, (cfg.K, cfg.C, cfg.R, cfg.S))
+    want = layouts.unpack_nhwc(direct.conv2d_int8(x, w, cfg.stride, cfg.pad))
+    for layout, cb in ((lib.LAYOUT_PACKED, 64), (lib.LAYOUT_IM2COL, 0)):
+        xp = lib.im2col_int8(dev(x), cfg.R, cfg.S, cfg.stride, cfg.pad) if layout == lib.LAYOUT_IM2COL else lib.pack_layout(dev(x), cb, cfg.pad)
+        wp = lib.pack_weights(dev(w), layout, cb)
+        for split in (0, 2):
+            out = torch.full(want.shape, -3, dtype=torch.int32, device=DEV)
+            lib.conv2d_int8_packed_nhwc(cfg.dims(), layout, cb, xp, wp, out, split_k=split)
+            assert np.array_equal(host(out), want), f"{lib.LAYOUT_NAMES[layout]} split {split}"
