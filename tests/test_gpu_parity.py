@@ -361,6 +361,53 @@ def test_batch_scaled_implicit_sampled_images(lib):
         del x, out
 
 
+def test_batch_scaled_newer_entries_sampled_images(lib):
+    """The other batch-scaled lines of the benchmark, at its sizes: C4b at N=8192 (the 1x1 kernel's batch form),
+    the three epilogues of the GEMM stage on C4a at N=2048, Image Pack of the C3 stem at N=4096, and the dilated
+    3x3 layer at N=4096 by its three routes; whole planes of sampled images against the definitions."""
+    g = torch.Generator(device=DEV); g.manual_seed(4245)
+    cfg = CONFIGS["C4b"].scaled(8192)
+    x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=DEV, generator=g)
+    w = torch.randint(-128, 128, (cfg.K, cfg.C, cfg.R, cfg.S), dtype=torch.int8, device=DEV, generator=g)
+    out = torch.empty((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=DEV)
+    lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_IMPLICIT, 0, x, w, out, None)
+    for n in _sample_images(cfg.N):
+        assert np.array_equal(host(out[n:n + 1]), direct.conv2d_int8(host(x[n:n + 1]), host(w), 1, 0)), ("C4b", n)
+    del x, out
+
+    cfg = CONFIGS["C4a"].scaled(2048)
+    x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=DEV, generator=g)
+    w = torch.randint(-128, 128, (cfg.K, cfg.C, cfg.R, cfg.S), dtype=torch.int8, device=DEV, generator=g)
+    xp = lib.pack_layout(x, 64, cfg.pad); wp = lib.pack_weights(w, lib.LAYOUT_PACKED, 64)
+    onh = torch.empty((cfg.N, cfg.P, cfg.Q, cfg.K), dtype=torch.int32, device=DEV)
+    lib.conv2d_int8_packed_nhwc(cfg.dims(), lib.LAYOUT_PACKED, 64, xp, wp, onh)
+    xact = lib.conv2d_int8_packed_requant(cfg.dims(), lib.LAYOUT_PACKED, 64, xp, wp, 64, 0, 9, True)
+    for n in _sample_images(cfg.N):
+        conv = direct.conv2d_int8(host(x[n:n + 1]), host(w), cfg.stride, cfg.pad)
+        assert np.array_equal(host(onh[n:n + 1]), layouts.unpack_nhwc(conv)), ("nhwc", n)
+        assert np.array_equal(host(xact[n:n + 1]), layouts.pack_layout(layouts.requant(conv, 9, True), 64, 0)), ("act", n)
+    del x, xp, onh, xact
+
+    cfg = CONFIGS["C3"].scaled(4096)
+    x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=DEV, generator=g)
+    x2 = lib.image_pack_int8(cfg.dims(), x)
+    for n in _sample_images(cfg.N):
+        assert np.array_equal(host(x2[n:n + 1]), layouts.image_pack(host(x[n:n + 1]), cfg.R, cfg.S, cfg.stride, cfg.pad)), ("ip", n)
+    del x, x2
+
+    dims, d = (4096, 64, 28, 28, 64, 3, 3, 1, 2), 2
+    x = torch.randint(-128, 128, dims[:4], dtype=torch.int8, device=DEV, generator=g)
+    w = torch.randint(-128, 128, (64, 64, 3, 3), dtype=torch.int8, device=DEV, generator=g)
+    packed = lib.conv2d_int8_dilated(dims, d, x, w)
+    direct_route = lib.conv2d_int8_dilated_direct(dims, d, x, w, 64)
+    x2 = lib.dilation_pack_int8(dims, d, x)
+    for n in _sample_images(dims[0]):
+        want = direct.conv2d_int8_dilated(host(x[n:n + 1]), host(w), 1, 2, d)
+        assert np.array_equal(host(packed[n:n + 1]), want), ("image pack route", n)
+        assert np.array_equal(host(direct_route[n:n + 1]), want), ("address multiplier", n)
+        assert np.array_equal(host(x2[4 * n:4 * n + 4]), layouts.dilation_pack(host(x[n:n + 1]), 2, d)), ("dilation pack", n)
+
+
 # ---- the one-shot path called repeatedly and under graph replay ------------------------------------
 def test_one_shot_back_to_back_and_mixed_shapes(lib):
     """Consecutive one-shot calls share the library's cached workspace: alternate shapes and layouts,
