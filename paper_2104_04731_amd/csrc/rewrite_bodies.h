@@ -110,21 +110,33 @@ __device__ __forceinline__ void pack_layout_wave_body(const PackWaveArgs &a, lon
         const int p = lane & 3, chq = lane >> 2;
         const bool whole = s0 + 64 <= HW;  // uniform
         v4i v[4];
+        // The loads of a lane are issued back to back, none under a per-lane condition (a load under a
+        // condition makes the compiler wait for it before the next one): channels past C and, in the
+        // last chunk of a plane, dwords past the plane are read from a clamped address and zeroed after.
+        if (whole) {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int ch = chq + 16 * k;
-            v[k] = v4i{0, 0, 0, 0};
-            if (c0 + ch < C) {
-                const int8_t *q = plane0 + (long long)ch * HW + 16 * p;
-                if (whole) {
-                    v[k] = *reinterpret_cast<const v4i_a4 *>(q);
-                } else {  // last chunk of a plane: dword by dword, guarded
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (s0 + 16 * p + 4 * e + 4 <= HW) v[k][e] = *reinterpret_cast<const int *>(q + 4 * e);
-                }
+            for (int k = 0; k < 4; ++k) {
+                const int ch = min(chq + 16 * k, C - 1 - c0);
+                v[k] = *reinterpret_cast<const v4i_a4 *>(plane0 + (long long)ch * HW + 16 * p);
             }
+        } else {
+            const int last = HW - s0 - 4;   // >= 0: a chunk holds at least one dword of the plane
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int ch = min(chq + 16 * k, C - 1 - c0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    v[k][e] = *reinterpret_cast<const int *>(plane0 + (long long)ch * HW + min(16 * p + 4 * e, last));
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (16 * p + 4 * e > last) v[k][e] = 0;
         }
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (c0 + chq + 16 * k >= C) v[k] = v4i{0, 0, 0, 0};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             unsigned *row = tile + (chq + 16 * k) * PW_PITCH + 4 * p;
