@@ -30,15 +30,20 @@ def stale() -> bool:
 
 
 def build_library(verbose: bool = False) -> str:
-    objs = []
-    for s in SOURCES:
+    from concurrent.futures import ThreadPoolExecutor
+
+    def compile_one(s):
         src = os.path.join(CSRC, s)
         obj = os.path.join(CSRC, os.path.splitext(s)[0] + ".o")
         cmd = ["hipcc", *HIPCC_FLAGS, "-x", "hip", "-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)
-        objs.append(obj)
+        return obj
+
+    # the translation units are independent: compile them side by side (the GEMM kernel's file dominates)
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1, 8)) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     if verbose:
         print(" ".join(cmd), flush=True)
