@@ -239,18 +239,19 @@ __device__ __forceinline__ void pack_weights_blocked_body(const WeightArgs &a, i
     const int g16 = cb / 16, RS = a.R * a.S;
     for (int t = vbid * nthreads + (int)threadIdx.x; t < total; t += vgrid * nthreads) {
         const int k = fast_div_any(t, chunks, a.m_chunks), ch = t - k * chunks;
+        // sixteen loads issued back to back, none under a condition: a piece past the real depth and the
+        // channels past C read a clamped address and are zeroed afterwards
         int v[16];
+        const int chr = min(ch, nreal - 1);
+        const int tap = fast_div_any(chr, g16, a.m_g16), sub = chr - tap * g16;
+        const int b = fast_div_any(tap, RS, a.m_RS), rs = tap - b * RS;
+        const int c0 = b * cb + sub * 16;
+        const int8_t *s = src + (long long)k * C * RS + rs;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) v[i] = 0;
-        if (ch < nreal) {
-            const int tap = fast_div_any(ch, g16, a.m_g16), sub = ch - tap * g16;
-            const int b = fast_div_any(tap, RS, a.m_RS), rs = tap - b * RS;
-            const int c0 = b * cb + sub * 16;
-            const int8_t *s = src + ((long long)k * C + c0) * RS + rs;
+        for (int i = 0; i < 16; ++i) v[i] = s[(long long)min(c0 + i, C - 1) * RS];
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-                if (c0 + i < C) v[i] = s[i * RS];
-        }
+        for (int i = 0; i < 16; ++i)
+            if (ch >= nreal || c0 + i >= C) v[i] = 0;
         v4i o;
         o[0] = pack4(v[0], v[1], v[2], v[3]);
         o[1] = pack4(v[4], v[5], v[6], v[7]);
