@@ -209,3 +209,30 @@ def dilation_unpack(o2: np.ndarray, dilation: int, P: int, Q: int) -> np.ndarray
                 sub = out[n, :, a::d, b::d]
                 sub[...] = o2[(n * d + a) * d + b][:, :sub.shape[1], :sub.shape[2]]
     return out
+
+
+def im2col_nhwc(xh: np.ndarray, R: int, S: int, stride: int, pad: int, kalign: int = 64) -> np.ndarray:
+    """Stencil Unroll + Fuse from an NHWC source (Sec. 5.2: the source layout decides what a rewrite costs):
+    [N,H,W,C] -> [N*P*Q, depth]; A[(n,p,q)][(r*S + s)*C + c] = x0[n][p*st+r-pad][q*st+s-pad][c] -- the
+    channels of a tap stay contiguous, so every tap is one run of C source bytes."""
+    N, H, W, C = xh.shape
+    P = (H + 2 * pad - R) // stride + 1
+    Q = (W + 2 * pad - S) // stride + 1
+    x0 = np.zeros((N, H + 2 * pad, W + 2 * pad, C), dtype=xh.dtype)
+    x0[:, pad:pad + H, pad:pad + W, :] = xh
+    A = np.zeros((N, P, Q, ceil_to(C * R * S, kalign)), dtype=xh.dtype)
+    for r in range(R):
+        for s in range(S):
+            A[:, :, :, (r * S + s) * C:(r * S + s + 1) * C] = \
+                x0[:, r:r + stride * (P - 1) + 1:stride, s:s + stride * (Q - 1) + 1:stride, :]
+    return A.reshape(N * P * Q, -1)
+
+
+def pack_weights_rsc(w: np.ndarray, kalign: int = 64) -> np.ndarray:
+    """[K,C,R,S] -> [K][depth], depth index (r*S + s)*C + c (the order im2col_nhwc unrolls in), zero-padded."""
+    K, C, R, S = w.shape
+    y = np.zeros((K, ceil_to(C * R * S, kalign)), dtype=w.dtype)
+    for r in range(R):
+        for s in range(S):
+            y[:, (r * S + s) * C:(r * S + s + 1) * C] = w[:, :, r, s]
+    return y

@@ -262,3 +262,44 @@ def test_dilation_unpack_element_by_element():
     out = layouts.dilation_unpack(o2, d, P, Q)
     for n, k, p, q in itertools.product(range(N), range(K), range(P), range(Q)):
         assert out[n, k, p, q] == o2[(n * d + p % d) * d + q % d, k, p // d, q // d]
+
+
+# ---- stencil unrolling from an NHWC source (Sec. 5.2) --------------------------------------------------------
+@pytest.mark.parametrize("dims", [(2, 3, 6, 7, 4, 3, 2, 2, 1), (1, 16, 9, 9, 5, 3, 3, 1, 1), (1, 5, 8, 6, 3, 1, 1, 2, 0),
+                                  (2, 20, 5, 11, 7, 5, 3, 1, 2), (1, 64, 7, 7, 8, 3, 3, 1, 1)], ids=str)
+def test_im2col_nhwc_then_gemm_is_the_convolution(dims):
+    N, C, H, W, K, R, S, st, pad = dims
+    x = uniform_int8(81, (N, C, H, W)); w = uniform_int8(82, (K, C, R, S))
+    xh = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+    A = layouts.im2col_nhwc(xh, R, S, st, pad)
+    B = layouts.pack_weights_rsc(w)
+    want = direct.conv2d_int8(x, w, st, pad)
+    P, Q = want.shape[2], want.shape[3]
+    assert A.shape == (N * P * Q, -(-C * R * S // 64) * 64) and B.shape == (K, A.shape[1])
+    got = layouts.gemm_nt(B, A).reshape(K, N, P, Q).transpose(1, 0, 2, 3)
+    np.testing.assert_array_equal(got, want)
+
+
+def test_im2col_nhwc_elementwise_small_and_against_the_nchw_form():
+    N, C, H, W, R, S, st, pad = 2, 3, 6, 7, 3, 2, 2, 1
+    x = uniform_int8(83, (N, C, H, W)); xl = x.tolist()
+    xh = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+    A = layouts.im2col_nhwc(xh, R, S, st, pad)
+    P = (H + 2 * pad - R) // st + 1; Q = (W + 2 * pad - S) // st + 1
+    for n, p, q, c, r, s in itertools.product(range(N), range(P), range(Q), range(C), range(R), range(S)):
+        h, ww = p * st + r - pad, q * st + s - pad
+        want = xl[n][c][h][ww] if (0 <= h < H and 0 <= ww < W) else 0
+        assert A[(n * P + p) * Q + q, (r * S + s) * C + c] == want
+    assert not A[:, C * R * S:].any()
+    # the same matrix as the NCHW form, with its depth columns permuted (c, r, s) -> (r, s, c)
+    A0 = layouts.im2col(x, R, S, st, pad)
+    perm = [(c * R + r) * S + s for r in range(R) for s in range(S) for c in range(C)]
+    np.testing.assert_array_equal(A[:, :C * R * S], A0[:, perm])
+
+
+def test_pack_weights_rsc_is_a_permutation_of_the_kernel():
+    w = np.arange(1, 2 * 3 * 2 * 4 + 1, dtype=np.int64).reshape(2, 3, 2, 4)
+    y = layouts.pack_weights_rsc(w)
+    assert y.shape == (2, 64) and not y[:, 24:].any()
+    for k, c, r, s in itertools.product(range(2), range(3), range(2), range(4)):
+        assert y[k, (r * 4 + s) * 3 + c] == w[k, c, r, s]
