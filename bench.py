@@ -383,6 +383,19 @@ def n_scaled(lib, timed, CONFIGS, dev):
                     "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2),
                     "tops": round(cfg.ops / (ms * 1e-3) / 1e12, 2)}
         del x, w, o
+    # stencil unrolling of the 64-channel 3x3 layer from both source layouts (Sec. 5.2): from NHWC a tap's
+    # channels are one contiguous run
+    cfg = CONFIGS["C2"].scaled(512)
+    x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=dev)
+    xh = x.permute(0, 2, 3, 1).contiguous()
+    a1 = lib.im2col_int8(x, cfg.R, cfg.S, cfg.stride, cfg.pad)
+    for key, fn in (("im2col_C2_N512", lambda: lib.im2col_int8(x, cfg.R, cfg.S, cfg.stride, cfg.pad, out=a1)),
+                    ("im2col_nhwc_C2_N512", lambda: lib.im2col_nhwc_int8(xh, cfg.R, cfg.S, cfg.stride, cfg.pad, out=a1))):
+        _, ms = timed(fn, 10, 2)
+        b = x.numel() + a1.numel()
+        out[key] = {"us": round(ms * 1e3, 2), "bytes": b, "GBps": round(b / (ms * 1e-3) / 1e9, 1),
+                    "pct_hbm_peak": round(100 * b / (ms * 1e-3) / PEAK_HBM_BPS, 2)}
+    del x, xh, a1
     # Image Pack of the same stem (stride phases to channels): bytes = input + packed image
     cfg = CONFIGS["C3"].scaled(4096)
     x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=dev)

@@ -158,6 +158,17 @@ int requant_int8(long long count, const int32_t *src, int8_t *dst, int shift, in
 int requant_pack_layout(int N, int K, int P, int Q, int cb, int pad, int shift, int relu,
                         const int32_t *src, int8_t *dst, void *stream);
 
+/* Stencil Unroll + Fuse from an NHWC source (Sec. 5.2): src int8 [N][H][W][C] -> dst [N*P*Q][kg_pad] with depth
+ * index (r*S + s)*C + c -- a tap's channels stay contiguous, so with C % 16 == 0 every destination 16-byte piece
+ * is one load (src must then be 16-byte aligned); kg_pad >= C*R*S, a multiple of 16; dst 16-byte aligned, of
+ * im2col_bytes(...) bytes.  pack_weights_rsc writes the weights in the same depth order:
+ * dst[k][(r*S + s)*C + c] = wt[k][c][r][s], rows zero-padded to ceil(C*R*S, 64) bytes (the size pack_weights_bytes
+ * gives for IM2COL).  The pair feeds the GEMM stage as an IM2COL operand (conv2d_int8_packed, _packed_nhwc,
+ * _packed_requant with layout IM2COL and kg_pad = ceil(C*R*S, 64)). */
+int im2col_nhwc_int8(int N, int C, int H, int W, int R, int S, int stride, int pad, int kg_pad,
+                     const int8_t *src, int8_t *dst, void *stream);
+int pack_weights_rsc(int K, int C, int R, int S, const int8_t *src, int8_t *dst, void *stream);
+
 /* The GEMM stage with an NHWC result (Sec. 5.2): as conv2d_int8_packed, but out_nhwc is int32 [N][P][Q][K],
  * written by the epilogue itself (a lane of the MFMA result holds four consecutive channels of a pixel:
  * 16-byte stores when K % 4 == 0).  PACKED, PAD_ONLY or IM2COL (IMPLICIT: CONV_ERR_UNSUPPORTED); all three

@@ -24,7 +24,7 @@ EXPORTS = [
     "conv2d_int8_tile_applies", "pack_layout", "pack_layout_bytes", "pack_layout_nhwc",
     "pack_weights", "pack_weights_depth", "pack_weights_bytes", "im2col_int8", "im2col_bytes",
     "image_pack_desc", "image_pack_bytes", "image_pack_weights_bytes", "image_pack_int8", "image_pack_weights",
-    "conv2d_int8_packed_requant", "conv2d_int8_packed_nhwc", "mfma_probe_int8",
+    "conv2d_int8_packed_requant", "conv2d_int8_packed_nhwc", "mfma_probe_int8", "im2col_nhwc_int8", "pack_weights_rsc",
     "dilated_desc", "dilation_pack_bytes", "dilation_pack_int8", "dilation_unpack_int32",
     "conv2d_int8_dilated_workspace_bytes", "conv2d_int8_dilated",
     "conv2d_int8_dilated_direct_workspace_bytes", "conv2d_int8_dilated_direct",
@@ -79,6 +79,8 @@ def load(path: str | None = None):
         "pack_weights_bytes": (sz, [i] * 6),
         "im2col_int8": (i, [i] * 9 + [vp, vp, vp]),
         "im2col_bytes": (sz, [i] * 9),
+        "im2col_nhwc_int8": (i, [i] * 9 + [vp, vp, vp]),
+        "pack_weights_rsc": (i, [i] * 4 + [vp, vp, vp]),
         "image_pack_desc": (i, [dp, dp]),
         "image_pack_bytes": (sz, [dp]),
         "image_pack_weights_bytes": (sz, [dp]),
@@ -321,6 +323,30 @@ def im2col_int8(x: torch.Tensor, R, S, stride, pad, kg_pad=None, out=None, strea
         out = torch.empty((N * max(P, 0) * max(Q, 0), kg_pad), dtype=torch.int8, device=x.device)
     _check(load().im2col_int8(N, C, H, W, R, S, stride, pad, kg_pad, _ptr(x), _ptr(out),
                               _stream(stream)), "im2col_int8")
+    return out
+
+
+def im2col_nhwc_int8(xh: torch.Tensor, R, S, stride, pad, kg_pad=None, out=None, stream=None):
+    """xh: [N, H, W, C] int8 -> [N*P*Q, kg_pad], depth index (r*S + s)*C + c."""
+    _require(xh, torch.int8, "input")
+    N, H, W, C = xh.shape
+    if kg_pad is None:
+        kg_pad = -(-C * R * S // 64) * 64
+    if out is None:
+        P, Q = out_hw(H, W, R, S, stride, pad)
+        out = torch.empty((N * max(P, 0) * max(Q, 0), kg_pad), dtype=torch.int8, device=xh.device)
+    _check(load().im2col_nhwc_int8(N, C, H, W, R, S, stride, pad, kg_pad, _ptr(xh), _ptr(out), _stream(stream)),
+           "im2col_nhwc_int8")
+    return out
+
+
+def pack_weights_rsc(w: torch.Tensor, out=None, stream=None):
+    """KCRS int8 -> [K, ceil(C*R*S, 64)] in the depth order of im2col_nhwc_int8."""
+    _require(w, torch.int8, "weights")
+    K, C, R, S = w.shape
+    if out is None:
+        out = torch.empty((K, -(-C * R * S // 64) * 64), dtype=torch.int8, device=w.device)
+    _check(load().pack_weights_rsc(K, C, R, S, _ptr(w), _ptr(out), _stream(stream)), "pack_weights_rsc")
     return out
 
 

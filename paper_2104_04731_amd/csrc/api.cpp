@@ -384,6 +384,29 @@ int im2col_int8(int N, int C, int H, int W, int R, int S, int stride, int pad, i
                    hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
 }
 
+int im2col_nhwc_int8(int N, int C, int H, int W, int R, int S, int stride, int pad, int kg_pad,
+                     const int8_t *src, int8_t *dst, void *stream)
+{
+    conv_desc_t d{N, C, H, W, 1, R, S, stride, pad};
+    int rc = check_desc(&d);
+    if (rc != CONV_OK) return rc;
+    if (!src || !dst || !aligned16(dst)) return CONV_ERR_INVALID_ARG;
+    if (C % 16 == 0 && !aligned16(src)) return CONV_ERR_INVALID_ARG;  // 16-byte loads of a tap's channels
+    if (kg_pad < C * R * S || kg_pad % 16) return CONV_ERR_INVALID_ARG;
+    const int P = (H + 2 * pad - R) / stride + 1, Q = (W + 2 * pad - S) / stride + 1;
+    return launch_im2col_nhwc(N, C, H, W, R, S, stride, pad, P, Q, kg_pad, src, dst, (hipStream_t)stream) == hipSuccess
+               ? CONV_OK : CONV_ERR_DEVICE;
+}
+
+int pack_weights_rsc(int K, int C, int R, int S, const int8_t *src, int8_t *dst, void *stream)
+{
+    if (K <= 0 || C <= 0 || R <= 0 || S <= 0 || !src || !dst) return CONV_ERR_INVALID_ARG;
+    if ((long long)C * R * S > 131072LL) return CONV_ERR_OVERFLOW_RISK;
+    const int depth = round_up_i(C * R * S, CONV_DEPTH_ALIGN);
+    return launch_pack_weights_rsc(K, C, R, S, depth, src, dst, (hipStream_t)stream) == hipSuccess ? CONV_OK
+                                                                                                  : CONV_ERR_DEVICE;
+}
+
 int image_pack_desc(const conv_desc_t *desc, conv_desc_t *packed)
 {
     if (!packed) return CONV_ERR_INVALID_ARG;

@@ -291,3 +291,17 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
     assert r.returncode != 0 and "one GPU only" in r.stderr and r.stdout.strip() == ""
+
+
+def test_im2col_nhwc_validation(lib):
+    raw = lib.load()
+    p = ctypes.c_void_p(256)
+    assert raw.im2col_nhwc_int8(1, 3, 8, 8, 3, 3, 1, 1, 64, None, p, None) == lib.ERR_INVALID_ARG
+    assert raw.im2col_nhwc_int8(1, 3, 8, 8, 3, 3, 1, 1, 64, p, ctypes.c_void_p(260), None) == lib.ERR_INVALID_ARG
+    assert raw.im2col_nhwc_int8(1, 16, 8, 8, 3, 3, 1, 1, 192, ctypes.c_void_p(260), p, None) == lib.ERR_INVALID_ARG  # 16-byte loads
+    assert raw.im2col_nhwc_int8(1, 3, 8, 8, 3, 3, 1, 1, 16, p, p, None) == lib.ERR_INVALID_ARG   # kg_pad < 27
+    assert raw.im2col_nhwc_int8(1, 3, 8, 8, 3, 3, 1, 1, 40, p, p, None) == lib.ERR_INVALID_ARG   # not a multiple of 16
+    assert raw.im2col_nhwc_int8(1, 3, 2, 2, 5, 5, 1, 0, 128, p, p, None) == lib.ERR_INVALID_ARG  # kernel larger than the image
+    assert raw.pack_weights_rsc(0, 3, 3, 3, p, p, None) == lib.ERR_INVALID_ARG
+    assert raw.pack_weights_rsc(4, 3, 3, 3, None, p, None) == lib.ERR_INVALID_ARG
+    assert raw.pack_weights_rsc(4, 65536, 3, 3, p, p, None) == lib.ERR_OVERFLOW_RISK

@@ -882,3 +882,23 @@ def test_gemm_stage_with_nhwc_result(lib, cfg):
             out = torch.full(want.shape, -3, dtype=torch.int32, device=DEV)
             lib.conv2d_int8_packed_nhwc(cfg.dims(), layout, cb, xp, wp, out, split_k=split)
             assert np.array_equal(host(out), want), f"{lib.LAYOUT_NAMES[layout]} split {split}"
+
+
+# ---- stencil unrolling from an NHWC source ---------------------------------------------------------------------
+@pytest.mark.parametrize("cfg", [CONFIGS["C1"], CONFIGS["C2"], CONFIGS["C3"], CONFIGS["C4a"],
+                                 ConvShape("in-ragged", 2, 37, 9, 11, 21, 3, 2, 2, 1), ConvShape("in-1ch", 1, 1, 20, 33, 8, 5, 4, 1, 2),
+                                 ConvShape("in-48", 2, 48, 7, 6, 9, 3, 3, 1, 1)], ids=lambda c: c.name)
+def test_im2col_from_nhwc(lib, cfg):
+    x = uniform_int8(981, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(982, (cfg.K, cfg.C, cfg.R, cfg.S))
+    xh = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+    A = lib.im2col_nhwc_int8(dev(xh), cfg.R, cfg.S, cfg.stride, cfg.pad)
+    B = lib.pack_weights_rsc(dev(w))
+    np.testing.assert_array_equal(host(A), layouts.im2col_nhwc(xh, cfg.R, cfg.S, cfg.stride, cfg.pad))
+    np.testing.assert_array_equal(host(B), layouts.pack_weights_rsc(w))
+    conv = direct.conv2d_int8(x, w, cfg.stride, cfg.pad)
+    out = torch.empty((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=DEV)
+    lib.conv2d_int8_packed(cfg.dims(), lib.LAYOUT_IM2COL, 0, A, B, out)
+    assert np.array_equal(host(out), conv)
+    onh = torch.empty((cfg.N, cfg.P, cfg.Q, cfg.K), dtype=torch.int32, device=DEV)
+    lib.conv2d_int8_packed_nhwc(cfg.dims(), lib.LAYOUT_IM2COL, 0, A, B, onh)     # NHWC in, NHWC out
+    assert np.array_equal(host(onh), layouts.unpack_nhwc(conv))
