@@ -430,7 +430,8 @@ __device__ __forceinline__ void im2col_tiled_body(const I2cArgs &a, int bid, uns
     int8_t *out0 = dst + ((n * a.P + p) * (long long)a.Q + q0) * a.kg_pad + j_begin;
 
     if (a.use_recipe) {
-        // Every destination dword is at most two byte runs of the patch (S >= 4): a run inside
+        // Every destination dword is at most two byte runs of the patch (S >= 3: the first run gives
+        // n0 >= 1 bytes, the next kernel row the other 4 - n0 <= 3 <= S): a run inside
         // one kernel row, then the start of the next row or the zero tail.  The recipe -- where
         // each run starts and how many bytes the first one gives -- depends on the depth only,
         // so it is tabulated once; a pixel adds q*stride.  A run is fetched as two aligned
@@ -550,7 +551,7 @@ static bool plan_im2col_tiled(int N, int C, int H, int W, int R, int S, int stri
     const long long zsz = ((((long long)TQ - 1) * stride + 12) + 3) & ~3LL;
     const long long slice_depth = cslices == 1 ? kg_pad : (long long)Cc * R * S + 64;
     const long long with_recipe = ((patch_bytes + zsz + 7) & ~7LL) + 2 * slice_depth;
-    const bool recipe = S >= 4 && with_recipe <= 60 * 1024;
+    const bool recipe = S >= 3 && with_recipe <= 60 * 1024;
     I2cArgs a;
     a.src = src; a.dst = dst;
     a.C = C; a.H = H; a.W = W; a.R = R; a.S = S; a.stride = stride; a.pad = pad; a.P = P; a.Q = Q;
