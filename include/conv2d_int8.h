@@ -90,9 +90,9 @@ int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int
                 const int8_t *in, const int8_t *wt, int32_t *out, void *stream);
 
 /* The same for NHWC tensors (Sec. 5.2): in [N][H][W][C], wt KCRS, out [N][P][Q][K] int32.  Channel
- * blocking straight from the NHWC source (pack_layout_nhwc), the weight rewrite, and a GEMM stage whose
- * epilogue writes NHWC itself: three launches.  (An `out` that does not start on 16 bytes goes through an
- * NKPQ staging tensor in the cached workspace and unpack_nhwc_int32: four.)  Same workspace rules as conv2d_int8. */
+ * blocking straight from the NHWC source (pack_layout_nhwc) and the weight rewrite in one launch, then a
+ * GEMM stage whose epilogue writes NHWC itself: two launches.  (An `out` that does not start on 16 bytes goes
+ * through an NKPQ staging tensor in the cached workspace and unpack_nhwc_int32: three.)  Same workspace rules as conv2d_int8. */
 int conv2d_int8_nhwc(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                      const int8_t *in, const int8_t *wt, int32_t *out, void *stream);
 

@@ -878,9 +878,12 @@ int conv2d_int8_nhwc(int N, int C, int H, int W, int K, int R, int S, int stride
     hipStream_t st = (hipStream_t)stream;
     int8_t *xq = static_cast<int8_t *>(c.ptr), *wq = xq + xb;
     int32_t *nkpq = reinterpret_cast<int32_t *>(wq + wb);
-    if (launch_pack_layout_nhwc(N, C, H, W, pl.cb, pad, in, xq, st) != hipSuccess) return CONV_ERR_DEVICE;
-    rc = rewrite_weights(&d, pl, wt, wq, st);
-    if (rc != CONV_OK) return rc;
+    const hipError_t e = launch_rewrite_fused_nhwc(N, C, H, W, K, R, S, pad, pl.cb, pl.depth, in, xq, wt, wq, st);
+    if (e == hipErrorNotSupported) {
+        if (launch_pack_layout_nhwc(N, C, H, W, pl.cb, pad, in, xq, st) != hipSuccess) return CONV_ERR_DEVICE;
+        rc = rewrite_weights(&d, pl, wt, wq, st);
+        if (rc != CONV_OK) return rc;
+    } else if (e != hipSuccess) return CONV_ERR_DEVICE;
     if (direct) {
         GemmProblem g = gemm_problem(&d, pl, xq, wq, out);
         g.out_nhwc = 1;

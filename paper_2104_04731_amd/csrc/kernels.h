@@ -56,6 +56,8 @@ hipError_t launch_pack_layout(int N, int C, int H, int W, int cb, int pad,
                               const int8_t *src, int8_t *dst, hipStream_t st);
 hipError_t launch_pack_layout_nhwc(int N, int C, int H, int W, int cb, int pad,
                                    const int8_t *src, int8_t *dst, hipStream_t st);  // cb % 16 == 0
+hipError_t launch_rewrite_fused_nhwc(int N, int C, int H, int W, int K, int R, int S, int pad, int cb, int depth,
+                                     const int8_t *in, int8_t *xq, const int8_t *wt, int8_t *wq, hipStream_t st);
 hipError_t launch_im2col_nhwc(int N, int C, int H, int W, int R, int S, int stride, int pad, int P, int Q, int kg_pad,
                               const int8_t *src, int8_t *dst, hipStream_t st);  // src 16-byte aligned if C % 16 == 0
 hipError_t launch_pack_weights_rsc(int K, int C, int R, int S, int depth, const int8_t *src, int8_t *dst, hipStream_t st);

@@ -664,9 +664,10 @@ struct PackNhwcArgs {
     unsigned m_g16, m_Wp, m_Hp, m_Cb;
 };
 
-__global__ void __launch_bounds__(256) pack_layout_nhwc_kernel(const PackNhwcArgs a)
+// (virtual workgroup vbid of vgrid: the one-shot path runs this as one workgroup range of a shared grid)
+__device__ __forceinline__ void pack_layout_nhwc_body(const PackNhwcArgs &a, int vbid, int vgrid)
 {
-    for (long long t = (long long)blockIdx.x * 256 + threadIdx.x; t < a.total; t += (long long)gridDim.x * 256) {
+    for (long long t = (long long)vbid * 256 + threadIdx.x; t < a.total; t += (long long)vgrid * 256) {
         int c16, wp, hp, b;
         long long n;
         if (a.total < (1LL << 31)) {
@@ -699,8 +700,20 @@ __global__ void __launch_bounds__(256) pack_layout_nhwc_kernel(const PackNhwcArg
     }
 }
 
-hipError_t launch_pack_layout_nhwc(int N, int C, int H, int W, int cb, int pad, const int8_t *src, int8_t *dst,
-                                   hipStream_t st)
+__global__ void __launch_bounds__(256) pack_layout_nhwc_kernel(const PackNhwcArgs a)
+{
+    pack_layout_nhwc_body(a, blockIdx.x, gridDim.x);
+}
+
+// channel blocking from NHWC and the blocked weight rewrite as two workgroup ranges of one grid
+__global__ void __launch_bounds__(256) rewrite_fused_nhwc_kernel(const PackNhwcArgs a, const WeightArgs w, int in_blocks,
+                                                                 int w_blocks)
+{
+    if ((int)blockIdx.x < in_blocks) pack_layout_nhwc_body(a, blockIdx.x, in_blocks);
+    else pack_weights_blocked_body(w, blockIdx.x - in_blocks, w_blocks, 256);
+}
+
+static PackNhwcArgs pack_nhwc_args(int N, int C, int H, int W, int cb, int pad, const int8_t *src, int8_t *dst)
 {
     PackNhwcArgs a{};
     a.src = src; a.dst = dst;
@@ -710,7 +723,28 @@ hipError_t launch_pack_layout_nhwc(int N, int C, int H, int W, int cb, int pad, 
     a.g16 = cb / 16;
     a.total = (long long)N * a.Cb * a.Hp * a.Wp * a.g16;
     a.m_g16 = magic_for(a.g16); a.m_Wp = magic_for(a.Wp); a.m_Hp = magic_for(a.Hp); a.m_Cb = magic_for(a.Cb);
+    return a;
+}
+
+hipError_t launch_pack_layout_nhwc(int N, int C, int H, int W, int cb, int pad, const int8_t *src, int8_t *dst,
+                                   hipStream_t st)
+{
+    const PackNhwcArgs a = pack_nhwc_args(N, C, H, W, cb, pad, src, dst);
     hipLaunchKernelGGL(pack_layout_nhwc_kernel, dim3(grid_for(a.total, 256)), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+// hipErrorNotSupported: more weight pieces than the blocked body indexes with 32 bits (the caller then
+// launches the two rewrites separately)
+hipError_t launch_rewrite_fused_nhwc(int N, int C, int H, int W, int K, int R, int S, int pad, int cb, int depth,
+                                     const int8_t *in, int8_t *xq, const int8_t *wt, int8_t *wq, hipStream_t st)
+{
+    const PackNhwcArgs a = pack_nhwc_args(N, C, H, W, cb, pad, in, xq);
+    const long long w_items = (long long)K * (depth / 16);
+    if (w_items >= (1LL << 31)) return hipErrorNotSupported;
+    const WeightArgs w = weight_args_blocked(K, C, R, S, cb, depth, wt, wq);
+    const int in_blocks = grid_for(a.total, 256), w_blocks = grid_for(w_items, 256);
+    hipLaunchKernelGGL(rewrite_fused_nhwc_kernel, dim3(in_blocks + w_blocks), dim3(256), 0, st, a, w, in_blocks, w_blocks);
     return hipGetLastError();
 }
 
