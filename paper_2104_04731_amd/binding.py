@@ -496,6 +496,16 @@ def select_layout(dims, w_mac=None, w_data=None):
     return lay.value, cb.value, sc.value
 
 
+def layout_applies(dims, layout, cb=0) -> bool:
+    """Whether the library has this layout for this problem (layout_overheads is the domain query)."""
+    d = _desc(*dims)
+    a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    st = load().layout_overheads(ctypes.byref(d), layout, cb, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    if st not in (OK, ERR_UNSUPPORTED):
+        raise ConvError(st, "layout_overheads")
+    return st == OK
+
+
 def layout_overheads(dims, layout, cb):
     d = _desc(*dims)
     a, b, c = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()

@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import direct, layouts, selection
+from oracle import direct, layouts
 from paper_2104_04731_amd.inputs import CONFIGS, PAPER_SHAPES, ConvShape, uniform_int8
 
 pytestmark = pytest.mark.gpu
@@ -466,7 +466,7 @@ def run_implicit(lib, cfg, x, w, rewritten, dx=None):
 def test_implicit_configs(lib, name):
     cfg = CONFIGS[name]
     x, w, want = oracle_conv(cfg)
-    if not selection.implicit_applies(*cfg.dims()):
+    if not lib.layout_applies(cfg.dims(), lib.LAYOUT_IMPLICIT):
         out = torch.zeros((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=DEV)
         with pytest.raises(lib.ConvError) as e:
             lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_IMPLICIT, 0, dev(x), dev(w), out, None)
@@ -496,7 +496,7 @@ IMPLICIT_SHAPES = [
 def test_implicit_shapes(lib, cfg):
     """All three tile shapes with ragged ends, strides, wide borders, image widths that are not a multiple
     of four, kernel rows of 1 to 9 taps, several output-channel blocks, both weight forms."""
-    assert selection.implicit_applies(*cfg.dims())
+    assert lib.layout_applies(cfg.dims(), lib.LAYOUT_IMPLICIT)
     x = uniform_int8(411, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(412, (cfg.K, cfg.C, cfg.R, cfg.S))
     want = direct.conv2d_int8(x, w, cfg.stride, cfg.pad)
     for rewritten in (False, True):
@@ -547,7 +547,7 @@ def test_image_pack(lib, cfg):
     for cb in (0, 16, 64):
         nbytes = lib.conv2d_int8_workspace_bytes(cfg.dims(), lib.LAYOUT_IMAGE_PACK, cb)
         out = torch.full((cfg.N, cfg.K, cfg.P, cfg.Q), -3, dtype=torch.int32, device=DEV)
-        if cb == 0 and not selection.implicit_applies(*d2):
+        if cb == 0 and not lib.layout_applies(d2, lib.LAYOUT_IMPLICIT):
             assert nbytes == 0
             with pytest.raises(lib.ConvError) as e:
                 lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_IMAGE_PACK, cb, dev(x), dev(w), out,
@@ -584,12 +584,12 @@ def _random_shapes(seed, count, want):
 
 
 def test_implicit_random_shapes(lib):
-    shapes = _random_shapes(9001, 60, lambda d: selection.implicit_applies(*d) and d[0] * d[4] * d[2] * d[3] < 400000)
+    shapes = _random_shapes(9001, 60, lambda d: lib.layout_applies(d, lib.LAYOUT_IMPLICIT) and d[0] * d[4] * d[2] * d[3] < 400000)
     rng = np.random.default_rng(9003)   # the 1x1 form has a narrow domain: drawn from inside it
     while len(shapes) < 75:
         dims = (int(rng.integers(1, 4)), 64 * int(rng.integers(1, 9)), int(rng.integers(1, 12)), int(rng.integers(1, 40)),
                 int(rng.choice([1, 31, 32, 100, 129, 260])), 1, 1, 1, 0)
-        if selection.implicit_applies(*dims):
+        if lib.layout_applies(dims, lib.LAYOUT_IMPLICIT):
             shapes.append(ConvShape(f"p{len(shapes)}", *dims))
     for cfg in shapes:
         x = uniform_int8(cfg.H * 131 + cfg.W, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(cfg.K * 17 + cfg.C, (cfg.K, cfg.C, cfg.R, cfg.S))
@@ -707,7 +707,7 @@ def test_dilated_convolution(lib, case):
     ran = 0
     for layout, cb in ((lib.LAYOUT_AUTO, 0), (lib.LAYOUT_PACKED, 16), (lib.LAYOUT_PACKED, 64), (lib.LAYOUT_IM2COL, 0),
                        (lib.LAYOUT_PAD_ONLY, 0), (lib.LAYOUT_IMPLICIT, 0)):
-        if layout == lib.LAYOUT_IMPLICIT and not selection.implicit_applies(*d2):
+        if layout == lib.LAYOUT_IMPLICIT and not lib.layout_applies(d2, lib.LAYOUT_IMPLICIT):
             assert lib.conv2d_int8_dilated_workspace_bytes(dims, d, layout, cb) == 0
             continue
         out = torch.full((N, K, P, Q), -3, dtype=torch.int32, device=DEV)
@@ -807,7 +807,7 @@ def test_pointwise_batch_form(lib, dims):
     """Batches large enough for the 1x1 kernel that owns up to 224 pixels of an image per workgroup:
     whole 14x14 images, several pixel ranges per image with a short last one, ragged output channels."""
     cfg = ConvShape("pw-batch", *dims)
-    assert selection.implicit_applies(*dims)
+    assert lib.layout_applies(dims, lib.LAYOUT_IMPLICIT)
     x = uniform_int8(951, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(952, (cfg.K, cfg.C, 1, 1))
     want = direct.conv2d_int8(x, w, 1, 0)
     for rewritten in (False, True):
@@ -859,7 +859,7 @@ def test_fused_activation_and_nhwc_random_shapes(lib):
                                  ConvShape("ia-batch", 300, 64, 14, 14, 40, 1, 1, 1, 0)], ids=lambda c: c.name)
 def test_implicit_kernels_with_fused_activation(lib, cfg):
     """The two kernels that read NCHW themselves, with the activation in their epilogue."""
-    assert selection.implicit_applies(*cfg.dims())
+    assert lib.layout_applies(cfg.dims(), lib.LAYOUT_IMPLICIT)
     x = uniform_int8(961, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(962, (cfg.K, cfg.C, cfg.R, cfg.S))
     conv = direct.conv2d_int8(x, w, cfg.stride, cfg.pad)
     wp = lib.pack_weights(dev(w), lib.LAYOUT_IMPLICIT, 0)
