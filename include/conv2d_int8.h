@@ -17,10 +17,9 @@
  *     invalid arguments).  Arguments are validated before anything is enqueued,
  *     so a non-zero status leaves all buffers untouched.  Nothing throws.
  *   - Calls on different host threads must use different streams AND, for the
- *     one-shot conv2d_int8, are serialised on the library's cached workspace:
- *     two conv2d_int8 calls on one device must not run concurrently (one stream,
- *     or streams ordered by events).  conv2d_int8 is also the one exception to
- *     "no host synchronisation": growing its workspace drains the device once.
+ *     one-shot conv2d_int8 / conv2d_int8_nhwc, are serialised on the library's cached
+ *     workspace: two such calls on one device must not run concurrently (one stream,
+ *     or streams ordered by events).
  *
  * Operation computed (Sec. 3 tensor expression / Fig. 5 step 1; access [n, i+k]
  * of Table 2 => cross-correlation; 8-bit operands, 32-bit accumulation, Sec. 5.1):
@@ -53,16 +52,13 @@ typedef enum {
     CONV_LAYOUT_IM2COL = 2,   /* Stencil Unroll + Fuse: [N*P*Q][depth], depth index (c,r,s) */
     CONV_LAYOUT_PAD_ONLY = 3, /* Pad only: one block cb = ceil(C,16), i.e. [N][H+2pad][W+2pad][cb] */
     CONV_LAYOUT_IMPLICIT = 4, /* Stencil Unroll + Fuse applied inside the GEMM stage: the input stays NCHW,
-                                 nothing rewritten is stored; depth index (c, r, s) with every kernel row
-                                 padded to S4 = ceil(S,4) taps.  Exists for the low-channel layers whose
-                                 unrolled matrix is many times the input (Sec. 6.2); applies when
-                                 ceil(C*R*S4, 64) <= 256, W >= 4 and the input window of one tile --
-                                 C*((PT-1)*stride + R) rows of ceil((QT-1)*stride + S4 + 3, 4) bytes, with
-                                 PT x QT = 1x128 output pixels if Q > 64, 2x64 if Q > 32, else 4x32 --
-                                 fits 40 KB.  1x1 kernels over C % 64 == 0 channels take a second form of
-                                 it (a workgroup turns its 32 pixels into depth-contiguous rows in LDS;
-                                 depth index c, weights as they are): stride 1, pad 0, C <= 512 and
-                                 H*W % 4 == 0.  Outside these domains: CONV_ERR_UNSUPPORTED. */
+                                 nothing rewritten is stored.  Exists for the low-channel layers whose
+                                 unrolled matrix is many times the input (Sec. 6.2), and for 1x1 kernels,
+                                 whose weights need no rewrite at all.  Which problems it takes is a
+                                 property of the kernels behind it, not of this interface: ask
+                                 layout_overheads(desc, CONV_LAYOUT_IMPLICIT, 0, ...), which returns
+                                 CONV_ERR_UNSUPPORTED outside the domain, exactly where every other entry
+                                 point does.  Weight order of pack_weights for it: see pack_weights. */
     CONV_LAYOUT_IMAGE_PACK = 5 /* Image Pack (Table 2 row 1, for strides s > 1): the s*s stride phases of the
                                  zero-padded image become channels, the kernel is split the same way, and the
                                  convolution becomes the stride-1, pad-0 problem of image_pack_desc, which
@@ -82,10 +78,15 @@ typedef struct {
 #define CONV_DEPTH_ALIGN 64 /* fused reduction depth is zero-padded to this (one MFMA k-step, bytes) */
 
 /* ---- one-shot convolution (layout rewrite of input and weights + GEMM stage) ---------
- * Picks the layout with select_layout, uses a workspace the library caches per device
- * (grown with hipMalloc when a larger problem arrives, never shrunk: make the first call for
- * a problem size outside stream capture).  Two launches: both rewrites, then the GEMM stage;
- * one launch and no workspace when the choice is IMPLICIT. */
+ * Picks the layout with select_layout, uses a workspace the library caches per device.
+ * Workspace rule: when a problem needs more than the cached block, a larger block is allocated
+ * (hipMalloc, no synchronisation) and the superseded block is kept allocated until the process
+ * ends, so work already enqueued and HIP graphs captured earlier stay valid.  Allocation is
+ * impossible while `stream` is being captured: a call that would have to grow the block then
+ * returns CONV_ERR_WORKSPACE with nothing enqueued -- make the first call for a problem size
+ * outside capture (or use conv2d_int8_ex with a workspace of your own).
+ * Two launches: both rewrites, then the GEMM stage; one launch and no workspace when the choice
+ * is IMPLICIT. */
 int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                 const int8_t *in, const int8_t *wt, int32_t *out, void *stream);
 
@@ -131,6 +132,10 @@ int conv2d_int8_tile_info(int tile, int *rows, int *cols, int *threads, int *ste
 /* Would conv2d_int8_packed accept this forced tile (>= 0) and split_k (>= 1) for this
  * problem?  CONV_OK or CONV_ERR_UNSUPPORTED (host only). */
 int conv2d_int8_tile_applies(const conv_desc_t *desc, int layout, int cb, int tile, int split_k);
+/* LDS bytes per workgroup that this tile and split would ask for on this problem (operand ring plus, for
+ * the blocked layouts, one offset per 16-byte depth chunk of a slice); 0 where the pair does not apply.
+ * Never above 160 KB, one compute unit's LDS (host only). */
+size_t conv2d_int8_tile_lds_bytes(const conv_desc_t *desc, int layout, int cb, int tile, int split_k);
 
 /* ---- layout rewrites, individually callable (the "Transf." column of Table 3) ---------
  * pack_layout (Table 2 rows 2-4 on the input, plus the convolution's zero border):
@@ -280,9 +285,8 @@ int gemm_int8_nt(int X, int Y, int Z, const int8_t *A, const int8_t *B, int32_t 
  * padding every mapped dimension to the intrinsic minus the MACs of the definition),
  * O_Data = elements moved by rewrites and GEMM stage minus |in| + |wt| + |out|.
  * Candidates: PACKED with cb in {64,32,16}, IM2COL, PAD_ONLY, and IMPLICIT where it applies
- * (no rewritten elements, O_Data = 0; MAC_total = N*P*ceil(Q,32) * ceil(K,32) * ceil(C*R*S4,64):
- * pixels are padded per output row, kernel rows to S4; in its 1x1 form
- * MAC_total = N*ceil(P*Q,32) * ceil(K,32) * C), and for strides above one IMAGE_PACK with inner
+ * (no rewritten elements, O_Data = 0; MAC_total = the MACs its kernels issue for the problem, as
+ * layout_overheads reports them), and for strides above one IMAGE_PACK with inner
  * cb in {0,16,32,64} (the inner layout's terms on the packed problem, measured against the MACs
  * of the original definition, plus 2*(|X2| + |W2|) moved elements for the pack itself).  Ties: fewer rewritten
  * elements, then lower layout code, then larger cb.  select_layout uses the library's

@@ -21,7 +21,7 @@ LAYOUT_NAMES = {LAYOUT_AUTO: "auto", LAYOUT_PACKED: "packed", LAYOUT_IM2COL: "im
 EXPORTS = [
     "conv2d_int8", "conv2d_int8_nhwc", "unpack_nhwc_int32", "requant_int8", "requant_pack_layout", "conv2d_int8_ex", "conv2d_int8_workspace_bytes", "conv2d_int8_packed",
     "conv2d_int8_query_tiling", "conv2d_int8_num_tiles", "conv2d_int8_tile_info",
-    "conv2d_int8_tile_applies", "pack_layout", "pack_layout_bytes", "pack_layout_nhwc",
+    "conv2d_int8_tile_applies", "conv2d_int8_tile_lds_bytes", "pack_layout", "pack_layout_bytes", "pack_layout_nhwc",
     "pack_weights", "pack_weights_depth", "pack_weights_bytes", "im2col_int8", "im2col_bytes",
     "image_pack_desc", "image_pack_bytes", "image_pack_weights_bytes", "image_pack_int8", "image_pack_weights",
     "conv2d_int8_packed_requant", "conv2d_int8_packed_nhwc", "mfma_probe_int8", "im2col_nhwc_int8", "pack_weights_rsc",
@@ -69,6 +69,7 @@ def load(path: str | None = None):
         "conv2d_int8_packed": (i, [dp, i, i, vp, vp, vp, i, i, vp]),
         "conv2d_int8_query_tiling": (i, [dp, i, i, ip, ip]),
         "conv2d_int8_tile_applies": (i, [dp, i, i, i, i]),
+        "conv2d_int8_tile_lds_bytes": (sz, [dp, i, i, i, i]),
         "conv2d_int8_num_tiles": (i, []),
         "conv2d_int8_tile_info": (i, [i, ip, ip, ip, ip]),
         "pack_layout": (i, [i] * 6 + [vp, vp, vp]),
@@ -236,6 +237,11 @@ def tile_applies(dims, layout, cb, tile, split_k=1):
     """True if conv2d_int8_packed would accept this forced tile and depth split."""
     d = _desc(*dims)
     return load().conv2d_int8_tile_applies(ctypes.byref(d), layout, cb, tile, split_k) == OK
+
+
+def tile_lds_bytes(dims, layout, cb, tile, split_k=1) -> int:
+    d = _desc(*dims)
+    return int(load().conv2d_int8_tile_lds_bytes(ctypes.byref(d), layout, cb, tile, split_k))
 
 
 def query_tiling(dims, layout, cb):

@@ -1,6 +1,7 @@
 // C-ABI glue: argument validation, layout resolution, workspace carving, launch order.
 // Every step of the path runs in the HIP kernels; nothing here touches tensor data.
 #include "../../include/conv2d_int8.h"
+#include "desc_check.h"
 #include "kernels.h"
 
 #include <mutex>
@@ -16,21 +17,7 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 int round_up_i(int x, int m) { return (x + m - 1) / m * m; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-int check_desc(const conv_desc_t *d)
-{
-    if (!d) return CONV_ERR_INVALID_ARG;
-    if (d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->K <= 0 || d->R <= 0 || d->S <= 0 ||
-        d->stride <= 0 || d->pad < 0)
-        return CONV_ERR_INVALID_ARG;
-    if (d->R > (long long)d->H + 2LL * d->pad || d->S > (long long)d->W + 2LL * d->pad)
-        return CONV_ERR_INVALID_ARG;
-    if ((long long)d->C * d->R * d->S > 131072LL) return CONV_ERR_OVERFLOW_RISK;
-    const long long Hp = (long long)d->H + 2LL * d->pad, Wp = (long long)d->W + 2LL * d->pad;
-    const long long P = (Hp - d->R) / d->stride + 1, Q = (Wp - d->S) / d->stride + 1;
-    if (Hp > INT_LIMIT || Wp > INT_LIMIT) return CONV_ERR_UNSUPPORTED;
-    if (P * Q > INT_LIMIT || (long long)d->N * P * Q > INT_LIMIT) return CONV_ERR_UNSUPPORTED;
-    return CONV_OK;
-}
+int check_desc(const conv_desc_t *d) { return check_conv_desc(d); }
 
 struct Plan {
     int layout, cb, Cb, depth, P, Q, Hp, Wp;
@@ -120,7 +107,7 @@ struct PackedProblem {
     int inner_layout, inner_cb;
 };
 
-int image_pack_problem(const conv_desc_t *d, int cb, PackedProblem *pp)
+int image_pack_problem(const conv_desc_t *d, int cb, PackedProblem *pp, bool with_inner = true)
 {
     int rc = check_desc(d);
     if (rc != CONV_OK) return rc;
@@ -136,6 +123,7 @@ int image_pack_problem(const conv_desc_t *d, int cb, PackedProblem *pp)
     pp->w2_bytes = (size_t)d->K * (size_t)C2 * (size_t)R2 * (size_t)S2;
     pp->inner_layout = cb == 0 ? CONV_LAYOUT_IMPLICIT : CONV_LAYOUT_PACKED;
     pp->inner_cb = cb;
+    if (!with_inner) return CONV_OK;  // the pack alone: whatever runs on its output is the caller's choice
     Plan inner;
     return make_plan(&pp->d2, pp->inner_layout, pp->inner_cb, &inner);
 }
@@ -207,6 +195,13 @@ GemmProblem gemm_problem(const conv_desc_t *d, const Plan &pl, const int8_t *x, 
     return g;
 }
 
+// hipErrorInvalidValue comes from the launcher's own guards (a tile / split pair the picker would not
+// offer); nothing was enqueued then.
+int gemm_status(hipError_t e)
+{
+    return e == hipSuccess ? CONV_OK : e == hipErrorInvalidValue ? CONV_ERR_UNSUPPORTED : CONV_ERR_DEVICE;
+}
+
 int run_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t st)
 {
     if (tile >= gemm_num_tiles()) return CONV_ERR_INVALID_ARG;
@@ -215,7 +210,7 @@ int run_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t st)
     if (!aligned16(g.out) && s == 0) s = 1;  // the clear before a depth split writes 16-byte pieces
     if (!aligned16(g.out) && s > 1) return CONV_ERR_INVALID_ARG;
     if (!gemm_pick(g, &t, &s)) return CONV_ERR_UNSUPPORTED;
-    return launch_gemm(g, t, s, st) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+    return gemm_status(launch_gemm(g, t, s, st));
 }
 
 int rewrite_weights(const conv_desc_t *d, const Plan &pl, const int8_t *wt, int8_t *dst, hipStream_t st)
@@ -239,13 +234,49 @@ int rewrite_input(const conv_desc_t *d, const Plan &pl, const int8_t *in, int8_t
     return e == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
 }
 
-// Cached workspace of the one-shot entry point, one per device, grown on demand.
+// Cached workspace of the one-shot entry points, one per device, grown on demand.  A block that a larger
+// problem supersedes is never freed: work already enqueued, or a HIP graph captured earlier, may still
+// reference it, so it stays allocated until the process ends (blocks grow geometrically, so all superseded
+// blocks together are smaller than the current one).
 struct DeviceCache {
     void *ptr = nullptr;
     size_t bytes = 0;
 };
 std::mutex g_cache_mutex;
 DeviceCache g_cache[64];
+
+// The current device's block of at least `need` bytes.  Growing allocates, which a stream under capture
+// must not do: then CONV_ERR_WORKSPACE, with no device call made.
+int cached_workspace(size_t need, hipStream_t st, void **ptr, size_t *bytes)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CONV_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    DeviceCache &c = g_cache[dev];
+    if (c.bytes < need) {
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(st, &cs) != hipSuccess) return CONV_ERR_DEVICE;
+        if (cs != hipStreamCaptureStatusNone) return CONV_ERR_WORKSPACE;
+        const size_t least = align_up(need, 1 << 20);
+        size_t want = align_up(need + need / 4, 1 << 20);
+        if (want < 2 * c.bytes) want = 2 * c.bytes;
+        void *p = nullptr;
+        if (hipMalloc(&p, want) != hipSuccess || !p) {
+            (void)hipGetLastError();  // the generous size did not fit: try what this problem needs
+            p = nullptr;
+            want = least;
+            if (hipMalloc(&p, want) != hipSuccess || !p) {
+                (void)hipGetLastError();
+                return CONV_ERR_WORKSPACE;
+            }
+        }
+        c.ptr = p;  // the superseded block stays allocated (see above)
+        c.bytes = want;
+    }
+    *ptr = c.ptr;
+    *bytes = c.bytes;
+    return CONV_OK;
+}
 
 }  // namespace
 
@@ -411,7 +442,7 @@ int image_pack_desc(const conv_desc_t *desc, conv_desc_t *packed)
 {
     if (!packed) return CONV_ERR_INVALID_ARG;
     PackedProblem pp;
-    int rc = image_pack_problem(desc, 16, &pp);
+    int rc = image_pack_problem(desc, 16, &pp, false);
     if (rc != CONV_OK) return rc;
     *packed = pp.d2;
     return CONV_OK;
@@ -420,19 +451,19 @@ int image_pack_desc(const conv_desc_t *desc, conv_desc_t *packed)
 size_t image_pack_bytes(const conv_desc_t *desc)
 {
     PackedProblem pp;
-    return image_pack_problem(desc, 16, &pp) == CONV_OK ? pp.x2_bytes : 0;
+    return image_pack_problem(desc, 16, &pp, false) == CONV_OK ? pp.x2_bytes : 0;
 }
 
 size_t image_pack_weights_bytes(const conv_desc_t *desc)
 {
     PackedProblem pp;
-    return image_pack_problem(desc, 16, &pp) == CONV_OK ? pp.w2_bytes : 0;
+    return image_pack_problem(desc, 16, &pp, false) == CONV_OK ? pp.w2_bytes : 0;
 }
 
 int image_pack_int8(const conv_desc_t *desc, const int8_t *src, int8_t *dst, void *stream)
 {
     PackedProblem pp;
-    int rc = image_pack_problem(desc, 16, &pp);
+    int rc = image_pack_problem(desc, 16, &pp, false);
     if (rc != CONV_OK) return rc;
     if (!src || !dst || (reinterpret_cast<uintptr_t>(dst) & 3)) return CONV_ERR_INVALID_ARG;
     return launch_image_pack(desc->N, desc->C, desc->H, desc->W, desc->stride, desc->pad, pp.d2.H, pp.d2.W, src, dst,
@@ -442,7 +473,7 @@ int image_pack_int8(const conv_desc_t *desc, const int8_t *src, int8_t *dst, voi
 int image_pack_weights(const conv_desc_t *desc, const int8_t *src, int8_t *dst, void *stream)
 {
     PackedProblem pp;
-    int rc = image_pack_problem(desc, 16, &pp);
+    int rc = image_pack_problem(desc, 16, &pp, false);
     if (rc != CONV_OK) return rc;
     if (!src || !dst) return CONV_ERR_INVALID_ARG;
     return launch_image_pack_weights(desc->K, desc->C, desc->R, desc->S, desc->stride, src, dst,
@@ -545,7 +576,7 @@ int conv2d_int8_dilated(const conv_desc_t *desc, int dilation, int layout, int c
     g.il_Q = dp.Q;
     int t = -1, s = 1;
     if (!gemm_pick(g, &t, &s)) return CONV_ERR_UNSUPPORTED;
-    return launch_gemm(g, t, 1, st) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+    return gemm_status(launch_gemm(g, t, 1, st));
 }
 
 // Dilation as an address multiplier: the plan of the undilated problem with the dilated layer's output extents.
@@ -701,7 +732,7 @@ int conv2d_int8_packed_requant(const conv_desc_t *desc, int layout, int cb, cons
     g.o_pad = out_pad;
     int t = -1, s = 1;
     if (!gemm_pick(g, &t, &s)) return CONV_ERR_UNSUPPORTED;
-    return launch_gemm(g, t, 1, st) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+    return gemm_status(launch_gemm(g, t, 1, st));
 }
 
 int conv2d_int8_query_tiling(const conv_desc_t *desc, int layout, int cb, int *tile, int *split_k)
@@ -727,6 +758,16 @@ int conv2d_int8_tile_applies(const conv_desc_t *desc, int layout, int cb, int ti
     if (pl.layout == CONV_LAYOUT_IMPLICIT) return CONV_ERR_UNSUPPORTED;
     int t = tile, s = split_k;
     return gemm_pick(gemm_problem(desc, pl, nullptr, nullptr, nullptr), &t, &s) ? CONV_OK : CONV_ERR_UNSUPPORTED;
+}
+
+size_t conv2d_int8_tile_lds_bytes(const conv_desc_t *desc, int layout, int cb, int tile, int split_k)
+{
+    if (conv2d_int8_tile_applies(desc, layout, cb, tile, split_k) != CONV_OK) return 0;
+    Plan pl;
+    if (make_plan(desc, layout, cb, &pl) != CONV_OK) return 0;
+    const int steps = pl.depth / 64, slices = split_k > steps ? steps : split_k;
+    const int per = (steps + slices - 1) / slices;
+    return gemm_tile_lds_bytes(tile, pl.layout == CONV_LAYOUT_IM2COL ? ACT_MATRIX : ACT_BLOCKED, per);
 }
 
 size_t conv2d_int8_workspace_bytes(const conv_desc_t *desc, int layout, int cb, int wt_is_packed)
@@ -819,26 +860,11 @@ int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int
         if (layout != CONV_LAYOUT_IMPLICIT) return CONV_ERR_UNSUPPORTED;
         return conv2d_int8_ex(&d, layout, 0, in, wt, 0, out, nullptr, 0, stream);
     }
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CONV_ERR_DEVICE;
-    std::lock_guard<std::mutex> lock(g_cache_mutex);
-    DeviceCache &c = g_cache[dev];
-    if (c.bytes < need) {
-        // Work already enqueued may still read the old block: drain the device before freeing it.
-        if (c.ptr) {
-            if (hipDeviceSynchronize() != hipSuccess) return CONV_ERR_DEVICE;
-            (void)hipFree(c.ptr);
-            c.ptr = nullptr;
-            c.bytes = 0;
-        }
-        const size_t want = align_up(need + need / 4, 1 << 20);
-        if (hipMalloc(&c.ptr, want) != hipSuccess) {
-            c.ptr = nullptr;
-            return CONV_ERR_WORKSPACE;
-        }
-        c.bytes = want;
-    }
-    return conv2d_int8_ex(&d, layout, cb, in, wt, 0, out, c.ptr, c.bytes, stream);
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+    rc = cached_workspace(need, (hipStream_t)stream, &ws, &ws_bytes);
+    if (rc != CONV_OK) return rc;
+    return conv2d_int8_ex(&d, layout, cb, in, wt, 0, out, ws, ws_bytes, stream);
 }
 
 int conv2d_int8_nhwc(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
@@ -857,26 +883,12 @@ int conv2d_int8_nhwc(int N, int C, int H, int W, int K, int R, int S, int stride
     const size_t xb = align_up(pl.x_bytes, WS_ALIGN), wb = align_up(pl.w_bytes, WS_ALIGN);
     const size_t ob = direct ? 0 : align_up((size_t)pl.M * d.K * sizeof(int32_t), WS_ALIGN);
     const size_t need = xb + wb + ob;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CONV_ERR_DEVICE;
-    std::lock_guard<std::mutex> lock(g_cache_mutex);
-    DeviceCache &c = g_cache[dev];
-    if (c.bytes < need) {
-        if (c.ptr) {
-            if (hipDeviceSynchronize() != hipSuccess) return CONV_ERR_DEVICE;
-            (void)hipFree(c.ptr);
-            c.ptr = nullptr;
-            c.bytes = 0;
-        }
-        const size_t want = align_up(need + need / 4, 1 << 20);
-        if (hipMalloc(&c.ptr, want) != hipSuccess) {
-            c.ptr = nullptr;
-            return CONV_ERR_WORKSPACE;
-        }
-        c.bytes = want;
-    }
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+    rc = cached_workspace(need, (hipStream_t)stream, &ws, &ws_bytes);
+    if (rc != CONV_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
-    int8_t *xq = static_cast<int8_t *>(c.ptr), *wq = xq + xb;
+    int8_t *xq = static_cast<int8_t *>(ws), *wq = xq + xb;
     int32_t *nkpq = reinterpret_cast<int32_t *>(wq + wb);
     const hipError_t e = launch_rewrite_fused_nhwc(N, C, H, W, K, R, S, pad, pl.cb, pl.depth, in, xq, wt, wq, st);
     if (e == hipErrorNotSupported) {

@@ -17,6 +17,7 @@
 // The activation row of pixel m is addressed as rowbase(m) + koff[chunk]: for the blocked
 // layout koff walks (channel block, r, s) over the zero-padded image (implicit GEMM, no
 // unrolled matrix in memory); for a row-major matrix (im2col output) it is 16*chunk.
+#include "act_requant.h"
 #include "kernels.h"
 
 #include <type_traits>
@@ -50,15 +51,6 @@ struct GemmArgs {
     int dil;  // ACT_BLOCKED: distance between kernel taps in the padded image (1 = dense kernel)
     int out_nhwc;  // `out` is [N][P][Q][K] instead of [N][K][P][Q]
 };
-
-// The ALU step between two int8 layers (Sec. 5.1): rounding right shift, optional max(., 0), clip.
-__device__ __forceinline__ int epilogue_requant(int x, int shift, int relu)
-{
-    // floor(x / 2^shift + 1/2) without leaving 32 bits: floor(x / 2^shift) + bit (shift-1) of x
-    int v = shift > 0 ? (x >> shift) + ((x >> (shift - 1)) & 1) : x;
-    if (relu) v = max(v, 0);
-    return min(max(v, -128), 127);
-}
 
 // n / d for 0 <= n < 2^31 with magic = ceil(2^32 / d) truncated to 32 bits (0 encodes d == 1):
 // the multiply-high estimate is never low and at most one too high.
@@ -527,7 +519,7 @@ __device__ __forceinline__ void igemm_body(const GemmArgs &a, int block_id, int 
                     if (k >= a.K) continue;
                     int y[4];
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) y[t] = epilogue_requant(acc[i][jm][4 * vg + t], a.act_shift, a.act_relu);
+                    for (int t = 0; t < 4; ++t) y[t] = act_requant(acc[i][jm][4 * vg + t], a.act_shift, a.act_relu);
                     int8_t *dst = a.act_out + ((((size_t)n * a.o_Cb + (k >> a.o_cb_log2)) * plane + pix) << a.o_cb_log2) +
                                   (k & (o_cb - 1));
                     if (k + 3 < a.K)
@@ -665,72 +657,87 @@ __global__ void __launch_bounds__((WK * WM * DS + HELP) * 64, (WK * WM * DS + HE
 struct TileDef {
     int tk, tm, wk, wm, ks, nstage, help, ds, wpc;
 };
+// One row per kernel instantiation: TK, TM, WK, WM, KS, NSTAGE, HELP, DS, WPC.  The table the picker reads and
+// the launch switch are both generated from this list, so a tile index means the same thing in both.
+#define C2I8_TILE_LIST(X) \
+    X(32, 32, 1, 1, 1, 8, 0, 1, 1) /* 0 */ \
+    X(64, 64, 2, 2, 1, 8, 0, 1, 1) /* 1 */ \
+    X(128, 128, 2, 2, 1, 6, 0, 1, 1) /* 2 */ \
+    X(32, 128, 1, 2, 1, 8, 0, 1, 1) /* 3 */ \
+    X(64, 128, 2, 2, 1, 8, 0, 1, 1) /* 4 */ \
+    X(64, 256, 1, 4, 1, 6, 0, 1, 1) /* 5 */ \
+    X(128, 64, 2, 2, 1, 8, 0, 1, 1) /* 6 */ \
+    X(256, 128, 2, 2, 1, 5, 0, 1, 1) /* 7 */ \
+    X(128, 256, 2, 2, 1, 5, 0, 1, 1) /* 8 */ \
+    X(256, 256, 2, 2, 1, 4, 0, 1, 1) /* 9 */ \
+    X(256, 128, 2, 2, 1, 3, 0, 1, 1) /* 10 */ \
+    X(128, 256, 2, 2, 1, 3, 0, 1, 1) /* 11 */ \
+    X(128, 128, 2, 2, 1, 4, 0, 1, 1) /* 12 */ \
+    X(256, 256, 2, 4, 2, 2, 0, 1, 1) /* 13 */ \
+    X(256, 256, 2, 2, 2, 2, 0, 1, 1) /* 14 */ \
+    X(256, 128, 2, 2, 2, 3, 0, 1, 1) /* 15 */ \
+    X(128, 128, 2, 2, 2, 4, 0, 1, 1) /* 16 */ \
+    X(64, 64, 2, 2, 2, 4, 0, 1, 1) /* 17 */ \
+    X(64, 64, 2, 2, 2, 6, 0, 1, 1) /* 18 */ \
+    X(32, 64, 1, 2, 2, 6, 0, 1, 1) /* 19 */ \
+    X(64, 128, 2, 2, 2, 4, 0, 1, 1) /* 20 */ \
+    X(64, 64, 2, 2, 2, 4, 4, 1, 1) /* 21 */ \
+    X(64, 64, 2, 2, 2, 8, 4, 1, 1) /* 22 */ \
+    X(128, 128, 2, 2, 2, 4, 4, 1, 1) /* 23 */ \
+    X(64, 128, 2, 2, 2, 4, 4, 1, 1) /* 24 */ \
+    X(128, 64, 2, 2, 2, 4, 4, 1, 1) /* 25 */ \
+    X(256, 128, 2, 2, 2, 3, 4, 1, 1) /* 26 */ \
+    X(128, 256, 2, 2, 2, 3, 4, 1, 1) /* 27 */ \
+    X(64, 64, 2, 2, 2, 4, 0, 2, 1) /* 28 */ \
+    X(64, 64, 2, 2, 2, 6, 0, 2, 1) /* 29 */ \
+    X(64, 128, 2, 2, 2, 4, 0, 2, 1) /* 30 */ \
+    X(128, 64, 2, 2, 2, 4, 0, 2, 1) /* 31 */ \
+    X(32, 64, 1, 2, 2, 6, 0, 2, 1) /* 32 */ \
+    X(32, 32, 1, 1, 2, 8, 0, 2, 1) /* 33 */ \
+    X(128, 256, 2, 4, 1, 3, 0, 1, 2) /* 34 */ \
+    X(256, 128, 4, 2, 1, 3, 0, 1, 2) /* 35 */ \
+    X(128, 128, 2, 2, 1, 4, 0, 1, 2) /* 36 */ \
+    X(128, 128, 2, 2, 2, 2, 0, 1, 2) /* 37 */ \
+    X(256, 256, 2, 4, 1, 4, 0, 1, 1) /* 38 */ \
+    X(256, 256, 4, 2, 1, 4, 0, 1, 1) /* 39 */ \
+    X(256, 256, 2, 4, 1, 3, 0, 1, 1) /* 40 */ \
+    X(64, 64, 2, 2, 4, 4, 4, 1, 1) /* 41 */ \
+    X(64, 64, 2, 2, 4, 4, 0, 2, 1) /* 42 */ \
+    X(64, 64, 2, 2, 4, 3, 4, 1, 1) /* 43 */ \
+    X(64, 64, 2, 2, 4, 4, 0, 1, 1) /* 44 */
+
 static const TileDef kTiles[] = {
-    {32, 32, 1, 1, 1, 8, 0, 1, 1},  // 0
-    {64, 64, 2, 2, 1, 8, 0, 1, 1},  // 1
-    {128, 128, 2, 2, 1, 6, 0, 1, 1},  // 2
-    {32, 128, 1, 2, 1, 8, 0, 1, 1},  // 3
-    {64, 128, 2, 2, 1, 8, 0, 1, 1},  // 4
-    {64, 256, 1, 4, 1, 6, 0, 1, 1},  // 5
-    {128, 64, 2, 2, 1, 8, 0, 1, 1},  // 6
-    {256, 128, 2, 2, 1, 5, 0, 1, 1},  // 7
-    {128, 256, 2, 2, 1, 5, 0, 1, 1},  // 8
-    {256, 256, 2, 2, 1, 4, 0, 1, 1},  // 9
-    {256, 128, 2, 2, 1, 3, 0, 1, 1},  // 10
-    {128, 256, 2, 2, 1, 3, 0, 1, 1},  // 11
-    {128, 128, 2, 2, 1, 4, 0, 1, 1},  // 12
-    {256, 256, 2, 4, 2, 2, 0, 1, 1},  // 13
-    {256, 256, 2, 2, 2, 2, 0, 1, 1},  // 14
-    {256, 128, 2, 2, 2, 3, 0, 1, 1},  // 15
-    {128, 128, 2, 2, 2, 4, 0, 1, 1},  // 16
-    {64, 64, 2, 2, 2, 4, 0, 1, 1},  // 17
-    {64, 64, 2, 2, 2, 6, 0, 1, 1},  // 18
-    {32, 64, 1, 2, 2, 6, 0, 1, 1},  // 19
-    {64, 128, 2, 2, 2, 4, 0, 1, 1},  // 20
-    {64, 64, 2, 2, 2, 4, 4, 1, 1},  // 21
-    {64, 64, 2, 2, 2, 8, 4, 1, 1},  // 22
-    {128, 128, 2, 2, 2, 4, 4, 1, 1},  // 23
-    {64, 128, 2, 2, 2, 4, 4, 1, 1},  // 24
-    {128, 64, 2, 2, 2, 4, 4, 1, 1},  // 25
-    {256, 128, 2, 2, 2, 3, 4, 1, 1},  // 26
-    {128, 256, 2, 2, 2, 3, 4, 1, 1},  // 27
-    {64, 64, 2, 2, 2, 4, 0, 2, 1},  // 28
-    {64, 64, 2, 2, 2, 6, 0, 2, 1},  // 29
-    {64, 128, 2, 2, 2, 4, 0, 2, 1},  // 30
-    {128, 64, 2, 2, 2, 4, 0, 2, 1},  // 31
-    {32, 64, 1, 2, 2, 6, 0, 2, 1},  // 32
-    {32, 32, 1, 1, 2, 8, 0, 2, 1},  // 33
-    {128, 256, 2, 4, 1, 3, 0, 1, 2},  // 34
-    {256, 128, 4, 2, 1, 3, 0, 1, 2},  // 35
-    {128, 128, 2, 2, 1, 4, 0, 1, 2},  // 36
-    {128, 128, 2, 2, 2, 2, 0, 1, 2},  // 37
-    {256, 256, 2, 4, 1, 4, 0, 1, 1},  // 38
-    {256, 256, 4, 2, 1, 4, 0, 1, 1},  // 39
-    {256, 256, 2, 4, 1, 3, 0, 1, 1},  // 40
-    {64, 64, 2, 2, 4, 4, 4, 1, 1},  // 41
-    {64, 64, 2, 2, 4, 4, 0, 2, 1},  // 42
-    {64, 64, 2, 2, 4, 3, 4, 1, 1},  // 43
-    {64, 64, 2, 2, 4, 4, 0, 1, 1},  // 44
+#define C2I8_ROW(...) {__VA_ARGS__},
+    C2I8_TILE_LIST(C2I8_ROW)
+#undef C2I8_ROW
 };
 constexpr int kNumTiles = sizeof(kTiles) / sizeof(kTiles[0]);
 
 int gemm_num_tiles() { return kNumTiles; }
+size_t gemm_tile_lds_bytes(int t, int mode, int steps_per_slice);
 TileInfo gemm_tile_info(int t)
 {
     return TileInfo{kTiles[t].tk, kTiles[t].tm, (kTiles[t].wk * kTiles[t].wm * kTiles[t].ds + kTiles[t].help) * 64, kTiles[t].ks};
+}
+
+// LDS a launch of tile `d` asks for: the operand ring plus, for the blocked layout, one offset per 16-byte
+// depth chunk of a slice (`per` 64-byte steps).  The picker and the launcher use the same figure.
+constexpr size_t kLdsLimit = 160 * 1024;
+static size_t tile_lds_bytes(const TileDef &d, int mode, int per)
+{
+    return (size_t)d.nstage * (d.tk + d.tm) * 64 * d.ks + (mode == ACT_BLOCKED ? (size_t)per * 16 : 0);
 }
 
 template <int TK, int TM, int WK, int WM, int KS, int NSTAGE, int HELP, int DS, int WPC = 1>
 static hipError_t launch_tile(const GemmArgs &a, int mode, hipStream_t st)
 {
     constexpr int NT = (WK * WM * DS + HELP) * 64;
-    constexpr int STAGE = (TK + TM) * 64 * KS;
-    const size_t lds = (size_t)NSTAGE * STAGE + (mode == ACT_BLOCKED ? (size_t)a.ksteps_per_split * 16 : 0);
+    const size_t lds = tile_lds_bytes(TileDef{TK, TM, WK, WM, KS, NSTAGE, HELP, DS, WPC}, mode, a.ksteps_per_split);
     const int grid = a.tiles_k * a.tiles_m * a.split_k;
     auto kb = igemm_i8_kernel<TK, TM, WK, WM, KS, NSTAGE, HELP, DS, WPC, ACT_BLOCKED>;
     auto km = igemm_i8_kernel<TK, TM, WK, WM, KS, NSTAGE, HELP, DS, WPC, ACT_MATRIX>;
     auto kern = mode == ACT_BLOCKED ? kb : km;
-    if (lds > 160 * 1024) return hipErrorInvalidValue;
+    if (lds > kLdsLimit) return hipErrorInvalidValue;  // the picker never offers such a pair
     static size_t raised[2] = {0, 0};  // dynamic-LDS ceiling already granted, per kernel
     if (lds > 64 * 1024 && lds > raised[mode]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -743,6 +750,8 @@ static hipError_t launch_tile(const GemmArgs &a, int mode, hipStream_t st)
 }
 
 static int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+size_t gemm_tile_lds_bytes(int t, int mode, int steps_per_slice) { return tile_lds_bytes(kTiles[t], mode, steps_per_slice); }
 
 // A tile with 128- or 256-byte stages walks the depth two or four steps at a time: every slice
 // must be a whole number of stages.
@@ -789,6 +798,7 @@ bool gemm_pick(const GemmProblem &g, int *tile, int *split_k)
             s = ceil_div(ksteps, ceil_div(ksteps, s));  // drop slices that would be empty
             const int per = ceil_div(ksteps, s);
             if (!tile_fits(d, ksteps, per)) continue;
+            if (tile_lds_bytes(d, g.mode, per) > kLdsLimit) continue;  // ring + offset table must fit one CU's LDS
             const double wgs = tiles * s;
             int res = (int)((wgs + 255) / 256);  // workgroups sharing a CU
             if (res > cap) res = cap;
@@ -907,53 +917,11 @@ hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t 
         hipError_t e = launch_fill_zero(g.out, (size_t)g.M * g.K * sizeof(int32_t), st);
         if (e != hipSuccess) return e;
     }
-    switch (tile) {
-        case 0: return launch_tile<32, 32, 1, 1, 1, 8, 0, 1>(a, g.mode, st);
-        case 1: return launch_tile<64, 64, 2, 2, 1, 8, 0, 1>(a, g.mode, st);
-        case 2: return launch_tile<128, 128, 2, 2, 1, 6, 0, 1>(a, g.mode, st);
-        case 3: return launch_tile<32, 128, 1, 2, 1, 8, 0, 1>(a, g.mode, st);
-        case 4: return launch_tile<64, 128, 2, 2, 1, 8, 0, 1>(a, g.mode, st);
-        case 5: return launch_tile<64, 256, 1, 4, 1, 6, 0, 1>(a, g.mode, st);
-        case 6: return launch_tile<128, 64, 2, 2, 1, 8, 0, 1>(a, g.mode, st);
-        case 7: return launch_tile<256, 128, 2, 2, 1, 5, 0, 1>(a, g.mode, st);
-        case 8: return launch_tile<128, 256, 2, 2, 1, 5, 0, 1>(a, g.mode, st);
-        case 9: return launch_tile<256, 256, 2, 2, 1, 4, 0, 1>(a, g.mode, st);
-        case 10: return launch_tile<256, 128, 2, 2, 1, 3, 0, 1>(a, g.mode, st);
-        case 11: return launch_tile<128, 256, 2, 2, 1, 3, 0, 1>(a, g.mode, st);
-        case 12: return launch_tile<128, 128, 2, 2, 1, 4, 0, 1>(a, g.mode, st);
-        case 13: return launch_tile<256, 256, 2, 4, 2, 2, 0, 1>(a, g.mode, st);
-        case 14: return launch_tile<256, 256, 2, 2, 2, 2, 0, 1>(a, g.mode, st);
-        case 15: return launch_tile<256, 128, 2, 2, 2, 3, 0, 1>(a, g.mode, st);
-        case 16: return launch_tile<128, 128, 2, 2, 2, 4, 0, 1>(a, g.mode, st);
-        case 17: return launch_tile<64, 64, 2, 2, 2, 4, 0, 1>(a, g.mode, st);
-        case 18: return launch_tile<64, 64, 2, 2, 2, 6, 0, 1>(a, g.mode, st);
-        case 19: return launch_tile<32, 64, 1, 2, 2, 6, 0, 1>(a, g.mode, st);
-        case 20: return launch_tile<64, 128, 2, 2, 2, 4, 0, 1>(a, g.mode, st);
-        case 21: return launch_tile<64, 64, 2, 2, 2, 4, 4, 1>(a, g.mode, st);
-        case 22: return launch_tile<64, 64, 2, 2, 2, 8, 4, 1>(a, g.mode, st);
-        case 23: return launch_tile<128, 128, 2, 2, 2, 4, 4, 1>(a, g.mode, st);
-        case 24: return launch_tile<64, 128, 2, 2, 2, 4, 4, 1>(a, g.mode, st);
-        case 25: return launch_tile<128, 64, 2, 2, 2, 4, 4, 1>(a, g.mode, st);
-        case 26: return launch_tile<256, 128, 2, 2, 2, 3, 4, 1>(a, g.mode, st);
-        case 27: return launch_tile<128, 256, 2, 2, 2, 3, 4, 1>(a, g.mode, st);
-        case 28: return launch_tile<64, 64, 2, 2, 2, 4, 0, 2>(a, g.mode, st);
-        case 29: return launch_tile<64, 64, 2, 2, 2, 6, 0, 2>(a, g.mode, st);
-        case 30: return launch_tile<64, 128, 2, 2, 2, 4, 0, 2>(a, g.mode, st);
-        case 31: return launch_tile<128, 64, 2, 2, 2, 4, 0, 2>(a, g.mode, st);
-        case 32: return launch_tile<32, 64, 1, 2, 2, 6, 0, 2>(a, g.mode, st);
-        case 33: return launch_tile<32, 32, 1, 1, 2, 8, 0, 2>(a, g.mode, st);
-        case 34: return launch_tile<128, 256, 2, 4, 1, 3, 0, 1, 2>(a, g.mode, st);
-        case 35: return launch_tile<256, 128, 4, 2, 1, 3, 0, 1, 2>(a, g.mode, st);
-        case 36: return launch_tile<128, 128, 2, 2, 1, 4, 0, 1, 2>(a, g.mode, st);
-        case 37: return launch_tile<128, 128, 2, 2, 2, 2, 0, 1, 2>(a, g.mode, st);
-        case 38: return launch_tile<256, 256, 2, 4, 1, 4, 0, 1, 1>(a, g.mode, st);
-        case 39: return launch_tile<256, 256, 4, 2, 1, 4, 0, 1, 1>(a, g.mode, st);
-        case 40: return launch_tile<256, 256, 2, 4, 1, 3, 0, 1, 1>(a, g.mode, st);
-        case 41: return launch_tile<64, 64, 2, 2, 4, 4, 4, 1, 1>(a, g.mode, st);
-        case 42: return launch_tile<64, 64, 2, 2, 4, 4, 0, 2, 1>(a, g.mode, st);
-        case 43: return launch_tile<64, 64, 2, 2, 4, 3, 4, 1, 1>(a, g.mode, st);
-        case 44: return launch_tile<64, 64, 2, 2, 4, 4, 0, 1, 1>(a, g.mode, st);
-    }
+    int index = 0;
+#define C2I8_CASE(tk, tm, wk, wm, ks, nstage, help, ds, wpc) \
+    if (tile == index++) return launch_tile<tk, tm, wk, wm, ks, nstage, help, ds, wpc>(a, g.mode, st);
+    C2I8_TILE_LIST(C2I8_CASE)
+#undef C2I8_CASE
     return hipErrorInvalidValue;
 }
 

@@ -43,6 +43,8 @@ struct TileInfo {
 
 int gemm_num_tiles();
 TileInfo gemm_tile_info(int tile);
+// Dynamic LDS a launch of `tile` asks for when a depth slice holds `steps_per_slice` 64-byte steps.
+size_t gemm_tile_lds_bytes(int tile, int mode, int steps_per_slice);
 // Chooses tile / split when tile < 0 / split_k <= 0; false if a forced choice cannot run
 // this problem (a tile with 128-byte stages needs an even number of depth steps per slice).
 bool gemm_pick(const GemmProblem &g, int *tile, int *split_k);

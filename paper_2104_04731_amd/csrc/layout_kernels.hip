@@ -896,13 +896,6 @@ hipError_t launch_unpack_nhwc(int N, int K, long long PQ, const int32_t *src, in
 
 // ---- activation between two int8 layers (Sec. 5.1: the accelerator's ALU; the benchmark's step
 // between convolution and unpacking): rounding right shift, optional max(., 0), clip to int8 -------
-__device__ __forceinline__ int requant1(int x, int shift, int relu)
-{
-    // floor(x / 2^shift + 1/2) without leaving 32 bits: floor(x / 2^shift) + bit (shift-1) of x
-    int v = shift > 0 ? (x >> shift) + ((x >> (shift - 1)) & 1) : x;
-    if (relu) v = max(v, 0);
-    return min(max(v, -128), 127);
-}
 
 // same element order, int32 -> int8; one thread per 16 elements
 __global__ void __launch_bounds__(256) requant_kernel(const int32_t *src, int8_t *dst, long long count, int shift, int relu)
@@ -916,12 +909,12 @@ __global__ void __launch_bounds__(256) requant_kernel(const int32_t *src, int8_t
             for (int j = 0; j < 4; ++j) {
                 v4i x;
                 __builtin_memcpy(&x, src + e0 + 4 * j, 16);
-                o[j] = (int)pack4(requant1(x[0], shift, relu), requant1(x[1], shift, relu), requant1(x[2], shift, relu),
-                                  requant1(x[3], shift, relu));
+                o[j] = (int)pack4(act_requant(x[0], shift, relu), act_requant(x[1], shift, relu), act_requant(x[2], shift, relu),
+                                  act_requant(x[3], shift, relu));
             }
             __builtin_memcpy(dst + e0, &o, 16);
         } else {
-            for (long long e = e0; e < count; ++e) dst[e] = (int8_t)requant1(src[e], shift, relu);
+            for (long long e = e0; e < count; ++e) dst[e] = (int8_t)act_requant(src[e], shift, relu);
         }
     }
 }
@@ -966,7 +959,7 @@ __global__ void __launch_bounds__(256) requant_pack_kernel(const RequantPackArgs
 #pragma unroll
             for (int i = 0; i < 16; ++i) x[i] = s[(size_t)min(i, a.K - 1 - k0) * PQ];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) v[i] = k0 + i < a.K ? requant1(x[i], a.shift, a.relu) : 0;
+            for (int i = 0; i < 16; ++i) v[i] = k0 + i < a.K ? act_requant(x[i], a.shift, a.relu) : 0;
 #pragma unroll
             for (int j = 0; j < 4; ++j) o[j] = (int)pack4(v[4 * j], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]);
         }

@@ -2,6 +2,7 @@
 // rewrite kernels, the two-rewrites-in-one-launch kernel, and the whole-convolution kernel),
 // with the host helpers that fill their argument blocks.
 #pragma once
+#include "act_requant.h"
 #include "kernels.h"
 
 namespace c2i8 {
@@ -36,14 +37,6 @@ __device__ __forceinline__ int fast_div_any(int n, int d, unsigned magic)
     int q = fast_div(n, magic);
     if ((long long)q * d > n) --q;
     return q;
-}
-// The ALU step between two int8 layers (Sec. 5.1): rounding right shift, optional max(., 0), clip to int8.
-__device__ __forceinline__ int act_requant(int x, int shift, int relu)
-{
-    // floor(x / 2^shift + 1/2) without leaving 32 bits: floor(x / 2^shift) + bit (shift-1) of x
-    int v = shift > 0 ? (x >> shift) + ((x >> (shift - 1)) & 1) : x;
-    if (relu) v = max(v, 0);
-    return min(max(v, -128), 127);
 }
 // Four consecutive output channels k .. k+3 of pixel (n, p, q) -- what one lane holds in v%4 of an MFMA
 // result block -- activated and stored as one dword of the blocked tensor (bytes past channel K-1 are not written).

@@ -3,6 +3,7 @@
 // candidate list.  Host arithmetic only (the one call into the kernel side asks whether the
 // stencil-unrolling GEMM stage takes the shape).
 #include "../../include/conv2d_int8.h"
+#include "desc_check.h"
 #include "kernels.h"
 
 #include <stdint.h>
@@ -24,10 +25,8 @@ struct Cand {
 extern "C" int layout_overheads(const conv_desc_t *d, int layout, int cb,
                                 int64_t *o_mac, int64_t *o_data, int64_t *rewritten)
 {
-    if (!d || d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->K <= 0 || d->R <= 0 ||
-        d->S <= 0 || d->stride <= 0 || d->pad < 0 || d->R > d->H + 2 * d->pad ||
-        d->S > d->W + 2 * d->pad)
-        return CONV_ERR_INVALID_ARG;
+    const int rc0 = c2i8::check_conv_desc(d);
+    if (rc0 != CONV_OK) return rc0;
     const int64_t P = ((int64_t)d->H + 2 * (int64_t)d->pad - d->R) / d->stride + 1;
     const int64_t Q = ((int64_t)d->W + 2 * (int64_t)d->pad - d->S) / d->stride + 1;
     const int64_t M = (int64_t)d->N * P * Q;
@@ -78,7 +77,7 @@ extern "C" int layout_overheads(const conv_desc_t *d, int layout, int cb,
     } else {
         const int64_t cpad = round_up(d->C, cb);
         depth = round_up(cpad * taps, UNIT_DEPTH);
-        x_elems = (int64_t)d->N * cpad * (d->H + 2 * d->pad) * (d->W + 2 * d->pad);
+        x_elems = (int64_t)d->N * cpad * ((int64_t)d->H + 2 * (int64_t)d->pad) * ((int64_t)d->W + 2 * (int64_t)d->pad);
     }
     const int64_t w_elems = (int64_t)d->K * depth;
     const int64_t mac_total = round_up(M, UNIT_PIXELS) * round_up(d->K, UNIT_CHANNELS) * depth;

@@ -141,6 +141,34 @@ def test_ex_and_packed_validation(lib):
         assert r % 32 == 0 and c % 32 == 0 and th % 64 == 0 and steps in (1, 2, 4)
 
 
+@pytest.mark.parametrize("dims,layout,cb", [
+    ((512, 8192, 14, 14, 4096, 3, 3, 1, 1), 1, 16), ((512, 8192, 14, 14, 4096, 3, 3, 1, 1), 1, 64),
+    ((64, 2048, 267, 162, 1000, 20, 2, 2, 1), 0, 0), ((4, 14000, 9, 9, 512, 3, 3, 1, 1), 1, 64),
+    ((2048, 4096, 7, 7, 2048, 3, 3, 1, 1), 2, 0)], ids=str)
+def test_deep_reductions_get_a_tile_that_fits(lib, dims, layout, cb):
+    """A deep reduction adds an offset per 16-byte chunk to the blocked layout's LDS footprint: the tile the
+    library picks must be one it can launch (the picker and the launcher share one LDS figure), and a forced
+    large ring whose footprint would not fit is refused as unsupported, not discovered at launch."""
+    if layout == 0:
+        layout, cb = lib.select_layout(dims)[:2]
+    tile, split = lib.query_tiling(dims, layout, cb)
+    assert tile >= 0 and split >= 1
+    assert lib.tile_applies(dims, layout, cb, tile, split)
+    assert 0 < lib.tile_lds_bytes(dims, layout, cb, tile, split) <= 160 * 1024
+    table = 0 if layout == 2 else lib.pack_weights_depth(dims[1], dims[5], dims[6], layout, cb) // 4   # 16 B per 64-byte step
+    refused = 0
+    for t in range(lib.num_tiles()):
+        need = lib.tile_lds_bytes(dims, layout, cb, t, 1)
+        assert need <= 160 * 1024
+        assert (need > 0) == lib.tile_applies(dims, layout, cb, t, 1)
+        rows, cols, threads, steps = lib.tile_info(t)
+        if need:
+            assert need >= 2 * (rows + cols) * 64 * steps + table      # at least two ring stages + the offsets
+        refused += need == 0
+    if table > 16 * 1024:
+        assert refused > 0     # the deepest rings do not fit beside an offset table of this size
+
+
 IMPLICIT_DOMAIN = [(1, 1, 8, 3, 4, 3, 3, 1, 1), (1, 16, 64, 4000, 4, 4, 4, 40, 0), (1, 1, 64, 4000, 4, 4, 4, 40, 0),
                    (1, 16, 9, 9, 8, 4, 4, 1, 0), (1, 17, 9, 9, 8, 4, 4, 1, 0), (2, 3, 40, 40, 8, 3, 3, 2, 1),
                    (1, 4, 30, 70, 8, 5, 5, 3, 2), (1, 64, 8, 200, 8, 1, 1, 5, 0), (1, 2, 300, 9, 8, 30, 4, 1, 0),

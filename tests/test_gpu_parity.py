@@ -304,8 +304,22 @@ def test_non_default_stream(lib):
 
 
 # ---- the batch-scaled shapes bench.py times (supplementary section): sampled images -------------
-def _sample_images(N):
-    return sorted({0, N // 2 - 1, N - 1})
+def _sample_images(N, pixels=None, bytes_per_image=()):
+    """About sixteen images of a batch: both ends and the middle; with `pixels` (output pixels per image) the
+    images on both sides of several 256-pixel tile boundaries (the widest GEMM tile), near the start, the
+    middle and the end of the pixel range; with per-image byte counts the last image below and the first
+    image at or above byte offsets 2^31 and 2^32 of each such tensor."""
+    pick = {0, 1, N // 2 - 1, N // 2, N - 2, N - 1}
+    if pixels:
+        tiles = N * pixels // 256
+        for t in (1, 2, tiles // 3, tiles // 2, 2 * tiles // 3, tiles - 1):
+            n = 256 * t // pixels            # the image that holds the tile's first pixel ...
+            pick |= {n - 1, n, n + 1} if 256 * t % pixels else {n - 1, n}   # ... and its neighbours across the boundary
+    for b in bytes_per_image:
+        for limit in (1 << 31, 1 << 32):
+            n = -(-limit // b)
+            pick |= {n - 1, n}
+    return sorted(n for n in pick if 0 <= n < N)
 
 
 def test_batch_scaled_gemm_stage_sampled_images(lib):
@@ -321,10 +335,45 @@ def test_batch_scaled_gemm_stage_sampled_images(lib):
     out = torch.empty((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=DEV)
     lib.conv2d_int8_packed(cfg.dims(), lay, cb, xp, wp, out)
     wh = host(w)
-    for n in _sample_images(cfg.N):
+    picked = _sample_images(cfg.N, cfg.P * cfg.Q)
+    assert len(picked) >= 14
+    for n in picked:
         want = direct.conv2d_int8(host(x[n:n + 1]), wh, cfg.stride, cfg.pad)
         assert np.array_equal(host(out[n:n + 1]), want), n
         assert np.array_equal(host(xp[n:n + 1]), layouts.pack_layout(host(x[n:n + 1]), cb, cfg.pad)), n
+
+
+def test_offsets_past_32_bits(lib):
+    """Batches whose tensors pass 2^31 and 2^32 bytes: the 64-channel 3x3 layer at N=10880 (NCHW input and
+    blocked input past 2^31, int32 result past 2^33) through channel blocking + GEMM stage, and the
+    three-channel stem at N=1400 (result past 2^32) through the stencil-unrolling GEMM stage.  Whole planes
+    of the images on both sides of each limit, and of tile-straddling images, against the definition."""
+    g = torch.Generator(device=DEV); g.manual_seed(4250)
+    cfg = CONFIGS["C2"].scaled(10880)
+    x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=DEV, generator=g)
+    w = torch.randint(-128, 128, (cfg.K, cfg.C, cfg.R, cfg.S), dtype=torch.int8, device=DEV, generator=g)
+    xp = lib.pack_layout(x, 64, cfg.pad)
+    wp = lib.pack_weights(w, lib.LAYOUT_PACKED, 64)
+    out = torch.empty((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=DEV)
+    lib.conv2d_int8_packed(cfg.dims(), lib.LAYOUT_PACKED, 64, xp, wp, out)
+    wh = host(w)
+    sizes = (cfg.C * cfg.H * cfg.W, xp[0].numel(), cfg.K * cfg.P * cfg.Q * 4)
+    assert cfg.N * sizes[0] > 1 << 31 and cfg.N * sizes[1] > 1 << 31 and cfg.N * sizes[2] > 1 << 33
+    for n in _sample_images(cfg.N, cfg.P * cfg.Q, sizes):
+        xh = host(x[n:n + 1])
+        assert np.array_equal(host(xp[n:n + 1]), layouts.pack_layout(xh, 64, cfg.pad)), ("pack", n)
+        assert np.array_equal(host(out[n:n + 1]), direct.conv2d_int8(xh, wh, cfg.stride, cfg.pad)), ("gemm", n)
+    del x, xp, out
+
+    cfg = CONFIGS["C3"].scaled(1400)
+    x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=DEV, generator=g)
+    w = torch.randint(-128, 128, (cfg.K, cfg.C, cfg.R, cfg.S), dtype=torch.int8, device=DEV, generator=g)
+    out = torch.empty((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=DEV)
+    lib.conv2d_int8_ex(cfg.dims(), lib.LAYOUT_IMPLICIT, 0, x, w, out, None)
+    wh = host(w)
+    assert out.numel() * 4 > 1 << 32
+    for n in _sample_images(cfg.N, None, (cfg.K * cfg.P * cfg.Q * 4,)):
+        assert np.array_equal(host(out[n:n + 1]), direct.conv2d_int8(host(x[n:n + 1]), wh, cfg.stride, cfg.pad)), ("stem", n)
 
 
 def test_batch_scaled_layout_kernels_sampled_images(lib):
@@ -449,6 +498,49 @@ def test_one_shot_graph_replay(lib):
         # eager work between replays, through the same path
         e = lib.conv2d_int8(ins[0][0], ins[0][1], cfgs[0].stride, cfgs[0].pad)
         assert np.array_equal(host(e), data[0][2])
+
+
+def test_one_shot_workspace_growth_keeps_captured_graphs_valid(lib):
+    """A graph captured while the cached workspace was small must still be valid after a larger problem has
+    made the library move to a bigger block (the superseded block stays allocated); and a call that would
+    have to grow the block while its stream is being captured is refused with nothing enqueued."""
+    small, big = CONFIGS["C2"], ConvShape("grow", 192, 64, 56, 56, 64, 3, 3, 1, 1)       # 41 MB of rewritten input
+    huge = ConvShape("grow2", 448, 64, 56, 56, 64, 3, 3, 1, 1)                           # 96 MB: beyond 2 x 41 MB
+    x, w, want = oracle_conv(small)
+    dx, dw = dev(x), dev(w)
+    out = torch.empty((small.N, small.K, small.P, small.Q), dtype=torch.int32, device=DEV)
+    lib.conv2d_int8(dx, dw, small.stride, small.pad, out=out)         # eager first: sizes the cached workspace
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        lib.conv2d_int8(dx, dw, small.stride, small.pad, out=out)
+    gen = torch.Generator(device=DEV); gen.manual_seed(4260)
+    bx = torch.randint(-128, 128, (huge.N, big.C, big.H, big.W), dtype=torch.int8, device=DEV, generator=gen)
+    bw = torch.randint(-128, 128, (big.K, big.C, big.R, big.S), dtype=torch.int8, device=DEV, generator=gen)
+    bout = lib.conv2d_int8(bx[:big.N], bw, big.stride, big.pad)       # grows the cache
+    for n in (0, big.N - 1):
+        assert np.array_equal(host(bout[n:n + 1]), direct.conv2d_int8(host(bx[n:n + 1]), host(bw), 1, 1)), n
+    for rep in range(2):
+        out.fill_(-1)
+        g.replay()                                                    # still reads and writes the first block
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), want), rep
+    # growth under capture: refused, the capture goes on and what it holds is intact
+    hout = torch.empty((huge.N, huge.K, huge.P, huge.Q), dtype=torch.int32, device=DEV)
+    g2 = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g2):
+        lib.conv2d_int8(dx, dw, small.stride, small.pad, out=out)
+        with pytest.raises(lib.ConvError) as e:
+            lib.conv2d_int8(bx, bw, huge.stride, huge.pad, out=hout)
+        assert e.value.status == lib.ERR_WORKSPACE
+    out.fill_(-1)
+    g2.replay()
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), want)
+    # outside capture the same call grows the block and runs
+    lib.conv2d_int8(bx, bw, huge.stride, huge.pad, out=hout)
+    n = huge.N - 1
+    assert np.array_equal(host(hout[n:n + 1]), direct.conv2d_int8(host(bx[n:n + 1]), host(bw), 1, 1))
 
 
 # ---- stencil unroll inside the GEMM stage ---------------------------------------------------
