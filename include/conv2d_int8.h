@@ -90,6 +90,20 @@ typedef struct {
 int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                 const int8_t *in, const int8_t *wt, int32_t *out, void *stream);
 
+/* conv2d_int8 for callers that cannot allocate: code under HIP graph capture, serving loops and harnesses
+ * that forbid hipMalloc.  Same arguments, same result; the rewritten operands go to a fixed device array of
+ * CONV_STATIC_WORKSPACE_BYTES that is part of the library's code object (every GPU the library is used on
+ * holds its own copy from the first call there until the process ends).  The call itself never allocates or
+ * frees and never synchronises.  A problem whose rewritten input + weights
+ * (conv2d_int8_workspace_bytes(desc, CONV_LAYOUT_AUTO, 0, 0)) exceed the array: CONV_ERR_WORKSPACE, nothing
+ * enqueued.  All calls on one GPU share the array and nothing orders them but the streams they are given:
+ * two calls that may overlap on one GPU race on it (use one stream, or order the streams with events).
+ * Nothing is assumed about what an earlier call left there: every byte the GEMM stage reads is written by
+ * this call's own rewrites. */
+#define CONV_STATIC_WORKSPACE_BYTES ((size_t)8 << 20)
+int conv2d_int8_static(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                       const int8_t *in, const int8_t *wt, int32_t *out, void *stream);
+
 /* The same for NHWC tensors (Sec. 5.2): in [N][H][W][C], wt KCRS, out [N][P][Q][K] int32.  Channel
  * blocking straight from the NHWC source (pack_layout_nhwc) and the weight rewrite in one launch, then a
  * GEMM stage whose epilogue writes NHWC itself: two launches.  (An `out` that does not start on 16 bytes goes

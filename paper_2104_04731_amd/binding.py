@@ -19,7 +19,7 @@ LAYOUT_NAMES = {LAYOUT_AUTO: "auto", LAYOUT_PACKED: "packed", LAYOUT_IM2COL: "im
                 LAYOUT_IMAGE_PACK: "image_pack"}
 
 EXPORTS = [
-    "conv2d_int8", "conv2d_int8_nhwc", "unpack_nhwc_int32", "requant_int8", "requant_pack_layout", "conv2d_int8_ex", "conv2d_int8_workspace_bytes", "conv2d_int8_packed",
+    "conv2d_int8", "conv2d_int8_static", "conv2d_int8_nhwc", "unpack_nhwc_int32", "requant_int8", "requant_pack_layout", "conv2d_int8_ex", "conv2d_int8_workspace_bytes", "conv2d_int8_packed",
     "conv2d_int8_query_tiling", "conv2d_int8_num_tiles", "conv2d_int8_tile_info",
     "conv2d_int8_tile_applies", "conv2d_int8_tile_lds_bytes", "pack_layout", "pack_layout_bytes", "pack_layout_nhwc",
     "pack_weights", "pack_weights_depth", "pack_weights_bytes", "im2col_int8", "im2col_bytes",
@@ -60,6 +60,7 @@ def load(path: str | None = None):
     dp, ip = ctypes.POINTER(ConvDesc), ctypes.POINTER(ctypes.c_int)
     sig = {
         "conv2d_int8": (i, [i] * 9 + [vp, vp, vp, vp]),
+        "conv2d_int8_static": (i, [i] * 9 + [vp, vp, vp, vp]),
         "conv2d_int8_nhwc": (i, [i] * 9 + [vp, vp, vp, vp]),
         "unpack_nhwc_int32": (i, [i] * 4 + [vp, vp, vp]),
         "requant_int8": (i, [ctypes.c_longlong, vp, vp, i, i, vp]),
@@ -154,6 +155,21 @@ def conv2d_int8(x: torch.Tensor, w: torch.Tensor, stride: int, pad: int, out=Non
         out = torch.empty((N, K, max(P, 0), max(Q, 0)), dtype=torch.int32, device=x.device)
     _check(load().conv2d_int8(N, C, H, W, K, R, S, stride, pad, _ptr(x), _ptr(w), _ptr(out),
                               _stream(stream)), "conv2d_int8")
+    return out
+
+
+STATIC_WORKSPACE_BYTES = 8 << 20
+
+
+def conv2d_int8_static(x: torch.Tensor, w: torch.Tensor, stride: int, pad: int, out: torch.Tensor, stream=None):
+    """conv2d_int8 through the library's fixed device array: the call allocates nothing (`out` is the caller's)."""
+    _require(x, torch.int8, "input"); _require(w, torch.int8, "weights"); _require(out, torch.int32, "output")
+    N, C, H, W = x.shape
+    K, C2, R, S = w.shape
+    if C2 != C:
+        raise ValueError("channel mismatch")
+    _check(load().conv2d_int8_static(N, C, H, W, K, R, S, stride, pad, _ptr(x), _ptr(w), _ptr(out),
+                                     _stream(stream)), "conv2d_int8_static")
     return out
 
 

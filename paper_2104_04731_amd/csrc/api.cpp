@@ -8,6 +8,10 @@
 
 using namespace c2i8;
 
+// Workspace of conv2d_int8_static, the entry point that allocates nothing (see there).
+constexpr size_t STATIC_WS_BYTES = CONV_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_WS_BYTES];
+
 namespace {
 
 constexpr size_t WS_ALIGN = 256;
@@ -275,6 +279,32 @@ int cached_workspace(size_t need, hipStream_t st, void **ptr, size_t *bytes)
     }
     *ptr = c.ptr;
     *bytes = c.bytes;
+    return CONV_OK;
+}
+
+// ---- workspace of the entry point that allocates nothing -----------------------------------------
+// A file-scope device array stands in for the cached workspace.  Every GPU the library runs on holds
+// its own copy of it, at its own address, from the moment the code object is loaded there until the
+// process ends.  In host code the array's NAME is only a handle for the runtime: the address kernels
+// can use is what hipGetSymbolAddress returns for the device that is current, asked once per device.
+std::mutex g_static_ws_mutex;
+void *g_static_ws[64] = {};  // per device: device address of `scratch` there
+
+int static_workspace(void **ptr)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return CONV_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_static_ws_mutex);
+    if (!g_static_ws[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return CONV_ERR_DEVICE;
+        }
+        if (reinterpret_cast<uintptr_t>(p) % WS_ALIGN) return CONV_ERR_DEVICE;
+        g_static_ws[dev] = p;
+    }
+    *ptr = g_static_ws[dev];
     return CONV_OK;
 }
 
@@ -865,6 +895,28 @@ int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int
     rc = cached_workspace(need, (hipStream_t)stream, &ws, &ws_bytes);
     if (rc != CONV_OK) return rc;
     return conv2d_int8_ex(&d, layout, cb, in, wt, 0, out, ws, ws_bytes, stream);
+}
+
+int conv2d_int8_static(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                       const int8_t *in, const int8_t *wt, int32_t *out, void *stream)
+{
+    conv_desc_t d{N, C, H, W, K, R, S, stride, pad};
+    int layout = CONV_LAYOUT_AUTO, cb = 0;
+    int rc = resolve_layout(&d, &layout, &cb);
+    if (rc != CONV_OK) return rc;
+    if (!in || !wt || !out) return CONV_ERR_INVALID_ARG;
+    const size_t need = conv2d_int8_workspace_bytes(&d, layout, cb, 0);
+    if (need == 0) {  // IMPLICIT: nothing to stage (any other layout reports its problem here)
+        if (layout != CONV_LAYOUT_IMPLICIT) return CONV_ERR_UNSUPPORTED;
+        return conv2d_int8_ex(&d, layout, 0, in, wt, 0, out, nullptr, 0, stream);
+    }
+    if (need > STATIC_WS_BYTES) return CONV_ERR_WORKSPACE;  // the rewritten operands do not fit the fixed array
+    void *ws = nullptr;
+    rc = static_workspace(&ws);
+    if (rc != CONV_OK) return rc;
+    // Both rewrites write every byte of what the GEMM stage reads (zero borders and padding included), and a
+    // depth split clears `out` with a kernel of its own: nothing is assumed about what the last call left.
+    return conv2d_int8_ex(&d, layout, cb, in, wt, 0, out, ws, STATIC_WS_BYTES, stream);
 }
 
 int conv2d_int8_nhwc(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
