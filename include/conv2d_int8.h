@@ -128,14 +128,19 @@ size_t conv2d_int8_workspace_bytes(const conv_desc_t *desc, int layout, int cb, 
  * in_packed: output of pack_layout (PACKED / PAD_ONLY) or im2col_int8 (IM2COL), or the NCHW
  * input itself (IMPLICIT); wt_packed: output of pack_weights.  layout must not be AUTO; cb as above (0 = 64 if
  * C >= 64 else ceil(C,16) rounded to 16/32/64).
- * tile: -1 = automatic, else an index < conv2d_int8_num_tiles() (for tuning sweeps);
+ * tile: -1 = automatic, else an index < conv2d_int8_num_tiles() (for tuning sweeps), or CONV_TILE_BAND:
+ * the second GEMM-stage kernel, for channel blocks of 64 (PACKED with cb = 64, or PAD_ONLY over 64 channels):
+ * it keeps the input rows a band of output rows touches resident in LDS (each activation byte is fetched
+ * once per workgroup, not once per kernel tap -- the buffer-residency argument of Sec. 6.1) and splits the
+ * reduction depth over its waves; picked automatically for small many-channel layers;
  * split_k: 0 = automatic, else the number of depth slices (>= 2 accumulates with int32
- * atomics after clearing `out`; exact, because integer addition is associative).
+ * atomics after clearing `out`; exact, because integer addition is associative; CONV_TILE_BAND: 0 or 1).
  * IMPLICIT has one kernel shape per problem: tile must be -1 and split_k 0 or 1. */
+#define CONV_TILE_BAND (-2)
 int conv2d_int8_packed(const conv_desc_t *desc, int layout, int cb,
                        const int8_t *in_packed, const int8_t *wt_packed, int32_t *out,
                        int tile, int split_k, void *stream);
-/* The tile and depth split the library would pick for this problem (host only);
+/* The tile (an index, or CONV_TILE_BAND) and depth split the library would pick for this problem (host only);
  * tile = -1, split_k = 1 for IMPLICIT. */
 int conv2d_int8_query_tiling(const conv_desc_t *desc, int layout, int cb, int *tile, int *split_k);
 int conv2d_int8_num_tiles(void);
@@ -143,7 +148,7 @@ int conv2d_int8_num_tiles(void);
  * steps = 64-byte depth steps per pipeline stage (a tile only runs problems whose depth
  * slices hold a whole number of stages; otherwise CONV_ERR_UNSUPPORTED). */
 int conv2d_int8_tile_info(int tile, int *rows, int *cols, int *threads, int *steps);
-/* Would conv2d_int8_packed accept this forced tile (>= 0) and split_k (>= 1) for this
+/* Would conv2d_int8_packed accept this forced tile (>= 0, or CONV_TILE_BAND) and split_k (>= 1) for this
  * problem?  CONV_OK or CONV_ERR_UNSUPPORTED (host only). */
 int conv2d_int8_tile_applies(const conv_desc_t *desc, int layout, int cb, int tile, int split_k);
 /* LDS bytes per workgroup that this tile and split would ask for on this problem (operand ring plus, for

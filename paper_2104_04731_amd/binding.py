@@ -14,6 +14,7 @@ from . import build as _build
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_OVERFLOW_RISK, ERR_WORKSPACE, ERR_DEVICE = range(6)
 LAYOUT_AUTO, LAYOUT_PACKED, LAYOUT_IM2COL, LAYOUT_PAD_ONLY, LAYOUT_IMPLICIT, LAYOUT_IMAGE_PACK = range(6)
+TILE_BAND = -2   # CONV_TILE_BAND
 LAYOUT_NAMES = {LAYOUT_AUTO: "auto", LAYOUT_PACKED: "packed", LAYOUT_IM2COL: "im2col",
                 LAYOUT_PAD_ONLY: "pad_only", LAYOUT_IMPLICIT: "implicit",
                 LAYOUT_IMAGE_PACK: "image_pack"}

@@ -8,7 +8,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libconv2d_int8.so")
-SOURCES = ["api.cpp", "selector.cpp", "igemm_mfma.hip", "layout_kernels.hip", "window_mfma.hip",
+SOURCES = ["api.cpp", "selector.cpp", "igemm_mfma.hip", "band_mfma.hip", "layout_kernels.hip", "window_mfma.hip",
            "pointwise_mfma.hip"]
 HEADERS = [os.path.join(CSRC, "kernels.h"), os.path.join(CSRC, "rewrite_bodies.h"), os.path.join(CSRC, "act_requant.h"), os.path.join(CSRC, "desc_check.h"),
            os.path.join(os.path.dirname(PKG), "include", "conv2d_int8.h")]

@@ -206,15 +206,47 @@ int gemm_status(hipError_t e)
     return e == hipSuccess ? CONV_OK : e == hipErrorInvalidValue ? CONV_ERR_UNSUPPORTED : CONV_ERR_DEVICE;
 }
 
+// Which kernel runs the GEMM stage: a tile of the general kernel with a depth split, or the band kernel.
+struct GemmChoice {
+    int tile, split_k;  // tile == CONV_TILE_BAND: the band kernel (split_k 1)
+};
+
+int choose_gemm(const GemmProblem &g, int tile, int split_k, GemmChoice *c)
+{
+    if (tile == CONV_TILE_BAND) {
+        if (split_k < 0 || split_k > 1 || !band_applies(g)) return split_k < 0 ? CONV_ERR_INVALID_ARG : CONV_ERR_UNSUPPORTED;
+        *c = GemmChoice{CONV_TILE_BAND, 1};
+        return CONV_OK;
+    }
+    if (tile < -1 || tile >= gemm_num_tiles()) return CONV_ERR_INVALID_ARG;
+    if (split_k < 0) return CONV_ERR_INVALID_ARG;
+    const bool free_choice = tile == -1 && split_k == 0;
+    int t = tile, s = split_k;
+    if (g.out && !aligned16(g.out) && s == 0) s = 1;  // the clear before a depth split writes 16-byte pieces
+    if (g.out && !aligned16(g.out) && s > 1) return CONV_ERR_INVALID_ARG;
+    double cost = 0;
+    if (!gemm_pick(g, &t, &s, &cost)) {
+        if (free_choice && band_applies(g)) {
+            *c = GemmChoice{CONV_TILE_BAND, 1};
+            return CONV_OK;
+        }
+        return CONV_ERR_UNSUPPORTED;
+    }
+    if (free_choice && band_cost(g) < cost) {
+        *c = GemmChoice{CONV_TILE_BAND, 1};
+        return CONV_OK;
+    }
+    *c = GemmChoice{t, s};
+    return CONV_OK;
+}
+
 int run_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t st)
 {
-    if (tile >= gemm_num_tiles()) return CONV_ERR_INVALID_ARG;
-    if (split_k < 0) return CONV_ERR_INVALID_ARG;
-    int t = tile, s = split_k;
-    if (!aligned16(g.out) && s == 0) s = 1;  // the clear before a depth split writes 16-byte pieces
-    if (!aligned16(g.out) && s > 1) return CONV_ERR_INVALID_ARG;
-    if (!gemm_pick(g, &t, &s)) return CONV_ERR_UNSUPPORTED;
-    return gemm_status(launch_gemm(g, t, s, st));
+    GemmChoice c;
+    const int rc = choose_gemm(g, tile, split_k, &c);
+    if (rc != CONV_OK) return rc;
+    if (c.tile == CONV_TILE_BAND) return gemm_status(launch_band_conv(g, st));
+    return gemm_status(launch_gemm(g, c.tile, c.split_k, st));
 }
 
 int rewrite_weights(const conv_desc_t *d, const Plan &pl, const int8_t *wt, int8_t *dst, hipStream_t st)
@@ -771,23 +803,27 @@ int conv2d_int8_query_tiling(const conv_desc_t *desc, int layout, int cb, int *t
     Plan pl;
     int rc = make_plan(desc, layout, cb, &pl);
     if (rc != CONV_OK) return rc;
-    int t = -1, s = pl.layout == CONV_LAYOUT_IMPLICIT ? 1 : 0;
-    if (pl.layout != CONV_LAYOUT_IMPLICIT) gemm_pick(gemm_problem(desc, pl, nullptr, nullptr, nullptr), &t, &s);
-    *tile = t;
-    *split_k = s;
+    *tile = -1;
+    *split_k = 1;
+    if (pl.layout == CONV_LAYOUT_IMPLICIT) return CONV_OK;
+    GemmChoice c;
+    rc = choose_gemm(gemm_problem(desc, pl, nullptr, nullptr, nullptr), -1, 0, &c);
+    if (rc != CONV_OK) return rc;
+    *tile = c.tile;
+    *split_k = c.split_k;
     return CONV_OK;
 }
 
 int conv2d_int8_tile_applies(const conv_desc_t *desc, int layout, int cb, int tile, int split_k)
 {
-    if (layout == CONV_LAYOUT_AUTO || tile < 0 || tile >= gemm_num_tiles() || split_k < 1)
+    if (layout == CONV_LAYOUT_AUTO || (tile < 0 && tile != CONV_TILE_BAND) || tile >= gemm_num_tiles() || split_k < 1)
         return CONV_ERR_INVALID_ARG;
     Plan pl;
     int rc = make_plan(desc, layout, cb, &pl);
     if (rc != CONV_OK) return rc;
     if (pl.layout == CONV_LAYOUT_IMPLICIT) return CONV_ERR_UNSUPPORTED;
-    int t = tile, s = split_k;
-    return gemm_pick(gemm_problem(desc, pl, nullptr, nullptr, nullptr), &t, &s) ? CONV_OK : CONV_ERR_UNSUPPORTED;
+    GemmChoice c;
+    return choose_gemm(gemm_problem(desc, pl, nullptr, nullptr, nullptr), tile, split_k, &c);
 }
 
 size_t conv2d_int8_tile_lds_bytes(const conv_desc_t *desc, int layout, int cb, int tile, int split_k)
@@ -795,6 +831,7 @@ size_t conv2d_int8_tile_lds_bytes(const conv_desc_t *desc, int layout, int cb, i
     if (conv2d_int8_tile_applies(desc, layout, cb, tile, split_k) != CONV_OK) return 0;
     Plan pl;
     if (make_plan(desc, layout, cb, &pl) != CONV_OK) return 0;
+    if (tile == CONV_TILE_BAND) return band_lds_bytes(gemm_problem(desc, pl, nullptr, nullptr, nullptr));
     const int steps = pl.depth / 64, slices = split_k > steps ? steps : split_k;
     const int per = (steps + slices - 1) / slices;
     return gemm_tile_lds_bytes(tile, pl.layout == CONV_LAYOUT_IM2COL ? ACT_MATRIX : ACT_BLOCKED, per);

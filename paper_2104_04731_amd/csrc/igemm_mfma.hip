@@ -767,7 +767,7 @@ static bool tile_fits(const TileDef &d, int ksteps, int per)
 // bytes per cycle a wave and a CU move global->LDS, the latency chain of a lone workgroup's
 // depth step, the sustained share of the MFMA issue rate, output bytes per cycle and CU,
 // the cost of starting a workgroup and each of its waves -- but only the ranking is used.
-bool gemm_pick(const GemmProblem &g, int *tile, int *split_k)
+bool gemm_pick(const GemmProblem &g, int *tile, int *split_k, double *cost)
 {
     const int ksteps = g.depth / 64;
     bool found = false;
@@ -823,6 +823,7 @@ bool gemm_pick(const GemmProblem &g, int *tile, int *split_k)
     }
     *tile = bt;
     *split_k = bs;
+    if (cost) *cost = best;
     return found;
 }
 

@@ -47,7 +47,15 @@ TileInfo gemm_tile_info(int tile);
 size_t gemm_tile_lds_bytes(int tile, int mode, int steps_per_slice);
 // Chooses tile / split when tile < 0 / split_k <= 0; false if a forced choice cannot run
 // this problem (a tile with 128-byte stages needs an even number of depth steps per slice).
-bool gemm_pick(const GemmProblem &g, int *tile, int *split_k);
+bool gemm_pick(const GemmProblem &g, int *tile, int *split_k, double *cost = nullptr);
+// The band kernel (band_mfma.hip): a GEMM stage for channel blocks of 64 that keeps a band of output rows'
+// input window resident in LDS and splits the depth over its waves.  band_cost: the same cycle scale as
+// the cost gemm_pick reports (1e300 where the kernel does not apply).
+bool band_applies(const GemmProblem &g);
+double band_cost(const GemmProblem &g);
+TileInfo band_tile_info(const GemmProblem &g);
+size_t band_lds_bytes(const GemmProblem &g);
+hipError_t launch_band_conv(const GemmProblem &g, hipStream_t st);
 // split_k > 1 clears `out` first and accumulates with atomics.
 hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t st);
 

@@ -234,6 +234,80 @@ def test_conv_every_applicable_tile_64_channel_blocks(lib, cfg):
     assert ran >= 10
 
 
+# ---- the band kernel (window resident in LDS, depth split over the waves) ---------------------------
+BAND_SHAPES = [
+    CONFIGS["C4a"], CONFIGS["C2"],
+    ConvShape("band-k-tail", 3, 128, 9, 9, 70, 3, 3, 1, 1),              # ragged output channels, 81-pixel images
+    ConvShape("band-stride2", 1, 128, 13, 11, 64, 5, 5, 2, 2),           # 5x5 taps, stride 2: 50 steps -> falls outside (13 per wave)
+    ConvShape("band-1x5", 2, 128, 6, 20, 33, 1, 5, 1, 0),                # one kernel row, ten steps: 3,3,3,1 per wave
+    ConvShape("band-odd-blocks", 2, 192, 7, 7, 64, 3, 3, 1, 1),          # 27 steps: 7,7,7,6; 49 pixels
+    ConvShape("band-short-last", 2, 64, 23, 14, 40, 3, 3, 1, 1),         # 23 output rows in bands of 7/8: a short last band
+    ConvShape("band-one-step", 1, 64, 5, 5, 32, 1, 1, 1, 0),             # a single depth step: three idle waves
+    ConvShape("band-two-steps", 2, 128, 6, 6, 16, 1, 1, 1, 0),           # fewer steps than waves, K below a row block
+    ConvShape("band-wide", 1, 64, 4, 100, 64, 3, 3, 1, 1),               # one output row per band, 100 pixels of 128
+    ConvShape("band-stride3", 1, 64, 20, 19, 48, 3, 2, 3, 1),            # stride 3 in both directions
+    ConvShape("band-padded-channels", 1, 70, 10, 10, 32, 3, 3, 1, 1),    # 70 channels in two blocks of 64
+    ConvShape("band-deep", 1, 512, 6, 6, 32, 3, 3, 1, 1),                # 72 steps: beyond twelve per wave
+    ConvShape("band-too-wide", 1, 128, 4, 140, 64, 3, 3, 1, 1),          # an output row wider than the largest pixel tile
+]
+
+
+@pytest.mark.parametrize("cfg", BAND_SHAPES, ids=lambda c: c.name)
+def test_band_kernel_shapes(lib, cfg):
+    x, w = cfg.make() if cfg.name in CONFIGS else (uniform_int8(511, (cfg.N, cfg.C, cfg.H, cfg.W)), uniform_int8(512, (cfg.K, cfg.C, cfg.R, cfg.S)))
+    applies = lib.tile_applies(cfg.dims(), lib.LAYOUT_PACKED, 64, lib.TILE_BAND, 1)
+    assert applies == (cfg.name not in ("band-stride2", "band-deep", "band-too-wide"))
+    if not applies:
+        out = torch.zeros((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=DEV)
+        with pytest.raises(lib.ConvError) as e:
+            lib.conv2d_int8_packed(cfg.dims(), lib.LAYOUT_PACKED, 64, lib.pack_layout(dev(x), 64, cfg.pad),
+                                   lib.pack_weights(dev(w), lib.LAYOUT_PACKED, 64), out, tile=lib.TILE_BAND)
+        assert e.value.status == lib.ERR_UNSUPPORTED
+        return
+    assert 0 < lib.tile_lds_bytes(cfg.dims(), lib.LAYOUT_PACKED, 64, lib.TILE_BAND, 1) <= 160 * 1024
+    assert not lib.tile_applies(cfg.dims(), lib.LAYOUT_PACKED, 64, lib.TILE_BAND, 2)      # it has no depth split
+    want = direct.conv2d_int8(x, w, cfg.stride, cfg.pad)
+    got = run_layout(lib, cfg, x, w, "packed", 64, tile=lib.TILE_BAND)
+    assert np.array_equal(got, want), f"{cfg.name}: {np.count_nonzero(got != want)} mismatches"
+
+
+def test_band_kernel_other_layouts_and_dilation(lib):
+    """It takes 64-channel blocks only (PAD_ONLY over exactly 64 channels is such a layout); kernel taps a
+    dilation apart are address offsets into its window like any other."""
+    cfg = ConvShape("band-pad-only", 2, 60, 9, 12, 40, 3, 3, 1, 1)
+    x = uniform_int8(521, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(522, (cfg.K, cfg.C, cfg.R, cfg.S))
+    assert lib.tile_applies(cfg.dims(), lib.LAYOUT_PAD_ONLY, 0, lib.TILE_BAND, 1)
+    assert np.array_equal(run_layout(lib, cfg, x, w, "pad_only", 0, tile=lib.TILE_BAND), direct.conv2d_int8(x, w, 1, 1))
+    for lname, cb in (("packed", 16), ("packed", 32), ("im2col", 0)):
+        lay = {"packed": lib.LAYOUT_PACKED, "im2col": lib.LAYOUT_IM2COL}[lname]
+        assert not lib.tile_applies(cfg.dims(), lay, cb, lib.TILE_BAND, 1)
+    # the dilated layer of the benchmark's supplementary section at N = 4: the address-multiplier route picks
+    # its GEMM-stage kernel itself; whichever it is, the result is the definition's
+    dims, d = (4, 64, 28, 28, 64, 3, 3, 1, 2), 2
+    x = uniform_int8(523, dims[:4]); w = uniform_int8(524, (64, 64, 3, 3))
+    got = lib.conv2d_int8_dilated_direct(dims, d, dev(x), dev(w), 64)
+    assert np.array_equal(host(got), direct.conv2d_int8_dilated(x, w, 1, 2, d))
+
+
+def test_band_kernel_random_shapes(lib):
+    rng = np.random.default_rng(9101)
+    ran = 0
+    while ran < 40:
+        N = int(rng.integers(1, 4)); C = 64 * int(rng.integers(1, 5)); K = int(rng.choice([8, 32, 40, 64, 100]))
+        R = int(rng.integers(1, 4)); S = int(rng.integers(1, 4)); st = int(rng.integers(1, 3)); pad = int(rng.integers(0, 3))
+        H = int(rng.integers(3, 30)); W = int(rng.integers(3, 60))
+        if R > H + 2 * pad or S > W + 2 * pad:
+            continue
+        cfg = ConvShape(f"b{ran}", N, C, H, W, K, R, S, st, pad)
+        if not lib.tile_applies(cfg.dims(), lib.LAYOUT_PACKED, 64, lib.TILE_BAND, 1):
+            continue
+        ran += 1
+        x = uniform_int8(600 + ran, (N, C, H, W)); w = uniform_int8(700 + ran, (K, C, R, S))
+        got = run_layout(lib, cfg, x, w, "packed", 64, tile=lib.TILE_BAND)
+        want = direct.conv2d_int8(x, w, st, pad)
+        assert np.array_equal(got, want), f"{cfg.dims()}: {np.count_nonzero(got != want)} mismatches"
+
+
 @pytest.mark.parametrize("cfg", PAPER_SHAPES, ids=lambda c: c.name)
 def test_conv_paper_table_shapes(lib, cfg):
     x, w, want = oracle_conv(cfg)
