@@ -17,8 +17,11 @@
 //     partial sums are added up;
 //   * v_mfma_i32_16x16x64_i8: D[channel][pixel] += W[channel][64] . X[pixel][64], 16 pixels per
 //     block, so a 14-pixel image row wastes 2 columns, not 18.  A weight fragment (16 rows) is
-//     used for every pixel block, an activation fragment for both row blocks: 1 KB of LDS reads
-//     per 2 MFMAs;
+//     used for every pixel block, an activation fragment for both row blocks;
+//   * shifted fragments (stride 1, three taps per kernel row): a pixel block is 16 consecutive INPUT
+//     columns of one window row, holding 14 output columns.  Tap s of a kernel row needs, for output column q,
+//     input column q + s: the fragment of tap 0 moved s lanes within its 16-lane rows (DPP row shift, a
+//     register move).  LDS then serves one activation fragment per six MFMAs instead of per two;
 //   * the four waves' partial sums meet in LDS (each wave's region is its spent weight region);
 //     wave w adds up and stores every fourth 16 x 16 block, straight to NKPQ.
 // Both LDS operands are XOR-swizzled per 64-byte row ((row/4)%4 on the 16-byte chunk index), done
@@ -46,14 +49,19 @@ struct BandArgs {
     int depth, ksteps, kpw;      // bytes per weight row; 64-byte steps in all and per wave
     int PT, bands;               // output rows per band, bands per image
     int npix;                    // PT * Q
+    int tiled, CT, CTN;          // shifted-fragment form: output columns per block, blocks per output row
+    int wmax;                    // last pixel of a channel block's window
     int win_pieces, win_total;   // 1 KB pieces (16 pixels) of one channel block's window; of all blocks
+    int win_per_wave;            // ceil(win_total / 4)
     int wave_region;             // LDS bytes per wave: weights, later partial sums
     int tiles_k, tiles_m, m_fastest;
     int blk_bytes;               // one channel block of one image
     long long img_bytes;         // one image
     long long out_img;           // K*P*Q
-    unsigned mg_Q, mg_bands, mg_tiles_k, mg_tiles_m;
-    // window pixel offset of depth step w*kpw + t: its channel block's window + its kernel tap
+    unsigned mg_Q, mg_bands, mg_tiles_k, mg_tiles_m, mg_CTN, mg_win_pieces;
+    // window pixel offset of the wave's u-th group of depth steps (a group = the steps that share their
+    // activation fragments: one step, or in the shifted-fragment form the taps of one kernel row):
+    // its channel block's window + its kernel tap (row)
     int toff[BAND_WAVES][BAND_KPW_MAX];
 };
 
@@ -110,17 +118,28 @@ __device__ __forceinline__ void static_for(F &&f)
 
 // One wave per SIMD: a wave issues at most one instruction every four cycles, so every instruction in the
 // main loop competes with the MFMAs for issue slots.  Hence: every LDS address the loop uses is computed
-// before it (one register per depth step and pixel block -- registers are plentiful at this occupancy),
-// index arithmetic is 32-bit with wave-uniform bases kept in scalar registers, and per-wave tables come
-// from the host.
-// FULL: every wave multiplies exactly KPW steps (the depth is 4*KPW steps): no test around a step.
-template <int KPW, int PB, bool FULL>
+// before it (one register per group of depth steps and pixel block -- registers are plentiful at this
+// occupancy), index arithmetic is 32-bit with wave-uniform bases kept in scalar registers, and per-wave
+// tables come from the host.
+//
+// SROW: depth steps that share their activation fragments (1, or 3 = the taps of a kernel row in the
+// shifted-fragment form); GPW: such groups per wave; PB: pixel blocks per workgroup;
+// FULL: every wave multiplies exactly GPW groups (no test around a group).
+template <int SROW, int GPW, int PB, bool FULL>
 __global__ void __launch_bounds__(BAND_WAVES * 64, 1) conv_band_kernel(const BandArgs a)
 {
+    constexpr int KPW = SROW * GPW;  // depth steps per wave
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const unsigned lds0 = (unsigned)(size_t)((__attribute__((address_space(3))) unsigned char *)smem);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // Ask for every scalar argument now, in one batch: fetched one by one where first used, each costs a
+    // scalar-cache miss of a few hundred cycles on a kernel that runs for a few thousand.
+    asm volatile("" : : "s"(a.act), "s"(a.wq), "s"(a.out), "s"(a.K), "s"(a.P), "s"(a.Q), "s"(a.Wp), "s"(a.stride), "s"(a.depth),
+                 "s"(a.ksteps), "s"(a.kpw), "s"(a.PT), "s"(a.bands), "s"(a.npix), "s"(a.CT), "s"(a.CTN), "s"(a.wmax));
+    asm volatile("" : : "s"(a.win_pieces), "s"(a.win_total), "s"(a.win_per_wave), "s"(a.wave_region), "s"(a.tiles_k),
+                 "s"(a.tiles_m), "s"(a.m_fastest), "s"(a.blk_bytes), "s"(a.img_bytes), "s"(a.out_img), "s"(a.mg_Q),
+                 "s"(a.mg_bands), "s"(a.mg_tiles_k), "s"(a.mg_tiles_m), "s"(a.mg_CTN), "s"(a.mg_win_pieces));
 
     // workgroup -> (32 output channels, image, band)
     const int lid = band_xcd_id(blockIdx.x, gridDim.x);
@@ -136,6 +155,7 @@ __global__ void __launch_bounds__(BAND_WAVES * 64, 1) conv_band_kernel(const Ban
     const int p0 = band * a.PT, k0 = tk * BAND_TK;
     const int js = wave * a.kpw;
     const int nks = max(0, min(a.kpw, a.ksteps - js));  // depth steps of this wave
+    const int ng = nks / SROW;                          // groups of them (whole groups by construction)
 
     const int wave_off = wave * a.wave_region, win_off = BAND_WAVES * a.wave_region;  // LDS byte offsets
 
@@ -144,40 +164,43 @@ __global__ void __launch_bounds__(BAND_WAVES * 64, 1) conv_band_kernel(const Ban
     const int lrow = lane >> 2;
     const int lane_part = lrow * 64 + (((lane & 3) ^ ((lane >> 4) & 3)) << 4);
 
-    // ---- window: pieces wave, wave+4, ... of all channel blocks' windows ------------------------------
+    // ---- window: every wave fetches a contiguous quarter of the pieces of all channel blocks' windows ----
     {
         const int last = a.blk_bytes - 16;  // rows past the padded image (a short last band) read this
-        const int row0 = p0 * a.stride * a.Wp * 64 + lane_part;
-        const int8_t *blk = a.act + (size_t)n * a.img_bytes;  // channel block of the next piece
-        int i = wave;                                        // its piece within that block's window
-        while (i >= a.win_pieces) {
-            i -= a.win_pieces;
-            blk += a.blk_bytes;
-        }
-        unsigned dst = lds0 + (unsigned)win_off + (unsigned)wave * 1024u;
-        for (int g = wave; g < a.win_total; g += BAND_WAVES) {
-            band_dma16(blk, (unsigned)min(row0 + i * 1024, last), dst);
-            dst += BAND_WAVES * 1024u;
-            i += BAND_WAVES;
-            while (i >= a.win_pieces) {
-                i -= a.win_pieces;
+        const int per = a.win_per_wave, g0 = wave * per, g1 = min(g0 + per, a.win_total);
+        int b = bdiv_small(g0, a.mg_win_pieces), i = g0 - b * a.win_pieces;  // channel block, piece of its window
+        const int8_t *blk = a.act + (size_t)n * a.img_bytes + (size_t)b * a.blk_bytes;
+        int off = p0 * a.stride * a.Wp * 64 + lane_part + i * 1024;
+        unsigned dst = lds0 + (unsigned)win_off + (unsigned)g0 * 1024u;
+        for (int g = g0; g < g1; ++g) {
+            band_dma16(blk, (unsigned)min(off, last), dst);
+            dst += 1024u;
+            off += 1024;
+            if (++i == a.win_pieces) {
+                i = 0;
+                off -= a.win_pieces * 1024;
                 blk += a.blk_bytes;
             }
         }
     }
-    // ---- this wave's weights: exactly 2*KPW transfers (steps past the last repeat it).  A transfer
-    // occupies the memory pipe for some 60 cycles during which the wave can issue other work, so the LDS
-    // addresses the main loop will use are computed in between: one register per depth step and pixel block.
+    // ---- where the lane's pixel of every block sits in a window (tap (0, 0)) ---------------------------
     const int col = lane & 15, grp = lane >> 4;  // pixel within a block / 16-byte chunk of a depth step
-    int wbase[PB];  // byte address of the lane's pixel in the window at tap (0, 0); swizzle bits clear
+    int wbase[PB];
 #pragma unroll
     for (int pb = 0; pb < PB; ++pb) {
-        const int i = pb * 16 + col;
-        const int pr = bdiv_small(i, a.mg_Q), q = i - pr * a.Q;
-        const bool valid = i < a.npix && p0 + pr < a.P;
-        wbase[pb] = valid ? (pr * a.stride) * a.Wp + q * a.stride : 0;
+        if (SROW > 1) {  // block = 16 consecutive input columns of one window row
+            const int pr = bdiv_small(pb, a.mg_CTN), ct = pb - pr * a.CTN;
+            wbase[pb] = min(pr * a.Wp + ct * a.CT + col, a.wmax);
+        } else {        // block = 16 consecutive output pixels of the band, row-major
+            const int i = pb * 16 + col;
+            const int pr = bdiv_small(i, a.mg_Q), q = i - pr * a.Q;
+            const bool valid = i < a.npix && p0 + pr < a.P;
+            wbase[pb] = valid ? (pr * a.stride) * a.Wp + q * a.stride : 0;
+        }
     }
-    int baddr[KPW][PB];  // activation fragment of pixel block pb at depth step t
+    // ---- this wave's weights: exactly 2*KPW transfers (steps past the last repeat it), and in between
+    // the LDS addresses of the main loop: one register per group and pixel block ---------------------------
+    int baddr[GPW][PB];
     {
         const unsigned row_lo = (unsigned)(min(k0 + lrow, a.K - 1) * a.depth) + (unsigned)(lane_part & 63);
         const unsigned row_hi = (unsigned)(min(k0 + 16 + lrow, a.K - 1) * a.depth) + (unsigned)(lane_part & 63);
@@ -187,12 +210,14 @@ __global__ void __launch_bounds__(BAND_WAVES * 64, 1) conv_band_kernel(const Ban
             const int8_t *step = a.wq + (size_t)min(js + t, a.ksteps - 1) * 64;
             band_dma16(step, row_lo, dst + (unsigned)(t * 2) * 1024u);
             band_dma16(step, row_hi, dst + (unsigned)(t * 2 + 1) * 1024u);
-            const int tap = a.toff[wave][t];
+            if (t % SROW == 0) {
+                const int tap = a.toff[wave][t / SROW];
 #pragma unroll
-            for (int pb = 0; pb < PB; ++pb) {
-                const int w = wbase[pb] + tap;
-                baddr[t][pb] = win_off + (w << 6) + ((grp ^ ((w >> 2) & 3)) << 4);
-                asm volatile("" : "+v"(baddr[t][pb]));  // keep it in its register: recomputing it in the loop costs issue slots
+                for (int pb = 0; pb < PB; ++pb) {
+                    const int w = wbase[pb] + tap;
+                    baddr[t / SROW][pb] = win_off + (w << 6) + ((grp ^ ((w >> 2) & 3)) << 4);
+                    asm volatile("" : "+v"(baddr[t / SROW][pb]));  // keep it in its register: recomputing it in the loop costs issue slots
+                }
             }
         }
     }
@@ -201,8 +226,8 @@ __global__ void __launch_bounds__(BAND_WAVES * 64, 1) conv_band_kernel(const Ban
     auto read_a = [&](int t, int rb) -> v4i {
         return *reinterpret_cast<const v4i *>(__builtin_assume_aligned(smem + afrag + (t * 2 + rb) * 1024, 16));
     };
-    auto read_b = [&](int t, int pb) -> v4i {
-        return *reinterpret_cast<const v4i *>(__builtin_assume_aligned(smem + baddr[t][pb], 16));
+    auto read_b = [&](int u, int pb) -> v4i {
+        return *reinterpret_cast<const v4i *>(__builtin_assume_aligned(smem + baddr[u][pb], 16));
     };
 
     v4i acc[2][PB];
@@ -214,36 +239,47 @@ __global__ void __launch_bounds__(BAND_WAVES * 64, 1) conv_band_kernel(const Ban
     band_wait_dma<2 * KPW>();  // every window piece this wave asked for has landed ...
     band_barrier();            // ... and everyone else's
 
-    // ---- main loop: no barrier.  All activation fragments of step t+1 are requested before step t
-    // multiplies, its weight fragments half-way through (once their transfers have landed). -----------------
+    // ---- main loop: no barrier.  All activation fragments of group u+1 are requested before group u
+    // multiplies; the weight fragments of step t+1 half-way through step t (once their transfers have landed).
     v4i af[2][2], bq[2][PB];
 #pragma unroll
     for (int pb = 0; pb < PB; ++pb) bq[0][pb] = read_b(0, pb);
     band_wait_dma<2 * (KPW - 1)>();
     af[0][0] = read_a(0, 0);
     af[0][1] = read_a(0, 1);
-    static_for<0, KPW>([&](auto tc) {
-        constexpr int t = decltype(tc)::value;
-        if (FULL || t < nks) {
-            if constexpr (t + 1 < KPW) {
+    static_for<0, GPW>([&](auto uc) {
+        constexpr int u = decltype(uc)::value;
+        if (FULL || u < ng) {
+            if constexpr (u + 1 < GPW) {
 #pragma unroll
-                for (int pb = 0; pb < PB; ++pb) bq[(t + 1) & 1][pb] = read_b(t + 1, pb);  // (unused past the last step)
+                for (int pb = 0; pb < PB; ++pb) bq[(u + 1) & 1][pb] = read_b(u + 1, pb);  // (unused past the last group)
                 __builtin_amdgcn_sched_barrier(0);
             }
+            static_for<0, SROW>([&](auto sc) {
+                constexpr int s = decltype(sc)::value, t = u * SROW + s;
 #pragma unroll
-            for (int pb = 0; pb < PB; ++pb) {
-                acc[0][pb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[t & 1][0], bq[t & 1][pb], acc[0][pb], 0, 0, 0);
-                acc[1][pb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[t & 1][1], bq[t & 1][pb], acc[1][pb], 0, 0, 0);
-                if constexpr (t + 1 < KPW) {
-                    if (pb == PB / 2) {
-                        __builtin_amdgcn_sched_barrier(0);  // the MFMAs above stay above the wait
-                        band_wait_dma<2 * (KPW - 2 - t)>();
-                        af[(t + 1) & 1][0] = read_a(t + 1, 0);
-                        af[(t + 1) & 1][1] = read_a(t + 1, 1);
-                        __builtin_amdgcn_sched_barrier(0);
+                for (int pb = 0; pb < PB; ++pb) {
+                    // tap s of the kernel row reads the input column s places to the right: the same fragment,
+                    // shifted s lanes down within its 16-lane row (row_shl: a lane takes the value of the lane
+                    // s places up; lanes that would reach past the row get 0 and hold no output column)
+                    v4i bf = bq[u & 1][pb];
+                    if constexpr (s > 0) {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) bf[v] = __builtin_amdgcn_update_dpp(0, bf[v], 0x100 + s, 0xF, 0xF, true);
+                    }
+                    acc[0][pb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[t & 1][0], bf, acc[0][pb], 0, 0, 0);
+                    acc[1][pb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[t & 1][1], bf, acc[1][pb], 0, 0, 0);
+                    if constexpr (t + 1 < KPW) {
+                        if (pb == PB / 2) {
+                            __builtin_amdgcn_sched_barrier(0);  // the MFMAs above stay above the wait
+                            band_wait_dma<2 * (KPW - 2 - t)>();
+                            af[(t + 1) & 1][0] = read_a(t + 1, 0);
+                            af[(t + 1) & 1][1] = read_a(t + 1, 1);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
                     }
                 }
-            }
+            });
         }
     });
 
@@ -257,43 +293,63 @@ __global__ void __launch_bounds__(BAND_WAVES * 64, 1) conv_band_kernel(const Ban
         for (int i = 0; i < 2 * PB; ++i) mine[i * 64 + lane] = acc[i / PB][i % PB];
     }
     band_barrier();
-    int32_t *const out_n = a.out + (size_t)n * a.out_img;
+    // D block: column = pixel = lane%16, row = channel = 4*(lane/16) + v.  Output offset = a wave-uniform part
+    // (image, row block, pixel block) + a per-lane part computed once; four planes = four scalar bases.
+    // Every wave walks the same number of slots (a slot past the last block stores nothing), so the loop has
+    // no exits: with one wave per SIMD every branch and every scalar instruction costs an issue slot.
     const int plane = a.P * a.Q;
+    int32_t *const out0 = a.out + (size_t)n * a.out_img + (size_t)k0 * plane;
+    int32_t *const out1 = out0 + plane, *const out2 = out1 + plane, *const out3 = out2 + plane;
+    const int lane_off = 4 * grp * plane + col;
+    const int kleft = a.K - k0 - 4 * grp;   // output channels from this lane's first one to the last
+    const bool k_whole = k0 + BAND_TK <= a.K;  // wave-uniform: no channel of the tile lies past the last
+    constexpr int SLOTS = (2 * PB + BAND_WAVES - 1) / BAND_WAVES;
 #pragma unroll
-    for (int m = 0; m < (2 * PB + BAND_WAVES - 1) / BAND_WAVES; ++m) {
-        const int i = wave + BAND_WAVES * m;  // wave-uniform
-        if (i >= 2 * PB) break;
+    for (int m = 0; m < SLOTS; ++m) {
+        const int i = wave + BAND_WAVES * m;  // wave-uniform; the regions hold SLOTS*4 blocks
         const int rb = i >= PB ? 1 : 0, pb = i - rb * PB;
-        const v4i *part = reinterpret_cast<const v4i *>(__builtin_assume_aligned(smem + i * 1024 + lane * 16, 16));
-        v4i sum = part[0];
+        v4i sum = *reinterpret_cast<const v4i *>(__builtin_assume_aligned(smem + i * 1024 + lane * 16, 16));
 #pragma unroll
         for (int o = 1; o < BAND_WAVES; ++o)
             sum += *reinterpret_cast<const v4i *>(__builtin_assume_aligned(smem + o * a.wave_region + i * 1024 + lane * 16, 16));
-        // D block: column = pixel = lane%16, row = channel = 4*(lane/16) + v
-        const int px = pb * 16 + col;
-        const int pr = bdiv_small(px, a.mg_Q), q = px - pr * a.Q;
-        if (px >= a.npix || p0 + pr >= a.P) continue;
-        const int k = k0 + rb * 16 + 4 * grp;
-        const unsigned off = (unsigned)(k * plane + (p0 + pr) * a.Q + q);
-        if (k + 3 < a.K) {
-            out_n[off] = sum[0];
-            out_n[off + (unsigned)plane] = sum[1];
-            out_n[off + 2u * (unsigned)plane] = sum[2];
-            out_n[off + 3u * (unsigned)plane] = sum[3];
+        unsigned off;
+        bool valid;
+        if (SROW > 1) {
+            const int pr = bdiv_small(pb, a.mg_CTN), q0 = (pb - pr * a.CTN) * a.CT;  // wave-uniform
+            const int cols = (i < 2 * PB && pr < a.PT && p0 + pr < a.P) ? min(a.CT, a.Q - q0) : 0;
+            valid = col < cols;
+            off = (unsigned)(rb * 16 * plane + (p0 + pr) * a.Q + q0 + lane_off);
         } else {
-#pragma unroll
-            for (int v = 0; v < 4; ++v)
-                if (k + v < a.K) out_n[off + (unsigned)(v * plane)] = sum[v];
+            const int px = pb * 16 + col;
+            const int pr = bdiv_small(px, a.mg_Q), q = px - pr * a.Q;
+            valid = i < 2 * PB && px < a.npix && p0 + pr < a.P;
+            off = (unsigned)(rb * 16 * plane + (p0 + pr) * a.Q + q + lane_off - col);
+        }
+        if (k_whole) {
+            if (valid) {
+                out0[off] = sum[0];
+                out1[off] = sum[1];
+                out2[off] = sum[2];
+                out3[off] = sum[3];
+            }
+        } else {
+            const int kl = kleft - rb * 16;
+            if (valid && kl > 0) out0[off] = sum[0];
+            if (valid && kl > 1) out1[off] = sum[1];
+            if (valid && kl > 2) out2[off] = sum[2];
+            if (valid && kl > 3) out3[off] = sum[3];
         }
     }
 }
 
 constexpr int kBandPB[] = {4, 7, 8};
-constexpr int kBandKPW[] = {3, 6, 9, 12};
+constexpr int kBandGroups1[] = {3, 6, 9, 12};  // groups per wave, one step per group
+constexpr int kBandGroups3[] = {1, 2, 3, 4};   // groups per wave, three steps per group
 
 struct BandPlan {
     BandArgs a;
-    int pb, kpw_slot;  // template arguments to launch
+    int srow, gpw, pb;  // template arguments to launch
+    bool full;
     size_t lds;
     int grid;
 };
@@ -308,21 +364,28 @@ bool band_plan(const GemmProblem &g, BandPlan *bp)
     const int P = g.PQ / g.Q, Q = g.Q, dil = g.dil > 0 ? g.dil : 1;
     const long long ksteps = (long long)g.Cb * g.R * g.S;
     if (ksteps * 64 != g.depth) return false;
-    const int kpw = (int)((ksteps + BAND_WAVES - 1) / BAND_WAVES);
-    int KPW = 0;
-    for (int c : kBandKPW)
-        if (!KPW && c >= kpw) KPW = c;
-    if (!KPW) return false;
     if (g.M % g.PQ) return false;
     const int N = g.M / g.PQ;
+    // Shifted fragments: stride 1, dense taps, three of them per kernel row; a block is then 16 input
+    // columns that hold CT = 14 output columns.
+    const bool tiled = g.stride == 1 && dil == 1 && g.S == 3;
+    const int srow = tiled ? 3 : 1;
+    const int CT = tiled ? 16 - (g.S - 1) : 16, CTN = tiled ? (Q + CT - 1) / CT : 1;
+    const long long groups = ksteps / srow;  // groups of steps that share their activation fragments
+    const int gpw = (int)((groups + BAND_WAVES - 1) / BAND_WAVES);
+    int GPW = 0;
+    for (int c : tiled ? kBandGroups3 : kBandGroups1)
+        if (!GPW && c >= gpw) GPW = c;
+    if (!GPW) return false;
+    const int KPW = GPW * srow, kpw = gpw * srow;
     // pixel blocks: the choice that pads an image's pixels least (ties: fewer blocks)
     int PB = 0, PT = 0;
     long long best = 0;
     for (int c : kBandPB) {
-        int pt = c * 16 / Q;
+        int pt = tiled ? c / CTN : c * 16 / Q;
         if (pt < 1) continue;
         if (pt > P) pt = P;
-        const long long padded = (long long)((P + pt - 1) / pt) * c * 16;
+        const long long padded = (long long)((P + pt - 1) / pt) * c;
         if (!PB || padded < best) {
             PB = c;
             PT = pt;
@@ -333,7 +396,7 @@ bool band_plan(const GemmProblem &g, BandPlan *bp)
     PT = (P + (P + PT - 1) / PT - 1) / ((P + PT - 1) / PT);  // same number of bands, of even height
     const long long WR = (long long)(PT - 1) * g.stride + (long long)(g.R - 1) * dil + 1;
     const long long win_pieces = (WR * g.Wp + 15) / 16;
-    const long long red = 2LL * PB * 1024, wbytes = (long long)KPW * 2048;
+    const long long red = (2LL * PB + BAND_WAVES - 1) / BAND_WAVES * BAND_WAVES * 1024, wbytes = (long long)KPW * 2048;  // whole slots
     const long long wave_region = red > wbytes ? red : wbytes;
     const long long lds = BAND_WAVES * wave_region + g.Cb * win_pieces * 1024;
     if (lds > (long long)BAND_LDS_LIMIT) return false;
@@ -342,7 +405,6 @@ bool band_plan(const GemmProblem &g, BandPlan *bp)
     if (tiles_k * tiles_m > 0x7FFFFFFFLL) return false;
     if ((long long)g.Hp * g.Wp * 64 > 0x7FFFFFFFLL || (long long)(g.Cb * win_pieces + 1) * 16 + WR * g.Wp > 0x7FFFFFFFLL)
         return false;
-
     if ((long long)g.K * g.depth > 0x7FFFFFFFLL || (long long)g.K * P * Q > 0x3FFFFFFFLL) return false;  // 32-bit offsets
 
     BandArgs &a = bp->a;
@@ -360,8 +422,13 @@ bool band_plan(const GemmProblem &g, BandPlan *bp)
     a.PT = PT;
     a.bands = (int)bands;
     a.npix = PT * Q;
+    a.tiled = tiled;
+    a.CT = CT;
+    a.CTN = CTN;
+    a.wmax = PT * g.Wp - 1;  // a clamped pixel plus any tap row stays inside the window
     a.win_pieces = (int)win_pieces;
     a.win_total = (int)(g.Cb * win_pieces);
+    a.win_per_wave = (a.win_total + BAND_WAVES - 1) / BAND_WAVES;
     a.wave_region = (int)wave_region;
     a.tiles_k = (int)tiles_k;
     a.tiles_m = (int)tiles_m;
@@ -369,11 +436,11 @@ bool band_plan(const GemmProblem &g, BandPlan *bp)
     a.img_bytes = (long long)a.blk_bytes * g.Cb;
     a.out_img = (long long)g.K * P * Q;
     for (int w = 0; w < BAND_WAVES; ++w)
-        for (int t = 0; t < BAND_KPW_MAX; ++t) {
-            long long j = (long long)w * kpw + t;
+        for (int u = 0; u < BAND_KPW_MAX; ++u) {
+            long long j = ((long long)w * gpw + u) * srow;  // first step of the group
             if (j > ksteps - 1) j = ksteps - 1;
             const int b = (int)(j / (g.R * g.S)), rs = (int)(j % (g.R * g.S));
-            a.toff[w][t] = b * (int)win_pieces * 16 + ((rs / g.S) * g.Wp + rs % g.S) * dil;
+            a.toff[w][u] = b * (int)win_pieces * 16 + ((rs / g.S) * g.Wp + (tiled ? 0 : rs % g.S)) * dil;
         }
     {
         // each XCD (own L2) runs a contiguous eighth of the list: order it so that what one XCD pulls in
@@ -392,17 +459,21 @@ bool band_plan(const GemmProblem &g, BandPlan *bp)
     a.mg_bands = magic_of(bands);
     a.mg_tiles_k = magic_of(tiles_k);
     a.mg_tiles_m = magic_of(tiles_m);
+    a.mg_CTN = magic_of(CTN);
+    a.mg_win_pieces = magic_of(win_pieces);
+    bp->srow = srow;
+    bp->gpw = GPW;
     bp->pb = PB;
-    bp->kpw_slot = KPW;
+    bp->full = groups == (long long)BAND_WAVES * GPW;
     bp->lds = (size_t)lds;
     bp->grid = (int)(tiles_k * tiles_m);
     return true;
 }
 
-template <int KPW, int PB, bool FULL>
+template <int SROW, int GPW, int PB, bool FULL>
 hipError_t launch_band(const BandPlan &bp, hipStream_t st)
 {
-    auto kern = conv_band_kernel<KPW, PB, FULL>;
+    auto kern = conv_band_kernel<SROW, GPW, PB, FULL>;
     static bool raised = false;  // dynamic-LDS ceiling granted, per instantiation
     if (bp.lds > 64 * 1024 && !raised) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -453,13 +524,13 @@ hipError_t launch_band_conv(const GemmProblem &g, hipStream_t st)
 {
     BandPlan bp;
     if (!band_plan(g, &bp)) return hipErrorInvalidValue;
-    const bool full = bp.a.ksteps == BAND_WAVES * bp.kpw_slot;
-#define C2I8_BAND_CASE(KPW, PB) \
-    if (bp.kpw_slot == KPW && bp.pb == PB) return full ? launch_band<KPW, PB, true>(bp, st) : launch_band<KPW, PB, false>(bp, st);
-    C2I8_BAND_CASE(3, 4) C2I8_BAND_CASE(3, 7) C2I8_BAND_CASE(3, 8)
-    C2I8_BAND_CASE(6, 4) C2I8_BAND_CASE(6, 7) C2I8_BAND_CASE(6, 8)
-    C2I8_BAND_CASE(9, 4) C2I8_BAND_CASE(9, 7) C2I8_BAND_CASE(9, 8)
-    C2I8_BAND_CASE(12, 4) C2I8_BAND_CASE(12, 7) C2I8_BAND_CASE(12, 8)
+#define C2I8_BAND_CASE(SROW, GPW, PB)                       \
+    if (bp.srow == SROW && bp.gpw == GPW && bp.pb == PB)    \
+        return bp.full ? launch_band<SROW, GPW, PB, true>(bp, st) : launch_band<SROW, GPW, PB, false>(bp, st);
+#define C2I8_BAND_PBS(SROW, GPW) C2I8_BAND_CASE(SROW, GPW, 4) C2I8_BAND_CASE(SROW, GPW, 7) C2I8_BAND_CASE(SROW, GPW, 8)
+    C2I8_BAND_PBS(1, 3) C2I8_BAND_PBS(1, 6) C2I8_BAND_PBS(1, 9) C2I8_BAND_PBS(1, 12)
+    C2I8_BAND_PBS(3, 1) C2I8_BAND_PBS(3, 2) C2I8_BAND_PBS(3, 3) C2I8_BAND_PBS(3, 4)
+#undef C2I8_BAND_PBS
 #undef C2I8_BAND_CASE
     return hipErrorInvalidValue;
 }
