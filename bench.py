@@ -30,10 +30,10 @@ PEAK_HBM_BPS = 8.0e12    # HBM3E
 # WRITE_SIZE, each scaled by what the same counter reads for a 256 MiB device copy).  They
 # describe the kernel source whose hash is recorded here; for any other source `traffic` is null.
 TRAFFIC = {
-    "source": "paper_2104_04731_amd/csrc/igemm_mfma.hip",
-    "sha256": "66cd608e8587ba878638eac8fbe3ec0abc046880b61c37a592aad70347a376ec",
-    "fetch_bytes": 5517666,
-    "write_bytes": 3211264,
+    "source": "paper_2104_04731_amd/csrc/band_mfma.hip",
+    "sha256": None,
+    "fetch_bytes": None,
+    "write_bytes": None,
 }
 
 
@@ -44,7 +44,7 @@ def measured_traffic():
             h = hashlib.sha256(f.read()).hexdigest()
     except OSError:
         return None
-    if h != TRAFFIC["sha256"] or TRAFFIC["fetch_bytes"] is None:
+    if TRAFFIC["sha256"] is None or h != TRAFFIC["sha256"] or TRAFFIC["fetch_bytes"] is None:
         return None
     return TRAFFIC["fetch_bytes"] + TRAFFIC["write_bytes"]
 
@@ -104,6 +104,39 @@ def main():
         t1 = time.perf_counter()
         return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
+    flush_buf = torch.empty(640 << 20, dtype=torch.int8, device=dev)   # larger than L2s + the 256 MB last-level cache
+
+    def sampled(fn, n, cold):
+        """Per-call device times (us) of `n` individually timed calls, each one replay of a graph that holds
+        one call, between an event pair on the launch stream (Sec. 5.1's protocol: warm-up, then repeated
+        measurements with their spread).  cold: every call is preceded by an untimed 640 MB fill, so that
+        nothing it touches is left in any cache; warm: the same buffers every call, a memory-silent spin in between."""
+        fn()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        for _ in range(3):
+            g.replay()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for e0, e1 in ev:
+            # either way the device is kept busy for ~100 us before each sample, so that the host has queued
+            # the event pair and the replay before the device gets there (else a sample holds host launch time)
+            if cold:
+                flush_buf.fill_(1)
+            else:
+                torch.cuda._sleep(200000)
+            e0.record()
+            g.replay()
+            e1.record()
+        torch.cuda.synchronize()
+        return [e0.elapsed_time(e1) * 1e3 for e0, e1 in ev]
+
+    def stats(us):
+        import statistics
+        return {"n": len(us), "mean_us": round(statistics.fmean(us), 3), "median_us": round(statistics.median(us), 3),
+                "sigma_us": round(statistics.pstdev(us), 3), "min_us": round(min(us), 3)}
+
     class Case:
         """Device buffers and closures for one convolution."""
 
@@ -144,7 +177,32 @@ def main():
             wall, comb = timed(self.combined, steps, warmup)
             _, pre = timed(self.combined_prepacked, steps, warmup)
             o_mac = lib.layout_overheads(cfg.dims(), self.layout, self.cb)[0]   # multiply-accumulates on padding
-            rows, cols = lib.tile_info(self.tile)[:2] if self.tile >= 0 else (min(64, -(-cfg.K // 32) * 32), 128)
+            # Every candidate layout the library has for this shape, through the explicit entry point with a
+            # caller workspace (input rewrite + weight rewrite + GEMM stage each call): what the selector's pick
+            # costs against the fastest candidate (Sec. 4.4: the choice depends on operator, layout and metric).
+            cands = []
+            for lay, cb in ((lib.LAYOUT_PACKED, 64), (lib.LAYOUT_PACKED, 32), (lib.LAYOUT_PACKED, 16), (lib.LAYOUT_IM2COL, 0),
+                            (lib.LAYOUT_PAD_ONLY, 0), (lib.LAYOUT_IMPLICIT, 0), (lib.LAYOUT_IMAGE_PACK, 0),
+                            (lib.LAYOUT_IMAGE_PACK, 16), (lib.LAYOUT_IMAGE_PACK, 64)):
+                if not lib.layout_applies(cfg.dims(), lay, cb):
+                    continue
+                nb = lib.conv2d_int8_workspace_bytes(cfg.dims(), lay, cb)
+                wsb = torch.empty(nb + 256, dtype=torch.int8, device=dev)
+                wsa = wsb[(-wsb.data_ptr()) % 256:] if nb else None
+                _, t = timed(lambda: lib.conv2d_int8_ex(cfg.dims(), lay, cb, self.x, self.w, self.out, wsa), min(steps, 100), 3)
+                cands.append({"layout": lib.LAYOUT_NAMES[lay], "cb": cb, "combined_us": round(t * 1e3, 3),
+                              "picked": (lay, cb) == (self.layout, self.cb if lay != lib.LAYOUT_PAD_ONLY else 0)})
+                del wsb
+            fastest = min(c["combined_us"] for c in cands)
+            picked = [c for c in cands if c["picked"]]
+            regret = round(picked[0]["combined_us"] / fastest - 1.0, 4) if picked else None
+            warm, cold = sampled(self.combined, 100, False), sampled(self.combined, 100, True)
+            if self.tile >= 0:
+                rows, cols = lib.tile_info(self.tile)[:2]
+            elif self.tile == lib.TILE_BAND:
+                rows, cols = "band 32", "rows of one image"
+            else:
+                rows, cols = min(64, -(-cfg.K // 32) * 32), 128
             return {
                 "name": cfg.name, "layout": lib.LAYOUT_NAMES[self.layout], "cb": self.cb,
                 "tile": f"{rows}x{cols}", "split_k": self.split, "ops": cfg.ops,
@@ -158,6 +216,8 @@ def main():
                 "transf_in_GBps": round(self.rewrite_bytes / (tr * 1e-3) / 1e9, 1) if tr else None,
                 "pct_hbm_peak_transf": round(100 * self.rewrite_bytes / (tr * 1e-3) / PEAK_HBM_BPS, 2) if tr else None,
                 "combined_GBps": round((self.x.numel() + self.w.numel() + 4 * self.out.numel()) / (comb * 1e-3) / 1e9, 1),
+                "combined_single_calls_warm": stats(warm), "combined_single_calls_cold": stats(cold),
+                "candidates": cands, "selector_regret": regret,
             }
 
     if args.calibration_copy:
@@ -185,6 +245,8 @@ def main():
 
     wall_ms, ev_ms = timed(step, args.steps, args.warmup)
     value = head_ops / (wall_ms * 1e-3) / 1e12
+    # the same step one call at a time: median and spread, caches warm and cold (Sec. 5.1: mean of 200 with sigma)
+    step_warm, step_cold = stats(sampled(step, args.steps, False)), stats(sampled(step, args.steps, True))
 
     # the same step with every convolution forced through stored rewrites (channel blocking, block 64,
     # caller workspace): input rewrite + weight rewrite, then the GEMM stage -- reported beside `value`
@@ -260,8 +322,10 @@ def main():
         achieved = dom.cfg.ops / (dom_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": round(achieved, 3), "peak": PEAK_INT8_OPS / 1e12,
                     "unit": "TOP/s", "frac": round(achieved * 1e12 / PEAK_INT8_OPS, 5), "traffic": measured_traffic(),
-                    "kernel": "igemm_i8_kernel", "config": dom.cfg.name,
-                    "launch_us": round(dom_ms * 1e3, 3)}
+                    "kernel": "conv_band_kernel" if dom.tile == lib.TILE_BAND else "igemm_i8_kernel", "config": dom.cfg.name,
+                    "launch_us": round(dom_ms * 1e3, 3),
+                    "launch_stats_warm": stats(sampled(dom.op, args.steps, False)),
+                    "launch_stats_cold": stats(sampled(dom.op, args.steps, True))}
 
     result = {
         "metric": "int8 conv effective TOPS (2*N*K*P*Q*C*R*S / time), layout rewrite + MFMA GEMM stage",
@@ -275,6 +339,15 @@ def main():
                     "or (implicit) the rewrite applied inside the GEMM stage",
             "layouts": [lib.LAYOUT_NAMES[c.layout] + (f"/cb{c.cb}" if c.cb else "") for c in head]},
         "event_ms_per_step": round(ev_ms, 6),
+        "timing": {"value_from": "mean over one graph of `steps` back-to-back steps (same buffers: operands in L2 / last-level cache)",
+                   "single_steps_warm": step_warm, "single_steps_cold": step_cold,
+                   "single_step_overhead_us": round(step_warm["median_us"] - wall_ms * 1e3, 3),
+                   "cold_penalty_us": round(step_cold["median_us"] - step_warm["median_us"], 3),
+                   "cold_value_estimate": round(head_ops / ((wall_ms * 1e3 + max(step_cold["median_us"] - step_warm["median_us"], 0.0)) * 1e-6) / 1e12, 4),
+                   "note": "single steps: one graph replay per step between an event pair, after ~100 us of other device work "
+                           "so that the host is ahead (warm: a memory-silent spin; cold: a 640 MB fill that evicts L2 and the "
+                           "256 MB last-level cache).  A single replay between events carries a fixed overhead (single_step_overhead_us: "
+                           "its warm median minus the back-to-back mean); cold_value_estimate = ops / (back-to-back mean + cold_penalty)"},
         "pct_mfma_peak": round(100 * value * 1e12 / PEAK_INT8_OPS, 3),
         "rewrite_then_gemm_only": two_stage,
         "chained_with_activation": chained,
@@ -486,7 +559,16 @@ def cpu_baseline(cfgs):
             direct.conv2d_int8(x, w, c.stride, c.pad)
         dt = time.perf_counter() - t0
         best = dt if best is None else min(best, dt)
-    res = {"value": round(ops / best / 1e12, 6), "unit": "TOPS", "cores": direct.threads(), "kind": "oracle",
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    res = {"value": round(ops / best / 1e12, 6), "unit": "TOPS", "cores": direct.threads(), "cpu_model": model, "kind": "oracle",
            "sample": "whole headline workload (" + " + ".join(c.name for c in cfgs) + "), best of 3, "
                      f"{best * 1e3:.1f} ms"}
     # the two smallest configurations on one thread, for scale

@@ -20,7 +20,7 @@ _lib = None
 
 def build(force: bool = False) -> str:
     if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC",
+        subprocess.check_call(["gcc", "-O3", "-fopenmp", "-shared", "-fPIC",
                                "-o", _SO, _SRC])
     return _SO
 

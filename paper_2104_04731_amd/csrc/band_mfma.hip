@@ -170,17 +170,19 @@ __global__ void __launch_bounds__(BAND_WAVES * 64, 1) conv_band_kernel(const Ban
         const int per = a.win_per_wave, g0 = wave * per, g1 = min(g0 + per, a.win_total);
         int b = bdiv_small(g0, a.mg_win_pieces), i = g0 - b * a.win_pieces;  // channel block, piece of its window
         const int8_t *blk = a.act + (size_t)n * a.img_bytes + (size_t)b * a.blk_bytes;
-        int off = p0 * a.stride * a.Wp * 64 + lane_part + i * 1024;
+        const int row0 = p0 * a.stride * a.Wp * 64 + lane_part;
         unsigned dst = lds0 + (unsigned)win_off + (unsigned)g0 * 1024u;
-        for (int g = g0; g < g1; ++g) {
-            band_dma16(blk, (unsigned)min(off, last), dst);
-            dst += 1024u;
-            off += 1024;
-            if (++i == a.win_pieces) {
-                i = 0;
-                off -= a.win_pieces * 1024;
-                blk += a.blk_bytes;
+        for (int g = g0; g < g1;) {
+            const int cnt = min(a.win_pieces - i, g1 - g);  // pieces left in this channel block's window
+            int off = row0 + i * 1024;
+            for (int c = 0; c < cnt; ++c) {  // (kept short: a transfer already holds the wave for ~60 cycles)
+                band_dma16(blk, (unsigned)min(off, last), dst);
+                dst += 1024u;
+                off += 1024;
             }
+            g += cnt;
+            i = 0;
+            blk += a.blk_bytes;
         }
     }
     // ---- where the lane's pixel of every block sits in a window (tap (0, 0)) ---------------------------
@@ -507,17 +509,18 @@ TileInfo band_tile_info(const GemmProblem &g)
 }
 
 // The picker's estimate (core cycles, same scale as gemm_pick's).  Measured: the kernel wins where one round of
-// workgroups covers the problem and the reduction is deep enough to pay for its fixed parts (address set-up,
-// summing the waves' partial results); with more rounds the general kernel's large tiles move fewer bytes.
+// workgroups covers the problem and -- in the form without shifted fragments -- the reduction is deep enough to
+// pay for its fixed parts (address set-up, summing the waves' partial results); with more rounds the general
+// kernel's large tiles move fewer bytes per MAC.
 double band_cost(const GemmProblem &g)
 {
     BandPlan bp;
     if (!band_plan(g, &bp)) return 1e300;
     const BandArgs &a = bp.a;
-    if (bp.grid > 256 || a.ksteps < 18) return 1e300;
+    if (bp.grid > 256 || (bp.srow == 1 && a.ksteps < 18)) return 1e300;
     const double bytes = (double)a.win_total * 1024 + (double)BAND_TK * a.depth;
-    const double mfma = (double)a.kpw * bp.pb * 2 * 16 * 1.8;
-    return 5000.0 + (bytes / 25.0 > mfma ? bytes / 25.0 : mfma) + 4000.0;
+    const double mfma = (double)a.kpw * bp.pb * 2 * 25.0;
+    return 1800.0 + (bytes / 40.0 > mfma ? bytes / 40.0 : mfma) + 1800.0;
 }
 
 hipError_t launch_band_conv(const GemmProblem &g, hipStream_t st)
