@@ -59,6 +59,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--n-scaled-only", action="store_true",
                     help="run only the supplementary steady-state section (for profiling runs)")
+    ap.add_argument("--steady-gemm-only", action="store_true",
+                    help="run only the GEMM stage of C4a at N=2048, a few launches (for counter runs)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (a known-size reference for "
                          "scaling hardware byte counters in profiler runs)")
@@ -229,6 +231,28 @@ def main():
 
     if args.n_scaled_only:
         print(json.dumps({"n_scaled": n_scaled(lib, timed, CONFIGS, dev)}), flush=True)
+        return
+
+    if args.steady_gemm_only:
+        # the steady-state GEMM stage on its own (for counter runs): random operands, all-zero operands (what the
+        # time owes to switching activity), and the register-resident MFMA probe under the same conditions
+        cfg = CONFIGS["C4a"].scaled(2048)
+        x = torch.randint(-128, 128, (cfg.N, cfg.C, cfg.H, cfg.W), dtype=torch.int8, device=dev)
+        w = torch.randint(-128, 128, (cfg.K, cfg.C, cfg.R, cfg.S), dtype=torch.int8, device=dev)
+        xp = lib.pack_layout(x, 64, cfg.pad)
+        wp = lib.pack_weights(w, lib.LAYOUT_PACKED, 64)
+        o = torch.empty((cfg.N, cfg.K, cfg.P, cfg.Q), dtype=torch.int32, device=dev)
+        _, ms = timed(lambda: lib.conv2d_int8_packed(cfg.dims(), lib.LAYOUT_PACKED, 64, xp, wp, o), 10, 3)
+        xz, wz = torch.zeros_like(xp), torch.zeros_like(wp)
+        _, ms_z = timed(lambda: lib.conv2d_int8_packed(cfg.dims(), lib.LAYOUT_PACKED, 64, xz, wz, o), 10, 3)
+        blocks, iters = 256 * 8, 4096
+        buf = torch.empty(blocks * 256, dtype=torch.int32, device=dev)
+        _, ms_p = timed(lambda: lib.mfma_probe_int8(blocks, iters, out=buf), 5, 2)
+        probe_ops = 2 * 32768 * 16 * iters * blocks
+        print(json.dumps({"gemm_stage_C4a_N2048_us": round(ms * 1e3, 2), "tiling": lib.query_tiling(cfg.dims(), lib.LAYOUT_PACKED, 64),
+                          "tops": round(cfg.ops / (ms * 1e-3) / 1e12, 2),
+                          "all_zero_operands_us": round(ms_z * 1e3, 2), "all_zero_operands_tops": round(cfg.ops / (ms_z * 1e-3) / 1e12, 2),
+                          "mfma_probe_us": round(ms_p * 1e3, 2), "mfma_probe_tops": round(probe_ops / (ms_p * 1e-3) / 1e12, 2)}), flush=True)
         return
 
     groups = {"C1": ["C1"], "C2": ["C2"], "C3": ["C3"], "C4": ["C4a", "C4b"], "C4a": ["C4a"], "C4b": ["C4b"],
