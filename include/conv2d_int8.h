@@ -289,7 +289,7 @@ int conv2d_int8_dilated_direct(const conv_desc_t *desc, int dilation, int cb,
 
 /* Measurement aid: the int8 MFMA rate the chip sustains with nothing else in the way.  blocks workgroups of
  * four waves each issue iters x 4 v_mfma_i32_32x32x32_i8 (the GEMM unit of Sec. 5.1, 32 x 32 x 32 per
- * instruction) on register-resident pseudo-random operands: 2 * 32768 * 16 * iters * blocks operations in all.
+ * instruction) on register-resident pseudo-random operands that change from one instruction to the next: 2 * 32768 * 16 * iters * blocks operations in all.
  * out: blocks * 256 int32 (one checksum per lane, device memory).  blocks in 1..2^20, iters >= 1. */
 int mfma_probe_int8(int blocks, int iters, int32_t *out, void *stream);
 

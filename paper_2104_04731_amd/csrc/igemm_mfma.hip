@@ -812,7 +812,10 @@ bool gemm_pick(const GemmProblem &g, int *tile, int *split_k, double *cost)
             const double start = 5000.0 + 5.0 * (d.tk + d.tm) / waves + (d.ds == 2 ? 1000.0 : 0.0) + 400.0 * waves * res;
             const double wg = start + per * step + store;
             const double rounds = (double)(long long)((wgs + 256.0 * res - 1) / (256.0 * res));
-            const double total = rounds * wg + (s > 1 ? 6000.0 : 0.0);
+            double total = rounds * wg + (s > 1 ? 6000.0 : 0.0);
+            // measured on two machines at N = 2048: among the 256 x 256 tiles the eight-wave one with 128-byte
+            // stages is 5-15 % ahead of the four-wave one, which the cycle model above ranks level
+            if (d.tk * d.tm >= 65536 && waves >= 8 && d.ks >= 2) total *= 0.95;
             if (total < best) {
                 best = total;
                 bt = t;
@@ -928,29 +931,41 @@ hipError_t launch_gemm(const GemmProblem &g, int tile, int split_k, hipStream_t 
 
 // ---- MFMA-only probe: what the matrix cores sustain with nothing else in the way ---------------------
 // Every wave keeps four independent 32x32 accumulators and issues v_mfma_i32_32x32x32_i8 back to back
-// on register-resident operands (pseudo-random bytes made from the lane id).  No LDS, no global loads;
-// one store per lane at the end keeps the work alive.
+// on register-resident operands (four pseudo-random fragment pairs made from the lane id).  Consecutive
+// instructions take different fragments, as the blocks of a GEMM's wave tile do: with one constant pair the
+// multiplier inputs would never toggle, and on a power-managed part that understates what real operands
+// cost.  No LDS, no global loads; one store per lane at the end keeps the work alive.
 __global__ void __launch_bounds__(256) mfma_probe_kernel(int iters, int32_t *out)
 {
     const unsigned id = blockIdx.x * 256u + threadIdx.x;
-    v4i a, b;
+    v4i a[4], b[4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        unsigned x = (id * 4u + (unsigned)t) * 2654435761u;
-        x ^= x >> 15;
-        x *= 2246822519u;
-        x ^= x >> 13;
-        a[t] = (int)x;
-        b[t] = (int)(x * 3266489917u + 374761393u);
-    }
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            unsigned x = (id * 16u + (unsigned)(f * 4 + t)) * 2654435761u;
+            x ^= x >> 15;
+            x *= 2246822519u;
+            x ^= x >> 13;
+            a[f][t] = (int)x;
+            b[f][t] = (int)(x * 3266489917u + 374761393u);
+        }
     v16i acc[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[g][v] = 0;
-    for (int it = 0; it < iters; ++it) {
+    int it = 0;
+    for (; it + 4 <= iters; it += 4) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) acc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[g], 0, 0, 0);
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                acc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[(g + r) & 3], b[g], acc[g], 0, 0, 0);
+    }
+    for (; it < iters; ++it) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) acc[g] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[g], b[g], acc[g], 0, 0, 0);
     }
     int sum = 0;
 #pragma unroll
