@@ -1415,11 +1415,129 @@ __global__ void __launch_bounds__(256) phase_split_kernel(const PhaseSplitArgs a
     }
 }
 
+// Phases of two (stride or dilation 2) need no tile: within a padded source row the two column phases are
+// the even and the odd bytes.  A thread takes 32 consecutive padded bytes of one row (two 16-byte loads at any
+// byte address), zeroes the bytes outside the image, separates even from odd bytes with one byte permute per
+// dword, and stores 16 bytes of each of the row's two phase planes; destination rows start at any byte, so
+// these are 16-byte stores at any address.  A workgroup is [row parity][destination rows][pieces of a row],
+// the piece index in the low lane bits and the destination rows running on across planes: a wave writes
+// consecutive rows of one phase plane, one contiguous run per store instruction.  The last piece of a row is
+// moved back to end with the row (it overlaps its neighbour, both write the same values) instead of being
+// cut short; rows shorter than 16 bytes go out in 8/4/2/1-byte units.  Every byte of HBM is touched once.
+struct PhaseSplit2Args {
+    const int8_t *src;
+    int8_t *dst;
+    int C, H, W, pad, H2, W2, planes;
+    long long pn, pc, pa, pb;
+    int npr, lp2;               // 16-byte destination pieces per row; log2 of the lanes a row takes (>= npr)
+    int slots, both;            // destination rows per workgroup; 1: a workgroup holds both row parities of them
+    int total;                  // planes * H2: destination rows of one phase, over all planes
+    unsigned m_H2, m_C;
+};
+
+// The first nb bytes (1..15) of v to o, any address.
+__device__ __forceinline__ void store_head(int8_t *o, v4i v, int nb)
+{
+    typedef int v2i_a1 __attribute__((ext_vector_type(2), aligned(1)));
+    typedef int i_a1 __attribute__((aligned(1)));
+    typedef short s_a1 __attribute__((aligned(1)));
+    if (nb & 8) *reinterpret_cast<v2i_a1 *>(o) = v2i_a1{v[0], v[1]};
+    const int d2 = (nb & 8) ? v[2] : v[0], d3 = (nb & 8) ? v[3] : v[1];
+    o += nb & 8;
+    if (nb & 4) *reinterpret_cast<i_a1 *>(o) = d2;
+    const unsigned d = (unsigned)((nb & 4) ? d3 : d2);
+    o += nb & 4;
+    if (nb & 2) *reinterpret_cast<s_a1 *>(o) = (short)d;
+    if (nb & 1) o[nb & 2] = (int8_t)(d >> (8 * (nb & 2)));
+}
+
+__global__ void __launch_bounds__(256) phase_split2_kernel(const PhaseSplit2Args a)
+{
+    const int tid = threadIdx.x;
+    const int t = tid & ((1 << a.lp2) - 1), rl = tid >> a.lp2;   // piece of the row; row of the workgroup
+    const int pa = a.both ? (rl >= a.slots) : (int)(blockIdx.x & 1);
+    const int g = a.both ? (int)blockIdx.x * a.slots + (rl - pa * a.slots) : (int)(blockIdx.x >> 1);
+    if (t >= a.npr || g >= a.total) return;
+    const int pl = fast_div_any(g, a.H2, a.m_H2), il = g - pl * a.H2;
+    const int n = fast_div_any(pl, a.C, a.m_C), c = pl - n * a.C;
+    const int col0 = a.W2 >= 16 ? min(16 * t, a.W2 - 16) : 0;   // first destination column of the piece
+    const int w0 = 2 * col0 - a.pad;                            // image column of the first of its 32 source bytes
+    const int h = 2 * il + pa - a.pad;
+    const long long bytes = (long long)a.planes * a.H * a.W;
+    const long long want = ((long long)pl * a.H + min(max(h, 0), a.H - 1)) * a.W + w0;
+    const long long o1 = min(max(want, 0LL), bytes - 16), o2 = min(max(want + 16, 0LL), bytes - 16);
+    v4i lo4, hi4;
+    __builtin_memcpy(&lo4, a.src + o1, 16);
+    __builtin_memcpy(&hi4, a.src + o2, 16);
+    if (o1 != want || o2 != want + 16) {   // the tensor's first or last bytes: byte by byte
+        asm volatile("" ::: "memory");     // stays a branch: only the first and the last rows come here
+        unsigned x[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+#pragma nounroll
+        for (int k = 0; k < 32; ++k)
+            if (want + k >= 0 && want + k < bytes) {
+                const unsigned b = (unsigned)(unsigned char)a.src[want + k] << (8 * (k & 3));
+#pragma unroll
+                for (int m = 0; m < 8; ++m)
+                    if ((k >> 2) == m) x[m] |= b;
+            }
+        lo4 = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
+        hi4 = v4i{(int)x[4], (int)x[5], (int)x[6], (int)x[7]};
+    }
+    // bytes [lo, hi) of the 32 lie inside the image row (none of them when the row itself is padding)
+    unsigned x[8];
+    {
+        const bool rowok = h >= 0 && h < a.H;
+        const int lo = min(max(-w0, 0), 32), hi = rowok ? min(max(a.W - w0, 0), 32) : 0;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {   // eight bytes at a time
+            const int l = min(max(lo - 8 * p, 0), 8), hh = min(max(hi - 8 * p, 0), 8);
+            const unsigned long long ml = l == 8 ? 0ull : ~0ull << (8 * l), mh = hh == 0 ? 0ull : ~0ull >> (64 - 8 * hh);
+            const unsigned k0 = (unsigned)(ml & mh), k1 = (unsigned)((ml & mh) >> 32);
+            x[2 * p] = (unsigned)(p < 2 ? lo4[2 * p] : hi4[2 * p - 4]) & k0;
+            x[2 * p + 1] = (unsigned)(p < 2 ? lo4[2 * p + 1] : hi4[2 * p - 3]) & k1;
+        }
+    }
+    v4i even, odd;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        even[m] = (int)__builtin_amdgcn_perm(x[2 * m + 1], x[2 * m], 0x06040200u);
+        odd[m] = (int)__builtin_amdgcn_perm(x[2 * m + 1], x[2 * m], 0x07050301u);
+    }
+    const long long plane_bytes = (long long)a.H2 * a.W2;
+    int8_t *o_even = a.dst + ((long long)n * a.pn + (long long)c * a.pc + pa * a.pa) * plane_bytes + (long long)il * a.W2 + col0;
+    int8_t *o_odd = o_even + a.pb * plane_bytes;
+    const int nb = a.W2 - col0;   // bytes of the destination row from this piece on (16 or more, or the whole short row)
+    if (nb >= 16) {
+        *reinterpret_cast<v4i_a1 *>(o_even) = even;
+        *reinterpret_cast<v4i_a1 *>(o_odd) = odd;
+    } else {
+        store_head(o_even, even, nb);
+        store_head(o_odd, odd, nb);
+    }
+}
+
 // Returns hipErrorNotSupported when a tile of one destination row does not fit LDS (the callers then
 // use their element-wise kernels).
 static hipError_t launch_phase_split(int N, int C, int H, int W, int pad, int s, int H2, int W2, long long pn, long long pc,
                                      long long pa, long long pb, const int8_t *src, int8_t *dst, hipStream_t st)
 {
+    if (s == 2 && (long long)N * C * H * W >= 32 && (long long)N * C * H2 <= 2147483647LL && W2 <= 16 * 256) {
+        PhaseSplit2Args b{};
+        b.src = src, b.dst = dst;
+        b.C = C, b.H = H, b.W = W, b.pad = pad, b.H2 = H2, b.W2 = W2, b.planes = N * C;
+        b.pn = pn, b.pc = pc, b.pa = pa, b.pb = pb;
+        b.npr = (W2 + 15) / 16;
+        while ((1 << b.lp2) < b.npr) ++b.lp2;
+        b.total = N * C * H2;
+        b.both = b.lp2 < 8;
+        b.slots = b.both ? 128 >> b.lp2 : 1;
+        const long long nblocks = b.both ? ((long long)b.total + b.slots - 1) / b.slots : 2LL * b.total;
+        if (nblocks <= 2147483647LL) {   // (larger tensors take the tile kernel below)
+            b.m_H2 = magic_for(H2), b.m_C = magic_for(C);
+            hipLaunchKernelGGL(phase_split2_kernel, dim3((unsigned)nblocks), dim3(256), 0, st, b);
+            return hipGetLastError();
+        }
+    }
     PhaseSplitArgs a{};
     a.src = src, a.dst = dst;
     a.C = C, a.H = H, a.W = W, a.pad = pad, a.s = s, a.H2 = H2, a.W2 = W2;

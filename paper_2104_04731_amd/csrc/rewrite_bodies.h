@@ -9,6 +9,7 @@ namespace c2i8 {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));  // 16 bytes at a dword-aligned address
+typedef int v4i_a1 __attribute__((ext_vector_type(4), aligned(1)));  // 16 bytes at any address
 
 // Workgroups are dealt round-robin over the 8 XCDs (each with its own L2).  Mapping the
 // hardware id to a logical id that is contiguous per XCD makes neighbouring tiles -- which
