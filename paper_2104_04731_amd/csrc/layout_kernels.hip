@@ -357,7 +357,9 @@ im2col_kernel(const int8_t *__restrict__ src, int8_t *__restrict__ dst,
 // part zero-filled, so building a destination piece needs no bounds tests: walking (c,r,s)
 // in depth order is "+1 byte" inside a kernel row and "+pitch-S+1" at the end of one.
 // Index splits use multiply-high by a host-computed reciprocal (exact for the small ranges
-// involved), and the patch loads are issued eight at a time before any is consumed.
+// involved), and the patch loads are issued four at a time before any is consumed.  The patch
+// pitch is an odd number of dwords: lanes of the second phase read the same columns of many
+// different rows, and an even pitch puts those on a handful of LDS banks.
 constexpr int I2C_LDS = 48 * 1024;
 
 struct I2cArgs {
@@ -367,7 +369,59 @@ struct I2cArgs {
     int TQ, qtiles, Cc, cslices, span, pitch;
     unsigned m_span, m_R, m_S;  // ceil(2^32 / d)
     int use_recipe;
+    long long src_bytes;        // N*C*H*W
 };
+constexpr int I2C_PBASE = 16;   // slack in front of the patch: a run may start up to three bytes before a row
+// Zero bytes behind the patch: what the zero tail of the depth reads, for every pixel of a tile (four pixels at a
+// time, a window of up to 16 bytes plus the alignment slack each).
+static __host__ __device__ inline int i2c_zero_run(int TQ, int stride) { return ((TQ + 3) * stride + 24) & ~3; }
+
+// Four consecutive pixels of one 16-byte depth piece per thread (stride ST known at compile time).  A run of
+// the recipe moves ST bytes per pixel, so the four pixels' runs lie in one window of 3*ST + 4 bytes: it is read
+// once as aligned dwords, shifted to start at byte 0 (per-lane shift), and each pixel's dword is then a fixed
+// byte-align of two of its dwords.
+template <int ST>
+__device__ __forceinline__ void i2c_produce4(const unsigned char *lds, const uint2 *rec, int8_t *out0, int nq, int chunks,
+                                             unsigned m_chunks, int kg_pad)
+{
+    constexpr int NW = (3 * ST + 4 + 3) / 4;   // dwords of the shifted window
+    const int groups = (nq + 3) >> 2;
+    for (int idx = threadIdx.x; idx < groups * chunks; idx += 256) {
+        const int gq = fast_div(idx, m_chunks), ch = idx - gq * chunks;
+        const unsigned px = (unsigned)(4 * gq * ST);
+        const uint4 *rp = reinterpret_cast<const uint4 *>(rec + ch * 4);
+        const uint4 ra = rp[0], rb = rp[1];
+        const unsigned ex[4] = {ra.x, ra.z, rb.x, rb.z}, em[4] = {ra.y, ra.w, rb.y, rb.w};
+        v4i ov[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            unsigned run[2][4];
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const unsigned at = (half ? ex[d] >> 16 : ex[d] & 0xFFFFu) + px;
+                const unsigned *p = reinterpret_cast<const unsigned *>(lds + (at & ~3u));
+                unsigned w[NW + 1], nrm[NW];
+#pragma unroll
+                for (int k = 0; k <= NW; ++k) w[k] = p[k];
+#pragma unroll
+                for (int k = 0; k < NW; ++k) nrm[k] = __builtin_amdgcn_alignbyte(w[k + 1], w[k], at & 3u);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int off = i * ST;
+                    run[half][i] = (off & 3) == 0 ? nrm[off >> 2]
+                                                  : __builtin_amdgcn_alignbyte(nrm[(off >> 2) + 1 < NW ? (off >> 2) + 1 : NW - 1],
+                                                                               nrm[off >> 2], (unsigned)(off & 3));
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) ov[i][d] = (int)((run[0][i] & em[d]) | (run[1][i] & ~em[d]));
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (4 * gq + i < nq)
+                __builtin_nontemporal_store(ov[i], reinterpret_cast<v4i *>(out0 + (long long)(4 * gq + i) * kg_pad + (ch << 4)));
+    }
+}
 
 __device__ __forceinline__ void im2col_tiled_body(const I2cArgs &a, int bid, unsigned char *lds)
 {
@@ -384,13 +438,73 @@ __device__ __forceinline__ void im2col_tiled_body(const I2cArgs &a, int bid, uns
     const int w_lo = q0 * a.stride - a.pad, h_lo = p * a.stride - a.pad;
     const int8_t *img = src + (n * a.C + c0) * (long long)a.H * a.W;
 
-    // LDS: [4 B slack][patch: nc*R rows x pitch][zero run][recipe table]
-    constexpr int PBASE = 4;
+    // LDS: [slack][patch: nc*R rows x pitch][zero run][recipe table]
+    constexpr int PBASE = I2C_PBASE;
     unsigned char *patch = lds + PBASE;
     const int rows = nc * a.R;
     const int zoff = PBASE + rows * a.pitch;
 
-    // stage the patch four columns at a time, without branches: one (unaligned) dword load
+    if (a.W >= 16) {
+        // stage the patch in 16-byte pieces: one load at any byte address
+        // -- a piece that starts left of the image row or runs past its end reads the neighbouring row's bytes
+        // -- and a byte mask that turns everything outside the row, and every row outside the image, to zero
+        const int pcs = (a.pitch + 15) >> 4;   // (the last piece of a row may be cut short by the pitch)
+        const int total = rows * pcs;
+        const unsigned m_pcs = magic_for_device(pcs);
+        const long long img_off = (n * a.C + c0) * (long long)a.H * a.W;
+        for (int base = 0; base < total; base += 256 * 4) {
+            v4i v[4];
+            int hh[4], ww[4];
+            long long want[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int idx = min(base + u * 256 + (int)threadIdx.x, total - 1);
+                const int row = fast_div(idx, m_pcs), t = idx - row * pcs;
+                const int cl = fast_div(row, a.m_R), r = row - cl * a.R;
+                hh[u] = h_lo + r, ww[u] = w_lo + 16 * t;
+                want[u] = img_off + ((long long)cl * a.H + min(max(hh[u], 0), a.H - 1)) * a.W + ww[u];
+                const long long at = min(max(want[u], 0LL), a.src_bytes - 16);
+                __builtin_memcpy(&v[u], src + at, 16);
+                if (at != want[u]) {   // the tensor's first or last bytes: byte by byte
+                    asm volatile("" ::: "memory");   // stays a branch
+                    unsigned x[4] = {0u, 0u, 0u, 0u};
+#pragma nounroll
+                    for (int k = 0; k < 16; ++k)
+                        if (want[u] + k >= 0 && want[u] + k < a.src_bytes) {
+                            const unsigned b = (unsigned)(unsigned char)src[want[u] + k] << (8 * (k & 3));
+#pragma unroll
+                            for (int m = 0; m < 4; ++m)
+                                if ((k >> 2) == m) x[m] |= b;
+                        }
+                    v[u] = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const bool rowok = hh[u] >= 0 && hh[u] < a.H;
+                const int lo = min(max(-ww[u], 0), 16), hi = rowok ? min(max(a.W - ww[u], 0), 16) : 0;
+                v4i x;
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {   // eight bytes at a time
+                    const int l = min(max(lo - 8 * q, 0), 8), h8 = min(max(hi - 8 * q, 0), 8);
+                    const unsigned long long ml = l == 8 ? 0ull : ~0ull << (8 * l), mh = h8 == 0 ? 0ull : ~0ull >> (64 - 8 * h8);
+                    x[2 * q] = (int)((unsigned)v[u][2 * q] & (unsigned)(ml & mh));
+                    x[2 * q + 1] = (int)((unsigned)v[u][2 * q + 1] & (unsigned)((ml & mh) >> 32));
+                }
+                const int idx = base + u * 256 + (int)threadIdx.x;
+                if (idx < total) {
+                    // dword stores: the pitch is an odd number of dwords, which keeps the column-wise reads of the
+                    // second phase off each other's banks
+                    const int row = fast_div(idx, m_pcs), t = idx - row * pcs;
+                    unsigned *o = reinterpret_cast<unsigned *>(patch + row * a.pitch + 16 * t);
+#pragma unroll
+                    for (int m = 0; m < 4; ++m)
+                        if (16 * t + 4 * m < a.pitch) o[m] = (unsigned)x[m];
+                }
+            }
+        }
+    } else {
+    // narrow images: four columns at a time, without branches: one (unaligned) dword load
     // from the column window clamped into the image row, shifted so that the bytes that fall
     // outside the row become the zero padding
     const int pd = a.pitch >> 2;  // dwords per patch row
@@ -419,6 +533,7 @@ __device__ __forceinline__ void im2col_tiled_body(const I2cArgs &a, int bid, uns
         for (int u = 0; u < 4; ++u)
             if (base + u * 256 + (int)threadIdx.x < total) *reinterpret_cast<unsigned *>(patch + at[u]) = v[u];
     }
+    }
 
     // destination pieces of this channel slice: depth range [c0*R*S, (c0+nc)*R*S), plus the
     // zero tail up to kg_pad for the last slice; slice boundaries are multiples of 16
@@ -436,10 +551,11 @@ __device__ __forceinline__ void im2col_tiled_body(const I2cArgs &a, int bid, uns
         // each run starts and how many bytes the first one gives -- depends on the depth only,
         // so it is tabulated once; a pixel adds q*stride.  A run is fetched as two aligned
         // dwords and one byte-align; the two runs are merged under a byte mask.
-        const int zsz = (((a.TQ - 1) * a.stride + 12) + 3) & ~3;
+        const int zsz = i2c_zero_run(a.TQ, a.stride);
         for (int i = threadIdx.x; i < (zsz >> 2); i += 256) *reinterpret_cast<unsigned *>(lds + zoff + 4 * i) = 0u;
-        if (threadIdx.x == 0) *reinterpret_cast<unsigned *>(lds) = 0u;
-        uint2 *rec = reinterpret_cast<uint2 *>(lds + ((zoff + zsz + 7) & ~7));
+        if (threadIdx.x < PBASE / 4) *reinterpret_cast<unsigned *>(lds + 4 * threadIdx.x) = 0u;
+        // per destination dword: {start of the first run | start of the second run minus n0 << 16, byte mask of the first run}
+        uint2 *rec = reinterpret_cast<uint2 *>(lds + ((zoff + zsz + 15) & ~15));
         const int ndw = (j_end - j_begin) >> 2;
         for (int dd = threadIdx.x; dd < ndw; dd += 256) {
             const int j0 = dd << 2;
@@ -455,9 +571,11 @@ __device__ __forceinline__ void im2col_tiled_body(const I2cArgs &a, int bid, uns
                     w1 = o1 - n0;
                 }
             }
-            rec[dd] = make_uint2(o0 | (n0 << 24), w1);
+            rec[dd] = make_uint2(o0 | (w1 << 16), n0 >= 4 ? 0xFFFFFFFFu : ((1u << (8 * n0)) - 1u));
         }
         __syncthreads();
+        if (a.stride == 1) return i2c_produce4<1>(lds, rec, out0, nq, chunks, m_chunks, a.kg_pad);
+        if (a.stride == 2) return i2c_produce4<2>(lds, rec, out0, nq, chunks, m_chunks, a.kg_pad);
         for (int idx = threadIdx.x; idx < nq * chunks; idx += 256) {
             const int ql = fast_div(idx, m_chunks), ch = idx - ql * chunks;
             const unsigned px = (unsigned)(ql * a.stride);
@@ -465,14 +583,12 @@ __device__ __forceinline__ void im2col_tiled_body(const I2cArgs &a, int bid, uns
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
                 const uint2 e = rec[ch * 4 + d];
-                const unsigned n0 = e.x >> 24;
-                const unsigned a0 = (e.x & 0xFFFFFFu) + px, a1 = e.y + px;
+                const unsigned a0 = (e.x & 0xFFFFu) + px, a1 = (e.x >> 16) + px;
                 const unsigned *p0 = reinterpret_cast<const unsigned *>(lds + (a0 & ~3u));
                 const unsigned *p1 = reinterpret_cast<const unsigned *>(lds + (a1 & ~3u));
                 const unsigned v0 = __builtin_amdgcn_alignbyte(p0[1], p0[0], a0 & 3u);
                 const unsigned v1 = __builtin_amdgcn_alignbyte(p1[1], p1[0], a1 & 3u);
-                const unsigned mask = n0 >= 4 ? 0xFFFFFFFFu : ((1u << (8 * n0)) - 1u);
-                ov[d] = (int)((v0 & mask) | (v1 & ~mask));
+                ov[d] = (int)((v0 & e.y) | (v1 & ~e.y));
             }
             __builtin_nontemporal_store(ov, reinterpret_cast<v4i *>(out0 + (long long)ql * a.kg_pad + (ch << 4)));
         }
@@ -532,7 +648,7 @@ static bool plan_im2col_tiled(int N, int C, int H, int W, int R, int S, int stri
     }
     if (TQ < 1) TQ = 1;
     const long long span64 = (long long)(TQ - 1) * stride + S;
-    const int span = (int)span64, pitch = (span + 3) & ~3;
+    const int span = (int)span64, pitch = 4 * (((span + 3) / 4) | 1);   // an odd number of dwords
     // channels per slice: all of them if the patch fits, else a multiple of 16 that does
     int Cc = C;
     if ((long long)C * R * pitch > I2C_LDS) Cc = (int)(I2C_LDS / ((long long)R * pitch)) / 16 * 16;
@@ -546,11 +662,11 @@ static bool plan_im2col_tiled(int N, int C, int H, int W, int R, int S, int stri
     const bool small = span64 < 65536 && S < 1024 && R < 65536 && (long long)C * R * S < (1LL << 20) &&
                        kg_pad < (1 << 19);
     if (!small || *blocks >= (1LL << 31)) return false;
-    // LDS: 4 B slack + patch + zero run + (recipe path) 8 B per destination dword of a slice
-    const long long patch_bytes = 4 + (long long)(Cc < C ? Cc : C) * R * pitch;
-    const long long zsz = ((((long long)TQ - 1) * stride + 12) + 3) & ~3LL;
+    // LDS: slack + patch + zero run + (recipe path) 8 B per destination dword of a slice
+    const long long patch_bytes = I2C_PBASE + (long long)(Cc < C ? Cc : C) * R * pitch;
+    const long long zsz = i2c_zero_run(TQ, stride);
     const long long slice_depth = cslices == 1 ? kg_pad : (long long)Cc * R * S + 64;
-    const long long with_recipe = ((patch_bytes + zsz + 7) & ~7LL) + 2 * slice_depth;
+    const long long with_recipe = ((patch_bytes + zsz + 15) & ~15LL) + 2 * slice_depth;
     const bool recipe = S >= 3 && with_recipe <= 60 * 1024;
     I2cArgs a;
     a.src = src; a.dst = dst;
@@ -561,6 +677,7 @@ static bool plan_im2col_tiled(int N, int C, int H, int W, int R, int S, int stri
     a.m_R = (unsigned)((0x100000000ULL + R - 1) / R);
     a.m_S = (unsigned)((0x100000000ULL + S - 1) / S);
     a.use_recipe = recipe;
+    a.src_bytes = (long long)N * C * H * W;
     *out = a;
     *lds = (size_t)(recipe ? with_recipe : patch_bytes + 8);
     return true;

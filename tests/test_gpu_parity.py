@@ -110,6 +110,24 @@ def test_im2col(lib, dims):
     np.testing.assert_array_equal(got, layouts.im2col(x, R, S, st, pad))
 
 
+def test_im2col_random_shapes(lib):
+    """Seeded random shapes over the unroll kernel's paths: wide and narrow rows, strides 1-3, kernel rows shorter
+    and longer than a dword, pads up to the kernel size, channel counts that need several slices, tile tails."""
+    rng = np.random.default_rng(20260)
+    done = 0
+    while done < 48:
+        S = int(rng.integers(1, 8)); R = int(rng.integers(1, 6))
+        st = int(rng.integers(1, 4)); pad = int(rng.integers(0, max(R, S) + 1))
+        W = int(rng.integers(max(4, S), 90)); H = int(rng.integers(R, 24))
+        C = int(rng.choice([1, 2, 3, 5, 16, 40, 130, 300])); N = int(rng.integers(1, 4))
+        if (H + 2 * pad - R) // st + 1 < 1 or (W + 2 * pad - S) // st + 1 < 1 or N * C * H * W > 400000:
+            continue
+        x = uniform_int8(1000 + done, (N, C, H, W))
+        got = host(lib.im2col_int8(dev(x), R, S, st, pad))
+        np.testing.assert_array_equal(got, layouts.im2col(x, R, S, st, pad), err_msg=str((N, C, H, W, R, S, st, pad)))
+        done += 1
+
+
 @pytest.mark.parametrize("name", ["C3", "C5"])
 def test_im2col_configs(lib, name):
     cfg = CONFIGS[name]
