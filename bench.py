@@ -199,6 +199,11 @@ def main():
             picked = [c for c in cands if c["picked"]]
             regret = round(picked[0]["combined_us"] / fastest - 1.0, 4) if picked else None
             warm, cold = sampled(self.combined, 100, False), sampled(self.combined, 100, True)
+            # the same convolution on NHWC tensors (Sec. 5.2): NHWC in, KCRS weights, NHWC result
+            xh = self.x.permute(0, 2, 3, 1).contiguous()
+            oh = torch.empty((cfg.N, cfg.P, cfg.Q, cfg.K), dtype=torch.int32, device=dev)
+            _, nh = timed(lambda: lib.conv2d_int8_nhwc(xh, self.w, cfg.stride, cfg.pad, out=oh), steps, warmup)
+            del xh, oh
             if self.tile >= 0:
                 rows, cols = lib.tile_info(self.tile)[:2]
             elif self.tile == lib.TILE_BAND:
@@ -219,6 +224,7 @@ def main():
                 "pct_hbm_peak_transf": round(100 * self.rewrite_bytes / (tr * 1e-3) / PEAK_HBM_BPS, 2) if tr else None,
                 "combined_GBps": round((self.x.numel() + self.w.numel() + 4 * self.out.numel()) / (comb * 1e-3) / 1e9, 1),
                 "combined_single_calls_warm": stats(warm), "combined_single_calls_cold": stats(cold),
+                "nhwc_one_shot_us": round(nh * 1e3, 3),
                 "candidates": cands, "selector_regret": regret,
             }
 

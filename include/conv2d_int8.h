@@ -107,7 +107,10 @@ int conv2d_int8_static(int N, int C, int H, int W, int K, int R, int S, int stri
 /* The same for NHWC tensors (Sec. 5.2): in [N][H][W][C], wt KCRS, out [N][P][Q][K] int32.  Channel
  * blocking straight from the NHWC source (pack_layout_nhwc) and the weight rewrite in one launch, then a
  * GEMM stage whose epilogue writes NHWC itself: two launches.  (An `out` that does not start on 16 bytes goes
- * through an NKPQ staging tensor in the cached workspace and unpack_nhwc_int32: three.)  Same workspace rules as conv2d_int8. */
+ * through an NKPQ staging tensor in the cached workspace and unpack_nhwc_int32: three.)  Same workspace rules as conv2d_int8.
+ * When select_layout's choice for the shape is IMPLICIT (not the 1x1 form) and R * ceil(S*C, 4) <= 256, the
+ * kernel that unrolls the stencil itself reads the NHWC source directly -- depth order (r, s, c), a kernel row's
+ * S*C bytes being one run of an image row -- and writes the NHWC result: one launch, no workspace. */
 int conv2d_int8_nhwc(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                      const int8_t *in, const int8_t *wt, int32_t *out, void *stream);
 

@@ -966,6 +966,14 @@ int conv2d_int8_nhwc(int N, int C, int H, int W, int K, int R, int S, int stride
     int rc = make_plan(&d, CONV_LAYOUT_PACKED, 0, &pl);
     if (rc != CONV_OK) return rc;
     if (!in || !wt || !out) return CONV_ERR_INVALID_ARG;
+    {   // the selector's choice is the kernel that unrolls the stencil itself, and its NHWC form takes the shape: one launch
+        int layout = CONV_LAYOUT_AUTO, cb = 0;
+        if (resolve_layout(&d, &layout, &cb) == CONV_OK && layout == CONV_LAYOUT_IMPLICIT && !pointwise_shape(C, R, S)) {
+            WindowProblem wp{in, wt, out, N, C, H, W, K, pl.P, pl.Q, R, S, stride, pad, 0, ActOut{}, 1, 1};
+            if (window_fits(wp))
+                return launch_window_conv(wp, (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
+        }
+    }
     // The GEMM stage's epilogue writes NHWC itself (a lane's four values are four consecutive channels of a
     // pixel); only a result that does not start on 16 bytes goes through an NKPQ staging tensor and a pass.
     const bool direct = aligned16(out);

@@ -116,6 +116,10 @@ struct WindowProblem {
     int N, C, H, W, K, P, Q, R, S, stride, pad;
     int wt_rewritten;
     ActOut act;
+    // NHWC source: in is [N][H][W][C] and the depth order is (r, s, c) -- a kernel row's S*C bytes are one run
+    // of an image row -- with the KCRS weights brought into that order on their way into LDS; not with wt_rewritten
+    int nhwc_in;
+    int out_nhwc;       // out is [N][P][Q][K]
 };
 int window_depth(int C, int R, int S);          // 0 if the padded depth exceeds what the kernel unrolls
 bool window_fits(const WindowProblem &g);       // depth, image width and LDS window within the kernel's limits

@@ -21,6 +21,12 @@
 //      and a byte-align each), its weight operand 16 bytes of weight row lane%32.
 //      v_mfma_i32_32x32x32_i8, channels x pixels;
 //   5. the D block (column = pixel = lane%32) goes straight to NKPQ: 128-byte runs per channel.
+//
+// NHWC source (Sec. 5.2).  A row of an NHWC image is W*C bytes in which the S*C bytes of a kernel row's taps
+// and channels are one run: the same kernel computes it as a one-channel image of W*C columns with a kernel
+// row of S*C bytes, a horizontal stride of stride*C and pad*C bytes of horizontal padding.  The depth order
+// is then (r, s, c); the KCRS weight rows are copied into LDS as they are and brought into that order there.
+// A lane's four results are four consecutive channels of a pixel, which is what an NHWC result stores.
 #include "kernels.h"
 #include "rewrite_bodies.h"
 
@@ -34,7 +40,11 @@ struct WindowArgs {
     const int8_t *in;
     const int8_t *wt;
     int32_t *out;
-    int C, H, W, K, P, Q, R, stride, pad;
+    int C, H, W, K, P, Q, R, stride, pad;   // (NHWC source: C = 1, W in bytes; stride and pad are the vertical ones)
+    int stride_w, pad_w;   // horizontal stride and padding in bytes of an image row
+    int gC, gS, gRS;       // NHWC source: the real channel count, S and R*S of the KCRS weights
+    int nhwc;              // NHWC source
+    int out_nhwc, out_wide_k;  // result [N][P][Q][K]; K % 4 == 0 and out 16-byte aligned
     int PT, qshift;        // output rows per tile; tile columns QT = 32 << qshift, PT << qshift = 4
     int RW;                // window rows per channel: (PT-1)*stride + R
     int pitch;             // bytes per window row, a multiple of 4
@@ -47,7 +57,7 @@ struct WindowArgs {
     int in_small;          // C*H*W < 2^31
     int wide_out;          // Q % 4 == 0 and out 16-byte aligned: 16-byte stores
     ActOut act;            // activation epilogue (act.out != null): `out` is not written
-    unsigned m_wd, m_RW, m_nd, m_R, m_tiles_q, m_tiles_p;
+    unsigned m_wd, m_RW, m_nd, m_R, m_tiles_q, m_tiles_p, m_gC;
 };
 
 __device__ __forceinline__ unsigned load_u32(const void *p)  // any alignment
@@ -57,7 +67,7 @@ __device__ __forceinline__ unsigned load_u32(const void *p)  // any alignment
     return x;
 }
 
-template <int NKK, int NKB, bool ACT>  // ACT: the activation epilogue, a kernel of its own
+template <int NKK, int NKB, bool ACT, bool NHWC>  // ACT: the activation epilogue, a kernel of its own; NHWC: the source
 // (six waves per SIMD asked for: the compiler then keeps the accumulators in the one 80-register budget
 // instead of 79 + 32 registers, and six workgroups fit a CU instead of four)
 __global__ void __launch_bounds__(256, 6) conv_window_kernel(const WindowArgs a)
@@ -78,7 +88,7 @@ __global__ void __launch_bounds__(256, 6) conv_window_kernel(const WindowArgs a)
     const int n = fast_div_any(t1, a.tiles_p, a.m_tiles_p), tp = t1 - n * a.tiles_p;
     const int p0 = tp * a.PT, q0 = tq << (5 + a.qshift), k0 = blockIdx.y * KB;
     const int h_lo = p0 * a.stride - a.pad;
-    const int w_first = q0 * a.stride - a.pad;
+    const int w_first = q0 * a.stride_w - a.pad_w;
     const int w_lo = (w_first >> 2) << 2;  // rounded down, also when negative
     const int delta = w_first - w_lo;
 
@@ -99,7 +109,16 @@ __global__ void __launch_bounds__(256, 6) conv_window_kernel(const WindowArgs a)
     const unsigned mask = !real ? 0u : left >= 4 ? 0xFFFFFFFFu : (1u << (8 * (left & 3))) - 1u;
     const int coff = wcr * a.w_S + ws0;
     unsigned wv[WMAX];
-    if (r0 < RPP && last >= 0) {
+    // NHWC: the rows as they are, whole dwords of the run of `rows` rows (the last one fetched lower and shifted)
+    constexpr int WRAW = NHWC ? KB / 4 : 1;   // rows of at most 256 bytes: 64 * KB dwords over 256 threads
+    unsigned wraw[WRAW];
+    const int raw_dw = (rows * a.w_row + 3) >> 2;
+    if (NHWC) {
+        if (last >= 0) {
+#pragma unroll
+            for (int u = 0; u < WRAW; ++u) wraw[u] = load_u32(wsrc + (unsigned)min(4 * min(tid + u * 256, raw_dw - 1), last));
+        }
+    } else if (r0 < RPP && last >= 0) {
 #pragma unroll
         for (int u = 0; u < WMAX; ++u) {
             const int row = min(r0 + u * RPP, rows - 1);
@@ -145,7 +164,43 @@ __global__ void __launch_bounds__(256, 6) conv_window_kernel(const WindowArgs a)
         else
             for (int base = 0; base < total; base += 256 * 8) stage_pass(base);
     }
-    if (r0 < RPP) {
+    unsigned char *wr = smem + a.win_bytes + a.wl_bytes + 4 * ND;   // NHWC: the weight rows as they came
+    if (NHWC) {
+        if (last >= 0) {
+#pragma unroll
+            for (int u = 0; u < WRAW; ++u) {
+                const int i = tid + u * 256;
+                if (i < raw_dw) *reinterpret_cast<unsigned *>(wr + 4 * i) = wraw[u] >> (8 * (unsigned)max(4 * i - last, 0));
+            }
+        } else {
+            for (int i = tid; i < rows * a.w_row; i += 256) wr[i] = (unsigned char)wsrc[i];
+        }
+        __syncthreads();
+        // LDS dword d of a row: bytes s' = ws0 .. ws0+3 of kernel row wcr, s' = s*C + c, from KCRS byte (c*R + wcr)*S + s
+        if (r0 < RPP) {
+            int src_off[4];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int sp = ws0 + b, sx = fast_div(sp, a.m_gC), c = sp - sx * a.gC;
+                src_off[b] = real && sp < a.w_S ? c * a.gRS + wcr * a.gS + sx : 0;   // (`mask` clears the bytes that are not there)
+            }
+            // all the byte reads first, straight-line: one LDS round trip for a thread's rows, not one per row
+            unsigned wb[WMAX][4];
+#pragma unroll
+            for (int u = 0; u < WMAX; ++u) {
+                const int row = min(r0 + u * RPP, rows - 1);
+#pragma unroll
+                for (int b = 0; b < 4; ++b) wb[u][b] = wr[row * a.w_row + src_off[b]];
+            }
+#pragma unroll
+            for (int u = 0; u < WMAX; ++u) {
+                const int row = r0 + u * RPP;
+                if (row < rows)
+                    *reinterpret_cast<unsigned *>(wl + row * a.w_pitch + 4 * d) =
+                        (wb[u][0] | (wb[u][1] << 8) | (wb[u][2] << 16) | (wb[u][3] << 24)) & mask;
+            }
+        }
+    } else if (r0 < RPP) {
         if (last >= 0) {
 #pragma unroll
             for (int u = 0; u < WMAX; ++u) {
@@ -177,7 +232,7 @@ __global__ void __launch_bounds__(256, 6) conv_window_kernel(const WindowArgs a)
     // 4. MFMA.  A pixel's four bytes start at any byte of the window: two aligned dwords and a
     //    byte-align (unaligned LDS reads are served one lane at a time).
     const int pw = wave >> a.qshift, qw = wave & ((1 << a.qshift) - 1);
-    const int abyte = (pw * a.stride) * a.pitch + delta + (qw * 32 + l31) * a.stride;
+    const int abyte = (pw * a.stride) * a.pitch + delta + (qw * 32 + l31) * a.stride_w;
     const unsigned char *a4 = win + (abyte & ~3);  // table offsets are multiples of 4: the byte shift is the lane's own
     const unsigned ash = (unsigned)abyte & 3u;
     const unsigned char *wbase = wl + l31 * a.w_pitch + half * 16;
@@ -217,6 +272,47 @@ __global__ void __launch_bounds__(256, 6) conv_window_kernel(const WindowArgs a)
     }
     const size_t PQ = (size_t)a.P * a.Q;
     int32_t *outn = a.out + (size_t)n * a.K * PQ;
+    if (a.out_nhwc && a.out_wide_k) {
+        // a lane's v%4 are channels k .. k+3 of its pixel: each wave lays its 32 pixels x KB channels out in LDS
+        // as the result has them ([pixel][channel], rows of KB + 4 dwords) and stores 16-byte pieces with the
+        // pieces of a pixel in consecutive lanes -- the channel runs of consecutive pixels follow each other in
+        // the result, so a store instruction writes whole runs instead of 32-byte pairs
+        __syncthreads();  // every wave is done with the window and the weights
+        constexpr int TPITCH = KB + 4, CPP = KB / 4;   // dwords per pixel row; 16-byte pieces per pixel
+        int *T = reinterpret_cast<int *>(smem) + wave * (32 * TPITCH);
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+            for (int vg = 0; vg < 4; ++vg)
+                *reinterpret_cast<v4i *>(T + l31 * TPITCH + kb * 32 + 8 * vg + 4 * half) =
+                    v4i{acc[kb][4 * vg], acc[kb][4 * vg + 1], acc[kb][4 * vg + 2], acc[kb][4 * vg + 3]};
+        __builtin_amdgcn_wave_barrier();  // LDS serves a wave's accesses in order
+        const int p = p0 + pw, pc = lane % CPP, pr0 = lane / CPP;
+        if (p >= a.P || k0 + 4 * pc >= a.K) return;
+        int32_t *row = outn + ((size_t)p * a.Q) * a.K + k0 + 4 * pc;
+#pragma unroll
+        for (int j = 0; j < CPP / 2; ++j) {
+            const int pr = pr0 + j * (64 / CPP), q = q0 + qw * 32 + pr;
+            const v4i t = *reinterpret_cast<const v4i *>(T + pr * TPITCH + 4 * pc);
+            if (q < a.Q) *reinterpret_cast<v4i *>(row + (size_t)q * a.K) = t;
+        }
+        return;
+    }
+    if (a.out_nhwc) {   // results that do not start on 16 bytes, or K % 4 != 0: one by one
+        const int p = p0 + pw, q = q0 + qw * 32 + l31;
+        if (p >= a.P || q >= a.Q) return;
+        int32_t *px = outn + ((size_t)p * a.Q + q) * a.K;
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb)
+#pragma unroll
+            for (int vg = 0; vg < 4; ++vg) {
+                const int k = k0 + kb * 32 + 8 * vg + 4 * half;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (k + j < a.K) px[k + j] = acc[kb][4 * vg + j];
+            }
+        return;
+    }
     if (a.wide_out) {
         // Q a multiple of 4 and `out` 16-byte aligned: each wave turns its 32x32 block around in LDS
         // (rows of 36 dwords) so that a lane stores four consecutive pixels of one channel -- 16-byte
@@ -299,31 +395,44 @@ constexpr long long WINDOW_LIMIT = 40 * 1024;  // bytes of LDS the input window 
 // Tile shape by output width, window geometry and the LDS it needs.
 static bool window_plan(const WindowProblem &g, WindowArgs *a)
 {
-    const int depth = window_depth(g.C, g.R, g.S);
-    if (depth == 0 || g.W < 4) return false;
+    if (g.nhwc_in && (g.wt_rewritten || (long long)g.S * g.C > 4096 || (long long)g.W * g.C > 2147483647LL ||
+                      (long long)g.stride * g.C > 65536 || (long long)g.pad * g.C > 2147483647LL))
+        return false;
+    // an NHWC source is computed as one channel of W*C columns under a kernel row of S*C bytes
+    const int C = g.nhwc_in ? 1 : g.C, W = g.nhwc_in ? g.W * g.C : g.W, S = g.nhwc_in ? g.S * g.C : g.S;
+    const long long stride_w = g.nhwc_in ? (long long)g.stride * g.C : g.stride;
+    const int depth = window_depth(C, g.R, S);
+    if (depth == 0 || W < 4) return false;
     WindowArgs w{};
     w.in = g.in;
     w.wt = g.wt;
     w.out = g.out;
-    w.C = g.C; w.H = g.H; w.W = g.W; w.K = g.K; w.P = g.P; w.Q = g.Q; w.R = g.R;
+    w.C = C; w.H = g.H; w.W = W; w.K = g.K; w.P = g.P; w.Q = g.Q; w.R = g.R;
     w.stride = g.stride; w.pad = g.pad;
+    w.stride_w = (int)stride_w; w.pad_w = g.nhwc_in ? g.pad * g.C : g.pad;
+    w.gC = g.C; w.gS = g.S; w.gRS = g.R * g.S;
+    w.m_gC = magic_for(g.C);
+    w.nhwc = g.nhwc_in;
+    w.out_nhwc = g.out_nhwc;
+    w.out_wide_k = g.K % 4 == 0 && (reinterpret_cast<uintptr_t>(g.out) & 15) == 0;
     w.qshift = g.Q > 64 ? 2 : g.Q > 32 ? 1 : 0;
     w.PT = 4 >> w.qshift;
     const int QT = 32 << w.qshift;
-    const int S4 = (g.S + 3) / 4 * 4;
+    const int S4 = (S + 3) / 4 * 4;
     const long long RW = (long long)(w.PT - 1) * g.stride + g.R;
-    const long long pitch = (((long long)(QT - 1) * g.stride + S4 + 3) + 3) / 4 * 4;
-    if (RW > WINDOW_LIMIT || pitch > WINDOW_LIMIT || g.C * RW * pitch > WINDOW_LIMIT) return false;
+    const long long pitch = (((long long)(QT - 1) * stride_w + S4 + 3) + 3) / 4 * 4;
+    if (RW > WINDOW_LIMIT || pitch > WINDOW_LIMIT || C * RW * pitch > WINDOW_LIMIT) return false;
     w.RW = (int)RW;
-    const long long win = (g.C * RW * pitch + 4 + 15) / 16 * 16;  // + the dword after the last one (read, never used)
-    w.CR = g.C * g.R;
+    const long long win = (C * RW * pitch + 4 + 15) / 16 * 16;  // + the dword after the last one (read, never used)
+    w.CR = C * g.R;
     w.nd = S4 / 4;
-    w.w_S = g.wt_rewritten ? S4 : g.S;
-    w.w_row = g.wt_rewritten ? depth : g.C * g.R * g.S;
+    w.w_S = g.wt_rewritten ? S4 : S;
+    w.w_row = g.wt_rewritten ? depth : C * g.R * S;
     w.w_pitch = depth + 16;
     const int kb = g.K > 32 ? 64 : 32;
     const long long wlb = (long long)kb * w.w_pitch;
-    if (win + 8 + wlb + depth > 64 * 1024) return false;  // cannot happen within the limits above
+    const long long raw = g.nhwc_in ? ((long long)kb * w.w_row + 3) / 4 * 4 : 0;   // the weight rows as they came
+    if (win + 8 + wlb + depth + raw > 64 * 1024) return false;  // cannot happen within the limits above
     w.pitch = (int)pitch;
     w.win_bytes = (int)win;
     w.wl_bytes = (int)wlb;
@@ -337,7 +446,7 @@ static bool window_plan(const WindowProblem &g, WindowArgs *a)
     w.m_tiles_q = magic_for(w.tiles_q);
     w.m_tiles_p = magic_for(w.tiles_p);
     w.out_small = 4LL * g.K * g.P * g.Q < (1LL << 32);
-    w.in_small = (long long)g.C * g.H * g.W < (1LL << 31);
+    w.in_small = (long long)C * g.H * W < (1LL << 31);
     w.wide_out = g.Q % 4 == 0 && (reinterpret_cast<uintptr_t>(g.out) & 15) == 0;
     w.act = g.act;
     if (a) *a = w;
@@ -349,11 +458,19 @@ bool window_fits(const WindowProblem &g) { return window_plan(g, nullptr); }
 template <int NKK>
 static hipError_t launch_window_nkk(const WindowArgs &a, dim3 grid, size_t lds, hipStream_t st)
 {
+    if (a.nhwc) {
+        if (a.act.out) {
+            if (a.K > 32) hipLaunchKernelGGL((conv_window_kernel<NKK, 2, true, true>), grid, dim3(256), lds, st, a);
+            else hipLaunchKernelGGL((conv_window_kernel<NKK, 1, true, true>), grid, dim3(256), lds, st, a);
+        } else if (a.K > 32) hipLaunchKernelGGL((conv_window_kernel<NKK, 2, false, true>), grid, dim3(256), lds, st, a);
+        else hipLaunchKernelGGL((conv_window_kernel<NKK, 1, false, true>), grid, dim3(256), lds, st, a);
+        return hipGetLastError();
+    }
     if (a.act.out) {
-        if (a.K > 32) hipLaunchKernelGGL((conv_window_kernel<NKK, 2, true>), grid, dim3(256), lds, st, a);
-        else hipLaunchKernelGGL((conv_window_kernel<NKK, 1, true>), grid, dim3(256), lds, st, a);
-    } else if (a.K > 32) hipLaunchKernelGGL((conv_window_kernel<NKK, 2, false>), grid, dim3(256), lds, st, a);
-    else hipLaunchKernelGGL((conv_window_kernel<NKK, 1, false>), grid, dim3(256), lds, st, a);
+        if (a.K > 32) hipLaunchKernelGGL((conv_window_kernel<NKK, 2, true, false>), grid, dim3(256), lds, st, a);
+        else hipLaunchKernelGGL((conv_window_kernel<NKK, 1, true, false>), grid, dim3(256), lds, st, a);
+    } else if (a.K > 32) hipLaunchKernelGGL((conv_window_kernel<NKK, 2, false, false>), grid, dim3(256), lds, st, a);
+    else hipLaunchKernelGGL((conv_window_kernel<NKK, 1, false, false>), grid, dim3(256), lds, st, a);
     return hipGetLastError();
 }
 
@@ -361,11 +478,12 @@ hipError_t launch_window_conv(const WindowProblem &g, hipStream_t st)
 {
     WindowArgs a;
     if (!window_plan(g, &a)) return hipErrorInvalidValue;
-    const int depth = window_depth(g.C, g.R, g.S);
+    const int depth = a.w_pitch - 16;
     const int kb = g.K > 32 ? 64 : 32;
     const dim3 grid((unsigned)(g.N * a.tiles_p * a.tiles_q), (unsigned)((g.K + kb - 1) / kb));
-    size_t lds = (size_t)a.win_bytes + a.wl_bytes + (size_t)depth;
+    size_t lds = (size_t)a.win_bytes + a.wl_bytes + (size_t)depth + (g.nhwc_in ? ((size_t)kb * a.w_row + 3) / 4 * 4 : 0);
     if (lds < 4 * 32 * 36 * 4) lds = 4 * 32 * 36 * 4;  // the output blocks of the four waves, turned around
+    if (g.out_nhwc && lds < (size_t)4 * 32 * (kb + 4) * 4) lds = (size_t)4 * 32 * (kb + 4) * 4;
     switch (depth / 32) {
         case 2: return launch_window_nkk<2>(a, grid, lds, st);
         case 4: return launch_window_nkk<4>(a, grid, lds, st);

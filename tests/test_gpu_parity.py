@@ -823,6 +823,55 @@ def test_conv_nhwc_one_shot(lib, cfg):
     assert np.array_equal(host(view), want) and int(buf[0]) == -3 and int(buf[-1]) == -3
 
 
+NHWC_WINDOW_SHAPES = [
+    ConvShape("nhwc-stem", 2, 3, 40, 52, 64, 7, 7, 2, 3),          # the C3 kind: S*C = 21 bytes per kernel row
+    ConvShape("nhwc-speech", 1, 1, 61, 90, 32, 20, 5, 2, 0),       # the C5 kind: one channel
+    ConvShape("nhwc-k70", 1, 5, 17, 23, 70, 3, 3, 1, 1),           # two channel blocks, the second ragged; K % 4 != 0
+    ConvShape("nhwc-k7", 3, 2, 9, 40, 7, 5, 4, 3, 2),              # fewer channels than one dword of results
+    ConvShape("nhwc-wide", 1, 4, 6, 300, 16, 3, 5, 1, 2),          # several tiles per row and a ragged last one
+    ConvShape("nhwc-c13", 1, 13, 12, 12, 32, 2, 3, 1, 0),          # S*C = 39: a kernel row that is not whole dwords
+]
+
+
+@pytest.mark.parametrize("cfg", NHWC_WINDOW_SHAPES, ids=lambda c: c.name)
+def test_conv_nhwc_unrolling_kernel(lib, cfg):
+    """Shapes the selector gives to the kernel that unrolls the stencil itself, from an NHWC source (Sec. 5.2):
+    depth order (r, s, c), KCRS weights reordered inside the kernel, NHWC result.  One launch: the cached
+    workspace is not touched."""
+    assert lib.select_layout(cfg.dims())[0] == lib.LAYOUT_IMPLICIT and cfg.R * (-(-cfg.S * cfg.C // 4) * 4) <= 256
+    x = uniform_int8(711, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(712, (cfg.K, cfg.C, cfg.R, cfg.S))
+    want = layouts.unpack_nhwc(direct.conv2d_int8(x, w, cfg.stride, cfg.pad))
+    xh = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+    got = host(lib.conv2d_int8_nhwc(dev(xh), dev(w), cfg.stride, cfg.pad))
+    assert got.shape == want.shape and np.array_equal(got, want)
+    buf = torch.full((want.size + 4,), -3, dtype=torch.int32, device=DEV)   # a result that starts on 4 bytes only
+    view = buf[1:1 + want.size].view(want.shape)
+    lib.conv2d_int8_nhwc(dev(xh), dev(w), cfg.stride, cfg.pad, out=view)
+    assert np.array_equal(host(view), want) and int(buf[0]) == -3 and int(buf[-1]) == -3
+
+
+def test_conv_nhwc_unrolling_kernel_random_shapes(lib):
+    rng = np.random.default_rng(8128)
+    done = 0
+    for _ in range(400):
+        if done == 24:
+            break
+        C = int(rng.choice([1, 2, 3, 4, 5, 7, 12])); R = int(rng.integers(1, 8)); S = int(rng.integers(1, 8))
+        st = int(rng.integers(1, 4)); pad = int(rng.integers(0, 4)); K = int(rng.choice([3, 16, 32, 33, 64, 100]))
+        H = int(rng.integers(R, 30)); W = int(rng.integers(max(S, 2), 80)); N = int(rng.integers(1, 3))
+        cfg = ConvShape("r", N, C, H, W, K, R, S, st, pad)
+        if cfg.P < 1 or cfg.Q < 1 or W * C < 4 or R * (-(-S * C // 4) * 4) > 256:
+            continue
+        if lib.select_layout(cfg.dims())[0] != lib.LAYOUT_IMPLICIT:
+            continue
+        x = uniform_int8(7000 + done, (N, C, H, W)); w = uniform_int8(7100 + done, (K, C, R, S))
+        want = layouts.unpack_nhwc(direct.conv2d_int8(x, w, st, pad))
+        got = host(lib.conv2d_int8_nhwc(dev(np.ascontiguousarray(x.transpose(0, 2, 3, 1))), dev(w), st, pad))
+        assert np.array_equal(got, want), cfg.dims()
+        done += 1
+    assert done == 24
+
+
 # ---- activation between layers -------------------------------------------------------------------
 @pytest.mark.parametrize("shift,relu", [(0, False), (0, True), (1, False), (7, True), (10, False), (31, False)])
 def test_requant(lib, shift, relu):
