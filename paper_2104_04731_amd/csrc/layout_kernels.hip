@@ -456,6 +456,7 @@ __device__ __forceinline__ void im2col_tiled_body(const I2cArgs &a, int bid, uns
             v4i v[4];
             int hh[4], ww[4];
             long long want[4];
+            bool moved[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int idx = min(base + u * 256 + (int)threadIdx.x, total - 1);
@@ -464,23 +465,16 @@ __device__ __forceinline__ void im2col_tiled_body(const I2cArgs &a, int bid, uns
                 hh[u] = h_lo + r, ww[u] = w_lo + 16 * t;
                 want[u] = img_off + ((long long)cl * a.H + min(max(hh[u], 0), a.H - 1)) * a.W + ww[u];
                 const long long at = min(max(want[u], 0LL), a.src_bytes - 16);
-                __builtin_memcpy(&v[u], src + at, 16);
-                if (at != want[u]) {   // the tensor's first or last bytes: byte by byte
-                    asm volatile("" ::: "memory");   // stays a branch
-                    unsigned x[4] = {0u, 0u, 0u, 0u};
-#pragma nounroll
-                    for (int k = 0; k < 16; ++k)
-                        if (want[u] + k >= 0 && want[u] + k < a.src_bytes) {
-                            const unsigned b = (unsigned)(unsigned char)src[want[u] + k] << (8 * (k & 3));
-#pragma unroll
-                            for (int m = 0; m < 4; ++m)
-                                if ((k >> 2) == m) x[m] |= b;
-                        }
-                    v[u] = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
-                }
+                moved[u] = at != want[u];
+                __builtin_memcpy(&v[u], src + at, 16);   // (nothing that needs the data between the loads)
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
+                if (moved[u]) {   // the tensor's first or last bytes: byte by byte
+                    asm volatile("" ::: "memory");   // stays a branch
+                    const long long at = min(max(want[u], 0LL), a.src_bytes - 16);
+                    v[u] = at - want[u] > -16 && at - want[u] < 16 ? shift_piece(v[u], (int)(at - want[u])) : v4i{0, 0, 0, 0};
+                }
                 const bool rowok = hh[u] >= 0 && hh[u] < a.H;
                 const int lo = min(max(-ww[u], 0), 16), hi = rowok ? min(max(a.W - ww[u], 0), 16) : 0;
                 v4i x;
@@ -1588,17 +1582,8 @@ __global__ void __launch_bounds__(256) phase_split2_kernel(const PhaseSplit2Args
     __builtin_memcpy(&hi4, a.src + o2, 16);
     if (o1 != want || o2 != want + 16) {   // the tensor's first or last bytes: byte by byte
         asm volatile("" ::: "memory");     // stays a branch: only the first and the last rows come here
-        unsigned x[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
-#pragma nounroll
-        for (int k = 0; k < 32; ++k)
-            if (want + k >= 0 && want + k < bytes) {
-                const unsigned b = (unsigned)(unsigned char)a.src[want + k] << (8 * (k & 3));
-#pragma unroll
-                for (int m = 0; m < 8; ++m)
-                    if ((k >> 2) == m) x[m] |= b;
-            }
-        lo4 = v4i{(int)x[0], (int)x[1], (int)x[2], (int)x[3]};
-        hi4 = v4i{(int)x[4], (int)x[5], (int)x[6], (int)x[7]};
+        lo4 = o1 - want > -16 && o1 - want < 16 ? shift_piece(lo4, (int)(o1 - want)) : v4i{0, 0, 0, 0};
+        hi4 = o2 - want - 16 > -16 && o2 - want - 16 < 16 ? shift_piece(hi4, (int)(o2 - want - 16)) : v4i{0, 0, 0, 0};
     }
     // bytes [lo, hi) of the 32 lie inside the image row (none of them when the row itself is padding)
     unsigned x[8];

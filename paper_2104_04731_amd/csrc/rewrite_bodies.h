@@ -10,6 +10,18 @@ namespace c2i8 {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));  // 16 bytes at a dword-aligned address
 typedef int v4i_a1 __attribute__((ext_vector_type(4), aligned(1)));  // 16 bytes at any address
+// A 16-byte piece wanted from byte offset `want` of a tensor was fetched from `at` instead (`want` clamped into the
+// tensor, |at - want| < 16): move the bytes to where they belong, zeros coming in -- the bytes that were outside the
+// tensor.  Registers only: the workgroup that holds a tensor's first bytes sets the kernel's time at small sizes,
+// and a second memory round trip there showed in it.
+__device__ __forceinline__ v4i shift_piece(v4i v, int at_minus_want)
+{
+    unsigned __int128 x;
+    __builtin_memcpy(&x, &v, 16);
+    x = at_minus_want > 0 ? x << (8 * at_minus_want) : x >> (8 * -at_minus_want);
+    __builtin_memcpy(&v, &x, 16);
+    return v;
+}
 
 // Workgroups are dealt round-robin over the 8 XCDs (each with its own L2).  Mapping the
 // hardware id to a logical id that is contiguous per XCD makes neighbouring tiles -- which
