@@ -1371,9 +1371,68 @@ hipError_t launch_dilation_pack(int N, int C, int H, int W, int pad, int d, int 
     return hipGetLastError();
 }
 
+// Dilation 2: output row p = 2i + a takes its even columns from row i of sub-result (a, 0) and its odd columns from
+// row i of sub-result (a, 1).  A thread loads four consecutive values of each (16 bytes, dword-aligned) and stores
+// the eight interleaved values as two 16-byte pieces; consecutive lanes take consecutive groups of a row, then the
+// next row, so both sides move in contiguous runs.  Rows shorter than a group, an odd last column, and the very end
+// of the tensor go value by value.
+struct Unpack2Args {
+    const int32_t *src;
+    int32_t *dst;
+    int K, P, Q, P2, Q2, ngrp;
+    long long items, src_elems;   // N*K * P * ngrp; elements of the sub-results
+    unsigned m_ngrp, m_P, m_K;
+};
+__global__ void __launch_bounds__(256) dilation_unpack2_kernel(const Unpack2Args a)
+{
+    const long long it = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (it >= a.items) return;
+    const int row = fast_div_any((int)it, a.ngrp, a.m_ngrp), g = (int)it - row * a.ngrp;   // (items < 2^31: the launcher checks)
+    const int plane = fast_div_any(row, a.P, a.m_P), p = row - plane * a.P;
+    const int n = fast_div_any(plane, a.K, a.m_K), k = plane - n * a.K;
+    // (the last group of a row is moved back to end with the row: it overlaps its neighbour, both write the same values)
+    const int i = p >> 1, pa = p & 1, j0 = a.Q2 >= 4 ? min(4 * g, a.Q2 - 4) : 0;
+    const long long sub_sz = (long long)a.P2 * a.Q2;
+    const long long s0 = (((long long)(n * 2 + pa) * 2 + 0) * a.K + k) * sub_sz + (long long)i * a.Q2 + j0;
+    const long long s1 = s0 + (long long)a.K * sub_sz;
+    int32_t *o = a.dst + ((long long)plane * a.P + p) * a.Q + 2 * j0;
+    if (j0 + 4 <= a.Q2 && 2 * j0 + 8 <= a.Q && s1 + 4 <= a.src_elems) {
+        const v4i e = *reinterpret_cast<const v4i_a4 *>(a.src + s0), f = *reinterpret_cast<const v4i_a4 *>(a.src + s1);
+        __builtin_nontemporal_store(v4i{e[0], f[0], e[1], f[1]}, reinterpret_cast<v4i_a4 *>(o));
+        __builtin_nontemporal_store(v4i{e[2], f[2], e[3], f[3]}, reinterpret_cast<v4i_a4 *>(o + 4));
+    } else {   // (every wave has such lanes when rows are not whole groups: the eight loads first, then the stores)
+        int32_t e[4], f[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int ju = min(j0 + u, a.Q2 - 1) - j0;
+            e[u] = a.src[s0 + ju];
+            f[u] = a.src[s1 + ju];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (j0 + u < a.Q2 && 2 * (j0 + u) < a.Q) o[2 * u] = e[u];
+            if (j0 + u < a.Q2 && 2 * (j0 + u) + 1 < a.Q) o[2 * u + 1] = f[u];
+        }
+    }
+}
+
 hipError_t launch_dilation_unpack(int N, int K, int P, int Q, int d, int P2, int Q2, const int32_t *src, int32_t *dst,
                                   hipStream_t st)
 {
+    if (d == 2 && (long long)N * K * P <= 2147483647LL && (long long)N * 2 <= 1073741823LL) {
+        Unpack2Args b{};
+        b.src = src, b.dst = dst;
+        b.K = K, b.P = P, b.Q = Q, b.P2 = P2, b.Q2 = Q2;
+        b.ngrp = (Q2 + 3) / 4;
+        b.items = (long long)N * K * P * b.ngrp;
+        b.src_elems = 4LL * N * K * P2 * Q2;
+        b.m_ngrp = magic_for(b.ngrp), b.m_P = magic_for(P), b.m_K = magic_for(K);
+        const long long blocks = (b.items + 255) / 256;
+        if (b.items <= 2147483647LL) {
+            hipLaunchKernelGGL(dilation_unpack2_kernel, dim3((unsigned)blocks), dim3(256), 0, st, b);
+            return hipGetLastError();
+        }
+    }
     DilationArgs a{};
     a.src = src;
     a.dst = dst;
