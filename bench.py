@@ -32,8 +32,8 @@ PEAK_HBM_BPS = 8.0e12    # HBM3E
 TRAFFIC = {
     "source": "paper_2104_04731_amd/csrc/band_mfma.hip",
     "sha256": "cf923172c294c91ebc13993e1ffd641e1690f034d9723c06d2a74033ad93224c",
-    "fetch_bytes": 5516689,
-    "write_bytes": 3211878,
+    "fetch_bytes": 5516695,
+    "write_bytes": 3211264,
 }
 
 
