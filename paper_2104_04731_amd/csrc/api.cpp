@@ -636,8 +636,12 @@ int conv2d_int8_dilated(const conv_desc_t *desc, int dilation, int layout, int c
     g.il_d = dilation;
     g.il_P = dp.P;
     g.il_Q = dp.Q;
+    // no depth split (the activation needs the whole sum): the band kernel, or the best tile of the general one
     int t = -1, s = 1;
-    if (!gemm_pick(g, &t, &s)) return CONV_ERR_UNSUPPORTED;
+    double cost = 0;
+    const bool tiled = gemm_pick(g, &t, &s, &cost);
+    if (band_applies(g) && (!tiled || band_cost(g) < cost)) return gemm_status(launch_band_conv(g, st));
+    if (!tiled) return CONV_ERR_UNSUPPORTED;
     return gemm_status(launch_gemm(g, t, 1, st));
 }
 
@@ -792,8 +796,12 @@ int conv2d_int8_packed_requant(const conv_desc_t *desc, int layout, int cb, cons
     g.act_relu = relu != 0;
     g.o_cb = out_cb;
     g.o_pad = out_pad;
+    // no depth split (the activation needs the whole sum): the band kernel, or the best tile of the general one
     int t = -1, s = 1;
-    if (!gemm_pick(g, &t, &s)) return CONV_ERR_UNSUPPORTED;
+    double cost = 0;
+    const bool tiled = gemm_pick(g, &t, &s, &cost);
+    if (band_applies(g) && (!tiled || band_cost(g) < cost)) return gemm_status(launch_band_conv(g, st));
+    if (!tiled) return CONV_ERR_UNSUPPORTED;
     return gemm_status(launch_gemm(g, t, 1, st));
 }
 

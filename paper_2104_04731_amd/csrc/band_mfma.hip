@@ -27,14 +27,13 @@
 // Both LDS operands are XOR-swizzled per 64-byte row ((row/4)%4 on the 16-byte chunk index), done
 // by the lanes' choice of source chunk, so the column-wise fragment reads spread over all banks.
 #include "kernels.h"
+#include "rewrite_bodies.h"
 
 #include <type_traits>
 
 namespace c2i8 {
 
 namespace {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int BAND_WAVES = 4, BAND_TK = 32;
 constexpr size_t BAND_LDS_LIMIT = 160 * 1024;
@@ -44,7 +43,9 @@ constexpr int BAND_KPW_MAX = 12;
 struct BandArgs {
     const int8_t *act;  // [N][Cb][Hp][Wp][64]
     const int8_t *wq;   // [K][depth], depth index ((b*R + r)*S + s)*64 + c
-    int32_t *out;       // [N][K][P][Q]
+    int32_t *out;       // [N][K][P][Q], or [N][P][Q][K] (out_nhwc)
+    int out_nhwc, out_wide_k;    // NHWC result; K % 4 == 0 and out on 16 bytes: a lane's four channels go out as one piece
+    ActOut aout;                 // activation epilogue (aout.out != null): `out` is not written
     int K, P, Q, Wp, stride;
     int depth, ksteps, kpw;      // bytes per weight row; 64-byte steps in all and per wave
     int PT, bands;               // output rows per band, bands per image
@@ -327,7 +328,32 @@ __global__ void __launch_bounds__(BAND_WAVES * 64, 1) conv_band_kernel(const Ban
             valid = i < 2 * PB && px < a.npix && p0 + pr < a.P;
             off = (unsigned)(rb * 16 * plane + (p0 + pr) * a.Q + q + lane_off - col);
         }
-        if (k_whole) {
+        // A lane's four values are channels k .. k+3 of one pixel: one piece of an NHWC result, one dword of the
+        // next layer's blocked input after the activation.  (Wave-uniform tests: one of the three forms runs.)
+        if (a.out_nhwc | (a.aout.out != nullptr)) {
+            int pp, qq;
+            if (SROW > 1) {
+                const int pr = bdiv_small(pb, a.mg_CTN);
+                pp = p0 + pr, qq = (pb - pr * a.CTN) * a.CT + col;
+            } else {
+                const int px = pb * 16 + col, pr = bdiv_small(px, a.mg_Q);
+                pp = p0 + pr, qq = px - pr * a.Q;
+            }
+            const int k = k0 + rb * 16 + 4 * grp;
+            if (valid && k < a.K) {
+                if (a.aout.out) {
+                    act_store4(a.aout, n, pp, qq, k, a.K, sum[0], sum[1], sum[2], sum[3]);
+                } else {
+                    int32_t *px = a.out + (((size_t)n * a.P + pp) * a.Q + qq) * a.K + k;
+                    if (a.out_wide_k) *reinterpret_cast<v4i *>(px) = sum;
+                    else {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            if (k + v < a.K) px[v] = sum[v];
+                    }
+                }
+            }
+        } else if (k_whole) {
             if (valid) {
                 out0[off] = sum[0];
                 out1[off] = sum[1];
@@ -361,7 +387,8 @@ unsigned magic_of(long long d) { return d <= 1 ? 0u : (unsigned)((0x100000000ULL
 // Fills the plan; false where the kernel does not apply.
 bool band_plan(const GemmProblem &g, BandPlan *bp)
 {
-    if (g.mode != ACT_BLOCKED || g.cb != 64 || g.act_out || g.il_d || g.out_nhwc) return false;
+    if (g.mode != ACT_BLOCKED || g.cb != 64 || g.il_d) return false;
+    if (g.act_out && (g.o_cb < 4 || (g.o_cb & (g.o_cb - 1)))) return false;
     if (g.Q <= 0 || g.PQ % g.Q) return false;
     const int P = g.PQ / g.Q, Q = g.Q, dil = g.dil > 0 ? g.dil : 1;
     const long long ksteps = (long long)g.Cb * g.R * g.S;
@@ -413,6 +440,14 @@ bool band_plan(const GemmProblem &g, BandPlan *bp)
     a.act = g.act;
     a.wq = g.wq;
     a.out = g.out;
+    a.out_nhwc = g.out_nhwc;
+    a.out_wide_k = g.K % 4 == 0 && (reinterpret_cast<uintptr_t>(g.out) & 15) == 0;
+    a.aout = ActOut{};
+    if (g.act_out) {
+        int lg = 0;
+        while ((1 << lg) < g.o_cb) ++lg;
+        a.aout = ActOut{g.act_out, g.act_shift, g.act_relu, lg, g.o_pad, P + 2 * g.o_pad, Q + 2 * g.o_pad, (g.K + g.o_cb - 1) / g.o_cb};
+    }
     a.K = g.K;
     a.P = P;
     a.Q = Q;

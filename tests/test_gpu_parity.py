@@ -289,6 +289,26 @@ def test_band_kernel_shapes(lib, cfg):
     assert np.array_equal(got, want), f"{cfg.name}: {np.count_nonzero(got != want)} mismatches"
 
 
+@pytest.mark.parametrize("cfg", [c for c in BAND_SHAPES if c.name not in ("band-stride2", "band-deep", "band-too-wide")],
+                         ids=lambda c: c.name)
+def test_band_kernel_nhwc_result_and_activation(lib, cfg):
+    """The band kernel's other two epilogues: the NHWC result (forced through the tile argument) and the activation + next layer's blocking (the GEMM stage picks
+    its kernel itself there: for the benchmark shapes that is the band kernel).  Output channels that are not a
+    multiple of four take the value-by-value stores."""
+    x, w = cfg.make() if cfg.name in CONFIGS else (uniform_int8(511, (cfg.N, cfg.C, cfg.H, cfg.W)), uniform_int8(512, (cfg.K, cfg.C, cfg.R, cfg.S)))
+    ref = direct.conv2d_int8(x, w, cfg.stride, cfg.pad)
+    xp = lib.pack_layout(dev(x), 64, cfg.pad); wp = lib.pack_weights(dev(w), lib.LAYOUT_PACKED, 64)
+    want = layouts.unpack_nhwc(ref)
+    buf = torch.full((want.size + 8,), -7, dtype=torch.int32, device=DEV)
+    view = buf[4:4 + want.size].view(want.shape)     # (the entry point asks for a result on 16 bytes)
+    lib.conv2d_int8_packed_nhwc(cfg.dims(), lib.LAYOUT_PACKED, 64, xp, wp, view, tile=lib.TILE_BAND)
+    assert np.array_equal(host(view), want), cfg.name
+    assert int(buf[3]) == -7 and int(buf[4 + want.size]) == -7
+    for out_cb, out_pad, shift, relu in ((64, 1, 9, True), (16, 0, 7, False)):
+        got = host(lib.conv2d_int8_packed_requant(cfg.dims(), lib.LAYOUT_PACKED, 64, xp, wp, out_cb, out_pad, shift, relu))
+        np.testing.assert_array_equal(got, layouts.pack_layout(layouts.requant(ref, shift, relu), out_cb, out_pad), err_msg=cfg.name)
+
+
 def test_band_kernel_other_layouts_and_dilation(lib):
     """It takes 64-channel blocks only (PAD_ONLY over exactly 64 channels is such a layout); kernel taps a
     dilation apart are address offsets into its window like any other."""
