@@ -982,6 +982,22 @@ int conv2d_int8_nhwc(int N, int C, int H, int W, int K, int R, int S, int stride
                 return launch_window_conv(wp, (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
         }
     }
+    if (R == 1 && S == 1 && stride == 1 && pad == 0 && C % CONV_DEPTH_ALIGN == 0 && aligned16(in) && aligned16(wt) && aligned16(out)) {
+        // A 1x1 layer on NHWC tensors is a plain matrix product of operands that are depth-contiguous as they are:
+        // pixels x channels times the weight rows, into pixels x output channels.  No rewrite, one launch.
+        GemmProblem g{};
+        g.act = in;
+        g.wq = wt;
+        g.out = out;
+        g.K = K;
+        g.M = (int)pl.M;
+        g.depth = C;
+        g.PQ = pl.P * pl.Q;
+        g.Q = pl.Q;
+        g.mode = ACT_MATRIX;
+        g.out_nhwc = 1;
+        return run_gemm(g, -1, 0, (hipStream_t)stream);
+    }
     // The GEMM stage's epilogue writes NHWC itself (a lane's four values are four consecutive channels of a
     // pixel); only a result that does not start on 16 bytes goes through an NKPQ staging tensor and a pass.
     const bool direct = aligned16(out);

@@ -828,7 +828,10 @@ def test_unpack_nhwc(lib, shape):
 @pytest.mark.parametrize("cfg", [CONFIGS["C1"], CONFIGS["C2"], CONFIGS["C4a"], CONFIGS["C4b"], CONFIGS["C3"],
                                  ConvShape("nhwc-ragged", 2, 37, 9, 11, 21, 3, 2, 2, 1),
                                  ConvShape("nhwc-deep", 1, 256, 7, 7, 64, 3, 3, 1, 1),      # small and deep: a depth split
-                                 ConvShape("nhwc-k130", 1, 32, 12, 12, 130, 3, 3, 1, 1)], ids=lambda c: c.name)
+                                 ConvShape("nhwc-k130", 1, 32, 12, 12, 130, 3, 3, 1, 1),
+                                 ConvShape("nhwc-1x1-k70", 3, 128, 7, 9, 70, 1, 1, 1, 0),   # 1x1: a plain matrix product, one launch
+                                 ConvShape("nhwc-1x1-s2", 2, 64, 9, 9, 32, 1, 1, 2, 0)],    # 1x1 with a stride: not that form
+                         ids=lambda c: c.name)
 def test_conv_nhwc_one_shot(lib, cfg):
     """NHWC in, NHWC out: the NCHW definition seen through transposed views.  The GEMM stage writes NHWC
     itself; a result that does not start on 16 bytes takes the staging tensor and the unpacking pass."""
