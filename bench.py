@@ -31,8 +31,8 @@ PEAK_HBM_BPS = 8.0e12    # HBM3E
 # describe the kernel source whose hash is recorded here; for any other source `traffic` is null.
 TRAFFIC = {
     "source": "paper_2104_04731_amd/csrc/band_mfma.hip",
-    "sha256": "cf923172c294c91ebc13993e1ffd641e1690f034d9723c06d2a74033ad93224c",
-    "fetch_bytes": 5516695,
+    "sha256": "c56ee57cf16f39d90474380977f0f3094bb72c30ebea59bd016bae760e65c2ab",
+    "fetch_bytes": 5552531,
     "write_bytes": 3211264,
 }
 
