@@ -34,7 +34,7 @@ WindowProblem window_problem(const conv_desc_t *d, const Plan &pl, const int8_t 
                              int32_t *out, int wt_rewritten)
 {
     return WindowProblem{x, w, out, d->N, d->C, d->H, d->W, d->K, pl.P, pl.Q, d->R, d->S, d->stride, d->pad,
-                         wt_rewritten, ActOut{}};
+                         wt_rewritten, ActOut{}, 0, 0};
 }
 
 int run_implicit(const Plan &pl, const WindowProblem &g, hipStream_t st)

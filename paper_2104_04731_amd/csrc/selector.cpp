@@ -52,7 +52,7 @@ extern "C" int layout_overheads(const conv_desc_t *d, int layout, int cb,
         // nothing rewritten, nothing moved twice; pixels padded per output row, kernel rows to dwords
         if (P > 2147483647LL || Q > 2147483647LL) return CONV_ERR_UNSUPPORTED;
         const c2i8::WindowProblem g{nullptr, nullptr, nullptr, d->N, d->C, d->H, d->W, d->K, (int)P, (int)Q,
-                                    d->R, d->S, d->stride, d->pad, 0};
+                                    d->R, d->S, d->stride, d->pad, 0, c2i8::ActOut{}, 0, 0};
         const bool pointwise = c2i8::pointwise_shape(d->C, d->R, d->S);
         if (!(pointwise ? c2i8::pointwise_fits(g) : c2i8::window_fits(g))) return CONV_ERR_UNSUPPORTED;
         // 1x1 over whole 64-channel multiples: pixels padded per image, depth as it is
