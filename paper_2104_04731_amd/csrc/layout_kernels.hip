@@ -178,6 +178,14 @@ __global__ void __launch_bounds__(256) pack_layout_wave_kernel(const PackWaveArg
     if (wid < a.waves) pack_layout_wave_body(a, wid, tile + wave * (PW_LDS / 4));
 }
 
+__global__ void __launch_bounds__(256) pack_layout_src_kernel(const PackSrcArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned tile[4 * PW_LDS / 4];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const long long wid = (long long)xcd_contiguous(blockIdx.x, gridDim.x) * 4 + wave;
+    if (wid < a.waves) pack_layout_src_body(a, wid, tile + wave * (PW_LDS / 4));
+}
+
 static int grid_for(long long work_items, int block)
 {
     long long g = (work_items + block - 1) / block;
@@ -210,9 +218,18 @@ hipError_t launch_pack_layout(int N, int C, int H, int W, int cb, int pad,
     const int Hp = H + 2 * pad, Wp = W + 2 * pad, Cb = (C + cb - 1) / cb;
     const long long pixels = (long long)N * Cb * Hp * Wp;
     {
+        // 64-channel slices: destination order once there are enough units to fill the chip (whole-line stores,
+        // 15 % faster there), source order below that (one round of LDS reads: a shorter dependent chain)
         PackWaveArgs a;
-        long long blocks;
-        if (plan_pack_wave(N, C, H, W, cb, pad, src, dst, &a, &blocks)) {
+        PackSrcArgs as;
+        long long blocks, blocks_s;
+        const bool dst_ok = plan_pack_wave(N, C, H, W, cb, pad, src, dst, &a, &blocks);
+        const bool src_ok = plan_pack_src(N, C, H, W, cb, pad, src, dst, &as, &blocks_s);
+        if (src_ok && !(dst_ok && a.waves >= 256 * 16)) {
+            hipLaunchKernelGGL(pack_layout_src_kernel, dim3((unsigned)blocks_s), dim3(256), 0, st, as);
+            return hipGetLastError();
+        }
+        if (dst_ok) {
             hipLaunchKernelGGL(pack_layout_wave_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
             return hipGetLastError();
         }
@@ -703,7 +720,7 @@ hipError_t launch_im2col(int N, int C, int H, int W, int R, int S, int stride, i
 struct FusedArgs {
     int in_blocks, w_blocks, in_is_im2col, w_is_blocked, in_is_wave;
     PackArgs pk;
-    PackWaveArgs pw;
+    PackSrcArgs pw;
     I2cArgs ic;
     WeightArgs wt;
 };
@@ -720,7 +737,7 @@ __global__ void __launch_bounds__(256) rewrite_fused_kernel(const FusedArgs a)
             const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
             const long long wid = (long long)lid * 4 + wave;
             if (wid < a.pw.waves)
-                pack_layout_wave_body(a.pw, wid, reinterpret_cast<unsigned *>(lds) + wave * (PW_LDS / 4));
+                pack_layout_src_body(a.pw, wid, reinterpret_cast<unsigned *>(lds) + wave * (PW_LDS / 4));
         } else {
             pack_layout_tiled_body(a.pk, lid, lds);
         }
@@ -744,7 +761,7 @@ hipError_t launch_rewrite_fused(bool im2col, int N, int C, int H, int W, int K, 
             return hipErrorNotSupported;
         a.wt = WeightArgs{wt, wq, K, C * R * S, 1, 1, 0, depth, 0, magic_for(depth / 16), 0u, 0u};
     } else {
-        if (plan_pack_wave(N, C, H, W, cb, pad, in, xq, &a.pw, &blocks)) {
+        if (plan_pack_src(N, C, H, W, cb, pad, in, xq, &a.pw, &blocks)) {
             a.in_is_wave = 1;
             lds = 4 * PW_LDS;
         } else if (!plan_pack_tiled(N, C, H, W, cb, pad, in, xq, &a.pk, &blocks)) {

@@ -72,7 +72,139 @@ __device__ __forceinline__ unsigned magic_for_device(int d)  // the same constan
 }
 static inline unsigned magic_for(long long d) { return (unsigned)((0x100000000ULL + (unsigned long long)d - 1) / (unsigned long long)d); }
 
-// Wave-tiled version for 64-channel slices (cb % 64 == 0).  The unit of work is one wave:
+// Wave-tiled version for 64-channel slices (cb % 64 == 0).  The unit of work is one wave and
+// 64 consecutive DESTINATION pixels (records of 64 channels) of one padded plane slice: 4 KB out, written as
+// four store instructions of 1 KB each -- whole lines, the zero border included, nothing left for a second
+// store to complete.  No workgroup barrier anywhere: the four waves of a workgroup only share a launch.
+//   source: the interior records of a unit are consecutive source pixels (image rows follow each other in
+//        memory and the border exists in the destination only): at most 64 bytes of every channel plane from
+//        the unit's first interior pixel on;
+//   in:  lane = (16-byte piece of that run, channel l/4 + 16k): four loads per lane at any byte address, each
+//        wave instruction covering the runs of 16 channels;
+//   LDS: a private [64 channels][17 dwords] tile per wave (odd pitch: the row-wise writes and the column-wise
+//        reads below are conflict-free);
+//   out: lane = (16-channel group g = l%4, record l/4 + 16u): where the record is a border pixel, zeros; else
+//        it reads the dword holding its source pixel from each of its 16 channel rows and picks that pixel's
+//        byte out of each (three byte operations per destination dword); the four lanes of a record write its
+//        64 bytes side by side, sixteen records per instruction one after the other in memory.
+// (The form in source order below lets the lane that writes a row's last pixel zero the border behind it: its
+// stores are runs broken at every image row plus a few-lane store for each border, which costs 15 % of the time once
+// the chip is full.)
+struct PackWaveArgs {
+    const int8_t *src;
+    int8_t *dst;
+    int C, H, W, cb, pad, Hp, Wp, Cb, slices, chunks;  // chunks = ceil(Hp*Wp / 64)
+    long long waves;
+    unsigned m_Wp, m_chunks, m_slices, m_Cb;
+};
+constexpr int PW_PITCH = 17;                      // dwords per channel row
+constexpr int PW_LDS = 64 * PW_PITCH * 4;         // bytes per wave
+
+__device__ __forceinline__ void pack_layout_wave_body(const PackWaveArgs &a, long long wid, unsigned *tile)
+{
+    const int C = a.C, H = a.H, W = a.W, cb = a.cb, pad = a.pad, Wp = a.Wp;
+    const int HW = H * W, HpWp = a.Hp * Wp;
+    const int lane = threadIdx.x & 63;
+    // wid = ((n*Cb + b)*slices + sl)*chunks + chunk
+    const int id = (int)wid;
+    const int q1 = fast_div_any(id, a.chunks, a.m_chunks), chunk = id - q1 * a.chunks;
+    const int q2 = fast_div_any(q1, a.slices, a.m_slices), sl = q1 - q2 * a.slices;
+    const int q3 = fast_div_any(q2, a.Cb, a.m_Cb), b = q2 - q3 * a.Cb;
+    const long long n = q3;
+    const int c0 = b * cb + sl * 64;
+    const int T0 = chunk * 64, nrec = min(64, HpWp - T0);   // this unit's records [T0, T0 + nrec)
+    int8_t *out0 = a.dst + ((n * a.Cb + b) * (long long)HpWp) * cb + sl * 64;
+
+    // the first interior record at or after T0 (wave-uniform) and its source pixel
+    int ha = fast_div_any(T0, Wp, a.m_Wp), wa = T0 - ha * Wp;
+    if (ha < pad) ha = pad, wa = pad;
+    else if (wa < pad) wa = pad;
+    else if (wa >= pad + W) ++ha, wa = pad;
+    const bool any = ha < pad + H && ha * Wp + wa < T0 + nrec;
+    const int src_lo = any ? (ha - pad) * W + (wa - pad) : 0;
+
+    if (any) {
+        const int8_t *plane0 = a.src + (n * C + c0) * (long long)HW + src_lo;
+        const int p = lane & 3, chq = lane >> 2;
+        v4i v[4];
+        // The loads of a lane are issued back to back, none under a per-lane condition (a load under a
+        // condition makes the compiler wait for it before the next one): channels past C are read from a
+        // clamped channel and zeroed after; in the unit that holds a plane's last pixels a piece that would run
+        // past the plane is fetched lower and moved down in registers.
+        if (src_lo + 64 <= HW) {   // uniform
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int ch = min(chq + 16 * k, C - 1 - c0);
+                v[k] = *reinterpret_cast<const v4i_a1 *>(plane0 + (long long)ch * HW + 16 * p);
+            }
+        } else {
+            const int left = HW - src_lo;                    // bytes of the plane from src_lo on (1..63)
+            const int at = max(min(16 * p, left - 16), -src_lo);   // (a plane holds at least 16 bytes: the launcher checks)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int ch = min(chq + 16 * k, C - 1 - c0);
+                const v4i x = *reinterpret_cast<const v4i_a1 *>(plane0 + (long long)ch * HW + at);
+                v[k] = 16 * p - at < 16 ? shift_piece(x, at - 16 * p) : v4i{0, 0, 0, 0};   // (a piece wholly past the plane is not used)
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (c0 + chq + 16 * k >= C) v[k] = v4i{0, 0, 0, 0};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            unsigned *row = tile + (chq + 16 * k) * PW_PITCH + 4 * p;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) row[e] = (unsigned)v[k][e];
+        }
+    }
+    // same wave on both sides: the LDS executes a wave's accesses in order
+    __builtin_amdgcn_wave_barrier();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_wave_barrier();
+
+    const int g = lane & 3;
+    const unsigned *rows = tile + (g * 16) * PW_PITCH;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int rec = (lane >> 2) + 16 * u, t = T0 + rec;
+        const int hp = fast_div_any(t, Wp, a.m_Wp), wp = t - hp * Wp;
+        const bool inside = any && hp >= pad && hp < pad + H && wp >= pad && wp < pad + W;
+        const int li = inside ? (hp - pad) * W + (wp - pad) - src_lo : 0;   // 0 .. 63
+        const unsigned sel = 0x0C0C0400u + (unsigned)(li & 3) * 0x0101u;    // byte li%4 of two dwords, into the low half
+        const unsigned *col = rows + (li >> 2);
+        unsigned d[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) d[c] = col[c * PW_PITCH];
+        v4i o;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const unsigned lo = __builtin_amdgcn_perm(d[4 * q + 1], d[4 * q], sel), hi = __builtin_amdgcn_perm(d[4 * q + 3], d[4 * q + 2], sel);
+            o[q] = inside ? (int)(lo | (hi << 16)) : 0;
+        }
+        if (rec < nrec) __builtin_nontemporal_store(o, reinterpret_cast<v4i *>(out0 + (long long)t * cb + g * 16));
+    }
+}
+
+// Fills `a` and the workgroup count if the wave-tiled kernel can run this problem.
+static inline bool plan_pack_wave(int N, int C, int H, int W, int cb, int pad, const int8_t *src, int8_t *dst,
+                           PackWaveArgs *a, long long *blocks)
+{
+    const int Hp = H + 2 * pad, Wp = W + 2 * pad, Cb = (C + cb - 1) / cb;
+    const long long hw = (long long)H * W;
+    if (!(cb % 64 == 0 && hw >= 16 && hw < (1LL << 30) && (long long)Hp * Wp < (1LL << 30))) return false;
+    const int slices = cb / 64;
+    const long long chunks = ((long long)Hp * Wp + 63) / 64;
+    const long long waves = (long long)N * Cb * slices * chunks;
+    if (waves >= (1LL << 31)) return false;
+    *blocks = (waves + 3) / 4;
+    *a = PackWaveArgs{src, dst, C, H, W, cb, pad, Hp, Wp, Cb, slices, (int)chunks, waves,
+                      magic_for(Wp), magic_for(chunks), magic_for(slices), magic_for(Cb)};
+    return true;
+}
+
+// The same in SOURCE order, for problems too small to fill the chip (there the time is the length of a wave's
+// dependent chain, and this form has one round of LDS reads where the destination-ordered form has four).
+// The unit of work is one wave:
 // 64 consecutive SOURCE pixels of the 64 channel planes of a slice (4 KB in, 4 KB out), with
 // no workgroup barrier anywhere -- the four waves of a workgroup only share a launch.
 //   in:  lane = (16-byte piece of the 64-byte run, channel l/4 + 16k): four loads per lane,
@@ -86,17 +218,15 @@ static inline unsigned magic_for(long long d) { return (unsigned)((0x100000000UL
 //        pixels that follow it in the padded order (right border + next row's left border);
 //        the waves holding the first and the last pixel of a plane zero the top and bottom rows.
 // Working in source order means there is no mapping from padded index back to the image.
-struct PackWaveArgs {
+struct PackSrcArgs {
     const int8_t *src;
     int8_t *dst;
     int C, H, W, cb, pad, Hp, Wp, Cb, slices, chunks;  // chunks = ceil(H*W / 64)
     long long waves;
     unsigned m_W, m_chunks, m_slices, m_Cb;
 };
-constexpr int PW_PITCH = 17;                      // dwords per channel row
-constexpr int PW_LDS = 64 * PW_PITCH * 4;         // bytes per wave
 
-__device__ __forceinline__ void pack_layout_wave_body(const PackWaveArgs &a, long long wid, unsigned *tile)
+__device__ __forceinline__ void pack_layout_src_body(const PackSrcArgs &a, long long wid, unsigned *tile)
 {
     const int C = a.C, H = a.H, W = a.W, cb = a.cb, pad = a.pad, Wp = a.Wp;
     const int HW = H * W, HpWp = a.Hp * Wp;
@@ -207,8 +337,8 @@ __device__ __forceinline__ void pack_layout_wave_body(const PackWaveArgs &a, lon
 }
 
 // Fills `a` and the workgroup count if the wave-tiled kernel can run this problem.
-static inline bool plan_pack_wave(int N, int C, int H, int W, int cb, int pad, const int8_t *src, int8_t *dst,
-                           PackWaveArgs *a, long long *blocks)
+static inline bool plan_pack_src(int N, int C, int H, int W, int cb, int pad, const int8_t *src, int8_t *dst,
+                           PackSrcArgs *a, long long *blocks)
 {
     const int Hp = H + 2 * pad, Wp = W + 2 * pad, Cb = (C + cb - 1) / cb;
     const long long hw = (long long)H * W;
@@ -220,7 +350,7 @@ static inline bool plan_pack_wave(int N, int C, int H, int W, int cb, int pad, c
     const long long waves = (long long)N * Cb * slices * chunks;
     if (waves >= (1LL << 31)) return false;
     *blocks = (waves + 3) / 4;
-    *a = PackWaveArgs{src, dst, C, H, W, cb, pad, Hp, Wp, Cb, slices, (int)chunks, waves,
+    *a = PackSrcArgs{src, dst, C, H, W, cb, pad, Hp, Wp, Cb, slices, (int)chunks, waves,
                       magic_for(W), magic_for(chunks), magic_for(slices), magic_for(Cb)};
     return true;
 }

@@ -31,6 +31,21 @@ def oracle_conv(cfg):
 
 # ---- layout rewrites ----------------------------------------------------------------------
 @pytest.mark.parametrize("shape,cb,pad", [
+    ((600, 200, 7, 9), 64, 2), ((1100, 64, 12, 16), 64, 1), ((90, 130, 20, 23), 128, 3), ((4100, 64, 3, 5), 64, 0),
+    ((520, 70, 14, 14), 64, 1),
+])
+def test_pack_layout_destination_order(lib, shape, cb, pad):
+    """Enough 64-record units to fill the chip: the kernel then works in destination order (whole-line stores with
+    the border inside them).  Planes whose size is not a multiple of four take that form at any size, so the small
+    shapes above cover its edge cases too; these cover its index arithmetic over many planes."""
+    N, C, H, W = shape
+    assert N * -(-C // cb) * (cb // 64) * -(-(H + 2 * pad) * (W + 2 * pad) // 64) >= 4096
+    x = uniform_int8(sum(shape) + cb + pad, shape)
+    got = host(lib.pack_layout(dev(x), cb, pad))
+    np.testing.assert_array_equal(got, layouts.pack_layout(x, cb, pad))
+
+
+@pytest.mark.parametrize("shape,cb,pad", [
     ((2, 37, 5, 6), 16, 1), ((1, 3, 31, 29), 16, 3), ((3, 64, 14, 14), 64, 1), ((1, 70, 9, 130), 32, 0),
     ((1, 16, 14, 14), 16, 1), ((2, 5, 7, 7), 4, 2), ((2, 20, 7, 9), 8, 1), ((1, 1, 161, 500), 16, 0),
     ((1, 100, 3, 3), 112, 2), ((1, 1, 1, 1), 16, 0),
