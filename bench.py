@@ -32,7 +32,7 @@ PEAK_HBM_BPS = 8.0e12    # HBM3E
 TRAFFIC = {
     "source": "paper_2104_04731_amd/csrc/band_mfma.hip",
     "sha256": "c56ee57cf16f39d90474380977f0f3094bb72c30ebea59bd016bae760e65c2ab",
-    "fetch_bytes": 5552531,
+    "fetch_bytes": 5552522,
     "write_bytes": 3211264,
 }
 
