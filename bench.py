@@ -31,9 +31,9 @@ PEAK_HBM_BPS = 8.0e12    # HBM3E
 # describe the kernel source whose hash is recorded here; for any other source `traffic` is null.
 TRAFFIC = {
     "source": "paper_2104_04731_amd/csrc/band_mfma.hip",
-    "sha256": "c56ee57cf16f39d90474380977f0f3094bb72c30ebea59bd016bae760e65c2ab",
-    "fetch_bytes": 5552522,
-    "write_bytes": 3211264,
+    "sha256": "8b46f02657a698c84b1490f69f5d8fdf9a09557a6713d9bb48f695e1eaff33fa",
+    "fetch_bytes": 4658686,
+    "write_bytes": 3211576,
 }
 
 

@@ -39,6 +39,7 @@ constexpr int BAND_WAVES = 4, BAND_TK = 32;
 constexpr size_t BAND_LDS_LIMIT = 160 * 1024;
 
 constexpr int BAND_KPW_MAX = 12;
+constexpr int BAND_MAP = 512;
 
 struct BandArgs {
     const int8_t *act;  // [N][Cb][Hp][Wp][64]
@@ -56,6 +57,8 @@ struct BandArgs {
     int win_per_wave;            // ceil(win_total / 4)
     int wave_region;             // LDS bytes per wave: weights, later partial sums
     int tiles_k, tiles_m, m_fastest;
+    int xk, bk, bm;              // 2-D split over the XCDs: xk XCD columns, an XCD's block is bk x bm tiles (0: off)
+    unsigned mg_bk, mg_per;
     int blk_bytes;               // one channel block of one image
     long long img_bytes;         // one image
     long long out_img;           // K*P*Q
@@ -64,6 +67,10 @@ struct BandArgs {
     // activation fragments: one step, or in the shifted-fragment form the taps of one kernel row):
     // its channel block's window + its kernel tap (row)
     int toff[BAND_WAVES][BAND_KPW_MAX];
+    // grids of up to BAND_MAP workgroups: block -> (tk | tm << 16), made on the host (one scalar load instead of
+    // the index arithmetic below; the kernel is short enough for that to show)
+    int use_map;
+    unsigned tmap[BAND_MAP];
 };
 
 // n / d for 0 <= n < 2^31 with magic = ceil(2^32 / d) truncated to 32 bits (0 encodes d == 1).
@@ -139,13 +146,22 @@ __global__ void __launch_bounds__(BAND_WAVES * 64, 1) conv_band_kernel(const Ban
     asm volatile("" : : "s"(a.act), "s"(a.wq), "s"(a.out), "s"(a.K), "s"(a.P), "s"(a.Q), "s"(a.Wp), "s"(a.stride), "s"(a.depth),
                  "s"(a.ksteps), "s"(a.kpw), "s"(a.PT), "s"(a.bands), "s"(a.npix), "s"(a.CT), "s"(a.CTN), "s"(a.wmax));
     asm volatile("" : : "s"(a.win_pieces), "s"(a.win_total), "s"(a.win_per_wave), "s"(a.wave_region), "s"(a.tiles_k),
-                 "s"(a.tiles_m), "s"(a.m_fastest), "s"(a.blk_bytes), "s"(a.img_bytes), "s"(a.out_img), "s"(a.mg_Q),
+                 "s"(a.tiles_m), "s"(a.m_fastest), "s"(a.xk), "s"(a.bk), "s"(a.bm), "s"(a.mg_bk), "s"(a.mg_per), "s"(a.blk_bytes), "s"(a.img_bytes), "s"(a.out_img), "s"(a.mg_Q),
                  "s"(a.mg_bands), "s"(a.mg_tiles_k), "s"(a.mg_tiles_m), "s"(a.mg_CTN), "s"(a.mg_win_pieces));
 
     // workgroup -> (32 output channels, image, band)
     const int lid = band_xcd_id(blockIdx.x, gridDim.x);
     int tk, tm;
-    if (a.m_fastest) {
+    if (a.use_map) {
+        const unsigned e = a.tmap[blockIdx.x];
+        tk = (int)(e & 0xFFFFu), tm = (int)(e >> 16);
+    } else if (a.bk) {   // XCD x = (x % xk, x / xk) owns the bk x bm block of tiles at that position
+        const int per = a.bk * a.bm, x = bdiv(lid, per, a.mg_per), j = lid - x * per;
+        const int jm = bdiv_small(j, a.mg_bk), jk = j - jm * a.bk;
+        const int xr = x / a.xk;
+        tk = (x - xr * a.xk) * a.bk + jk;
+        tm = xr * a.bm + jm;
+    } else if (a.m_fastest) {
         tk = bdiv(lid, a.tiles_m, a.mg_tiles_m);
         tm = lid - tk * a.tiles_m;
     } else {
@@ -491,6 +507,40 @@ bool band_plan(const GemmProblem &g, BandPlan *bp)
             return nf * fb + ns * sb;
         };
         a.m_fastest = cost(tiles_m, tiles_k, win_bytes, wbytes_k) < cost(tiles_k, tiles_m, wbytes_k, win_bytes);
+        // ... or, where both tile counts divide, a 2-D split: XCD columns x XCD rows = 8, every XCD a block of tiles
+        // (what it pulls in: its block's weight rows + its block's windows)
+        double best = a.m_fastest ? cost(tiles_m, tiles_k, win_bytes, wbytes_k) : cost(tiles_k, tiles_m, wbytes_k, win_bytes);
+        a.xk = a.bk = a.bm = 0;
+        for (int xk = 2; xk <= 4; xk *= 2) {
+            const int xm = 8 / xk;
+            if (tiles_k % xk || tiles_m % xm) continue;
+            const double c = (double)(tiles_k / xk) * wbytes_k + (double)(tiles_m / xm) * win_bytes;
+            if (c < best) {
+                best = c;
+                a.xk = xk, a.bk = (int)(tiles_k / xk), a.bm = (int)(tiles_m / xm);
+            }
+        }
+        a.mg_bk = magic_of(a.bk);
+        a.mg_per = magic_of((long long)a.bk * a.bm);
+        // the same mapping as a table, where it fits
+        const long long grid = tiles_k * tiles_m;
+        a.use_map = grid <= BAND_MAP && tiles_k < 65536 && tiles_m < 65536;
+        if (a.use_map)
+            for (int i = 0; i < (int)grid; ++i) {
+                const int x = i & 7, q = (int)grid >> 3, rem = (int)grid & 7;
+                const int lid = x * q + (x < rem ? x : rem) + (i >> 3);   // (band_xcd_id)
+                int tk, tm;
+                if (a.bk) {
+                    const int per = a.bk * a.bm, xx = lid / per, j = lid - xx * per, jm = j / a.bk, jk = j - jm * a.bk;
+                    tk = (xx % a.xk) * a.bk + jk;
+                    tm = (xx / a.xk) * a.bm + jm;
+                } else if (a.m_fastest) {
+                    tk = lid / (int)tiles_m, tm = lid - tk * (int)tiles_m;
+                } else {
+                    tm = lid / (int)tiles_k, tk = lid - tm * (int)tiles_k;
+                }
+                a.tmap[i] = (unsigned)tk | ((unsigned)tm << 16);
+            }
     }
     a.mg_Q = magic_of(Q);
     a.mg_bands = magic_of(bands);
