@@ -141,9 +141,10 @@ __global__ void __launch_bounds__(BAND_WAVES * 64, 1) conv_band_kernel(const Ban
     const unsigned lds0 = (unsigned)(size_t)((__attribute__((address_space(3))) unsigned char *)smem);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned tmap_e = a.tmap[min(blockIdx.x, (unsigned)BAND_MAP - 1)];   // (asked for with the rest, used if use_map)
     // Ask for every scalar argument now, in one batch: fetched one by one where first used, each costs a
     // scalar-cache miss of a few hundred cycles on a kernel that runs for a few thousand.
-    asm volatile("" : : "s"(a.act), "s"(a.wq), "s"(a.out), "s"(a.K), "s"(a.P), "s"(a.Q), "s"(a.Wp), "s"(a.stride), "s"(a.depth),
+    asm volatile("" : : "s"(tmap_e), "s"(a.use_map), "s"(a.act), "s"(a.wq), "s"(a.out), "s"(a.K), "s"(a.P), "s"(a.Q), "s"(a.Wp), "s"(a.stride), "s"(a.depth),
                  "s"(a.ksteps), "s"(a.kpw), "s"(a.PT), "s"(a.bands), "s"(a.npix), "s"(a.CT), "s"(a.CTN), "s"(a.wmax));
     asm volatile("" : : "s"(a.win_pieces), "s"(a.win_total), "s"(a.win_per_wave), "s"(a.wave_region), "s"(a.tiles_k),
                  "s"(a.tiles_m), "s"(a.m_fastest), "s"(a.xk), "s"(a.bk), "s"(a.bm), "s"(a.mg_bk), "s"(a.mg_per), "s"(a.blk_bytes), "s"(a.img_bytes), "s"(a.out_img), "s"(a.mg_Q),
@@ -153,8 +154,7 @@ __global__ void __launch_bounds__(BAND_WAVES * 64, 1) conv_band_kernel(const Ban
     const int lid = band_xcd_id(blockIdx.x, gridDim.x);
     int tk, tm;
     if (a.use_map) {
-        const unsigned e = a.tmap[blockIdx.x];
-        tk = (int)(e & 0xFFFFu), tm = (int)(e >> 16);
+        tk = (int)(tmap_e & 0xFFFFu), tm = (int)(tmap_e >> 16);
     } else if (a.bk) {   // XCD x = (x % xk, x / xk) owns the bk x bm block of tiles at that position
         const int per = a.bk * a.bm, x = bdiv(lid, per, a.mg_per), j = lid - x * per;
         const int jm = bdiv_small(j, a.mg_bk), jk = j - jm * a.bk;
