@@ -31,9 +31,9 @@ PEAK_HBM_BPS = 8.0e12    # HBM3E
 # describe the kernel source whose hash is recorded here; for any other source `traffic` is null.
 TRAFFIC = {
     "source": "paper_2104_04731_amd/csrc/band_mfma.hip",
-    "sha256": "8b46f02657a698c84b1490f69f5d8fdf9a09557a6713d9bb48f695e1eaff33fa",
-    "fetch_bytes": 4658686,
-    "write_bytes": 3211576,
+    "sha256": "cfd2693efffe723b8c3db41f5c412641544f7cdd8eac4d72df60e3c11426e4ef",
+    "fetch_bytes": 4658679,
+    "write_bytes": 3211611,
 }
 
 
