@@ -562,6 +562,27 @@ def n_scaled(lib, timed, CONFIGS, dev):
                          "pct_mfma_peak": round(100 * probe_ops / (ms * 1e-3) / PEAK_INT8_OPS, 2),
                          "shape": f"{blocks} workgroups x 4 waves x {iters} x 4 v_mfma_i32_32x32x32_i8, pseudo-random operands"}
     out["gemm_stage_C4a_N2048"]["pct_of_mfma_probe"] = round(100 * out["gemm_stage_C4a_N2048"]["tops"] / out["mfma_probe"]["tops"], 2)
+    # the vendor library's int8 GEMM on a matrix of the same sizes as that stage (M = N*P*Q rows of C*R*S bytes,
+    # already unrolled and row-major, times K columns), for scale only: torch._int_mm, i.e. hipBLASLt
+    try:
+        c4 = CONFIGS["C4a"].scaled(2048)
+        gm, gk, gn = c4.N * c4.P * c4.Q, c4.C * c4.R * c4.S, c4.K
+        ga = torch.randint(-128, 128, (gm, gk), dtype=torch.int8, device=dev)
+        gb = torch.randint(-128, 128, (gn, gk), dtype=torch.int8, device=dev).t()
+        for _ in range(2):
+            torch._int_mm(ga, gb)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()                      # eager calls: ~1 ms each, far above the launch cost
+        for _ in range(5):
+            torch._int_mm(ga, gb)
+        ev1.record()
+        torch.cuda.synchronize()
+        ms = ev0.elapsed_time(ev1) / 5
+        out["vendor_gemm_reference"] = {"us": round(ms * 1e3, 2), "tops": round(2.0 * gm * gk * gn / (ms * 1e-3) / 1e12, 1),
+                                        "shape": f"torch._int_mm [{gm} x {gk}] x [{gk} x {gn}], second operand column-major"}
+        del ga, gb
+    except Exception as e:  # not every build has the routine
+        out["vendor_gemm_reference"] = {"error": str(e)[:120]}
     # a plain device-to-device copy of the same size, for scale
     y = torch.empty_like(xp)
     _, ms = timed(lambda: y.copy_(xp), 10, 2)

@@ -50,6 +50,7 @@ struct GemmArgs {
     unsigned mg_il_dd, mg_il_d;
     int dil;  // ACT_BLOCKED: distance between kernel taps in the padded image (1 = dense kernel)
     int out_nhwc;  // `out` is [N][P][Q][K] instead of [N][K][P][Q]
+    int stagger;   // start offsets of the first round of workgroups: this many 1024-cycle naps per phase step (0: none)
 };
 
 // n / d for 0 <= n < 2^31 with magic = ceil(2^32 / d) truncated to 32 bits (0 encodes d == 1):
@@ -148,6 +149,13 @@ __device__ __forceinline__ void igemm_body(const GemmArgs &a, int block_id, int 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int grp = DS == 1 ? 0 : wave / NWM;  // depth group of this wave
     const int wk = (wave % NWM) % WK, wm = (wave % NWM) / WK;
+
+    // The workgroups of one round finish together, and so do their output tiles: every compute unit then
+    // writes at once, the memory system takes the tiles in turn and the matrix pipes idle meanwhile.  In a
+    // launch of many rounds the first round therefore starts at 32 different offsets (one per compute unit
+    // of an XCD; ids are dealt round-robin over the XCDs), which spreads the writes of every later round too.
+    if (a.stagger && block_id < 256)
+        for (int z = ((block_id >> 3) & 31) * a.stagger; z > 0; --z) __builtin_amdgcn_s_sleep(16);
 
     int lid = xcd_contiguous_id(block_id, nblocks);
     int tk, tm;
@@ -876,6 +884,21 @@ static bool make_gemm_args(const GemmProblem &g, int tile, int split_k, GemmArgs
     a.split_k = ceil_div(a.ksteps_total, a.ksteps_per_split);
     if (!tile_fits(d, a.ksteps_total, a.ksteps_per_split)) return false;
     a.out_fits_32bit = (unsigned long long)g.M * g.K * sizeof(int32_t) < (1ULL << 32);
+    {
+        // Start offsets of the first round (see the kernel): worth their idle time where the launch runs many
+        // rounds and an output tile is a sizeable part of a workgroup's life.  Estimates in core cycles: 60 per
+        // MFMA and SIMD in the main loop (measured at steady state), 8 output bytes per cycle as a compute unit's
+        // share of the memory system.  The offsets span about 0.6 of a workgroup's life (measured best).
+        const double mfma_per_simd = (double)(d.tk / 32) * (d.tm / 32) * 2 / 4;  // per 64-byte depth step
+        const double main_clk = (double)a.ksteps_per_split * mfma_per_simd * 60.0;
+        const double epi_clk = (double)d.tk * d.tm * (g.act_out ? 1 : 4) / 8.0;
+        const long long grid = (long long)a.tiles_k * a.tiles_m * a.split_k;
+        a.stagger = 0;
+        if (grid >= 6 * 256 && a.split_k == 1 && epi_clk >= 0.15 * (main_clk + epi_clk)) {
+            a.stagger = (int)(0.6 * (main_clk + epi_clk) / (32 * 1024) + 0.5);
+            if (a.stagger < 1) a.stagger = 1;
+        }
+    }
     {
         // Each XCD has its own L2 and gets a contiguous eighth of the tile list: order the
         // list so that the operand rows one XCD has to pull in are as few as possible.
