@@ -50,7 +50,7 @@ struct GemmArgs {
     unsigned mg_il_dd, mg_il_d;
     int dil;  // ACT_BLOCKED: distance between kernel taps in the padded image (1 = dense kernel)
     int out_nhwc;  // `out` is [N][P][Q][K] instead of [N][K][P][Q]
-    int stagger;   // start offsets of the first round of workgroups: this many 1024-cycle naps per phase step (0: none)
+    int stagger;   // start offsets of the first round of workgroups: this many 64-cycle units per phase step (0: none)
 };
 
 // n / d for 0 <= n < 2^31 with magic = ceil(2^32 / d) truncated to 32 bits (0 encodes d == 1):
@@ -155,7 +155,7 @@ __device__ __forceinline__ void igemm_body(const GemmArgs &a, int block_id, int 
     // launch of many rounds the first round therefore starts at 32 different offsets (one per compute unit
     // of an XCD; ids are dealt round-robin over the XCDs), which spreads the writes of every later round too.
     if (a.stagger && block_id < 256)
-        for (int z = ((block_id >> 3) & 31) * a.stagger; z > 0; --z) __builtin_amdgcn_s_sleep(16);
+        for (int z = ((block_id >> 3) & 31) * a.stagger; z >= 16; z -= 16) __builtin_amdgcn_s_sleep(16);
 
     int lid = xcd_contiguous_id(block_id, nblocks);
     int tk, tm;
@@ -885,18 +885,18 @@ static bool make_gemm_args(const GemmProblem &g, int tile, int split_k, GemmArgs
     if (!tile_fits(d, a.ksteps_total, a.ksteps_per_split)) return false;
     a.out_fits_32bit = (unsigned long long)g.M * g.K * sizeof(int32_t) < (1ULL << 32);
     {
-        // Start offsets of the first round (see the kernel): worth their idle time where the launch runs many
-        // rounds and an output tile is a sizeable part of a workgroup's life.  Estimates in core cycles: 60 per
+        // Start offsets of the first round (see the kernel): worth their idle time where the launch runs several
+        // rounds and a large output tile is a sizeable part of a workgroup's life (small tiles drift apart by
+        // themselves: measured level or slightly worse with offsets).  Estimates in core cycles: 60 per
         // MFMA and SIMD in the main loop (measured at steady state), 8 output bytes per cycle as a compute unit's
-        // share of the memory system.  The offsets span about 0.6 of a workgroup's life (measured best).
+        // share of the memory system.  The offsets span about twice the time an output tile takes (measured best).
         const double mfma_per_simd = (double)(d.tk / 32) * (d.tm / 32) * 2 / 4;  // per 64-byte depth step
         const double main_clk = (double)a.ksteps_per_split * mfma_per_simd * 60.0;
         const double epi_clk = (double)d.tk * d.tm * (g.act_out ? 1 : 4) / 8.0;
         const long long grid = (long long)a.tiles_k * a.tiles_m * a.split_k;
         a.stagger = 0;
-        if (grid >= 6 * 256 && a.split_k == 1 && epi_clk >= 0.15 * (main_clk + epi_clk)) {
-            a.stagger = (int)(0.6 * (main_clk + epi_clk) / (32 * 1024) + 0.5);
-            if (a.stagger < 1) a.stagger = 1;
+        if (grid >= 2 * 256 && a.split_k == 1 && epi_clk >= 16000 && epi_clk >= 0.15 * (main_clk + epi_clk)) {
+            a.stagger = (int)(2.0 * epi_clk / (32 * 64) + 0.5);
         }
     }
     {
