@@ -255,7 +255,51 @@ def main():
         buf = torch.empty(blocks * 256, dtype=torch.int32, device=dev)
         _, ms_p = timed(lambda: lib.mfma_probe_int8(blocks, iters, out=buf), 5, 2)
         probe_ops = 2 * 32768 * 16 * iters * blocks
+        def eager_ms(fn, n=5):
+            for _ in range(2):
+                fn()
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ev0.record()
+            for _ in range(n):
+                fn()
+            ev1.record()
+            torch.cuda.synchronize()
+            return ev0.elapsed_time(ev1) / n
+
+        # for scale: the vendor library's int8 GEMM (torch._int_mm = hipBLASLt) on matrices of the same sizes, and both
+        # on a square 8192^3 problem (ours as a 1x1 convolution over 8 images of 32x32 pixels, 8192 -> 8192 channels)
+        vendor = {}
+        try:
+            gm, gk, gn = cfg.N * cfg.P * cfg.Q, cfg.C * cfg.R * cfg.S, cfg.K
+            ga = torch.randint(-128, 128, (gm, gk), dtype=torch.int8, device=dev)
+            gb = torch.randint(-128, 128, (gn, gk), dtype=torch.int8, device=dev).t()
+            vendor["same_sizes_tops"] = round(2.0 * gm * gk * gn / (eager_ms(lambda: torch._int_mm(ga, gb)) * 1e-3) / 1e12, 1)
+            ga.zero_()
+            gbz = torch.zeros((gn, gk), dtype=torch.int8, device=dev).t()
+            vendor["same_sizes_zero_tops"] = round(2.0 * gm * gk * gn / (eager_ms(lambda: torch._int_mm(ga, gbz)) * 1e-3) / 1e12, 1)
+            del ga, gb, gbz
+            sq = 8192
+            sa = torch.randint(-128, 128, (sq, sq), dtype=torch.int8, device=dev)
+            sb = torch.randint(-128, 128, (sq, sq), dtype=torch.int8, device=dev).t()
+            vendor["square_8192_tops"] = round(2.0 * sq ** 3 / (eager_ms(lambda: torch._int_mm(sa, sb)) * 1e-3) / 1e12, 1)
+            sa.zero_()
+            sbz = torch.zeros((sq, sq), dtype=torch.int8, device=dev).t()
+            vendor["square_8192_zero_tops"] = round(2.0 * sq ** 3 / (eager_ms(lambda: torch._int_mm(sa, sbz)) * 1e-3) / 1e12, 1)
+            del sa, sb, sbz
+        except Exception as e:  # not every build has the routine
+            vendor["error"] = str(e)[:120]
+        sdims = (8, 8192, 32, 32, 8192, 1, 1, 1, 0)
+        sx = lib.pack_layout(torch.randint(-128, 128, (8, 8192, 32, 32), dtype=torch.int8, device=dev), 64, 0)
+        sw = lib.pack_weights(torch.randint(-128, 128, (8192, 8192, 1, 1), dtype=torch.int8, device=dev), lib.LAYOUT_PACKED, 64)
+        so = torch.empty((8, 8192, 32, 32), dtype=torch.int32, device=dev)
+        ours_sq = 2.0 * 8192 ** 3 / (eager_ms(lambda: lib.conv2d_int8_packed(sdims, lib.LAYOUT_PACKED, 64, sx, sw, so)) * 1e-3) / 1e12
+        sx.zero_()
+        sw.zero_()
+        ours_sq_z = 2.0 * 8192 ** 3 / (eager_ms(lambda: lib.conv2d_int8_packed(sdims, lib.LAYOUT_PACKED, 64, sx, sw, so)) * 1e-3) / 1e12
+        del sx, sw, so
         print(json.dumps({"gemm_stage_C4a_N2048_us": round(ms * 1e3, 2), "tiling": lib.query_tiling(cfg.dims(), lib.LAYOUT_PACKED, 64),
+                          "tile": "%dx%d, %d threads" % tuple(lib.tile_info(lib.query_tiling(cfg.dims(), lib.LAYOUT_PACKED, 64)[0])[:3]),
+                          "vendor_gemm": vendor, "square_8192_tops": round(ours_sq, 1), "square_8192_zero_tops": round(ours_sq_z, 1),
                           "tops": round(cfg.ops / (ms * 1e-3) / 1e12, 2),
                           "all_zero_operands_us": round(ms_z * 1e3, 2), "all_zero_operands_tops": round(cfg.ops / (ms_z * 1e-3) / 1e12, 2),
                           "mfma_probe_us": round(ms_p * 1e3, 2), "mfma_probe_tops": round(probe_ops / (ms_p * 1e-3) / 1e12, 2)}), flush=True)
