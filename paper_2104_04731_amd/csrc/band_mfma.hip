@@ -323,6 +323,62 @@ __global__ void __launch_bounds__(BAND_WAVES * 64, 1) conv_band_kernel(const Ban
     const int kleft = a.K - k0 - 4 * grp;   // output channels from this lane's first one to the last
     const bool k_whole = k0 + BAND_TK <= a.K;  // wave-uniform: no channel of the tile lies past the last
     constexpr int SLOTS = (2 * PB + BAND_WAVES - 1) / BAND_WAVES;
+    if (SROW > 1 && k_whole && a.out_nhwc && a.out_wide_k && a.aout.out == nullptr) {
+        // The same for an NHWC result whose pixels take 16-byte pieces: a lane's four sums are channels k .. k+3 of
+        // one pixel; 32-bit byte offsets against the image's base.
+        v4i sums[SLOTS];
+#pragma unroll
+        for (int m = 0; m < SLOTS; ++m) {
+            const int i = wave + BAND_WAVES * m;
+            sums[m] = *reinterpret_cast<const v4i *>(__builtin_assume_aligned(smem + i * 1024 + lane * 16, 16));
+#pragma unroll
+            for (int o = 1; o < BAND_WAVES; ++o)
+                sums[m] += *reinterpret_cast<const v4i *>(__builtin_assume_aligned(smem + o * a.wave_region + i * 1024 + lane * 16, 16));
+        }
+        const char *const img = reinterpret_cast<const char *>(a.out + (size_t)n * a.out_img);
+#pragma unroll
+        for (int m = 0; m < SLOTS; ++m) {
+            const int i = wave + BAND_WAVES * m;
+            const int rb = i >= PB ? 1 : 0, pb = i - rb * PB;
+            const int pr = bdiv_small(pb, a.mg_CTN), q0 = (pb - pr * a.CTN) * a.CT;  // wave-uniform
+            const int cols = (i < 2 * PB && pr < a.PT && p0 + pr < a.P) ? min(a.CT, a.Q - q0) : 0;
+            const unsigned offb = (unsigned)(((p0 + pr) * a.Q + q0 + col) * a.K + k0 + rb * 16 + 4 * grp) * 4u;
+            if (col < cols) *reinterpret_cast<v4i *>(const_cast<char *>(img) + offb) = sums[m];
+        }
+        return;
+    }
+    if (SROW > 1 && k_whole && !(a.out_nhwc | (a.aout.out != nullptr))) {
+        // The common case -- int32 NKPQ result, whole channel tile, shifted-fragment form -- on a path of its own:
+        // every sum is read before the first store (one LDS round trip for the wave, not one per slot), no test of
+        // the result's form inside the loop, and 32-bit byte offsets against four scalar plane bases (the host
+        // refuses results of 2^30 elements per image and more).
+        v4i sums[SLOTS];
+#pragma unroll
+        for (int m = 0; m < SLOTS; ++m) {
+            const int i = wave + BAND_WAVES * m;
+            sums[m] = *reinterpret_cast<const v4i *>(__builtin_assume_aligned(smem + i * 1024 + lane * 16, 16));
+#pragma unroll
+            for (int o = 1; o < BAND_WAVES; ++o)
+                sums[m] += *reinterpret_cast<const v4i *>(__builtin_assume_aligned(smem + o * a.wave_region + i * 1024 + lane * 16, 16));
+        }
+        const char *const b0 = reinterpret_cast<const char *>(out0), *const b1 = reinterpret_cast<const char *>(out1);
+        const char *const b2 = reinterpret_cast<const char *>(out2), *const b3 = reinterpret_cast<const char *>(out3);
+#pragma unroll
+        for (int m = 0; m < SLOTS; ++m) {
+            const int i = wave + BAND_WAVES * m;
+            const int rb = i >= PB ? 1 : 0, pb = i - rb * PB;
+            const int pr = bdiv_small(pb, a.mg_CTN), q0 = (pb - pr * a.CTN) * a.CT;  // wave-uniform
+            const int cols = (i < 2 * PB && pr < a.PT && p0 + pr < a.P) ? min(a.CT, a.Q - q0) : 0;
+            const unsigned offb = (unsigned)(rb * 16 * plane + (p0 + pr) * a.Q + q0 + lane_off) * 4u;
+            if (col < cols) {
+                *reinterpret_cast<int32_t *>(const_cast<char *>(b0) + offb) = sums[m][0];
+                *reinterpret_cast<int32_t *>(const_cast<char *>(b1) + offb) = sums[m][1];
+                *reinterpret_cast<int32_t *>(const_cast<char *>(b2) + offb) = sums[m][2];
+                *reinterpret_cast<int32_t *>(const_cast<char *>(b3) + offb) = sums[m][3];
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int m = 0; m < SLOTS; ++m) {
         const int i = wave + BAND_WAVES * m;  // wave-uniform; the regions hold SLOTS*4 blocks
