@@ -31,9 +31,9 @@ PEAK_HBM_BPS = 8.0e12    # HBM3E
 # describe the kernel source whose hash is recorded here; for any other source `traffic` is null.
 TRAFFIC = {
     "source": "paper_2104_04731_amd/csrc/band_mfma.hip",
-    "sha256": "cfd2693efffe723b8c3db41f5c412641544f7cdd8eac4d72df60e3c11426e4ef",
-    "fetch_bytes": 4658679,
-    "write_bytes": 3211611,
+    "sha256": "fca480ff4cc07f1c3ac0289a0f33ec7652b88cec35c838be8373bbbea4b59404",
+    "fetch_bytes": 4642305,
+    "write_bytes": 3211264,
 }
 
 
