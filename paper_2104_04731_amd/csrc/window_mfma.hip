@@ -70,7 +70,7 @@ __device__ __forceinline__ unsigned load_u32(const void *p)  // any alignment
 template <int NKK, int NKB, bool ACT, bool NHWC>  // ACT: the activation epilogue, a kernel of its own; NHWC: the source
 // (six waves per SIMD asked for: the compiler then keeps the accumulators in the one 80-register budget
 // instead of 79 + 32 registers, and six workgroups fit a CU instead of four)
-__global__ void __launch_bounds__(256, 6) conv_window_kernel(const WindowArgs a)
+__global__ void __launch_bounds__(256, 4) conv_window_kernel(const WindowArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char *win = smem;
