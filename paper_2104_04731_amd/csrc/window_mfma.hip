@@ -145,7 +145,7 @@ __global__ void __launch_bounds__(256, 4) conv_window_kernel(const WindowArgs a)
                 const int c = a.RW == 1 ? row : (int)chi, rr = row - c * a.RW;
                 const int h = h_lo + rr, w = w_lo + 4 * c4;
                 const int hc = min(max(h, 0), a.H - 1), wc = min(max(w, 0), a.W - 4);  // W >= 4
-                x[u] = load_u32(img + ((size_t)c * a.H + hc) * a.W + wc);
+                x[u] = load_u32(img + (unsigned)((c * a.H + hc) * a.W + wc));   // an image is below 2^31 bytes (host check)
                 const int dd = wc - w;  // > 0: the dword starts left of the row, < 0: it runs past its end
                 const unsigned sh = (unsigned)(dd > 0 ? dd : -dd) * 8u;
                 fix[u] = (dd > 0 ? (sh & 31u) : 0u) | ((dd < 0 ? (sh & 31u) : 0u) << 8) |
@@ -402,7 +402,7 @@ static bool window_plan(const WindowProblem &g, WindowArgs *a)
     const int C = g.nhwc_in ? 1 : g.C, W = g.nhwc_in ? g.W * g.C : g.W, S = g.nhwc_in ? g.S * g.C : g.S;
     const long long stride_w = g.nhwc_in ? (long long)g.stride * g.C : g.stride;
     const int depth = window_depth(C, g.R, S);
-    if (depth == 0 || W < 4) return false;
+    if (depth == 0 || W < 4 || (long long)C * g.H * W > 0x7FFFFFFFLL) return false;  // (32-bit offsets inside an image)
     WindowArgs w{};
     w.in = g.in;
     w.wt = g.wt;
