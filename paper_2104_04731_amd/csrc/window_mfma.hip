@@ -55,6 +55,7 @@ struct WindowArgs {
     int win_bytes, wl_bytes;  // LDS bytes of the window and of the weight rows (multiples of 16)
     int out_small;         // 4*K*P*Q < 2^32
     int in_small;          // C*H*W < 2^31
+    int rpp;               // window fill by columns (0: not): window rows per pass of 256 threads, 256 / (pitch/4)
     int wide_out;          // Q % 4 == 0 and out 16-byte aligned: 16-byte stores
     ActOut act;            // activation epilogue (act.out != null): `out` is not written
     unsigned m_wd, m_RW, m_nd, m_R, m_tiles_q, m_tiles_p, m_gC;
@@ -68,8 +69,8 @@ __device__ __forceinline__ unsigned load_u32(const void *p)  // any alignment
 }
 
 template <int NKK, int NKB, bool ACT, bool NHWC>  // ACT: the activation epilogue, a kernel of its own; NHWC: the source
-// (six waves per SIMD asked for: the compiler then keeps the accumulators in the one 80-register budget
-// instead of 79 + 32 registers, and six workgroups fit a CU instead of four)
+// (four workgroups per compute unit asked for, i.e. up to 128 registers: the deep instantiations use 86 -- five
+// fit -- and under a bound of 85 the compiler spilled their weight loads one by one, a wait behind each)
 __global__ void __launch_bounds__(256, 4) conv_window_kernel(const WindowArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -158,9 +159,38 @@ __global__ void __launch_bounds__(256, 4) conv_window_kernel(const WindowArgs a)
                     *reinterpret_cast<unsigned *>(win + 4 * (base + u * 256 + tid)) = (fix[u] & 0x10000u) ? 0u : y;
                 }
         };
+        // Narrow windows (a row of at most 256 dwords, at most eight passes of rows): a thread keeps its column --
+        // everything that depends on the column only (clamp, shifts, zero flag) is made once -- and walks down
+        // the rows, one division per element instead of two and no multiply for the column.
+        auto stage_columns = [&]() {
+            const int r0 = (int)__umulhi((unsigned)tid, a.m_wd), c4 = tid - r0 * wd;   // wd >= 2
+            const int rows_all = a.C * a.RW;
+            const int w = w_lo + 4 * c4, wc = min(max(w, 0), a.W - 4);
+            const int dd = wc - w;
+            const unsigned sh = (unsigned)(dd > 0 ? dd : -dd) * 8u;
+            const unsigned lsh = dd > 0 ? (sh & 31u) : 0u, rsh = dd < 0 ? (sh & 31u) : 0u;
+            const bool col_zero = sh >= 32u;
+            unsigned x[8];
+            bool zero[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int row = min(r0 + u * a.rpp, rows_all - 1);
+                const int c = a.RW == 1 ? row : (int)__umulhi((unsigned)row, a.m_RW), rr = row - c * a.RW;
+                const int h = h_lo + rr, hc = min(max(h, 0), a.H - 1);
+                x[u] = load_u32(img + (unsigned)((c * a.H + hc) * a.W + wc));
+                zero[u] = col_zero || h != hc;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int row = r0 + u * a.rpp;
+                if (r0 < a.rpp && row < rows_all)
+                    *reinterpret_cast<unsigned *>(win + 4 * (row * wd + c4)) = zero[u] ? 0u : (x[u] << lsh) >> rsh;
+            }
+        };
         // windows of up to 8 KB -- the usual case -- in straight-line code: a loop header would make the
         // compiler drain the weight loads above before the first window load
-        if (total <= 256 * 8) stage_pass(0);
+        if (a.rpp) stage_columns();
+        else if (total <= 256 * 8) stage_pass(0);
         else
             for (int base = 0; base < total; base += 256 * 8) stage_pass(base);
     }
@@ -440,6 +470,7 @@ static bool window_plan(const WindowProblem &g, WindowArgs *a)
     w.tiles_p = (g.P + w.PT - 1) / w.PT;
     if ((long long)g.N * w.tiles_p * w.tiles_q > 2147483647LL || (g.K + kb - 1) / kb > 65535) return false;
     w.m_wd = magic_for(pitch / 4);
+    w.rpp = (pitch / 4 <= 256 && (long long)C * RW <= 8 * (256 / (pitch / 4))) ? (int)(256 / (pitch / 4)) : 0;
     w.m_RW = magic_for(w.RW);
     w.m_nd = magic_for(w.nd);
     w.m_R = magic_for(g.R);
