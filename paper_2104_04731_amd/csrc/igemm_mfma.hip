@@ -50,6 +50,8 @@ struct GemmArgs {
     unsigned mg_il_dd, mg_il_d;
     int dil;  // ACT_BLOCKED: distance between kernel taps in the padded image (1 = dense kernel)
     int out_nhwc;  // `out` is [N][P][Q][K] instead of [N][K][P][Q]
+    int grp_m;     // > 0: tile order in groups of grp_m pixel tiles (below); 0: one of the two row-major orders
+    unsigned mg_grp_sz, mg_grp_m, mg_tiles_km;  // ceil(2^32 / d) for grp_m * tiles_k, grp_m, tiles_k * tiles_m
     int stagger;   // start offsets of the first round of workgroups: this many 64-cycle units per phase step (0: none)
 };
 
@@ -159,7 +161,17 @@ __device__ __forceinline__ void igemm_body(const GemmArgs &a, int block_id, int 
 
     int lid = xcd_contiguous_id(block_id, nblocks);
     int tk, tm;
-    if (a.m_fastest) {  // consecutive tiles share a weight tile (few output channels per XCD)
+    if (a.grp_m) {
+        // Groups of grp_m pixel tiles, each crossed with every channel tile; inside a group the pixel tiles run
+        // fastest.  The 32 tiles an XCD works on at a time then form a grp_m x 32/grp_m block of the tile grid and
+        // share grp_m + 32/grp_m operand panels instead of 33 (a row of the grid): what its L2 must hold and pull in.
+        const int per = a.tiles_k * a.tiles_m, split_id = div_magic(lid, per, a.mg_tiles_km), r = lid - split_id * per;
+        const int gsz = a.grp_m * a.tiles_k, g = div_magic(r, gsz, a.mg_grp_sz), j = r - g * gsz;
+        const int gm = min(a.grp_m, a.tiles_m - g * a.grp_m);   // the last group may be narrower
+        tk = gm == a.grp_m ? div_magic(j, a.grp_m, a.mg_grp_m) : j / gm;
+        tm = g * a.grp_m + j - tk * gm;
+        lid = split_id;
+    } else if (a.m_fastest) {  // consecutive tiles share a weight tile (few output channels per XCD)
         const int q1 = div_magic(lid, a.tiles_m, a.mg_tiles_m);
         tm = lid - q1 * a.tiles_m;
         lid = div_magic(q1, a.tiles_k, a.mg_tiles_k);
@@ -919,6 +931,23 @@ static bool make_gemm_args(const GemmProblem &g, int tile, int split_k, GemmArgs
         const double k_fast = rows(a.tiles_k, a.tiles_m, d.tk, d.tm / reuse);
         const double m_fast = rows(a.tiles_m, a.tiles_k, d.tm / reuse, d.tk);
         a.m_fastest = m_fast < k_fast;
+        // ... or a blocked order, judged by the panels the 32 tiles that an XCD runs at a time share (the
+        // row-major orders are the blockings 1 x 32 and min(32, tiles_k)-wide)
+        a.grp_m = 0;
+        if (a.tiles_k >= 4 && a.tiles_m >= 4) {
+            auto panels = [&](long long gm_, long long gk_) { return gm_ * (d.tm / reuse) + gk_ * d.tk; };
+            const long long kk = a.tiles_k < 32 ? a.tiles_k : 32, mm = a.tiles_m < 32 ? a.tiles_m : 32;
+            double best = a.m_fastest ? panels(mm, (32 + mm - 1) / mm) : panels((32 + kk - 1) / kk, kk);
+            for (int gmc = 2; gmc <= 16; gmc *= 2) {
+                const long long gk_ = (32 + gmc - 1) / gmc;
+                if (gmc > a.tiles_m || gk_ > a.tiles_k) continue;
+                const double c = panels(gmc, gk_);
+                if (c < 0.9 * best) {
+                    best = c;
+                    a.grp_m = gmc;
+                }
+            }
+        }
     }
     auto magic = [](long long d) { return d <= 1 ? 0u : (unsigned)((0x100000000ULL + (unsigned long long)d - 1) / (unsigned long long)d); };
     a.mg_g16 = magic(a.g16);
@@ -930,6 +959,9 @@ static bool make_gemm_args(const GemmProblem &g, int tile, int split_k, GemmArgs
     a.mg_il_d = g.il_d ? magic(g.il_d) : 0;
     a.mg_tiles_k = magic(a.tiles_k);
     a.mg_tiles_m = magic(a.tiles_m);
+    a.mg_grp_sz = magic((long long)a.grp_m * a.tiles_k);
+    a.mg_grp_m = magic(a.grp_m);
+    a.mg_tiles_km = magic((long long)a.tiles_k * a.tiles_m);
     *out = a;
     return true;
 }

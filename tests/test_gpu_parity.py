@@ -248,6 +248,8 @@ BLOCK64 = [
     ConvShape("k-tail", 3, 128, 9, 9, 70, 3, 3, 1, 1), ConvShape("5x5-stride2", 1, 128, 13, 11, 64, 5, 5, 2, 2),
     ConvShape("1x5", 2, 128, 6, 20, 33, 1, 5, 1, 0), ConvShape("3x3-odd-blocks", 2, 192, 7, 7, 64, 3, 3, 1, 1),
     ConvShape("two-images-per-tile", 9, 64, 5, 5, 40, 2, 3, 1, 1), ConvShape("too-wide", 1, 128, 4, 140, 64, 3, 3, 1, 1),
+    # five channel tiles x ten pixel tiles of 32 x 32 (both ragged): the blocked tile order with a narrower last group
+    ConvShape("blocked-tile-order", 2, 64, 12, 13, 150, 3, 3, 1, 1),
 ]
 
 
