@@ -933,6 +933,19 @@ int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int
     const size_t need = conv2d_int8_workspace_bytes(&d, layout, cb, 0);
     if (need == 0) {  // IMPLICIT: nothing to stage (any other layout reports its problem here)
         if (layout != CONV_LAYOUT_IMPLICIT) return CONV_ERR_UNSUPPORTED;
+        // Large batches: every workgroup of the stencil-unrolling kernel brings the tile's weight rows into the
+        // padded depth order on its way into LDS, dword by dword; rows rewritten once by a small kernel are copied
+        // in 16-byte pieces instead (a tenth of a workgroup's instructions).  Worth its launch from a few thousand
+        // workgroups on (C3 at N=512: 495 -> 405 us); below that the single launch stays.
+        const int depth = pack_weights_depth(C, R, S, CONV_LAYOUT_IMPLICIT, 0);
+        const long long P = ((long long)H + 2 * pad - R) / stride + 1, Q = ((long long)W + 2 * pad - S) / stride + 1;
+        if (!pointwise_shape(C, R, S) && depth > 0 && (long long)N * P * Q >= (1LL << 21)) {
+            void *ws = nullptr;
+            size_t ws_bytes = 0;
+            if (cached_workspace(align_up((size_t)K * depth, WS_ALIGN), (hipStream_t)stream, &ws, &ws_bytes) == CONV_OK &&
+                launch_pack_weights_window(K, C, R, S, wt, static_cast<int8_t *>(ws), (hipStream_t)stream) == hipSuccess)
+                return conv2d_int8_ex(&d, layout, 0, in, static_cast<const int8_t *>(ws), 1, out, nullptr, 0, stream);
+        }
         return conv2d_int8_ex(&d, layout, 0, in, wt, 0, out, nullptr, 0, stream);
     }
     void *ws = nullptr;

@@ -55,6 +55,7 @@ struct WindowArgs {
     int win_bytes, wl_bytes;  // LDS bytes of the window and of the weight rows (multiples of 16)
     int out_small;         // 4*K*P*Q < 2^32
     int in_small;          // C*H*W < 2^31
+    int wt16;              // the weights are rewritten rows of `depth` bytes at a 16-byte aligned address: copied in 16-byte pieces
     int rpp;               // window fill by columns (0: not): window rows per pass of 256 threads, 256 / (pitch/4)
     int wide_out;          // Q % 4 == 0 and out 16-byte aligned: 16-byte stores
     ActOut act;            // activation epilogue (act.out != null): `out` is not written
@@ -114,7 +115,15 @@ __global__ void __launch_bounds__(256, 4) conv_window_kernel(const WindowArgs a)
     constexpr int WRAW = NHWC ? KB / 4 : 1;   // rows of at most 256 bytes: 64 * KB dwords over 256 threads
     unsigned wraw[WRAW];
     const int raw_dw = (rows * a.w_row + 3) >> 2;
-    if (NHWC) {
+    // rewritten weights (rows of exactly the padded depth, zeros included): the tile's rows are one contiguous block,
+    // fetched in 16-byte pieces -- three loads and three stores per thread for 64 rows of 192 bytes, no masks
+    constexpr int PPR = ND / 4, WP16 = (KB * PPR + 255) / 256;   // pieces per row; pieces per thread
+    v4i wp16[WP16];
+    if (!NHWC && a.wt16) {
+#pragma unroll
+        for (int u = 0; u < WP16; ++u)
+            wp16[u] = *reinterpret_cast<const v4i *>(wsrc + 16 * (unsigned)min(tid + u * 256, rows * PPR - 1));
+    } else if (NHWC) {
         if (last >= 0) {
 #pragma unroll
             for (int u = 0; u < WRAW; ++u) wraw[u] = load_u32(wsrc + (unsigned)min(4 * min(tid + u * 256, raw_dw - 1), last));
@@ -229,6 +238,12 @@ __global__ void __launch_bounds__(256, 4) conv_window_kernel(const WindowArgs a)
                     *reinterpret_cast<unsigned *>(wl + row * a.w_pitch + 4 * d) =
                         (wb[u][0] | (wb[u][1] << 8) | (wb[u][2] << 16) | (wb[u][3] << 24)) & mask;
             }
+        }
+    } else if (a.wt16) {
+#pragma unroll
+        for (int u = 0; u < WP16; ++u) {
+            const int i = tid + u * 256, row = i / PPR, col = i - row * PPR;
+            if (i < rows * PPR) *reinterpret_cast<v4i *>(wl + row * a.w_pitch + col * 16) = wp16[u];
         }
     } else if (r0 < RPP) {
         if (last >= 0) {
@@ -458,6 +473,7 @@ static bool window_plan(const WindowProblem &g, WindowArgs *a)
     w.nd = S4 / 4;
     w.w_S = g.wt_rewritten ? S4 : S;
     w.w_row = g.wt_rewritten ? depth : C * g.R * S;
+    w.wt16 = g.wt_rewritten && (reinterpret_cast<uintptr_t>(g.wt) & 15) == 0;
     w.w_pitch = depth + 16;
     const int kb = g.K > 32 ? 64 : 32;
     const long long wlb = (long long)kb * w.w_pitch;
