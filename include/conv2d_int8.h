@@ -86,7 +86,9 @@ typedef struct {
  * returns CONV_ERR_WORKSPACE with nothing enqueued -- make the first call for a problem size
  * outside capture (or use conv2d_int8_ex with a workspace of your own).
  * Two launches: both rewrites, then the GEMM stage; one launch and no workspace when the choice
- * is IMPLICIT. */
+ * is IMPLICIT -- except for large batches of a non-1x1 layer (2^21 output pixels and more), where the
+ * weights are first rewritten into the cached workspace by a small kernel (if that block cannot be had,
+ * e.g. under capture, the single launch runs instead: never an error from this). */
 int conv2d_int8(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                 const int8_t *in, const int8_t *wt, int32_t *out, void *stream);
 
