@@ -286,15 +286,27 @@ __global__ void __launch_bounds__(256, 4) conv_window_kernel(const WindowArgs a)
     for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[kb][v] = 0;
+    // Every step's table entries first, then the dword pairs one step ahead of their use: written step by step, each
+    // step was two dependent LDS round trips (table, then pairs) in front of its MFMAs.
+    v4i ta[NKK];
 #pragma unroll
-    for (int kk = 0; kk < NKK; ++kk) {
-        const v4i ta = *reinterpret_cast<const v4i *>(tab + kk * 8 + half * 4);
-        v4i af;
+    for (int kk = 0; kk < NKK; ++kk) ta[kk] = *reinterpret_cast<const v4i *>(tab + kk * 8 + half * 4);
+    unsigned plo[2][4], phi[2][4];
+    auto fetch_pairs = [&](int kk) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const unsigned *pp = reinterpret_cast<const unsigned *>(a4 + ta[i]);
-            af[i] = (int)__builtin_amdgcn_alignbyte(pp[1], pp[0], ash);
+            const unsigned *pp = reinterpret_cast<const unsigned *>(a4 + ta[kk][i]);
+            plo[kk & 1][i] = pp[0];
+            phi[kk & 1][i] = pp[1];
         }
+    };
+    fetch_pairs(0);
+#pragma unroll
+    for (int kk = 0; kk < NKK; ++kk) {
+        if (kk + 1 < NKK) fetch_pairs(kk + 1);
+        v4i af;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) af[i] = (int)__builtin_amdgcn_alignbyte(phi[kk & 1][i], plo[kk & 1][i], ash);
 #pragma unroll
         for (int kb = 0; kb < NKB; ++kb) {
             const v4i wf = *reinterpret_cast<const v4i *>(wbase + kb * 32 * a.w_pitch + kk * 32);
