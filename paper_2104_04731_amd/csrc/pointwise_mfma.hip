@@ -62,13 +62,6 @@ __global__ void __launch_bounds__(256) conv_pointwise_kernel(const PointArgs a)
     const int l31 = lane & 31, half = lane >> 5;
     const int k0 = blockIdx.y * 128 + wave * 32;
 
-    // 1. weights (waves past the last output channel compute on row K-1 and store nothing)
-    v4i wf[NKK];
-    {
-        const int8_t *row = a.wt + (size_t)min(k0 + l31, a.K - 1) * C + half * 16;
-#pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) wf[kk] = ld_v4(row + kk * 32);
-    }
     // A workgroup keeps its weight operands in registers and walks over pixel tiles gridDim.x apart.
     const int g = tid & 7, cq = tid >> 3;
     // The next tile's pixels are fetched while this tile is multiplied and stored.
@@ -87,6 +80,15 @@ __global__ void __launch_bounds__(256) conv_pointwise_kernel(const PointArgs a)
     };
     const int lid0 = xcd_contiguous(blockIdx.x, gridDim.x);
     if (lid0 < a.ntiles) fetch(lid0);
+    // 1. weights (waves past the last output channel compute on row K-1 and store nothing).  Asked for after the
+    //    first tile's pixels: loads return in order, and the pixels are needed first (turned around and written to
+    //    LDS while the four times larger weight operand is still arriving).
+    v4i wf[NKK];
+    {
+        const int8_t *row = a.wt + (size_t)min(k0 + l31, a.K - 1) * C + half * 16;
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) wf[kk] = ld_v4(row + kk * 32);
+    }
     for (int lid = lid0; lid < a.ntiles; lid += gridDim.x) {
     const int n = fast_div_any(lid, a.tiles, a.m_tiles), px0 = (lid - n * a.tiles) * 32;
 #pragma unroll
