@@ -15,6 +15,8 @@
 //   4. the D block (column = pixel = lane%32) goes straight to NKPQ in 128-byte runs.
 // All global loads of a thread are issued before its first LDS store; a workgroup that has more
 // than one tile keeps its weight operands and fetches the next tile's pixels during the current one.
+// Two more forms of the same layer follow it: one for grids too small to fill the chip (a workgroup of 32 pixels x 32
+// output channels whose waves share the depth) and one for large batches (a workgroup owns 224 pixels of an image).
 #include "kernels.h"
 #include "rewrite_bodies.h"
 
@@ -141,6 +143,98 @@ __global__ void __launch_bounds__(256) conv_pointwise_kernel(const PointArgs a)
     }
     if (lid + (int)gridDim.x >= a.ntiles) break;
     __syncthreads();  // the next tile's pixels replace these in LDS
+    }
+}
+
+// ---- the same layer when the grid above would leave most of the chip idle: the depth split over the waves ----
+// A single image of 14x14 pixels and 1024 output channels is 7 pixel tiles x 8 channel groups = 56 workgroups
+// for 256 compute units, each waiting for sixteen 16-byte weight loads per lane and then running sixteen
+// dependent MFMAs.  Here a workgroup is 32 pixels x 32 output channels and each of its four waves takes a
+// quarter of the channels: four weight loads and four MFMAs per lane, four times as many workgroups.  A wave
+// turns around only the channels it multiplies, in an LDS tile of its own, so nothing waits for another wave
+// until the four partial D blocks are added: each wave leaves its block in LDS, one barrier, and wave w adds
+// up and stores rows 8w .. 8w+7 of the 32.
+template <int NKK>  // C = 32 * NKK, NKK a multiple of 4
+__global__ void __launch_bounds__(256) conv_pointwise_split_kernel(const PointArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    static_assert(NKK % 4 == 0, "four waves share the depth");
+    constexpr int C = 32 * NKK, CW = C / 4, PITCH = CW + 16;   // CW: channels of one wave
+    constexpr int NK = NKK / 4;                                // 32-deep steps of one wave
+    constexpr int PASSES = CW / 32;                            // 64 lanes = 8 pixel groups x 8 quads of channels per pass
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l31 = lane & 31, half = lane >> 5;
+    const int k0 = blockIdx.y * 32, c0 = wave * CW;
+    const int tile = blockIdx.x;
+    const int n = fast_div_any(tile, a.tiles, a.m_tiles), px0 = (tile - n * a.tiles) * 32;
+    const int g = lane & 7, cq = lane >> 3;
+
+    // pixels before weights: loads return in order and the pixels are needed first
+    unsigned xv[PASSES][4];
+    {
+        const int px = min(px0 + 4 * g, a.HW - 4);   // HW is a multiple of 4: a group is inside the image or past it
+        const int8_t *img = a.in + ((size_t)n * C + c0) * a.HW + px;
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) xv[ps][j] = ld_u32(img + (size_t)(4 * (cq + 8 * ps) + j) * a.HW);
+    }
+    v4i wf[NK];
+    {
+        const int8_t *row = a.wt + (size_t)min(k0 + l31, a.K - 1) * C + c0 + half * 16;
+#pragma unroll
+        for (int kk = 0; kk < NK; ++kk) wf[kk] = ld_v4(row + kk * 32);
+    }
+    unsigned char *xt = smem + wave * (32 * PITCH);   // this wave's XT[pixel][its channels]
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) {
+        const int q = cq + 8 * ps;
+        const unsigned lo01 = __builtin_amdgcn_perm(xv[ps][1], xv[ps][0], 0x05010400u);
+        const unsigned hi01 = __builtin_amdgcn_perm(xv[ps][1], xv[ps][0], 0x07030602u);
+        const unsigned lo23 = __builtin_amdgcn_perm(xv[ps][3], xv[ps][2], 0x05010400u);
+        const unsigned hi23 = __builtin_amdgcn_perm(xv[ps][3], xv[ps][2], 0x07030602u);
+        unsigned *dst = reinterpret_cast<unsigned *>(xt + (4 * g) * PITCH + 4 * q);
+        dst[0 * PITCH / 4] = __builtin_amdgcn_perm(lo23, lo01, 0x05040100u);
+        dst[1 * PITCH / 4] = __builtin_amdgcn_perm(lo23, lo01, 0x07060302u);
+        dst[2 * PITCH / 4] = __builtin_amdgcn_perm(hi23, hi01, 0x05040100u);
+        dst[3 * PITCH / 4] = __builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
+    }
+    // The tile is this wave's alone and LDS serves a wave's accesses in order: no barrier, only the order kept.
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+
+    v16i acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0;
+    const unsigned char *xrow = xt + l31 * PITCH + half * 16;
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) {
+        const v4i xf = *reinterpret_cast<const v4i *>(xrow + kk * 32);
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[kk], xf, acc, 0, 0, 0);
+    }
+
+    // D block: column = lane%32 = pixel, row = 8*(v/4) + 4*(lane/32) + v%4 = channel.  red[wave][v/4][lane] = four rows.
+    v4i *red = reinterpret_cast<v4i *>(smem + 4 * 32 * PITCH);
+#pragma unroll
+    for (int vg = 0; vg < 4; ++vg)
+        red[(wave * 4 + vg) * 64 + lane] = v4i{acc[4 * vg], acc[4 * vg + 1], acc[4 * vg + 2], acc[4 * vg + 3]};
+    __syncthreads();
+    v4i sum = red[wave * 64 + lane];
+#pragma unroll
+    for (int o = 1; o < 4; ++o) {
+        const v4i t = red[(o * 4 + wave) * 64 + lane];
+        sum[0] += t[0];
+        sum[1] += t[1];
+        sum[2] += t[2];
+        sum[3] += t[3];
+    }
+    const int p = px0 + l31, kr = k0 + 8 * wave + 4 * half;
+    if (p < a.HW) {
+        int32_t *base = a.out + ((size_t)n * a.K + kr) * a.HW + p;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (kr + j < a.K) base[(size_t)j * a.HW] = sum[j];
     }
 }
 
@@ -305,6 +399,14 @@ hipError_t launch_nkk(const PointArgs &a, dim3 grid, hipStream_t st)
     return hipGetLastError();
 }
 
+template <int NKK>
+hipError_t launch_split(const PointArgs &a, hipStream_t st)
+{
+    const dim3 grid((unsigned)a.ntiles, (unsigned)((a.K + 31) / 32));
+    hipLaunchKernelGGL((conv_pointwise_split_kernel<NKK>), grid, dim3(256), (size_t)4 * 32 * (8 * NKK + 16) + 4 * 4 * 64 * 16, st, a);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 bool pointwise_fits(const WindowProblem &g)
@@ -335,6 +437,17 @@ hipError_t launch_pointwise_conv(const WindowProblem &g, hipStream_t st)
     a.m_W = magic_for(g.W);
     a.act = g.act;
     const int kgroups = (g.K + 127) / 128;
+    // While the split form has at most one workgroup per compute unit it is the faster one (one 14x14 image, C = 512,
+    // K = 1024: 2.9 against 3.8 us; C = K = 256, four images: 2.4 against 2.9); at about two per compute unit the two
+    // are level, beyond that the form below, which turns a pixel tile around once for 128 output channels, wins.
+    if (!a.act.out && g.C % 128 == 0 && (long long)a.ntiles * ((g.K + 31) / 32) <= 256) {
+        switch (g.C / 128) {
+            case 1: return launch_split<4>(a, st);
+            case 2: return launch_split<8>(a, st);
+            case 3: return launch_split<12>(a, st);
+            case 4: return launch_split<16>(a, st);
+        }
+    }
     int wgs = 256 * 4 / kgroups;  // about four workgroups fit a CU
     if (wgs < 256) wgs = 256;
     const dim3 grid((unsigned)(a.ntiles < wgs ? a.ntiles : wgs), (unsigned)kgroups);

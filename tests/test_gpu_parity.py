@@ -1089,6 +1089,25 @@ def test_pointwise_batch_form(lib, dims):
         assert np.array_equal(got, want), f"rewritten={rewritten}: {np.count_nonzero(got != want)} mismatches"
 
 
+@pytest.mark.parametrize("dims", [(1, 512, 14, 14, 1024, 1, 1, 1, 0), (1, 128, 14, 14, 33, 1, 1, 1, 0),
+                                  (2, 256, 5, 4, 70, 1, 1, 1, 0), (1, 384, 1, 36, 1, 1, 1, 1, 0),
+                                  (3, 512, 2, 2, 257, 1, 1, 1, 0), (7, 128, 3, 12, 31, 1, 1, 1, 0),
+                                  (1, 256, 9, 28, 64, 1, 1, 1, 0)], ids=str)
+def test_pointwise_split_depth_form(lib, dims):
+    """Few pixel tiles (below half the chip's compute units) and C % 128 = 0: the 1x1 kernel whose four waves share
+    the depth and add their partial blocks up through LDS.  The headline 1x1 layer itself, every C / 128, output
+    channels ragged against 32 and against 8 (a single one too), pixel tiles ragged against 32, images of one tile
+    and of four pixels."""
+    cfg = ConvShape("pw-split", *dims)
+    assert lib.layout_applies(dims, lib.LAYOUT_IMPLICIT)
+    x = uniform_int8(961, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(962, (cfg.K, cfg.C, 1, 1))
+    want = direct.conv2d_int8(x, w, 1, 0)
+    for rewritten in (False, True):
+        got = run_implicit(lib, cfg, x, w, rewritten)
+        assert np.array_equal(got, want), f"rewritten={rewritten}: {np.count_nonzero(got != want)} mismatches"
+    np.testing.assert_array_equal(host(lib.conv2d_int8(dev(x), dev(w), 1, 0)), want)
+
+
 # ---- seeded random shapes through the routes added around the GEMM stage's epilogue ---------------------------
 def test_dilated_random_shapes(lib):
     rng = np.random.default_rng(9101)
