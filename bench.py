@@ -390,7 +390,7 @@ def main():
         achieved = nbytes / (dom_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_BPS / 1e9, "unit": "GB/s",
                     "frac": round(achieved * 1e9 / PEAK_HBM_BPS, 5), "traffic": None,
-                    "kernel": "conv_pointwise_kernel" if (dom.cfg.R, dom.cfg.S) == (1, 1) and dom.cfg.C % 64 == 0
+                    "kernel": "conv_pointwise_*_kernel (the library picks among the 1x1 forms by grid size)" if (dom.cfg.R, dom.cfg.S) == (1, 1) and dom.cfg.C % 64 == 0
                     else "conv_window_kernel", "config": dom.cfg.name, "launch_us": round(dom_ms * 1e3, 3)}
     else:
         achieved = dom.cfg.ops / (dom_ms * 1e-3) / 1e12

@@ -420,6 +420,25 @@ def test_ex_with_caller_workspace_and_prepacked_weights(lib):
     assert e.value.status == lib.ERR_WORKSPACE
 
 
+@pytest.mark.parametrize("dims,cb", [((1, 64, 6, 6, 1, 3, 3, 1, 1), 64), ((2, 128, 5, 7, 33, 3, 3, 1, 1), 64),
+                                     ((1, 192, 6, 5, 100, 5, 5, 2, 2), 64), ((1, 64, 9, 9, 257, 1, 1, 1, 0), 16),
+                                     ((1, 96, 7, 8, 70, 2, 3, 1, 1), 32), ((1, 64, 8, 8, 16, 5, 5, 1, 2), 64),
+                                     ((1, 64, 12, 12, 20, 7, 7, 1, 3), 64), ((1, 80, 6, 6, 40, 3, 3, 1, 1), 64)], ids=str)
+def test_fused_rewrite_weight_range(lib, dims, cb):
+    """The weight half of the fused rewrite launch (channel blocking of KCRS, Table 2), one thread per 16 destination
+    bytes: fewer pieces than a workgroup has threads, (k, channel block) pairs of 36 and 100 pieces that straddle
+    workgroups, a ragged last workgroup, single-piece pairs (1x1, cb 16), large pairs (5x5 and 7x7, cb 64), and a
+    channel count that is not whole blocks."""
+    cfg = ConvShape("fused-w", *dims)
+    assert lib.layout_applies(dims, lib.LAYOUT_PACKED, cb)
+    x = uniform_int8(971, (cfg.N, cfg.C, cfg.H, cfg.W)); w = uniform_int8(972, (cfg.K, cfg.C, cfg.R, cfg.S))
+    want = direct.conv2d_int8(x, w, cfg.stride, cfg.pad)
+    ws = torch.empty(lib.conv2d_int8_workspace_bytes(dims, lib.LAYOUT_PACKED, cb), dtype=torch.int8, device=DEV)
+    out = torch.full(want.shape, -5, dtype=torch.int32, device=DEV)
+    lib.conv2d_int8_ex(dims, lib.LAYOUT_PACKED, cb, dev(x), dev(w), out, ws)
+    assert np.array_equal(host(out), want), f"{np.count_nonzero(host(out) != want)} mismatches"
+
+
 def test_non_default_stream(lib):
     cfg = CONFIGS["C1"]
     x, w, want = oracle_conv(cfg)
