@@ -998,6 +998,8 @@ int conv2d_int8_nhwc(int N, int C, int H, int W, int K, int R, int S, int stride
     if (R == 1 && S == 1 && stride == 1 && pad == 0 && C % CONV_DEPTH_ALIGN == 0 && aligned16(in) && aligned16(wt) && aligned16(out)) {
         // A 1x1 layer on NHWC tensors is a plain matrix product of operands that are depth-contiguous as they are:
         // pixels x channels times the weight rows, into pixels x output channels.  No rewrite, one launch.
+        if (pointwise_nhwc_split_fits(pl.M, C, K))   // a grid that leaves most of the chip idle: the depth split over a workgroup's waves
+            return launch_pointwise_nhwc_split(in, wt, out, pl.M, C, K, (hipStream_t)stream) == hipSuccess ? CONV_OK : CONV_ERR_DEVICE;
         GemmProblem g{};
         g.act = in;
         g.wq = wt;

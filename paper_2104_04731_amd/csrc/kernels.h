@@ -130,5 +130,9 @@ hipError_t launch_pack_weights_window(int K, int C, int R, int S, const int8_t *
 inline bool pointwise_shape(int C, int R, int S) { return R == 1 && S == 1 && C % 64 == 0; }
 bool pointwise_fits(const WindowProblem &g);    // stride 1, no padding, C <= 512, H*W a multiple of 4
 hipError_t launch_pointwise_conv(const WindowProblem &g, hipStream_t st);
+// 1x1, stride 1, no padding on NHWC tensors ([M][C] pixels, [K][C] weights, [M][K] result), small grids only
+bool pointwise_nhwc_split_fits(long long M, int C, int K);
+hipError_t launch_pointwise_nhwc_split(const int8_t *in, const int8_t *wt, int32_t *out, long long M, int C, int K,
+                                       hipStream_t st);
 
 }  // namespace c2i8

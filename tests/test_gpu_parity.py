@@ -867,7 +867,14 @@ def test_unpack_nhwc(lib, shape):
                                  ConvShape("nhwc-deep", 1, 256, 7, 7, 64, 3, 3, 1, 1),      # small and deep: a depth split
                                  ConvShape("nhwc-k130", 1, 32, 12, 12, 130, 3, 3, 1, 1),
                                  ConvShape("nhwc-1x1-k70", 3, 128, 7, 9, 70, 1, 1, 1, 0),   # 1x1: a plain matrix product, one launch
-                                 ConvShape("nhwc-1x1-s2", 2, 64, 9, 9, 32, 1, 1, 2, 0)],    # 1x1 with a stride: not that form
+                                 ConvShape("nhwc-1x1-s2", 2, 64, 9, 9, 32, 1, 1, 2, 0),     # 1x1 with a stride: not that form
+                                 # 1x1 on a grid too small for the chip: the depth split over a workgroup's waves (every C / 128,
+                                 # pixels ragged against 32 and against 8, channels against 32, one pixel, four channels)
+                                 ConvShape("nhwc-1x1-split-128", 3, 128, 7, 9, 72, 1, 1, 1, 0),
+                                 ConvShape("nhwc-1x1-split-256", 2, 256, 3, 5, 4, 1, 1, 1, 0),
+                                 ConvShape("nhwc-1x1-split-384", 1, 384, 1, 1, 36, 1, 1, 1, 0),
+                                 ConvShape("nhwc-1x1-split-512", 1, 512, 5, 5, 100, 1, 1, 1, 0),
+                                 ConvShape("nhwc-1x1-split-most", 2, 128, 14, 14, 1248, 1, 1, 1, 0)],   # 13 x 39 workgroups: just inside its bound
                          ids=lambda c: c.name)
 def test_conv_nhwc_one_shot(lib, cfg):
     """NHWC in, NHWC out: the NCHW definition seen through transposed views.  The GEMM stage writes NHWC
