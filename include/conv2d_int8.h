@@ -114,7 +114,8 @@ int conv2d_int8_static(int N, int C, int H, int W, int K, int R, int S, int stri
  * kernel that unrolls the stencil itself reads the NHWC source directly -- depth order (r, s, c), a kernel row's
  * S*C bytes being one run of an image row -- and writes the NHWC result: one launch, no workspace.  A 1x1 layer
  * (stride 1, no padding, C a multiple of 64, all three tensors on 16 bytes) is a plain matrix product of the NHWC
- * input and the weight rows as they are: one launch of the GEMM stage, no rewrite, no workspace. */
+ * input and the weight rows as they are: one launch of the GEMM stage (for a grid too small to fill the chip, of a
+ * kernel whose waves share the depth), no rewrite, no workspace. */
 int conv2d_int8_nhwc(int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                      const int8_t *in, const int8_t *wt, int32_t *out, void *stream);
 
