@@ -147,7 +147,7 @@ __global__ void __launch_bounds__(256) conv_pointwise_kernel(const PointArgs a)
 }
 
 // ---- the same layer when the grid above would leave most of the chip idle: the depth split over the waves ----
-// A single image of 14x14 pixels and 1024 output channels is 7 pixel tiles x 8 channel groups = 56 workgroups
+// Eight images of 14x14 pixels and 128 output channels are 56 pixel tiles x 1 channel group = 56 workgroups
 // for 256 compute units, each waiting for sixteen 16-byte weight loads per lane and then running sixteen
 // dependent MFMAs.  Here a workgroup is 32 pixels x 32 output channels and each of its four waves takes a
 // quarter of the channels: four weight loads and four MFMAs per lane, four times as many workgroups.  A wave
@@ -524,8 +524,8 @@ hipError_t launch_pointwise_conv(const WindowProblem &g, hipStream_t st)
     a.m_W = magic_for(g.W);
     a.act = g.act;
     const int kgroups = (g.K + 127) / 128;
-    // While the split form has at most one workgroup per compute unit it is the faster one (one 14x14 image, C = 512,
-    // K = 1024: 2.9 against 3.8 us; C = K = 256, four images: 2.4 against 2.9); at about two per compute unit the two
+    // While the split form has at most one workgroup per compute unit it is the faster one (eight 14x14 images, C = 512,
+    // K = 128: 2.9 against 3.8 us; C = K = 256, four images: 2.4 against 2.9); at about two per compute unit the two
     // are level, beyond that the form below, which turns a pixel tile around once for 128 output channels, wins.
     if (!a.act.out && g.C % 128 == 0 && (long long)a.ntiles * ((g.K + 31) / 32) <= 256) {
         switch (g.C / 128) {

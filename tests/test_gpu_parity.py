@@ -1115,13 +1115,14 @@ def test_pointwise_batch_form(lib, dims):
         assert np.array_equal(got, want), f"rewritten={rewritten}: {np.count_nonzero(got != want)} mismatches"
 
 
-@pytest.mark.parametrize("dims", [(1, 512, 14, 14, 1024, 1, 1, 1, 0), (1, 128, 14, 14, 33, 1, 1, 1, 0),
+@pytest.mark.parametrize("dims", [(8, 512, 14, 14, 128, 1, 1, 1, 0), (1, 512, 14, 14, 1024, 1, 1, 1, 0), (1, 128, 14, 14, 33, 1, 1, 1, 0),
                                   (2, 256, 5, 4, 70, 1, 1, 1, 0), (1, 384, 1, 36, 1, 1, 1, 1, 0),
                                   (3, 512, 2, 2, 257, 1, 1, 1, 0), (7, 128, 3, 12, 31, 1, 1, 1, 0),
                                   (1, 256, 9, 28, 64, 1, 1, 1, 0)], ids=str)
 def test_pointwise_split_depth_form(lib, dims):
     """Few pixel tiles (below half the chip's compute units) and C % 128 = 0: the 1x1 kernel whose four waves share
-    the depth and add their partial blocks up through LDS.  The headline 1x1 layer itself, every C / 128, output
+    the depth and add their partial blocks up through LDS.  The headline 1x1 layer itself (eight images, 128 output
+    channels) and its transpose in batch and channels, every C / 128, output
     channels ragged against 32 and against 8 (a single one too), pixel tiles ragged against 32, images of one tile
     and of four pixels."""
     cfg = ConvShape("pw-split", *dims)
